@@ -1,0 +1,116 @@
+"""Python face of the CPU oracle (TEST INFRASTRUCTURE ONLY).
+
+forward() calls the plain C loops of tsvd_oracle.c (fp64, natural order); the
+remaining functions restate the paper's operation counts:
+
+  * op_counts      -- supplement Table S1: per token the map costs K
+                      multiplications and nnz(U)+nnz(V) = r K (M+N) additions.
+  * acceleration   -- supplement Table S2, TSVD row, with the instruction cost
+                      model 1 Mul = (d-2) Add of the section "Hardware Cost of
+                      Basic Instruction": M N (d-1) / (K (d-2) + r K (M+N)).
+  * critical_rank  -- Eq. (2): the rank at which that acceleration equals 1.
+
+Nothing here is imported by the GPU library or its binding.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tsvd_oracle.c")
+_LIB = os.path.join(_HERE, "libtsvd_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile tsvd_oracle.c with gcc (-O2, OpenMP) into libtsvd_oracle.so."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
+                               "-Wall", "-Wextra", "-o", _LIB, _SRC])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        p = ctypes.c_void_p
+        i64 = ctypes.c_int64
+        lib.tsvd_oracle_forward.argtypes = [p, p, p, p, p, i64, i64, i64, i64]
+        lib.tsvd_oracle_forward.restype = ctypes.c_int
+        lib.tsvd_oracle_forward_vec.argtypes = [p, p, p, p, p, p, i64, i64, i64]
+        lib.tsvd_oracle_forward_vec.restype = ctypes.c_int
+        lib.tsvd_oracle_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def threads() -> int:
+    return int(_load().tsvd_oracle_threads())
+
+
+def _check(U, S, V, X):
+    U = np.ascontiguousarray(U, dtype=np.int8)
+    V = np.ascontiguousarray(V, dtype=np.int8)
+    S = np.ascontiguousarray(S, dtype=np.float32)
+    X = np.asarray(X)
+    if X.ndim == 1:
+        X = X[:, None]
+    X = np.ascontiguousarray(X, dtype=np.float64)      # bf16 / fp32 -> fp64 is exact
+    M, K = U.shape
+    K2, N = V.shape
+    if K2 != K or S.shape != (K,) or X.shape[0] != N:
+        raise ValueError("shape mismatch: U [M,K], S [K], V [K,N], X [N,B] expected")
+    return U, S, V, X, M, K, N
+
+
+def forward(U, S, V, X) -> np.ndarray:
+    """Y = U (diag(S) (V X)) in fp64; X is [N,B] (or [N]); returns [M,B] float64."""
+    U, S, V, X, M, K, N = _check(U, S, V, X)
+    B = X.shape[1]
+    Y = np.empty((M, B), dtype=np.float64)
+    lib = _load()
+    if B == 1:
+        z = np.empty(K, dtype=np.float64)
+        rc = lib.tsvd_oracle_forward_vec(U.ctypes.data, S.ctypes.data, V.ctypes.data,
+                                         X.ctypes.data, Y.ctypes.data, z.ctypes.data, M, K, N)
+    else:
+        rc = lib.tsvd_oracle_forward(U.ctypes.data, S.ctypes.data, V.ctypes.data,
+                                     X.ctypes.data, Y.ctypes.data, M, K, N, B)
+    if rc == 2:
+        raise ValueError("U or V holds an entry outside {-1, 0, +1}")
+    if rc != 0:
+        raise RuntimeError(f"oracle failed with status {rc}")
+    return Y
+
+
+def forward_columns(U, S, V, X, cols) -> np.ndarray:
+    """Outputs for a subset of tokens: columns are independent, so this is exact."""
+    X = np.asarray(X)
+    return forward(U, S, V, X[:, np.asarray(cols, dtype=np.int64)])
+
+
+def op_counts(U, V) -> dict:
+    """Per-token operation counts of supplement Table S1 for given U, V."""
+    U = np.asarray(U)
+    V = np.asarray(V)
+    M, K = U.shape
+    N = V.shape[1]
+    nnz_u = int(np.count_nonzero(U))
+    nnz_v = int(np.count_nonzero(V))
+    return {"mults": K, "adds": nnz_u + nnz_v, "adds_U": nnz_u, "adds_V": nnz_v,
+            "r": (nnz_u + nnz_v) / float(K * (M + N))}
+
+
+def acceleration(M: int, N: int, K: int, r: float, d: int) -> float:
+    """Cost of W(.) over cost of U diag(S) V(.) in equivalent additions (Table S2)."""
+    return M * N * (d - 1) / (K * (d - 2) + r * K * (M + N))
+
+
+def critical_rank(M: int, N: int, r: float, d: int) -> float:
+    """Eq. (2): the rank where TSVD and the dense map cost the same."""
+    return (d - 1) * M * N / (d + r * (M + N) - 2)
