@@ -1,0 +1,118 @@
+/*
+ * tsvd.h -- C ABI of the MI355X (gfx950) Ternary-SVD forward library.
+ *
+ * The operation (paper, section "Truncated SVD in Network Compression": a
+ * linear layer y = W x with W [M,N] is evaluated as y ~= U (diag(S) (V x));
+ * section "Ternary SVD": U [M,K] and V [K,N] hold only -1, 0, +1 and S [K] is
+ * a real scale vector, so V(.) and U(.) need additions only and diag(S)(.)
+ * needs K multiplications -- supplement Table S1).  The rank K is not assumed
+ * small: K > min(M,N) is allowed.  There is no bias term (Eq. 1).
+ *
+ * All functions are plain C, never throw, and report failure through
+ * tsvd_status; on failure outputs are left untouched.  "host" and "device"
+ * below say where a pointer must live.  Nothing in the signatures is a torch
+ * type: a stream is a hipStream_t passed as void*.
+ */
+#ifndef TSVD_H
+#define TSVD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tsvd_handle tsvd_handle; /* opaque; owns or borrows the packed device blob */
+
+typedef enum {
+    TSVD_OK = 0,
+    TSVD_EINVAL = 1,       /* null pointer, non-positive size, bad leading dimension, short buffer */
+    TSVD_EVALUE = 2,       /* an entry of U or V is not -1, 0 or +1 (or a packed code is corrupt)  */
+    TSVD_ENOMEM = 3,       /* host allocation failed                                               */
+    TSVD_EDEVICE = 4,      /* a HIP call failed (no device, out of device memory, launch error)    */
+    TSVD_EUNSUPPORTED = 5  /* valid request this build does not implement                          */
+} tsvd_status;
+
+typedef enum { TSVD_F32 = 0, TSVD_BF16 = 1 } tsvd_dtype;
+
+/* ---- packing: the 2-bit ternary weight format ------------------------------------------
+ *
+ * The paper only says that a ternary element needs 2 bits (section "Connection with BNN").
+ * This library's code is  bit0 = "non-zero", bit1 = "negative":  00 -> 0, 01 -> +1,
+ * 11 -> -1; 10 is never produced and is rejected when read back.  That is the U = U+ - U-
+ * bit-plane view of the same section (bit0 = U+ | U-, bit1 = U-).  Codes are stored in
+ * 1 KiB tiles of 16 rows x 256 columns ordered for 128-byte-coalesced wavefront reads,
+ * with one non-zero count per tile; dimensions are zero-padded to multiples of 256
+ * (padding adds nothing to y and nothing to the counts).  The sum of the tile counts is
+ * nnz(U) + nnz(V), the per-token addition count r K (M+N) of supplement Table S1.
+ */
+
+/* Size in bytes of the packed blob for given dimensions (0 if a dimension is <= 0). */
+size_t tsvd_packed_bytes(int64_t M, int64_t K, int64_t N);
+
+/* Pack on the host into host memory (no GPU needed).
+ *   U: host int8 [M][K] row-major, V: host int8 [K][N] row-major, S: host float [K].
+ *   blob: host buffer of at least tsvd_packed_bytes(M,K,N) bytes; fully overwritten.
+ * Returns TSVD_EVALUE if U or V holds anything but -1, 0, +1. */
+tsvd_status tsvd_pack_host(const int8_t* U, const float* S, const int8_t* V,
+                           int64_t M, int64_t K, int64_t N, void* blob, size_t blob_bytes);
+
+/* Exact inverse of tsvd_pack_host.  Any of U, S, V may be NULL (skipped); each of M, K, N
+ * may be NULL.  With U, S and V all NULL only the dimensions are returned. */
+tsvd_status tsvd_unpack_host(const void* blob, size_t blob_bytes, int8_t* U, float* S, int8_t* V,
+                             int64_t* M, int64_t* K, int64_t* N);
+
+/* Pack and upload.  U, S, V as for tsvd_pack_host (caller keeps ownership).
+ *   dev_buf == NULL : the library hipMallocs the blob and tsvd_free releases it.
+ *   dev_buf != NULL : caller-owned device memory (e.g. a torch uint8 tensor) of
+ *                     dev_buf_bytes >= tsvd_packed_bytes(M,K,N), 256-byte aligned; it must
+ *                     outlive the handle and is not freed by tsvd_free.
+ * Uses the current HIP device; synchronous.  *out is written only on success. */
+tsvd_status tsvd_pack(const int8_t* U, const float* S, const int8_t* V,
+                      int64_t M, int64_t K, int64_t N,
+                      void* dev_buf, size_t dev_buf_bytes, tsvd_handle** out);
+
+/* Download and unpack (bit-exact inverse of tsvd_pack); host outputs, any may be NULL. */
+tsvd_status tsvd_unpack(const tsvd_handle* h, int8_t* U, float* S, int8_t* V);
+
+/* Dimensions and the sums of the per-tile non-zero counts; any output may be NULL. */
+tsvd_status tsvd_info(const tsvd_handle* h, int64_t* M, int64_t* K, int64_t* N,
+                      int64_t* nnzU, int64_t* nnzV);
+
+/* ---- forward ------------------------------------------------------------------------
+ *
+ * Y = U (diag(S) (V X)) for B tokens (columns), following the three steps of the paper's
+ * identity: t = V x (additions), z = S * t (the K multiplications), y = U z (additions).
+ *
+ *   x_dev : device, [N][B] row-major with row stride ldx >= B elements of x_dtype.
+ *   y_dev : device, [M][B] row-major with row stride ldy >= B; y_dtype must be TSVD_F32.
+ *   workspace : device scratch for the intermediate z, at least
+ *               tsvd_workspace_bytes(h, B, x_dtype) bytes, 256-byte aligned; contents
+ *               are undefined afterwards.  NULL (with workspace_bytes 0) makes the library
+ *               use scratch owned by the handle, grown with hipMalloc when needed; such
+ *               calls on one handle must not overlap each other.
+ *   stream : hipStream_t as void* (NULL = the default stream).  Work is enqueued and the
+ *            call returns without synchronising.
+ * x, y and workspace are owned by the caller and must not alias.  Inputs must be finite.
+ * Accumulation is fp32; TSVD_F32 activations are consumed exactly (split into bf16 parts),
+ * so the result differs from exact arithmetic only by fp32 summation rounding.  For B >= 64
+ * with TSVD_BF16 activations the intermediate z is rounded to fp16 (11 significant bits)
+ * after a per-token power-of-two scaling that keeps it in range.
+ */
+size_t tsvd_workspace_bytes(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype);
+
+tsvd_status tsvd_forward(const tsvd_handle* h, const void* x_dev, tsvd_dtype x_dtype,
+                         int64_t B, int64_t ldx, void* y_dev, tsvd_dtype y_dtype, int64_t ldy,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Releases the handle and whatever device memory it owns.  NULL is allowed. */
+void tsvd_free(tsvd_handle* h);
+
+/* Static description of a status code. */
+const char* tsvd_strerror(tsvd_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TSVD_H */

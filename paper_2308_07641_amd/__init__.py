@@ -1,0 +1,10 @@
+"""MI355X-native forward pass of the Ternary-SVD linear map y = U (diag(S) (V x)).
+
+Thin Python binding over the C-ABI library libtsvd.so (see include/tsvd.h).  The binding
+only marshals arguments: every step of the computation runs in the HIP kernels.
+"""
+from .tsvd import (  # noqa: F401
+    TSVD_F32, TSVD_BF16, TsvdError, Handle, lib_path, load_library,
+    tsvd_packed_bytes, tsvd_pack_host, tsvd_unpack_host, tsvd_pack, tsvd_unpack, tsvd_info,
+    tsvd_workspace_bytes, tsvd_forward, tsvd_free, tsvd_strerror,
+)

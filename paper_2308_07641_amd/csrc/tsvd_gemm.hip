@@ -1,0 +1,342 @@
+// Batched path (B >= 64, bf16 activations): both stages of Y = U (diag(S) (V X)) as
+// ternary-weight x 16-bit-activation contractions on the matrix cores.
+//
+// Paper: section "Truncated SVD in Network Compression" (the three-step identity) and
+// supplement Table S1 (V(.) and U(.) are additions, diag(S)(.) is K multiplications per
+// token).  With hundreds of tokens per weight the work is a dense contraction, so the 2-bit
+// codes are expanded exactly to +-2 / 0 16-bit floats in registers (one shift and one mask per
+// pair) and fed to v_mfma_f32_16x16x32; products are exact and accumulation is fp32.
+//
+//   kernel 0  column maxima of |X| (partial, per row slice)       -> workspace
+//   kernel 1  Z = fp16( scale_b * S_k * (V X)[k][b] )            (bf16 MFMA, S fused in the epilogue)
+//   kernel 2  Y = (U Z)[m][b] / scale_b                           (fp16 MFMA)
+//
+// scale_b is a power of two chosen from the bound |z[k][b]| <= max_k(|S_k| nnz(V[k,:])) *
+// max_n |x[n][b]| so that fp16 cannot overflow; fp16 keeps 11 significant bits of z where bf16
+// would keep 8 (the 8-bit rounding alone costs about 1.7e-3 of max|y| at these shapes).
+//
+// Weights never pass through LDS: each wavefront loads the code words of its own rows straight
+// from L2 (they are 8x smaller than the activations).  Activation tiles [64 k][BT tokens] are
+// staged in LDS in their natural row-major order with a 32-byte XOR swizzle and read in MFMA
+// operand order with ds_read_b64_tr_b16.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tsvd_kernels.h"
+#include "tsvd_layout.h"
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+#define TSVD_DEC(w, j) ((((uint32_t)(w)) << (14 - 2 * (j))) & 0xC000C000u)
+#define KT 64   // contraction depth of one LDS stage
+
+namespace {
+
+// ---- kernel 0: partial column maxima of |x| ----------------------------------------------
+// grid (ceil(B/128), PARTS); block 256 = 64 column pairs x 4 row lanes.  part[p][b] = max over
+// the rows of slice p of |x[n][b]| as an fp32 value.
+__global__ void __launch_bounds__(256)
+tsvd_colmax_kernel(const uint16_t* __restrict__ x, long long ldx, int N, int B, int Bp, float* __restrict__ part) {
+    __shared__ uint32_t red[4][128];
+    const int cp = threadIdx.x & 63, rl = threadIdx.x >> 6;
+    const int c0 = blockIdx.x * 128 + 2 * cp;
+    const int rows_per = (N + gridDim.y - 1) / gridDim.y;
+    const int r0 = blockIdx.y * rows_per, r1 = min(N, r0 + rows_per);
+    uint32_t m0 = 0, m1 = 0;       // magnitudes as bf16 bit patterns (order-preserving)
+    for (int r = r0 + rl; r < r1; r += 4) {
+        const uint16_t* row = x + (size_t)r * ldx;
+        if (c0 < B) m0 = max(m0, (uint32_t)(row[c0] & 0x7FFFu));
+        if (c0 + 1 < B) m1 = max(m1, (uint32_t)(row[c0 + 1] & 0x7FFFu));
+    }
+    red[rl][2 * cp] = m0;
+    red[rl][2 * cp + 1] = m1;
+    __syncthreads();
+    if (threadIdx.x < 128) {
+        const int c = blockIdx.x * 128 + threadIdx.x;
+        uint32_t m = max(max(red[0][threadIdx.x], red[1][threadIdx.x]), max(red[2][threadIdx.x], red[3][threadIdx.x]));
+        if (c < Bp) part[(size_t)blockIdx.y * Bp + c] = __uint_as_float(m << 16);
+    }
+}
+
+// Power-of-two scale for column b: bound_V * xmax * scale <= 2^14.
+__device__ __forceinline__ float column_scale(const float* part, int Bp, int col, float bound_V) {
+    float m = 0.f;
+    for (int p = 0; p < TSVD_COLMAX_PARTS; ++p) m = fmaxf(m, part[(size_t)p * Bp + col]);
+    const float bound = bound_V * m;
+    int ex = 0;
+    if (bound > 0.f && bound < 3.0e38f) (void)frexpf(bound, &ex);   // bound < 2^ex
+    int e = 14 - ex;
+    e = max(-110, min(110, e));
+    return ldexpf(1.0f, e);
+}
+
+// ---- kernels 1 and 2 ------------------------------------------------------------------------
+struct gemm_args {
+    const uint32_t* tiles;    // packed A: [strips][nkt][256 words]
+    int nkt;                  // 256-wide tiles along the contraction index
+    const uint16_t* act;      // activations [kdim][ld] 16-bit
+    long long ld;
+    int kvalid;               // activation rows that exist (stage 1: N); others read as zero
+    int bvalid;               // activation columns that exist
+    int act_fast;             // 1: rows 16-byte aligned, any full 8-column chunk may be loaded whole
+    const float* S;           // stage 1: row scales
+    const float* colpart;     // column maxima partials [PARTS][Bp]
+    int Bp;
+    float bound_V;
+    void* out;                // stage 1: fp16 [Kp][Bp];  stage 2: fp32 [M][ldy]
+    long long ld_out;
+    int rows_valid;           // stage 2: M
+};
+
+template <bool STAGE2>
+__device__ __forceinline__ f32x4 mfma16(const u32x4& a, const u32x2& blo, const u32x2& bhi, f32x4 acc) {
+    u32x4 b = {blo.x, blo.y, bhi.x, bhi.y};
+    if constexpr (STAGE2)
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), acc, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+}
+
+__device__ __forceinline__ u32x2 lds_tr(const unsigned char* lds_byte_ptr) {
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr_t;
+    s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(lds_byte_ptr));
+    return __builtin_bit_cast(u32x2, r);
+}
+
+// Workgroup tile (WM*TM*16 rows) x (WN*TN*16 tokens); WM x WN wavefronts, each TM x TN MFMA blocks.
+template <int WM, int WN, int TM, int TN, bool STAGE2>
+__global__ void __launch_bounds__(64 * WM * WN)
+tsvd_gemm_kernel(gemm_args p) {
+    constexpr int THREADS = 64 * WM * WN;
+    constexpr int BT = WN * TN * 16;                 // tokens per workgroup tile
+    constexpr int ROWB = BT * 2;                     // bytes per LDS row
+    constexpr int NBLK = BT / 16;                    // 32-byte blocks per LDS row
+    constexpr int CHUNKS = KT * BT / 8;              // 16-byte chunks per stage
+    constexpr int CPT = CHUNKS / THREADS;            // chunks per thread
+    static_assert(CHUNKS % THREADS == 0, "tile/threads mismatch");
+    extern __shared__ __align__(16) unsigned char smem[];   // 2 stages x KT x ROWB
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / WN, wn = wave - wm * WN;
+    const int i = lane & 15, g = lane >> 4;
+    const int b0 = blockIdx.x * BT;
+    const int strip0 = (blockIdx.y * WM + wm) * TM;  // first 16-row strip of this wavefront
+    const int nstages = p.nkt * (256 / KT);
+
+    // swizzle: 32-byte block j of row r is stored at block j ^ f(r), f(r) = (r & 3) | ((r >> 3) & 3) << 2
+    const int f_lane = ((i >> 2) | (g << 2)) & (NBLK - 1);
+    // byte offset (within a stage) of this lane's transposed read for k-step q, second half adds 4 rows
+    const int tr_row = 8 * g + (i >> 2);
+    const int tr_in = (i & 3) * 8;
+
+    f32x4 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // ---- activation tile: global -> registers -> LDS
+    u32x4 xreg[CPT];
+    auto load_x = [&](int stage) {
+        const int k0 = stage * KT;
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) {
+            const int id = threadIdx.x + c * THREADS;
+            const int r = id / (BT / 8), ch = id - r * (BT / 8);
+            const int k = k0 + r, col = b0 + ch * 8;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (k < p.kvalid) {
+                const uint16_t* src = p.act + (size_t)k * p.ld + col;
+                if (p.act_fast && col + 8 <= p.bvalid) {
+                    v = *reinterpret_cast<const u32x4*>(src);
+                } else {
+                    uint32_t e[8];
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) e[t] = (col + t < p.bvalid) ? (uint32_t)src[t] : 0u;
+                    v = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+                }
+            }
+            xreg[c] = v;
+        }
+    };
+    auto store_x = [&](int buf) {
+        unsigned char* base = smem + buf * (KT * ROWB);
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) {
+            const int id = threadIdx.x + c * THREADS;
+            const int r = id / (BT / 8), ch = id - r * (BT / 8);
+            const int f = ((r & 3) | (((r >> 3) & 3) << 2)) & (NBLK - 1);
+            const int blk = (ch >> 1) ^ f;
+            *reinterpret_cast<u32x4*>(base + r * ROWB + blk * 32 + (ch & 1) * 16) = xreg[c];
+        }
+    };
+    // ---- weights: one code word per strip and stage, straight from global/L2
+    const uint32_t* wbase = p.tiles + ((size_t)strip0 * p.nkt) * 256 + lane * 4;
+    uint32_t wcur[TM], wnext[TM];
+    auto load_w = [&](int stage, uint32_t (&w)[TM]) {
+        const int T = stage >> 2, d = stage & 3;
+#pragma unroll
+        for (int a = 0; a < TM; ++a) w[a] = wbase[((size_t)a * p.nkt + T) * 256 + d];
+    };
+
+    load_x(0);
+    load_w(0, wcur);
+    store_x(0);
+    __syncthreads();
+
+    for (int s = 0; s < nstages; ++s) {
+        const bool more = s + 1 < nstages;
+        if (more) {
+            load_x(s + 1);
+            load_w(s + 1, wnext);
+        }
+        const unsigned char* base = smem + (s & 1) * (KT * ROWB);
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            u32x2 blo[TN], bhi[TN];
+#pragma unroll
+            for (int b = 0; b < TN; ++b) {
+                const int blk = ((wn * TN + b) ^ f_lane);
+                const unsigned char* ptr = base + (32 * q + tr_row) * ROWB + blk * 32 + tr_in;
+                blo[b] = lds_tr(ptr);
+                bhi[b] = lds_tr(ptr + 4 * ROWB);
+            }
+#pragma unroll
+            for (int a = 0; a < TM; ++a) {
+                const uint32_t w = wcur[a];
+                u32x4 av;
+                if (q == 0) av = u32x4{TSVD_DEC(w, 0), TSVD_DEC(w, 1), TSVD_DEC(w, 2), TSVD_DEC(w, 3)};
+                else        av = u32x4{TSVD_DEC(w, 4), TSVD_DEC(w, 5), TSVD_DEC(w, 6), w & 0xC000C000u};
+#pragma unroll
+                for (int b = 0; b < TN; ++b) acc[a][b] = mfma16<STAGE2>(av, blo[b], bhi[b], acc[a][b]);
+            }
+        }
+        if (more) {
+            store_x((s + 1) & 1);
+#pragma unroll
+            for (int a = 0; a < TM; ++a) wcur[a] = wnext[a];
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue.  D block layout: lane holds column i, rows 4 g + v.
+    float cs[TN];
+#pragma unroll
+    for (int b = 0; b < TN; ++b) {
+        const int col = b0 + (wn * TN + b) * 16 + i;
+        const float sc = column_scale(p.colpart, p.Bp, col, p.bound_V);
+        cs[b] = STAGE2 ? 0.5f / sc : 0.5f * sc;      // powers of two: exact
+    }
+#pragma unroll
+    for (int a = 0; a < TM; ++a) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int row = (strip0 + a) * 16 + 4 * g + v;
+            if constexpr (STAGE2) {
+                if (row < p.rows_valid) {
+                    float* dst = static_cast<float*>(p.out) + (size_t)row * p.ld_out;
+#pragma unroll
+                    for (int b = 0; b < TN; ++b) {
+                        const int col = b0 + (wn * TN + b) * 16 + i;
+                        if (col < p.bvalid) dst[col] = acc[a][b][v] * cs[b];
+                    }
+                }
+            } else {
+                const float sr = p.S[row];            // zero beyond K: padded rows of Z become 0
+                _Float16* dst = static_cast<_Float16*>(p.out) + (size_t)row * p.ld_out;
+#pragma unroll
+                for (int b = 0; b < TN; ++b) {
+                    const int col = b0 + (wn * TN + b) * 16 + i;
+                    dst[col] = (_Float16)((acc[a][b][v] * sr) * cs[b]);
+                }
+            }
+        }
+    }
+}
+
+template <int WM, int WN, int TM, int TN, bool STAGE2>
+hipError_t launch_gemm(const gemm_args& a, int row_tiles, int col_tiles, hipStream_t stream) {
+    constexpr int BT = WN * TN * 16;
+    constexpr size_t lds = 2 * KT * BT * 2;
+    hipLaunchKernelGGL((tsvd_gemm_kernel<WM, WN, TM, TN, STAGE2>), dim3(col_tiles, row_tiles), dim3(64 * WM * WN), lds,
+                       stream, a);
+    return hipGetLastError();
+}
+
+template <int WM, int WN, int TM, int TN, bool STAGE2>
+hipError_t init_gemm() {
+    constexpr int BT = WN * TN * 16;
+    constexpr int lds = 2 * KT * BT * 2;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_kernel<WM, WN, TM, TN, STAGE2>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+}
+
+}  // namespace
+
+hipError_t tsvd_gemm_init() {
+    hipError_t e;
+    if ((e = init_gemm<2, 4, 8, 4, false>()) != hipSuccess) return e;
+    if ((e = init_gemm<2, 4, 8, 4, true>()) != hipSuccess) return e;
+    if ((e = init_gemm<2, 2, 4, 4, false>()) != hipSuccess) return e;
+    if ((e = init_gemm<2, 2, 4, 4, true>()) != hipSuccess) return e;
+    return hipSuccess;
+}
+
+hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
+    const tsvd_blob_header& hd = *g.hd;
+    const int Bp = (int)tsvd_round_up(g.B, 256);
+    float* colpart = static_cast<float*>(g.ws);
+    const size_t part_bytes = (((size_t)TSVD_COLMAX_PARTS * Bp * 4) + 255) & ~(size_t)255;
+    _Float16* Z = reinterpret_cast<_Float16*>(static_cast<uint8_t*>(g.ws) + part_bytes);
+
+    hipLaunchKernelGGL(tsvd_colmax_kernel, dim3((unsigned)((g.B + 127) / 128), TSVD_COLMAX_PARTS), dim3(256), 0, stream,
+                       static_cast<const uint16_t*>(g.x), g.ldx, (int)hd.N, (int)g.B, Bp, colpart);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+
+    gemm_args a1;
+    a1.tiles = reinterpret_cast<const uint32_t*>(g.blob + hd.off_V);
+    a1.nkt = (int)(hd.Np / 256);
+    a1.act = static_cast<const uint16_t*>(g.x);
+    a1.ld = g.ldx;
+    a1.kvalid = (int)hd.N;
+    a1.bvalid = (int)g.B;
+    a1.act_fast = (g.ldx % 8 == 0) && ((reinterpret_cast<uintptr_t>(g.x) & 15u) == 0);
+    a1.S = reinterpret_cast<const float*>(g.blob + hd.off_S);
+    a1.colpart = colpart;
+    a1.Bp = Bp;
+    a1.bound_V = g.bound_V;
+    a1.out = Z;
+    a1.ld_out = Bp;
+    a1.rows_valid = (int)hd.Kp;
+
+    gemm_args a2 = a1;
+    a2.tiles = reinterpret_cast<const uint32_t*>(g.blob + hd.off_U);
+    a2.nkt = (int)(hd.Kp / 256);
+    a2.act = reinterpret_cast<const uint16_t*>(Z);
+    a2.ld = Bp;
+    a2.kvalid = (int)hd.Kp;
+    a2.bvalid = (int)g.B;
+    a2.act_fast = 1;
+    a2.S = nullptr;
+    a2.out = g.y;
+    a2.ld_out = g.ldy;
+    a2.rows_valid = (int)hd.M;
+
+    // Large tiles (256 x 256) when they still give every compute unit work; else 128 x 128.
+    const long long big_tiles = (hd.Mp / 256) * (long long)(Bp / 256);
+    const bool big = big_tiles >= 256;
+    if (big) {
+        e = launch_gemm<2, 4, 8, 4, false>(a1, (int)(hd.Kp / 256), Bp / 256, stream);
+        if (e != hipSuccess) return e;
+        return launch_gemm<2, 4, 8, 4, true>(a2, (int)(hd.Mp / 256), Bp / 256, stream);
+    }
+    e = launch_gemm<2, 2, 4, 4, false>(a1, (int)(hd.Kp / 128), Bp / 128, stream);
+    if (e != hipSuccess) return e;
+    return launch_gemm<2, 2, 4, 4, true>(a2, (int)(hd.Mp / 128), Bp / 128, stream);
+}

@@ -1,0 +1,237 @@
+// Host-side packer / unpacker of the 2-bit ternary tile format (see tsvd_layout.h).
+// Pure host code: usable without a GPU.
+#include "tsvd_layout.h"
+#include "../../include/tsvd.h"
+
+#include <algorithm>
+#include <atomic>
+#include <cstring>
+#include <thread>
+#include <vector>
+
+namespace {
+
+struct Sections {
+    int64_t Mp, Kp, Np;
+    uint64_t off_S, off_U, off_V, off_nnzU, off_nnzV, total;
+    int64_t tilesU, tilesV;
+};
+
+bool sections(int64_t M, int64_t K, int64_t N, Sections* s) {
+    if (M <= 0 || K <= 0 || N <= 0) return false;
+    // keep every tile index and byte offset far inside 63 bits
+    if (M > (int64_t(1) << 28) || K > (int64_t(1) << 28) || N > (int64_t(1) << 28)) return false;
+    s->Mp = tsvd_round_up(M, TSVD_DIM_ALIGN);
+    s->Kp = tsvd_round_up(K, TSVD_DIM_ALIGN);
+    s->Np = tsvd_round_up(N, TSVD_DIM_ALIGN);
+    s->tilesU = (s->Mp / TSVD_TILE_ROWS) * (s->Kp / TSVD_TILE_COLS);
+    s->tilesV = (s->Kp / TSVD_TILE_ROWS) * (s->Np / TSVD_TILE_COLS);
+    uint64_t off = sizeof(tsvd_blob_header);
+    s->off_S = off;
+    off += (uint64_t)tsvd_round_up(s->Kp * 4, 256);
+    s->off_U = off;
+    off += (uint64_t)s->tilesU * TSVD_TILE_BYTES;
+    s->off_V = off;
+    off += (uint64_t)s->tilesV * TSVD_TILE_BYTES;
+    s->off_nnzU = off;
+    off += (uint64_t)tsvd_round_up(s->tilesU * 2, 256);
+    s->off_nnzV = off;
+    off += (uint64_t)tsvd_round_up(s->tilesV * 2, 256);
+    s->total = off;
+    return true;
+}
+
+unsigned worker_count(int64_t work_items) {
+    unsigned hw = std::thread::hardware_concurrency();
+    if (hw == 0) hw = 1;
+    hw = std::min(hw, 32u);
+    if (work_items < 64) return 1;
+    return (unsigned)std::min<int64_t>(hw, work_items / 32 + 1);
+}
+
+// Packs A [R][C] (row-major, valid part R x C, padded to Rp x Cp) into tiles.
+// Returns false if an entry is outside {-1,0,+1}.  nnz_total receives the sum of counts.
+bool pack_matrix(const int8_t* A, int64_t R, int64_t C, int64_t Rp, int64_t Cp,
+                 uint32_t* tiles, uint16_t* nnz, int64_t* nnz_total) {
+    const int64_t strips = Rp / TSVD_TILE_ROWS, nkt = Cp / TSVD_TILE_COLS;
+    std::atomic<bool> bad(false);
+    std::atomic<int64_t> total(0);
+    auto work = [&](int64_t s0, int64_t s1) {
+        int64_t local_total = 0;
+        for (int64_t s = s0; s < s1 && !bad.load(std::memory_order_relaxed); ++s) {
+            for (int64_t T = 0; T < nkt; ++T) {
+                uint32_t* tile = tiles + (s * nkt + T) * (TSVD_TILE_BYTES / 4);
+                std::memset(tile, 0, TSVD_TILE_BYTES);
+                int count = 0;
+                for (int i = 0; i < TSVD_TILE_ROWS; ++i) {
+                    const int64_t r = s * TSVD_TILE_ROWS + i;
+                    if (r >= R) break;
+                    const int64_t c0 = T * TSVD_TILE_COLS;
+                    const int64_t cn = std::min<int64_t>(TSVD_TILE_COLS, C - c0);
+                    const int8_t* row = A + r * C + c0;
+                    for (int64_t c = 0; c < cn; ++c) {
+                        const int v = row[c];
+                        if (v == 0) continue;
+                        if (v != 1 && v != -1) { bad.store(true); return; }
+                        int word, bit;
+                        tsvd_code_position(i, (int)c, &word, &bit);
+                        tile[word] |= (v > 0 ? 1u : 3u) << bit;
+                        ++count;
+                    }
+                }
+                nnz[s * nkt + T] = (uint16_t)count;
+                local_total += count;
+            }
+        }
+        total.fetch_add(local_total);
+    };
+    const unsigned nw = worker_count(strips);
+    if (nw <= 1) {
+        work(0, strips);
+    } else {
+        std::vector<std::thread> th;
+        const int64_t per = (strips + nw - 1) / nw;
+        for (unsigned w = 0; w < nw; ++w) {
+            const int64_t a = w * per, b = std::min<int64_t>(strips, a + per);
+            if (a < b) th.emplace_back(work, a, b);
+        }
+        for (auto& t : th) t.join();
+    }
+    *nnz_total = total.load();
+    return !bad.load();
+}
+
+// Inverse of pack_matrix for the valid R x C part; verifies padding is zero, no code is 10b
+// and the stored counts match.  Returns false on any corruption.
+bool unpack_matrix(int8_t* A, int64_t R, int64_t C, int64_t Rp, int64_t Cp,
+                   const uint32_t* tiles, const uint16_t* nnz, bool check_only) {
+    const int64_t strips = Rp / TSVD_TILE_ROWS, nkt = Cp / TSVD_TILE_COLS;
+    std::atomic<bool> bad(false);
+    auto work = [&](int64_t s0, int64_t s1) {
+        for (int64_t s = s0; s < s1 && !bad.load(std::memory_order_relaxed); ++s) {
+            for (int64_t T = 0; T < nkt; ++T) {
+                const uint32_t* tile = tiles + (s * nkt + T) * (TSVD_TILE_BYTES / 4);
+                int count = 0;
+                for (int i = 0; i < TSVD_TILE_ROWS; ++i) {
+                    const int64_t r = s * TSVD_TILE_ROWS + i;
+                    for (int c = 0; c < TSVD_TILE_COLS; ++c) {
+                        int word, bit;
+                        tsvd_code_position(i, c, &word, &bit);
+                        const unsigned code = (tile[word] >> bit) & 3u;
+                        const int64_t col = T * TSVD_TILE_COLS + c;
+                        const bool inside = r < R && col < C;
+                        if (code == 2u || (!inside && code != 0u)) { bad.store(true); return; }
+                        if (code) ++count;
+                        if (inside && !check_only) A[r * C + col] = code == 0u ? 0 : (code == 1u ? 1 : -1);
+                    }
+                }
+                if (count != nnz[s * nkt + T]) { bad.store(true); return; }
+            }
+        }
+    };
+    const unsigned nw = worker_count(strips);
+    if (nw <= 1) {
+        work(0, strips);
+    } else {
+        std::vector<std::thread> th;
+        const int64_t per = (strips + nw - 1) / nw;
+        for (unsigned w = 0; w < nw; ++w) {
+            const int64_t a = w * per, b = std::min<int64_t>(strips, a + per);
+            if (a < b) th.emplace_back(work, a, b);
+        }
+        for (auto& t : th) t.join();
+    }
+    return !bad.load();
+}
+
+}  // namespace
+
+extern "C" size_t tsvd_packed_bytes(int64_t M, int64_t K, int64_t N) {
+    Sections s;
+    return sections(M, K, N, &s) ? (size_t)s.total : 0;
+}
+
+extern "C" tsvd_status tsvd_pack_host(const int8_t* U, const float* S, const int8_t* V,
+                                      int64_t M, int64_t K, int64_t N, void* blob, size_t blob_bytes) {
+    Sections sc;
+    if (!U || !S || !V || !blob || !sections(M, K, N, &sc)) return TSVD_EINVAL;
+    if (blob_bytes < sc.total) return TSVD_EINVAL;
+    uint8_t* base = static_cast<uint8_t*>(blob);
+
+    // Validate before touching the output so that a failure leaves it untouched.
+    // (pack_matrix re-validates while packing; this pass is cheap next to it.)
+    for (int64_t i = 0; i < M * K; ++i)
+        if (U[i] < -1 || U[i] > 1) return TSVD_EVALUE;
+    for (int64_t i = 0; i < K * N; ++i)
+        if (V[i] < -1 || V[i] > 1) return TSVD_EVALUE;
+
+    std::memset(base, 0, sc.total);
+    tsvd_blob_header hd;
+    std::memset(&hd, 0, sizeof hd);
+    hd.magic = TSVD_MAGIC;
+    hd.version = TSVD_FORMAT_VERSION;
+    hd.header_bytes = sizeof hd;
+    hd.M = M; hd.K = K; hd.N = N;
+    hd.Mp = sc.Mp; hd.Kp = sc.Kp; hd.Np = sc.Np;
+    hd.off_S = sc.off_S; hd.off_U = sc.off_U; hd.off_V = sc.off_V;
+    hd.off_nnzU = sc.off_nnzU; hd.off_nnzV = sc.off_nnzV;
+    hd.total_bytes = sc.total;
+
+    std::memcpy(base + sc.off_S, S, (size_t)K * sizeof(float));
+    if (!pack_matrix(U, M, K, sc.Mp, sc.Kp, reinterpret_cast<uint32_t*>(base + sc.off_U),
+                     reinterpret_cast<uint16_t*>(base + sc.off_nnzU), &hd.nnzU))
+        return TSVD_EVALUE;
+    if (!pack_matrix(V, K, N, sc.Kp, sc.Np, reinterpret_cast<uint32_t*>(base + sc.off_V),
+                     reinterpret_cast<uint16_t*>(base + sc.off_nnzV), &hd.nnzV))
+        return TSVD_EVALUE;
+    std::memcpy(base, &hd, sizeof hd);
+    return TSVD_OK;
+}
+
+extern "C" tsvd_status tsvd_unpack_host(const void* blob, size_t blob_bytes, int8_t* U, float* S,
+                                        int8_t* V, int64_t* M, int64_t* K, int64_t* N) {
+    if (!blob || blob_bytes < sizeof(tsvd_blob_header)) return TSVD_EINVAL;
+    tsvd_blob_header hd;
+    std::memcpy(&hd, blob, sizeof hd);
+    if (hd.magic != TSVD_MAGIC || hd.version != TSVD_FORMAT_VERSION || hd.header_bytes != sizeof hd)
+        return TSVD_EINVAL;
+    Sections sc;
+    if (!sections(hd.M, hd.K, hd.N, &sc)) return TSVD_EINVAL;
+    if (sc.total != hd.total_bytes || blob_bytes < sc.total || sc.Mp != hd.Mp || sc.Kp != hd.Kp ||
+        sc.Np != hd.Np || sc.off_S != hd.off_S || sc.off_U != hd.off_U || sc.off_V != hd.off_V ||
+        sc.off_nnzU != hd.off_nnzU || sc.off_nnzV != hd.off_nnzV)
+        return TSVD_EINVAL;
+    const uint8_t* base = static_cast<const uint8_t*>(blob);
+    if (U || S || V) {
+        // S padding must be zero: the kernels rely on it.
+        const float* Sp = reinterpret_cast<const float*>(base + sc.off_S);
+        for (int64_t k = hd.K; k < sc.Kp; ++k) {
+            uint32_t bits;
+            std::memcpy(&bits, Sp + k, 4);
+            if (bits != 0) return TSVD_EVALUE;
+        }
+        if (!unpack_matrix(U, hd.M, hd.K, sc.Mp, sc.Kp, reinterpret_cast<const uint32_t*>(base + sc.off_U),
+                           reinterpret_cast<const uint16_t*>(base + sc.off_nnzU), U == nullptr))
+            return TSVD_EVALUE;
+        if (!unpack_matrix(V, hd.K, hd.N, sc.Kp, sc.Np, reinterpret_cast<const uint32_t*>(base + sc.off_V),
+                           reinterpret_cast<const uint16_t*>(base + sc.off_nnzV), V == nullptr))
+            return TSVD_EVALUE;
+        if (S) std::memcpy(S, Sp, (size_t)hd.K * sizeof(float));
+    }
+    if (M) *M = hd.M;
+    if (K) *K = hd.K;
+    if (N) *N = hd.N;
+    return TSVD_OK;
+}
+
+extern "C" const char* tsvd_strerror(tsvd_status s) {
+    switch (s) {
+        case TSVD_OK: return "ok";
+        case TSVD_EINVAL: return "invalid argument";
+        case TSVD_EVALUE: return "entry of U or V outside {-1,0,+1}, or corrupt packed code";
+        case TSVD_ENOMEM: return "host memory allocation failed";
+        case TSVD_EDEVICE: return "HIP call failed";
+        case TSVD_EUNSUPPORTED: return "unsupported request";
+    }
+    return "unknown status";
+}

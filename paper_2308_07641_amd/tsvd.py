@@ -1,0 +1,201 @@
+"""ctypes binding with the same names as the C ABI (include/tsvd.h).
+
+Argument marshalling only.  If libtsvd.so has not been built the import of this module still
+succeeds (so that the build step can import the package) but every call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+TSVD_F32 = 0
+TSVD_BF16 = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libtsvd.so")
+_lib = None
+
+_vp = ctypes.c_void_p
+_i64 = ctypes.c_int64
+_sz = ctypes.c_size_t
+_pi64 = ctypes.POINTER(ctypes.c_int64)
+
+_PROTOTYPES = {
+    "tsvd_packed_bytes": (_sz, [_i64, _i64, _i64]),
+    "tsvd_pack_host": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _sz]),
+    "tsvd_unpack_host": (ctypes.c_int, [_vp, _sz, _vp, _vp, _vp, _pi64, _pi64, _pi64]),
+    "tsvd_pack": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _sz, ctypes.POINTER(_vp)]),
+    "tsvd_unpack": (ctypes.c_int, [_vp, _vp, _vp, _vp]),
+    "tsvd_info": (ctypes.c_int, [_vp, _pi64, _pi64, _pi64, _pi64, _pi64]),
+    "tsvd_workspace_bytes": (_sz, [_vp, _i64, ctypes.c_int]),
+    "tsvd_forward": (ctypes.c_int, [_vp, _vp, ctypes.c_int, _i64, _i64, _vp, ctypes.c_int, _i64, _vp, _sz, _vp]),
+    "tsvd_free": (None, [_vp]),
+    "tsvd_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+}
+
+
+class TsvdError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {tsvd_strerror(status)} (status {status})")
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libtsvd.so; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it with "
+                               "`python -m paper_2308_07641_amd.build` (or __graft_entry__.build())")
+        lib = ctypes.CDLL(_LIB_PATH)
+        for name, (res, args) in _PROTOTYPES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def tsvd_strerror(status: int) -> str:
+    return load_library().tsvd_strerror(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise TsvdError(status, where)
+
+
+def _weights(U, S, V):
+    U = np.ascontiguousarray(U, dtype=np.int8)
+    V = np.ascontiguousarray(V, dtype=np.int8)
+    S = np.ascontiguousarray(S, dtype=np.float32)
+    if U.ndim != 2 or V.ndim != 2 or S.ndim != 1 or U.shape[1] != V.shape[0] or S.shape[0] != U.shape[1]:
+        raise ValueError("expected U [M,K] int8, S [K] float32, V [K,N] int8")
+    return U, S, V
+
+
+def tsvd_packed_bytes(M: int, K: int, N: int) -> int:
+    return int(load_library().tsvd_packed_bytes(M, K, N))
+
+
+def tsvd_pack_host(U, S, V) -> np.ndarray:
+    """Packs into a host uint8 array (no GPU needed)."""
+    U, S, V = _weights(U, S, V)
+    M, K = U.shape
+    N = V.shape[1]
+    blob = np.empty(tsvd_packed_bytes(M, K, N), dtype=np.uint8)
+    _check(load_library().tsvd_pack_host(U.ctypes.data, S.ctypes.data, V.ctypes.data, M, K, N,
+                                         blob.ctypes.data, blob.nbytes), "tsvd_pack_host")
+    return blob
+
+
+def tsvd_unpack_host(blob: np.ndarray):
+    """Returns (U, S, V) from a host blob."""
+    blob = np.ascontiguousarray(blob, dtype=np.uint8)
+    lib = load_library()
+    M, K, N = _i64(), _i64(), _i64()
+    _check(lib.tsvd_unpack_host(blob.ctypes.data, blob.nbytes, None, None, None,
+                                ctypes.byref(M), ctypes.byref(K), ctypes.byref(N)), "tsvd_unpack_host")
+    U = np.empty((M.value, K.value), dtype=np.int8)
+    S = np.empty(K.value, dtype=np.float32)
+    V = np.empty((K.value, N.value), dtype=np.int8)
+    _check(lib.tsvd_unpack_host(blob.ctypes.data, blob.nbytes, U.ctypes.data, S.ctypes.data, V.ctypes.data,
+                                None, None, None), "tsvd_unpack_host")
+    return U, S, V
+
+
+class Handle:
+    """Owner of a tsvd_handle*; free with tsvd_free (also freed on garbage collection)."""
+
+    def __init__(self, ptr: int, M: int, K: int, N: int, keepalive=None):
+        self.ptr = ptr
+        self.M, self.K, self.N = M, K, N
+        self._keepalive = keepalive     # caller-provided device buffer, if any
+
+    def __del__(self):
+        try:
+            tsvd_free(self)
+        except Exception:
+            pass
+
+
+def tsvd_pack(U, S, V, dev_buf=None) -> Handle:
+    """Packs and uploads to the current HIP device.  dev_buf: optional torch uint8 CUDA tensor."""
+    U, S, V = _weights(U, S, V)
+    M, K = U.shape
+    N = V.shape[1]
+    out = _vp()
+    buf_ptr, buf_bytes = None, 0
+    if dev_buf is not None:
+        buf_ptr, buf_bytes = dev_buf.data_ptr(), dev_buf.numel() * dev_buf.element_size()
+    _check(load_library().tsvd_pack(U.ctypes.data, S.ctypes.data, V.ctypes.data, M, K, N,
+                                    buf_ptr, buf_bytes, ctypes.byref(out)), "tsvd_pack")
+    return Handle(out.value, M, K, N, keepalive=dev_buf)
+
+
+def tsvd_unpack(h: Handle):
+    U = np.empty((h.M, h.K), dtype=np.int8)
+    S = np.empty(h.K, dtype=np.float32)
+    V = np.empty((h.K, h.N), dtype=np.int8)
+    _check(load_library().tsvd_unpack(h.ptr, U.ctypes.data, S.ctypes.data, V.ctypes.data), "tsvd_unpack")
+    return U, S, V
+
+
+def tsvd_info(h: Handle) -> dict:
+    vals = [_i64() for _ in range(5)]
+    _check(load_library().tsvd_info(h.ptr, *[ctypes.byref(v) for v in vals]), "tsvd_info")
+    return dict(zip(("M", "K", "N", "nnzU", "nnzV"), (v.value for v in vals)))
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return TSVD_F32
+    if t.dtype == torch.bfloat16:
+        return TSVD_BF16
+    raise TypeError(f"unsupported activation dtype {t.dtype}")
+
+
+def tsvd_workspace_bytes(h: Handle, B: int, x_dtype: int) -> int:
+    return int(load_library().tsvd_workspace_bytes(h.ptr, B, x_dtype))
+
+
+def tsvd_forward(h: Handle, x, y=None, workspace=None, stream=None):
+    """y[M,B] (fp32) = U (diag(S) (V x)) for x [N,B] (or [N]) fp32/bf16 on the GPU.
+
+    x, y, workspace are torch CUDA tensors used as plain device buffers; the work is
+    enqueued on `stream` (default: torch's current stream) and not synchronised.
+    """
+    import torch
+    if not x.is_cuda:
+        raise ValueError("x must live on the GPU")
+    x2 = x if x.dim() == 2 else x.unsqueeze(1)
+    if x2.shape[0] != h.N or x2.stride(1) != 1:
+        raise ValueError("x must be [N,B] with unit column stride")
+    B = x2.shape[1]
+    ldx = x2.stride(0) if x2.shape[0] > 1 else max(B, x2.stride(0))
+    if y is None:
+        y = torch.empty((h.M, B), dtype=torch.float32, device=x.device)
+    if y.dtype != torch.float32 or y.shape != (h.M, B) or y.stride(1) != 1 or not y.is_cuda:
+        raise ValueError("y must be a float32 GPU tensor [M,B] with unit column stride")
+    ldy = y.stride(0) if y.shape[0] > 1 else max(B, y.stride(0))
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    _check(load_library().tsvd_forward(h.ptr, x2.data_ptr(), _dtype_code(x2), B, ldx, y.data_ptr(), TSVD_F32, ldy,
+                                       ws_ptr, ws_bytes, stream), "tsvd_forward")
+    return y
+
+
+def tsvd_free(h: Handle) -> None:
+    if h is not None and getattr(h, "ptr", None):
+        load_library().tsvd_free(h.ptr)
+        h.ptr = None

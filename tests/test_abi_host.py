@@ -1,0 +1,157 @@
+"""CPU-only tests of the C-ABI library: exported symbols, the host packer and its error paths.
+No compute entry point is called here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2308_07641_amd as tsvd
+import workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "tsvd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tsvd_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert {"tsvd_pack", "tsvd_forward", "tsvd_free"} <= set(names)
+    lib = ctypes.CDLL(tsvd.lib_path())
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/tsvd.h but not exported"
+
+
+def test_strerror_covers_all_codes():
+    texts = [tsvd.tsvd_strerror(s) for s in range(6)]
+    assert texts[0] == "ok" and len(set(texts)) == 6
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (4, 4, 4), (3, 5, 7), (16, 256, 16), (17, 257, 33),
+                                   (256, 256, 512), (300, 70, 513), (5, 1000, 2)])
+def test_pack_unpack_round_trip_is_bit_exact(M, N, K):
+    i = workloads.make_inputs(M, N, K, 1, 0.5, 0.02, "f32", seed=M * 1000 + N * 10 + K)
+    blob = tsvd.tsvd_pack_host(i.U, i.S, i.V)
+    assert blob.nbytes == tsvd.tsvd_packed_bytes(M, K, N)
+    U, S, V = tsvd.tsvd_unpack_host(blob)
+    assert U.dtype == np.int8 and np.array_equal(U, i.U)
+    assert V.dtype == np.int8 and np.array_equal(V, i.V)
+    assert np.array_equal(S.view(np.uint32), i.S.view(np.uint32))
+    assert set(np.unique(U)) <= {-1, 0, 1} and set(np.unique(V)) <= {-1, 0, 1}
+    # packing is a pure function of its inputs
+    assert np.array_equal(blob, tsvd.tsvd_pack_host(i.U, i.S, i.V))
+
+
+def _sections(blob):
+    """Reads the blob header (layout documented in csrc/tsvd_layout.h)."""
+    h = np.frombuffer(blob[:256].tobytes(), dtype=np.int64)
+    names = ("magic", "ver_hdr", "M", "K", "N", "Mp", "Kp", "Np", "off_S", "off_U", "off_V",
+             "off_nnzU", "off_nnzV", "total", "nnzU", "nnzV")
+    return dict(zip(names, h[:16].tolist()))
+
+
+def test_two_bit_codes_and_counts():
+    """2 bits per element (section "Connection with BNN"): 00 = 0, 01 = +1, 11 = -1, 10 unused;
+    the per-tile counts sum to the addition count of supplement Table S1."""
+    i = workloads.make_inputs(40, 300, 70, 1, 0.6, 0.02, "f32", seed=5)
+    blob = tsvd.tsvd_pack_host(i.U, i.S, i.V)
+    s = _sections(blob)
+    assert (s["Mp"], s["Kp"], s["Np"]) == (256, 256, 512)
+    assert s["nnzU"] == np.count_nonzero(i.U) and s["nnzV"] == np.count_nonzero(i.V)
+    for off, end, ref, noff in ((s["off_U"], s["off_V"], i.U, s["off_nnzU"]),
+                                (s["off_V"], s["off_nnzU"], i.V, s["off_nnzV"])):
+        words = np.frombuffer(blob[off:end].tobytes(), dtype=np.uint32)
+        codes = (words[:, None] >> (2 * np.arange(16, dtype=np.uint32))[None, :]) & 3
+        counts = np.bincount(codes.ravel(), minlength=4)
+        assert counts[2] == 0                                   # 10 is never produced
+        assert counts[1] == np.count_nonzero(ref == 1)
+        assert counts[3] == np.count_nonzero(ref == -1)
+        ntiles = words.size // 256
+        nnz = np.frombuffer(blob[noff:noff + 2 * ntiles].tobytes(), dtype=np.uint16)
+        per_tile = (codes != 0).reshape(ntiles, -1).sum(axis=1)
+        assert np.array_equal(nnz, per_tile)
+        assert nnz.sum() == np.count_nonzero(ref)
+    # storage really is 2 bits per (padded) element
+    assert s["off_V"] - s["off_U"] == s["Mp"] * s["Kp"] // 4
+    assert s["off_nnzU"] - s["off_V"] == s["Kp"] * s["Np"] // 4
+
+
+def test_single_element_sets_exactly_its_code():
+    U = np.zeros((20, 300), dtype=np.int8)
+    V = np.zeros((300, 10), dtype=np.int8)
+    S = np.ones(300, dtype=np.float32)
+    base = tsvd.tsvd_pack_host(U, S, V)
+    s = _sections(base)
+    for (r, c, val, bits) in ((0, 0, 1, 1), (19, 299, -1, 2), (7, 131, 1, 1), (16, 256, -1, 2)):
+        U2 = U.copy()
+        U2[r, c] = val
+        b2 = tsvd.tsvd_pack_host(U2, S, V)
+        diff = np.flatnonzero(base != b2)
+        # one code byte, the tile's count, and the header's total change; nothing else
+        in_tiles = diff[(diff >= s["off_U"]) & (diff < s["off_V"])]
+        assert in_tiles.size == 1
+        assert bin(int(base[in_tiles[0]] ^ b2[in_tiles[0]])).count("1") == bits
+        U3, _, _ = tsvd.tsvd_unpack_host(b2)
+        assert np.array_equal(U3, U2)
+
+
+def test_pack_rejects_bad_input_and_leaves_output_untouched():
+    i = workloads.make_inputs(8, 8, 8, 1, 0.5, 0.02, "f32", seed=1)
+    lib = tsvd.load_library()
+    n = tsvd.tsvd_packed_bytes(8, 8, 8)
+    blob = np.full(n, 0xAB, dtype=np.uint8)
+    U = i.U.copy()
+    U[3, 3] = 2
+    rc = lib.tsvd_pack_host(U.ctypes.data, i.S.ctypes.data, i.V.ctypes.data, 8, 8, 8, blob.ctypes.data, n)
+    assert rc == 2 and np.all(blob == 0xAB)
+    V = i.V.copy()
+    V[0, 7] = -128
+    rc = lib.tsvd_pack_host(i.U.ctypes.data, i.S.ctypes.data, V.ctypes.data, 8, 8, 8, blob.ctypes.data, n)
+    assert rc == 2 and np.all(blob == 0xAB)
+    # null pointers, bad sizes, short buffer
+    assert lib.tsvd_pack_host(None, i.S.ctypes.data, i.V.ctypes.data, 8, 8, 8, blob.ctypes.data, n) == 1
+    assert lib.tsvd_pack_host(i.U.ctypes.data, i.S.ctypes.data, i.V.ctypes.data, 0, 8, 8, blob.ctypes.data, n) == 1
+    assert lib.tsvd_pack_host(i.U.ctypes.data, i.S.ctypes.data, i.V.ctypes.data, 8, 8, 8, blob.ctypes.data, n - 1) == 1
+    assert np.all(blob == 0xAB)
+    assert tsvd.tsvd_packed_bytes(0, 1, 1) == 0 and tsvd.tsvd_packed_bytes(1, -1, 1) == 0
+
+
+def test_unpack_detects_corruption():
+    i = workloads.make_inputs(8, 8, 8, 1, 0.0, 0.02, "f32", seed=2)    # no zeros: every code is 01 or 11
+    blob = tsvd.tsvd_pack_host(i.U, i.S, i.V)
+    s = _sections(blob)
+    bad = blob.copy()
+    bad[0] ^= 0xFF                                                     # magic
+    with pytest.raises(tsvd.TsvdError):
+        tsvd.tsvd_unpack_host(bad)
+    with pytest.raises(tsvd.TsvdError):
+        tsvd.tsvd_unpack_host(blob[:100])
+    # turn a +1 (01) into the unused code 10
+    tiles = blob[s["off_U"]:s["off_V"]]
+    pos = int(np.flatnonzero((tiles & 3) == 1)[0]) + s["off_U"]
+    bad = blob.copy()
+    bad[pos] = (bad[pos] & ~np.uint8(3)) | np.uint8(2)
+    with pytest.raises(tsvd.TsvdError) as e:
+        tsvd.tsvd_unpack_host(bad)
+    assert e.value.status == 2
+    # a code in the zero padding
+    bad = blob.copy()
+    bad[s["off_V"] - 1] |= 1
+    with pytest.raises(tsvd.TsvdError):
+        tsvd.tsvd_unpack_host(bad)
+
+
+def test_no_gpu_calls_fail_cleanly_without_a_device():
+    """tsvd_pack needs a device: without one it must return a status, not crash."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    i = workloads.make_inputs(4, 4, 4, 1, 0.5, 0.02, "f32", seed=3)
+    with pytest.raises(tsvd.TsvdError) as e:
+        tsvd.tsvd_pack(i.U, i.S, i.V)
+    assert e.value.status == 4

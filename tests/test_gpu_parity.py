@@ -1,0 +1,153 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Tolerances (max|y_gpu - y_ref| / max|y_ref| over the whole output):
+2e-3 for bf16 activations, 1e-5 for fp32 activations; integer instances must match exactly."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from gpu_util import rel_err, run_forward, to_device
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 2e-3, "f32": 1e-5}
+
+
+@pytest.fixture(scope="module")
+def tsvd():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: the HIP path has no fallback")
+    import paper_2308_07641_amd as t
+    t.load_library()
+    return t
+
+
+# ---- exact-integer instances: every partial sum is exact in fp32, so any correct kernel
+# ---- agrees with the oracle bit for bit (catches tile, padding and index mistakes).
+INT_SHAPES = [
+    # M, N, K, B
+    (16, 256, 16, 1), (1, 1, 1, 1), (3, 5, 7, 1), (37, 29, 61, 1), (256, 256, 512, 1),
+    (300, 513, 270, 1), (64, 48, 200, 3), (64, 48, 200, 5), (33, 300, 257, 8), (50, 70, 90, 16),
+    (20, 40, 30, 17), (100, 260, 300, 40),
+    (128, 128, 128, 64), (256, 256, 256, 128), (300, 200, 270, 100), (130, 64, 520, 257),
+    (512, 256, 384, 256), (260, 100, 300, 1000),
+]
+
+
+@pytest.mark.parametrize("x_dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("M,N,K,B", INT_SHAPES)
+def test_integer_instances_match_bit_for_bit(tsvd, M, N, K, B, x_dtype):
+    i = workloads.make_integer_inputs(M, N, K, B, 0.5, x_dtype, seed=M + 3 * N + 7 * K + 11 * B)
+    print(f"case int M={M} N={N} K={K} B={B} {x_dtype}", flush=True)
+    ref = oracle.forward(i.U, i.S, i.V, i.X)
+    y, h = run_forward(i)
+    tsvd.tsvd_free(h)
+    assert not np.isnan(y).any(), "an output element was not written"
+    assert np.array_equal(y, ref)
+
+
+# ---- random instances within tolerance, ragged shapes spanning several tiles
+RAND_SHAPES = [
+    (256, 256, 512, 1, 0.5), (1000, 300, 777, 1, 0.6), (2048, 1024, 1536, 1, 0.7),
+    (530, 270, 1030, 2, 0.5), (530, 270, 1030, 5, 0.5), (530, 270, 1030, 16, 0.5), (515, 100, 300, 33, 0.6),
+    (384, 256, 512, 64, 0.5), (515, 300, 777, 130, 0.6), (1024, 512, 768, 512, 0.5), (300, 2000, 260, 1025, 0.6),
+]
+
+
+@pytest.mark.parametrize("x_dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("M,N,K,B,p0", RAND_SHAPES)
+def test_random_instances_within_tolerance(tsvd, M, N, K, B, p0, x_dtype):
+    i = workloads.make_inputs(M, N, K, B, p0, 0.02, x_dtype, seed=99 + M + N + K + B)
+    print(f"case rand M={M} N={N} K={K} B={B} {x_dtype}", flush=True)
+    ref = oracle.forward(i.U, i.S, i.V, i.X)
+    y, h = run_forward(i)
+    tsvd.tsvd_free(h)
+    assert not np.isnan(y).any()
+    assert rel_err(y, ref) <= TOL[x_dtype]
+
+
+def test_activation_scale_extremes_batched(tsvd):
+    """The fp16 intermediate of the batched path is rescaled per token: tokens of very different
+    magnitude in one batch must all keep their accuracy (error measured per token here)."""
+    i = workloads.make_inputs(256, 256, 256, 128, 0.5, 0.02, "bf16", seed=77)
+    scale = np.ldexp(1.0, np.random.default_rng(1).integers(-60, 60, size=128)).astype(np.float32)
+    i.X = i.X * scale[None, :]
+    i.X_bits = workloads.f32_to_bf16_bits(i.X)
+    i.X = workloads.bf16_bits_to_f32(i.X_bits)
+    ref = oracle.forward(i.U, i.S, i.V, i.X)
+    y, h = run_forward(i)
+    tsvd.tsvd_free(h)
+    per_token = np.max(np.abs(y - ref), axis=0) / np.max(np.abs(ref), axis=0)
+    assert np.all(per_token <= 2e-3)
+
+
+def test_strided_inputs_outputs_and_caller_workspace(tsvd):
+    import torch
+    i = workloads.make_inputs(300, 200, 270, 70, 0.5, 0.02, "bf16", seed=5)
+    ref = oracle.forward(i.U, i.S, i.V, i.X)
+    h = tsvd.tsvd_pack(i.U, i.S, i.V)
+    xfull = torch.zeros((200, 91), dtype=torch.bfloat16, device="cuda:0")     # odd stride: slow load path
+    xfull[:, :70] = to_device(i)
+    yfull = torch.full((300, 75), 7.0, dtype=torch.float32, device="cuda:0")
+    ws = torch.empty(tsvd.tsvd_workspace_bytes(h, 70, tsvd.TSVD_BF16), dtype=torch.uint8, device="cuda:0")
+    tsvd.tsvd_forward(h, xfull[:, :70], yfull[:, :70], workspace=ws)
+    torch.cuda.synchronize()
+    y = yfull.cpu().numpy().astype(np.float64)
+    assert rel_err(y[:, :70], ref) <= 2e-3
+    assert np.all(y[:, 70:] == 7.0)                                           # padding columns untouched
+    # a side stream and the handle-owned workspace
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        y2 = tsvd.tsvd_forward(h, xfull[:, :70])
+    st.synchronize()
+    assert np.array_equal(y2.cpu().numpy(), yfull[:, :70].cpu().numpy())      # deterministic
+    tsvd.tsvd_free(h)
+
+
+def test_device_round_trip_info_and_errors(tsvd):
+    import torch
+    i = workloads.make_inputs(70, 50, 90, 4, 0.6, 0.02, "f32", seed=8)
+    buf = torch.empty(tsvd.tsvd_packed_bytes(70, 90, 50), dtype=torch.uint8, device="cuda:0")
+    h = tsvd.tsvd_pack(i.U, i.S, i.V, dev_buf=buf)           # caller-owned device blob
+    U, S, V = tsvd.tsvd_unpack(h)
+    assert np.array_equal(U, i.U) and np.array_equal(V, i.V) and np.array_equal(S, i.S)
+    info = tsvd.tsvd_info(h)
+    c = oracle.op_counts(i.U, i.V)
+    assert (info["M"], info["K"], info["N"]) == (70, 90, 50)
+    assert info["nnzU"] == c["adds_U"] and info["nnzV"] == c["adds_V"]     # Table S1 addition count
+    x = to_device(i)
+    lib = tsvd.load_library()
+    y = torch.zeros((70, 4), dtype=torch.float32, device="cuda:0")
+    args = dict(B=4, ldx=4, ldy=4)
+    call = lambda **o: lib.tsvd_forward(o.get("h", h.ptr), o.get("x", x.data_ptr()), o.get("xd", 0), o.get("B", 4),
+                                        o.get("ldx", 4), o.get("y", y.data_ptr()), o.get("yd", 0), o.get("ldy", 4),
+                                        o.get("ws", None), o.get("wsb", 0), None)
+    assert call(h=None) == 1 and call(x=None) == 1 and call(y=None) == 1
+    assert call(B=0) == 1 and call(ldx=3) == 1 and call(ldy=3) == 1 and call(xd=7) == 1
+    assert call(yd=1) == 5 and call(yd=9) == 1
+    assert call(ws=x.data_ptr(), wsb=16) == 1                 # workspace too small
+    torch.cuda.synchronize()
+    assert torch.all(y == 0)                                   # failures leave outputs untouched
+    assert call() == 0
+    torch.cuda.synchronize()
+    ref = oracle.forward(i.U, i.S, i.V, i.X)
+    assert rel_err(y.cpu().numpy().astype(np.float64), ref) <= 1e-5
+    with pytest.raises(tsvd.TsvdError):
+        bad = i.U.copy()
+        bad[0, 0] = 5
+        tsvd.tsvd_pack(bad, i.S, i.V)
+    tsvd.tsvd_free(h)
+    tsvd.tsvd_free(h)                                          # double free of the wrapper is a no-op
+    lib.tsvd_free(None)
+
+
+def test_repeated_calls_are_bit_identical(tsvd):
+    import torch
+    for (M, N, K, B, dt) in ((2048, 1024, 1536, 1, "bf16"), (512, 256, 768, 300, "bf16")):
+        i = workloads.make_inputs(M, N, K, B, 0.5, 0.02, dt, seed=21)
+        h = tsvd.tsvd_pack(i.U, i.S, i.V)
+        x = to_device(i)
+        ys = [tsvd.tsvd_forward(h, x).cpu().numpy() for _ in range(3)]
+        assert np.array_equal(ys[0], ys[1]) and np.array_equal(ys[0], ys[2])
+        tsvd.tsvd_free(h)
