@@ -1,0 +1,225 @@
+#!/usr/bin/env python3
+"""Benchmark of the TSVD forward path y = U (diag(S) (V x)) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workloads a,b,...]
+
+A step is one pass of the whole hot path (all kernels of tsvd_forward) over one batch of the
+seeded synthetic workload; inputs are resident in HBM before the timed region.  The headline
+line is for the BERT-base FFN-in shape (configs[1] of the benchmark spec); the other workloads are
+reported in "per_config" of the same JSON line.  Rooflines use executed flops 2 K (M+N) B
+against 2.5 PFLOP/s (bf16/fp16 MFMA) for the batched shapes and algorithmic bytes
+K (M+N)/4 + 4K + N sizeof(x) + 4M against 8 TB/s for B = 1.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import workloads  # noqa: E402
+
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_TFLOPS = 2500.0
+PRIMARY = "bert_ffn_in"
+
+
+def _device_x(inputs, dev):
+    import torch
+    if inputs.x_dtype == "bf16":
+        return torch.from_numpy(inputs.X_bits.view(np.int16)).to(dev).view(torch.bfloat16)
+    return torch.from_numpy(inputs.X).to(dev)
+
+
+def _timed(fn, steps, warmup):
+    """Runs fn() warmup + steps times; returns (wall ms per step, event ms per step)."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+
+def _set_stage_mask(mask):
+    """Library debug switch: which kernels of the batched path run (1 colmax, 2 stage V, 4 stage U)."""
+    if mask is None:
+        os.environ.pop("TSVD_STAGE_MASK", None)
+    else:
+        os.environ["TSVD_STAGE_MASK"] = str(mask)
+
+
+def cpu_baseline(w, inputs, budget_s=20.0):
+    """The oracle as it stands, timed on this host; tokens/s on a bounded sample."""
+    import oracle
+    if w.B == 1:
+        reps, t0 = 0, time.perf_counter()
+        while True:
+            oracle.forward(inputs.U, inputs.S, inputs.V, inputs.X)
+            reps += 1
+            dt = time.perf_counter() - t0
+            if dt > 2.0 or reps >= 20:
+                break
+        return {"value": reps / dt, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+                "sample": f"{reps} full single-token passes"}
+    per_token = float(w.K) * (w.M + w.N)                     # multiply-adds per token
+    ncols = int(max(oracle.threads(), min(w.B, budget_s * 1.0e9 / per_token)))
+    ncols = min(w.B, ncols)
+    cols = np.linspace(0, w.B - 1, ncols).astype(np.int64)
+    X = np.ascontiguousarray(inputs.X[:, cols])
+    t0 = time.perf_counter()
+    ref = oracle.forward(inputs.U, inputs.S, inputs.V, X)
+    dt = time.perf_counter() - t0
+    return ({"value": ncols / dt, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+             "sample": f"{ncols} of {w.B} tokens (evenly spaced columns), all {w.M} rows, {dt:.2f} s"},
+            cols, ref)
+
+
+def bench_workload(name, steps, warmup, with_cpu=True):
+    import torch
+    import paper_2308_07641_amd as tsvd
+
+    w = workloads.WORKLOADS[name]
+    dev = torch.device("cuda:0")
+    t_gen = time.perf_counter()
+    inputs = workloads.make_workload(name)
+    print(f"[bench] {name}: inputs drawn in {time.perf_counter() - t_gen:.1f} s", file=sys.stderr, flush=True)
+    batched = w.B >= 64
+    x = _device_x(inputs, dev)
+    y = torch.empty((w.M, w.B), dtype=torch.float32, device=dev)
+
+    # B = 1 streams the weights once per token: rotate over enough copies of the packed
+    # weights that the 256 MB memory-side cache cannot serve them (the HBM figure), and also
+    # report the cache-warm time on a single copy.
+    blob_bytes = tsvd.tsvd_packed_bytes(w.M, w.K, w.N)
+    ncopies = 1 if batched else max(2, int(np.ceil(640e6 / blob_bytes)))
+    ncopies = min(ncopies, 64)
+    handles = [tsvd.tsvd_pack(inputs.U, inputs.S, inputs.V) for _ in range(ncopies)]
+    ws = torch.empty(tsvd.tsvd_workspace_bytes(handles[0], w.B, tsvd.TSVD_BF16 if w.x_dtype == "bf16" else tsvd.TSVD_F32),
+                     dtype=torch.uint8, device=dev)
+    info = tsvd.tsvd_info(handles[0])
+    print(f"[bench] {name}: packed {blob_bytes / 1e6:.1f} MB x {ncopies}", file=sys.stderr, flush=True)
+
+    state = {"i": 0}
+
+    def step_rot():
+        h = handles[state["i"] % ncopies]
+        state["i"] += 1
+        tsvd.tsvd_forward(h, x, y, workspace=ws)
+
+    def step_one():
+        tsvd.tsvd_forward(handles[0], x, y, workspace=ws)
+
+    wall_ms, ev_ms = _timed(step_rot, steps, warmup)
+    res = {"workload": name, "M": w.M, "N": w.N, "K": w.K, "B": w.B, "x_dtype": w.x_dtype,
+           "ms_per_step": wall_ms, "event_ms_per_step": ev_ms, "tokens_per_s": w.B / (wall_ms * 1e-3),
+           "weight_copies_rotated": ncopies,
+           "paper_counts_per_token": {"mults": w.K, "adds": info["nnzU"] + info["nnzV"]}}
+    flops_exec = 2.0 * w.K * (w.M + w.N) * w.B
+    flops_dense = 2.0 * w.M * w.N * w.B
+    res["executed_tflops"] = flops_exec / (ev_ms * 1e-3) / 1e12
+    res["dense_equiv_tflops"] = flops_dense / (ev_ms * 1e-3) / 1e12
+
+    if batched:
+        # dominant kernel: stage U (M/(M+N) of the executed flops), timed alone on the Z left
+        # in the workspace by the full passes above
+        _set_stage_mask(4)
+        _, u_ms = _timed(step_one, steps, max(2, warmup // 2))
+        _set_stage_mask(2)
+        _, v_ms = _timed(step_one, steps, max(2, warmup // 2))
+        _set_stage_mask(None)
+        fl_u = 2.0 * w.K * w.M * w.B
+        res["stage_ms"] = {"V": v_ms, "U": u_ms}
+        res["roofline"] = {"bound": "mfma", "kernel": "tsvd_gemm_kernel<stage U>", "achieved": fl_u / (u_ms * 1e-3) / 1e12,
+                           "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": fl_u / (u_ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS,
+                           "traffic": None,
+                           "whole_path_frac": res["executed_tflops"] / PEAK_MFMA_TFLOPS}
+    else:
+        xb = 2 if w.x_dtype == "bf16" else 4
+        bytes_alg = w.K * (w.M + w.N) / 4.0 + 4.0 * w.K + w.N * xb + 4.0 * w.M
+        warm_wall, warm_ev = _timed(step_one, steps, warmup)
+        res["cache_warm_event_ms"] = warm_ev
+        gbs = bytes_alg / (ev_ms * 1e-3) / 1e9
+        res["roofline"] = {"bound": "hbm", "kernel": "tsvd_skinny_kernel (V and U launches of one token)",
+                           "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                           "traffic": None, "algorithmic_bytes": bytes_alg,
+                           "cache_warm_gbs": bytes_alg / (warm_ev * 1e-3) / 1e9}
+
+    if with_cpu:
+        import oracle
+        out = cpu_baseline(w, inputs)
+        if w.B == 1:
+            res["cpu_baseline"] = out
+            ref = oracle.forward(inputs.U, inputs.S, inputs.V, inputs.X)
+            got = y.cpu().numpy().astype(np.float64)
+        else:
+            res["cpu_baseline"], cols, ref = out
+            got = y[:, torch.from_numpy(cols).to(dev)].cpu().numpy().astype(np.float64)
+        res["parity_rel_err"] = float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+    for h in handles:
+        tsvd.tsvd_free(h)
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workloads", default="bert_ffn_in,tiny,convnext_mlp,opt6b7_fc1_decode,opt66b_fc1_prefill")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing / parity leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus above 1 is not supported "
+              "(the path would shard over tokens or rank slices, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    import paper_2308_07641_amd as tsvd
+    tsvd.load_library()
+
+    names = [n for n in args.workloads.split(",") if n]
+    if PRIMARY not in names:
+        names.insert(0, PRIMARY)
+    per = {}
+    for n in names:
+        steps = args.steps if workloads.WORKLOADS[n].B * workloads.WORKLOADS[n].K < 1 << 24 else max(5, args.steps // 10)
+        per[n] = bench_workload(n, steps, args.warmup, with_cpu=not args.no_cpu)
+        per[n]["steps"] = steps
+        print(f"[bench] {n}: {json.dumps(per[n])}", file=sys.stderr, flush=True)
+
+    p = per[PRIMARY]
+    w = workloads.WORKLOADS[PRIMARY]
+    line = {
+        "metric": "TSVD linear fwd: tokens/s + HBM GB/s (B=1) / MFMA util (batched) vs roofline",
+        "value": p["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": p["steps"], "warmup": args.warmup,
+        "ms_per_step": p["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{PRIMARY}: M={w.M} N={w.N} K={w.K} B={w.B}, ternary U,V P(0)={w.p0}, bf16 X"},
+        "roofline": {k: p["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")},
+        "cpu_baseline": p.get("cpu_baseline"),
+        "per_config": per,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

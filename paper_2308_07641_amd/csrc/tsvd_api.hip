@@ -20,6 +20,7 @@ struct tsvd_handle {
     void* scratch;          // device, handle-owned workspace (grown on demand)
     size_t scratch_bytes;
     float bound_V;          // max_k |S_k| * nnz(V[k,:]) : |z_k| <= bound_V * max|x| for every token
+    long long* clocks;      // tuning aid (TSVD_CLOCKS=1 at pack time): phase timestamps of the B <= 2 kernel
 };
 
 namespace {
@@ -40,95 +41,162 @@ hipError_t device_init(int device) {
     if (e != hipSuccess) return e;
     e = tsvd_gemm_init();
     if (e != hipSuccess) return e;
+    e = tsvd_gemv_init();
+    if (e != hipSuccess) return e;
     done[device] = true;
     return hipSuccess;
 }
 
-// ---- skinny path (few tokens): two launches per token chunk ---------------------------------
-struct skinny_plan {
-    int pieces_x, pieces_z, chunk;   // bf16 parts of x and of z, tokens per launch
-};
-
-skinny_plan plan_skinny(int64_t B, tsvd_dtype x_dtype) {
-    skinny_plan p;
-    p.pieces_x = x_dtype == TSVD_BF16 ? 1 : 3;
-    // z is fp32.  Three parts are exact; two parts keep 16 significant bits (2^-17 relative),
-    // far inside the bf16-activation tolerance, and let 8 tokens share one pass.
-    if (x_dtype == TSVD_F32 || B * 3 <= 16) {
-        p.pieces_z = 3;
-        p.chunk = 5;
-    } else {
-        p.pieces_z = 2;
-        p.chunk = 8;
-    }
-    return p;
+// ---- skinny path (few tokens): two launches per pair of tokens --------------------------------
+void shape_skinny(tsvd_skinny_args& a) {
+    // LDS: digit planes [8 * tokens][slab_k + 16] bytes + reduction tiles (<= 16 KiB) + 256 B
+    const size_t budget = TSVD_SKINNY_MAX_LDS - 16 * 1024 - 1024;
+    const int cols = 8 * a.tokens;
+    const int slab = (int)std::min<size_t>((size_t)a.nkt, (budget / (size_t)cols - 16) / 256);
+    a.slab_tiles = std::max(slab, 1);
+    // One workgroup of up to 16 wavefronts per compute unit when the matrix is large enough:
+    // sw strips x kw contraction splits, every wavefront streaming nkt / kw tiles.
+    int sw = 1;
+    while (sw < 16 && a.strips / (sw * 2) >= 256) sw *= 2;
+    int kw = 1;
+    while (sw * kw * 2 <= 16 && kw * 2 <= a.nkt) kw *= 2;
+    a.sw = std::max(1, std::min(16, env_int("TSVD_SKINNY_SW", sw)));
+    a.kw = std::max(1, std::min(std::min(16 / a.sw, a.nkt), env_int("TSVD_SKINNY_KW", kw)));
 }
 
-void shape_skinny(tsvd_skinny_args& a, int cols) {
-    // LDS budget: activations [cols][slab_k + 8] bf16 + reduction tiles (<= 16 KiB)
-    const size_t budget = TSVD_SKINNY_MAX_LDS - 16 * 1024 - 512;
-    int slab = (int)std::min<size_t>((size_t)a.nkt, (budget / ((size_t)cols * 2) - 8) / 256);
-    a.slab_tiles = std::max(slab, 1);
-    // Aim for >= 2 workgroups per compute unit when the matrix allows it, 8..16 wavefronts each.
-    int sw = 1;
-    while (sw < 4 && a.strips / (sw * 2) >= 512) sw *= 2;
-    int kw = 1;
-    while (sw * kw * 2 <= 16 && a.nkt / (kw * 2) >= 2) kw *= 2;
-    a.sw = std::max(1, std::min(16, env_int("TSVD_SKINNY_SW", sw)));
-    a.kw = std::max(1, std::min(16 / a.sw, env_int("TSVD_SKINNY_KW", kw)));
+size_t skinny_workspace(const tsvd_handle* h) {
+    return 256 + (size_t)16 * (size_t)h->hd.Kp;      // exponents, then 16 digit planes of Kp bytes
+}
+
+int pow2_ceil(int64_t v) {
+    int r = 1;
+    while (r < v) r *= 2;
+    return r;
+}
+int pow2_floor(int64_t v) {
+    int r = 1;
+    while ((int64_t)r * 2 <= v) r *= 2;
+    return r;
+}
+
+// One token through the tsvd_gemv kernels; returns false if the shape does not fit them.
+bool try_gemv(const tsvd_handle* h, const void* x, tsvd_dtype x_dtype, int64_t ldx, float* y, int64_t ldy,
+              int* meta, unsigned char* planes, hipStream_t stream, tsvd_status* st) {
+    const tsvd_blob_header& hd = h->hd;
+    if (env_int("TSVD_GEMV", 1) == 0 || !tsvd_gemv_fits(hd.Np, hd.Kp)) return false;
+    const int mask = tsvd_stage_mask();
+    // sw strips x kw splits = 16 wavefronts; about one workgroup per compute unit for large matrices
+    auto shape = [&](tsvd_gemv_args& a) {
+        int sw = 1;
+        while (sw < 16 && a.strips / (sw * 2) >= 256) sw *= 2;
+        int kl = 0;
+        while ((sw << (kl + 1)) <= 16 && (2 << kl) <= a.nkt) ++kl;
+        a.sw = std::max(1, std::min(16, env_int("TSVD_GEMV_SW", sw)));
+        a.kw_log2 = std::max(0, env_int("TSVD_GEMV_KWLOG2", kl));
+        while ((a.sw << a.kw_log2) > 16) --a.kw_log2;
+    };
+    tsvd_gemv_args a;
+    std::memset(&a, 0, sizeof a);
+    a.N = (int)hd.N; a.Np = (int)hd.Np; a.Kp = (int)hd.Kp;
+    a.meta = meta;
+    a.clocks = h->clocks;
+    if (mask & 2) {
+        a.tiles = h->blob + hd.off_V;
+        a.strips = (int)(hd.Kp / 16);
+        a.nkt = (int)(hd.Np / 256);
+        a.rows_out = (int)hd.Kp;
+        a.x = x;
+        a.x_is_bf16 = x_dtype == TSVD_BF16;
+        a.ldx = ldx;
+        a.x_vec = ldx == 1 && hd.N % 4 == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
+        a.S = reinterpret_cast<const float*>(h->blob + hd.off_S);
+        a.bound_V = h->bound_V;
+        a.planes_out = planes;
+        shape(a);
+        if (tsvd_launch_gemv(a, false, stream) != hipSuccess) {
+            *st = TSVD_EDEVICE;
+            return true;
+        }
+    }
+    if (mask & 4) {
+        a.tiles = h->blob + hd.off_U;
+        a.strips = (int)((hd.M + 15) / 16);
+        a.nkt = (int)(hd.Kp / 256);
+        a.rows_out = (int)hd.M;
+        a.planes_in = planes;
+        a.y = y;
+        a.ldy = ldy;
+        shape(a);
+        if (tsvd_launch_gemv(a, true, stream) != hipSuccess) {
+            *st = TSVD_EDEVICE;
+            return true;
+        }
+    }
+    *st = TSVD_OK;
+    return true;
 }
 
 tsvd_status forward_skinny(const tsvd_handle* h, const void* x, tsvd_dtype x_dtype, int64_t B, int64_t ldx,
                            float* y, int64_t ldy, void* ws, hipStream_t stream) {
     const tsvd_blob_header& hd = h->hd;
-    const skinny_plan pl = plan_skinny(B, x_dtype);
-    float* z = static_cast<float*>(ws);   // [K][B] fp32
+    int* meta = static_cast<int*>(ws);
+    unsigned char* planes = static_cast<unsigned char*>(ws) + 256;
     const size_t xelt = x_dtype == TSVD_BF16 ? 2 : 4;
-    for (int64_t b0 = 0; b0 < B; b0 += pl.chunk) {
-        const int tokens = (int)std::min<int64_t>(pl.chunk, B - b0);
+    const int mask = tsvd_stage_mask();
+    if (tsvd_gemv_fits(hd.Np, hd.Kp) && env_int("TSVD_GEMV", 1) != 0) {
+        // one token at a time through the fast kernels (each pass re-reads the weights)
+        for (int64_t b0 = 0; b0 < B; ++b0) {
+            tsvd_status gst = TSVD_OK;
+            if (!try_gemv(h, static_cast<const uint8_t*>(x) + (size_t)b0 * xelt, x_dtype, ldx, y + b0, ldy, meta, planes,
+                          stream, &gst))
+                return TSVD_EUNSUPPORTED;
+            if (gst != TSVD_OK) return gst;
+        }
+        return TSVD_OK;
+    }
+    for (int64_t b0 = 0; b0 < B; b0 += 2) {
+        const int tokens = (int)std::min<int64_t>(2, B - b0);
         tsvd_skinny_args v;
         std::memset(&v, 0, sizeof v);
         v.tiles = h->blob + hd.off_V;
-        v.strips = (int)((hd.K + 15) / 16);
+        v.strips = (int)(hd.Kp / 16);           // padded rows give z = 0: every plane byte is written
         v.nkt = (int)(hd.Np / 256);
+        v.mode = TSVD_SKINNY_STAGE_V;
         v.in = static_cast<const uint8_t*>(x) + (size_t)b0 * xelt;
         v.in_is_bf16 = x_dtype == TSVD_BF16;
         v.kvalid = (int)hd.N;
         v.ld_in = ldx;
         v.tokens = tokens;
-        v.pieces = pl.pieces_x;
         v.rowscale = reinterpret_cast<const float*>(h->blob + hd.off_S);
-        v.post = 0.5f;
-        v.out = z + b0;
-        v.ld_out = B;
-        v.rows_valid = (int)hd.K;
-        shape_skinny(v, v.tokens * v.pieces);
-        if (tsvd_launch_skinny(v, stream) != hipSuccess) return TSVD_EDEVICE;
+        v.bound_V = h->bound_V;
+        v.meta_out = meta;
+        v.out = planes;
+        v.ld_out = hd.Kp;
+        v.rows_out = (int)hd.Kp;
+        shape_skinny(v);
+        if ((mask & 2) && tsvd_launch_skinny(v, stream) != hipSuccess) return TSVD_EDEVICE;
 
         tsvd_skinny_args u;
         std::memset(&u, 0, sizeof u);
         u.tiles = h->blob + hd.off_U;
         u.strips = (int)((hd.M + 15) / 16);
         u.nkt = (int)(hd.Kp / 256);
-        u.in = z + b0;
-        u.in_is_bf16 = 0;
-        u.kvalid = (int)hd.K;
-        u.ld_in = B;
+        u.mode = TSVD_SKINNY_STAGE_U;
+        u.in = planes;
+        u.ld_in = hd.Kp;
         u.tokens = tokens;
-        u.pieces = pl.pieces_z;
-        u.rowscale = nullptr;
-        u.post = 0.5f;
+        u.meta_in = meta;
         u.out = y + b0;
         u.ld_out = ldy;
-        u.rows_valid = (int)hd.M;
-        shape_skinny(u, u.tokens * u.pieces);
-        if (tsvd_launch_skinny(u, stream) != hipSuccess) return TSVD_EDEVICE;
+        u.rows_out = (int)hd.M;
+        shape_skinny(u);
+        if ((mask & 4) && tsvd_launch_skinny(u, stream) != hipSuccess) return TSVD_EDEVICE;
     }
     return TSVD_OK;
 }
 
 bool use_gemm(const tsvd_handle*, int64_t B, tsvd_dtype x_dtype) {
-    const int min_b = env_int("TSVD_GEMM_MIN_B", 64);
+    const int min_b = env_int("TSVD_GEMM_MIN_B", 17);
     return x_dtype == TSVD_BF16 && B >= min_b;
 }
 
@@ -171,6 +239,7 @@ extern "C" tsvd_status tsvd_pack(const int8_t* U, const float* S, const int8_t* 
     h->bound_V = (float)bound;
     h->scratch = nullptr;
     h->scratch_bytes = 0;
+    h->clocks = nullptr;
 
     bool ok = hipGetDevice(&h->device) == hipSuccess && device_init(h->device) == hipSuccess;
     if (ok) {
@@ -185,6 +254,17 @@ extern "C" tsvd_status tsvd_pack(const int8_t* U, const float* S, const int8_t* 
         }
     }
     if (ok) ok = hipMemcpy(h->blob, host, bytes, hipMemcpyHostToDevice) == hipSuccess;
+    if (ok) {
+        {
+            if (ok && env_int("TSVD_CLOCKS", 0)) {
+                void* c = nullptr;
+                if (hipMalloc(&c, TSVD_GEMV_MAX_GRID * 16 * sizeof(long long)) == hipSuccess) {
+                    (void)hipMemset(c, 0, TSVD_GEMV_MAX_GRID * 16 * sizeof(long long));
+                    h->clocks = static_cast<long long*>(c);
+                }
+            }
+        }
+    }
     std::free(host);
     if (!ok) {
         if (h->owns_blob && h->blob) (void)hipFree(h->blob);
@@ -224,7 +304,7 @@ extern "C" tsvd_status tsvd_info(const tsvd_handle* h, int64_t* M, int64_t* K, i
 extern "C" size_t tsvd_workspace_bytes(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype) {
     if (!h || B <= 0 || (x_dtype != TSVD_F32 && x_dtype != TSVD_BF16)) return 0;
     if (use_gemm(h, B, x_dtype)) return gemm_workspace(h, B);
-    return round256((size_t)h->hd.K * (size_t)B * sizeof(float));
+    return round256(skinny_workspace(h));
 }
 
 extern "C" tsvd_status tsvd_forward(const tsvd_handle* h, const void* x_dev, tsvd_dtype x_dtype, int64_t B,
@@ -276,9 +356,16 @@ extern "C" tsvd_status tsvd_forward(const tsvd_handle* h, const void* x_dev, tsv
     return forward_skinny(h, x_dev, x_dtype, B, ldx, static_cast<float*>(y_dev), ldy, ws, s);
 }
 
+// Tuning aid, not part of the public header: copies the phase timestamps of the last B <= 2 launch.
+extern "C" int tsvd_internal_read_clocks(const tsvd_handle* h, long long* out, int workgroups) {
+    if (!h || !h->clocks || !out || workgroups < 1 || workgroups > TSVD_GEMV_MAX_GRID) return 1;
+    return hipMemcpy(out, h->clocks, (size_t)workgroups * 16 * sizeof(long long), hipMemcpyDeviceToHost) == hipSuccess ? 0 : 4;
+}
+
 extern "C" void tsvd_free(tsvd_handle* h) {
     if (!h) return;
     if (h->scratch) (void)hipFree(h->scratch);
+    if (h->clocks) (void)hipFree(h->clocks);
     if (h->owns_blob && h->blob) (void)hipFree(h->blob);
     delete h;
 }

@@ -16,11 +16,14 @@
 // would keep 8 (the 8-bit rounding alone costs about 1.7e-3 of max|y| at these shapes).
 //
 // Weights never pass through LDS: each wavefront loads the code words of its own rows straight
-// from L2 (they are 8x smaller than the activations).  Activation tiles [64 k][BT tokens] are
-// staged in LDS in their natural row-major order with a 32-byte XOR swizzle and read in MFMA
-// operand order with ds_read_b64_tr_b16.
+// from L2 (they are 8x smaller than the activations).  One 32-bit code word per lane covers the
+// 64 contraction indices k0 + {0..31} and k0 + 64 + {0..31} (the tile order is that of the fp4
+// MFMA operand used by the skinny path), so an LDS stage holds exactly those 64 activation rows
+// [64][BT tokens], row-major with a 32-byte XOR swizzle, read in MFMA operand order with
+// ds_read_b64_tr_b16.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "tsvd_kernels.h"
 #include "tsvd_layout.h"
@@ -128,10 +131,15 @@ tsvd_gemm_kernel(gemm_args p) {
     const int strip0 = (blockIdx.y * WM + wm) * TM;  // first 16-row strip of this wavefront
     const int nstages = p.nkt * (256 / KT);
 
-    // swizzle: 32-byte block j of row r is stored at block j ^ f(r), f(r) = (r & 3) | ((r >> 3) & 3) << 2
-    const int f_lane = ((i >> 2) | (g << 2)) & (NBLK - 1);
-    // byte offset (within a stage) of this lane's transposed read for k-step q, second half adds 4 rows
-    const int tr_row = 8 * g + (i >> 2);
+    // Stage st covers code word d = st & 3 of tile T = st >> 2: contraction indices
+    // k0 + 64 (r >> 5) + (r & 31), r = 0..63, with k0 = 256 T + 128 (d >> 1) + 32 (d & 1).
+    // LDS row r, 32-byte block j is stored at block j ^ f(r),
+    //   f(r) = ((r & 1) << 1) | ((r >> 2) & 1) | (((r >> 4) & 3) << 2).
+    // For MFMA step hh (code parity) lane group g needs rows 32 (g & 1) + 16 (g >> 1) + 8 hh + o with
+    // o = {0,4,1,5} (first four operand elements) and o + 2 (last four): 16 rows with 16 distinct f.
+    const int rsel = i >> 2;
+    const int tr_row = 32 * (g & 1) + 16 * (g >> 1) + (rsel >> 1) + 4 * (rsel & 1);
+    const int f_lane = ((((tr_row & 1) << 1) | ((tr_row >> 2) & 1) | (((tr_row >> 4) & 3) << 2))) & (NBLK - 1);
     const int tr_in = (i & 3) * 8;
 
     f32x4 acc[TM][TN];
@@ -143,12 +151,13 @@ tsvd_gemm_kernel(gemm_args p) {
     // ---- activation tile: global -> registers -> LDS
     u32x4 xreg[CPT];
     auto load_x = [&](int stage) {
-        const int k0 = stage * KT;
+        const int T = stage >> 2, d = stage & 3;
+        const int k0 = 256 * T + 128 * (d >> 1) + 32 * (d & 1);
 #pragma unroll
         for (int c = 0; c < CPT; ++c) {
             const int id = threadIdx.x + c * THREADS;
             const int r = id / (BT / 8), ch = id - r * (BT / 8);
-            const int k = k0 + r, col = b0 + ch * 8;
+            const int k = k0 + 64 * (r >> 5) + (r & 31), col = b0 + ch * 8;
             u32x4 v = {0u, 0u, 0u, 0u};
             if (k < p.kvalid) {
                 const uint16_t* src = p.act + (size_t)k * p.ld + col;
@@ -170,7 +179,7 @@ tsvd_gemm_kernel(gemm_args p) {
         for (int c = 0; c < CPT; ++c) {
             const int id = threadIdx.x + c * THREADS;
             const int r = id / (BT / 8), ch = id - r * (BT / 8);
-            const int f = ((r & 3) | (((r >> 3) & 3) << 2)) & (NBLK - 1);
+            const int f = (((r & 1) << 1) | ((r >> 2) & 1) | (((r >> 4) & 3) << 2)) & (NBLK - 1);
             const int blk = (ch >> 1) ^ f;
             *reinterpret_cast<u32x4*>(base + r * ROWB + blk * 32 + (ch & 1) * 16) = xreg[c];
         }
@@ -197,21 +206,22 @@ tsvd_gemm_kernel(gemm_args p) {
         }
         const unsigned char* base = smem + (s & 1) * (KT * ROWB);
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
+        for (int hh = 0; hh < 2; ++hh) {
             u32x2 blo[TN], bhi[TN];
 #pragma unroll
             for (int b = 0; b < TN; ++b) {
                 const int blk = ((wn * TN + b) ^ f_lane);
-                const unsigned char* ptr = base + (32 * q + tr_row) * ROWB + blk * 32 + tr_in;
+                const unsigned char* ptr = base + (tr_row + 8 * hh) * ROWB + blk * 32 + tr_in;
                 blo[b] = lds_tr(ptr);
-                bhi[b] = lds_tr(ptr + 4 * ROWB);
+                bhi[b] = lds_tr(ptr + 2 * ROWB);
             }
 #pragma unroll
             for (int a = 0; a < TM; ++a) {
                 const uint32_t w = wcur[a];
+                // register m of the operand = codes hh + 2 m (low half) and hh + 2 m + 8 (high half)
                 u32x4 av;
-                if (q == 0) av = u32x4{TSVD_DEC(w, 0), TSVD_DEC(w, 1), TSVD_DEC(w, 2), TSVD_DEC(w, 3)};
-                else        av = u32x4{TSVD_DEC(w, 4), TSVD_DEC(w, 5), TSVD_DEC(w, 6), w & 0xC000C000u};
+                if (hh == 0) av = u32x4{TSVD_DEC(w, 0), TSVD_DEC(w, 2), TSVD_DEC(w, 4), TSVD_DEC(w, 6)};
+                else         av = u32x4{TSVD_DEC(w, 1), TSVD_DEC(w, 3), TSVD_DEC(w, 5), w & 0xC000C000u};
 #pragma unroll
                 for (int b = 0; b < TN; ++b) acc[a][b] = mfma16<STAGE2>(av, blo[b], bhi[b], acc[a][b]);
             }
@@ -278,6 +288,11 @@ hipError_t init_gemm() {
 
 }  // namespace
 
+int tsvd_stage_mask() {
+    const char* v = getenv("TSVD_STAGE_MASK");
+    return (v && *v) ? atoi(v) : 7;
+}
+
 hipError_t tsvd_gemm_init() {
     hipError_t e;
     if ((e = init_gemm<2, 4, 8, 4, false>()) != hipSuccess) return e;
@@ -294,10 +309,16 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     const size_t part_bytes = (((size_t)TSVD_COLMAX_PARTS * Bp * 4) + 255) & ~(size_t)255;
     _Float16* Z = reinterpret_cast<_Float16*>(static_cast<uint8_t*>(g.ws) + part_bytes);
 
-    hipLaunchKernelGGL(tsvd_colmax_kernel, dim3((unsigned)((g.B + 127) / 128), TSVD_COLMAX_PARTS), dim3(256), 0, stream,
-                       static_cast<const uint16_t*>(g.x), g.ldx, (int)hd.N, (int)g.B, Bp, colpart);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    // Profiling switch: TSVD_STAGE_MASK selects the kernels to launch (1 column maxima,
+    // 2 stage V, 4 stage U; default all).  Skipped kernels leave the workspace as it is.
+    const int mask = tsvd_stage_mask();
+    hipError_t e = hipSuccess;
+    if (mask & 1) {
+        hipLaunchKernelGGL(tsvd_colmax_kernel, dim3((unsigned)((g.B + 127) / 128), TSVD_COLMAX_PARTS), dim3(256), 0,
+                           stream, static_cast<const uint16_t*>(g.x), g.ldx, (int)hd.N, (int)g.B, Bp, colpart);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
 
     gemm_args a1;
     a1.tiles = reinterpret_cast<const uint32_t*>(g.blob + hd.off_V);
@@ -332,11 +353,13 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     const long long big_tiles = (hd.Mp / 256) * (long long)(Bp / 256);
     const bool big = big_tiles >= 256;
     if (big) {
-        e = launch_gemm<2, 4, 8, 4, false>(a1, (int)(hd.Kp / 256), Bp / 256, stream);
+        if (mask & 2) e = launch_gemm<2, 4, 8, 4, false>(a1, (int)(hd.Kp / 256), Bp / 256, stream);
         if (e != hipSuccess) return e;
-        return launch_gemm<2, 4, 8, 4, true>(a2, (int)(hd.Mp / 256), Bp / 256, stream);
+        if (mask & 4) e = launch_gemm<2, 4, 8, 4, true>(a2, (int)(hd.Mp / 256), Bp / 256, stream);
+        return e;
     }
-    e = launch_gemm<2, 2, 4, 4, false>(a1, (int)(hd.Kp / 128), Bp / 128, stream);
+    if (mask & 2) e = launch_gemm<2, 2, 4, 4, false>(a1, (int)(hd.Kp / 128), Bp / 128, stream);
     if (e != hipSuccess) return e;
-    return launch_gemm<2, 2, 4, 4, true>(a2, (int)(hd.Mp / 128), Bp / 128, stream);
+    if (mask & 4) e = launch_gemm<2, 2, 4, 4, true>(a2, (int)(hd.Mp / 128), Bp / 128, stream);
+    return e;
 }

@@ -1,0 +1,331 @@
+// Fast single-token path (B = 1): the two stages of y = U (diag(S) (V x)) (paper, section
+// "Truncated SVD in Network Compression"; supplement Table S1: V(.) and U(.) are additions only,
+// diag(S)(.) is K multiplications), one launch each, 16 wavefronts per workgroup and about one
+// workgroup per compute unit.
+//
+// Arithmetic.  The 2-bit codes are never widened to 16 or 32 bits: three ALU operations turn a
+// 32-bit word (16 codes) into two registers of fp4 (E2M1) numbers 0 / +2 / -2, the A operand of
+// v_mfma_scale_f32_16x16x128_f8f6f4.  The activation vector is converted to sign-magnitude
+// 30-bit fixed point relative to its largest magnitude and cut into eight base-16 digits; digit
+// plane p (sign * digit, exact in fp8 E4M3) is column p of the MFMA's B operand.  Every product
+// is +-2 * digit and every sum an integer below 2^24, so the matrix core performs exact integer
+// additions and subtractions in its fp32 accumulators; the eight planes are recombined in fp64
+// (Horner, base 16) and scaled back.  Only the fixed-point conversion (2^-31 of the largest
+// magnitude) and the final rounding to fp32 are inexact.
+//
+// Schedule.  At B = 1 a call lasts a few microseconds and every instruction of the prologue is
+// executed by all 16 wavefronts of a compute unit, so the code is kept short and every serial
+// round trip to memory counts.  Vector-memory results return to a wavefront in issue order:
+// each wavefront issues all its loads at entry in the order it needs them, first the small,
+// latency-critical activations (x, or the digit planes of z written by stage V), then every
+// weight tile it owns (up to 8; more are streamed).  The activations are staged in LDS while the
+// weights are in flight.  Stage V multiplies by S and writes z already digitised (power-of-two
+// scale from the bound |z_k| <= max_k(|S_k| nnz(V[k,:])) * max|x|), so stage U only copies planes.
+// (Measured on MI355X: a device-wide barrier inside one launch costs 4 us or more with
+// agent-scope atomics and fences, more than the boundary between two launches, so the stages
+// are separate launches.)
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tsvd_kernels.h"
+
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+#define NPRE 8       // weight tiles per wavefront loaded at entry
+#define XR_MAX 4     // x: groups of 4 consecutive elements per thread  (N <= 16384)
+#define ZR_MAX 8     // z planes: 16-byte chunks per thread             (K <= 16384)
+
+// Optional phase timestamps (100 MHz wall clock) of thread 0 of every workgroup, for tuning.
+#define TICK(n) do { if (p.clocks && threadIdx.x == 0 && blockIdx.x < TSVD_GEMV_MAX_GRID) p.clocks[blockIdx.x * 16 + (n)] = wall_clock64(); } while (0)
+
+namespace {
+
+__device__ __forceinline__ f32x4 mfma_step(uint32_t w0, uint32_t w1, const u32x4& b0, const u32x4& b1, f32x4 acc) {
+    const i32x8 a = {(int)((w0 << 2) & 0xCCCCCCCCu), (int)(w0 & 0xCCCCCCCCu),
+                     (int)((w1 << 2) & 0xCCCCCCCCu), (int)(w1 & 0xCCCCCCCCu), 0, 0, 0, 0};
+    const i32x8 b = {(int)b0.x, (int)b0.y, (int)b0.z, (int)b0.w, (int)b1.x, (int)b1.y, (int)b1.z, (int)b1.w};
+    // cbsz = 4: A is fp4 (E2M1); blgp = 0: B is fp8 (E4M3); both block scales 2^0
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, acc, 4, 0, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
+}
+
+__device__ __forceinline__ void tile_steps(const u32x4& w, const unsigned char* xrow, f32x4& acc0, f32x4& acc1) {
+    const u32x4* xb = reinterpret_cast<const u32x4*>(xrow);
+    acc0 = mfma_step(w.x, w.y, xb[0], xb[1], acc0);      // columns   0..127 of the tile
+    acc1 = mfma_step(w.z, w.w, xb[8], xb[9], acc1);      // columns 128..255
+}
+
+// fp8 (E4M3) codes of four integers 0..15 held one per byte.
+__device__ __forceinline__ uint32_t fp8_of_nibbles(uint32_t v) {
+    // 0..7 by table (0x00 0x38 0x40 0x44 | 0x48 0x4A 0x4C 0x4E), 8..15 are 0x48 + n
+    const uint32_t small = __builtin_amdgcn_perm(0x4E4C4A48u, 0x44403800u, v & 0x07070707u);
+    const uint32_t big = v + 0x48484848u;
+    const uint32_t mask = ((v >> 3) & 0x01010101u) * 0xFFu;
+    return (big & mask) | (small & ~mask);
+}
+
+// Digit planes of one activation: sign-magnitude fixed point, |v| < 2^ex -> magnitude <= 2^30.
+// even: digits 0,2,4,6 (one per byte), odd: digits 1,3,5,7, as fp8 codes with the sign applied.
+__device__ __forceinline__ void digit_codes(float v, int ex, uint32_t& even, uint32_t& odd) {
+    const uint32_t mag = (uint32_t)rintf(ldexpf(fabsf(v), 30 - ex));
+    const uint32_t sign = v < 0.f ? 0x80808080u : 0u;
+    even = fp8_of_nibbles(mag & 0x0F0F0F0Fu) | sign;
+    odd = fp8_of_nibbles((mag >> 4) & 0x0F0F0F0Fu) | sign;
+}
+
+// exponent ex with m < 2^ex (m >= 0 finite); 0 for m == 0
+__device__ __forceinline__ int bound_exponent(float m) {
+    int ex = 0;
+    if (m > 0.f && m < 3.0e38f) (void)frexpf(m, &ex);
+    return ex;
+}
+
+__device__ __forceinline__ double pow2(int e) {      // 2^e for -1022 <= e <= 1023
+    return __hiloint2double((1023 + e) << 20, 0);
+}
+
+// Maximum over the 64 lanes, returned in every lane (inputs >= 0).
+__device__ __forceinline__ float wave_max(float v) {
+    int x = __float_as_int(v);                                          // order-preserving for v >= 0
+    x = max(x, __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, true));    // quad_perm [1,0,3,2]
+    x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, true));    // quad_perm [2,3,0,1]
+    x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, true));   // row_half_mirror
+    x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, true));   // row_mirror
+    const int r = max(max(__builtin_amdgcn_readlane(x, 0), __builtin_amdgcn_readlane(x, 16)),
+                      max(__builtin_amdgcn_readlane(x, 32), __builtin_amdgcn_readlane(x, 48)));
+    return __int_as_float(r);
+}
+
+// Horner recombination (base 16) of the eight digit-plane sums of one output row.
+__device__ __forceinline__ double combine_planes(const float* sums) {
+    const f32x4 lo = *reinterpret_cast<const f32x4*>(sums), hi = *reinterpret_cast<const f32x4*>(sums + 4);
+    double acc = (double)hi.w;
+    acc = acc * 16.0 + (double)hi.z;
+    acc = acc * 16.0 + (double)hi.y;
+    acc = acc * 16.0 + (double)hi.x;
+    acc = acc * 16.0 + (double)lo.w;
+    acc = acc * 16.0 + (double)lo.z;
+    acc = acc * 16.0 + (double)lo.y;
+    acc = acc * 16.0 + (double)lo.x;
+    return acc;
+}
+
+}  // namespace
+
+// Dynamic LDS: digit planes [8][kdim + 16] bytes, reduction tiles [16 wavefronts][16][16] fp32,
+// plane sums [256 rows][8] fp32, 64 words of scratch.  blockDim.x = 1024; wavefront w works on strip w >> kw_log2 of the
+// workgroup with contraction split w & (kw - 1).  ROUNDS = activation load rounds per thread
+// (stage V: 4096 elements of x per round; stage U: 2048 columns of the planes per round).
+// All loads are unconditional (out-of-range indices are clamped to valid memory and the values
+// discarded): a load under a branch would make the compiler wait for every outstanding load.
+template <bool STAGE_U, int ROUNDS>
+__global__ void __launch_bounds__(1024)
+tsvd_gemv_kernel(tsvd_gemv_args p) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 15, g = lane >> 4;
+    const int kdim = STAGE_U ? p.Kp : p.Np;               // contraction length (padded)
+    const int pstride = kdim + 16;
+    unsigned char* planes = smem;
+    float* red = reinterpret_cast<float*>(smem + (((size_t)8 * pstride + 255) & ~(size_t)255));
+    float* sums = red + 16 * 256;
+    float* scratch = sums + 256 * 8;
+    const unsigned char* xlane = planes + (size_t)(i & 7) * pstride + 32 * g;   // MFMA columns 8..15 repeat 0..7
+    const int kw = 1 << p.kw_log2;
+    const int sidx = wave >> p.kw_log2, q = wave & (kw - 1);
+    const int strip = blockIdx.x * p.sw + sidx;
+    const bool active = sidx < p.sw && strip < p.strips;
+    const u32x4* wp = reinterpret_cast<const u32x4*>(p.tiles) + ((size_t)(active ? strip : 0) * p.nkt) * 64 + lane;
+    TICK(0);
+
+    // ---- every load of this wavefront, in the order of need: activations first, then weights
+    float xv[ROUNDS][4];
+    u32x4 zv[ROUNDS];
+    int ex_in = 0, ex_z = 0;
+    if constexpr (STAGE_U) {
+        ex_in = p.meta[0];
+        // plane c is copied by threads c * 128 .. c * 128 + 127, 16 bytes each per round
+        const int c = threadIdx.x >> 7, t = threadIdx.x & 127;
+        const u32x4* src = reinterpret_cast<const u32x4*>(p.planes_in + (size_t)c * p.Kp);
+        const int last = p.Kp / 16 - 1;
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) zv[r] = src[min(t + 128 * r, last)];
+    } else {
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) {
+            const int k = 4 * (threadIdx.x + 1024 * r);
+            if (p.x_vec) {                                     // contiguous, aligned, N % 4 == 0
+                const int kc = min(k, p.N - 4);
+                if (p.x_is_bf16) {
+                    const u32x2 v = *reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(p.x) + kc);
+                    xv[r][0] = __uint_as_float(v.x << 16); xv[r][1] = __uint_as_float(v.x & 0xFFFF0000u);
+                    xv[r][2] = __uint_as_float(v.y << 16); xv[r][3] = __uint_as_float(v.y & 0xFFFF0000u);
+                } else {
+                    const f32x4 v = *reinterpret_cast<const f32x4*>(static_cast<const float*>(p.x) + kc);
+                    xv[r][0] = v.x; xv[r][1] = v.y; xv[r][2] = v.z; xv[r][3] = v.w;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const size_t off = (size_t)min(k + e, p.N - 1) * p.ldx;
+                    xv[r][e] = p.x_is_bf16 ? __uint_as_float(((uint32_t) static_cast<const uint16_t*>(p.x)[off]) << 16)
+                                           : static_cast<const float*>(p.x)[off];
+                }
+            }
+        }
+    }
+    u32x4 pre[NPRE];
+#pragma unroll
+    for (int n = 0; n < NPRE; ++n) pre[n] = __builtin_nontemporal_load(wp + (size_t)min(q + n * kw, p.nkt - 1) * 64);
+    TICK(1);
+
+    // ---- stage the digit planes in LDS
+    if constexpr (STAGE_U) {
+        const int c = threadIdx.x >> 7, t = threadIdx.x & 127;
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) {
+            const int ch = t + 128 * r;
+            if (ch * 16 < p.Kp) *reinterpret_cast<u32x4*>(planes + (size_t)c * pstride + ch * 16) = zv[r];
+        }
+    } else {
+        float m = 0.f;
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) {
+            const int k = 4 * (threadIdx.x + 1024 * r);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                xv[r][e] = k + e < p.N ? xv[r][e] : 0.f;          // clamped loads beyond N
+                m = fmaxf(m, fabsf(xv[r][e]));
+            }
+        }
+        m = wave_max(m);
+        if (lane == 0) scratch[wave] = m;
+        __syncthreads();
+        m = scratch[lane & 15];
+        m = wave_max(m);
+        ex_in = bound_exponent(m);
+        ex_z = bound_exponent(p.bound_V * m) + 1;   // one more bit for the rounding of the bound itself
+        if (blockIdx.x == 0 && threadIdx.x == 0) p.meta[0] = ex_z;
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) {
+            const int k = 4 * (threadIdx.x + 1024 * r);
+            if (k < p.Np) {
+                // four consecutive activations -> one 32-bit word per plane
+                uint32_t ev[4], od[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) digit_codes(xv[r][e], ex_in, ev[e], od[e]);
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const uint32_t we = ((ev[0] >> (8 * d)) & 0xFFu) | (((ev[1] >> (8 * d)) & 0xFFu) << 8) |
+                                        (((ev[2] >> (8 * d)) & 0xFFu) << 16) | (((ev[3] >> (8 * d)) & 0xFFu) << 24);
+                    const uint32_t wo = ((od[0] >> (8 * d)) & 0xFFu) | (((od[1] >> (8 * d)) & 0xFFu) << 8) |
+                                        (((od[2] >> (8 * d)) & 0xFFu) << 16) | (((od[3] >> (8 * d)) & 0xFFu) << 24);
+                    *reinterpret_cast<uint32_t*>(planes + (size_t)(2 * d) * pstride + k) = we;
+                    *reinterpret_cast<uint32_t*>(planes + (size_t)(2 * d + 1) * pstride + k) = wo;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    TICK(2);
+
+    // ---- stream this wavefront's tiles T = q, q + kw, ...
+    f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    if (active) {
+#pragma unroll
+        for (int n = 0; n < NPRE; ++n) {
+            const int T = q + n * kw;
+            if (T < p.nkt) tile_steps(pre[n], xlane + T * 256, acc0, acc1);
+        }
+        for (int T = q + NPRE * kw; T < p.nkt; T += kw) {
+            const u32x4 w0 = __builtin_nontemporal_load(wp + (size_t)T * 64);
+            tile_steps(w0, xlane + T * 256, acc0, acc1);
+        }
+    }
+    // D layout of the 16x16 MFMA: lane holds column i, rows 4 g + v.  Only columns 0..7 matter.
+    if (i < 8) {
+        float* mine = red + (size_t)wave * 256;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) mine[(4 * g + v) * 16 + i] = acc0[v] + acc1[v];
+    }
+    __syncthreads();
+    TICK(3);
+
+    // ---- add the kw partial tiles (all threads), then recombine the planes, scale, store
+    for (int idx = threadIdx.x; idx < p.sw * 128; idx += blockDim.x) {
+        const int rl = idx >> 3, pc = idx & 7;                      // row within the workgroup, plane
+        const float* src = red + (size_t)((rl >> 4) * kw) * 256 + (rl & 15) * 16 + pc;
+        float part = 0.f;
+        for (int qq = 0; qq < kw; ++qq) part += src[qq * 256];      // integers < 2^24: exact
+        sums[idx] = part;
+    }
+    __syncthreads();
+    for (int rl = threadIdx.x; rl < p.sw * 16; rl += blockDim.x) {
+        const int row = blockIdx.x * p.sw * 16 + rl;
+        if (row >= p.rows_out) continue;
+        // acc = 2 * sum_k A[row][k] * fixed(in[k]): undo the factor 2 and the fixed-point scale
+        const double val = combine_planes(sums + rl * 8) * pow2(ex_in - 31);
+        if constexpr (STAGE_U) {
+            p.y[(size_t)row * p.ldy] = (float)val;
+        } else {
+            const float z = (float)((double)p.S[row] * val);
+            uint32_t ev, od;
+            digit_codes(z, ex_z, ev, od);
+            unsigned char* dst = p.planes_out + row;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                dst[(size_t)(2 * d) * p.Kp] = (unsigned char)(ev >> (8 * d));
+                dst[(size_t)(2 * d + 1) * p.Kp] = (unsigned char)(od >> (8 * d));
+            }
+        }
+    }
+    TICK(4);
+}
+
+namespace {
+template <bool STAGE_U, int ROUNDS>
+hipError_t init_one() {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemv_kernel<STAGE_U, ROUNDS>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, TSVD_SKINNY_MAX_LDS);
+}
+size_t gemv_lds_bytes(long long kdim) {
+    return ((8 * (size_t)(kdim + 16) + 255) & ~(size_t)255) + (16 * 256 + 256 * 8 + 64) * sizeof(float);
+}
+}  // namespace
+
+hipError_t tsvd_gemv_init() {
+    hipError_t e;
+    if ((e = init_one<false, 1>()) != hipSuccess) return e;
+    if ((e = init_one<false, 2>()) != hipSuccess) return e;
+    if ((e = init_one<false, 4>()) != hipSuccess) return e;
+    if ((e = init_one<true, 1>()) != hipSuccess) return e;
+    if ((e = init_one<true, 2>()) != hipSuccess) return e;
+    if ((e = init_one<true, 4>()) != hipSuccess) return e;
+    return init_one<true, 8>();
+}
+
+// Limits of the one-batch loads and of LDS.
+bool tsvd_gemv_fits(long long Np, long long Kp) {
+    return Np <= 4096LL * XR_MAX && Kp <= 2048LL * ZR_MAX && gemv_lds_bytes(Np > Kp ? Np : Kp) <= TSVD_SKINNY_MAX_LDS;
+}
+
+hipError_t tsvd_launch_gemv(const tsvd_gemv_args& a, bool stage_u, hipStream_t stream) {
+    if (!tsvd_gemv_fits(a.Np, a.Kp) || a.sw < 1 || a.kw_log2 < 0 || (a.sw << a.kw_log2) > 16 || a.strips < 1)
+        return hipErrorInvalidValue;
+    const dim3 grid((a.strips + a.sw - 1) / a.sw), block(1024);
+    if (stage_u) {
+        const size_t lds = gemv_lds_bytes(a.Kp);
+        if (a.Kp <= 2048) hipLaunchKernelGGL((tsvd_gemv_kernel<true, 1>), grid, block, lds, stream, a);
+        else if (a.Kp <= 4096) hipLaunchKernelGGL((tsvd_gemv_kernel<true, 2>), grid, block, lds, stream, a);
+        else if (a.Kp <= 8192) hipLaunchKernelGGL((tsvd_gemv_kernel<true, 4>), grid, block, lds, stream, a);
+        else hipLaunchKernelGGL((tsvd_gemv_kernel<true, 8>), grid, block, lds, stream, a);
+    } else {
+        const size_t lds = gemv_lds_bytes(a.Np);
+        if (a.Np <= 4096) hipLaunchKernelGGL((tsvd_gemv_kernel<false, 1>), grid, block, lds, stream, a);
+        else if (a.Np <= 8192) hipLaunchKernelGGL((tsvd_gemv_kernel<false, 2>), grid, block, lds, stream, a);
+        else hipLaunchKernelGGL((tsvd_gemv_kernel<false, 4>), grid, block, lds, stream, a);
+    }
+    return hipGetLastError();
+}

@@ -5,31 +5,56 @@
 
 #define TSVD_SKINNY_MAX_LDS (150 * 1024)
 
-// out[row][tok] = post * rowscale[row] * sum_k A[row][k] * in[k][tok]   (A entries are +-2, 0
-// after decoding, so post carries the factor 1/2).
+// One stage of the skinny path: out = A . in for a packed ternary A and one or two tokens.
+#define TSVD_SKINNY_STAGE_V 0   // in: raw activations; out: digit planes of z = S * (V x)
+#define TSVD_SKINNY_STAGE_U 1   // in: digit planes of z;  out: y fp32
 struct tsvd_skinny_args {
     const void* tiles;      // packed tiles of A: [strips_total][nkt][1 KiB]
-    int strips;             // strips to compute = ceil(rows_valid / 16)
+    int strips;             // 16-row strips to compute
     int nkt;                // tiles per strip along the contraction index
-    const void* in;         // activations [kvalid][tokens], row stride ld_in elements
-    int in_is_bf16;         // 1: bf16 bit patterns, 0: fp32
-    int kvalid;             // rows of `in` that exist; the rest is taken as zero
+    int mode;
+    const void* in;         // stage V: activations [kvalid][tokens] (row stride ld_in elements)
+                            // stage U: fp8 digit planes [8 * tokens][ld_in bytes]
+    int in_is_bf16;         // stage V: 1 = bf16 bit patterns, 0 = fp32
+    int kvalid;             // stage V: rows of `in` that exist; the rest is taken as zero
     long long ld_in;
-    int tokens;             // tokens in this launch; tokens * pieces <= 16
-    int pieces;             // bf16 parts per activation: 1 (bf16 input), 2 or 3 (fp32 input)
-    const float* rowscale;  // nullable
-    float post;
-    float* out;             // [rows_valid][tokens], row stride ld_out
+    int tokens;             // 1 or 2
+    const float* rowscale;  // stage V: S (zero-padded to the strips computed)
+    float bound_V;          // stage V: |z| <= bound_V * max|x|
+    const int* meta_in;     // stage U: per-token fixed-point exponent of z
+    int* meta_out;          // stage V: writes that exponent
+    void* out;              // stage V: digit planes [8 * tokens][ld_out bytes]; stage U: fp32 [rows_out][ld_out]
     long long ld_out;
-    int rows_valid;
+    int rows_out;           // rows of the result that exist
     int slab_tiles;         // contraction tiles staged in LDS at a time
     int sw, kw;             // workgroup = sw strips x kw contraction splits (one wavefront each)
 };
 
 hipError_t tsvd_launch_skinny(const tsvd_skinny_args& a, hipStream_t stream);
-
-// Per-device one-time setup of kernel attributes (dynamic LDS limits).
 hipError_t tsvd_skinny_init();
+size_t tsvd_skinny_lds_bytes(int tokens, int slab_tiles, int sw, int kw);
+
+// One stage of the single-token fast path (tsvd_gemv.hip).  Workgroup b owns strips
+// [b sw, (b+1) sw) of the stage's matrix; wavefront w works on strip w >> kw_log2 with contraction
+// split w & (kw - 1); sw << kw_log2 <= 16.
+struct tsvd_gemv_args {
+    const void* tiles; int strips, nkt;   // stage V: V, Kp/16 strips, Np/256 tiles; stage U: U, ceil(M/16), Kp/256
+    int sw, kw_log2;
+    int N, Np, Kp, rows_out;              // rows_out: Kp (stage V, padding rows give z = 0) or M (stage U)
+    // stage V
+    const void* x; int x_is_bf16; int x_vec; long long ldx;   // x_vec: contiguous and 16-byte aligned
+    const float* S; float bound_V;
+    unsigned char* planes_out;            // fp8 digit planes of z, [8][Kp]
+    // stage U
+    const unsigned char* planes_in;
+    float* y; long long ldy;
+    int* meta;                            // fixed-point exponent of z (written by V, read by U)
+    long long* clocks;                    // optional tuning aid: [grid][16] phase timestamps, or null
+};
+hipError_t tsvd_gemv_init();
+bool tsvd_gemv_fits(long long Np, long long Kp);
+hipError_t tsvd_launch_gemv(const tsvd_gemv_args& a, bool stage_u, hipStream_t stream);
+#define TSVD_GEMV_MAX_GRID 1024
 
 // ---- batched path ----------------------------------------------------------------------------
 struct tsvd_blob_header;
@@ -46,3 +71,4 @@ struct tsvd_gemm_problem {
 hipError_t tsvd_gemm_init();
 hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream);
 #define TSVD_COLMAX_PARTS 16
+int tsvd_stage_mask();   // profiling switch read from the environment (default 7 = everything)

@@ -8,20 +8,26 @@
 // 256 columns.  Tile (strip s, column block T) lives at tile index s * (C/256) + T and is
 // 1 KiB: 64 lanes x 16 bytes in lane order, so one wavefront reads it with a single fully
 // coalesced 16-byte-per-lane load.  Lane l = 16 g + i (i = l % 16, g = l / 16) owns row
-// 16 s + i.  Its four 32-bit words d = 0..3 hold 16 codes each: the code at bit 2 j + 16 h
-// (j = 0..7, h = 0..1) is the element of column
-//      256 T + 32 (2 d + j / 4) + 8 g + 2 (j % 4) + h .
-// This is the operand order of v_mfma_f32_16x16x32_{bf16,f16}: for k-step q = 2 d + j / 4
-// lane l supplies row i and the 8 contraction indices 8 g + e, e = 2 (j % 4) + h, and
-// (word << (14 - 2 j)) & 0xC000C000 turns codes j (low half) and j (high half) into the two
-// 16-bit floats of register j % 4 of that step: 0x0000, 0x4000 (+2), 0xC000 (-2) in both
-// bf16 and fp16.  The factor 2 per stage is removed exactly by the epilogues.
+// 16 s + i.  The order of the codes inside the lane's four 32-bit words w[0..3] is the A-operand
+// order of v_mfma_scale_f32_16x16x128_f8f6f4 with A in fp4 (E2M1):
+//   * words w[2h], w[2h+1] serve the MFMA step h (columns 128 h .. 128 h + 127 of the tile);
+//   * (w << 2) & 0xCCCCCCCC and w & 0xCCCCCCCC are operand registers 2u and 2u+1 (u = word & 1):
+//     code c = 2 n + p of the word becomes nibble n of register 2u + p, and a nibble holding
+//     code << 2 is the fp4 number 0 (00), +2 (01) or -2 (11);
+//   * operand element e = 8 (2u + p) + n of lane group g multiplies the B row
+//         kk = 64 (g & 1) + 32 (e >> 4) + 16 (g >> 1) + (e & 15)
+//     of the step (measured on gfx950: with an fp4 A operand the hardware pairs A elements 0..15
+//     and 16..31 of lane group g with two different B lane groups).
+// The same words feed v_mfma_f32_16x16x32_{bf16,f16} in the batched kernels: there
+// (w << (14 - 2 c)) & 0xC000C000 turns codes c and c + 8 into the two 16-bit floats 0x0000,
+// 0x4000 (+2), 0xC000 (-2) (same patterns in bf16 and fp16) and the activation rows are fetched
+// in the matching order.  The factor 2 per stage is removed exactly by the epilogues.
 #pragma once
 #include <stdint.h>
 #include <stddef.h>
 
 #define TSVD_MAGIC 0x5449423244565354ull /* "TSVD2BIT" little endian */
-#define TSVD_FORMAT_VERSION 1u
+#define TSVD_FORMAT_VERSION 2u
 #define TSVD_TILE_ROWS 16
 #define TSVD_TILE_COLS 256
 #define TSVD_TILE_BYTES 1024
@@ -42,17 +48,19 @@ static_assert(sizeof(tsvd_blob_header) == 256, "header must be 256 bytes");
 
 static inline int64_t tsvd_round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
+// Column kk (0..127) of an MFMA step  <->  (lane group g, operand element e).
+static inline int tsvd_step_column(int g, int e) { return 64 * (g & 1) + 32 * (e >> 4) + 16 * (g >> 1) + (e & 15); }
+
 // Bit position of element (row r, column c) inside its tile: returns the lane's 32-bit word
 // index (0..255 within the tile) in *word and the bit offset of the 2-bit code.
 static inline void tsvd_code_position(int r_in_tile, int c_in_tile, int* word, int* bit) {
-    const int i = r_in_tile;            // 0..15
-    const int q = c_in_tile >> 5;       // k-step 0..7
-    const int g = (c_in_tile >> 3) & 3; // lane group
-    const int e = c_in_tile & 7;        // element within the lane's 8
+    const int i = r_in_tile;                 // 0..15
+    const int h = c_in_tile >> 7;            // MFMA step of 128 columns
+    const int kk = c_in_tile & 127;
+    const int g = ((kk >> 6) & 1) | (((kk >> 4) & 1) << 1);
+    const int e = (((kk >> 5) & 1) << 4) | (kk & 15);
+    const int v = e >> 3, n = e & 7;         // operand register, nibble
     const int lane = 16 * g + i;
-    const int d = q >> 1;
-    const int j = 4 * (q & 1) + (e >> 1);
-    const int h = e & 1;
-    *word = lane * 4 + d;
-    *bit = 2 * j + 16 * h;
+    *word = lane * 4 + 2 * h + (v >> 1);
+    *bit = 2 * (2 * n + (v & 1));
 }
