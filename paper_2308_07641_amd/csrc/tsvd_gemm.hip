@@ -86,7 +86,8 @@ struct gemm_args {
     long long ld;
     int kvalid;               // activation rows that exist (stage 1: N); others read as zero
     int bvalid;               // activation columns that exist
-    int act_fast;             // 1: rows 16-byte aligned, any full 8-column chunk may be loaded whole
+    unsigned act_bytes;       // size of the activation buffer (buffer-load range check)
+    unsigned tile_bytes;      // size of the packed tiles
     const float* S;           // stage 1: row scales
     const float* colpart;     // column maxima partials [PARTS][Bp]
     int Bp;
@@ -111,17 +112,66 @@ __device__ __forceinline__ u32x2 lds_tr(const unsigned char* lds_byte_ptr) {
     return __builtin_bit_cast(u32x2, r);
 }
 
+// D block layout: lane holds column i, rows 4 g + v.  col0 = first token of this wavefront's tile.
+template <int TM, int TN, bool STAGE2>
+__device__ __forceinline__ void gemm_epilogue(const gemm_args& p, f32x4 (&acc)[TM][TN], int strip0, int col0, int i, int g) {
+    float cs[TN];
+#pragma unroll
+    for (int b = 0; b < TN; ++b) {
+        const int col = col0 + b * 16 + i;
+        const float sc = column_scale(p.colpart, p.Bp, col, p.bound_V);
+        cs[b] = STAGE2 ? 0.5f / sc : 0.5f * sc;      // powers of two: exact
+    }
+#pragma unroll
+    for (int a = 0; a < TM; ++a) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int row = (strip0 + a) * 16 + 4 * g + v;
+            if constexpr (STAGE2) {
+                if (row < p.rows_valid) {
+                    float* dst = static_cast<float*>(p.out) + (size_t)row * p.ld_out;
+#pragma unroll
+                    for (int b = 0; b < TN; ++b) {
+                        const int col = col0 + b * 16 + i;
+                        if (col < p.bvalid) dst[col] = acc[a][b][v] * cs[b];
+                    }
+                }
+            } else {
+                const float sr = p.S[row];            // zero beyond K: padded rows of Z become 0
+                _Float16* dst = static_cast<_Float16*>(p.out) + (size_t)row * p.ld_out;
+#pragma unroll
+                for (int b = 0; b < TN; ++b) {
+                    const int col = col0 + b * 16 + i;
+                    dst[col] = (_Float16)((acc[a][b][v] * sr) * cs[b]);
+                }
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ u32x4 buf_load128(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+}
+__device__ __forceinline__ uint32_t buf_load32(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
+    return __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0);
+}
+
 // Workgroup tile (WM*TM*16 rows) x (WN*TN*16 tokens); WM x WN wavefronts, each TM x TN MFMA blocks.
-template <int WM, int WN, int TM, int TN, bool STAGE2>
+// FAST: activation rows are 16-byte aligned, so tiles are fetched with buffer loads whose
+// range check returns zero beyond the last row (no per-element guards, no address arithmetic
+// in the loop: a per-thread offset plus a scalar offset per stage).
+template <int WM, int WN, int TM, int TN, bool STAGE2, bool FAST>
 __global__ void __launch_bounds__(64 * WM * WN)
 tsvd_gemm_kernel(gemm_args p) {
     constexpr int THREADS = 64 * WM * WN;
     constexpr int BT = WN * TN * 16;                 // tokens per workgroup tile
     constexpr int ROWB = BT * 2;                     // bytes per LDS row
     constexpr int NBLK = BT / 16;                    // 32-byte blocks per LDS row
-    constexpr int CHUNKS = KT * BT / 8;              // 16-byte chunks per stage
+    constexpr int CPR = BT / 8;                      // 16-byte chunks per LDS row
+    constexpr int CHUNKS = KT * CPR;                 // chunks per stage
     constexpr int CPT = CHUNKS / THREADS;            // chunks per thread
-    static_assert(CHUNKS % THREADS == 0, "tile/threads mismatch");
+    constexpr int STAGE_BYTES = KT * ROWB;
+    static_assert(CHUNKS % THREADS == 0 && THREADS % CPR == 0, "tile/threads mismatch");
     extern __shared__ __align__(16) unsigned char smem[];   // 2 stages x KT x ROWB
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -140,7 +190,24 @@ tsvd_gemm_kernel(gemm_args p) {
     const int rsel = i >> 2;
     const int tr_row = 32 * (g & 1) + 16 * (g >> 1) + (rsel >> 1) + 4 * (rsel & 1);
     const int f_lane = ((((tr_row & 1) << 1) | ((tr_row >> 2) & 1) | (((tr_row >> 4) & 3) << 2))) & (NBLK - 1);
-    const int tr_in = (i & 3) * 8;
+    int lds_rd[TN];                                   // byte offset of this lane's transposed reads
+#pragma unroll
+    for (int b = 0; b < TN; ++b) lds_rd[b] = tr_row * ROWB + (((wn * TN + b) ^ f_lane) * 32) + (i & 3) * 8;
+
+    // activation chunk c of this thread: LDS row r_c, 16-byte chunk ch (same for all c)
+    const int ch = threadIdx.x % CPR, r_first = threadIdx.x / CPR;
+    int lds_wr[CPT], x_voff[CPT];
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+        const int r = r_first + c * (THREADS / CPR);
+        const int f = (((r & 1) << 1) | ((r >> 2) & 1) | (((r >> 4) & 3) << 2)) & (NBLK - 1);
+        lds_wr[c] = r * ROWB + (((ch >> 1) ^ f) * 32) + (ch & 1) * 16;
+        x_voff[c] = (64 * (r >> 5) + (r & 31)) * (int)p.ld * 2 + (b0 + ch * 8) * 2;
+    }
+    const __amdgpu_buffer_rsrc_t act_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.act), 0, p.act_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t w_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(p.tiles), 0, p.tile_bytes, 0x00020000);
 
     f32x4 acc[TM][TN];
 #pragma unroll
@@ -148,133 +215,237 @@ tsvd_gemm_kernel(gemm_args p) {
 #pragma unroll
         for (int b = 0; b < TN; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    auto stage_k0 = [](int stage) { return 256 * (stage >> 2) + 128 * ((stage >> 1) & 1) + 32 * (stage & 1); };
+
     // ---- activation tile: global -> registers -> LDS
     u32x4 xreg[CPT];
     auto load_x = [&](int stage) {
-        const int T = stage >> 2, d = stage & 3;
-        const int k0 = 256 * T + 128 * (d >> 1) + 32 * (d & 1);
+        const int k0 = stage_k0(stage);
+        if constexpr (FAST) {
+            const int soff = k0 * (int)p.ld * 2;
 #pragma unroll
-        for (int c = 0; c < CPT; ++c) {
-            const int id = threadIdx.x + c * THREADS;
-            const int r = id / (BT / 8), ch = id - r * (BT / 8);
-            const int k = k0 + 64 * (r >> 5) + (r & 31), col = b0 + ch * 8;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (k < p.kvalid) {
-                const uint16_t* src = p.act + (size_t)k * p.ld + col;
-                if (p.act_fast && col + 8 <= p.bvalid) {
-                    v = *reinterpret_cast<const u32x4*>(src);
-                } else {
+            for (int c = 0; c < CPT; ++c) xreg[c] = buf_load128(act_rsrc, x_voff[c], soff);
+        } else {
+#pragma unroll
+            for (int c = 0; c < CPT; ++c) {
+                const int r = r_first + c * (THREADS / CPR);
+                const int k = k0 + 64 * (r >> 5) + (r & 31), col = b0 + ch * 8;
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (k < p.kvalid) {
+                    const uint16_t* src = p.act + (size_t)k * p.ld + col;
                     uint32_t e[8];
 #pragma unroll
                     for (int t = 0; t < 8; ++t) e[t] = (col + t < p.bvalid) ? (uint32_t)src[t] : 0u;
                     v = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
                 }
+                xreg[c] = v;
             }
-            xreg[c] = v;
         }
     };
     auto store_x = [&](int buf) {
-        unsigned char* base = smem + buf * (KT * ROWB);
 #pragma unroll
-        for (int c = 0; c < CPT; ++c) {
-            const int id = threadIdx.x + c * THREADS;
-            const int r = id / (BT / 8), ch = id - r * (BT / 8);
-            const int f = (((r & 1) << 1) | ((r >> 2) & 1) | (((r >> 4) & 3) << 2)) & (NBLK - 1);
-            const int blk = (ch >> 1) ^ f;
-            *reinterpret_cast<u32x4*>(base + r * ROWB + blk * 32 + (ch & 1) * 16) = xreg[c];
-        }
+        for (int c = 0; c < CPT; ++c) *reinterpret_cast<u32x4*>(smem + buf * STAGE_BYTES + lds_wr[c]) = xreg[c];
     };
     // ---- weights: one code word per strip and stage, straight from global/L2
-    const uint32_t* wbase = p.tiles + ((size_t)strip0 * p.nkt) * 256 + lane * 4;
-    uint32_t wcur[TM], wnext[TM];
+    const int w_voff = lane * 16;
     auto load_w = [&](int stage, uint32_t (&w)[TM]) {
-        const int T = stage >> 2, d = stage & 3;
+        const int soff = (strip0 * p.nkt + (stage >> 2)) * 1024 + (stage & 3) * 4;
 #pragma unroll
-        for (int a = 0; a < TM; ++a) w[a] = wbase[((size_t)a * p.nkt + T) * 256 + d];
+        for (int a = 0; a < TM; ++a) w[a] = buf_load32(w_rsrc, w_voff, soff + a * p.nkt * 1024);
     };
-
-    load_x(0);
-    load_w(0, wcur);
-    store_x(0);
-    __syncthreads();
-
-    for (int s = 0; s < nstages; ++s) {
-        const bool more = s + 1 < nstages;
-        if (more) {
-            load_x(s + 1);
-            load_w(s + 1, wnext);
-        }
-        const unsigned char* base = smem + (s & 1) * (KT * ROWB);
+    auto compute = [&](int buf, const uint32_t (&w)[TM]) {
+        const unsigned char* base = smem + buf * STAGE_BYTES;
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {
             u32x2 blo[TN], bhi[TN];
 #pragma unroll
             for (int b = 0; b < TN; ++b) {
-                const int blk = ((wn * TN + b) ^ f_lane);
-                const unsigned char* ptr = base + (tr_row + 8 * hh) * ROWB + blk * 32 + tr_in;
-                blo[b] = lds_tr(ptr);
-                bhi[b] = lds_tr(ptr + 2 * ROWB);
+                blo[b] = lds_tr(base + lds_rd[b] + hh * 8 * ROWB);
+                bhi[b] = lds_tr(base + lds_rd[b] + hh * 8 * ROWB + 2 * ROWB);
             }
 #pragma unroll
             for (int a = 0; a < TM; ++a) {
-                const uint32_t w = wcur[a];
+                const uint32_t ww = w[a];
                 // register m of the operand = codes hh + 2 m (low half) and hh + 2 m + 8 (high half)
                 u32x4 av;
-                if (hh == 0) av = u32x4{TSVD_DEC(w, 0), TSVD_DEC(w, 2), TSVD_DEC(w, 4), TSVD_DEC(w, 6)};
-                else         av = u32x4{TSVD_DEC(w, 1), TSVD_DEC(w, 3), TSVD_DEC(w, 5), w & 0xC000C000u};
+                if (hh == 0) av = u32x4{TSVD_DEC(ww, 0), TSVD_DEC(ww, 2), TSVD_DEC(ww, 4), TSVD_DEC(ww, 6)};
+                else         av = u32x4{TSVD_DEC(ww, 1), TSVD_DEC(ww, 3), TSVD_DEC(ww, 5), ww & 0xC000C000u};
 #pragma unroll
                 for (int b = 0; b < TN; ++b) acc[a][b] = mfma16<STAGE2>(av, blo[b], bhi[b], acc[a][b]);
             }
         }
-        if (more) {
-            store_x((s + 1) & 1);
-#pragma unroll
-            for (int a = 0; a < TM; ++a) wcur[a] = wnext[a];
-        }
+    };
+
+    uint32_t w0[TM], w1[TM];
+    load_x(0);
+    load_w(0, w0);
+    store_x(0);
+    __syncthreads();
+
+    // Two stages per iteration so that the LDS buffer and the weight registers alternate at
+    // compile time.  The prefetch of the stage after the last one re-reads the last stage
+    // (unconditional loads keep the wait counts exact); its results are never used.
+    const int last = nstages - 1;
+    for (int s = 0; s < nstages; s += 2) {
+        load_x(min(s + 1, last));
+        load_w(min(s + 1, last), w1);
+        compute(0, w0);
+        store_x(1);
+        __syncthreads();
+        load_x(min(s + 2, last));
+        load_w(min(s + 2, last), w0);
+        compute(1, w1);
+        store_x(0);
         __syncthreads();
     }
 
-    // ---- epilogue.  D block layout: lane holds column i, rows 4 g + v.
-    float cs[TN];
-#pragma unroll
-    for (int b = 0; b < TN; ++b) {
-        const int col = b0 + (wn * TN + b) * 16 + i;
-        const float sc = column_scale(p.colpart, p.Bp, col, p.bound_V);
-        cs[b] = STAGE2 ? 0.5f / sc : 0.5f * sc;      // powers of two: exact
-    }
-#pragma unroll
-    for (int a = 0; a < TM; ++a) {
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int row = (strip0 + a) * 16 + 4 * g + v;
-            if constexpr (STAGE2) {
-                if (row < p.rows_valid) {
-                    float* dst = static_cast<float*>(p.out) + (size_t)row * p.ld_out;
-#pragma unroll
-                    for (int b = 0; b < TN; ++b) {
-                        const int col = b0 + (wn * TN + b) * 16 + i;
-                        if (col < p.bvalid) dst[col] = acc[a][b][v] * cs[b];
-                    }
-                }
-            } else {
-                const float sr = p.S[row];            // zero beyond K: padded rows of Z become 0
-                _Float16* dst = static_cast<_Float16*>(p.out) + (size_t)row * p.ld_out;
-#pragma unroll
-                for (int b = 0; b < TN; ++b) {
-                    const int col = b0 + (wn * TN + b) * 16 + i;
-                    dst[col] = (_Float16)((acc[a][b][v] * sr) * cs[b]);
-                }
-            }
-        }
-    }
+    gemm_epilogue<TM, TN, STAGE2>(p, acc, strip0, b0 + wn * TN * 16, i, g);
+}
+
+// ---- pipelined variant (activation rows 16-byte aligned) -----------------------------------
+// Same tiling and arithmetic as tsvd_gemm_kernel, different data movement: activation tiles go
+// from global memory straight into LDS (buffer_load ... lds, 16 bytes per lane, no registers, the
+// range check writes zeros beyond the last row), two stages ahead of the MFMAs, through a ring of
+// four LDS buffers.  One barrier per stage.  Each wavefront fills SPW 1-KiB slots per stage; a
+// slot is written in lane order, so the XOR swizzle is applied on the global side (which chunk
+// of the row a lane fetches).
+// 16 bytes per lane from a buffer straight into LDS at lds_base + 16 * lane (lds_base wave-uniform).
+__device__ __forceinline__ void buf_load128_to_lds(__amdgpu_buffer_rsrc_t r, unsigned char* lds_base, int voff, int soff) {
+    typedef __attribute__((address_space(3))) void* lds_void_ptr;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void_ptr)lds_base, 16, voff, soff, 0, 0);
 }
 
 template <int WM, int WN, int TM, int TN, bool STAGE2>
-hipError_t launch_gemm(const gemm_args& a, int row_tiles, int col_tiles, hipStream_t stream) {
+__global__ void __launch_bounds__(64 * WM * WN)
+tsvd_gemm_pipe_kernel(gemm_args p) {
+    constexpr int NW = WM * WN;
+    constexpr int BT = WN * TN * 16;                 // tokens per workgroup tile
+    constexpr int ROWB = BT * 2;                     // bytes per LDS row
+    constexpr int NBLK = BT / 16;                    // 32-byte blocks per LDS row
+    constexpr int CPR = BT / 8;                      // 16-byte chunks per LDS row
+    constexpr int STAGE_BYTES = KT * ROWB;
+    constexpr int SLOTS = STAGE_BYTES / 1024;        // 1-KiB slots per stage
+    constexpr int SPW = SLOTS / NW;                  // slots per wavefront
+    constexpr int RPS = 64 / CPR;                    // rows per slot
+    static_assert(SLOTS % NW == 0 && 64 % CPR == 0, "tile/wavefront mismatch");
+    extern __shared__ __align__(16) unsigned char smem[];   // 4 stages x KT x ROWB
+
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave / WN, wn = wave - wm * WN;
+    const int i = lane & 15, g = lane >> 4;
+    const int b0 = blockIdx.x * BT;
+    const int strip0 = (blockIdx.y * WM + wm) * TM;
+    const int nstages = p.nkt * (256 / KT), last = nstages - 1;
+
+    // (row and swizzle conventions: see tsvd_gemm_kernel)
+    const int rsel = i >> 2;
+    const int tr_row = 32 * (g & 1) + 16 * (g >> 1) + (rsel >> 1) + 4 * (rsel & 1);
+    const int f_lane = ((((tr_row & 1) << 1) | ((tr_row >> 2) & 1) | (((tr_row >> 4) & 3) << 2))) & (NBLK - 1);
+    int lds_rd[TN];
+#pragma unroll
+    for (int b = 0; b < TN; ++b) lds_rd[b] = tr_row * ROWB + (((wn * TN + b) ^ f_lane) * 32) + (i & 3) * 8;
+
+    // slot j = c * NW + wave of a stage holds LDS rows j * RPS .. ; lane l writes physical chunk l % CPR
+    // of row j * RPS + l / CPR, which must hold logical chunk ((pc >> 1) ^ f(row)) * 2 + (pc & 1).
+    int x_voff[SPW];
+#pragma unroll
+    for (int c = 0; c < SPW; ++c) {
+        const int r = (c * NW + wave) * RPS + lane / CPR, pc = lane % CPR;
+        const int f = (((r & 1) << 1) | ((r >> 2) & 1) | (((r >> 4) & 3) << 2)) & (NBLK - 1);
+        const int lc = (((pc >> 1) ^ f) << 1) | (pc & 1);
+        x_voff[c] = (64 * (r >> 5) + (r & 31)) * (int)p.ld * 2 + (b0 + lc * 8) * 2;
+    }
+    const __amdgpu_buffer_rsrc_t act_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.act), 0, p.act_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t w_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(p.tiles), 0, p.tile_bytes, 0x00020000);
+
+    f32x4 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    auto issue_x = [&](int stage, int buf) {
+        const int soff = (256 * (stage >> 2) + 128 * ((stage >> 1) & 1) + 32 * (stage & 1)) * (int)p.ld * 2;
+#pragma unroll
+        for (int c = 0; c < SPW; ++c)
+            buf_load128_to_lds(act_rsrc, smem + buf * STAGE_BYTES + (c * NW + wave) * 1024, x_voff[c], soff);
+    };
+    const int w_voff = lane * 16;
+    auto load_w = [&](int stage, uint32_t (&w)[TM]) {
+        const int soff = (strip0 * p.nkt + (stage >> 2)) * 1024 + (stage & 3) * 4;
+#pragma unroll
+        for (int a = 0; a < TM; ++a) w[a] = buf_load32(w_rsrc, w_voff, soff + a * p.nkt * 1024);
+    };
+    auto compute = [&](int buf, const uint32_t (&w)[TM]) {
+        const unsigned char* base = smem + buf * STAGE_BYTES;
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            u32x2 blo[TN], bhi[TN];
+#pragma unroll
+            for (int b = 0; b < TN; ++b) {
+                blo[b] = lds_tr(base + lds_rd[b] + hh * 8 * ROWB);
+                bhi[b] = lds_tr(base + lds_rd[b] + hh * 8 * ROWB + 2 * ROWB);
+            }
+#pragma unroll
+            for (int a = 0; a < TM; ++a) {
+                const uint32_t ww = w[a];
+                u32x4 av;
+                if (hh == 0) av = u32x4{TSVD_DEC(ww, 0), TSVD_DEC(ww, 2), TSVD_DEC(ww, 4), TSVD_DEC(ww, 6)};
+                else         av = u32x4{TSVD_DEC(ww, 1), TSVD_DEC(ww, 3), TSVD_DEC(ww, 5), ww & 0xC000C000u};
+#pragma unroll
+                for (int b = 0; b < TN; ++b) acc[a][b] = mfma16<STAGE2>(av, blo[b], bhi[b], acc[a][b]);
+            }
+        }
+    };
+
+    // Issue order keeps "weights of the next stage" older than "activations two stages ahead", so the
+    // MFMAs of a stage never wait for the far prefetch.  Loads past the last stage re-read it.
+    uint32_t w0[TM], w1[TM];
+    load_w(0, w0);
+    issue_x(0, 0);
+    issue_x(min(1, last), 1);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(SPW) : "memory");      // stage 0 has landed (this wavefront's part)
+    __syncthreads();
+
+    for (int s = 0; s < nstages; s += 4) {          // one 256-wide tile of codes per iteration
+        load_w(min(s + 1, last), w1);
+        issue_x(min(s + 2, last), 2);
+        compute(0, w0);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(TM + SPW) : "memory");   // stage s + 1 has landed
+        __syncthreads();
+
+        load_w(min(s + 2, last), w0);
+        issue_x(min(s + 3, last), 3);
+        compute(1, w1);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(TM + SPW) : "memory");
+        __syncthreads();
+
+        load_w(min(s + 3, last), w1);
+        issue_x(min(s + 4, last), 0);
+        compute(2, w0);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(TM + SPW) : "memory");
+        __syncthreads();
+
+        load_w(min(s + 4, last), w0);
+        issue_x(min(s + 5, last), 1);
+        compute(3, w1);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(TM + SPW) : "memory");
+        __syncthreads();
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no LDS write may still be in flight at exit
+
+    gemm_epilogue<TM, TN, STAGE2>(p, acc, strip0, b0 + wn * TN * 16, i, g);
+}
+
+template <int WM, int WN, int TM, int TN, bool STAGE2>
+hipError_t launch_gemm(const gemm_args& a, bool fast, int row_tiles, int col_tiles, hipStream_t stream) {
     constexpr int BT = WN * TN * 16;
     constexpr size_t lds = 2 * KT * BT * 2;
-    hipLaunchKernelGGL((tsvd_gemm_kernel<WM, WN, TM, TN, STAGE2>), dim3(col_tiles, row_tiles), dim3(64 * WM * WN), lds,
-                       stream, a);
+    const dim3 grid(col_tiles, row_tiles), block(64 * WM * WN);
+    if (fast) hipLaunchKernelGGL((tsvd_gemm_pipe_kernel<WM, WN, TM, TN, STAGE2>), grid, block, 2 * lds, stream, a);
+    else hipLaunchKernelGGL((tsvd_gemm_kernel<WM, WN, TM, TN, STAGE2, false>), grid, block, lds, stream, a);
     return hipGetLastError();
 }
 
@@ -282,7 +453,10 @@ template <int WM, int WN, int TM, int TN, bool STAGE2>
 hipError_t init_gemm() {
     constexpr int BT = WN * TN * 16;
     constexpr int lds = 2 * KT * BT * 2;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_kernel<WM, WN, TM, TN, STAGE2>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_pipe_kernel<WM, WN, TM, TN, STAGE2>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 2 * lds);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_kernel<WM, WN, TM, TN, STAGE2, false>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, lds);
 }
 
@@ -309,6 +483,10 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     const size_t part_bytes = (((size_t)TSVD_COLMAX_PARTS * Bp * 4) + 255) & ~(size_t)255;
     _Float16* Z = reinterpret_cast<_Float16*>(static_cast<uint8_t*>(g.ws) + part_bytes);
 
+    // buffer loads address with 32-bit byte offsets
+    if ((size_t)hd.N * g.ldx * 2 >= (1ull << 31) || (size_t)hd.Kp * Bp * 2 >= (1ull << 31) ||
+        (size_t)hd.Mp * hd.Kp / 4 >= (1ull << 31) || (size_t)hd.Kp * hd.Np / 4 >= (1ull << 31))
+        return hipErrorInvalidValue;
     // Profiling switch: TSVD_STAGE_MASK selects the kernels to launch (1 column maxima,
     // 2 stage V, 4 stage U; default all).  Skipped kernels leave the workspace as it is.
     const int mask = tsvd_stage_mask();
@@ -327,7 +505,9 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     a1.ld = g.ldx;
     a1.kvalid = (int)hd.N;
     a1.bvalid = (int)g.B;
-    a1.act_fast = (g.ldx % 8 == 0) && ((reinterpret_cast<uintptr_t>(g.x) & 15u) == 0);
+    const bool fast1 = (g.ldx % 8 == 0) && ((reinterpret_cast<uintptr_t>(g.x) & 15u) == 0);
+    a1.act_bytes = (unsigned)((size_t)hd.N * g.ldx * 2);
+    a1.tile_bytes = (unsigned)((size_t)hd.Kp * hd.Np / 4);
     a1.S = reinterpret_cast<const float*>(g.blob + hd.off_S);
     a1.colpart = colpart;
     a1.Bp = Bp;
@@ -343,7 +523,8 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     a2.ld = Bp;
     a2.kvalid = (int)hd.Kp;
     a2.bvalid = (int)g.B;
-    a2.act_fast = 1;
+    a2.act_bytes = (unsigned)((size_t)hd.Kp * Bp * 2);
+    a2.tile_bytes = (unsigned)((size_t)hd.Mp * hd.Kp / 4);
     a2.S = nullptr;
     a2.out = g.y;
     a2.ld_out = g.ldy;
@@ -353,13 +534,13 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     const long long big_tiles = (hd.Mp / 256) * (long long)(Bp / 256);
     const bool big = big_tiles >= 256;
     if (big) {
-        if (mask & 2) e = launch_gemm<2, 4, 8, 4, false>(a1, (int)(hd.Kp / 256), Bp / 256, stream);
+        if (mask & 2) e = launch_gemm<2, 4, 8, 4, false>(a1, fast1, (int)(hd.Kp / 256), Bp / 256, stream);
         if (e != hipSuccess) return e;
-        if (mask & 4) e = launch_gemm<2, 4, 8, 4, true>(a2, (int)(hd.Mp / 256), Bp / 256, stream);
+        if (mask & 4) e = launch_gemm<2, 4, 8, 4, true>(a2, true, (int)(hd.Mp / 256), Bp / 256, stream);
         return e;
     }
-    if (mask & 2) e = launch_gemm<2, 2, 4, 4, false>(a1, (int)(hd.Kp / 128), Bp / 128, stream);
+    if (mask & 2) e = launch_gemm<2, 2, 4, 4, false>(a1, fast1, (int)(hd.Kp / 128), Bp / 128, stream);
     if (e != hipSuccess) return e;
-    if (mask & 4) e = launch_gemm<2, 2, 4, 4, true>(a2, (int)(hd.Mp / 128), Bp / 128, stream);
+    if (mask & 4) e = launch_gemm<2, 2, 4, 4, true>(a2, true, (int)(hd.Mp / 128), Bp / 128, stream);
     return e;
 }
