@@ -16,7 +16,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-pth
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, "-o", LIB]
+    cmd = [hipcc, *FLAGS, *os.environ.get("TSVD_CXXFLAGS", "").split(), "-o", LIB]
     for s in SOURCES:
         if s.endswith(".cpp"):
             cmd += ["-x", "hip", os.path.join(CSRC, s)]   # host-only source, same compiler

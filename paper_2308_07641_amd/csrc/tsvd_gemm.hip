@@ -37,6 +37,13 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 #define TSVD_DEC(w, j) ((((uint32_t)(w)) << (14 - 2 * (j))) & 0xC000C000u)
 #define KT 64   // contraction depth of one LDS stage
+#ifndef TSVD_SCHED
+#define TSVD_SCHED 0
+#endif
+// workgroup shape of the large-tile kernels: WM x WN wavefronts of TM x TN MFMA blocks (256 x 256 tile)
+#ifndef TSVD_BIG
+#define TSVD_BIG 2, 4, 8, 4
+#endif
 
 namespace {
 
@@ -309,10 +316,20 @@ tsvd_gemm_kernel(gemm_args p) {
 // four LDS buffers.  One barrier per stage.  Each wavefront fills SPW 1-KiB slots per stage; a
 // slot is written in lane order, so the XOR swizzle is applied on the global side (which chunk
 // of the row a lane fetches).
-// 16 bytes per lane from a buffer straight into LDS at lds_base + 16 * lane (lds_base wave-uniform).
-__device__ __forceinline__ void buf_load128_to_lds(__amdgpu_buffer_rsrc_t r, unsigned char* lds_base, int voff, int soff) {
-    typedef __attribute__((address_space(3))) void* lds_void_ptr;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void_ptr)lds_base, 16, voff, soff, 0, 0);
+// 16 bytes per lane from a buffer straight into LDS at lds_addr + 16 * lane (lds_addr wave-uniform).
+// Written as inline assembly on purpose: when the compiler knows about an outstanding
+// buffer_load ... lds it waits for ALL vector-memory operations (vmcnt(0)) before every later LDS
+// read, which would serialise the prefetch with the MFMAs.  Hidden from it, the only waits are
+// the explicit s_waitcnt vmcnt(n) before the barriers below.  M0 (the LDS destination) is a
+// reserved register that the compiler re-initialises before each of its own uses.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void buf_load128_to_lds(i32x4 rsrc, uint32_t lds_addr, int voff, int soff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+}
+__device__ __forceinline__ i32x4 raw_rsrc(const void* base, uint32_t bytes) {
+    const uint64_t a = reinterpret_cast<uint64_t>(base);
+    return i32x4{(int)(uint32_t)a, (int)(uint32_t)(a >> 32), (int)bytes, 0x00020000};
 }
 
 template <int WM, int WN, int TM, int TN, bool STAGE2>
@@ -355,10 +372,11 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
         const int lc = (((pc >> 1) ^ f) << 1) | (pc & 1);
         x_voff[c] = (64 * (r >> 5) + (r & 31)) * (int)p.ld * 2 + (b0 + lc * 8) * 2;
     }
-    const __amdgpu_buffer_rsrc_t act_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.act), 0, p.act_bytes, 0x00020000);
+    const i32x4 act_rsrc = raw_rsrc(p.act, p.act_bytes);
     const __amdgpu_buffer_rsrc_t w_rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(p.tiles), 0, p.tile_bytes, 0x00020000);
+    typedef __attribute__((address_space(3))) unsigned char* lds_byte_ptr;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_byte_ptr)smem + wave * 1024;
 
     f32x4 acc[TM][TN];
 #pragma unroll
@@ -370,15 +388,16 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
         const int soff = (256 * (stage >> 2) + 128 * ((stage >> 1) & 1) + 32 * (stage & 1)) * (int)p.ld * 2;
 #pragma unroll
         for (int c = 0; c < SPW; ++c)
-            buf_load128_to_lds(act_rsrc, smem + buf * STAGE_BYTES + (c * NW + wave) * 1024, x_voff[c], soff);
+            buf_load128_to_lds(act_rsrc, lds0 + buf * STAGE_BYTES + c * NW * 1024, x_voff[c], soff);
     };
+    // weights: the two code words of a pair of stages per strip, straight from global/L2
     const int w_voff = lane * 16;
-    auto load_w = [&](int stage, uint32_t (&w)[TM]) {
-        const int soff = (strip0 * p.nkt + (stage >> 2)) * 1024 + (stage & 3) * 4;
+    auto load_w = [&](int pair, u32x2 (&w)[TM]) {
+        const int soff = (strip0 * p.nkt + (pair >> 1)) * 1024 + (pair & 1) * 8;
 #pragma unroll
-        for (int a = 0; a < TM; ++a) w[a] = buf_load32(w_rsrc, w_voff, soff + a * p.nkt * 1024);
+        for (int a = 0; a < TM; ++a) w[a] = __builtin_amdgcn_raw_buffer_load_b64(w_rsrc, w_voff, soff + a * p.nkt * 1024, 0);
     };
-    auto compute = [&](int buf, const uint32_t (&w)[TM]) {
+    auto compute = [&](int buf, const u32x2 (&w)[TM], int word) {
         const unsigned char* base = smem + buf * STAGE_BYTES;
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {
@@ -390,48 +409,52 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
             }
 #pragma unroll
             for (int a = 0; a < TM; ++a) {
-                const uint32_t ww = w[a];
+                const uint32_t ww = word == 0 ? w[a].x : w[a].y;
                 u32x4 av;
                 if (hh == 0) av = u32x4{TSVD_DEC(ww, 0), TSVD_DEC(ww, 2), TSVD_DEC(ww, 4), TSVD_DEC(ww, 6)};
                 else         av = u32x4{TSVD_DEC(ww, 1), TSVD_DEC(ww, 3), TSVD_DEC(ww, 5), ww & 0xC000C000u};
 #pragma unroll
                 for (int b = 0; b < TN; ++b) acc[a][b] = mfma16<STAGE2>(av, blo[b], bhi[b], acc[a][b]);
             }
+#if TSVD_SCHED == 1
+            // interleave: one MFMA, then the two ALU operations that decode a register of the next operand
+#pragma unroll
+            for (int n = 0; n < TM * TN; ++n) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+            }
+#endif
         }
     };
 
-    // Issue order keeps "weights of the next stage" older than "activations two stages ahead", so the
-    // MFMAs of a stage never wait for the far prefetch.  Loads past the last stage re-read it.
-    uint32_t w0[TM], w1[TM];
-    load_w(0, w0);
+    // A pair of stages (128 contraction indices, two LDS buffers) per barrier.  While pair P is
+    // multiplied, the activations of pair P + 1 stream into the other two buffers and its code
+    // words into registers.  Loads past the last pair re-read it (never used).
+    const int npairs = nstages / 2, lastp = npairs - 1;
+    u32x2 wa[TM], wb[TM];
+    load_w(0, wa);
     issue_x(0, 0);
-    issue_x(min(1, last), 1);
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(SPW) : "memory");      // stage 0 has landed (this wavefront's part)
+    issue_x(1, 1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
-    for (int s = 0; s < nstages; s += 4) {          // one 256-wide tile of codes per iteration
-        load_w(min(s + 1, last), w1);
-        issue_x(min(s + 2, last), 2);
-        compute(0, w0);
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(TM + SPW) : "memory");   // stage s + 1 has landed
+    for (int P = 0; P < npairs; P += 2) {           // one 256-wide tile of codes per iteration
+        int nx = min(P + 1, lastp);
+        load_w(nx, wb);
+        issue_x(2 * nx, 2);
+        issue_x(2 * nx + 1, 3);
+        compute(0, wa, 0);
+        compute(1, wa, 1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // pair P + 1 has landed (this wavefront's part)
         __syncthreads();
 
-        load_w(min(s + 2, last), w0);
-        issue_x(min(s + 3, last), 3);
-        compute(1, w1);
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(TM + SPW) : "memory");
-        __syncthreads();
-
-        load_w(min(s + 3, last), w1);
-        issue_x(min(s + 4, last), 0);
-        compute(2, w0);
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(TM + SPW) : "memory");
-        __syncthreads();
-
-        load_w(min(s + 4, last), w0);
-        issue_x(min(s + 5, last), 1);
-        compute(3, w1);
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(TM + SPW) : "memory");
+        nx = min(P + 2, lastp);
+        load_w(nx, wa);
+        issue_x(2 * nx, 0);
+        issue_x(2 * nx + 1, 1);
+        compute(2, wb, 0);
+        compute(3, wb, 1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no LDS write may still be in flight at exit
@@ -469,8 +492,8 @@ int tsvd_stage_mask() {
 
 hipError_t tsvd_gemm_init() {
     hipError_t e;
-    if ((e = init_gemm<2, 4, 8, 4, false>()) != hipSuccess) return e;
-    if ((e = init_gemm<2, 4, 8, 4, true>()) != hipSuccess) return e;
+    if ((e = init_gemm<TSVD_BIG, false>()) != hipSuccess) return e;
+    if ((e = init_gemm<TSVD_BIG, true>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 2, 4, 4, false>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 2, 4, 4, true>()) != hipSuccess) return e;
     return hipSuccess;
@@ -534,9 +557,9 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     const long long big_tiles = (hd.Mp / 256) * (long long)(Bp / 256);
     const bool big = big_tiles >= 256;
     if (big) {
-        if (mask & 2) e = launch_gemm<2, 4, 8, 4, false>(a1, fast1, (int)(hd.Kp / 256), Bp / 256, stream);
+        if (mask & 2) e = launch_gemm<TSVD_BIG, false>(a1, fast1, (int)(hd.Kp / 256), Bp / 256, stream);
         if (e != hipSuccess) return e;
-        if (mask & 4) e = launch_gemm<2, 4, 8, 4, true>(a2, true, (int)(hd.Mp / 256), Bp / 256, stream);
+        if (mask & 4) e = launch_gemm<TSVD_BIG, true>(a2, true, (int)(hd.Mp / 256), Bp / 256, stream);
         return e;
     }
     if (mask & 2) e = launch_gemm<2, 2, 4, 4, false>(a1, fast1, (int)(hd.Kp / 128), Bp / 128, stream);
