@@ -73,6 +73,54 @@ tsvd_colmax_kernel(const uint16_t* __restrict__ x, long long ldx, int N, int B, 
     }
 }
 
+// Per-half maximum of two words holding two 16-bit magnitudes each.
+__device__ __forceinline__ uint32_t max_halves(uint32_t a, uint32_t b) {
+    const uint32_t lo = max(a & 0xFFFFu, b & 0xFFFFu), hi = max(a >> 16, b >> 16);
+    return lo | (hi << 16);
+}
+
+// Same result for 16-byte-aligned rows: each thread owns 8 adjacent columns and reads 16 bytes per
+// row.  grid (ceil(B/512), PARTS); block 256 = 64 column groups x 4 row lanes.  Columns >= B of
+// the last group may read the start of the next row (inside the buffer, except in the last row,
+// which is clamped); their maxima are never used.
+__global__ void __launch_bounds__(256)
+tsvd_colmax_vec_kernel(const uint16_t* __restrict__ x, long long ldx, int N, int B, int Bp, float* __restrict__ part) {
+    __shared__ u32x4 red[4][64];
+    const int cg = threadIdx.x & 63, rl = threadIdx.x >> 6;
+    const int c0 = blockIdx.x * 512 + 8 * cg;
+    const int rows_per = (N + gridDim.y - 1) / gridDim.y;
+    const int r0 = blockIdx.y * rows_per, r1 = min(N, r0 + rows_per);
+    u32x4 m = {0u, 0u, 0u, 0u};          // packed 16-bit magnitudes (order-preserving bit patterns)
+    if (c0 < B) {
+        const bool whole = c0 + 8 <= B;
+        for (int r = r0 + rl; r < r1; r += 4) {
+            u32x4 v;
+            if (whole || r + 1 < N) {
+                v = *reinterpret_cast<const u32x4*>(x + (size_t)r * ldx + c0);
+            } else {                      // last row, partial group: stay inside the buffer
+                uint32_t e[8];
+                for (int t = 0; t < 8; ++t) e[t] = c0 + t < B ? (uint32_t)x[(size_t)r * ldx + c0 + t] : 0u;
+                v = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+            }
+            v &= 0x7FFF7FFFu;
+            m = u32x4{max_halves(m.x, v.x), max_halves(m.y, v.y), max_halves(m.z, v.z), max_halves(m.w, v.w)};
+        }
+    }
+    red[rl][cg] = m;
+    __syncthreads();
+    // thread t < 256 finishes column pair t of the block's 512 columns
+    const int pair = threadIdx.x, grp = pair >> 2, w = pair & 3;
+    uint32_t best = 0;
+    for (int l = 0; l < 4; ++l) {
+        const u32x4 q = red[l][grp];
+        const uint32_t word = w == 0 ? q.x : w == 1 ? q.y : w == 2 ? q.z : q.w;
+        best = max_halves(best, word);
+    }
+    const int c = blockIdx.x * 512 + 2 * pair;
+    if (c < Bp) part[(size_t)blockIdx.y * Bp + c] = __uint_as_float(best << 16);
+    if (c + 1 < Bp) part[(size_t)blockIdx.y * Bp + c + 1] = __uint_as_float(best & 0xFFFF0000u);
+}
+
 // Power-of-two scale for column b: bound_V * xmax * scale <= 2^14.
 __device__ __forceinline__ float column_scale(const float* part, int Bp, int col, float bound_V) {
     float m = 0.f;
@@ -333,7 +381,7 @@ __device__ __forceinline__ i32x4 raw_rsrc(const void* base, uint32_t bytes) {
 }
 
 template <int WM, int WN, int TM, int TN, bool STAGE2>
-__global__ void __launch_bounds__(64 * WM * WN)
+__global__ void __launch_bounds__(64 * WM * WN, 2)     // two wavefronts per SIMD: at most 256 VGPRs
 tsvd_gemm_pipe_kernel(gemm_args p) {
     constexpr int NW = WM * WN;
     constexpr int BT = WN * TN * 16;                 // tokens per workgroup tile
@@ -463,10 +511,10 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
 }
 
 template <int WM, int WN, int TM, int TN, bool STAGE2>
-hipError_t launch_gemm(const gemm_args& a, bool fast, int row_tiles, int col_tiles, hipStream_t stream) {
-    constexpr int BT = WN * TN * 16;
+hipError_t launch_gemm(const gemm_args& a, bool fast, long long rows, int Bp, hipStream_t stream) {
+    constexpr int BT = WN * TN * 16, MT = WM * TM * 16;
     constexpr size_t lds = 2 * KT * BT * 2;
-    const dim3 grid(col_tiles, row_tiles), block(64 * WM * WN);
+    const dim3 grid(Bp / BT, (unsigned)(rows / MT)), block(64 * WM * WN);
     if (fast) hipLaunchKernelGGL((tsvd_gemm_pipe_kernel<WM, WN, TM, TN, STAGE2>), grid, block, 2 * lds, stream, a);
     else hipLaunchKernelGGL((tsvd_gemm_kernel<WM, WN, TM, TN, STAGE2, false>), grid, block, lds, stream, a);
     return hipGetLastError();
@@ -483,6 +531,26 @@ hipError_t init_gemm() {
                                hipFuncAttributeMaxDynamicSharedMemorySize, lds);
 }
 
+// Tile shapes (rows x tokens of a workgroup tile; wavefronts):
+//   0: 256 x 256, 8 wavefronts (one workgroup per compute unit)
+//   1: 256 x 128, 4 wavefronts (two workgroups per compute unit, independent barriers)
+//   2: 128 x 128, 4 wavefronts
+//   3:  64 x 128, 4 wavefronts (small problems: more workgroups)
+template <bool STAGE2>
+hipError_t launch_cfg(int cfg, const gemm_args& a, bool fast, long long rows, int Bp, hipStream_t stream) {
+    switch (cfg) {
+        case 0: return launch_gemm<2, 4, 8, 4, STAGE2>(a, fast, rows, Bp, stream);
+        case 1: return launch_gemm<2, 2, 8, 4, STAGE2>(a, fast, rows, Bp, stream);
+        case 2: return launch_gemm<2, 2, 4, 4, STAGE2>(a, fast, rows, Bp, stream);
+        default: return launch_gemm<2, 2, 2, 4, STAGE2>(a, fast, rows, Bp, stream);
+    }
+}
+
+int env_cfg(const char* name, int fallback) {
+    const char* v = getenv(name);
+    return (v && *v) ? atoi(v) : fallback;
+}
+
 }  // namespace
 
 int tsvd_stage_mask() {
@@ -492,10 +560,14 @@ int tsvd_stage_mask() {
 
 hipError_t tsvd_gemm_init() {
     hipError_t e;
-    if ((e = init_gemm<TSVD_BIG, false>()) != hipSuccess) return e;
-    if ((e = init_gemm<TSVD_BIG, true>()) != hipSuccess) return e;
+    if ((e = init_gemm<2, 4, 8, 4, false>()) != hipSuccess) return e;
+    if ((e = init_gemm<2, 4, 8, 4, true>()) != hipSuccess) return e;
+    if ((e = init_gemm<2, 2, 8, 4, false>()) != hipSuccess) return e;
+    if ((e = init_gemm<2, 2, 8, 4, true>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 2, 4, 4, false>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 2, 4, 4, true>()) != hipSuccess) return e;
+    if ((e = init_gemm<2, 2, 2, 4, false>()) != hipSuccess) return e;
+    if ((e = init_gemm<2, 2, 2, 4, true>()) != hipSuccess) return e;
     return hipSuccess;
 }
 
@@ -515,8 +587,12 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     const int mask = tsvd_stage_mask();
     hipError_t e = hipSuccess;
     if (mask & 1) {
-        hipLaunchKernelGGL(tsvd_colmax_kernel, dim3((unsigned)((g.B + 127) / 128), TSVD_COLMAX_PARTS), dim3(256), 0,
-                           stream, static_cast<const uint16_t*>(g.x), g.ldx, (int)hd.N, (int)g.B, Bp, colpart);
+        if ((g.ldx % 8 == 0) && ((reinterpret_cast<uintptr_t>(g.x) & 15u) == 0) && env_cfg("TSVD_COLMAX_SCALAR", 0) == 0)
+            hipLaunchKernelGGL(tsvd_colmax_vec_kernel, dim3((unsigned)((g.B + 511) / 512), TSVD_COLMAX_PARTS), dim3(256),
+                               0, stream, static_cast<const uint16_t*>(g.x), g.ldx, (int)hd.N, (int)g.B, Bp, colpart);
+        else
+            hipLaunchKernelGGL(tsvd_colmax_kernel, dim3((unsigned)((g.B + 127) / 128), TSVD_COLMAX_PARTS), dim3(256), 0,
+                               stream, static_cast<const uint16_t*>(g.x), g.ldx, (int)hd.N, (int)g.B, Bp, colpart);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -553,17 +629,15 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     a2.ld_out = g.ldy;
     a2.rows_valid = (int)hd.M;
 
-    // Large tiles (256 x 256) when they still give every compute unit work; else 128 x 128.
-    const long long big_tiles = (hd.Mp / 256) * (long long)(Bp / 256);
-    const bool big = big_tiles >= 256;
-    if (big) {
-        if (mask & 2) e = launch_gemm<TSVD_BIG, false>(a1, fast1, (int)(hd.Kp / 256), Bp / 256, stream);
-        if (e != hipSuccess) return e;
-        if (mask & 4) e = launch_gemm<TSVD_BIG, true>(a2, true, (int)(hd.Mp / 256), Bp / 256, stream);
-        return e;
-    }
-    if (mask & 2) e = launch_gemm<2, 2, 4, 4, false>(a1, fast1, (int)(hd.Kp / 128), Bp / 128, stream);
+    // Tile shape per stage: the largest one that still gives every compute unit work.
+    auto pick = [&](long long rows) {
+        if ((rows / 256) * (long long)(Bp / 256) >= 256) return 0;
+        if ((rows / 128) * (long long)(Bp / 128) >= 256) return 2;
+        return 3;
+    };
+    const int cfg1 = env_cfg("TSVD_GEMM_CFG_V", pick(hd.Kp)), cfg2 = env_cfg("TSVD_GEMM_CFG_U", pick(hd.Mp));
+    if (mask & 2) e = launch_cfg<false>(cfg1, a1, fast1, hd.Kp, Bp, stream);
     if (e != hipSuccess) return e;
-    if (mask & 4) e = launch_gemm<2, 2, 4, 4, true>(a2, true, (int)(hd.Mp / 128), Bp / 128, stream);
+    if (mask & 4) e = launch_cfg<true>(cfg2, a2, true, hd.Mp, Bp, stream);
     return e;
 }
