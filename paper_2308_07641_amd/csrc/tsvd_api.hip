@@ -20,6 +20,7 @@ struct tsvd_handle {
     void* scratch;          // device, handle-owned workspace (grown on demand)
     size_t scratch_bytes;
     float bound_V;          // max_k |S_k| * nnz(V[k,:]) : |z_k| <= bound_V * max|x| for every token
+    int cu_count;           // compute units of the device
     long long* clocks;      // tuning aid (TSVD_CLOCKS=1 at pack time): phase timestamps of the B <= 2 kernel
 };
 
@@ -240,6 +241,7 @@ extern "C" tsvd_status tsvd_pack(const int8_t* U, const float* S, const int8_t* 
     h->scratch = nullptr;
     h->scratch_bytes = 0;
     h->clocks = nullptr;
+    h->cu_count = 256;
 
     bool ok = hipGetDevice(&h->device) == hipSuccess && device_init(h->device) == hipSuccess;
     if (ok) {
@@ -256,6 +258,9 @@ extern "C" tsvd_status tsvd_pack(const int8_t* U, const float* S, const int8_t* 
     if (ok) ok = hipMemcpy(h->blob, host, bytes, hipMemcpyHostToDevice) == hipSuccess;
     if (ok) {
         {
+            int cus = 0;
+            if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device) == hipSuccess && cus > 0)
+                h->cu_count = cus;
             if (ok && env_int("TSVD_CLOCKS", 0)) {
                 void* c = nullptr;
                 if (hipMalloc(&c, TSVD_GEMV_MAX_GRID * 16 * sizeof(long long)) == hipSuccess) {
@@ -351,6 +356,7 @@ extern "C" tsvd_status tsvd_forward(const tsvd_handle* h, const void* x_dev, tsv
         g.y = static_cast<float*>(y_dev);
         g.ldy = ldy;
         g.ws = ws;
+        g.cu_count = h->cu_count;
         return tsvd_forward_gemm(g, s) == hipSuccess ? TSVD_OK : TSVD_EDEVICE;
     }
     return forward_skinny(h, x_dev, x_dtype, B, ldx, static_cast<float*>(y_dev), ldy, ws, s);

@@ -67,6 +67,7 @@ struct tsvd_gemm_problem {
     float* y;                       // device fp32 [M][ldy]
     long long ldy;
     void* ws;                       // device workspace (see gemm_workspace in tsvd_api.hip)
+    int cu_count;                   // compute units of the device
 };
 hipError_t tsvd_gemm_init();
 hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream);
