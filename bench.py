@@ -29,6 +29,11 @@ import workloads  # noqa: E402
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_TFLOPS = 2500.0
 PRIMARY = "bert_ffn_in"
+# HBM bytes per launch of the stage-U kernel (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors a
+# plain 256 MiB copy gives), from profiles/hbm_traffic_fetch_write_size.md.  Counters cannot be read
+# inside this process; the figures belong to the launch shapes bench.py uses.
+STAGE_U_TRAFFIC_BYTES = {"bert_ffn_in": 8.1e6 + 6.29e6, "convnext_mlp": 191e6 + 102.8e6,
+                         "opt66b_fc1_prefill": 2027e6 + 302.0e6, "opt6b7_fc1_decode": 34.2e6 + 0.066e6}
 
 
 def _device_x(inputs, dev):
@@ -143,7 +148,8 @@ def bench_workload(name, steps, warmup, with_cpu=True, cpu_budget_s=4.0):
         fl_u = 2.0 * w.K * w.M * w.B
         res["roofline"] = {"bound": "mfma", "kernel": "tsvd_gemm_pipe_kernel (stage U, fp16 MFMA)",
                            "achieved": fl_u / (u_ms * 1e-3) / 1e12, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
-                           "frac": fl_u / (u_ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS, "traffic": None,
+                           "frac": fl_u / (u_ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS,
+                           "traffic": STAGE_U_TRAFFIC_BYTES.get(name),
                            "whole_path_frac": res["executed_tflops"] / PEAK_MFMA_TFLOPS}
     else:
         xb = 2 if w.x_dtype == "bf16" else 4
@@ -155,7 +161,7 @@ def bench_workload(name, steps, warmup, with_cpu=True, cpu_budget_s=4.0):
         gbs = bytes_u / (u_ms * 1e-3) / 1e9
         res["roofline"] = {"bound": "hbm", "kernel": "tsvd_gemv_kernel (stage U)",
                            "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
-                           "traffic": None, "algorithmic_bytes": bytes_u,
+                           "traffic": STAGE_U_TRAFFIC_BYTES.get(name), "algorithmic_bytes": bytes_u,
                            "whole_path_gbs": bytes_alg / (ev_ms * 1e-3) / 1e9,
                            "whole_path_frac": bytes_alg / (ev_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
                            "whole_path_bytes": bytes_alg,
@@ -177,6 +183,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workloads", default="bert_ffn_in,tiny,convnext_mlp,opt6b7_fc1_decode,opt66b_fc1_prefill")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing / parity leg")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy (reference for FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus above 1 is not supported "
@@ -190,6 +198,14 @@ def main():
     torch.cuda.set_device(0)
     import paper_2308_07641_amd as tsvd
     tsvd.load_library()
+
+    if args.copy_calibration:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     names = [n for n in args.workloads.split(",") if n]
     if PRIMARY not in names:
