@@ -204,7 +204,7 @@ bool use_gemm(const tsvd_handle*, int64_t B, tsvd_dtype x_dtype) {
 size_t gemm_workspace(const tsvd_handle* h, int64_t B) {
     // partial column maxima [PARTS][Bp] fp32, then Z as fp16 [Kp][Bp]
     const int64_t Bp = tsvd_round_up(B, 256);
-    return round256((size_t)TSVD_COLMAX_PARTS * Bp * 4) + round256((size_t)h->hd.Kp * (size_t)Bp * 2);
+    return round256((size_t)(TSVD_COLMAX_PARTS + 1) * Bp * 4) + round256((size_t)h->hd.Kp * (size_t)Bp * 2);
 }
 
 }  // namespace
@@ -357,6 +357,7 @@ extern "C" tsvd_status tsvd_forward(const tsvd_handle* h, const void* x_dev, tsv
         g.ldy = ldy;
         g.ws = ws;
         g.cu_count = h->cu_count;
+        g.clocks = h->clocks;
         return tsvd_forward_gemm(g, s) == hipSuccess ? TSVD_OK : TSVD_EDEVICE;
     }
     return forward_skinny(h, x_dev, x_dtype, B, ldx, static_cast<float*>(y_dev), ldy, ws, s);

@@ -131,17 +131,13 @@ tsvd_colmax_vec_kernel(const uint16_t* __restrict__ x, long long ldx, int N, int
     }
 }
 
-// Power-of-two scale for column b: bound_V * xmax * scale <= 2^14.
-__device__ __forceinline__ float column_scale(const float* part, int Bp, int col, float bound_V) {
-    float m = 0.f;
-#pragma unroll
-    for (int p = 0; p < TSVD_COLMAX_PARTS; ++p) m = fmaxf(m, part[(size_t)p * Bp + col]);
+// Exponent e of the power-of-two scale for a column whose largest |x| is m:
+// bound_V * m * 2^e <= 2^14.
+__device__ __forceinline__ int scale_exponent(float m, float bound_V) {
     const float bound = bound_V * m;
     int ex = 0;
     if (bound > 0.f && bound < 3.0e38f) (void)frexpf(bound, &ex);   // bound < 2^ex
-    int e = 14 - ex;
-    e = max(-110, min(110, e));
-    return ldexpf(1.0f, e);
+    return max(-110, min(110, 14 - ex));
 }
 
 // ---- kernels 1 and 2 ------------------------------------------------------------------------
@@ -155,21 +151,26 @@ struct gemm_args {
     unsigned act_bytes;       // size of the activation buffer (buffer-load range check)
     unsigned tile_bytes;      // size of the packed tiles
     const float* S;           // stage 1: row scales
-    const float* colpart;     // column maxima partials [PARTS][Bp]
+    const float* colpart;     // column maxima: partials [PARTS][Bp], then the final row [Bp]
+    float* colmax;            // the final row (stage 1 writes it, stage 2 reads it)
     int Bp;
     float bound_V;
     void* out;                // stage 1: fp16 [Kp][Bp];  stage 2: fp32 [M][ldy]
     long long ld_out;
     int rows_valid;           // stage 2: M
+    long long* clocks;        // tuning aid: phase timestamps per workgroup (stage 1: 0..7, stage 2: 8..15), or null
 };
 
+// One MFMA block with the activations as the row operand and the decoded weights as the column
+// operand: the result block is [16 tokens][16 weight rows], so a lane (i, g) ends up with the four
+// adjacent tokens 4 g .. 4 g + 3 of weight row i, which it can store with one vector write.
 template <bool STAGE2>
-__device__ __forceinline__ f32x4 mfma16(const u32x4& a, const u32x2& blo, const u32x2& bhi, f32x4 acc) {
-    u32x4 b = {blo.x, blo.y, bhi.x, bhi.y};
+__device__ __forceinline__ f32x4 mfma16(const u32x4& w, const u32x2& xlo, const u32x2& xhi, f32x4 acc) {
+    u32x4 x = {xlo.x, xlo.y, xhi.x, xhi.y};
     if constexpr (STAGE2)
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), acc, 0, 0, 0);
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, w), __builtin_bit_cast(f16x8, x), acc, 0, 0, 0);
     else
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, x), acc, 0, 0, 0);
 }
 
 __device__ __forceinline__ u32x2 lds_tr(const unsigned char* lds_byte_ptr) {
@@ -178,15 +179,41 @@ __device__ __forceinline__ u32x2 lds_tr(const unsigned char* lds_byte_ptr) {
     return __builtin_bit_cast(u32x2, r);
 }
 
-// D block layout: lane holds column i, rows 4 g + v.  col0 = first token of this wavefront's tile.
+// Per-token factors of a workgroup tile, computed once per workgroup into LDS before the main
+// loop (thread t owns token b0 + t): stage 1 multiplies by scale / 2, stage 2 by 1 / (2 scale); the
+// 2 undoes the +-2 of the decoded weights.  Stage 1 reduces the partial maxima and (first row of
+// workgroups only) publishes the final maximum for stage 2.
+template <bool STAGE2>
+__device__ __forceinline__ float load_column_max(const gemm_args& p, int col) {
+    if constexpr (STAGE2) return p.colmax[col];
+    float m = 0.f;
+#pragma unroll
+    for (int q = 0; q < TSVD_COLMAX_PARTS; ++q) m = fmaxf(m, p.colpart[(size_t)q * p.Bp + col]);
+    return m;
+}
+template <bool STAGE2>
+__device__ __forceinline__ void publish_column_factor(const gemm_args& p, int col, float m, float* cs_lds, int t) {
+    const int e = scale_exponent(m, p.bound_V);
+    cs_lds[t] = ldexpf(1.0f, STAGE2 ? -e - 1 : e - 1);
+    if constexpr (!STAGE2)
+        if (blockIdx.y == 0) p.colmax[col] = m;
+}
+
+// Result block layout: lane (i, g) holds token i, weight rows 4 g + v.
 template <int TM, int TN, bool STAGE2>
-__device__ __forceinline__ void gemm_epilogue(const gemm_args& p, f32x4 (&acc)[TM][TN], int strip0, int col0, int i, int g) {
+__device__ __forceinline__ void gemm_epilogue(const gemm_args& p, f32x4 (&acc)[TM][TN], int strip0, int b0, int tok0,
+                                              const float* cs_lds, int i, int g) {
     float cs[TN];
 #pragma unroll
-    for (int b = 0; b < TN; ++b) {
-        const int col = col0 + b * 16 + i;
-        const float sc = column_scale(p.colpart, p.Bp, col, p.bound_V);
-        cs[b] = STAGE2 ? 0.5f / sc : 0.5f * sc;      // powers of two: exact
+    for (int b = 0; b < TN; ++b) cs[b] = cs_lds[tok0 + b * 16 + i];
+    const int col0 = b0 + tok0;
+    float sr[TM][4];
+    if constexpr (!STAGE2) {
+#pragma unroll
+        for (int a = 0; a < TM; ++a) {
+            const f32x4 q = *reinterpret_cast<const f32x4*>(p.S + (strip0 + a) * 16 + 4 * g);
+            sr[a][0] = q.x; sr[a][1] = q.y; sr[a][2] = q.z; sr[a][3] = q.w;
+        }
     }
 #pragma unroll
     for (int a = 0; a < TM; ++a) {
@@ -203,13 +230,9 @@ __device__ __forceinline__ void gemm_epilogue(const gemm_args& p, f32x4 (&acc)[T
                     }
                 }
             } else {
-                const float sr = p.S[row];            // zero beyond K: padded rows of Z become 0
-                _Float16* dst = static_cast<_Float16*>(p.out) + (size_t)row * p.ld_out;
+                _Float16* dst = static_cast<_Float16*>(p.out) + (size_t)row * p.ld_out;   // zero S beyond K
 #pragma unroll
-                for (int b = 0; b < TN; ++b) {
-                    const int col = col0 + b * 16 + i;
-                    dst[col] = (_Float16)((acc[a][b][v] * sr) * cs[b]);
-                }
+                for (int b = 0; b < TN; ++b) dst[col0 + b * 16 + i] = (_Float16)((acc[a][b][v] * sr[a][v]) * cs[b]);
             }
         }
     }
@@ -238,7 +261,9 @@ tsvd_gemm_kernel(gemm_args p) {
     constexpr int CPT = CHUNKS / THREADS;            // chunks per thread
     constexpr int STAGE_BYTES = KT * ROWB;
     static_assert(CHUNKS % THREADS == 0 && THREADS % CPR == 0, "tile/threads mismatch");
-    extern __shared__ __align__(16) unsigned char smem[];   // 2 stages x KT x ROWB
+    static_assert(BT <= THREADS, "one thread per token of the tile");
+    extern __shared__ __align__(16) unsigned char smem[];   // 2 stages x KT x ROWB, then BT column factors
+    float* cs_lds = reinterpret_cast<float*>(smem + 2 * STAGE_BYTES);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / WN, wn = wave - wm * WN;
@@ -345,6 +370,8 @@ tsvd_gemm_kernel(gemm_args p) {
     uint32_t w0[TM], w1[TM];
     load_x(0);
     load_w(0, w0);
+    if (threadIdx.x < BT)
+        publish_column_factor<STAGE2>(p, b0 + threadIdx.x, load_column_max<STAGE2>(p, b0 + threadIdx.x), cs_lds, threadIdx.x);
     store_x(0);
     __syncthreads();
 
@@ -365,7 +392,7 @@ tsvd_gemm_kernel(gemm_args p) {
         __syncthreads();
     }
 
-    gemm_epilogue<TM, TN, STAGE2>(p, acc, strip0, b0 + wn * TN * 16, i, g);
+    gemm_epilogue<TM, TN, STAGE2>(p, acc, strip0, b0, wn * TN * 16, cs_lds, i, g);
 }
 
 // ---- pipelined variant (activation rows 16-byte aligned) -----------------------------------
@@ -404,7 +431,9 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
     constexpr int SPW = SLOTS / NW;                  // slots per wavefront
     constexpr int RPS = 64 / CPR;                    // rows per slot
     static_assert(SLOTS % NW == 0 && 64 % CPR == 0, "tile/wavefront mismatch");
-    extern __shared__ __align__(16) unsigned char smem[];   // 4 stages x KT x ROWB
+    static_assert(BT <= 64 * NW, "one thread per token of the tile");
+    extern __shared__ __align__(16) unsigned char smem[];   // 4 stages x KT x ROWB, then BT column factors
+    float* cs_lds = reinterpret_cast<float*>(smem + 4 * STAGE_BYTES);
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave / WN, wn = wave - wm * WN;
@@ -412,6 +441,11 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
     const int b0 = blockIdx.x * BT;
     const int strip0 = (blockIdx.y * WM + wm) * TM;
     const int nstages = p.nkt * (256 / KT), last = nstages - 1;
+    auto tick = [&](int n) {
+        const unsigned wg = blockIdx.y * gridDim.x + blockIdx.x;
+        if (p.clocks && threadIdx.x == 0 && wg < TSVD_GEMV_MAX_GRID) p.clocks[wg * 16 + (STAGE2 ? 8 : 0) + n] = wall_clock64();
+    };
+    tick(0);
 
     // (row and swizzle conventions: see tsvd_gemm_kernel)
     const int rsel = i >> 2;
@@ -497,13 +531,25 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
     // A pair of stages (128 contraction indices, two LDS buffers) per barrier.  While pair P is
     // multiplied, the activations of pair P + 1 stream into the other two buffers and its code
     // words into registers.  Loads past the last pair re-read it (never used).
+    // The compiler does not see the LDS-bound loads, so its own wait for a code word (counted in
+    // the loads it knows) would also drain the activation loads issued after it.  Using the words
+    // right after the explicit wait makes the compiler place its wait there, where it costs nothing.
+    auto touch = [&](const u32x2 (&w)[TM]) {
+#pragma unroll
+        for (int a = 0; a < TM; ++a) asm volatile("" :: "v"(w[a].x), "v"(w[a].y));
+    };
     const int npairs = nstages / 2, lastp = npairs - 1;
     u32x2 wa[TM], wb[TM];
+    float cmax = 0.f;
+    if (threadIdx.x < BT) cmax = load_column_max<STAGE2>(p, b0 + threadIdx.x);
     load_w(0, wa);
     issue_x(0, 0);
     issue_x(1, 1);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    touch(wa);
+    if (threadIdx.x < BT) publish_column_factor<STAGE2>(p, b0 + threadIdx.x, cmax, cs_lds, threadIdx.x);
     __syncthreads();
+    tick(2);
 
     for (int P = 0; P < npairs; P += 2) {           // one 256-wide tile of codes per iteration
         int nx = min(P + 1, lastp);
@@ -512,6 +558,7 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
         issue_x(2 * nx + 1, 3);
         compute_pair(0, wa);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // pair P + 1 has landed (this wavefront's part)
+        touch(wb);
         __syncthreads();
 
         nx = min(P + 2, lastp);
@@ -520,46 +567,309 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
         issue_x(2 * nx + 1, 1);
         compute_pair(2, wb);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        touch(wa);
         __syncthreads();
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no LDS write may still be in flight at exit
+    tick(3);
 
-    gemm_epilogue<TM, TN, STAGE2>(p, acc, strip0, b0 + wn * TN * 16, i, g);
+    gemm_epilogue<TM, TN, STAGE2>(p, acc, strip0, b0, wn * TN * 16, cs_lds, i, g);
+    tick(5);
+}
+
+// ---- ring variant for small problems -----------------------------------------------------------
+// A launch with about one workgroup per compute unit cannot lean on other workgroups to hide its
+// waits, and the 256-row tiles above would leave most compute units idle.  This variant uses small
+// tiles and EVERY load of its main loop is a buffer_load ... lds issued from inline assembly: a ring
+// of NPB slots, each holding one pair of stages (128 contraction indices) of activations AND the
+// code words of the workgroup's rows for that pair; pair P + NPB - 1 is requested before pair P is
+// multiplied, and the only waits are the explicit s_waitcnt vmcnt(n) below (vector-memory results
+// return in issue order: the loads of the NPB - 2 younger pairs may still be in flight).  Code
+// words take 4 bytes per lane per load (word j of strip s of the pair lands at
+// s * 512 + j * 256 + 4 lane).  Measured on MI355X: small tiles are bound by what one compute unit
+// can move (64 bytes per clock into LDS, 128 bytes per clock out of it), not by memory latency, so
+// a ring of 3 that lets two or three workgroups share a compute unit beats rings of 4 to 6 with one.
+//
+// FUSEMAX (stage 1 only): the workgroup streams all N rows of its token columns through LDS anyway,
+// so it also computes their largest magnitudes there; no column-maximum kernel runs before it.
+__device__ __forceinline__ void buf_load32_to_lds(i32x4 rsrc, uint32_t lds_addr, int voff, int soff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                 :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+}
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+    uint32_t r;
+    asm("v_pk_max_u16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+template <int WM, int WN, int TM, int TN, bool STAGE2, int NPB, bool FUSEMAX>
+__global__ void __launch_bounds__(64 * WM * WN)
+tsvd_gemm_ring_kernel(gemm_args p) {
+    constexpr int NW = WM * WN, THREADS = 64 * NW;
+    constexpr int BT = WN * TN * 16;                 // tokens per workgroup tile
+    constexpr int ROWB = BT * 2;                     // bytes per LDS row
+    constexpr int NBLK = BT / 16;                    // 32-byte blocks per LDS row
+    constexpr int CPR = BT / 8;                      // 16-byte chunks per LDS row
+    constexpr int STAGE_BYTES = KT * ROWB;
+    constexpr int SLOTS = STAGE_BYTES / 1024;        // 1-KiB pieces per stage
+    constexpr int SPW = SLOTS / NW;                  // pieces per wavefront and stage
+    constexpr int RPS = 64 / CPR;                    // rows per piece
+    constexpr int WSTRIPS = WM * TM;                 // 16-row strips of the workgroup tile
+    constexpr int W_BYTES = WSTRIPS * 512;           // code words of one pair
+    constexpr int WOPS = WSTRIPS * 2 / NW;           // code-word loads per wavefront and pair
+    constexpr int SLOT_BYTES = 2 * STAGE_BYTES + W_BYTES;
+    constexpr int OPS = 2 * SPW + WOPS;              // loads per wavefront and pair
+    constexpr int CPT = KT * CPR / THREADS;          // FUSEMAX: chunks per thread and stage
+    static_assert(SLOTS % NW == 0 && 64 % CPR == 0 && (WSTRIPS * 2) % NW == 0 && NW % 2 == 0, "tile/wavefront mismatch");
+    static_assert(NPB >= 2 && (NPB - 2) * OPS <= 63, "ring too deep for the load counter");
+    static_assert(BT <= THREADS && (KT * CPR) % THREADS == 0 && THREADS % CPR == 0, "one thread per token of the tile");
+    static_assert(!(FUSEMAX && STAGE2), "column maxima belong to stage 1");
+    static_assert(THREADS * 16 <= NPB * SLOT_BYTES, "the reduction reuses the ring");
+    extern __shared__ __align__(16) unsigned char smem[];   // NPB slots, then BT column factors
+    float* cs_lds = reinterpret_cast<float*>(smem + NPB * SLOT_BYTES);
+
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave / WN, wn = wave - wm * WN;
+    const int i = lane & 15, g = lane >> 4;
+    const int b0 = blockIdx.x * BT;
+    const int strip0 = (blockIdx.y * WM + wm) * TM;
+    const int npairs = p.nkt * 2, lastp = npairs - 1;
+    auto tick = [&](int n) {
+        const unsigned wg = blockIdx.y * gridDim.x + blockIdx.x;
+        if (p.clocks && threadIdx.x == 0 && wg < TSVD_GEMV_MAX_GRID) p.clocks[wg * 16 + (STAGE2 ? 8 : 0) + n] = wall_clock64();
+    };
+    tick(0);
+
+    // (row and swizzle conventions: see tsvd_gemm_kernel)
+    const int rsel = i >> 2;
+    const int tr_row = 32 * (g & 1) + 16 * (g >> 1) + (rsel >> 1) + 4 * (rsel & 1);
+    const int f_lane = ((((tr_row & 1) << 1) | ((tr_row >> 2) & 1) | (((tr_row >> 4) & 3) << 2))) & (NBLK - 1);
+    int lds_rd[TN];
+#pragma unroll
+    for (int b = 0; b < TN; ++b) lds_rd[b] = tr_row * ROWB + (((wn * TN + b) ^ f_lane) * 32) + (i & 3) * 8;
+
+    int x_voff[SPW];
+#pragma unroll
+    for (int c = 0; c < SPW; ++c) {
+        const int r = (c * NW + wave) * RPS + lane / CPR, pc = lane % CPR;
+        const int f = (((r & 1) << 1) | ((r >> 2) & 1) | (((r >> 4) & 3) << 2)) & (NBLK - 1);
+        const int lc = (((pc >> 1) ^ f) << 1) | (pc & 1);
+        x_voff[c] = (64 * (r >> 5) + (r & 31)) * (int)p.ld * 2 + (b0 + lc * 8) * 2;
+    }
+    const i32x4 act_rsrc = raw_rsrc(p.act, p.act_bytes);
+    const i32x4 w_rsrc = raw_rsrc(p.tiles, p.tile_bytes);
+    typedef __attribute__((address_space(3))) unsigned char* lds_byte_ptr;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_byte_ptr)smem;
+    const uint32_t lds_x = lds_base + wave * 1024;
+    // code-word load q of this wavefront: strip q * (NW / 2) + (wave >> 1), word wave & 1
+    const uint32_t lds_w = lds_base + 2 * STAGE_BYTES + (wave >> 1) * 512 + (wave & 1) * 256;
+    const int w_voff = lane * 16 + (wave & 1) * 4;
+    const int w_soff0 = (blockIdx.y * WSTRIPS + (wave >> 1)) * p.nkt * 1024;
+
+    f32x4 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    auto issue = [&](int pair, int slot) {
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+            const int stage = 2 * pair + st;
+            const int soff = (256 * (stage >> 2) + 128 * ((stage >> 1) & 1) + 32 * (stage & 1)) * (int)p.ld * 2;
+#pragma unroll
+            for (int c = 0; c < SPW; ++c)
+                buf_load128_to_lds(act_rsrc, lds_x + slot * SLOT_BYTES + st * STAGE_BYTES + c * NW * 1024, x_voff[c], soff);
+        }
+        const int soff_w = w_soff0 + (pair >> 1) * 1024 + (pair & 1) * 8;
+#pragma unroll
+        for (int q = 0; q < WOPS; ++q)
+            buf_load32_to_lds(w_rsrc, lds_w + slot * SLOT_BYTES + q * (NW / 2) * 512, w_voff, soff_w + q * (NW / 2) * p.nkt * 1024);
+    };
+    auto load_frags = [&](const unsigned char* stage_base, int hh, u32x2 (&lo)[TN], u32x2 (&hi)[TN]) {
+        const unsigned char* base = stage_base + hh * 8 * ROWB;
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+            lo[b] = lds_tr(base + lds_rd[b]);
+            hi[b] = lds_tr(base + lds_rd[b] + 2 * ROWB);
+        }
+    };
+    auto mfma_step = [&](const u32x2 (&w)[TM], int word, int hh, const u32x2 (&lo)[TN], const u32x2 (&hi)[TN]) {
+#pragma unroll
+        for (int a = 0; a < TM; ++a) {
+            const uint32_t ww = word == 0 ? w[a].x : w[a].y;
+            u32x4 av;
+            if (hh == 0) av = u32x4{TSVD_DEC(ww, 0), TSVD_DEC(ww, 2), TSVD_DEC(ww, 4), TSVD_DEC(ww, 6)};
+            else         av = u32x4{TSVD_DEC(ww, 1), TSVD_DEC(ww, 3), TSVD_DEC(ww, 5), ww & 0xC000C000u};
+#pragma unroll
+            for (int b = 0; b < TN; ++b) acc[a][b] = mfma16<STAGE2>(av, lo[b], hi[b], acc[a][b]);
+        }
+    };
+    auto compute_pair = [&](int slot) {
+        const unsigned char* base = smem + slot * SLOT_BYTES;
+        u32x2 w[TM];
+        const uint32_t* wl = reinterpret_cast<const uint32_t*>(base + 2 * STAGE_BYTES) + wm * TM * 128 + lane;
+#pragma unroll
+        for (int a = 0; a < TM; ++a) w[a] = u32x2{wl[a * 128], wl[a * 128 + 64]};
+        u32x2 f0lo[TN], f0hi[TN], f1lo[TN], f1hi[TN];
+        load_frags(base, 0, f0lo, f0hi);
+        load_frags(base, 1, f1lo, f1hi);
+        mfma_step(w, 0, 0, f0lo, f0hi);
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(base + STAGE_BYTES, 0, f0lo, f0hi);
+        mfma_step(w, 0, 1, f1lo, f1hi);
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(base + STAGE_BYTES, 1, f1lo, f1hi);
+        mfma_step(w, 1, 0, f0lo, f0hi);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_step(w, 1, 1, f1lo, f1hi);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // FUSEMAX: thread t scans logical chunk t % CPR (8 tokens) of rows t / CPR + c * (THREADS / CPR)
+    u32x4 cm = {0u, 0u, 0u, 0u};                      // packed 16-bit magnitudes (order-preserving bit patterns)
+    int lds_sc[FUSEMAX ? CPT : 1];
+    if constexpr (FUSEMAX) {
+        const int ch = threadIdx.x % CPR;
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) {
+            const int r = threadIdx.x / CPR + c * (THREADS / CPR);
+            const int f = (((r & 1) << 1) | ((r >> 2) & 1) | (((r >> 4) & 3) << 2)) & (NBLK - 1);
+            lds_sc[c] = r * ROWB + (((ch >> 1) ^ f) * 32) + (ch & 1) * 16;
+        }
+    }
+    auto scan_pair = [&](int slot) {
+        if constexpr (FUSEMAX) {
+#pragma unroll
+            for (int st = 0; st < 2; ++st)
+#pragma unroll
+                for (int c = 0; c < CPT; ++c) {
+                    u32x4 v = *reinterpret_cast<const u32x4*>(smem + slot * SLOT_BYTES + st * STAGE_BYTES + lds_sc[c]);
+                    v &= 0x7FFF7FFFu;
+                    cm = u32x4{pk_max_u16(cm.x, v.x), pk_max_u16(cm.y, v.y), pk_max_u16(cm.z, v.z), pk_max_u16(cm.w, v.w)};
+                }
+        }
+    };
+
+    float cmax = 0.f;
+    if constexpr (!FUSEMAX)
+        if (threadIdx.x < BT) cmax = load_column_max<STAGE2>(p, b0 + threadIdx.x);
+#pragma unroll
+    for (int j = 0; j < NPB - 1; ++j) issue(min(j, lastp), j);
+    tick(1);
+    wait_vmcnt<(NPB - 2) * OPS>();                    // pair 0 has landed (this wavefront's part)
+    if constexpr (!FUSEMAX)
+        if (threadIdx.x < BT) publish_column_factor<STAGE2>(p, b0 + threadIdx.x, cmax, cs_lds, threadIdx.x);
+    __syncthreads();
+    tick(2);
+
+    for (int P = 0; P < npairs; P += NPB) {
+#pragma unroll
+        for (int j = 0; j < NPB; ++j) {
+            if (P + j >= npairs) break;
+            issue(min(P + j + NPB - 1, lastp), (j + NPB - 1) % NPB);   // into the slot multiplied last time
+            compute_pair(j);
+            scan_pair(j);
+            wait_vmcnt<(NPB - 2) * OPS>();            // pair P + j + 1 has landed
+            __syncthreads();
+        }
+    }
+    wait_vmcnt<0>();                                  // no LDS write may still be in flight
+    tick(3);
+
+    if constexpr (FUSEMAX) {
+        __syncthreads();                              // every wavefront's loads have landed: the ring is free
+        u32x4* red = reinterpret_cast<u32x4*>(smem);  // [THREADS / CPR][CPR]
+        red[threadIdx.x] = cm;
+        __syncthreads();
+        if (threadIdx.x < BT) {
+            const uint16_t* r16 = reinterpret_cast<const uint16_t*>(smem) + threadIdx.x;   // chunk t / 8, element t % 8
+            uint32_t best = 0;
+#pragma unroll 4
+            for (int l = 0; l < THREADS / CPR; ++l) best = max(best, (uint32_t)r16[l * CPR * 8]);
+            publish_column_factor<false>(p, b0 + threadIdx.x, __uint_as_float(best << 16), cs_lds, threadIdx.x);
+        }
+        __syncthreads();
+    }
+    tick(4);
+
+    gemm_epilogue<TM, TN, STAGE2>(p, acc, strip0, b0, wn * TN * 16, cs_lds, i, g);
+    tick(5);
 }
 
 template <int WM, int WN, int TM, int TN, bool STAGE2>
 hipError_t launch_gemm(const gemm_args& a, bool fast, long long rows, int Bp, hipStream_t stream) {
     constexpr int BT = WN * TN * 16, MT = WM * TM * 16;
-    constexpr size_t lds = 2 * KT * BT * 2;
+    constexpr size_t lds = 2 * KT * BT * 2, cs = BT * 4;      // two stages; the column factors
     const dim3 grid(Bp / BT, (unsigned)(rows / MT)), block(64 * WM * WN);
-    if (fast) hipLaunchKernelGGL((tsvd_gemm_pipe_kernel<WM, WN, TM, TN, STAGE2>), grid, block, 2 * lds, stream, a);
-    else hipLaunchKernelGGL((tsvd_gemm_kernel<WM, WN, TM, TN, STAGE2, false>), grid, block, lds, stream, a);
+    if (fast) hipLaunchKernelGGL((tsvd_gemm_pipe_kernel<WM, WN, TM, TN, STAGE2>), grid, block, 2 * lds + cs, stream, a);
+    else hipLaunchKernelGGL((tsvd_gemm_kernel<WM, WN, TM, TN, STAGE2, false>), grid, block, lds + cs, stream, a);
     return hipGetLastError();
 }
 
 template <int WM, int WN, int TM, int TN, bool STAGE2>
 hipError_t init_gemm() {
     constexpr int BT = WN * TN * 16;
-    constexpr int lds = 2 * KT * BT * 2;
+    constexpr int lds = 2 * KT * BT * 2, cs = BT * 4;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_pipe_kernel<WM, WN, TM, TN, STAGE2>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 2 * lds);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 2 * lds + cs);
     if (e != hipSuccess) return e;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_kernel<WM, WN, TM, TN, STAGE2, false>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+                               hipFuncAttributeMaxDynamicSharedMemorySize, lds + cs);
+}
+
+template <int WM, int WN, int TM, int TN, bool STAGE2, int NPB, bool FUSEMAX>
+constexpr int ring_lds_bytes() {
+    return NPB * (2 * KT * (WN * TN * 16) * 2 + WM * TM * 512) + WN * TN * 16 * 4;
+}
+template <int WM, int WN, int TM, int TN, bool STAGE2, int NPB, bool FUSEMAX>
+hipError_t launch_ring(const gemm_args& a, long long rows, int Bp, hipStream_t stream) {
+    constexpr int BT = WN * TN * 16, MT = WM * TM * 16;
+    constexpr size_t lds = ring_lds_bytes<WM, WN, TM, TN, STAGE2, NPB, FUSEMAX>();
+    const dim3 grid(Bp / BT, (unsigned)(rows / MT)), block(64 * WM * WN);
+    hipLaunchKernelGGL((tsvd_gemm_ring_kernel<WM, WN, TM, TN, STAGE2, NPB, FUSEMAX>), grid, block, lds, stream, a);
+    return hipGetLastError();
+}
+template <int WM, int WN, int TM, int TN, int NPB>
+hipError_t init_ring() {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, ring_lds_bytes<WM, WN, TM, TN, true, NPB, false>());
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, false, NPB, false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, ring_lds_bytes<WM, WN, TM, TN, false, NPB, false>());
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, false, NPB, true>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, ring_lds_bytes<WM, WN, TM, TN, false, NPB, true>());
 }
 
 // Tile shapes (rows x tokens of a workgroup tile; wavefronts):
 //   0: 256 x 256, 8 wavefronts (one workgroup per compute unit)
 //   1: 256 x 128, 4 wavefronts (two workgroups per compute unit, independent barriers)
 //   2: 128 x 128, 4 wavefronts
-//   3:  64 x 128, 4 wavefronts (small problems: more workgroups)
-template <bool STAGE2>
+//   3:  64 x 128, 4 wavefronts
+// Ring-kernel shapes for launches of few workgroups (4 wavefronts, ring of 3 pairs of stages, small
+// enough in LDS and registers for two to three workgroups per compute unit):
+//   14:  64 x 64     15: 128 x 64
+#define TSVD_RING_SHAPES(X) X(14, 2, 2, 2, 2, 3) X(15, 2, 2, 4, 2, 3)
+constexpr bool is_ring(int cfg) { return cfg >= 10; }
+
+template <bool STAGE2, bool FUSEMAX>
 hipError_t launch_cfg(int cfg, const gemm_args& a, bool fast, long long rows, int Bp, hipStream_t stream) {
     switch (cfg) {
         case 0: return launch_gemm<2, 4, 8, 4, STAGE2>(a, fast, rows, Bp, stream);
         case 1: return launch_gemm<2, 2, 8, 4, STAGE2>(a, fast, rows, Bp, stream);
         case 2: return launch_gemm<2, 2, 4, 4, STAGE2>(a, fast, rows, Bp, stream);
-        default: return launch_gemm<2, 2, 2, 4, STAGE2>(a, fast, rows, Bp, stream);
+        case 3: return launch_gemm<2, 2, 2, 4, STAGE2>(a, fast, rows, Bp, stream);
+#define TSVD_RING_CASE(id, wm, wn, tm, tn, npb) \
+        case id: return launch_ring<wm, wn, tm, tn, STAGE2, npb, FUSEMAX>(a, rows, Bp, stream);
+        TSVD_RING_SHAPES(TSVD_RING_CASE)
+#undef TSVD_RING_CASE
+        default: return hipErrorInvalidValue;
     }
 }
 
@@ -585,6 +895,10 @@ hipError_t tsvd_gemm_init() {
     if ((e = init_gemm<2, 2, 4, 4, true>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 2, 2, 4, false>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 2, 2, 4, true>()) != hipSuccess) return e;
+#define TSVD_RING_INIT(id, wm, wn, tm, tn, npb) \
+    if ((e = init_ring<wm, wn, tm, tn, npb>()) != hipSuccess) return e;
+    TSVD_RING_SHAPES(TSVD_RING_INIT)
+#undef TSVD_RING_INIT
     return hipSuccess;
 }
 
@@ -592,28 +906,13 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     const tsvd_blob_header& hd = *g.hd;
     const int Bp = (int)tsvd_round_up(g.B, 256);
     float* colpart = static_cast<float*>(g.ws);
-    const size_t part_bytes = (((size_t)TSVD_COLMAX_PARTS * Bp * 4) + 255) & ~(size_t)255;
+    const size_t part_bytes = (((size_t)(TSVD_COLMAX_PARTS + 1) * Bp * 4) + 255) & ~(size_t)255;
     _Float16* Z = reinterpret_cast<_Float16*>(static_cast<uint8_t*>(g.ws) + part_bytes);
 
     // buffer loads address with 32-bit byte offsets
     if ((size_t)hd.N * g.ldx * 2 >= (1ull << 31) || (size_t)hd.Kp * Bp * 2 >= (1ull << 31) ||
         (size_t)hd.Mp * hd.Kp / 4 >= (1ull << 31) || (size_t)hd.Kp * hd.Np / 4 >= (1ull << 31))
         return hipErrorInvalidValue;
-    // Profiling switch: TSVD_STAGE_MASK selects the kernels to launch (1 column maxima,
-    // 2 stage V, 4 stage U; default all).  Skipped kernels leave the workspace as it is.
-    const int mask = tsvd_stage_mask();
-    hipError_t e = hipSuccess;
-    if (mask & 1) {
-        if ((g.ldx % 8 == 0) && ((reinterpret_cast<uintptr_t>(g.x) & 15u) == 0) && env_cfg("TSVD_COLMAX_SCALAR", 0) == 0)
-            hipLaunchKernelGGL(tsvd_colmax_vec_kernel, dim3((unsigned)((g.B + 127) / 128), TSVD_COLMAX_PARTS), dim3(256),
-                               0, stream, static_cast<const uint16_t*>(g.x), g.ldx, (int)hd.N, (int)g.B, Bp, colpart);
-        else
-            hipLaunchKernelGGL(tsvd_colmax_kernel, dim3((unsigned)((g.B + 127) / 128), TSVD_COLMAX_PARTS), dim3(256), 0,
-                               stream, static_cast<const uint16_t*>(g.x), g.ldx, (int)hd.N, (int)g.B, Bp, colpart);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
-
     gemm_args a1;
     a1.tiles = reinterpret_cast<const uint32_t*>(g.blob + hd.off_V);
     a1.nkt = (int)(hd.Np / 256);
@@ -626,11 +925,13 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     a1.tile_bytes = (unsigned)((size_t)hd.Kp * hd.Np / 4);
     a1.S = reinterpret_cast<const float*>(g.blob + hd.off_S);
     a1.colpart = colpart;
+    a1.colmax = colpart + (size_t)TSVD_COLMAX_PARTS * Bp;
     a1.Bp = Bp;
     a1.bound_V = g.bound_V;
     a1.out = Z;
     a1.ld_out = Bp;
     a1.rows_valid = (int)hd.Kp;
+    a1.clocks = g.clocks;
 
     gemm_args a2 = a1;
     a2.tiles = reinterpret_cast<const uint32_t*>(g.blob + hd.off_U);
@@ -648,20 +949,40 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
 
     // Tile shape per stage.  Large problems: 256 x 256 (one workgroup per compute unit) or 256 x 128
     // (two, with independent barriers), whichever needs less time in rounds of workgroups; the
-    // second is about 3 % more efficient per unit of work on MI355X.  Small problems: the shape that
-    // still gives most compute units a workgroup.
-    auto pick = [&](long long rows) {
+    // second is about 3 % more efficient per unit of work on MI355X.  Small problems (fewer
+    // workgroups than about 1.5 per compute unit even at 256 x 128): the ring kernel, 128 x 64 tiles
+    // if they still give every compute unit a workgroup, else 64 x 64; it needs 16-byte-aligned rows.
+    auto pick = [&](long long rows, bool aligned) {
         const long long cus = g.cu_count;
         const long long t0 = (rows / 256) * (Bp / 256), t1 = (rows / 256) * (Bp / 128), t2 = (rows / 128) * (Bp / 128);
         if (2 * t1 >= 3 * cus) {
             const double c0 = (double)((t0 + cus - 1) / cus) / 0.97, c1 = 0.5 * (double)((t1 + cus - 1) / cus);
             return c0 < c1 ? 0 : 1;
         }
-        return t2 >= cus ? 2 : 3;
+        if (!aligned) return t2 >= cus ? 2 : 3;
+        return (rows / 128) * (Bp / 64) >= cus ? 15 : 14;
     };
-    const int cfg1 = env_cfg("TSVD_GEMM_CFG_V", pick(hd.Kp)), cfg2 = env_cfg("TSVD_GEMM_CFG_U", pick(hd.Mp));
-    if (mask & 2) e = launch_cfg<false>(cfg1, a1, fast1, hd.Kp, Bp, stream);
+    int cfg1 = env_cfg("TSVD_GEMM_CFG_V", pick(hd.Kp, fast1)), cfg2 = env_cfg("TSVD_GEMM_CFG_U", pick(hd.Mp, true));
+    if (is_ring(cfg1) && !fast1) cfg1 = 3;
+    const bool fuse = is_ring(cfg1) && env_cfg("TSVD_FUSEMAX", 1) != 0;
+
+    // Profiling switch: TSVD_STAGE_MASK selects the kernels to launch (1 column maxima,
+    // 2 stage V, 4 stage U; default all).  Skipped kernels leave the workspace as it is.
+    const int mask = tsvd_stage_mask();
+    hipError_t e = hipSuccess;
+    if ((mask & 1) && !fuse) {
+        if (fast1 && env_cfg("TSVD_COLMAX_SCALAR", 0) == 0)
+            hipLaunchKernelGGL(tsvd_colmax_vec_kernel, dim3((unsigned)((g.B + 127) / 128), TSVD_COLMAX_PARTS), dim3(256),
+                               0, stream, static_cast<const uint16_t*>(g.x), g.ldx, (int)hd.N, (int)g.B, Bp, colpart);
+        else
+            hipLaunchKernelGGL(tsvd_colmax_kernel, dim3((unsigned)((g.B + 127) / 128), TSVD_COLMAX_PARTS), dim3(256), 0,
+                               stream, static_cast<const uint16_t*>(g.x), g.ldx, (int)hd.N, (int)g.B, Bp, colpart);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (mask & 2) e = fuse ? launch_cfg<false, true>(cfg1, a1, fast1, hd.Kp, Bp, stream)
+                           : launch_cfg<false, false>(cfg1, a1, fast1, hd.Kp, Bp, stream);
     if (e != hipSuccess) return e;
-    if (mask & 4) e = launch_cfg<true>(cfg2, a2, true, hd.Mp, Bp, stream);
+    if (mask & 4) e = launch_cfg<true, false>(cfg2, a2, true, hd.Mp, Bp, stream);
     return e;
 }

@@ -68,6 +68,7 @@ struct tsvd_gemm_problem {
     long long ldy;
     void* ws;                       // device workspace (see gemm_workspace in tsvd_api.hip)
     int cu_count;                   // compute units of the device
+    long long* clocks;              // optional tuning aid: [TSVD_GEMV_MAX_GRID][16] phase timestamps, or null
 };
 hipError_t tsvd_gemm_init();
 hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream);

@@ -67,6 +67,44 @@ def test_random_instances_within_tolerance(tsvd, M, N, K, B, p0, x_dtype):
     assert rel_err(y, ref) <= TOL[x_dtype]
 
 
+# ---- every tile shape of the batched kernels on the same ragged instance.  The library reads
+# ---- these tuning switches per call; normally the shape follows from the problem size, so the
+# ---- small test instances above would never reach the large-tile kernels.
+TILE_SHAPES = [0, 1, 2, 3, 14, 15]
+
+
+@pytest.mark.parametrize("fuse", ["1", "0"])
+@pytest.mark.parametrize("cfg", TILE_SHAPES)
+def test_every_tile_shape_batched(tsvd, cfg, fuse, monkeypatch):
+    monkeypatch.setenv("TSVD_GEMM_CFG_V", str(cfg))
+    monkeypatch.setenv("TSVD_GEMM_CFG_U", str(cfg))
+    monkeypatch.setenv("TSVD_FUSEMAX", fuse)
+    print(f"case tile shape {cfg} fuse {fuse}", flush=True)
+    i = workloads.make_integer_inputs(300, 200, 520, 300, 0.5, "bf16", seed=4242 + cfg)
+    ref = oracle.forward(i.U, i.S, i.V, i.X)
+    y, h = run_forward(i)
+    tsvd.tsvd_free(h)
+    assert not np.isnan(y).any()
+    assert np.array_equal(y, ref)
+    j = workloads.make_inputs(515, 300, 777, 600, 0.6, 0.02, "bf16", seed=777 + cfg)
+    ref = oracle.forward(j.U, j.S, j.V, j.X)
+    y, h = run_forward(j)
+    tsvd.tsvd_free(h)
+    assert not np.isnan(y).any()
+    assert rel_err(y, ref) <= TOL["bf16"]
+
+
+def test_larger_small_problem_uses_wider_ring_tiles(tsvd):
+    """2048 x 1024 outputs per stage: enough 128 x 64 tiles for every compute unit."""
+    i = workloads.make_inputs(2048, 512, 2048, 1024, 0.6, 0.02, "bf16", seed=31337)
+    print("case rand M=2048 N=512 K=2048 B=1024 bf16", flush=True)
+    ref = oracle.forward(i.U, i.S, i.V, i.X)
+    y, h = run_forward(i)
+    tsvd.tsvd_free(h)
+    assert not np.isnan(y).any()
+    assert rel_err(y, ref) <= TOL["bf16"]
+
+
 def test_activation_scale_extremes_batched(tsvd):
     """The fp16 intermediate of the batched path is rescaled per token: tokens of very different
     magnitude in one batch must all keep their accuracy (error measured per token here)."""
