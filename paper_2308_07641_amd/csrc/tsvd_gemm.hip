@@ -607,10 +607,13 @@ __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
-template <int WM, int WN, int TM, int TN, bool STAGE2, int NPB, bool FUSEMAX>
-__global__ void __launch_bounds__(64 * WM * WN)
+// KG > 1 splits the contraction over KG groups of WM x WN wavefronts: a ring slot then holds KG
+// pairs, group kg multiplies pair KG * P + kg, and the groups' accumulators are added through LDS
+// at the end.  Same tile and same bytes moved, KG times the wavefronts to hide waits with.
+template <int WM, int WN, int TM, int TN, bool STAGE2, int NPB, bool FUSEMAX, int KG>
+__global__ void __launch_bounds__(64 * WM * WN * KG)
 tsvd_gemm_ring_kernel(gemm_args p) {
-    constexpr int NW = WM * WN, THREADS = 64 * NW;
+    constexpr int NWG = WM * WN, NW = NWG * KG, THREADS = 64 * NW;
     constexpr int BT = WN * TN * 16;                 // tokens per workgroup tile
     constexpr int ROWB = BT * 2;                     // bytes per LDS row
     constexpr int NBLK = BT / 16;                    // 32-byte blocks per LDS row
@@ -622,23 +625,26 @@ tsvd_gemm_ring_kernel(gemm_args p) {
     constexpr int WSTRIPS = WM * TM;                 // 16-row strips of the workgroup tile
     constexpr int W_BYTES = WSTRIPS * 512;           // code words of one pair
     constexpr int WOPS = WSTRIPS * 2 / NW;           // code-word loads per wavefront and pair
-    constexpr int SLOT_BYTES = 2 * STAGE_BYTES + W_BYTES;
-    constexpr int OPS = 2 * SPW + WOPS;              // loads per wavefront and pair
+    constexpr int SUB_BYTES = 2 * STAGE_BYTES + W_BYTES;   // one pair
+    constexpr int SLOT_BYTES = KG * SUB_BYTES;       // one ring slot: KG pairs
+    constexpr int OPS = KG * (2 * SPW + WOPS);       // loads per wavefront and slot
     constexpr int CPT = KT * CPR / THREADS;          // FUSEMAX: chunks per thread and stage
     static_assert(SLOTS % NW == 0 && 64 % CPR == 0 && (WSTRIPS * 2) % NW == 0 && NW % 2 == 0, "tile/wavefront mismatch");
     static_assert(NPB >= 2 && (NPB - 2) * OPS <= 63, "ring too deep for the load counter");
     static_assert(BT <= THREADS && (KT * CPR) % THREADS == 0 && THREADS % CPR == 0, "one thread per token of the tile");
     static_assert(!(FUSEMAX && STAGE2), "column maxima belong to stage 1");
-    static_assert(THREADS * 16 <= NPB * SLOT_BYTES, "the reduction reuses the ring");
+    static_assert(THREADS * 16 <= NPB * SLOT_BYTES && (KG - 1) * NWG * 64 * TM * TN * 16 <= NPB * SLOT_BYTES, "the reductions reuse the ring");
+    static_assert(KG == 1 || KG == 2, "pairs per tile of codes");
     extern __shared__ __align__(16) unsigned char smem[];   // NPB slots, then BT column factors
     float* cs_lds = reinterpret_cast<float*>(smem + NPB * SLOT_BYTES);
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wm = wave / WN, wn = wave - wm * WN;
+    const int kg = wave / NWG, w2 = wave - kg * NWG;
+    const int wm = w2 / WN, wn = w2 - wm * WN;
     const int i = lane & 15, g = lane >> 4;
     const int b0 = blockIdx.x * BT;
     const int strip0 = (blockIdx.y * WM + wm) * TM;
-    const int npairs = p.nkt * 2, lastp = npairs - 1;
+    const int nslots = p.nkt * 2 / KG, lasts = nslots - 1;   // ring slots to go through
     auto tick = [&](int n) {
         const unsigned wg = blockIdx.y * gridDim.x + blockIdx.x;
         if (p.clocks && threadIdx.x == 0 && wg < TSVD_GEMV_MAX_GRID) p.clocks[wg * 16 + (STAGE2 ? 8 : 0) + n] = wall_clock64();
@@ -677,19 +683,30 @@ tsvd_gemm_ring_kernel(gemm_args p) {
 #pragma unroll
         for (int b = 0; b < TN; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    auto issue = [&](int pair, int slot) {
+    // The loads of a ring slot (all wavefronts load for all KG pairs), in four parts (part < 0: all
+    // of them): a wavefront's load occupies the address unit for many cycles, so inside the loop
+    // they are spread over the four MFMA steps of the pair being multiplied.
+    auto issue = [&](int sl, int slot, int part) {
 #pragma unroll
-        for (int st = 0; st < 2; ++st) {
-            const int stage = 2 * pair + st;
-            const int soff = (256 * (stage >> 2) + 128 * ((stage >> 1) & 1) + 32 * (stage & 1)) * (int)p.ld * 2;
+        for (int s = 0; s < KG; ++s) {
+            const int pair = KG * sl + s;
 #pragma unroll
-            for (int c = 0; c < SPW; ++c)
-                buf_load128_to_lds(act_rsrc, lds_x + slot * SLOT_BYTES + st * STAGE_BYTES + c * NW * 1024, x_voff[c], soff);
+            for (int st = 0; st < 2; ++st) {
+                const int stage = 2 * pair + st;
+                const int soff = (256 * (stage >> 2) + 128 * ((stage >> 1) & 1) + 32 * (stage & 1)) * (int)p.ld * 2;
+#pragma unroll
+                for (int c = 0; c < SPW; ++c)
+                    if (part < 0 || (((s * 2 + st) * SPW + c) & 3) == part)
+                        buf_load128_to_lds(act_rsrc, lds_x + slot * SLOT_BYTES + s * SUB_BYTES + st * STAGE_BYTES + c * NW * 1024,
+                                           x_voff[c], soff);
+            }
+            const int soff_w = w_soff0 + (pair >> 1) * 1024 + (pair & 1) * 8;
+#pragma unroll
+            for (int q = 0; q < WOPS; ++q)
+                if (part < 0 || ((KG * 2 * SPW + s * WOPS + q) & 3) == part)
+                    buf_load32_to_lds(w_rsrc, lds_w + slot * SLOT_BYTES + s * SUB_BYTES + q * (NW / 2) * 512, w_voff,
+                                      soff_w + q * (NW / 2) * p.nkt * 1024);
         }
-        const int soff_w = w_soff0 + (pair >> 1) * 1024 + (pair & 1) * 8;
-#pragma unroll
-        for (int q = 0; q < WOPS; ++q)
-            buf_load32_to_lds(w_rsrc, lds_w + slot * SLOT_BYTES + q * (NW / 2) * 512, w_voff, soff_w + q * (NW / 2) * p.nkt * 1024);
     };
     auto load_frags = [&](const unsigned char* stage_base, int hh, u32x2 (&lo)[TN], u32x2 (&hi)[TN]) {
         const unsigned char* base = stage_base + hh * 8 * ROWB;
@@ -710,8 +727,9 @@ tsvd_gemm_ring_kernel(gemm_args p) {
             for (int b = 0; b < TN; ++b) acc[a][b] = mfma16<STAGE2>(av, lo[b], hi[b], acc[a][b]);
         }
     };
-    auto compute_pair = [&](int slot) {
-        const unsigned char* base = smem + slot * SLOT_BYTES;
+    // this wavefront's pair of ring slot `slot`, while the loads of slot index next_sl go out
+    auto compute_pair = [&](int slot, int next_sl, int next_slot) {
+        const unsigned char* base = smem + slot * SLOT_BYTES + kg * SUB_BYTES;
         u32x2 w[TM];
         const uint32_t* wl = reinterpret_cast<const uint32_t*>(base + 2 * STAGE_BYTES) + wm * TM * 128 + lane;
 #pragma unroll
@@ -719,14 +737,18 @@ tsvd_gemm_ring_kernel(gemm_args p) {
         u32x2 f0lo[TN], f0hi[TN], f1lo[TN], f1hi[TN];
         load_frags(base, 0, f0lo, f0hi);
         load_frags(base, 1, f1lo, f1hi);
+        issue(next_sl, next_slot, 0);
         mfma_step(w, 0, 0, f0lo, f0hi);
         __builtin_amdgcn_sched_barrier(0);
         load_frags(base + STAGE_BYTES, 0, f0lo, f0hi);
+        issue(next_sl, next_slot, 1);
         mfma_step(w, 0, 1, f1lo, f1hi);
         __builtin_amdgcn_sched_barrier(0);
         load_frags(base + STAGE_BYTES, 1, f1lo, f1hi);
+        issue(next_sl, next_slot, 2);
         mfma_step(w, 1, 0, f0lo, f0hi);
         __builtin_amdgcn_sched_barrier(0);
+        issue(next_sl, next_slot, 3);
         mfma_step(w, 1, 1, f1lo, f1hi);
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -743,16 +765,18 @@ tsvd_gemm_ring_kernel(gemm_args p) {
             lds_sc[c] = r * ROWB + (((ch >> 1) ^ f) * 32) + (ch & 1) * 16;
         }
     }
-    auto scan_pair = [&](int slot) {
+    auto scan_slot = [&](int slot) {
         if constexpr (FUSEMAX) {
 #pragma unroll
-            for (int st = 0; st < 2; ++st)
+            for (int s = 0; s < KG; ++s)
 #pragma unroll
-                for (int c = 0; c < CPT; ++c) {
-                    u32x4 v = *reinterpret_cast<const u32x4*>(smem + slot * SLOT_BYTES + st * STAGE_BYTES + lds_sc[c]);
-                    v &= 0x7FFF7FFFu;
-                    cm = u32x4{pk_max_u16(cm.x, v.x), pk_max_u16(cm.y, v.y), pk_max_u16(cm.z, v.z), pk_max_u16(cm.w, v.w)};
-                }
+                for (int st = 0; st < 2; ++st)
+#pragma unroll
+                    for (int c = 0; c < CPT; ++c) {
+                        u32x4 v = *reinterpret_cast<const u32x4*>(smem + slot * SLOT_BYTES + s * SUB_BYTES + st * STAGE_BYTES + lds_sc[c]);
+                        v &= 0x7FFF7FFFu;
+                        cm = u32x4{pk_max_u16(cm.x, v.x), pk_max_u16(cm.y, v.y), pk_max_u16(cm.z, v.z), pk_max_u16(cm.w, v.w)};
+                    }
         }
     };
 
@@ -760,22 +784,21 @@ tsvd_gemm_ring_kernel(gemm_args p) {
     if constexpr (!FUSEMAX)
         if (threadIdx.x < BT) cmax = load_column_max<STAGE2>(p, b0 + threadIdx.x);
 #pragma unroll
-    for (int j = 0; j < NPB - 1; ++j) issue(min(j, lastp), j);
+    for (int j = 0; j < NPB - 1; ++j) issue(min(j, lasts), j, -1);
     tick(1);
-    wait_vmcnt<(NPB - 2) * OPS>();                    // pair 0 has landed (this wavefront's part)
+    wait_vmcnt<(NPB - 2) * OPS>();                    // slot 0 has landed (this wavefront's part)
     if constexpr (!FUSEMAX)
         if (threadIdx.x < BT) publish_column_factor<STAGE2>(p, b0 + threadIdx.x, cmax, cs_lds, threadIdx.x);
     __syncthreads();
     tick(2);
 
-    for (int P = 0; P < npairs; P += NPB) {
+    for (int P = 0; P < nslots; P += NPB) {
 #pragma unroll
         for (int j = 0; j < NPB; ++j) {
-            if (P + j >= npairs) break;
-            issue(min(P + j + NPB - 1, lastp), (j + NPB - 1) % NPB);   // into the slot multiplied last time
-            compute_pair(j);
-            scan_pair(j);
-            wait_vmcnt<(NPB - 2) * OPS>();            // pair P + j + 1 has landed
+            if (P + j >= nslots) break;
+            compute_pair(j, min(P + j + NPB - 1, lasts), (j + NPB - 1) % NPB);   // loads go into the slot multiplied last time
+            scan_slot(j);
+            wait_vmcnt<(NPB - 2) * OPS>();            // slot P + j + 1 has landed
             __syncthreads();
         }
     }
@@ -795,6 +818,23 @@ tsvd_gemm_ring_kernel(gemm_args p) {
             publish_column_factor<false>(p, b0 + threadIdx.x, __uint_as_float(best << 16), cs_lds, threadIdx.x);
         }
         __syncthreads();
+    }
+    if constexpr (KG > 1) {
+        // group 1 hands its accumulators to group 0 through the (now free) ring: [wavefront][block][lane]
+        __syncthreads();
+        f32x4* xch = reinterpret_cast<f32x4*>(smem) + (size_t)w2 * (TM * TN * 64) + lane;
+        if (kg == 1) {
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b) xch[(a * TN + b) * 64] = acc[a][b];
+        }
+        __syncthreads();
+        if (kg != 0) return;
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b) acc[a][b] += xch[(a * TN + b) * 64];
     }
     tick(4);
 
@@ -823,28 +863,29 @@ hipError_t init_gemm() {
                                hipFuncAttributeMaxDynamicSharedMemorySize, lds + cs);
 }
 
-template <int WM, int WN, int TM, int TN, bool STAGE2, int NPB, bool FUSEMAX>
+template <int WM, int WN, int TM, int TN, int NPB, int KG>
 constexpr int ring_lds_bytes() {
-    return NPB * (2 * KT * (WN * TN * 16) * 2 + WM * TM * 512) + WN * TN * 16 * 4;
+    return NPB * KG * (2 * KT * (WN * TN * 16) * 2 + WM * TM * 512) + WN * TN * 16 * 4;
 }
-template <int WM, int WN, int TM, int TN, bool STAGE2, int NPB, bool FUSEMAX>
+template <int WM, int WN, int TM, int TN, bool STAGE2, int NPB, bool FUSEMAX, int KG>
 hipError_t launch_ring(const gemm_args& a, long long rows, int Bp, hipStream_t stream) {
     constexpr int BT = WN * TN * 16, MT = WM * TM * 16;
-    constexpr size_t lds = ring_lds_bytes<WM, WN, TM, TN, STAGE2, NPB, FUSEMAX>();
-    const dim3 grid(Bp / BT, (unsigned)(rows / MT)), block(64 * WM * WN);
-    hipLaunchKernelGGL((tsvd_gemm_ring_kernel<WM, WN, TM, TN, STAGE2, NPB, FUSEMAX>), grid, block, lds, stream, a);
+    constexpr size_t lds = ring_lds_bytes<WM, WN, TM, TN, NPB, KG>();
+    const dim3 grid(Bp / BT, (unsigned)(rows / MT)), block(64 * WM * WN * KG);
+    hipLaunchKernelGGL((tsvd_gemm_ring_kernel<WM, WN, TM, TN, STAGE2, NPB, FUSEMAX, KG>), grid, block, lds, stream, a);
     return hipGetLastError();
 }
-template <int WM, int WN, int TM, int TN, int NPB>
+template <int WM, int WN, int TM, int TN, int NPB, int KG>
 hipError_t init_ring() {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, ring_lds_bytes<WM, WN, TM, TN, true, NPB, false>());
+    constexpr int lds = ring_lds_bytes<WM, WN, TM, TN, NPB, KG>();
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false, KG>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, false, NPB, false>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, ring_lds_bytes<WM, WN, TM, TN, false, NPB, false>());
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, false, NPB, false, KG>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, false, NPB, true>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, ring_lds_bytes<WM, WN, TM, TN, false, NPB, true>());
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, false, NPB, true, KG>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, lds);
 }
 
 // Tile shapes (rows x tokens of a workgroup tile; wavefronts):
@@ -852,10 +893,11 @@ hipError_t init_ring() {
 //   1: 256 x 128, 4 wavefronts (two workgroups per compute unit, independent barriers)
 //   2: 128 x 128, 4 wavefronts
 //   3:  64 x 128, 4 wavefronts
-// Ring-kernel shapes for launches of few workgroups (4 wavefronts, ring of 3 pairs of stages, small
-// enough in LDS and registers for two to three workgroups per compute unit):
-//   14:  64 x 64     15: 128 x 64
-#define TSVD_RING_SHAPES(X) X(14, 2, 2, 2, 2, 3) X(15, 2, 2, 4, 2, 3)
+// Ring-kernel shapes for launches of few workgroups (ring of 3 or 2 slots, small enough in LDS and
+// registers for two to three workgroups per compute unit):
+//   14:  64 x 64, 4 wavefronts     15: 128 x 64, 4 wavefronts
+//   16:  64 x 64, 8 wavefronts: the contraction split over two groups of four
+#define TSVD_RING_SHAPES(X) X(14, 2, 2, 2, 2, 3, 1) X(15, 2, 2, 4, 2, 3, 1) X(16, 2, 2, 2, 2, 2, 2)
 constexpr bool is_ring(int cfg) { return cfg >= 10; }
 
 template <bool STAGE2, bool FUSEMAX>
@@ -865,8 +907,8 @@ hipError_t launch_cfg(int cfg, const gemm_args& a, bool fast, long long rows, in
         case 1: return launch_gemm<2, 2, 8, 4, STAGE2>(a, fast, rows, Bp, stream);
         case 2: return launch_gemm<2, 2, 4, 4, STAGE2>(a, fast, rows, Bp, stream);
         case 3: return launch_gemm<2, 2, 2, 4, STAGE2>(a, fast, rows, Bp, stream);
-#define TSVD_RING_CASE(id, wm, wn, tm, tn, npb) \
-        case id: return launch_ring<wm, wn, tm, tn, STAGE2, npb, FUSEMAX>(a, rows, Bp, stream);
+#define TSVD_RING_CASE(id, wm, wn, tm, tn, npb, kg) \
+        case id: return launch_ring<wm, wn, tm, tn, STAGE2, npb, FUSEMAX, kg>(a, rows, Bp, stream);
         TSVD_RING_SHAPES(TSVD_RING_CASE)
 #undef TSVD_RING_CASE
         default: return hipErrorInvalidValue;
@@ -895,8 +937,8 @@ hipError_t tsvd_gemm_init() {
     if ((e = init_gemm<2, 2, 4, 4, true>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 2, 2, 4, false>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 2, 2, 4, true>()) != hipSuccess) return e;
-#define TSVD_RING_INIT(id, wm, wn, tm, tn, npb) \
-    if ((e = init_ring<wm, wn, tm, tn, npb>()) != hipSuccess) return e;
+#define TSVD_RING_INIT(id, wm, wn, tm, tn, npb, kg) \
+    if ((e = init_ring<wm, wn, tm, tn, npb, kg>()) != hipSuccess) return e;
     TSVD_RING_SHAPES(TSVD_RING_INIT)
 #undef TSVD_RING_INIT
     return hipSuccess;
@@ -951,7 +993,8 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     // (two, with independent barriers), whichever needs less time in rounds of workgroups; the
     // second is about 3 % more efficient per unit of work on MI355X.  Small problems (fewer
     // workgroups than about 1.5 per compute unit even at 256 x 128): the ring kernel, 128 x 64 tiles
-    // if they still give every compute unit a workgroup, else 64 x 64; it needs 16-byte-aligned rows.
+    // if they still give every compute unit a workgroup, else 64 x 64 with the contraction split
+    // over two groups of wavefronts; it needs 16-byte-aligned rows.
     auto pick = [&](long long rows, bool aligned) {
         const long long cus = g.cu_count;
         const long long t0 = (rows / 256) * (Bp / 256), t1 = (rows / 256) * (Bp / 128), t2 = (rows / 128) * (Bp / 128);
@@ -960,7 +1003,7 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
             return c0 < c1 ? 0 : 1;
         }
         if (!aligned) return t2 >= cus ? 2 : 3;
-        return (rows / 128) * (Bp / 64) >= cus ? 15 : 14;
+        return (rows / 128) * (Bp / 64) >= cus ? 15 : 16;
     };
     int cfg1 = env_cfg("TSVD_GEMM_CFG_V", pick(hd.Kp, fast1)), cfg2 = env_cfg("TSVD_GEMM_CFG_U", pick(hd.Mp, true));
     if (is_ring(cfg1) && !fast1) cfg1 = 3;

@@ -70,7 +70,7 @@ def test_random_instances_within_tolerance(tsvd, M, N, K, B, p0, x_dtype):
 # ---- every tile shape of the batched kernels on the same ragged instance.  The library reads
 # ---- these tuning switches per call; normally the shape follows from the problem size, so the
 # ---- small test instances above would never reach the large-tile kernels.
-TILE_SHAPES = [0, 1, 2, 3, 14, 15]
+TILE_SHAPES = [0, 1, 2, 3, 14, 15, 16]
 
 
 @pytest.mark.parametrize("fuse", ["1", "0"])
