@@ -140,6 +140,20 @@ __device__ __forceinline__ int scale_exponent(float m, float bound_V) {
     return max(-110, min(110, 14 - ex));
 }
 
+// XOR swizzle of the activation tiles in LDS: row r stores its logical 32-byte block j at block
+// j ^ swizzle(r).  One transposed read (ds_read_b64_tr_b16) touches rows
+// 32 (g & 1) + 16 (g >> 1) + {0, 4, 1, 5} (+ a constant) for lane groups g = 0..3, 32 bytes of each.
+// The 64-bank LDS serves half a wavefront (two lane groups, eight such segments = 256 bytes) per
+// cycle, so those eight rows need eight different bank groups: row bits 0 and 2 tell the four
+// rows of a lane group apart and bit 4 ^ bit 5 tells apart the lane groups of either half
+// (and of the even/odd pairing).  With 128-byte rows (4 blocks) bit 0 already selects the bank
+// half, so two swizzle bits suffice; 64-byte rows (2 blocks) cannot avoid two-way conflicts.
+template <int NBLK>
+__device__ __forceinline__ constexpr int swizzle(int r) {
+    const int q = ((r >> 4) ^ (r >> 5)) & 1;
+    return NBLK >= 8 ? (((r >> 2) & 1) | ((r & 1) << 1) | (q << 2)) : NBLK == 4 ? (((r >> 2) & 1) | (q << 1)) : ((r >> 2) & 1);
+}
+
 // ---- kernels 1 and 2 ------------------------------------------------------------------------
 struct gemm_args {
     const uint32_t* tiles;    // packed A: [strips][nkt][256 words]
@@ -280,7 +294,7 @@ tsvd_gemm_kernel(gemm_args p) {
     // o = {0,4,1,5} (first four operand elements) and o + 2 (last four): 16 rows with 16 distinct f.
     const int rsel = i >> 2;
     const int tr_row = 32 * (g & 1) + 16 * (g >> 1) + (rsel >> 1) + 4 * (rsel & 1);
-    const int f_lane = ((((tr_row & 1) << 1) | ((tr_row >> 2) & 1) | (((tr_row >> 4) & 3) << 2))) & (NBLK - 1);
+    const int f_lane = swizzle<NBLK>(tr_row);
     int lds_rd[TN];                                   // byte offset of this lane's transposed reads
 #pragma unroll
     for (int b = 0; b < TN; ++b) lds_rd[b] = tr_row * ROWB + (((wn * TN + b) ^ f_lane) * 32) + (i & 3) * 8;
@@ -291,7 +305,7 @@ tsvd_gemm_kernel(gemm_args p) {
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {
         const int r = r_first + c * (THREADS / CPR);
-        const int f = (((r & 1) << 1) | ((r >> 2) & 1) | (((r >> 4) & 3) << 2)) & (NBLK - 1);
+        const int f = swizzle<NBLK>(r);
         lds_wr[c] = r * ROWB + (((ch >> 1) ^ f) * 32) + (ch & 1) * 16;
         x_voff[c] = (64 * (r >> 5) + (r & 31)) * (int)p.ld * 2 + (b0 + ch * 8) * 2;
     }
@@ -450,7 +464,7 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
     // (row and swizzle conventions: see tsvd_gemm_kernel)
     const int rsel = i >> 2;
     const int tr_row = 32 * (g & 1) + 16 * (g >> 1) + (rsel >> 1) + 4 * (rsel & 1);
-    const int f_lane = ((((tr_row & 1) << 1) | ((tr_row >> 2) & 1) | (((tr_row >> 4) & 3) << 2))) & (NBLK - 1);
+    const int f_lane = swizzle<NBLK>(tr_row);
     int lds_rd[TN];
 #pragma unroll
     for (int b = 0; b < TN; ++b) lds_rd[b] = tr_row * ROWB + (((wn * TN + b) ^ f_lane) * 32) + (i & 3) * 8;
@@ -461,7 +475,7 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
 #pragma unroll
     for (int c = 0; c < SPW; ++c) {
         const int r = (c * NW + wave) * RPS + lane / CPR, pc = lane % CPR;
-        const int f = (((r & 1) << 1) | ((r >> 2) & 1) | (((r >> 4) & 3) << 2)) & (NBLK - 1);
+        const int f = swizzle<NBLK>(r);
         const int lc = (((pc >> 1) ^ f) << 1) | (pc & 1);
         x_voff[c] = (64 * (r >> 5) + (r & 31)) * (int)p.ld * 2 + (b0 + lc * 8) * 2;
     }
@@ -654,7 +668,7 @@ tsvd_gemm_ring_kernel(gemm_args p) {
     // (row and swizzle conventions: see tsvd_gemm_kernel)
     const int rsel = i >> 2;
     const int tr_row = 32 * (g & 1) + 16 * (g >> 1) + (rsel >> 1) + 4 * (rsel & 1);
-    const int f_lane = ((((tr_row & 1) << 1) | ((tr_row >> 2) & 1) | (((tr_row >> 4) & 3) << 2))) & (NBLK - 1);
+    const int f_lane = swizzle<NBLK>(tr_row);
     int lds_rd[TN];
 #pragma unroll
     for (int b = 0; b < TN; ++b) lds_rd[b] = tr_row * ROWB + (((wn * TN + b) ^ f_lane) * 32) + (i & 3) * 8;
@@ -663,7 +677,7 @@ tsvd_gemm_ring_kernel(gemm_args p) {
 #pragma unroll
     for (int c = 0; c < SPW; ++c) {
         const int r = (c * NW + wave) * RPS + lane / CPR, pc = lane % CPR;
-        const int f = (((r & 1) << 1) | ((r >> 2) & 1) | (((r >> 4) & 3) << 2)) & (NBLK - 1);
+        const int f = swizzle<NBLK>(r);
         const int lc = (((pc >> 1) ^ f) << 1) | (pc & 1);
         x_voff[c] = (64 * (r >> 5) + (r & 31)) * (int)p.ld * 2 + (b0 + lc * 8) * 2;
     }
@@ -687,6 +701,7 @@ tsvd_gemm_ring_kernel(gemm_args p) {
     // of them): a wavefront's load occupies the address unit for many cycles, so inside the loop
     // they are spread over the four MFMA steps of the pair being multiplied.
     auto issue = [&](int sl, int slot, int part) {
+        if (sl > lasts) return;                      // nothing left to fetch (uniform)
 #pragma unroll
         for (int s = 0; s < KG; ++s) {
             const int pair = KG * sl + s;
@@ -761,7 +776,7 @@ tsvd_gemm_ring_kernel(gemm_args p) {
 #pragma unroll
         for (int c = 0; c < CPT; ++c) {
             const int r = threadIdx.x / CPR + c * (THREADS / CPR);
-            const int f = (((r & 1) << 1) | ((r >> 2) & 1) | (((r >> 4) & 3) << 2)) & (NBLK - 1);
+            const int f = swizzle<NBLK>(r);
             lds_sc[c] = r * ROWB + (((ch >> 1) ^ f) * 32) + (ch & 1) * 16;
         }
     }
@@ -784,9 +799,10 @@ tsvd_gemm_ring_kernel(gemm_args p) {
     if constexpr (!FUSEMAX)
         if (threadIdx.x < BT) cmax = load_column_max<STAGE2>(p, b0 + threadIdx.x);
 #pragma unroll
-    for (int j = 0; j < NPB - 1; ++j) issue(min(j, lasts), j, -1);
+    for (int j = 0; j < NPB - 1; ++j) issue(j, j, -1);
     tick(1);
-    wait_vmcnt<(NPB - 2) * OPS>();                    // slot 0 has landed (this wavefront's part)
+    if (NPB - 2 <= lasts) wait_vmcnt<(NPB - 2) * OPS>();   // slot 0 has landed (this wavefront's part)
+    else wait_vmcnt<0>();
     if constexpr (!FUSEMAX)
         if (threadIdx.x < BT) publish_column_factor<STAGE2>(p, b0 + threadIdx.x, cmax, cs_lds, threadIdx.x);
     __syncthreads();
@@ -796,9 +812,12 @@ tsvd_gemm_ring_kernel(gemm_args p) {
 #pragma unroll
         for (int j = 0; j < NPB; ++j) {
             if (P + j >= nslots) break;
-            compute_pair(j, min(P + j + NPB - 1, lasts), (j + NPB - 1) % NPB);   // loads go into the slot multiplied last time
+            compute_pair(j, P + j + NPB - 1, (j + NPB - 1) % NPB);   // loads go into the slot multiplied last time
             scan_slot(j);
-            wait_vmcnt<(NPB - 2) * OPS>();            // slot P + j + 1 has landed
+            // slot P + j + 1 has landed: all but the loads of the NPB - 2 younger slots are back.  Near
+            // the end fewer slots are requested, so everything outstanding is awaited.
+            if (P + j + NPB - 1 <= lasts) wait_vmcnt<(NPB - 2) * OPS>();
+            else wait_vmcnt<0>();
             __syncthreads();
         }
     }
