@@ -32,8 +32,8 @@ PRIMARY = "bert_ffn_in"
 # HBM bytes per launch of the stage-U kernel (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors a
 # plain 256 MiB copy gives), from profiles/hbm_traffic_fetch_write_size.md.  Counters cannot be read
 # inside this process; the figures belong to the launch shapes bench.py uses.
-STAGE_U_TRAFFIC_BYTES = {"bert_ffn_in": 8.1e6 + 6.29e6, "convnext_mlp": 191e6 + 102.8e6,
-                         "opt66b_fc1_prefill": 2027e6 + 302.0e6, "opt6b7_fc1_decode": 34.2e6 + 0.066e6}
+STAGE_U_TRAFFIC_BYTES = {"bert_ffn_in": 11.1e6 + 6.29e6, "convnext_mlp": 186e6 + 102.8e6,
+                         "opt66b_fc1_prefill": 2021e6 + 302.0e6, "opt6b7_fc1_decode": 34.2e6 + 0.066e6}
 
 
 def _device_x(inputs, dev):
@@ -58,6 +58,19 @@ def _timed(fn, steps, warmup):
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+
+def _stage_u_kernel_name(tsvd, handle, B):
+    """Name of the batched stage-U kernel the library picks (its tile-shape rule, asked through the
+    tuning helper that the library exports beside the public entry points)."""
+    import ctypes
+    sv, su = ctypes.c_int(-1), ctypes.c_int(-1)
+    lib = tsvd.load_library()
+    lib.tsvd_internal_tile_shapes.restype = ctypes.c_int
+    rc = lib.tsvd_internal_tile_shapes(ctypes.c_void_p(handle.ptr), ctypes.c_longlong(B), ctypes.byref(sv), ctypes.byref(su))
+    if rc != 0 or su.value < 0:
+        return "batched stage-U kernel"
+    return "tsvd_gemm_ring_kernel" if su.value >= 14 else "tsvd_gemm_pipe_kernel"
 
 
 def _set_stage_mask(mask):
@@ -146,7 +159,7 @@ def bench_workload(name, steps, warmup, with_cpu=True, cpu_budget_s=4.0):
     res["stage_ms"] = {"V": v_ms, "U": u_ms}
     if batched:
         fl_u = 2.0 * w.K * w.M * w.B
-        res["roofline"] = {"bound": "mfma", "kernel": "tsvd_gemm_pipe_kernel (stage U, fp16 MFMA)",
+        res["roofline"] = {"bound": "mfma", "kernel": _stage_u_kernel_name(tsvd, handles[0], w.B) + " (stage U, fp16 MFMA)",
                            "achieved": fl_u / (u_ms * 1e-3) / 1e12, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                            "frac": fl_u / (u_ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS,
                            "traffic": STAGE_U_TRAFFIC_BYTES.get(name),

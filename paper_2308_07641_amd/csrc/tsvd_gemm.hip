@@ -946,6 +946,22 @@ int tsvd_stage_mask() {
     return (v && *v) ? atoi(v) : 7;
 }
 
+// Tile shape per stage.  Large problems: 256 x 256 (one workgroup per compute unit) or 256 x 128
+// (two, with independent barriers), whichever needs less time in rounds of workgroups; the
+// second is about 3 % more efficient per unit of work on MI355X.  Small problems (fewer
+// workgroups than about 1.5 per compute unit even at 256 x 128): the ring kernel, 128 x 64 tiles
+// if they still give every compute unit a workgroup, else 64 x 64 with the contraction split
+// over two groups of wavefronts; it needs 16-byte-aligned rows.
+int tsvd_gemm_tile_shape(long long rows, long long Bp, long long cus, bool aligned) {
+    const long long t0 = (rows / 256) * (Bp / 256), t1 = (rows / 256) * (Bp / 128), t2 = (rows / 128) * (Bp / 128);
+    if (2 * t1 >= 3 * cus) {
+        const double c0 = (double)((t0 + cus - 1) / cus) / 0.97, c1 = 0.5 * (double)((t1 + cus - 1) / cus);
+        return c0 < c1 ? 0 : 1;
+    }
+    if (!aligned) return t2 >= cus ? 2 : 3;
+    return (rows / 128) * (Bp / 64) >= cus ? 15 : 16;
+}
+
 hipError_t tsvd_gemm_init() {
     hipError_t e;
     if ((e = init_gemm<2, 4, 8, 4, false>()) != hipSuccess) return e;
@@ -1008,23 +1024,8 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     a2.ld_out = g.ldy;
     a2.rows_valid = (int)hd.M;
 
-    // Tile shape per stage.  Large problems: 256 x 256 (one workgroup per compute unit) or 256 x 128
-    // (two, with independent barriers), whichever needs less time in rounds of workgroups; the
-    // second is about 3 % more efficient per unit of work on MI355X.  Small problems (fewer
-    // workgroups than about 1.5 per compute unit even at 256 x 128): the ring kernel, 128 x 64 tiles
-    // if they still give every compute unit a workgroup, else 64 x 64 with the contraction split
-    // over two groups of wavefronts; it needs 16-byte-aligned rows.
-    auto pick = [&](long long rows, bool aligned) {
-        const long long cus = g.cu_count;
-        const long long t0 = (rows / 256) * (Bp / 256), t1 = (rows / 256) * (Bp / 128), t2 = (rows / 128) * (Bp / 128);
-        if (2 * t1 >= 3 * cus) {
-            const double c0 = (double)((t0 + cus - 1) / cus) / 0.97, c1 = 0.5 * (double)((t1 + cus - 1) / cus);
-            return c0 < c1 ? 0 : 1;
-        }
-        if (!aligned) return t2 >= cus ? 2 : 3;
-        return (rows / 128) * (Bp / 64) >= cus ? 15 : 16;
-    };
-    int cfg1 = env_cfg("TSVD_GEMM_CFG_V", pick(hd.Kp, fast1)), cfg2 = env_cfg("TSVD_GEMM_CFG_U", pick(hd.Mp, true));
+    int cfg1 = env_cfg("TSVD_GEMM_CFG_V", tsvd_gemm_tile_shape(hd.Kp, Bp, g.cu_count, fast1));
+    int cfg2 = env_cfg("TSVD_GEMM_CFG_U", tsvd_gemm_tile_shape(hd.Mp, Bp, g.cu_count, true));
     if (is_ring(cfg1) && !fast1) cfg1 = 3;
     const bool fuse = is_ring(cfg1) && env_cfg("TSVD_FUSEMAX", 1) != 0;
 
