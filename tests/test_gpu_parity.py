@@ -120,6 +120,59 @@ def test_activation_scale_extremes_batched(tsvd):
     assert np.all(per_token <= 2e-3)
 
 
+def test_general_single_token_kernel(tsvd, monkeypatch):
+    """The slab kernel that serves contraction lengths beyond the fast single-token kernel's
+    limits, forced on ordinary sizes (exact instance, then a random one per activation type)."""
+    monkeypatch.setenv("TSVD_GEMV", "0")
+    for B in (1, 2, 5):
+        i = workloads.make_integer_inputs(300, 513, 270, B, 0.5, "bf16", seed=900 + B)
+        print(f"case general kernel int B={B}", flush=True)
+        y, h = run_forward(i)
+        tsvd.tsvd_free(h)
+        assert np.array_equal(y, oracle.forward(i.U, i.S, i.V, i.X))
+    for x_dtype in ("bf16", "f32"):
+        i = workloads.make_inputs(1000, 300, 777, 3, 0.6, 0.02, x_dtype, seed=901)
+        print(f"case general kernel rand {x_dtype}", flush=True)
+        y, h = run_forward(i)
+        tsvd.tsvd_free(h)
+        assert rel_err(y, oracle.forward(i.U, i.S, i.V, i.X)) <= TOL[x_dtype]
+
+
+def test_long_contraction_single_token(tsvd):
+    """N and K beyond 16384: the single-token path falls back to the slab kernel by itself."""
+    i = workloads.make_inputs(64, 20000, 17000, 1, 0.6, 0.02, "bf16", seed=902)
+    print("case rand M=64 N=20000 K=17000 B=1 bf16", flush=True)
+    y, h = run_forward(i)
+    tsvd.tsvd_free(h)
+    assert not np.isnan(y).any()
+    assert rel_err(y, oracle.forward(i.U, i.S, i.V, i.X)) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("B", [1, 4, 64, 300])
+def test_degenerate_inputs(tsvd, B):
+    """All-zero factors or activations give exact zeros; an all-zero token inside a batch does not
+    disturb its neighbours (its scale is computed from a zero maximum)."""
+    base = workloads.make_inputs(130, 96, 200, B, 0.5, 0.02, "bf16", seed=903 + B)
+    print(f"case degenerate B={B}", flush=True)
+    for which in ("U", "V", "S", "X"):
+        i = workloads.Inputs(base.U.copy(), base.S.copy(), base.V.copy(), base.X.copy(), base.X_bits.copy(), "bf16")
+        getattr(i, which)[...] = 0
+        if which == "X":
+            i.X_bits[...] = 0
+        y, h = run_forward(i)
+        tsvd.tsvd_free(h)
+        assert np.array_equal(y, np.zeros_like(y)), which
+    if B > 1:
+        i = workloads.Inputs(base.U, base.S, base.V, base.X.copy(), base.X_bits.copy(), "bf16")
+        i.X[:, B // 2] = 0
+        i.X_bits[:, B // 2] = 0x8000          # negative zeros
+        ref = oracle.forward(i.U, i.S, i.V, i.X)
+        y, h = run_forward(i)
+        tsvd.tsvd_free(h)
+        assert np.array_equal(y[:, B // 2], np.zeros(y.shape[0]))
+        assert rel_err(y, ref) <= TOL["bf16"]
+
+
 def test_strided_inputs_outputs_and_caller_workspace(tsvd):
     import torch
     i = workloads.make_inputs(300, 200, 270, 70, 0.5, 0.02, "bf16", seed=5)
