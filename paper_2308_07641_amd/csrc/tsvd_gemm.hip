@@ -41,7 +41,7 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 #define TSVD_DEC(w, j) ((((uint32_t)(w)) << (14 - 2 * (j))) & 0xC000C000u)
 #define KT 64   // contraction depth of one LDS stage
 #ifndef TSVD_SCHED
-#define TSVD_SCHED 0
+#define TSVD_SCHED 1
 #endif
 #ifndef TSVD_STEP_FENCE
 #define TSVD_STEP_FENCE 1
@@ -526,19 +526,38 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
             for (int b = 0; b < TN; ++b) acc[a][b] = mfma16<STAGE2>(av, lo[b], hi[b], acc[a][b]);
         }
     };
+    // Issue order inside one step: the LDS reads of the next step first, the decode of the first
+    // strip, then one MFMA followed by two decode operations of the next strip, and so on: the
+    // decode hides in the shadow of the MFMAs instead of alternating with them in blocks.
+    // (The 8-wavefront shape has no registers to spare for the second set of decoded operands.)
+#define TSVD_INTERLEAVE(DS_READS)                                                        \
+    do {                                                                                 \
+        if constexpr (TSVD_SCHED && NW <= 4) {                                           \
+            if constexpr ((DS_READS) > 0) __builtin_amdgcn_sched_group_barrier(0x100, (DS_READS), 0); \
+            __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);                           \
+            _Pragma("unroll") for (int n_ = 0; n_ < TM * TN; ++n_) {                     \
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       \
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);                       \
+            }                                                                            \
+        }                                                                                \
+    } while (0)
     auto compute_pair = [&](int buf0, const u32x2 (&w)[TM]) {
         u32x2 f0lo[TN], f0hi[TN], f1lo[TN], f1hi[TN];
         load_frags(buf0, 0, f0lo, f0hi);
         load_frags(buf0, 1, f1lo, f1hi);
         mfma_step(w, 0, 0, f0lo, f0hi);
+        TSVD_INTERLEAVE(4 * TN);
         if (TSVD_STEP_FENCE) __builtin_amdgcn_sched_barrier(0);
         load_frags(buf0 + 1, 0, f0lo, f0hi);
         mfma_step(w, 0, 1, f1lo, f1hi);
+        TSVD_INTERLEAVE(2 * TN);
         if (TSVD_STEP_FENCE) __builtin_amdgcn_sched_barrier(0);
         load_frags(buf0 + 1, 1, f1lo, f1hi);
         mfma_step(w, 1, 0, f0lo, f0hi);
+        TSVD_INTERLEAVE(2 * TN);
         if (TSVD_STEP_FENCE) __builtin_amdgcn_sched_barrier(0);
         mfma_step(w, 1, 1, f1lo, f1hi);
+        TSVD_INTERLEAVE(0);
         __builtin_amdgcn_sched_barrier(0);
     };
 
