@@ -32,6 +32,7 @@ PRIMARY = "bert_ffn_in"
 # HBM bytes per launch of the stage-U kernel (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors a
 # plain 256 MiB copy gives), from profiles/hbm_traffic_fetch_write_size.md.  Counters cannot be read
 # inside this process; the figures belong to the launch shapes bench.py uses.
+PANEL_TRAFFIC_BYTES = {}   # token-panel launches: filled from the same profile when measured
 STAGE_U_TRAFFIC_BYTES = {"bert_ffn_in": 11.1e6 + 6.29e6, "convnext_mlp": 186e6 + 102.8e6,
                          "opt66b_fc1_prefill": 2021e6 + 302.0e6, "opt6b7_fc1_decode": 34.2e6 + 0.066e6}
 
@@ -70,6 +71,8 @@ def _stage_u_kernel_name(tsvd, handle, B):
     rc = lib.tsvd_internal_tile_shapes(ctypes.c_void_p(handle.ptr), ctypes.c_longlong(B), ctypes.byref(sv), ctypes.byref(su))
     if rc != 0 or su.value < 0:
         return "batched stage-U kernel"
+    if su.value == 32:
+        return "tsvd_panel_kernel"
     return "tsvd_gemm_ring_kernel" if su.value >= 14 else "tsvd_gemm_pipe_kernel"
 
 
@@ -157,9 +160,19 @@ def bench_workload(name, steps, warmup, with_cpu=True, cpu_budget_s=4.0):
     _, v_ms = _timed(step_rot, steps, max(2, warmup // 2))
     _set_stage_mask(None)
     res["stage_ms"] = {"V": v_ms, "U": u_ms}
-    if batched:
+    kernel_name = _stage_u_kernel_name(tsvd, handles[0], w.B) if batched else None
+    if batched and kernel_name == "tsvd_panel_kernel":
+        # one launch does both stages (z stays in LDS): the call IS the dominant kernel; the stage
+        # times above belong to the two-launch path that the stage mask falls back to
+        res["two_launch_stage_ms"] = res.pop("stage_ms")
+        res["roofline"] = {"bound": "mfma", "kernel": "tsvd_panel_kernel (both stages, bf16 + fp16 MFMA)",
+                           "achieved": res["executed_tflops"], "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
+                           "frac": res["executed_tflops"] / PEAK_MFMA_TFLOPS,
+                           "traffic": PANEL_TRAFFIC_BYTES.get(name),
+                           "whole_path_frac": res["executed_tflops"] / PEAK_MFMA_TFLOPS}
+    elif batched:
         fl_u = 2.0 * w.K * w.M * w.B
-        res["roofline"] = {"bound": "mfma", "kernel": _stage_u_kernel_name(tsvd, handles[0], w.B) + " (stage U, fp16 MFMA)",
+        res["roofline"] = {"bound": "mfma", "kernel": kernel_name + " (stage U, fp16 MFMA)",
                            "achieved": fl_u / (u_ms * 1e-3) / 1e12, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                            "frac": fl_u / (u_ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS,
                            "traffic": STAGE_U_TRAFFIC_BYTES.get(name),

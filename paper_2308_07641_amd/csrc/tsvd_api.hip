@@ -365,14 +365,19 @@ extern "C" tsvd_status tsvd_forward(const tsvd_handle* h, const void* x_dev, tsv
 
 // Tuning aid, not part of the public header: copies the phase timestamps of the last B <= 2 launch.
 // Tuning aid, not part of the public header: the tile shapes tsvd_forward picks for B tokens of
-// 16-byte-aligned bf16 activations (stage V, stage U); -1 where the batched kernels are not used.
+// 16-byte-aligned bf16 activations (stage V, stage U); 32 for both when the call is one token-panel
+// launch; -1 where the batched kernels are not used.
 extern "C" int tsvd_internal_tile_shapes(const tsvd_handle* h, long long B, int* shape_v, int* shape_u) {
     if (!h || !shape_v || !shape_u || B < 1) return 1;
     *shape_v = *shape_u = -1;
     if (use_gemm(h, B, TSVD_BF16)) {
         const long long Bp = (long long)tsvd_round_up(B, 256);
-        *shape_v = tsvd_gemm_tile_shape(h->hd.Kp, Bp, h->cu_count, true);
-        *shape_u = tsvd_gemm_tile_shape(h->hd.Mp, Bp, h->cu_count, true);
+        if (tsvd_gemm_use_panel(h->hd.Mp, h->hd.Kp, h->hd.Np, B, h->cu_count, true)) {
+            *shape_v = *shape_u = 32;                 // one token-panel launch
+        } else {
+            *shape_v = tsvd_gemm_tile_shape(h->hd.Kp, Bp, h->cu_count, true);
+            *shape_u = tsvd_gemm_tile_shape(h->hd.Mp, Bp, h->cu_count, true);
+        }
     }
     return 0;
 }

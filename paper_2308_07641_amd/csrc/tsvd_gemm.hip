@@ -26,6 +26,7 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <type_traits>
 #include <cmath>
 
 #include "tsvd_kernels.h"
@@ -880,6 +881,297 @@ tsvd_gemm_ring_kernel(gemm_args p) {
     tick(5);
 }
 
+// ---- token-panel kernel: both stages in one launch, z never leaves the compute unit ----------
+// For many tokens and a small factorisation (K <= 1024, code words of U and V a few MB: the MLP of
+// a convolutional network) a workgroup of 8 wavefronts owns 64 tokens from x to y:
+//   phase 1  Z[K][64] = fp16(scale * S * (V X[:, 64 tokens]))   into LDS (128 KB), with the column
+//            maxima of X computed on the way (the workgroup streams all N rows of its tokens);
+//   phase 2  Y[M][64] = (U Z) / scale, in passes of 1024 rows; Z is read from LDS in MFMA operand
+//            order, the code words of U go straight to registers, so this phase has no barrier at
+//            all: the wavefronts drift apart and one's stores of Y overlap the others' MFMAs.
+// No intermediate in HBM, no column-maximum launch, no launch boundary, and one round of
+// workgroups (ceil(B / 64) of them) instead of separate rounds per stage.  Arithmetic, operand
+// order and rounding are those of the two-launch path.
+struct panel_args {
+    const uint32_t* tiles_v;  // packed V [Kp/16][Np/256][256 words]
+    const uint32_t* tiles_u;  // packed U [Mp/16][Kp/256][256 words]
+    unsigned tile_v_bytes, tile_u_bytes;
+    int nkt_v, nkt_u;         // Np / 256, Kp / 256
+    const uint16_t* x;        // bf16 [N][ldx]
+    long long ldx;
+    unsigned x_bytes;
+    const float* S;
+    float bound_V;
+    int Kp, Mp, M, B;
+    float* y;
+    long long ldy;
+    long long* clocks;
+};
+#define TSVD_PANEL_MAX_KP 1024
+#ifndef TSVD_PANEL_SCHED
+#define TSVD_PANEL_SCHED 0
+#endif
+#define TSVD_PANEL_LDS (TSVD_PANEL_MAX_KP * 128 + 4 * KT * 128)
+
+__global__ void __launch_bounds__(512, 2)
+tsvd_panel_kernel(panel_args p) {
+    constexpr int NW = 8, TM = 8, TN = 4, BT = 64, THREADS = 64 * NW;
+    constexpr int ROWB = BT * 2, NBLK = BT / 16, CPR = BT / 8, STAGE_BYTES = KT * ROWB, RPS = 64 / CPR;
+    static_assert(STAGE_BYTES / 1024 == NW && THREADS == KT * CPR, "one 1-KiB piece per wavefront and stage; one scan chunk per thread");
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char* zl = smem;                                   // Z: Kp / 64 stages of [64 rows][64 tokens] fp16, swizzled
+    unsigned char* ring = smem + TSVD_PANEL_MAX_KP * ROWB;      // phase 1: four activation stages; then reductions and factors
+    float* cs1 = reinterpret_cast<float*>(ring + THREADS * 16); // per-token factor of phase 1 (scale / 2) ...
+    float* cs2 = cs1 + BT;                                      // ... and of phase 2 (1 / (2 scale))
+
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int i = lane & 15, g = lane >> 4;
+    const int b0 = blockIdx.x * BT;
+    auto tick = [&](int n) {
+        if (p.clocks && threadIdx.x == 0 && blockIdx.x < TSVD_GEMV_MAX_GRID) p.clocks[blockIdx.x * 16 + n] = wall_clock64();
+    };
+    tick(0);
+
+    // (row and swizzle conventions: see tsvd_gemm_kernel; this tile is one wavefront wide)
+    const int rsel = i >> 2;
+    const int tr_row = 32 * (g & 1) + 16 * (g >> 1) + (rsel >> 1) + 4 * (rsel & 1);
+    const int f_lane = swizzle<NBLK>(tr_row);
+    int lds_rd[TN];
+#pragma unroll
+    for (int b = 0; b < TN; ++b) lds_rd[b] = tr_row * ROWB + ((b ^ f_lane) * 32) + (i & 3) * 8;
+
+    f32x4 acc[TM][TN];
+    auto clear_acc = [&]() {
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+    };
+    auto load_frags = [&](const unsigned char* stage_base, int hh, u32x2 (&lo)[TN], u32x2 (&hi)[TN]) {
+        const unsigned char* base = stage_base + hh * 8 * ROWB;
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+            lo[b] = lds_tr(base + lds_rd[b]);
+            hi[b] = lds_tr(base + lds_rd[b] + 2 * ROWB);
+        }
+    };
+#define TSVD_PANEL_INTERLEAVE(DS_READS)                                                  \
+    do {                                                                                 \
+        if constexpr (TSVD_PANEL_SCHED) {                                                \
+            if constexpr ((DS_READS) > 0) __builtin_amdgcn_sched_group_barrier(0x100, (DS_READS), 0); \
+            __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);                           \
+            _Pragma("unroll") for (int n_ = 0; n_ < TM * TN; ++n_) {                     \
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       \
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);                       \
+            }                                                                            \
+        }                                                                                \
+    } while (0)
+    // the four MFMA steps of a pair of stages whose activations sit at s0 and s1 in LDS
+    auto compute_pair = [&](auto stage2, const unsigned char* s0, const unsigned char* s1, const u32x2 (&w)[TM]) {
+        constexpr bool STAGE2 = decltype(stage2)::value;
+        auto mfma_step = [&](int word, int hh, const u32x2 (&lo)[TN], const u32x2 (&hi)[TN]) {
+#pragma unroll
+            for (int a = 0; a < TM; ++a) {
+                const uint32_t ww = word == 0 ? w[a].x : w[a].y;
+                u32x4 av;
+                if (hh == 0) av = u32x4{TSVD_DEC(ww, 0), TSVD_DEC(ww, 2), TSVD_DEC(ww, 4), TSVD_DEC(ww, 6)};
+                else         av = u32x4{TSVD_DEC(ww, 1), TSVD_DEC(ww, 3), TSVD_DEC(ww, 5), ww & 0xC000C000u};
+#pragma unroll
+                for (int b = 0; b < TN; ++b) acc[a][b] = mfma16<STAGE2>(av, lo[b], hi[b], acc[a][b]);
+            }
+        };
+        u32x2 f0lo[TN], f0hi[TN], f1lo[TN], f1hi[TN];
+        load_frags(s0, 0, f0lo, f0hi);
+        load_frags(s0, 1, f1lo, f1hi);
+        mfma_step(0, 0, f0lo, f0hi);
+        TSVD_PANEL_INTERLEAVE(4 * TN);
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(s1, 0, f0lo, f0hi);
+        mfma_step(0, 1, f1lo, f1hi);
+        TSVD_PANEL_INTERLEAVE(2 * TN);
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(s1, 1, f1lo, f1hi);
+        mfma_step(1, 0, f0lo, f0hi);
+        TSVD_PANEL_INTERLEAVE(2 * TN);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_step(1, 1, f1lo, f1hi);
+        TSVD_PANEL_INTERLEAVE(0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    const int w_voff = lane * 16;
+
+    // ================= phase 1: Z = fp16(scale * S * (V X)) into LDS =================
+    {
+        const int strip0 = wave * TM;                 // this wavefront's rows of Z: 128 wave .. 128 wave + 127
+        // piece `wave` of a stage: LDS rows wave * RPS + lane / CPR, physical chunk lane % CPR
+        const int r = wave * RPS + lane / CPR, pc = lane % CPR;
+        const int lc = (((pc >> 1) ^ swizzle<NBLK>(r)) << 1) | (pc & 1);
+        const int x_voff = (64 * (r >> 5) + (r & 31)) * (int)p.ldx * 2 + (b0 + lc * 8) * 2;
+        const i32x4 act_rsrc = raw_rsrc(p.x, p.x_bytes);
+        const __amdgpu_buffer_rsrc_t w_rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(p.tiles_v), 0, p.tile_v_bytes, 0x00020000);
+        typedef __attribute__((address_space(3))) unsigned char* lds_byte_ptr;
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_byte_ptr)ring + wave * 1024;
+        auto issue_x = [&](int stage, int buf) {
+            const int soff = (256 * (stage >> 2) + 128 * ((stage >> 1) & 1) + 32 * (stage & 1)) * (int)p.ldx * 2;
+            buf_load128_to_lds(act_rsrc, lds0 + buf * STAGE_BYTES, x_voff, soff);
+        };
+        auto load_w = [&](int pair, u32x2 (&w)[TM]) {
+            const int soff = (strip0 * p.nkt_v + (pair >> 1)) * 1024 + (pair & 1) * 8;
+#pragma unroll
+            for (int a = 0; a < TM; ++a) w[a] = __builtin_amdgcn_raw_buffer_load_b64(w_rsrc, w_voff, soff + a * p.nkt_v * 1024, 0);
+        };
+        auto touch = [&](const u32x2 (&w)[TM]) {      // see tsvd_gemm_pipe_kernel
+#pragma unroll
+            for (int a = 0; a < TM; ++a) asm volatile("" :: "v"(w[a].x), "v"(w[a].y));
+        };
+        // column maxima: thread t scans logical chunk t % CPR (8 tokens) of row t / CPR of every stage
+        u32x4 cm = {0u, 0u, 0u, 0u};
+        const int sr_ = threadIdx.x / CPR, sch = threadIdx.x % CPR;
+        const int lds_sc = sr_ * ROWB + (((sch >> 1) ^ swizzle<NBLK>(sr_)) * 32) + (sch & 1) * 16;
+        auto scan = [&](int buf) {
+            u32x4 v = *reinterpret_cast<const u32x4*>(ring + buf * STAGE_BYTES + lds_sc);
+            v &= 0x7FFF7FFFu;
+            cm = u32x4{pk_max_u16(cm.x, v.x), pk_max_u16(cm.y, v.y), pk_max_u16(cm.z, v.z), pk_max_u16(cm.w, v.w)};
+        };
+
+        clear_acc();
+        const int npairs = p.nkt_v * 2, lastp = npairs - 1;
+        u32x2 wa[TM], wb[TM];
+        load_w(0, wa);
+        issue_x(0, 0);
+        issue_x(1, 1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        touch(wa);
+        __syncthreads();
+        tick(1);
+        for (int P = 0; P < npairs; P += 2) {
+            int nx = min(P + 1, lastp);
+            load_w(nx, wb);
+            issue_x(2 * nx, 2);
+            issue_x(2 * nx + 1, 3);
+            compute_pair(std::false_type{}, ring, ring + STAGE_BYTES, wa);
+            scan(0);
+            scan(1);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            touch(wb);
+            __syncthreads();
+
+            nx = min(P + 2, lastp);
+            load_w(nx, wa);
+            issue_x(2 * nx, 0);
+            issue_x(2 * nx + 1, 1);
+            compute_pair(std::false_type{}, ring + 2 * STAGE_BYTES, ring + 3 * STAGE_BYTES, wb);
+            scan(2);
+            scan(3);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            touch(wa);
+            __syncthreads();
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();                              // every wavefront's loads have landed: the ring is free
+        tick(2);
+
+        // S of this wavefront's rows (needed after the reduction; the loads fly meanwhile)
+        f32x4 sv[TM];
+#pragma unroll
+        for (int a = 0; a < TM; ++a) sv[a] = *reinterpret_cast<const f32x4*>(p.S + min((strip0 + a) * 16 + 4 * g, p.Kp - 4));
+
+        // column maxima -> per-token factors (two levels: every wavefront reduces 8 of the 64 rows)
+        reinterpret_cast<u32x4*>(ring)[threadIdx.x] = cm;      // [row][chunk] = [64][64 tokens] of 16-bit magnitudes
+        __syncthreads();
+        {
+            const uint16_t* r16 = reinterpret_cast<const uint16_t*>(ring) + wave * 8 * BT + lane;   // rows 8 wave .., token `lane`
+            uint32_t part = 0;
+#pragma unroll
+            for (int l = 0; l < 8; ++l) part = max(part, (uint32_t)r16[l * BT]);
+            reinterpret_cast<uint32_t*>(ring + THREADS * 16 + 2 * BT * 4)[threadIdx.x] = part;       // [wavefront][token]
+        }
+        __syncthreads();
+        if (threadIdx.x < BT) {
+            const uint32_t* r32 = reinterpret_cast<const uint32_t*>(ring + THREADS * 16 + 2 * BT * 4) + threadIdx.x;
+            uint32_t best = 0;
+#pragma unroll
+            for (int l = 0; l < NW; ++l) best = max(best, r32[l * BT]);
+            const int e = scale_exponent(__uint_as_float(best << 16), p.bound_V);
+            cs1[threadIdx.x] = ldexpf(1.0f, e - 1);
+            cs2[threadIdx.x] = ldexpf(1.0f, -e - 1);
+        }
+        __syncthreads();
+
+        // z of this wavefront's rows -> LDS in the stage/row order phase 2 reads: row k sits in stage
+        // 4 (k >> 8) + 2 ((k >> 7) & 1) + ((k >> 5) & 1), LDS row 32 ((k >> 6) & 1) + (k & 31).  With
+        // k = 128 wave + 16 a + 4 g + v the stage is 2 wave + ((a >> 1) & 1), the row is
+        // 32 ((a >> 2) & 1) + 16 (a & 1) + 4 g + v, and its swizzle is (g & 1) | (((a ^ (a >> 2)) & 1) << 1):
+        // everything but two per-lane terms is a compile-time offset.
+        float c1[TN];
+        int blk[TN];
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+            c1[b] = cs1[b * 16 + i];
+            blk[b] = (b ^ (g & 1)) * 32;
+        }
+        unsigned char* lane_base = zl + (2 * wave) * STAGE_BYTES + (4 * g) * ROWB + i * 2;
+#pragma unroll
+        for (int a = 0; a < TM; ++a) {
+            if ((strip0 + a) * 16 < p.Kp) {                     // (uniform) rows of the padded rank only
+                unsigned char* pa = lane_base + ((a >> 1) & 1) * STAGE_BYTES + (32 * ((a >> 2) & 1) + 16 * (a & 1)) * ROWB;
+                const int fa = ((a ^ (a >> 2)) & 1) << 1;
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+#pragma unroll
+                    for (int b = 0; b < TN; ++b)
+                        *reinterpret_cast<_Float16*>(pa + v * ROWB + blk[b ^ fa]) = (_Float16)((acc[a][b][v] * sv[a][v]) * c1[b]);
+            }
+        }
+        __syncthreads();
+        tick(3);
+    }
+
+    // ================= phase 2: Y = (U Z) / scale, 1024 rows per pass, no barriers =================
+    {
+        const __amdgpu_buffer_rsrc_t w_rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(p.tiles_u), 0, p.tile_u_bytes, 0x00020000);
+        float c2[TN];
+#pragma unroll
+        for (int b = 0; b < TN; ++b) c2[b] = cs2[b * 16 + i];
+        const int npairs = p.nkt_u * 2, lastp = npairs - 1;
+        for (int strip0 = wave * TM; strip0 * 16 < p.Mp; strip0 += NW * TM) {
+            auto load_w = [&](int pair, u32x2 (&w)[TM]) {
+                const int soff = (strip0 * p.nkt_u + (pair >> 1)) * 1024 + (pair & 1) * 8;
+#pragma unroll
+                for (int a = 0; a < TM; ++a) w[a] = __builtin_amdgcn_raw_buffer_load_b64(w_rsrc, w_voff, soff + a * p.nkt_u * 1024, 0);
+            };
+            clear_acc();
+            u32x2 wa[TM], wb[TM];
+            load_w(0, wa);
+            for (int P = 0; P < npairs; P += 2) {
+                load_w(min(P + 1, lastp), wb);
+                compute_pair(std::true_type{}, zl + (2 * P) * STAGE_BYTES, zl + (2 * P + 1) * STAGE_BYTES, wa);
+                load_w(min(P + 2, lastp), wa);
+                compute_pair(std::true_type{}, zl + (2 * P + 2) * STAGE_BYTES, zl + (2 * P + 3) * STAGE_BYTES, wb);
+            }
+#pragma unroll
+            for (int a = 0; a < TM; ++a) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int row = (strip0 + a) * 16 + 4 * g + v;
+                    if (row < p.M) {
+                        float* dst = p.y + (size_t)row * p.ldy;
+#pragma unroll
+                        for (int b = 0; b < TN; ++b) {
+                            const int col = b0 + b * 16 + i;
+                            if (col < p.B) dst[col] = acc[a][b][v] * c2[b];
+                        }
+                    }
+                }
+            }
+        }
+    }
+    tick(4);
+    if (p.clocks && lane == 0 && blockIdx.x < TSVD_GEMV_MAX_GRID) p.clocks[blockIdx.x * 16 + 8 + wave] = wall_clock64();   // per-wavefront end
+}
+
 template <int WM, int WN, int TM, int TN, bool STAGE2>
 hipError_t launch_gemm(const gemm_args& a, bool fast, long long rows, int Bp, hipStream_t stream) {
     constexpr int BT = WN * TN * 16, MT = WM * TM * 16;
@@ -981,6 +1273,18 @@ int tsvd_gemm_tile_shape(long long rows, long long Bp, long long cus, bool align
     return (rows / 128) * (Bp / 64) >= cus ? 15 : 16;
 }
 
+// The token-panel kernel serves 16-byte-aligned activations, K <= 1024, code words of both factors
+// small enough to stay in every L2 (each workgroup reads all of them), and a token count whose
+// 64-token panels fill at least 60 % of the compute units of their last round.
+bool tsvd_gemm_use_panel(long long Mp, long long Kp, long long Np, long long B, long long cus, bool aligned) {
+    const char* v = getenv("TSVD_PANEL");
+    const int mode = (v && *v) ? atoi(v) : -1;       // 0 never, 1 whenever the shape allows, default: by rule
+    if (!aligned || Kp > TSVD_PANEL_MAX_KP || mode == 0) return false;
+    if (mode == 1) return true;
+    const long long n = (B + 63) / 64, rounds = (n + cus - 1) / cus;
+    return (Mp + Np) * Kp / 4 <= (8ll << 20) && 10 * n >= 6 * rounds * cus;
+}
+
 hipError_t tsvd_gemm_init() {
     hipError_t e;
     if ((e = init_gemm<2, 4, 8, 4, false>()) != hipSuccess) return e;
@@ -991,6 +1295,8 @@ hipError_t tsvd_gemm_init() {
     if ((e = init_gemm<2, 2, 4, 4, true>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 2, 2, 4, false>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 2, 2, 4, true>()) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 TSVD_PANEL_LDS)) != hipSuccess) return e;
 #define TSVD_RING_INIT(id, wm, wn, tm, tn, npb, kg) \
     if ((e = init_ring<wm, wn, tm, tn, npb, kg>()) != hipSuccess) return e;
     TSVD_RING_SHAPES(TSVD_RING_INIT)
@@ -1043,6 +1349,29 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     a2.ld_out = g.ldy;
     a2.rows_valid = (int)hd.M;
 
+    if (tsvd_stage_mask() == 7 && tsvd_gemm_use_panel(hd.Mp, hd.Kp, hd.Np, g.B, g.cu_count, fast1)) {
+        panel_args pa;
+        pa.tiles_v = a1.tiles;
+        pa.tiles_u = a2.tiles;
+        pa.tile_v_bytes = a1.tile_bytes;
+        pa.tile_u_bytes = a2.tile_bytes;
+        pa.nkt_v = a1.nkt;
+        pa.nkt_u = a2.nkt;
+        pa.x = a1.act;
+        pa.ldx = g.ldx;
+        pa.x_bytes = a1.act_bytes;
+        pa.S = a1.S;
+        pa.bound_V = g.bound_V;
+        pa.Kp = (int)hd.Kp;
+        pa.Mp = (int)hd.Mp;
+        pa.M = (int)hd.M;
+        pa.B = (int)g.B;
+        pa.y = g.y;
+        pa.ldy = g.ldy;
+        pa.clocks = g.clocks;
+        hipLaunchKernelGGL(tsvd_panel_kernel, dim3((unsigned)((g.B + 63) / 64)), dim3(512), TSVD_PANEL_LDS, stream, pa);
+        return hipGetLastError();
+    }
     int cfg1 = env_cfg("TSVD_GEMM_CFG_V", tsvd_gemm_tile_shape(hd.Kp, Bp, g.cu_count, fast1));
     int cfg2 = env_cfg("TSVD_GEMM_CFG_U", tsvd_gemm_tile_shape(hd.Mp, Bp, g.cu_count, true));
     if (is_ring(cfg1) && !fast1) cfg1 = 3;

@@ -94,6 +94,31 @@ def test_every_tile_shape_batched(tsvd, cfg, fuse, monkeypatch):
     assert rel_err(y, ref) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("M,N,K,B", [(300, 200, 520, 300), (64, 48, 200, 17), (1030, 100, 1000, 70), (2048, 512, 1024, 1000)])
+def test_token_panel_kernel(tsvd, M, N, K, B, monkeypatch):
+    """Both stages in one launch with z kept in LDS (K <= 1024), forced on small instances: exact
+    integers bit for bit, random values within tolerance, and next to identical to the two-launch path."""
+    print(f"case panel M={M} N={N} K={K} B={B}", flush=True)
+    i = workloads.make_integer_inputs(M, N, K, B, 0.5, "bf16", seed=5150 + B)
+    monkeypatch.setenv("TSVD_PANEL", "1")
+    y, h = run_forward(i)
+    tsvd.tsvd_free(h)
+    assert not np.isnan(y).any()
+    assert np.array_equal(y, oracle.forward(i.U, i.S, i.V, i.X))
+    j = workloads.make_inputs(M, N, K, B, 0.6, 0.02, "bf16", seed=5151 + B)
+    ref = oracle.forward(j.U, j.S, j.V, j.X)
+    y1, h = run_forward(j)
+    tsvd.tsvd_free(h)
+    assert not np.isnan(y1).any()
+    assert rel_err(y1, ref) <= TOL["bf16"]
+    monkeypatch.setenv("TSVD_PANEL", "0")
+    y0, h = run_forward(j)
+    tsvd.tsvd_free(h)
+    # same products; only the fp32 summation order differs between the kernels (a different order in
+    # stage V can move an fp16 rounding of z by one unit in the last place)
+    assert rel_err(y0, y1) <= 1e-5
+
+
 def test_larger_small_problem_uses_wider_ring_tiles(tsvd):
     """2048 x 1024 outputs per stage: enough 128 x 64 tiles for every compute unit."""
     i = workloads.make_inputs(2048, 512, 2048, 1024, 0.6, 0.02, "bf16", seed=31337)
