@@ -884,8 +884,9 @@ tsvd_gemm_ring_kernel(gemm_args p) {
 // ---- token-panel kernel: both stages in one launch, z never leaves the compute unit ----------
 // For many tokens and a small factorisation (K <= 1024, code words of U and V a few MB: the MLP of
 // a convolutional network) a workgroup of 8 wavefronts owns 64 tokens from x to y:
-//   phase 1  Z[K][64] = fp16(scale * S * (V X[:, 64 tokens]))   into LDS (128 KB), with the column
-//            maxima of X computed on the way (the workgroup streams all N rows of its tokens);
+//   phase 1  the activation panel X[N][64 tokens] is fetched whole into LDS (N <= 1024), then
+//            Z[K][64] = fp16(scale * S * (V X)) replaces it (128 KB), with the column maxima of X
+//            computed on the way;
 //   phase 2  Y[M][64] = (U Z) / scale, in passes of 1024 rows; Z is read from LDS in MFMA operand
 //            order, the code words of U go straight to registers, so this phase has no barrier at
 //            all: the wavefronts drift apart and one's stores of Y overlap the others' MFMAs.
@@ -911,7 +912,8 @@ struct panel_args {
 #ifndef TSVD_PANEL_SCHED
 #define TSVD_PANEL_SCHED 0
 #endif
-#define TSVD_PANEL_LDS (TSVD_PANEL_MAX_KP * 128 + 4 * KT * 128)
+#define TSVD_PANEL_MAX_NP 1024
+#define TSVD_PANEL_LDS (TSVD_PANEL_MAX_KP * 128 + 512 * 16 + 2 * 64 * 4 + 512 * 4)
 
 __global__ void __launch_bounds__(512, 2)
 tsvd_panel_kernel(panel_args p) {
@@ -919,8 +921,8 @@ tsvd_panel_kernel(panel_args p) {
     constexpr int ROWB = BT * 2, NBLK = BT / 16, CPR = BT / 8, STAGE_BYTES = KT * ROWB, RPS = 64 / CPR;
     static_assert(STAGE_BYTES / 1024 == NW && THREADS == KT * CPR, "one 1-KiB piece per wavefront and stage; one scan chunk per thread");
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char* zl = smem;                                   // Z: Kp / 64 stages of [64 rows][64 tokens] fp16, swizzled
-    unsigned char* ring = smem + TSVD_PANEL_MAX_KP * ROWB;      // phase 1: four activation stages; then reductions and factors
+    unsigned char* zl = smem;                                   // X, then Z: stages of [64 rows][64 tokens] 16-bit, swizzled
+    unsigned char* ring = smem + TSVD_PANEL_MAX_KP * ROWB;      // reductions and per-token factors
     float* cs1 = reinterpret_cast<float*>(ring + THREADS * 16); // per-token factor of phase 1 (scale / 2) ...
     float* cs2 = cs1 + BT;                                      // ... and of phase 2 (1 / (2 scale))
 
@@ -957,7 +959,7 @@ tsvd_panel_kernel(panel_args p) {
     };
 #define TSVD_PANEL_INTERLEAVE(DS_READS)                                                  \
     do {                                                                                 \
-        if constexpr (TSVD_PANEL_SCHED) {                                                \
+        if constexpr (TSVD_PANEL_SCHED && STAGE2) {                                      \
             if constexpr ((DS_READS) > 0) __builtin_amdgcn_sched_group_barrier(0x100, (DS_READS), 0); \
             __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);                           \
             _Pragma("unroll") for (int n_ = 0; n_ < TM * TN; ++n_) {                     \
@@ -1011,7 +1013,7 @@ tsvd_panel_kernel(panel_args p) {
         const __amdgpu_buffer_rsrc_t w_rsrc =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(p.tiles_v), 0, p.tile_v_bytes, 0x00020000);
         typedef __attribute__((address_space(3))) unsigned char* lds_byte_ptr;
-        const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_byte_ptr)ring + wave * 1024;
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_byte_ptr)zl + wave * 1024;
         auto issue_x = [&](int stage, int buf) {
             const int soff = (256 * (stage >> 2) + 128 * ((stage >> 1) & 1) + 32 * (stage & 1)) * (int)p.ldx * 2;
             buf_load128_to_lds(act_rsrc, lds0 + buf * STAGE_BYTES, x_voff, soff);
@@ -1021,55 +1023,38 @@ tsvd_panel_kernel(panel_args p) {
 #pragma unroll
             for (int a = 0; a < TM; ++a) w[a] = __builtin_amdgcn_raw_buffer_load_b64(w_rsrc, w_voff, soff + a * p.nkt_v * 1024, 0);
         };
-        auto touch = [&](const u32x2 (&w)[TM]) {      // see tsvd_gemm_pipe_kernel
-#pragma unroll
-            for (int a = 0; a < TM; ++a) asm volatile("" :: "v"(w[a].x), "v"(w[a].y));
-        };
         // column maxima: thread t scans logical chunk t % CPR (8 tokens) of row t / CPR of every stage
         u32x4 cm = {0u, 0u, 0u, 0u};
         const int sr_ = threadIdx.x / CPR, sch = threadIdx.x % CPR;
         const int lds_sc = sr_ * ROWB + (((sch >> 1) ^ swizzle<NBLK>(sr_)) * 32) + (sch & 1) * 16;
         auto scan = [&](int buf) {
-            u32x4 v = *reinterpret_cast<const u32x4*>(ring + buf * STAGE_BYTES + lds_sc);
+            u32x4 v = *reinterpret_cast<const u32x4*>(zl + buf * STAGE_BYTES + lds_sc);
             v &= 0x7FFF7FFFu;
             cm = u32x4{pk_max_u16(cm.x, v.x), pk_max_u16(cm.y, v.y), pk_max_u16(cm.z, v.z), pk_max_u16(cm.w, v.w)};
         };
 
+        // The whole activation panel [Np][64 tokens] (at most 128 KB) is fetched into the area that
+        // will hold Z afterwards: one wait, one barrier, and the wavefronts run their contraction
+        // loops without meeting again until all of them are done with X.
         clear_acc();
         const int npairs = p.nkt_v * 2, lastp = npairs - 1;
         u32x2 wa[TM], wb[TM];
         load_w(0, wa);
-        issue_x(0, 0);
-        issue_x(1, 1);
+        for (int st = 0; st < 2 * npairs; ++st) issue_x(st, st);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        touch(wa);
         __syncthreads();
         tick(1);
         for (int P = 0; P < npairs; P += 2) {
-            int nx = min(P + 1, lastp);
-            load_w(nx, wb);
-            issue_x(2 * nx, 2);
-            issue_x(2 * nx + 1, 3);
-            compute_pair(std::false_type{}, ring, ring + STAGE_BYTES, wa);
-            scan(0);
-            scan(1);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            touch(wb);
-            __syncthreads();
-
-            nx = min(P + 2, lastp);
-            load_w(nx, wa);
-            issue_x(2 * nx, 0);
-            issue_x(2 * nx + 1, 1);
-            compute_pair(std::false_type{}, ring + 2 * STAGE_BYTES, ring + 3 * STAGE_BYTES, wb);
-            scan(2);
-            scan(3);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            touch(wa);
-            __syncthreads();
+            load_w(min(P + 1, lastp), wb);
+            compute_pair(std::false_type{}, zl + (2 * P) * STAGE_BYTES, zl + (2 * P + 1) * STAGE_BYTES, wa);
+            scan(2 * P);
+            scan(2 * P + 1);
+            load_w(min(P + 2, lastp), wa);
+            compute_pair(std::false_type{}, zl + (2 * P + 2) * STAGE_BYTES, zl + (2 * P + 3) * STAGE_BYTES, wb);
+            scan(2 * P + 2);
+            scan(2 * P + 3);
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();                              // every wavefront's loads have landed: the ring is free
+        __syncthreads();                              // every wavefront is done with X: its area becomes Z
         tick(2);
 
         // S of this wavefront's rows (needed after the reduction; the loads fly meanwhile)
@@ -1273,13 +1258,13 @@ int tsvd_gemm_tile_shape(long long rows, long long Bp, long long cus, bool align
     return (rows / 128) * (Bp / 64) >= cus ? 15 : 16;
 }
 
-// The token-panel kernel serves 16-byte-aligned activations, K <= 1024, code words of both factors
+// The token-panel kernel serves 16-byte-aligned activations, K <= 1024, N <= 1024, code words of both factors
 // small enough to stay in every L2 (each workgroup reads all of them), and a token count whose
 // 64-token panels fill at least 60 % of the compute units of their last round.
 bool tsvd_gemm_use_panel(long long Mp, long long Kp, long long Np, long long B, long long cus, bool aligned) {
     const char* v = getenv("TSVD_PANEL");
     const int mode = (v && *v) ? atoi(v) : -1;       // 0 never, 1 whenever the shape allows, default: by rule
-    if (!aligned || Kp > TSVD_PANEL_MAX_KP || mode == 0) return false;
+    if (!aligned || Kp > TSVD_PANEL_MAX_KP || Np > TSVD_PANEL_MAX_NP || mode == 0) return false;
     if (mode == 1) return true;
     const long long n = (B + 63) / 64, rounds = (n + cus - 1) / cus;
     return (Mp + Np) * Kp / 4 <= (8ll << 20) && 10 * n >= 6 * rounds * cus;
