@@ -913,13 +913,16 @@ struct panel_args {
 #define TSVD_PANEL_SCHED 0
 #endif
 #define TSVD_PANEL_MAX_NP 1024
-#define TSVD_PANEL_LDS (TSVD_PANEL_MAX_KP * 128 + 512 * 16 + 2 * 64 * 4 + 512 * 4)
+#define TSVD_PANEL_LDS(NW) (TSVD_PANEL_MAX_KP * 128 + 64 * (NW) * 16 + 2 * 64 * 4 + 64 * (NW) * 4)
 
-__global__ void __launch_bounds__(512, 2)
+// NW = 8 wavefronts of 128 rows each (two per SIMD, up to 256 registers) or 16 of 64 rows (four per SIMD).
+template <int NW>
+__global__ void __launch_bounds__(64 * NW, NW / 4)
 tsvd_panel_kernel(panel_args p) {
-    constexpr int NW = 8, TM = 8, TN = 4, BT = 64, THREADS = 64 * NW;
+    constexpr int TM = 64 / NW, TN = 4, BT = 64, THREADS = 64 * NW;
     constexpr int ROWB = BT * 2, NBLK = BT / 16, CPR = BT / 8, STAGE_BYTES = KT * ROWB, RPS = 64 / CPR;
-    static_assert(STAGE_BYTES / 1024 == NW && THREADS == KT * CPR, "one 1-KiB piece per wavefront and stage; one scan chunk per thread");
+    static_assert(NW == 8 || NW == 16, "1024 rows of Z per pass");
+    static_assert(STAGE_BYTES == 8 * 1024 && KT * CPR == 512, "eight 1-KiB pieces and 512 scan chunks per stage");
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* zl = smem;                                   // X, then Z: stages of [64 rows][64 tokens] 16-bit, swizzled
     unsigned char* ring = smem + TSVD_PANEL_MAX_KP * ROWB;      // reductions and per-token factors
@@ -982,6 +985,23 @@ tsvd_panel_kernel(panel_args p) {
                 for (int b = 0; b < TN; ++b) acc[a][b] = mfma16<STAGE2>(av, lo[b], hi[b], acc[a][b]);
             }
         };
+        if constexpr (NW == 16) {
+            // four wavefronts per SIMD hide the LDS latency of one another: one operand set, half the registers
+            u32x2 lo[TN], hi[TN];
+            load_frags(s0, 0, lo, hi);
+            mfma_step(0, 0, lo, hi);
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(s0, 1, lo, hi);
+            mfma_step(0, 1, lo, hi);
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(s1, 0, lo, hi);
+            mfma_step(1, 0, lo, hi);
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(s1, 1, lo, hi);
+            mfma_step(1, 1, lo, hi);
+            __builtin_amdgcn_sched_barrier(0);
+            return;
+        }
         u32x2 f0lo[TN], f0hi[TN], f1lo[TN], f1hi[TN];
         load_frags(s0, 0, f0lo, f0hi);
         load_frags(s0, 1, f1lo, f1hi);
@@ -1005,15 +1025,17 @@ tsvd_panel_kernel(panel_args p) {
     // ================= phase 1: Z = fp16(scale * S * (V X)) into LDS =================
     {
         const int strip0 = wave * TM;                 // this wavefront's rows of Z: 128 wave .. 128 wave + 127
-        // piece `wave` of a stage: LDS rows wave * RPS + lane / CPR, physical chunk lane % CPR
-        const int r = wave * RPS + lane / CPR, pc = lane % CPR;
+        // piece wave % 8 of the stages wave / 8, wave / 8 + NW / 8, ...: LDS rows piece * RPS + lane / CPR,
+        // physical chunk lane % CPR
+        const int piece = wave & 7;
+        const int r = piece * RPS + lane / CPR, pc = lane % CPR;
         const int lc = (((pc >> 1) ^ swizzle<NBLK>(r)) << 1) | (pc & 1);
         const int x_voff = (64 * (r >> 5) + (r & 31)) * (int)p.ldx * 2 + (b0 + lc * 8) * 2;
         const i32x4 act_rsrc = raw_rsrc(p.x, p.x_bytes);
         const __amdgpu_buffer_rsrc_t w_rsrc =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(p.tiles_v), 0, p.tile_v_bytes, 0x00020000);
         typedef __attribute__((address_space(3))) unsigned char* lds_byte_ptr;
-        const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_byte_ptr)zl + wave * 1024;
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_byte_ptr)zl + piece * 1024;
         auto issue_x = [&](int stage, int buf) {
             const int soff = (256 * (stage >> 2) + 128 * ((stage >> 1) & 1) + 32 * (stage & 1)) * (int)p.ldx * 2;
             buf_load128_to_lds(act_rsrc, lds0 + buf * STAGE_BYTES, x_voff, soff);
@@ -1023,85 +1045,83 @@ tsvd_panel_kernel(panel_args p) {
 #pragma unroll
             for (int a = 0; a < TM; ++a) w[a] = __builtin_amdgcn_raw_buffer_load_b64(w_rsrc, w_voff, soff + a * p.nkt_v * 1024, 0);
         };
-        // column maxima: thread t scans logical chunk t % CPR (8 tokens) of row t / CPR of every stage
-        u32x4 cm = {0u, 0u, 0u, 0u};
-        const int sr_ = threadIdx.x / CPR, sch = threadIdx.x % CPR;
-        const int lds_sc = sr_ * ROWB + (((sch >> 1) ^ swizzle<NBLK>(sr_)) * 32) + (sch & 1) * 16;
-        auto scan = [&](int buf) {
-            u32x4 v = *reinterpret_cast<const u32x4*>(zl + buf * STAGE_BYTES + lds_sc);
-            v &= 0x7FFF7FFFu;
-            cm = u32x4{pk_max_u16(cm.x, v.x), pk_max_u16(cm.y, v.y), pk_max_u16(cm.z, v.z), pk_max_u16(cm.w, v.w)};
-        };
-
         // The whole activation panel [Np][64 tokens] (at most 128 KB) is fetched into the area that
         // will hold Z afterwards: one wait, one barrier, and the wavefronts run their contraction
         // loops without meeting again until all of them are done with X.
         clear_acc();
-        const int npairs = p.nkt_v * 2, lastp = npairs - 1;
+        const int npairs = p.nkt_v * 2, lastp = npairs - 1, nst = 2 * npairs;
         u32x2 wa[TM], wb[TM];
         load_w(0, wa);
-        for (int st = 0; st < 2 * npairs; ++st) issue_x(st, st);
+        for (int st = wave >> 3; st < nst; st += NW / 8) issue_x(st, st);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         tick(1);
-        for (int P = 0; P < npairs; P += 2) {
-            load_w(min(P + 1, lastp), wb);
-            compute_pair(std::false_type{}, zl + (2 * P) * STAGE_BYTES, zl + (2 * P + 1) * STAGE_BYTES, wa);
-            scan(2 * P);
-            scan(2 * P + 1);
-            load_w(min(P + 2, lastp), wa);
-            compute_pair(std::false_type{}, zl + (2 * P + 2) * STAGE_BYTES, zl + (2 * P + 3) * STAGE_BYTES, wb);
-            scan(2 * P + 2);
-            scan(2 * P + 3);
-        }
-        __syncthreads();                              // every wavefront is done with X: its area becomes Z
-        tick(2);
 
-        // S of this wavefront's rows (needed after the reduction; the loads fly meanwhile)
-        f32x4 sv[TM];
-#pragma unroll
-        for (int a = 0; a < TM; ++a) sv[a] = *reinterpret_cast<const f32x4*>(p.S + min((strip0 + a) * 16 + 4 * g, p.Kp - 4));
-
-        // column maxima -> per-token factors (two levels: every wavefront reduces 8 of the 64 rows)
-        reinterpret_cast<u32x4*>(ring)[threadIdx.x] = cm;      // [row][chunk] = [64][64 tokens] of 16-bit magnitudes
-        __syncthreads();
+        // column maxima -> per-token factors.  Thread t scans logical chunk c % CPR (8 tokens) of LDS row
+        // c / CPR, c = t % 512, of the stages t / 512, t / 512 + THREADS / 512, ...; then two levels of
+        // reduction (every wavefront reduces 8 of the THREADS / 8 partial rows).
         {
+            u32x4 cm = {0u, 0u, 0u, 0u};              // packed 16-bit magnitudes (order-preserving bit patterns)
+            const int c = threadIdx.x & 511, sr_ = c / CPR, sch = c % CPR;
+            const int lds_sc = sr_ * ROWB + (((sch >> 1) ^ swizzle<NBLK>(sr_)) * 32) + (sch & 1) * 16;
+            for (int st = threadIdx.x >> 9; st < nst; st += THREADS / 512) {
+                u32x4 v = *reinterpret_cast<const u32x4*>(zl + st * STAGE_BYTES + lds_sc);
+                v &= 0x7FFF7FFFu;
+                cm = u32x4{pk_max_u16(cm.x, v.x), pk_max_u16(cm.y, v.y), pk_max_u16(cm.z, v.z), pk_max_u16(cm.w, v.w)};
+            }
+            reinterpret_cast<u32x4*>(ring)[threadIdx.x] = cm;      // [THREADS / 8 partial rows][64 tokens] of 16-bit magnitudes
+            __syncthreads();
             const uint16_t* r16 = reinterpret_cast<const uint16_t*>(ring) + wave * 8 * BT + lane;   // rows 8 wave .., token `lane`
             uint32_t part = 0;
 #pragma unroll
             for (int l = 0; l < 8; ++l) part = max(part, (uint32_t)r16[l * BT]);
-            reinterpret_cast<uint32_t*>(ring + THREADS * 16 + 2 * BT * 4)[threadIdx.x] = part;       // [wavefront][token]
-        }
-        __syncthreads();
-        if (threadIdx.x < BT) {
-            const uint32_t* r32 = reinterpret_cast<const uint32_t*>(ring + THREADS * 16 + 2 * BT * 4) + threadIdx.x;
-            uint32_t best = 0;
+            uint32_t* partials = reinterpret_cast<uint32_t*>(ring + THREADS * 16 + 2 * BT * 4);    // [wavefront][token]
+            partials[threadIdx.x] = part;
+            __syncthreads();
+            if (threadIdx.x < BT) {
+                uint32_t best = 0;
 #pragma unroll
-            for (int l = 0; l < NW; ++l) best = max(best, r32[l * BT]);
-            const int e = scale_exponent(__uint_as_float(best << 16), p.bound_V);
-            cs1[threadIdx.x] = ldexpf(1.0f, e - 1);
-            cs2[threadIdx.x] = ldexpf(1.0f, -e - 1);
+                for (int l = 0; l < NW; ++l) best = max(best, partials[l * BT + threadIdx.x]);
+                const int e = scale_exponent(__uint_as_float(best << 16), p.bound_V);
+                cs1[threadIdx.x] = ldexpf(1.0f, e - 1);
+                cs2[threadIdx.x] = ldexpf(1.0f, -e - 1);
+            }
         }
-        __syncthreads();
+
+        for (int P = 0; P < npairs; P += 2) {
+            load_w(min(P + 1, lastp), wb);
+            compute_pair(std::false_type{}, zl + (2 * P) * STAGE_BYTES, zl + (2 * P + 1) * STAGE_BYTES, wa);
+            load_w(min(P + 2, lastp), wa);
+            compute_pair(std::false_type{}, zl + (2 * P + 2) * STAGE_BYTES, zl + (2 * P + 3) * STAGE_BYTES, wb);
+        }
+        // S of this wavefront's rows
+        f32x4 sv[TM];
+#pragma unroll
+        for (int a = 0; a < TM; ++a) sv[a] = *reinterpret_cast<const f32x4*>(p.S + min((strip0 + a) * 16 + 4 * g, p.Kp - 4));
+        __syncthreads();                              // every wavefront is done with X: its area becomes Z (factors are published)
+        tick(2);
 
         // z of this wavefront's rows -> LDS in the stage/row order phase 2 reads: row k sits in stage
         // 4 (k >> 8) + 2 ((k >> 7) & 1) + ((k >> 5) & 1), LDS row 32 ((k >> 6) & 1) + (k & 31).  With
-        // k = 128 wave + 16 a + 4 g + v the stage is 2 wave + ((a >> 1) & 1), the row is
-        // 32 ((a >> 2) & 1) + 16 (a & 1) + 4 g + v, and its swizzle is (g & 1) | (((a ^ (a >> 2)) & 1) << 1):
-        // everything but two per-lane terms is a compile-time offset.
+        // k = 16 s + 4 g + v, s = strip0 + a: stage 2 (strip0 >> 3) + ((a >> 1) & 1), row
+        // 32 ((s >> 2) & 1) + 16 (a & 1) + 4 g + v, swizzle (g & 1) | (((s ^ (s >> 2)) & 1) << 1), where
+        // (s >> 2) & 1 is (a >> 2) & 1 for 8 strips per wavefront and (strip0 >> 2) & 1 for 4:
+        // everything but a few per-lane or per-wavefront terms is a compile-time offset.
+        const int hi_rt = TM == 8 ? 0 : (strip0 >> 2) & 1;
         float c1[TN];
         int blk[TN];
 #pragma unroll
         for (int b = 0; b < TN; ++b) {
             c1[b] = cs1[b * 16 + i];
-            blk[b] = (b ^ (g & 1)) * 32;
+            blk[b] = (b ^ (g & 1) ^ (hi_rt << 1)) * 32;
         }
-        unsigned char* lane_base = zl + (2 * wave) * STAGE_BYTES + (4 * g) * ROWB + i * 2;
+        unsigned char* lane_base = zl + (2 * (strip0 >> 3)) * STAGE_BYTES + (32 * hi_rt + 4 * g) * ROWB + i * 2;
 #pragma unroll
         for (int a = 0; a < TM; ++a) {
             if ((strip0 + a) * 16 < p.Kp) {                     // (uniform) rows of the padded rank only
-                unsigned char* pa = lane_base + ((a >> 1) & 1) * STAGE_BYTES + (32 * ((a >> 2) & 1) + 16 * (a & 1)) * ROWB;
-                const int fa = ((a ^ (a >> 2)) & 1) << 1;
+                const int hi_ct = TM == 8 ? (a >> 2) & 1 : 0;
+                unsigned char* pa = lane_base + ((a >> 1) & 1) * STAGE_BYTES + (32 * hi_ct + 16 * (a & 1)) * ROWB;
+                const int fa = ((a ^ (TM == 8 ? a >> 2 : 0)) & 1) << 1;
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
 #pragma unroll
@@ -1154,7 +1174,8 @@ tsvd_panel_kernel(panel_args p) {
         }
     }
     tick(4);
-    if (p.clocks && lane == 0 && blockIdx.x < TSVD_GEMV_MAX_GRID) p.clocks[blockIdx.x * 16 + 8 + wave] = wall_clock64();   // per-wavefront end
+    if (p.clocks && lane == 0 && blockIdx.x < TSVD_GEMV_MAX_GRID)
+        p.clocks[blockIdx.x * 16 + 8 + wave / (NW / 8)] = wall_clock64();   // end of (one of) the wavefronts of each eighth
 }
 
 template <int WM, int WN, int TM, int TN, bool STAGE2>
@@ -1280,8 +1301,10 @@ hipError_t tsvd_gemm_init() {
     if ((e = init_gemm<2, 2, 4, 4, true>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 2, 2, 4, false>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 2, 2, 4, true>()) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 TSVD_PANEL_LDS)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_kernel<8>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 TSVD_PANEL_LDS(8))) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_kernel<16>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 TSVD_PANEL_LDS(16))) != hipSuccess) return e;
 #define TSVD_RING_INIT(id, wm, wn, tm, tn, npb, kg) \
     if ((e = init_ring<wm, wn, tm, tn, npb, kg>()) != hipSuccess) return e;
     TSVD_RING_SHAPES(TSVD_RING_INIT)
@@ -1354,7 +1377,10 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
         pa.y = g.y;
         pa.ldy = g.ldy;
         pa.clocks = g.clocks;
-        hipLaunchKernelGGL(tsvd_panel_kernel, dim3((unsigned)((g.B + 63) / 64)), dim3(512), TSVD_PANEL_LDS, stream, pa);
+        if (env_cfg("TSVD_PANEL_WAVES", 16) == 16)   // tuning switch: 16 is about 5 % faster on MI355X
+            hipLaunchKernelGGL(tsvd_panel_kernel<16>, dim3((unsigned)((g.B + 63) / 64)), dim3(1024), TSVD_PANEL_LDS(16), stream, pa);
+        else
+            hipLaunchKernelGGL(tsvd_panel_kernel<8>, dim3((unsigned)((g.B + 63) / 64)), dim3(512), TSVD_PANEL_LDS(8), stream, pa);
         return hipGetLastError();
     }
     int cfg1 = env_cfg("TSVD_GEMM_CFG_V", tsvd_gemm_tile_shape(hd.Kp, Bp, g.cu_count, fast1));

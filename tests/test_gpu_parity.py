@@ -94,13 +94,15 @@ def test_every_tile_shape_batched(tsvd, cfg, fuse, monkeypatch):
     assert rel_err(y, ref) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("waves", ["16", "8"])
 @pytest.mark.parametrize("M,N,K,B", [(300, 200, 520, 300), (64, 48, 200, 17), (1030, 100, 1000, 70), (2048, 512, 1024, 1000)])
-def test_token_panel_kernel(tsvd, M, N, K, B, monkeypatch):
+def test_token_panel_kernel(tsvd, M, N, K, B, waves, monkeypatch):
     """Both stages in one launch with z kept in LDS (K <= 1024), forced on small instances: exact
     integers bit for bit, random values within tolerance, and next to identical to the two-launch path."""
     print(f"case panel M={M} N={N} K={K} B={B}", flush=True)
     i = workloads.make_integer_inputs(M, N, K, B, 0.5, "bf16", seed=5150 + B)
     monkeypatch.setenv("TSVD_PANEL", "1")
+    monkeypatch.setenv("TSVD_PANEL_WAVES", waves)
     y, h = run_forward(i)
     tsvd.tsvd_free(h)
     assert not np.isnan(y).any()
