@@ -32,7 +32,7 @@ PRIMARY = "bert_ffn_in"
 # HBM bytes per launch of the stage-U kernel (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors a
 # plain 256 MiB copy gives), from profiles/hbm_traffic_fetch_write_size.md.  Counters cannot be read
 # inside this process; the figures belong to the launch shapes bench.py uses.
-PANEL_TRAFFIC_BYTES = {}   # token-panel launches: filled from the same profile when measured
+PANEL_TRAFFIC_BYTES = {"convnext_mlp": 18.4e6 + 102.8e6}   # token-panel launches, same profile
 STAGE_U_TRAFFIC_BYTES = {"bert_ffn_in": 11.1e6 + 6.29e6, "convnext_mlp": 186e6 + 102.8e6,
                          "opt66b_fc1_prefill": 2021e6 + 302.0e6, "opt6b7_fc1_decode": 34.2e6 + 0.066e6}
 
