@@ -16,9 +16,10 @@
 // Schedule.  At B = 1 a call lasts a few microseconds and every instruction of the prologue is
 // executed by all 16 wavefronts of a compute unit, so the code is kept short and every serial
 // round trip to memory counts.  Vector-memory results return to a wavefront in issue order:
-// each wavefront issues all its loads at entry in the order it needs them, first the small,
-// latency-critical activations (x, or the digit planes of z written by stage V), then every
-// weight tile it owns (up to 8; more are streamed).  The activations are staged in LDS while the
+// each wavefront issues its loads at entry in the order it needs them, first the small,
+// latency-critical activations (x, or the digit planes of z written by stage V), then its first
+// weight tiles; the rest are streamed with a fixed number in flight (NPRE below: requesting
+// everything at once made every load slower).  The activations are staged in LDS while the
 // weights are in flight.  Stage V multiplies by S and writes z already digitised (power-of-two
 // scale from the bound |z_k| <= max_k(|S_k| nnz(V[k,:])) * max|x|), so stage U only copies planes.
 // (Measured on MI355X: a device-wide barrier inside one launch costs 4 us or more with
@@ -34,7 +35,13 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-#define NPRE 8       // weight tiles per wavefront loaded at entry
+// Weight tiles per wavefront in flight.  16 wavefronts x 256 compute units x 2 KiB = 8.4 MB is
+// about the bandwidth-delay product of the memory system; with 8 in flight (all 33.5 MB of the
+// decode workload requested in the first microsecond) every load, the activations included, came
+// back later: 17.0 us per token against 13.9 us.
+#ifndef NPRE
+#define NPRE 2
+#endif
 #define XR_MAX 4     // x: groups of 4 consecutive elements per thread  (N <= 16384)
 #define ZR_MAX 8     // z planes: 16-byte chunks per thread             (K <= 16384)
 
@@ -234,14 +241,17 @@ tsvd_gemv_kernel(tsvd_gemv_args p) {
     // ---- stream this wavefront's tiles T = q, q + kw, ...
     f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
     if (active) {
+        // NPRE tiles stay in flight: each one is replaced by the tile NPRE places further on as soon
+        // as it has been copied out of its registers (unconditional, clamped loads; results return
+        // in issue order, so the wait before tile n is for all but the NPRE - 1 younger loads).
+        for (int T0 = q; T0 < p.nkt; T0 += NPRE * kw) {
 #pragma unroll
-        for (int n = 0; n < NPRE; ++n) {
-            const int T = q + n * kw;
-            if (T < p.nkt) tile_steps(pre[n], xlane + T * 256, acc0, acc1);
-        }
-        for (int T = q + NPRE * kw; T < p.nkt; T += kw) {
-            const u32x4 w0 = __builtin_nontemporal_load(wp + (size_t)T * 64);
-            tile_steps(w0, xlane + T * 256, acc0, acc1);
+            for (int n = 0; n < NPRE; ++n) {
+                const int T = T0 + n * kw;
+                const u32x4 w0 = pre[n];
+                pre[n] = __builtin_nontemporal_load(wp + (size_t)min(T + NPRE * kw, p.nkt - 1) * 64);
+                if (T < p.nkt) tile_steps(w0, xlane + T * 256, acc0, acc1);
+            }
         }
     }
     // D layout of the 16x16 MFMA: lane holds column i, rows 4 g + v.  Only columns 0..7 matter.
