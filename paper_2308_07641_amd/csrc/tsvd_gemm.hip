@@ -912,6 +912,9 @@ struct panel_args {
 #ifndef TSVD_PANEL_SCHED
 #define TSVD_PANEL_SCHED 0
 #endif
+#ifndef TSVD_PANEL_BALANCE
+#define TSVD_PANEL_BALANCE 1
+#endif
 #define TSVD_PANEL_MAX_NP 1024
 #define TSVD_PANEL_LDS(NW) (TSVD_PANEL_MAX_KP * 128 + 64 * (NW) * 16 + 2 * 64 * 4 + 64 * (NW) * 4)
 
@@ -1141,7 +1144,24 @@ tsvd_panel_kernel(panel_args p) {
 #pragma unroll
         for (int b = 0; b < TN; ++b) c2[b] = cs2[b * 16 + i];
         const int npairs = p.nkt_u * 2, lastp = npairs - 1;
-        for (int strip0 = wave * TM; strip0 * 16 < p.Mp; strip0 += NW * TM) {
+        // Units of TM strips (64 or 128 rows).  A SIMD always issues from its oldest ready wavefront,
+        // so with equal shares the wavefronts of a SIMD (w, w + 4, w + 8, w + 12) finish one after
+        // the other and the last runs alone (phase timestamps: 41, 47, 54, 60 us).  The units of a
+        // SIMD are therefore split 3 : 2 : 2 : 1 by age (1 : 1 with two wavefronts per SIMD): unit
+        // j of SIMD s is rows (4 j + s) * 16 TM .., and age group a takes units [lo, hi).
+        const int simd = wave & 3, age = wave >> 2;
+        const int per_simd = (p.Mp / (16 * TM) - simd + 3) / 4;
+        int lo, hi;
+        if (NW == 16 && TSVD_PANEL_BALANCE) {
+            const int c1 = (3 * per_simd + 4) / 8, c2 = (5 * per_simd + 4) / 8, c3 = (7 * per_simd + 4) / 8;
+            lo = age == 0 ? 0 : age == 1 ? c1 : age == 2 ? c2 : c3;
+            hi = age == 0 ? c1 : age == 1 ? c2 : age == 2 ? c3 : per_simd;
+        } else {
+            lo = age * per_simd / (NW / 4);
+            hi = (age + 1) * per_simd / (NW / 4);
+        }
+        for (int j = lo; j < hi; ++j) {
+            const int strip0 = (4 * j + simd) * TM;
             auto load_w = [&](int pair, u32x2 (&w)[TM]) {
                 const int soff = (strip0 * p.nkt_u + (pair >> 1)) * 1024 + (pair & 1) * 8;
 #pragma unroll
