@@ -44,6 +44,8 @@ hipError_t device_init(int device) {
     if (e != hipSuccess) return e;
     e = tsvd_gemv_init();
     if (e != hipSuccess) return e;
+    e = tsvd_mid_init();
+    if (e != hipSuccess) return e;
     done[device] = true;
     return hipSuccess;
 }
@@ -196,6 +198,75 @@ tsvd_status forward_skinny(const tsvd_handle* h, const void* x, tsvd_dtype x_dty
     return TSVD_OK;
 }
 
+// ---- few-token path: 2 <= B <= 16 tokens of bf16 activations, two launches -------------------
+bool use_mid(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype, int64_t ldx) {
+    // (32-bit byte offsets into x in the kernel, which also addresses up to four slabs of 2048 rows
+    // beyond the last one: the range check returns zeros there)
+    return x_dtype == TSVD_BF16 && B >= 2 && B <= 16 && env_int("TSVD_MID", 1) != 0 &&
+           ((uint64_t)h->hd.Np + 8192) * (uint64_t)ldx * 2 < (1ull << 31);
+}
+
+size_t mid_workspace(const tsvd_handle* h) {
+    return 256 + (size_t)32 * (size_t)h->hd.Kp;      // per-token maxima, then z fp16 [Kp][16]
+}
+
+tsvd_status forward_mid(const tsvd_handle* h, const void* x, int64_t B, int64_t ldx, float* y, int64_t ldy, void* ws,
+                        hipStream_t stream) {
+    const tsvd_blob_header& hd = h->hd;
+    const int mask = tsvd_stage_mask();
+    // about one workgroup of 16 wavefronts per compute unit: sw strips x kw contraction splits
+    auto shape = [&](tsvd_mid_args& a) {
+        int sw = 2;
+        while (sw < 16 && a.strips / (sw * 2) >= h->cu_count) sw *= 2;
+        int kl = 0;
+        while (kl < 3 && (sw << (kl + 1)) <= 16 && (2 << kl) <= a.nkt) ++kl;
+        a.sw = std::max(1, std::min(16, env_int("TSVD_MID_SW", sw)));
+        a.kw_log2 = std::max(0, std::min(3, env_int("TSVD_MID_KWLOG2", kl)));
+        while ((a.sw << a.kw_log2) > 16) --a.kw_log2;
+    };
+    tsvd_mid_args a;
+    std::memset(&a, 0, sizeof a);
+    a.bvalid = (int)B;
+    a.bound_V = h->bound_V;
+    a.colmax = static_cast<float*>(ws);
+    uint16_t* z = reinterpret_cast<uint16_t*>(static_cast<uint8_t*>(ws) + 256);
+    if (mask & 2) {
+        a.tiles = h->blob + hd.off_V;
+        a.strips = (int)(hd.Kp / 16);
+        a.nkt = (int)(hd.Np / 256);
+        a.act = static_cast<const uint16_t*>(x);
+        a.ld = ldx;
+        a.kvalid = (int)hd.N;
+        // extent of x, rounded up to the 4-byte granularity of the buffer range check (for odd B the
+        // dword holding the last element would otherwise read as zero; it lies inside an aligned dword
+        // whose first half is the caller's, so it cannot cross into an unmapped page)
+        a.act_bytes = (unsigned)((((((size_t)hd.N - 1) * (size_t)ldx + (size_t)B) * 2) + 3) & ~(size_t)3);
+        a.S = reinterpret_cast<const float*>(h->blob + hd.off_S);
+        a.out = z;
+        a.ld_out = 16;
+        a.rows_valid = (int)hd.Kp;
+        shape(a);
+        const bool dma = ldx % 8 == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
+        if (tsvd_launch_mid(a, false, dma, stream) != hipSuccess) return TSVD_EDEVICE;
+    }
+    if (mask & 4) {
+        a.tiles = h->blob + hd.off_U;
+        a.strips = (int)((hd.M + 15) / 16);
+        a.nkt = (int)(hd.Kp / 256);
+        a.act = z;
+        a.ld = 16;
+        a.kvalid = (int)hd.Kp;
+        a.act_bytes = (unsigned)((size_t)hd.Kp * 32);
+        a.S = nullptr;
+        a.out = y;
+        a.ld_out = ldy;
+        a.rows_valid = (int)hd.M;
+        shape(a);
+        if (tsvd_launch_mid(a, true, true, stream) != hipSuccess) return TSVD_EDEVICE;
+    }
+    return TSVD_OK;
+}
+
 bool use_gemm(const tsvd_handle*, int64_t B, tsvd_dtype x_dtype) {
     const int min_b = env_int("TSVD_GEMM_MIN_B", 17);
     return x_dtype == TSVD_BF16 && B >= min_b;
@@ -309,7 +380,8 @@ extern "C" tsvd_status tsvd_info(const tsvd_handle* h, int64_t* M, int64_t* K, i
 extern "C" size_t tsvd_workspace_bytes(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype) {
     if (!h || B <= 0 || (x_dtype != TSVD_F32 && x_dtype != TSVD_BF16)) return 0;
     if (use_gemm(h, B, x_dtype)) return gemm_workspace(h, B);
-    return round256(skinny_workspace(h));
+    // (the few-token path is chosen per call, by the row stride too: cover both)
+    return round256(std::max(skinny_workspace(h), mid_workspace(h)));
 }
 
 extern "C" tsvd_status tsvd_forward(const tsvd_handle* h, const void* x_dev, tsvd_dtype x_dtype, int64_t B,
@@ -360,6 +432,7 @@ extern "C" tsvd_status tsvd_forward(const tsvd_handle* h, const void* x_dev, tsv
         g.clocks = h->clocks;
         return tsvd_forward_gemm(g, s) == hipSuccess ? TSVD_OK : TSVD_EDEVICE;
     }
+    if (use_mid(h, B, x_dtype, ldx)) return forward_mid(h, x_dev, B, ldx, static_cast<float*>(y_dev), ldy, ws, s);
     return forward_skinny(h, x_dev, x_dtype, B, ldx, static_cast<float*>(y_dev), ldy, ws, s);
 }
 

@@ -56,6 +56,22 @@ bool tsvd_gemv_fits(long long Np, long long Kp);
 hipError_t tsvd_launch_gemv(const tsvd_gemv_args& a, bool stage_u, hipStream_t stream);
 #define TSVD_GEMV_MAX_GRID 1024
 
+// One stage of the few-token path (tsvd_mid.hip): 2 <= B <= 16 tokens of bf16 activations.
+struct tsvd_mid_args {
+    const void* tiles; int strips, nkt;   // stage V: V, Kp/16 strips, Np/256 tiles; stage U: U, ceil(M/16), Kp/256
+    int sw, kw_log2;                      // workgroup = sw strips x (1 << kw_log2) contraction splits, kw <= 8
+    const uint16_t* act;                  // stage V: x bf16 [N][ld]; stage U: z fp16 [Kp][16]
+    long long ld;
+    int kvalid, bvalid;                   // rows of act that exist (stage V: N), tokens (<= 16)
+    unsigned act_bytes;                   // extent of act in bytes (reads beyond it give zero)
+    const float* S; float bound_V;        // stage V: row scales (zero beyond K); |z| <= bound_V * max|x|
+    float* colmax;                        // [16] per-token max |x| (stage V writes, stage U reads)
+    void* out; long long ld_out;          // stage V: z fp16 [Kp][16]; stage U: y fp32 [M][ld_out]
+    int rows_valid;                       // stage U: M
+};
+hipError_t tsvd_mid_init();
+hipError_t tsvd_launch_mid(const tsvd_mid_args& a, bool stage_u, bool vec, hipStream_t stream);
+
 // ---- batched path ----------------------------------------------------------------------------
 struct tsvd_blob_header;
 struct tsvd_gemm_problem {

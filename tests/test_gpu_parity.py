@@ -132,6 +132,51 @@ def test_larger_small_problem_uses_wider_ring_tiles(tsvd):
     assert rel_err(y, ref) <= TOL["bf16"]
 
 
+# ---- few-token kernel (2 <= B <= 16, bf16): contraction lengths of several LDS slabs with a ragged
+# ---- last one, every contraction split, aligned rows (vector loads) and unaligned rows (gather)
+@pytest.mark.parametrize("kwlog2", ["0", "1", "2", "3"])
+@pytest.mark.parametrize("M,N,K,B", [(100, 2300, 4500, 16), (530, 270, 5000, 8), (70, 6000, 300, 7), (200, 4100, 2049, 2)])
+def test_few_token_kernel(tsvd, M, N, K, B, kwlog2, monkeypatch):
+    import torch
+    monkeypatch.setenv("TSVD_MID_KWLOG2", kwlog2)
+    monkeypatch.setenv("TSVD_MID_SW", "2")
+    i = workloads.make_integer_inputs(M, N, K, B, 0.5, "bf16", seed=31 + M + B)
+    print(f"case few-token int M={M} N={N} K={K} B={B} kw=2^{kwlog2}", flush=True)
+    y, h = run_forward(i)
+    tsvd.tsvd_free(h)
+    assert np.array_equal(y, oracle.forward(i.U, i.S, i.V, i.X))
+    i = workloads.make_inputs(M, N, K, B, 0.6, 0.02, "bf16", seed=32 + M + B)
+    print(f"case few-token rand M={M} N={N} K={K} B={B} kw=2^{kwlog2}", flush=True)
+    ref = oracle.forward(i.U, i.S, i.V, i.X)
+    y, h = run_forward(i)
+    assert not np.isnan(y).any()
+    assert rel_err(y, ref) <= TOL["bf16"]
+    # the same tokens as columns of a wider, 16-byte-aligned matrix (vector loads, neighbours in the padding lanes)
+    xfull = torch.randn((N, 24), dtype=torch.float32, device="cuda:0").to(torch.bfloat16)
+    xfull[:, :B] = to_device(i)
+    y2 = tsvd.tsvd_forward(h, xfull[:, :B]).cpu().numpy().astype(np.float64)
+    assert np.array_equal(y2, y)
+    # and against the one-token-at-a-time path
+    monkeypatch.setenv("TSVD_MID", "0")
+    y3 = tsvd.tsvd_forward(h, to_device(i)).cpu().numpy().astype(np.float64)
+    tsvd.tsvd_free(h)
+    assert rel_err(y3, ref) <= 1e-5 and rel_err(y, y3) <= TOL["bf16"]
+
+
+def test_activation_scale_extremes_few_tokens(tsvd):
+    """Per-token scaling of the fp16 intermediate in the few-token kernel."""
+    i = workloads.make_inputs(256, 256, 256, 16, 0.5, 0.02, "bf16", seed=78)
+    scale = np.ldexp(1.0, np.random.default_rng(2).integers(-60, 60, size=16)).astype(np.float32)
+    i.X = i.X * scale[None, :]
+    i.X_bits = workloads.f32_to_bf16_bits(i.X)
+    i.X = workloads.bf16_bits_to_f32(i.X_bits)
+    ref = oracle.forward(i.U, i.S, i.V, i.X)
+    y, h = run_forward(i)
+    tsvd.tsvd_free(h)
+    per_token = np.max(np.abs(y - ref), axis=0) / np.max(np.abs(ref), axis=0)
+    assert np.all(per_token <= 2e-3)
+
+
 def test_activation_scale_extremes_batched(tsvd):
     """The fp16 intermediate of the batched path is rescaled per token: tokens of very different
     magnitude in one batch must all keep their accuracy (error measured per token here)."""
