@@ -96,7 +96,7 @@ tsvd_status tsvd_info(const tsvd_handle* h, int64_t* M, int64_t* K, int64_t* N,
  *            call returns without synchronising.
  * x, y and workspace are owned by the caller and must not alias.  Inputs must be finite.
  * Accumulation is fp32; TSVD_F32 activations are consumed exactly (split into bf16 parts),
- * so the result differs from exact arithmetic only by fp32 summation rounding.  For B >= 64
+ * so the result differs from exact arithmetic only by fp32 summation rounding.  For B >= 2
  * with TSVD_BF16 activations the intermediate z is rounded to fp16 (11 significant bits)
  * after a per-token power-of-two scaling that keeps it in range.
  */

@@ -198,12 +198,25 @@ tsvd_status forward_skinny(const tsvd_handle* h, const void* x, tsvd_dtype x_dty
     return TSVD_OK;
 }
 
-// ---- few-token path: 2 <= B <= 16 tokens of bf16 activations, two launches -------------------
+// ---- few-token path: groups of up to 16 tokens of bf16 activations, two launches per group ------
+// Up to 16 tokens always; up to 64 tokens (2..4 groups, each streaming the weights again, mostly
+// from the last-level cache) when the packed weights are large: there the batched kernels, with
+// few and narrow token tiles, spend their time re-reading z through L2 (measured on MI355X,
+// 16384 x 4096 x 8192: 38 us against 111 us at B = 32; 3072 x 768 x 1536: 24 us against 15 us).
 bool use_mid(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype, int64_t ldx) {
+    if (x_dtype != TSVD_BF16 || B < 2 || B > 64 || env_int("TSVD_MID", 1) == 0) return false;
     // (32-bit byte offsets into x in the kernel, which also addresses up to four slabs of 2048 rows
     // beyond the last one: the range check returns zeros there)
-    return x_dtype == TSVD_BF16 && B >= 2 && B <= 16 && env_int("TSVD_MID", 1) != 0 &&
-           ((uint64_t)h->hd.Np + 8192) * (uint64_t)ldx * 2 < (1ull << 31);
+    if (((uint64_t)h->hd.Np + 8192) * (uint64_t)ldx * 2 >= (1ull << 31)) return false;
+    if (B <= 16) return true;
+    const int forced = env_int("TSVD_MID_MAX_B", 0);       // tuning switch: largest B served here
+    if (forced > 0) return B <= forced;
+    // measured break-even against the batched kernels (aligned rows): 2, 3, 4 groups pay off from
+    // about 4, 11 and 20 MB of packed weights; unaligned rows take a slower batched kernel
+    static const double min_bytes[5] = {0.0, 0.0, 4.2e6, 11.2e6, 20.0e6};
+    const double code_bytes = (double)h->hd.Kp * (double)(h->hd.Mp + h->hd.Np) / 4.0;
+    const bool aligned = ldx % 8 == 0;
+    return code_bytes >= min_bytes[(B + 15) / 16] * (aligned ? 1.0 : 0.4);
 }
 
 size_t mid_workspace(const tsvd_handle* h) {
@@ -224,30 +237,34 @@ tsvd_status forward_mid(const tsvd_handle* h, const void* x, int64_t B, int64_t 
         a.kw_log2 = std::max(0, std::min(3, env_int("TSVD_MID_KWLOG2", kl)));
         while ((a.sw << a.kw_log2) > 16) --a.kw_log2;
     };
+    for (int64_t b0 = 0; b0 < B; b0 += 16) {
+    const int64_t nb = std::min<int64_t>(16, B - b0);
     tsvd_mid_args a;
     std::memset(&a, 0, sizeof a);
-    a.bvalid = (int)B;
+    a.bvalid = (int)nb;
     a.bound_V = h->bound_V;
     a.colmax = static_cast<float*>(ws);
+    a.clocks = h->clocks;
+    a.resident_ok = env_int("TSVD_MID_RESIDENT", 1) != 0;
     uint16_t* z = reinterpret_cast<uint16_t*>(static_cast<uint8_t*>(ws) + 256);
     if (mask & 2) {
         a.tiles = h->blob + hd.off_V;
         a.strips = (int)(hd.Kp / 16);
         a.nkt = (int)(hd.Np / 256);
-        a.act = static_cast<const uint16_t*>(x);
+        a.act = static_cast<const uint16_t*>(x) + b0;
         a.ld = ldx;
         a.kvalid = (int)hd.N;
         // extent of x, rounded up to the 4-byte granularity of the buffer range check (for odd B the
         // dword holding the last element would otherwise read as zero; it lies inside an aligned dword
         // whose first half is the caller's, so it cannot cross into an unmapped page)
-        a.act_bytes = (unsigned)((((((size_t)hd.N - 1) * (size_t)ldx + (size_t)B) * 2) + 3) & ~(size_t)3);
+        a.act_bytes = (unsigned)((((((size_t)hd.N - 1) * (size_t)ldx + (size_t)nb) * 2) + 3) & ~(size_t)3);
         a.S = reinterpret_cast<const float*>(h->blob + hd.off_S);
         a.out = z;
         a.ld_out = 16;
         a.rows_valid = (int)hd.Kp;
         shape(a);
-        const bool dma = ldx % 8 == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
-        if (tsvd_launch_mid(a, false, dma, stream) != hipSuccess) return TSVD_EDEVICE;
+        const bool vec = ldx % 8 == 0 && (reinterpret_cast<uintptr_t>(a.act) & 15u) == 0;
+        if (tsvd_launch_mid(a, false, vec, stream) != hipSuccess) return TSVD_EDEVICE;
     }
     if (mask & 4) {
         a.tiles = h->blob + hd.off_U;
@@ -258,11 +275,12 @@ tsvd_status forward_mid(const tsvd_handle* h, const void* x, int64_t B, int64_t 
         a.kvalid = (int)hd.Kp;
         a.act_bytes = (unsigned)((size_t)hd.Kp * 32);
         a.S = nullptr;
-        a.out = y;
+        a.out = y + b0;
         a.ld_out = ldy;
         a.rows_valid = (int)hd.M;
         shape(a);
         if (tsvd_launch_mid(a, true, true, stream) != hipSuccess) return TSVD_EDEVICE;
+    }
     }
     return TSVD_OK;
 }
@@ -379,9 +397,10 @@ extern "C" tsvd_status tsvd_info(const tsvd_handle* h, int64_t* M, int64_t* K, i
 
 extern "C" size_t tsvd_workspace_bytes(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype) {
     if (!h || B <= 0 || (x_dtype != TSVD_F32 && x_dtype != TSVD_BF16)) return 0;
-    if (use_gemm(h, B, x_dtype)) return gemm_workspace(h, B);
-    // (the few-token path is chosen per call, by the row stride too: cover both)
-    return round256(std::max(skinny_workspace(h), mid_workspace(h)));
+    // (the few-token path is chosen per call, by the row stride too: cover every candidate)
+    const size_t few = round256(std::max(skinny_workspace(h), mid_workspace(h)));
+    if (use_gemm(h, B, x_dtype)) return std::max(gemm_workspace(h, B), B <= 64 ? few : (size_t)0);
+    return few;
 }
 
 extern "C" tsvd_status tsvd_forward(const tsvd_handle* h, const void* x_dev, tsvd_dtype x_dtype, int64_t B,
@@ -417,6 +436,7 @@ extern "C" tsvd_status tsvd_forward(const tsvd_handle* h, const void* x_dev, tsv
         ws = hm->scratch;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (use_mid(h, B, x_dtype, ldx)) return forward_mid(h, x_dev, B, ldx, static_cast<float*>(y_dev), ldy, ws, s);
     if (use_gemm(h, B, x_dtype)) {
         tsvd_gemm_problem g;
         g.blob = h->blob;
@@ -432,7 +452,6 @@ extern "C" tsvd_status tsvd_forward(const tsvd_handle* h, const void* x_dev, tsv
         g.clocks = h->clocks;
         return tsvd_forward_gemm(g, s) == hipSuccess ? TSVD_OK : TSVD_EDEVICE;
     }
-    if (use_mid(h, B, x_dtype, ldx)) return forward_mid(h, x_dev, B, ldx, static_cast<float*>(y_dev), ldy, ws, s);
     return forward_skinny(h, x_dev, x_dtype, B, ldx, static_cast<float*>(y_dev), ldy, ws, s);
 }
 
@@ -443,6 +462,7 @@ extern "C" tsvd_status tsvd_forward(const tsvd_handle* h, const void* x_dev, tsv
 extern "C" int tsvd_internal_tile_shapes(const tsvd_handle* h, long long B, int* shape_v, int* shape_u) {
     if (!h || !shape_v || !shape_u || B < 1) return 1;
     *shape_v = *shape_u = -1;
+    if (use_mid(h, B, TSVD_BF16, tsvd_round_up(B, 8))) return 0;
     if (use_gemm(h, B, TSVD_BF16)) {
         const long long Bp = (long long)tsvd_round_up(B, 256);
         if (tsvd_gemm_use_panel(h->hd.Mp, h->hd.Kp, h->hd.Np, B, h->cu_count, true)) {

@@ -68,6 +68,8 @@ struct tsvd_mid_args {
     float* colmax;                        // [16] per-token max |x| (stage V writes, stage U reads)
     void* out; long long ld_out;          // stage V: z fp16 [Kp][16]; stage U: y fp32 [M][ld_out]
     int rows_valid;                       // stage U: M
+    long long* clocks;                    // optional tuning aid: [grid][16] phase timestamps (stage V 0..7, U 8..15), or null
+    int resident_ok;                      // tuning switch: 0 forces the slab hand-over loop for short contractions too
 };
 hipError_t tsvd_mid_init();
 hipError_t tsvd_launch_mid(const tsvd_mid_args& a, bool stage_u, bool vec, hipStream_t stream);

@@ -36,7 +36,7 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 #define MID_SLAB_TILES 8                                  // 256-wide tiles per slab
 #define MID_STAGE_BYTES 2048                              // 64 rows x 16 tokens x 2 bytes
 #define MID_SLAB_BYTES (MID_SLAB_TILES * 4 * MID_STAGE_BYTES)   // 64 KiB
-#define MID_LDS_BYTES (2 * MID_SLAB_BYTES + 256)
+#define MID_LDS_BYTES (2 * MID_SLAB_BYTES + 256 + 16384 + 512)   // slabs, token factors, maxima scratch
 #ifndef MID_LOOKAHEAD
 #define MID_LOOKAHEAD 2                                   // weight tiles per wavefront in flight
 #endif
@@ -95,7 +95,11 @@ __device__ __forceinline__ void unrolled(F& f, std::integer_sequence<int, U...>)
 // unconditional and at a fixed place of the unrolled body (slabs beyond the contraction length
 // are fetched as zeros by the range check, tiles beyond it are clamped re-reads that meet those
 // zeros), so the compiler's wait counts are exact and no wait drains the tiles still in flight.
-template <bool STAGE2, bool VEC, int LTS>
+// RES: the contraction is at most two slabs long, so all activations are fetched at once and stay
+// in LDS: no slab hand-over in the loop, and stage V reduces the token maxima while the first
+// weight tiles are still on their way (measured on the 16384 x 4096 x 8192 shape, stage V with one
+// tile per wavefront and slab: each hand-over waited a full L2 round trip, 6 us for two tiles).
+template <bool STAGE2, bool VEC, int LTS, bool RES>
 __global__ void __launch_bounds__(1024)
 tsvd_mid_kernel(tsvd_mid_args p) {
     constexpr int KWL = 3 - LTS, n_ts = 1 << LTS, kw = 1 << KWL;
@@ -103,10 +107,22 @@ tsvd_mid_kernel(tsvd_mid_args p) {
     float* cs_lds = reinterpret_cast<float*>(smem + 2 * MID_SLAB_BYTES);
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i = lane & 15, g = lane >> 4;
+    auto tick = [&](int n) {      // phase timestamps (100 MHz wall clock) of thread 0, for tuning
+        if (p.clocks && tid == 0 && blockIdx.x < TSVD_GEMV_MAX_GRID) p.clocks[blockIdx.x * 16 + (STAGE2 ? 8 : 0) + n] = wall_clock64();
+    };
+    tick(0);
     const int sidx = wave >> KWL, q = wave & (kw - 1);
     const int strip = min(blockIdx.x * p.sw + sidx, p.strips - 1);
     const u32x4* wp = reinterpret_cast<const u32x4*>(p.tiles) + (size_t)strip * p.nkt * 64 + lane;
     const int nslab = (p.nkt + MID_SLAB_TILES - 1) / MID_SLAB_TILES;
+    // operands of the epilogue, requested first: thread t finishes outputs t, t + 1024, ... (row
+    // (t >> 4) + 64 n of the workgroup, token t & 15)
+    float fin[4];
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+        if constexpr (STAGE2) fin[n] = n == 0 ? p.colmax[tid & 15] : 0.f;
+        else fin[n] = p.S[min((int)blockIdx.x * p.sw * 16 + (tid >> 4) + 64 * n, p.strips * 16 - 1)];
+    }
 
     // ---- slab fetch: thread t owns the 16-byte chunks t, t + 1024, t + 2048, t + 3072 of a slab
     // (chunk c: stage c >> 7, position (c >> 1) & 63, half c & 1)
@@ -116,12 +132,12 @@ tsvd_mid_kernel(tsvd_mid_args p) {
     const int x_voff = kk * (int)p.ld * 2 + half * 16;
     const __amdgpu_buffer_rsrc_t act_rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.act), 0, p.act_bytes, 0x00020000);
-    u32x4 xreg[4];
-    auto fetch_slab = [&](int s) {
+    u32x4 xreg[4], xreg2[4];
+    auto fetch_slab = [&](int s, u32x4 (&xr)[4]) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             if constexpr (VEC) {
-                xreg[j] = __builtin_amdgcn_raw_buffer_load_b128(act_rsrc, x_voff, (s * 2048 + 512 * j) * (int)p.ld * 2, 0);
+                xr[j] = __builtin_amdgcn_raw_buffer_load_b128(act_rsrc, x_voff, (s * 2048 + 512 * j) * (int)p.ld * 2, 0);
             } else {
                 const int k = s * 2048 + 512 * j + kk;
                 uint32_t e[8];
@@ -130,21 +146,46 @@ tsvd_mid_kernel(tsvd_mid_args p) {
                     const bool ok = k < p.kvalid && 8 * half + t < p.bvalid;
                     e[t] = ok ? (uint32_t)p.act[(size_t)(ok ? k : 0) * p.ld + (ok ? 8 * half + t : 0)] : 0u;
                 }
-                xreg[j] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+                xr[j] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
             }
         }
     };
     // the fetched slab goes to LDS; stage V also keeps running maxima of |x| over this thread's
     // chunks (tokens 8 half .. 8 half + 7, packed pairs)
     u32x4 cmax = {0u, 0u, 0u, 0u};
-    auto commit_slab = [&](int s) {
+    auto commit_slab = [&](int s, const u32x4 (&xr)[4]) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            *reinterpret_cast<u32x4*>(smem + (s & 1) * MID_SLAB_BYTES + j * 16384 + tid * 16) = xreg[j];
+            *reinterpret_cast<u32x4*>(smem + (s & 1) * MID_SLAB_BYTES + j * 16384 + tid * 16) = xr[j];
             if constexpr (!STAGE2)
-                cmax = u32x4{pk_max_u16(cmax.x, xreg[j].x & 0x7FFF7FFFu), pk_max_u16(cmax.y, xreg[j].y & 0x7FFF7FFFu),
-                             pk_max_u16(cmax.z, xreg[j].z & 0x7FFF7FFFu), pk_max_u16(cmax.w, xreg[j].w & 0x7FFF7FFFu)};
+                cmax = u32x4{pk_max_u16(cmax.x, xr[j].x & 0x7FFF7FFFu), pk_max_u16(cmax.y, xr[j].y & 0x7FFF7FFFu),
+                             pk_max_u16(cmax.z, xr[j].z & 0x7FFF7FFFu), pk_max_u16(cmax.w, xr[j].w & 0x7FFF7FFFu)};
         }
+    };
+    // stage V: token maxima over all threads -> per-token factors in LDS (three barriers)
+    u32x4* cm = reinterpret_cast<u32x4*>(smem + 2 * MID_SLAB_BYTES + 256);          // [1024]
+    uint32_t* cm2 = reinterpret_cast<uint32_t*>(smem + 2 * MID_SLAB_BYTES + 256 + 16384);   // [128]
+    auto reduce_maxima = [&]() {
+        cm[tid] = cmax;
+        __syncthreads();
+        // threads of parity h hold tokens 8 h + 2 w (low half of word w) and 8 h + 2 w + 1 (high half)
+        if (tid < 128) {
+            const int h = tid & 1, w = (tid >> 1) & 3, part = tid >> 3;
+            const uint32_t* cw = reinterpret_cast<const uint32_t*>(cm);
+            uint32_t best = 0;
+            for (int n = 0; n < 32; ++n) best = pk_max_u16(best, cw[(2 * (part * 32 + n) + h) * 4 + w]);
+            cm2[tid] = best;
+        }
+        __syncthreads();
+        if (tid < 16) {
+            const int h = tid >> 3, w = (tid & 7) >> 1;
+            uint32_t best = 0;
+            for (int part = 0; part < 16; ++part) best = pk_max_u16(best, cm2[(part << 3) | (w << 1) | h]);
+            const float mx = __uint_as_float(((tid & 1) ? (best >> 16) : (best & 0xFFFFu)) << 16);
+            cs_lds[tid] = ldexpf(1.0f, scale_exponent(mx, p.bound_V) - 1);   // 1/2 undoes the +-2 of the codes
+            if (blockIdx.x == 0) p.colmax[tid] = mx;
+        }
+        __syncthreads();
     };
 
     // ---- operand reads: lane (i, g) of a transposed read supplies the address of row
@@ -178,79 +219,81 @@ tsvd_mid_kernel(tsvd_mid_args p) {
     constexpr int LA = MID_LOOKAHEAD, ROUND = n_ts > 4 ? n_ts : 4;
     static_assert(LA >= 1 && LA <= 3, "lookahead");
     u32x4 wbuf[4];
-    const int steps = ((nslab << LTS) + ROUND - 1) / ROUND * ROUND;
-    fetch_slab(0);
-    __builtin_amdgcn_sched_barrier(0);        // slab first: the same request order as inside the loop
+    const int steps_valid = nslab << LTS;
+    const int steps = (steps_valid + ROUND - 1) / ROUND * ROUND;
+    fetch_slab(0, xreg);
+    if constexpr (RES) fetch_slab(1, xreg2);
+    __builtin_amdgcn_sched_barrier(0);        // activations first: the same request order as inside the loop
 #pragma unroll
     for (int n = 0; n < LA; ++n) wbuf[n] = __builtin_nontemporal_load(wp + (size_t)min(q + n * kw, p.nkt - 1) * 64);
+    tick(1);
+    if constexpr (RES) {
+        commit_slab(0, xreg);
+        commit_slab(1, xreg2);
+        __syncthreads();
+        if constexpr (!STAGE2) reduce_maxima();
+    }
     for (int m0 = 0; m0 < steps; m0 += ROUND) {
         auto step = [&](auto uc) {
             constexpr int u = decltype(uc)::value;
             const int m = m0 + u, s = m >> LTS, T = q + (m << KWL);
-            if constexpr ((u & (n_ts - 1)) == 0) {
-                commit_slab(s);
+            if constexpr (!RES && (u & (n_ts - 1)) == 0) {
+                commit_slab(s, xreg);
                 __syncthreads();                   // slab s complete; nobody reads slab s - 1 any more
-                fetch_slab(s + 1);
+                fetch_slab(s + 1, xreg);
             }
             __builtin_amdgcn_sched_barrier(0);
             wbuf[(u + LA) % 4] = __builtin_nontemporal_load(wp + (size_t)min(T + LA * kw, p.nkt - 1) * 64);
-            tile(wbuf[u % 4], smem + (s & 1) * MID_SLAB_BYTES + (T & (MID_SLAB_TILES - 1)) * (4 * MID_STAGE_BYTES));
+            const unsigned char* tb = smem + (s & 1) * MID_SLAB_BYTES + (T & (MID_SLAB_TILES - 1)) * (4 * MID_STAGE_BYTES);
+            if constexpr (RES) {
+                if (m < steps_valid) tile(wbuf[u % 4], tb);     // (no third slab to meet the padding steps)
+            } else {
+                tile(wbuf[u % 4], tb);
+            }
         };
         unrolled(step, std::make_integer_sequence<int, ROUND>{});
     }
+    tick(2);
     __syncthreads();
+    tick(3);
 
     // ---- reduce the contraction splits through LDS (the slabs are dead), finish, store
     float* red = reinterpret_cast<float*>(smem);                      // [16 wavefronts][16 rows][16 tokens]
-    u32x4* cm = reinterpret_cast<u32x4*>(smem + 16384);               // [1024]
-    uint32_t* cm2 = reinterpret_cast<uint32_t*>(smem + 32768);        // [128]
     // result block of the MFMA: lane (i, g) holds token i, weight rows 4 g + v
 #pragma unroll
     for (int v = 0; v < 4; ++v) red[wave * 256 + (4 * g + v) * 16 + i] = acc0[v] + acc1[v];
-    if constexpr (!STAGE2) cm[tid] = cmax;
-    __syncthreads();
-    if constexpr (!STAGE2) {
-        // threads of parity h hold tokens 8 h + 2 w (low half of word w) and 8 h + 2 w + 1 (high half)
-        if (tid < 128) {
-            const int h = tid & 1, w = (tid >> 1) & 3, part = tid >> 3;
-            const uint32_t* cw = reinterpret_cast<const uint32_t*>(cm);
-            uint32_t best = 0;
-            for (int n = 0; n < 32; ++n) best = pk_max_u16(best, cw[(2 * (part * 32 + n) + h) * 4 + w]);
-            cm2[tid] = best;
-        }
-        __syncthreads();
-        if (tid < 16) {
-            const int h = tid >> 3, w = (tid & 7) >> 1;
-            uint32_t best = 0;
-            for (int part = 0; part < 16; ++part) best = pk_max_u16(best, cm2[(part << 3) | (w << 1) | h]);
-            const float mx = __uint_as_float(((tid & 1) ? (best >> 16) : (best & 0xFFFFu)) << 16);
-            cs_lds[tid] = ldexpf(1.0f, scale_exponent(mx, p.bound_V) - 1);   // 1/2 undoes the +-2 of the codes
-            if (blockIdx.x == 0) p.colmax[tid] = mx;
-        }
-        __syncthreads();
-    }
-    for (int idx = tid; idx < p.sw * 256; idx += 1024) {
-        const int rl = idx >> 4, tok = idx & 15;
-        const float* src = red + (size_t)((rl >> 4) * kw) * 256 + (rl & 15) * 16 + tok;
-        float sum = 0.f;
-        for (int c = 0; c < kw; ++c) sum += src[c * 256];
-        const int row = blockIdx.x * p.sw * 16 + rl;
-        if constexpr (STAGE2) {
-            if (row < p.rows_valid && tok < p.bvalid) {
-                const float f = ldexpf(1.0f, -scale_exponent(p.colmax[tok], p.bound_V) - 1);
-                static_cast<float*>(p.out)[(size_t)row * p.ld_out + tok] = sum * f;
+    if constexpr (!STAGE2 && !RES) reduce_maxima();      // (its first barrier also publishes red)
+    else __syncthreads();
+    tick(4);
+    const int tok = tid & 15;
+    const float ftok = STAGE2 ? ldexpf(1.0f, -scale_exponent(fin[0], p.bound_V) - 1) : cs_lds[tok];
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+        const int rl = (tid >> 4) + 64 * n;                    // row within the workgroup
+        if (rl < p.sw * 16) {
+            const float* src = red + (size_t)((rl >> 4) * kw) * 256 + (rl & 15) * 16 + tok;
+            float sum = 0.f;
+#pragma unroll
+            for (int c = 0; c < kw; ++c) sum += src[c * 256];
+            const int row = blockIdx.x * p.sw * 16 + rl;
+            if constexpr (STAGE2) {
+                if (row < p.rows_valid && tok < p.bvalid) static_cast<float*>(p.out)[(size_t)row * p.ld_out + tok] = sum * ftok;
+            } else {
+                if (row < p.strips * 16)   // S is zero beyond K: padded rows of z are written as zeros
+                    static_cast<_Float16*>(p.out)[(size_t)row * 16 + tok] = (_Float16)((sum * fin[n]) * ftok);
             }
-        } else {
-            if (row < p.strips * 16)       // S is zero beyond K: padded rows of z are written as zeros
-                static_cast<_Float16*>(p.out)[(size_t)row * 16 + tok] = (_Float16)((sum * p.S[row]) * cs_lds[tok]);
         }
     }
+    tick(5);
 }
 
 namespace {
 template <bool STAGE2, bool VEC, int LTS>
 hipError_t init_one() {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_mid_kernel<STAGE2, VEC, LTS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_mid_kernel<STAGE2, VEC, LTS, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, MID_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_mid_kernel<STAGE2, VEC, LTS, true>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, MID_LDS_BYTES);
 }
 template <bool STAGE2, bool VEC>
@@ -264,12 +307,19 @@ hipError_t init_all() {
 template <bool STAGE2, bool VEC>
 void launch(const tsvd_mid_args& a, dim3 grid, hipStream_t stream) {
     const dim3 block(1024);
+    const bool res = a.nkt <= 2 * MID_SLAB_TILES && a.resident_ok;
+#define MID_LAUNCH(LTS)                                                                                              \
+    do {                                                                                                             \
+        if (res) hipLaunchKernelGGL((tsvd_mid_kernel<STAGE2, VEC, LTS, true>), grid, block, MID_LDS_BYTES, stream, a);  \
+        else hipLaunchKernelGGL((tsvd_mid_kernel<STAGE2, VEC, LTS, false>), grid, block, MID_LDS_BYTES, stream, a);     \
+    } while (0)
     switch (3 - a.kw_log2) {
-        case 0: hipLaunchKernelGGL((tsvd_mid_kernel<STAGE2, VEC, 0>), grid, block, MID_LDS_BYTES, stream, a); break;
-        case 1: hipLaunchKernelGGL((tsvd_mid_kernel<STAGE2, VEC, 1>), grid, block, MID_LDS_BYTES, stream, a); break;
-        case 2: hipLaunchKernelGGL((tsvd_mid_kernel<STAGE2, VEC, 2>), grid, block, MID_LDS_BYTES, stream, a); break;
-        default: hipLaunchKernelGGL((tsvd_mid_kernel<STAGE2, VEC, 3>), grid, block, MID_LDS_BYTES, stream, a); break;
+        case 0: MID_LAUNCH(0); break;
+        case 1: MID_LAUNCH(1); break;
+        case 2: MID_LAUNCH(2); break;
+        default: MID_LAUNCH(3); break;
     }
+#undef MID_LAUNCH
 }
 }  // namespace
 

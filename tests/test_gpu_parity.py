@@ -134,10 +134,13 @@ def test_larger_small_problem_uses_wider_ring_tiles(tsvd):
 
 # ---- few-token kernel (2 <= B <= 16, bf16): contraction lengths of several LDS slabs with a ragged
 # ---- last one, every contraction split, aligned rows (vector loads) and unaligned rows (gather)
+# ---- (contractions of at most two slabs normally stay resident in LDS; "0" sends them through the hand-over loop too)
+@pytest.mark.parametrize("resident", ["1", "0"])
 @pytest.mark.parametrize("kwlog2", ["0", "1", "2", "3"])
 @pytest.mark.parametrize("M,N,K,B", [(100, 2300, 4500, 16), (530, 270, 5000, 8), (70, 6000, 300, 7), (200, 4100, 2049, 2)])
-def test_few_token_kernel(tsvd, M, N, K, B, kwlog2, monkeypatch):
+def test_few_token_kernel(tsvd, M, N, K, B, kwlog2, resident, monkeypatch):
     import torch
+    monkeypatch.setenv("TSVD_MID_RESIDENT", resident)
     monkeypatch.setenv("TSVD_MID_KWLOG2", kwlog2)
     monkeypatch.setenv("TSVD_MID_SW", "2")
     i = workloads.make_integer_inputs(M, N, K, B, 0.5, "bf16", seed=31 + M + B)
@@ -161,6 +164,28 @@ def test_few_token_kernel(tsvd, M, N, K, B, kwlog2, monkeypatch):
     y3 = tsvd.tsvd_forward(h, to_device(i)).cpu().numpy().astype(np.float64)
     tsvd.tsvd_free(h)
     assert rel_err(y3, ref) <= 1e-5 and rel_err(y, y3) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("B", [17, 40, 64])
+def test_few_token_kernel_in_groups(tsvd, B, monkeypatch):
+    """Up to 64 tokens go through the few-token kernel in groups of 16 when the weights are large;
+    forced here on a small instance (exact, then random against the oracle and the batched path)."""
+    monkeypatch.setenv("TSVD_MID_MAX_B", "64")
+    i = workloads.make_integer_inputs(150, 300, 2100, B, 0.5, "bf16", seed=41 + B)
+    print(f"case few-token groups int B={B}", flush=True)
+    y, h = run_forward(i)
+    tsvd.tsvd_free(h)
+    assert np.array_equal(y, oracle.forward(i.U, i.S, i.V, i.X))
+    i = workloads.make_inputs(150, 300, 2100, B, 0.6, 0.02, "bf16", seed=42 + B)
+    print(f"case few-token groups rand B={B}", flush=True)
+    ref = oracle.forward(i.U, i.S, i.V, i.X)
+    y, h = run_forward(i)
+    assert not np.isnan(y).any()
+    assert rel_err(y, ref) <= TOL["bf16"]
+    monkeypatch.setenv("TSVD_MID_MAX_B", "16")
+    y2 = tsvd.tsvd_forward(h, to_device(i)).cpu().numpy().astype(np.float64)
+    tsvd.tsvd_free(h)
+    assert rel_err(y2, ref) <= TOL["bf16"] and rel_err(y, y2) <= 1e-5    # same arithmetic, other summation order
 
 
 def test_activation_scale_extremes_few_tokens(tsvd):
