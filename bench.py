@@ -34,7 +34,8 @@ PRIMARY = "bert_ffn_in"
 # inside this process; the figures belong to the launch shapes bench.py uses.
 PANEL_TRAFFIC_BYTES = {"convnext_mlp": 18.4e6 + 102.8e6}   # token-panel launches, same profile
 STAGE_U_TRAFFIC_BYTES = {"bert_ffn_in": 11.1e6 + 6.29e6, "convnext_mlp": 186e6 + 102.8e6,
-                         "opt66b_fc1_prefill": 2021e6 + 302.0e6, "opt6b7_fc1_decode": 34.2e6 + 0.066e6}
+                         "opt66b_fc1_prefill": 2021e6 + 302.0e6, "opt6b7_fc1_decode": 34.2e6 + 0.066e6,
+                         "opt6b7_fc1_decode_b16": 35.9e6 + 1.05e6}
 
 
 def _device_x(inputs, dev):
@@ -159,6 +160,8 @@ def bench_workload(name, steps, warmup, with_cpu=True, cpu_budget_s=4.0):
     _set_stage_mask(2)
     _, v_ms = _timed(step_rot, steps, max(2, warmup // 2))
     _set_stage_mask(None)
+    step_rot()                      # a full pass again: y is compared with the oracle below
+    torch.cuda.synchronize()
     res["stage_ms"] = {"V": v_ms, "U": u_ms}
     kernel_name = _stage_u_kernel_name(tsvd, handles[0], w.B) if batched else None
     if batched and kernel_name == "tsvd_panel_kernel":
@@ -180,12 +183,14 @@ def bench_workload(name, steps, warmup, with_cpu=True, cpu_budget_s=4.0):
     else:
         xb = 2 if w.x_dtype == "bf16" else 4
         kp = -(-w.K // 256) * 256
-        bytes_alg = w.K * (w.M + w.N) / 4.0 + 4.0 * w.K + w.N * xb + 4.0 * w.M
-        bytes_u = w.K * w.M / 4.0 + 8.0 * kp + 4.0 * w.M          # codes of U + digit planes of z + y
+        bytes_alg = w.K * (w.M + w.N) / 4.0 + 4.0 * w.K + w.N * xb * w.B + 4.0 * w.M * w.B
+        few = w.B > 1                                             # few-token kernel: z is fp16 [Kp][16]
+        # codes of U + z (B = 1: 8 digit planes of Kp bytes; few tokens: fp16 [Kp][16]) + y
+        bytes_u = w.K * w.M / 4.0 + (32.0 * kp if few else 8.0 * kp) + 4.0 * w.M * w.B
         _, warm_ev = _timed(step_one, steps, warmup)
         res["cache_warm_event_ms"] = warm_ev
         gbs = bytes_u / (u_ms * 1e-3) / 1e9
-        res["roofline"] = {"bound": "hbm", "kernel": "tsvd_gemv_kernel (stage U)",
+        res["roofline"] = {"bound": "hbm", "kernel": "tsvd_mid_kernel (stage U)" if few else "tsvd_gemv_kernel (stage U)",
                            "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
                            "traffic": STAGE_U_TRAFFIC_BYTES.get(name), "algorithmic_bytes": bytes_u,
                            "whole_path_gbs": bytes_alg / (ev_ms * 1e-3) / 1e9,
@@ -207,7 +212,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workloads", default="bert_ffn_in,tiny,convnext_mlp,opt6b7_fc1_decode,opt66b_fc1_prefill")
+    ap.add_argument("--workloads",
+                    default="bert_ffn_in,tiny,convnext_mlp,opt6b7_fc1_decode,opt6b7_fc1_decode_b16,opt66b_fc1_prefill")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing / parity leg")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for FETCH_SIZE / WRITE_SIZE counters)")

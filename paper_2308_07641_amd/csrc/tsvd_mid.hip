@@ -241,6 +241,8 @@ tsvd_mid_kernel(tsvd_mid_args p) {
                 commit_slab(s, xreg);
                 __syncthreads();                   // slab s complete; nobody reads slab s - 1 any more
                 fetch_slab(s + 1, xreg);
+                if (s == 0) tick(6);
+                if (s == nslab - 1) tick(7);
             }
             __builtin_amdgcn_sched_barrier(0);
             wbuf[(u + LA) % 4] = __builtin_nontemporal_load(wp + (size_t)min(T + LA * kw, p.nkt - 1) * 64);

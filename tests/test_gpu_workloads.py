@@ -1,4 +1,4 @@
-"""GPU parity on the five named workloads at full size, in the launch configuration bench.py
+"""GPU parity on the named workloads at full size, in the launch configuration bench.py
 times.  Where the full output is too much work for the CPU oracle, a seeded subset of tokens
 (columns are independent, so this checks those columns exactly) including tile-boundary
 columns is compared."""
@@ -26,6 +26,7 @@ def _columns(B, count, seed):
     ("convnext_mlp", 384, 2e-3),
     ("opt6b7_fc1_decode", None, 2e-3),
     ("opt66b_fc1_prefill", 24, 2e-3),
+    ("opt6b7_fc1_decode_b16", None, 2e-3),
 ])
 def test_named_workload(name, ncols, tol):
     import paper_2308_07641_amd as tsvd

@@ -43,6 +43,8 @@ WORKLOADS = {
         Workload("convnext_mlp", 3, 2048, 512, 1024, 12544, 0.6, 0.02, "bf16"),
         Workload("opt6b7_fc1_decode", 4, 16384, 4096, 8192, 1, 0.6, 0.01, "bf16"),
         Workload("opt66b_fc1_prefill", 5, 36864, 9216, 18432, 2048, 0.6, 0.01, "bf16"),
+        # the decode layer with a small batch of tokens (measurement case of the few-token path)
+        Workload("opt6b7_fc1_decode_b16", 6, 16384, 4096, 8192, 16, 0.6, 0.01, "bf16"),
     )
 }
 
