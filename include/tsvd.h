@@ -35,6 +35,9 @@ typedef enum {
 } tsvd_status;
 
 typedef enum { TSVD_F32 = 0, TSVD_BF16 = 1 } tsvd_dtype;
+/* Layout of the activations: feature-major x[n][b] (the paper's column vectors side by side) or
+ * token-major x[b][n] (one row per token). */
+typedef enum { TSVD_FEATURE_MAJOR = 0, TSVD_TOKEN_MAJOR = 1 } tsvd_layout;
 
 /* ---- packing: the 2-bit ternary weight format ------------------------------------------
  *
@@ -86,7 +89,8 @@ tsvd_status tsvd_info(const tsvd_handle* h, int64_t* M, int64_t* K, int64_t* N,
  * identity: t = V x (additions), z = S * t (the K multiplications), y = U z (additions).
  *
  *   x_dev : device, [N][B] row-major with row stride ldx >= B elements of x_dtype.
- *   y_dev : device, [M][B] row-major with row stride ldy >= B; y_dtype must be TSVD_F32.
+ *   y_dev : device, [M][B] row-major with row stride ldy >= B elements of y_dtype (TSVD_F32, or
+ *           TSVD_BF16: the fp32 result rounded to nearest even).
  *   workspace : device scratch for the intermediate z, at least
  *               tsvd_workspace_bytes(h, B, x_dtype) bytes, 256-byte aligned; contents
  *               are undefined afterwards.  NULL (with workspace_bytes 0) makes the library
@@ -105,6 +109,29 @@ size_t tsvd_workspace_bytes(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype)
 tsvd_status tsvd_forward(const tsvd_handle* h, const void* x_dev, tsvd_dtype x_dtype,
                          int64_t B, int64_t ldx, void* y_dev, tsvd_dtype y_dtype, int64_t ldy,
                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- forward with the options of a linear layer -----------------------------------------
+ *
+ * Y = U (diag(S) (V X)) + bias: the same three steps, then the bias of the layer (the paper's
+ * listing of a converted network in the supplement shows its ternary-SVD linear layers with
+ * bias=True) added to every token, fused into the last kernel of the call.
+ *
+ *   x_layout : TSVD_FEATURE_MAJOR: x_dev is [N][B], ldx >= B (as tsvd_forward);
+ *              TSVD_TOKEN_MAJOR:   x_dev is [B][N], ldx >= N; the call first rewrites it
+ *              feature-major into the workspace (one extra pass over x), then proceeds as above.
+ *   bias_dev : device fp32 [M], or NULL for none.
+ *   y_dev    : [M][B] with row stride ldy >= B, TSVD_F32 or TSVD_BF16 (rounded to nearest even
+ *              from the fp32 value after the bias).
+ *   workspace: at least tsvd_workspace_bytes_ex(h, B, x_dtype, x_layout) bytes, 256-byte aligned,
+ *              or NULL (with workspace_bytes 0) for scratch owned by the handle.
+ * Everything else (ownership, stream, errors, arithmetic) is as for tsvd_forward, which is this
+ * call with a feature-major x and no bias.
+ */
+size_t tsvd_workspace_bytes_ex(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype, tsvd_layout x_layout);
+
+tsvd_status tsvd_forward_ex(const tsvd_handle* h, const void* x_dev, tsvd_dtype x_dtype, tsvd_layout x_layout,
+                            int64_t B, int64_t ldx, const float* bias_dev, void* y_dev, tsvd_dtype y_dtype,
+                            int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Releases the handle and whatever device memory it owns.  NULL is allowed. */
 void tsvd_free(tsvd_handle* h);

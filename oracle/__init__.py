@@ -4,6 +4,6 @@ Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
 this package.  It shares nothing with the GPU library.
 """
 from .tsvd_oracle import (  # noqa: F401
-    build, forward, forward_columns, op_counts, acceleration, critical_rank,
-    threads,
+    build, forward, forward_columns, forward_layer, round_to_bf16, op_counts, acceleration,
+    critical_rank, threads,
 )

@@ -94,6 +94,46 @@ def forward_columns(U, S, V, X, cols) -> np.ndarray:
     return forward(U, S, V, X[:, np.asarray(cols, dtype=np.int64)])
 
 
+def round_to_bf16(y) -> np.ndarray:
+    """Nearest bf16 value (8 significant bits, ties to even) of each fp64 entry, as fp64.
+
+    Written from the definition of the format: split off the binary exponent, round the
+    significand to 8 bits with the ties-to-even rule of np.rint, put the exponent back.
+    Values below the bf16 normal range (2^-126) are rounded on the fixed subnormal grid 2^-133.
+    """
+    y = np.asarray(y, dtype=np.float64)
+    m, e = np.frexp(y)                                  # y = m * 2^e, 0.5 <= |m| < 1
+    e = np.maximum(e, -125)                             # subnormals share the exponent of 2^-126
+    m = y / np.ldexp(1.0, e)
+    return np.ldexp(np.rint(np.ldexp(m, 8)), e - 8)
+
+
+def forward_layer(U, S, V, X, bias=None, x_layout="feature_major", y_dtype="f32") -> np.ndarray:
+    """The map as a linear layer uses it: Y = U (diag(S) (V X)) + bias, per token.
+
+    The paper's listing of a converted network (supplement) shows its ternary-SVD linear
+    layers with bias=True: the bias [M] is added to every token's output.  x_layout
+    "token_major" takes X as [B,N] (one row per token).  y_dtype "bf16" rounds the result
+    (after the bias) to the nearest bf16 value; the return is always [M,B] float64.
+    """
+    X = np.asarray(X)
+    if x_layout == "token_major":
+        X = X.T
+    elif x_layout != "feature_major":
+        raise ValueError("x_layout")
+    Y = forward(U, S, V, X)
+    if bias is not None:
+        b = np.asarray(bias, dtype=np.float64)
+        if b.shape != (Y.shape[0],):
+            raise ValueError("bias must be [M]")
+        Y = Y + b[:, None]
+    if y_dtype == "bf16":
+        Y = round_to_bf16(Y)
+    elif y_dtype != "f32":
+        raise ValueError("y_dtype")
+    return Y
+
+
 def op_counts(U, V) -> dict:
     """Per-token operation counts of supplement Table S1 for given U, V."""
     U = np.asarray(U)

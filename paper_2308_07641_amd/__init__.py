@@ -4,7 +4,7 @@ Thin Python binding over the C-ABI library libtsvd.so (see include/tsvd.h).  The
 only marshals arguments: every step of the computation runs in the HIP kernels.
 """
 from .tsvd import (  # noqa: F401
-    TSVD_F32, TSVD_BF16, TsvdError, Handle, lib_path, load_library,
+    TSVD_F32, TSVD_BF16, TSVD_FEATURE_MAJOR, TSVD_TOKEN_MAJOR, TsvdError, Handle, lib_path, load_library,
     tsvd_packed_bytes, tsvd_pack_host, tsvd_unpack_host, tsvd_pack, tsvd_unpack, tsvd_info,
-    tsvd_workspace_bytes, tsvd_forward, tsvd_free, tsvd_strerror,
+    tsvd_workspace_bytes, tsvd_forward, tsvd_workspace_bytes_ex, tsvd_forward_ex, tsvd_free, tsvd_strerror,
 )

@@ -33,6 +33,33 @@ int env_int(const char* name, int fallback) {
 
 size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 
+// Options of the last stage (tsvd_forward_ex).
+struct out_opts {
+    const float* bias;   // device [M] or null
+    int out_bf16;
+};
+
+// Token-major activations [B][ldx] -> feature-major [N][ldt] (ldt a multiple of 8 elements, the
+// padding columns zero), through 32 x 32 LDS tiles; T is the 16- or 32-bit storage type.
+template <typename T>
+__global__ void __launch_bounds__(256)
+tsvd_transpose_kernel(const T* __restrict__ x, long long ldx, int B, int N, T* __restrict__ xt, long long ldt) {
+    __shared__ T tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;          // 32 x 8 threads
+    const int n0 = blockIdx.x * 32, b0 = blockIdx.y * 32;
+#pragma unroll
+    for (int r = ty; r < 32; r += 8) {
+        const int b = b0 + r, n = n0 + tx;
+        tile[r][tx] = (b < B && n < N) ? x[(size_t)b * ldx + n] : T(0);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = ty; r < 32; r += 8) {
+        const int n = n0 + r, b = b0 + tx;
+        if (n < N && b < ldt) xt[(size_t)n * ldt + b] = tile[tx][r];
+    }
+}
+
 // One-time, per-device kernel attribute setup.
 hipError_t device_init(int device) {
     static bool done[64] = {};
@@ -83,8 +110,8 @@ int pow2_floor(int64_t v) {
 }
 
 // One token through the tsvd_gemv kernels; returns false if the shape does not fit them.
-bool try_gemv(const tsvd_handle* h, const void* x, tsvd_dtype x_dtype, int64_t ldx, float* y, int64_t ldy,
-              int* meta, unsigned char* planes, hipStream_t stream, tsvd_status* st) {
+bool try_gemv(const tsvd_handle* h, const void* x, tsvd_dtype x_dtype, int64_t ldx, void* y, int64_t ldy,
+              const out_opts& oo, int* meta, unsigned char* planes, hipStream_t stream, tsvd_status* st) {
     const tsvd_blob_header& hd = h->hd;
     if (env_int("TSVD_GEMV", 1) == 0 || !tsvd_gemv_fits(hd.Np, hd.Kp)) return false;
     const int mask = tsvd_stage_mask();
@@ -129,6 +156,8 @@ bool try_gemv(const tsvd_handle* h, const void* x, tsvd_dtype x_dtype, int64_t l
         a.planes_in = planes;
         a.y = y;
         a.ldy = ldy;
+        a.bias = oo.bias;
+        a.out_bf16 = oo.out_bf16;
         shape(a);
         if (tsvd_launch_gemv(a, true, stream) != hipSuccess) {
             *st = TSVD_EDEVICE;
@@ -140,7 +169,8 @@ bool try_gemv(const tsvd_handle* h, const void* x, tsvd_dtype x_dtype, int64_t l
 }
 
 tsvd_status forward_skinny(const tsvd_handle* h, const void* x, tsvd_dtype x_dtype, int64_t B, int64_t ldx,
-                           float* y, int64_t ldy, void* ws, hipStream_t stream) {
+                           void* y, int64_t ldy, const out_opts& oo, void* ws, hipStream_t stream) {
+    const size_t yelt = oo.out_bf16 ? 2 : 4;
     const tsvd_blob_header& hd = h->hd;
     int* meta = static_cast<int*>(ws);
     unsigned char* planes = static_cast<unsigned char*>(ws) + 256;
@@ -150,8 +180,8 @@ tsvd_status forward_skinny(const tsvd_handle* h, const void* x, tsvd_dtype x_dty
         // one token at a time through the fast kernels (each pass re-reads the weights)
         for (int64_t b0 = 0; b0 < B; ++b0) {
             tsvd_status gst = TSVD_OK;
-            if (!try_gemv(h, static_cast<const uint8_t*>(x) + (size_t)b0 * xelt, x_dtype, ldx, y + b0, ldy, meta, planes,
-                          stream, &gst))
+            if (!try_gemv(h, static_cast<const uint8_t*>(x) + (size_t)b0 * xelt, x_dtype, ldx,
+                          static_cast<uint8_t*>(y) + (size_t)b0 * yelt, ldy, oo, meta, planes, stream, &gst))
                 return TSVD_EUNSUPPORTED;
             if (gst != TSVD_OK) return gst;
         }
@@ -189,9 +219,11 @@ tsvd_status forward_skinny(const tsvd_handle* h, const void* x, tsvd_dtype x_dty
         u.ld_in = hd.Kp;
         u.tokens = tokens;
         u.meta_in = meta;
-        u.out = y + b0;
+        u.out = static_cast<uint8_t*>(y) + (size_t)b0 * yelt;
         u.ld_out = ldy;
         u.rows_out = (int)hd.M;
+        u.bias = oo.bias;
+        u.out_bf16 = oo.out_bf16;
         shape_skinny(u);
         if ((mask & 4) && tsvd_launch_skinny(u, stream) != hipSuccess) return TSVD_EDEVICE;
     }
@@ -223,8 +255,8 @@ size_t mid_workspace(const tsvd_handle* h) {
     return 256 + (size_t)32 * (size_t)h->hd.Kp;      // per-token maxima, then z fp16 [Kp][16]
 }
 
-tsvd_status forward_mid(const tsvd_handle* h, const void* x, int64_t B, int64_t ldx, float* y, int64_t ldy, void* ws,
-                        hipStream_t stream) {
+tsvd_status forward_mid(const tsvd_handle* h, const void* x, int64_t B, int64_t ldx, void* y, int64_t ldy,
+                        const out_opts& oo, void* ws, hipStream_t stream) {
     const tsvd_blob_header& hd = h->hd;
     const int mask = tsvd_stage_mask();
     // about one workgroup of 16 wavefronts per compute unit: sw strips x kw contraction splits
@@ -275,9 +307,11 @@ tsvd_status forward_mid(const tsvd_handle* h, const void* x, int64_t B, int64_t 
         a.kvalid = (int)hd.Kp;
         a.act_bytes = (unsigned)((size_t)hd.Kp * 32);
         a.S = nullptr;
-        a.out = y + b0;
+        a.out = static_cast<uint8_t*>(y) + (size_t)b0 * (oo.out_bf16 ? 2 : 4);
         a.ld_out = ldy;
         a.rows_valid = (int)hd.M;
+        a.bias = oo.bias;
+        a.out_bf16 = oo.out_bf16;
         shape(a);
         if (tsvd_launch_mid(a, true, true, stream) != hipSuccess) return TSVD_EDEVICE;
     }
@@ -395,22 +429,39 @@ extern "C" tsvd_status tsvd_info(const tsvd_handle* h, int64_t* M, int64_t* K, i
     return TSVD_OK;
 }
 
-extern "C" size_t tsvd_workspace_bytes(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype) {
-    if (!h || B <= 0 || (x_dtype != TSVD_F32 && x_dtype != TSVD_BF16)) return 0;
+namespace {
+size_t base_workspace(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype) {
     // (the few-token path is chosen per call, by the row stride too: cover every candidate)
     const size_t few = round256(std::max(skinny_workspace(h), mid_workspace(h)));
     if (use_gemm(h, B, x_dtype)) return std::max(gemm_workspace(h, B), B <= 64 ? few : (size_t)0);
     return few;
 }
+// feature-major copy of token-major activations: [N][B rounded up to 8] elements
+size_t transposed_bytes(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype) {
+    return round256((size_t)h->hd.N * (size_t)tsvd_round_up(B, 8) * (x_dtype == TSVD_BF16 ? 2 : 4));
+}
+}  // namespace
 
-extern "C" tsvd_status tsvd_forward(const tsvd_handle* h, const void* x_dev, tsvd_dtype x_dtype, int64_t B,
-                                    int64_t ldx, void* y_dev, tsvd_dtype y_dtype, int64_t ldy, void* workspace,
-                                    size_t workspace_bytes, void* stream) {
-    if (!h || !x_dev || !y_dev || B <= 0 || ldx < B || ldy < B) return TSVD_EINVAL;
+extern "C" size_t tsvd_workspace_bytes_ex(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype, tsvd_layout x_layout) {
+    if (!h || B <= 0 || (x_dtype != TSVD_F32 && x_dtype != TSVD_BF16)) return 0;
+    if (x_layout != TSVD_FEATURE_MAJOR && x_layout != TSVD_TOKEN_MAJOR) return 0;
+    return base_workspace(h, B, x_dtype) + (x_layout == TSVD_TOKEN_MAJOR ? transposed_bytes(h, B, x_dtype) : 0);
+}
+
+extern "C" size_t tsvd_workspace_bytes(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype) {
+    return tsvd_workspace_bytes_ex(h, B, x_dtype, TSVD_FEATURE_MAJOR);
+}
+
+extern "C" tsvd_status tsvd_forward_ex(const tsvd_handle* h, const void* x_dev, tsvd_dtype x_dtype, tsvd_layout x_layout,
+                                       int64_t B, int64_t ldx, const float* bias_dev, void* y_dev, tsvd_dtype y_dtype,
+                                       int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!h || !x_dev || !y_dev || B <= 0 || ldy < B) return TSVD_EINVAL;
     if (x_dtype != TSVD_F32 && x_dtype != TSVD_BF16) return TSVD_EINVAL;
-    if (y_dtype != TSVD_F32) return y_dtype == TSVD_BF16 ? TSVD_EUNSUPPORTED : TSVD_EINVAL;
+    if (y_dtype != TSVD_F32 && y_dtype != TSVD_BF16) return TSVD_EINVAL;
+    if (x_layout != TSVD_FEATURE_MAJOR && x_layout != TSVD_TOKEN_MAJOR) return TSVD_EINVAL;
+    if (ldx < (x_layout == TSVD_TOKEN_MAJOR ? h->hd.N : B)) return TSVD_EINVAL;
     if (B > (int64_t(1) << 24)) return TSVD_EUNSUPPORTED;
-    const size_t need = tsvd_workspace_bytes(h, B, x_dtype);
+    const size_t need = tsvd_workspace_bytes_ex(h, B, x_dtype, x_layout);
     void* ws = workspace;
     if (ws) {
         if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 255u)) return TSVD_EINVAL;
@@ -436,7 +487,24 @@ extern "C" tsvd_status tsvd_forward(const tsvd_handle* h, const void* x_dev, tsv
         ws = hm->scratch;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (use_mid(h, B, x_dtype, ldx)) return forward_mid(h, x_dev, B, ldx, static_cast<float*>(y_dev), ldy, ws, s);
+    const out_opts oo = {bias_dev, y_dtype == TSVD_BF16};
+    if (x_layout == TSVD_TOKEN_MAJOR) {
+        // one pass that rewrites x as [N][B rounded up to 8] at the front of the workspace; the rows
+        // of the copy are 16-byte aligned, so every kernel family takes its fast loads
+        const int64_t ldt = tsvd_round_up(B, 8);
+        const dim3 grid((unsigned)((h->hd.N + 31) / 32), (unsigned)((ldt + 31) / 32));
+        if (x_dtype == TSVD_BF16)
+            hipLaunchKernelGGL(tsvd_transpose_kernel<uint16_t>, grid, dim3(256), 0, s, static_cast<const uint16_t*>(x_dev), ldx,
+                               (int)B, (int)h->hd.N, static_cast<uint16_t*>(ws), ldt);
+        else
+            hipLaunchKernelGGL(tsvd_transpose_kernel<uint32_t>, grid, dim3(256), 0, s, static_cast<const uint32_t*>(x_dev), ldx,
+                               (int)B, (int)h->hd.N, static_cast<uint32_t*>(ws), ldt);
+        if (hipGetLastError() != hipSuccess) return TSVD_EDEVICE;
+        x_dev = ws;
+        ldx = ldt;
+        ws = static_cast<uint8_t*>(ws) + transposed_bytes(h, B, x_dtype);
+    }
+    if (use_mid(h, B, x_dtype, ldx)) return forward_mid(h, x_dev, B, ldx, y_dev, ldy, oo, ws, s);
     if (use_gemm(h, B, x_dtype)) {
         tsvd_gemm_problem g;
         g.blob = h->blob;
@@ -445,14 +513,23 @@ extern "C" tsvd_status tsvd_forward(const tsvd_handle* h, const void* x_dev, tsv
         g.x = x_dev;
         g.B = B;
         g.ldx = ldx;
-        g.y = static_cast<float*>(y_dev);
+        g.y = y_dev;
         g.ldy = ldy;
+        g.bias = oo.bias;
+        g.out_bf16 = oo.out_bf16;
         g.ws = ws;
         g.cu_count = h->cu_count;
         g.clocks = h->clocks;
         return tsvd_forward_gemm(g, s) == hipSuccess ? TSVD_OK : TSVD_EDEVICE;
     }
-    return forward_skinny(h, x_dev, x_dtype, B, ldx, static_cast<float*>(y_dev), ldy, ws, s);
+    return forward_skinny(h, x_dev, x_dtype, B, ldx, y_dev, ldy, oo, ws, s);
+}
+
+extern "C" tsvd_status tsvd_forward(const tsvd_handle* h, const void* x_dev, tsvd_dtype x_dtype, int64_t B,
+                                    int64_t ldx, void* y_dev, tsvd_dtype y_dtype, int64_t ldy, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+    return tsvd_forward_ex(h, x_dev, x_dtype, TSVD_FEATURE_MAJOR, B, ldx, nullptr, y_dev, y_dtype, ldy, workspace,
+                           workspace_bytes, stream);
 }
 
 // Tuning aid, not part of the public header: copies the phase timestamps of the last B <= 2 launch.

@@ -29,6 +29,7 @@
 #include <type_traits>
 #include <cmath>
 
+#include "tsvd_epilogue.h"
 #include "tsvd_kernels.h"
 #include "tsvd_layout.h"
 
@@ -170,8 +171,10 @@ struct gemm_args {
     float* colmax;            // the final row (stage 1 writes it, stage 2 reads it)
     int Bp;
     float bound_V;
-    void* out;                // stage 1: fp16 [Kp][Bp];  stage 2: fp32 [M][ldy]
+    void* out;                // stage 1: fp16 [Kp][Bp];  stage 2: fp32 (or bf16 with out_bf16) [M][ldy]
     long long ld_out;
+    const float* bias;        // stage 2 (EX kernels): added per output row, or null
+    int out_bf16;             // stage 2 (EX kernels): output type
     int rows_valid;           // stage 2: M
     long long* clocks;        // tuning aid: phase timestamps per workgroup (stage 1: 0..7, stage 2: 8..15), or null
 };
@@ -215,7 +218,9 @@ __device__ __forceinline__ void publish_column_factor(const gemm_args& p, int co
 }
 
 // Result block layout: lane (i, g) holds token i, weight rows 4 g + v.
-template <int TM, int TN, bool STAGE2>
+// EX: the variant with the bias and the choice of the output type (instantiated apart so that the
+// plain fp32 epilogue of the tuned kernels stays as it is).
+template <int TM, int TN, bool STAGE2, bool EX = false>
 __device__ __forceinline__ void gemm_epilogue(const gemm_args& p, f32x4 (&acc)[TM][TN], int strip0, int b0, int tok0,
                                               const float* cs_lds, int i, int g) {
     float cs[TN];
@@ -235,7 +240,16 @@ __device__ __forceinline__ void gemm_epilogue(const gemm_args& p, f32x4 (&acc)[T
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int row = (strip0 + a) * 16 + 4 * g + v;
-            if constexpr (STAGE2) {
+            if constexpr (STAGE2 && EX) {
+                if (row < p.rows_valid) {
+                    const float br = p.bias ? p.bias[row] : 0.f;
+#pragma unroll
+                    for (int b = 0; b < TN; ++b) {
+                        const int col = col0 + b * 16 + i;
+                        if (col < p.bvalid) tsvd_store_y(p.out, (size_t)row * p.ld_out + col, acc[a][b][v] * cs[b] + br, p.out_bf16);
+                    }
+                }
+            } else if constexpr (STAGE2) {
                 if (row < p.rows_valid) {
                     float* dst = static_cast<float*>(p.out) + (size_t)row * p.ld_out;
 #pragma unroll
@@ -264,7 +278,7 @@ __device__ __forceinline__ uint32_t buf_load32(__amdgpu_buffer_rsrc_t r, int vof
 // FAST: activation rows are 16-byte aligned, so tiles are fetched with buffer loads whose
 // range check returns zero beyond the last row (no per-element guards, no address arithmetic
 // in the loop: a per-thread offset plus a scalar offset per stage).
-template <int WM, int WN, int TM, int TN, bool STAGE2, bool FAST>
+template <int WM, int WN, int TM, int TN, bool STAGE2, bool FAST, bool EX = false>
 __global__ void __launch_bounds__(64 * WM * WN)
 tsvd_gemm_kernel(gemm_args p) {
     constexpr int THREADS = 64 * WM * WN;
@@ -407,7 +421,7 @@ tsvd_gemm_kernel(gemm_args p) {
         __syncthreads();
     }
 
-    gemm_epilogue<TM, TN, STAGE2>(p, acc, strip0, b0, wn * TN * 16, cs_lds, i, g);
+    gemm_epilogue<TM, TN, STAGE2, EX>(p, acc, strip0, b0, wn * TN * 16, cs_lds, i, g);
 }
 
 // ---- pipelined variant (activation rows 16-byte aligned) -----------------------------------
@@ -433,7 +447,7 @@ __device__ __forceinline__ i32x4 raw_rsrc(const void* base, uint32_t bytes) {
     return i32x4{(int)(uint32_t)a, (int)(uint32_t)(a >> 32), (int)bytes, 0x00020000};
 }
 
-template <int WM, int WN, int TM, int TN, bool STAGE2>
+template <int WM, int WN, int TM, int TN, bool STAGE2, bool EX = false>
 __global__ void __launch_bounds__(64 * WM * WN, 2)     // two wavefronts per SIMD: at most 256 VGPRs
 tsvd_gemm_pipe_kernel(gemm_args p) {
     constexpr int NW = WM * WN;
@@ -607,7 +621,7 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no LDS write may still be in flight at exit
     tick(3);
 
-    gemm_epilogue<TM, TN, STAGE2>(p, acc, strip0, b0, wn * TN * 16, cs_lds, i, g);
+    gemm_epilogue<TM, TN, STAGE2, EX>(p, acc, strip0, b0, wn * TN * 16, cs_lds, i, g);
     tick(5);
 }
 
@@ -644,7 +658,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 // KG > 1 splits the contraction over KG groups of WM x WN wavefronts: a ring slot then holds KG
 // pairs, group kg multiplies pair KG * P + kg, and the groups' accumulators are added through LDS
 // at the end.  Same tile and same bytes moved, KG times the wavefronts to hide waits with.
-template <int WM, int WN, int TM, int TN, bool STAGE2, int NPB, bool FUSEMAX, int KG>
+template <int WM, int WN, int TM, int TN, bool STAGE2, int NPB, bool FUSEMAX, int KG, bool EX = false>
 __global__ void __launch_bounds__(64 * WM * WN * KG)
 tsvd_gemm_ring_kernel(gemm_args p) {
     constexpr int NWG = WM * WN, NW = NWG * KG, THREADS = 64 * NW;
@@ -877,7 +891,7 @@ tsvd_gemm_ring_kernel(gemm_args p) {
     }
     tick(4);
 
-    gemm_epilogue<TM, TN, STAGE2>(p, acc, strip0, b0, wn * TN * 16, cs_lds, i, g);
+    gemm_epilogue<TM, TN, STAGE2, EX>(p, acc, strip0, b0, wn * TN * 16, cs_lds, i, g);
     tick(5);
 }
 
@@ -904,8 +918,10 @@ struct panel_args {
     const float* S;
     float bound_V;
     int Kp, Mp, M, B;
-    float* y;
+    void* y;                  // fp32 (or bf16 with out_bf16) [M][ldy]
     long long ldy;
+    const float* bias;        // EX kernels: added per output row, or null
+    int out_bf16;             // EX kernels: output type
     long long* clocks;
 };
 #define TSVD_PANEL_MAX_KP 1024
@@ -919,7 +935,7 @@ struct panel_args {
 #define TSVD_PANEL_LDS(NW) (TSVD_PANEL_MAX_KP * 128 + 64 * (NW) * 16 + 2 * 64 * 4 + 64 * (NW) * 4)
 
 // NW = 8 wavefronts of 128 rows each (two per SIMD, up to 256 registers) or 16 of 64 rows (four per SIMD).
-template <int NW>
+template <int NW, bool EX = false>
 __global__ void __launch_bounds__(64 * NW, NW / 4)
 tsvd_panel_kernel(panel_args p) {
     constexpr int TM = 64 / NW, TN = 4, BT = 64, THREADS = 64 * NW;
@@ -1182,11 +1198,20 @@ tsvd_panel_kernel(panel_args p) {
                 for (int v = 0; v < 4; ++v) {
                     const int row = (strip0 + a) * 16 + 4 * g + v;
                     if (row < p.M) {
-                        float* dst = p.y + (size_t)row * p.ldy;
+                        if constexpr (EX) {
+                            const float br = p.bias ? p.bias[row] : 0.f;
 #pragma unroll
-                        for (int b = 0; b < TN; ++b) {
-                            const int col = b0 + b * 16 + i;
-                            if (col < p.B) dst[col] = acc[a][b][v] * c2[b];
+                            for (int b = 0; b < TN; ++b) {
+                                const int col = b0 + b * 16 + i;
+                                if (col < p.B) tsvd_store_y(p.y, (size_t)row * p.ldy + col, acc[a][b][v] * c2[b] + br, p.out_bf16);
+                            }
+                        } else {
+                            float* dst = static_cast<float*>(p.y) + (size_t)row * p.ldy;
+#pragma unroll
+                            for (int b = 0; b < TN; ++b) {
+                                const int col = b0 + b * 16 + i;
+                                if (col < p.B) dst[col] = acc[a][b][v] * c2[b];
+                            }
                         }
                     }
                 }
@@ -1203,6 +1228,13 @@ hipError_t launch_gemm(const gemm_args& a, bool fast, long long rows, int Bp, hi
     constexpr int BT = WN * TN * 16, MT = WM * TM * 16;
     constexpr size_t lds = 2 * KT * BT * 2, cs = BT * 4;      // two stages; the column factors
     const dim3 grid(Bp / BT, (unsigned)(rows / MT)), block(64 * WM * WN);
+    if constexpr (STAGE2) {
+        if (a.bias || a.out_bf16) {       // the epilogue with bias / bf16 output
+            if (fast) hipLaunchKernelGGL((tsvd_gemm_pipe_kernel<WM, WN, TM, TN, true, true>), grid, block, 2 * lds + cs, stream, a);
+            else hipLaunchKernelGGL((tsvd_gemm_kernel<WM, WN, TM, TN, true, false, true>), grid, block, lds + cs, stream, a);
+            return hipGetLastError();
+        }
+    }
     if (fast) hipLaunchKernelGGL((tsvd_gemm_pipe_kernel<WM, WN, TM, TN, STAGE2>), grid, block, 2 * lds + cs, stream, a);
     else hipLaunchKernelGGL((tsvd_gemm_kernel<WM, WN, TM, TN, STAGE2, false>), grid, block, lds + cs, stream, a);
     return hipGetLastError();
@@ -1215,6 +1247,14 @@ hipError_t init_gemm() {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_pipe_kernel<WM, WN, TM, TN, STAGE2>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 2 * lds + cs);
     if (e != hipSuccess) return e;
+    if constexpr (STAGE2) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_pipe_kernel<WM, WN, TM, TN, true, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * lds + cs);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_kernel<WM, WN, TM, TN, true, false, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds + cs);
+        if (e != hipSuccess) return e;
+    }
     return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_kernel<WM, WN, TM, TN, STAGE2, false>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, lds + cs);
 }
@@ -1228,6 +1268,12 @@ hipError_t launch_ring(const gemm_args& a, long long rows, int Bp, hipStream_t s
     constexpr int BT = WN * TN * 16, MT = WM * TM * 16;
     constexpr size_t lds = ring_lds_bytes<WM, WN, TM, TN, NPB, KG>();
     const dim3 grid(Bp / BT, (unsigned)(rows / MT)), block(64 * WM * WN * KG);
+    if constexpr (STAGE2) {
+        if (a.bias || a.out_bf16) {
+            hipLaunchKernelGGL((tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false, KG, true>), grid, block, lds, stream, a);
+            return hipGetLastError();
+        }
+    }
     hipLaunchKernelGGL((tsvd_gemm_ring_kernel<WM, WN, TM, TN, STAGE2, NPB, FUSEMAX, KG>), grid, block, lds, stream, a);
     return hipGetLastError();
 }
@@ -1236,6 +1282,9 @@ hipError_t init_ring() {
     constexpr int lds = ring_lds_bytes<WM, WN, TM, TN, NPB, KG>();
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false, KG>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false, KG, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, false, NPB, false, KG>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -1325,6 +1374,10 @@ hipError_t tsvd_gemm_init() {
                                  TSVD_PANEL_LDS(8))) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_kernel<16>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  TSVD_PANEL_LDS(16))) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_kernel<8, true>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 TSVD_PANEL_LDS(8))) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_kernel<16, true>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 TSVD_PANEL_LDS(16))) != hipSuccess) return e;
 #define TSVD_RING_INIT(id, wm, wn, tm, tn, npb, kg) \
     if ((e = init_ring<wm, wn, tm, tn, npb, kg>()) != hipSuccess) return e;
     TSVD_RING_SHAPES(TSVD_RING_INIT)
@@ -1360,6 +1413,8 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     a1.bound_V = g.bound_V;
     a1.out = Z;
     a1.ld_out = Bp;
+    a1.bias = nullptr;
+    a1.out_bf16 = 0;
     a1.rows_valid = (int)hd.Kp;
     a1.clocks = g.clocks;
 
@@ -1375,6 +1430,8 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     a2.S = nullptr;
     a2.out = g.y;
     a2.ld_out = g.ldy;
+    a2.bias = g.bias;
+    a2.out_bf16 = g.out_bf16;
     a2.rows_valid = (int)hd.M;
 
     if (tsvd_stage_mask() == 7 && tsvd_gemm_use_panel(hd.Mp, hd.Kp, hd.Np, g.B, g.cu_count, fast1)) {
@@ -1396,11 +1453,18 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
         pa.B = (int)g.B;
         pa.y = g.y;
         pa.ldy = g.ldy;
+        pa.bias = g.bias;
+        pa.out_bf16 = g.out_bf16;
         pa.clocks = g.clocks;
-        if (env_cfg("TSVD_PANEL_WAVES", 16) == 16)   // tuning switch: 16 is about 5 % faster on MI355X
-            hipLaunchKernelGGL(tsvd_panel_kernel<16>, dim3((unsigned)((g.B + 63) / 64)), dim3(1024), TSVD_PANEL_LDS(16), stream, pa);
-        else
-            hipLaunchKernelGGL(tsvd_panel_kernel<8>, dim3((unsigned)((g.B + 63) / 64)), dim3(512), TSVD_PANEL_LDS(8), stream, pa);
+        const dim3 pgrid((unsigned)((g.B + 63) / 64));
+        const bool ex = g.bias || g.out_bf16;
+        if (env_cfg("TSVD_PANEL_WAVES", 16) == 16) {   // tuning switch: 16 is about 5 % faster on MI355X
+            if (ex) hipLaunchKernelGGL((tsvd_panel_kernel<16, true>), pgrid, dim3(1024), TSVD_PANEL_LDS(16), stream, pa);
+            else hipLaunchKernelGGL((tsvd_panel_kernel<16>), pgrid, dim3(1024), TSVD_PANEL_LDS(16), stream, pa);
+        } else {
+            if (ex) hipLaunchKernelGGL((tsvd_panel_kernel<8, true>), pgrid, dim3(512), TSVD_PANEL_LDS(8), stream, pa);
+            else hipLaunchKernelGGL((tsvd_panel_kernel<8>), pgrid, dim3(512), TSVD_PANEL_LDS(8), stream, pa);
+        }
         return hipGetLastError();
     }
     int cfg1 = env_cfg("TSVD_GEMM_CFG_V", tsvd_gemm_tile_shape(hd.Kp, Bp, g.cu_count, fast1));

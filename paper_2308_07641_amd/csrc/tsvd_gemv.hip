@@ -28,6 +28,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "tsvd_epilogue.h"
 #include "tsvd_kernels.h"
 
 typedef int i32x8 __attribute__((ext_vector_type(8)));
@@ -278,7 +279,7 @@ tsvd_gemv_kernel(tsvd_gemv_args p) {
         // acc = 2 * sum_k A[row][k] * fixed(in[k]): undo the factor 2 and the fixed-point scale
         const double val = combine_planes(sums + rl * 8) * pow2(ex_in - 31);
         if constexpr (STAGE_U) {
-            p.y[(size_t)row * p.ldy] = (float)val;
+            tsvd_store_y(p.y, (size_t)row * p.ldy, (float)(p.bias ? val + (double)p.bias[row] : val), p.out_bf16);
         } else {
             const float z = (float)((double)p.S[row] * val);
             uint32_t ev, od;

@@ -28,6 +28,8 @@ struct tsvd_skinny_args {
     int rows_out;           // rows of the result that exist
     int slab_tiles;         // contraction tiles staged in LDS at a time
     int sw, kw;             // workgroup = sw strips x kw contraction splits (one wavefront each)
+    const float* bias;      // stage U: added per output row, or null
+    int out_bf16;           // stage U: out is bf16 [rows_out][ld_out] instead of fp32
 };
 
 hipError_t tsvd_launch_skinny(const tsvd_skinny_args& a, hipStream_t stream);
@@ -47,7 +49,8 @@ struct tsvd_gemv_args {
     unsigned char* planes_out;            // fp8 digit planes of z, [8][Kp]
     // stage U
     const unsigned char* planes_in;
-    float* y; long long ldy;
+    void* y; long long ldy;               // fp32 (or bf16 with out_bf16) [M][ldy]
+    const float* bias; int out_bf16;      // bias per output row or null; output type
     int* meta;                            // fixed-point exponent of z (written by V, read by U)
     long long* clocks;                    // optional tuning aid: [grid][16] phase timestamps, or null
 };
@@ -66,7 +69,8 @@ struct tsvd_mid_args {
     unsigned act_bytes;                   // extent of act in bytes (reads beyond it give zero)
     const float* S; float bound_V;        // stage V: row scales (zero beyond K); |z| <= bound_V * max|x|
     float* colmax;                        // [16] per-token max |x| (stage V writes, stage U reads)
-    void* out; long long ld_out;          // stage V: z fp16 [Kp][16]; stage U: y fp32 [M][ld_out]
+    void* out; long long ld_out;          // stage V: z fp16 [Kp][16]; stage U: y fp32 (or bf16) [M][ld_out]
+    const float* bias; int out_bf16;      // stage U: bias per output row or null; output type
     int rows_valid;                       // stage U: M
     long long* clocks;                    // optional tuning aid: [grid][16] phase timestamps (stage V 0..7, U 8..15), or null
     int resident_ok;                      // tuning switch: 0 forces the slab hand-over loop for short contractions too
@@ -82,8 +86,10 @@ struct tsvd_gemm_problem {
     float bound_V;                  // |z[k][b]| <= bound_V * max_n |x[n][b]|
     const void* x;                  // device bf16 [N][ldx]
     long long B, ldx;
-    float* y;                       // device fp32 [M][ldy]
+    void* y;                        // device fp32 (or bf16 with out_bf16) [M][ldy]
     long long ldy;
+    const float* bias;              // device [M] added per output row, or null
+    int out_bf16;
     void* ws;                       // device workspace (see gemm_workspace in tsvd_api.hip)
     int cu_count;                   // compute units of the device
     long long* clocks;              // optional tuning aid: [TSVD_GEMV_MAX_GRID][16] phase timestamps, or null

@@ -23,6 +23,7 @@
 #include <type_traits>
 #include <utility>
 
+#include "tsvd_epilogue.h"
 #include "tsvd_kernels.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -279,7 +280,8 @@ tsvd_mid_kernel(tsvd_mid_args p) {
             for (int c = 0; c < kw; ++c) sum += src[c * 256];
             const int row = blockIdx.x * p.sw * 16 + rl;
             if constexpr (STAGE2) {
-                if (row < p.rows_valid && tok < p.bvalid) static_cast<float*>(p.out)[(size_t)row * p.ld_out + tok] = sum * ftok;
+                if (row < p.rows_valid && tok < p.bvalid)
+                    tsvd_store_y(p.out, (size_t)row * p.ld_out + tok, p.bias ? sum * ftok + p.bias[row] : sum * ftok, p.out_bf16);
             } else {
                 if (row < p.strips * 16)   // S is zero beyond K: padded rows of z are written as zeros
                     static_cast<_Float16*>(p.out)[(size_t)row * 16 + tok] = (_Float16)((sum * fin[n]) * ftok);

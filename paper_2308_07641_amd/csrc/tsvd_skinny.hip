@@ -21,6 +21,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "tsvd_epilogue.h"
 #include "tsvd_kernels.h"
 
 typedef int i32x8 __attribute__((ext_vector_type(8)));
@@ -234,7 +235,7 @@ tsvd_skinny_kernel(tsvd_skinny_args p) {
                 dst[(size_t)(d + 4) * p.ld_out] = (unsigned char)(hi >> (8 * d));
             }
         } else {
-            static_cast<float*>(p.out)[(size_t)row * p.ld_out + tok] = (float)val;
+            tsvd_store_y(p.out, (size_t)row * p.ld_out + tok, (float)(p.bias ? val + (double)p.bias[row] : val), p.out_bf16);
         }
     }
 }

@@ -12,6 +12,8 @@ import numpy as np
 
 TSVD_F32 = 0
 TSVD_BF16 = 1
+TSVD_FEATURE_MAJOR = 0
+TSVD_TOKEN_MAJOR = 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libtsvd.so")
@@ -31,6 +33,9 @@ _PROTOTYPES = {
     "tsvd_info": (ctypes.c_int, [_vp, _pi64, _pi64, _pi64, _pi64, _pi64]),
     "tsvd_workspace_bytes": (_sz, [_vp, _i64, ctypes.c_int]),
     "tsvd_forward": (ctypes.c_int, [_vp, _vp, ctypes.c_int, _i64, _i64, _vp, ctypes.c_int, _i64, _vp, _sz, _vp]),
+    "tsvd_workspace_bytes_ex": (_sz, [_vp, _i64, ctypes.c_int, ctypes.c_int]),
+    "tsvd_forward_ex": (ctypes.c_int, [_vp, _vp, ctypes.c_int, ctypes.c_int, _i64, _i64, _vp, _vp, ctypes.c_int, _i64,
+                                       _vp, _sz, _vp]),
     "tsvd_free": (None, [_vp]),
     "tsvd_strerror": (ctypes.c_char_p, [ctypes.c_int]),
 }
@@ -192,6 +197,45 @@ def tsvd_forward(h: Handle, x, y=None, workspace=None, stream=None):
         stream = torch.cuda.current_stream(x.device).cuda_stream
     _check(load_library().tsvd_forward(h.ptr, x2.data_ptr(), _dtype_code(x2), B, ldx, y.data_ptr(), TSVD_F32, ldy,
                                        ws_ptr, ws_bytes, stream), "tsvd_forward")
+    return y
+
+
+def tsvd_workspace_bytes_ex(h: Handle, B: int, x_dtype: int, x_layout: int) -> int:
+    return int(load_library().tsvd_workspace_bytes_ex(h.ptr, B, x_dtype, x_layout))
+
+
+def tsvd_forward_ex(h: Handle, x, x_layout=TSVD_FEATURE_MAJOR, bias=None, y=None, y_dtype=TSVD_F32, workspace=None,
+                    stream=None):
+    """y[M,B] = U (diag(S) (V x)) + bias, fp32 or bf16; x is [N,B] (feature-major) or [B,N] (token-major).
+
+    Same conventions as tsvd_forward; bias is a float32 GPU tensor [M] or None.
+    """
+    import torch
+    if not x.is_cuda or x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be a 2-d GPU tensor with unit inner stride")
+    token_major = x_layout == TSVD_TOKEN_MAJOR
+    B, feat = (x.shape[0], x.shape[1]) if token_major else (x.shape[1], x.shape[0])
+    if feat != h.N:
+        raise ValueError("x does not have N features")
+    ldx = x.stride(0) if x.shape[0] > 1 else max(x.shape[1], x.stride(0))
+    ydt = torch.bfloat16 if y_dtype == TSVD_BF16 else torch.float32
+    if y is None:
+        y = torch.empty((h.M, B), dtype=ydt, device=x.device)
+    if y.dtype != ydt or y.shape != (h.M, B) or y.stride(1) != 1 or not y.is_cuda:
+        raise ValueError("y must be a GPU tensor [M,B] of the requested type with unit column stride")
+    ldy = y.stride(0) if y.shape[0] > 1 else max(B, y.stride(0))
+    bias_ptr = None
+    if bias is not None:
+        if bias.dtype != torch.float32 or bias.shape != (h.M,) or not bias.is_cuda or not bias.is_contiguous():
+            raise ValueError("bias must be a contiguous float32 GPU tensor [M]")
+        bias_ptr = bias.data_ptr()
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    _check(load_library().tsvd_forward_ex(h.ptr, x.data_ptr(), _dtype_code(x), x_layout, B, ldx, bias_ptr, y.data_ptr(),
+                                          y_dtype, ldy, ws_ptr, ws_bytes, stream), "tsvd_forward_ex")
     return y
 
 

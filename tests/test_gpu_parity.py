@@ -270,6 +270,85 @@ def test_degenerate_inputs(tsvd, B):
         assert rel_err(y, ref) <= TOL["bf16"]
 
 
+# ---- the layer form (tsvd_forward_ex): bias, bf16 output, token-major activations, in every
+# ---- kernel family.  Exact instances: an integer bias keeps every value an exactly representable
+# ---- integer, so the fp32 output must equal the oracle and the bf16 output its exact rounding.
+LAYER_CASES = [
+    # M, N, K, B, environment that routes the call
+    (300, 513, 270, 1, {}),                                   # single-token kernels
+    (300, 513, 270, 2, {"TSVD_GEMV": "0", "TSVD_MID": "0"}),  # general slab kernel, two tokens per pass
+    (100, 2300, 4500, 13, {}),                                # few-token kernel
+    (130, 64, 520, 257, {}),                                  # ring kernels (unaligned rows: large-tile fallback)
+    (130, 64, 520, 264, {}),                                  # ring kernels (aligned rows)
+    (300, 200, 270, 72, {"TSVD_MID": "0", "TSVD_GEMM_CFG_U": "0", "TSVD_GEMM_CFG_V": "1"}),   # pipelined large tiles
+    (300, 200, 270, 72, {"TSVD_MID": "0", "TSVD_GEMM_CFG_U": "2", "TSVD_GEMM_CFG_V": "3"}),
+    (300, 200, 520, 304, {"TSVD_PANEL": "1"}),                            # token-panel kernel, 16 wavefronts
+    (300, 200, 520, 304, {"TSVD_PANEL": "1", "TSVD_PANEL_WAVES": "8"}),   # token-panel kernel, 8 wavefronts
+    (300, 200, 520, 304, {"TSVD_PANEL": "0", "TSVD_GEMM_CFG_U": "14", "TSVD_GEMM_CFG_V": "15"}),   # ring kernels, other shapes
+]
+
+
+@pytest.mark.parametrize("M,N,K,B,env", LAYER_CASES)
+def test_layer_form_every_kernel_family(tsvd, M, N, K, B, env, monkeypatch):
+    import torch
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    dev = "cuda:0"
+    rng = np.random.default_rng(M + B)
+
+    def run(i, bias, layout, y_dtype):
+        h = tsvd.tsvd_pack(i.U, i.S, i.V)
+        x = to_device(i)
+        if layout == tsvd.TSVD_TOKEN_MAJOR:
+            x = x.t().contiguous()
+        b = None if bias is None else torch.from_numpy(bias).to(dev)
+        y = torch.full((M, B), float("nan"), dtype=torch.bfloat16 if y_dtype == tsvd.TSVD_BF16 else torch.float32, device=dev)
+        tsvd.tsvd_forward_ex(h, x, x_layout=layout, bias=b, y=y, y_dtype=y_dtype)
+        torch.cuda.synchronize()
+        tsvd.tsvd_free(h)
+        return y.float().cpu().numpy().astype(np.float64)
+
+    i = workloads.make_integer_inputs(M, N, K, B, 0.5, "bf16", seed=5 + M + B)
+    bias = rng.integers(-8, 9, size=M).astype(np.float32)
+    print(f"case layer int M={M} N={N} K={K} B={B} {env}", flush=True)
+    ref = oracle.forward_layer(i.U, i.S, i.V, i.X, bias=bias)
+    assert np.array_equal(run(i, bias, tsvd.TSVD_FEATURE_MAJOR, tsvd.TSVD_F32), ref)
+    assert np.array_equal(run(i, bias, tsvd.TSVD_TOKEN_MAJOR, tsvd.TSVD_F32), ref)
+    assert np.array_equal(run(i, bias, tsvd.TSVD_FEATURE_MAJOR, tsvd.TSVD_BF16), oracle.round_to_bf16(ref))
+    assert np.array_equal(run(i, None, tsvd.TSVD_TOKEN_MAJOR, tsvd.TSVD_BF16),
+                          oracle.round_to_bf16(oracle.forward(i.U, i.S, i.V, i.X)))
+
+    i = workloads.make_inputs(M, N, K, B, 0.6, 0.02, "bf16", seed=6 + M + B)
+    bias = rng.standard_normal(M).astype(np.float32)
+    print(f"case layer rand M={M} N={N} K={K} B={B} {env}", flush=True)
+    ref = oracle.forward_layer(i.U, i.S, i.V, i.X, bias=bias)
+    scale = np.max(np.abs(oracle.forward(i.U, i.S, i.V, i.X)))       # the tolerance of the map itself
+    for layout in (tsvd.TSVD_FEATURE_MAJOR, tsvd.TSVD_TOKEN_MAJOR):
+        y = run(i, bias, layout, tsvd.TSVD_F32)
+        assert not np.isnan(y).any()
+        assert np.max(np.abs(y - ref)) <= TOL["bf16"] * scale
+        # bf16 output: the same error, then at most one step of the bf16 grid apart (a step is at
+        # most 2^-7 of the value)
+        yb = run(i, bias, layout, tsvd.TSVD_BF16)
+        assert np.all(np.abs(yb - oracle.round_to_bf16(ref)) <= TOL["bf16"] * scale + 2.0 ** -7 * np.abs(ref))
+        assert np.array_equal(oracle.round_to_bf16(yb), yb)
+
+
+@pytest.mark.parametrize("B", [1, 3, 40])
+def test_layer_form_fp32_activations(tsvd, B):
+    import torch
+    i = workloads.make_inputs(256, 300, 512, B, 0.5, 0.02, "f32", seed=50 + B)
+    bias = np.random.default_rng(B).standard_normal(256).astype(np.float32)
+    ref = oracle.forward_layer(i.U, i.S, i.V, i.X, bias=bias)
+    h = tsvd.tsvd_pack(i.U, i.S, i.V)
+    xt = to_device(i).t().contiguous()
+    ws = torch.empty(tsvd.tsvd_workspace_bytes_ex(h, B, tsvd.TSVD_F32, tsvd.TSVD_TOKEN_MAJOR), dtype=torch.uint8, device="cuda:0")
+    y = tsvd.tsvd_forward_ex(h, xt, x_layout=tsvd.TSVD_TOKEN_MAJOR, bias=torch.from_numpy(bias).to("cuda:0"), workspace=ws)
+    torch.cuda.synchronize()
+    tsvd.tsvd_free(h)
+    assert np.max(np.abs(y.cpu().numpy().astype(np.float64) - ref)) <= 1e-5 * np.max(np.abs(ref))
+
+
 def test_strided_inputs_outputs_and_caller_workspace(tsvd):
     import torch
     i = workloads.make_inputs(300, 200, 270, 70, 0.5, 0.02, "bf16", seed=5)
@@ -313,7 +392,7 @@ def test_device_round_trip_info_and_errors(tsvd):
                                         o.get("ws", None), o.get("wsb", 0), None)
     assert call(h=None) == 1 and call(x=None) == 1 and call(y=None) == 1
     assert call(B=0) == 1 and call(ldx=3) == 1 and call(ldy=3) == 1 and call(xd=7) == 1
-    assert call(yd=1) == 5 and call(yd=9) == 1
+    assert call(yd=9) == 1
     assert call(ws=x.data_ptr(), wsb=16) == 1                 # workspace too small
     torch.cuda.synchronize()
     assert torch.all(y == 0)                                   # failures leave outputs untouched

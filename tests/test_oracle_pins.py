@@ -242,3 +242,53 @@ def test_op_counts_and_cost_model():
     assert abs(oracle.critical_rank(100, 50, 1.0, 3) - 2 * 100 * 50 / (1 + 150)) < 1e-9
     # numbers implied by the paper's cost model at the BERT-like shape, r = 0.5
     assert abs(oracle.acceleration(3072, 768, 1536, 0.5, 32) - 24.4) < 0.05
+
+
+# ---- the layer form: bias, token-major activations, bf16 output -----------------------------
+def test_bf16_rounding_against_known_values_and_the_bit_trick():
+    """round_to_bf16 (from the definition of the format) against hand-worked values (ties to
+    even, carry into the exponent, subnormals) and against the independent integer bit trick
+    of the input generators on fp32-representable values."""
+    cases = {
+        1.0: 1.0,
+        1.0 + 2.0 ** -8: 1.0,                     # tie, even significand below
+        1.0 + 3 * 2.0 ** -8: 1.0 + 2.0 ** -6,     # tie, even significand above (1.015625)
+        1.0 + 2.0 ** -8 + 2.0 ** -20: 1.0 + 2.0 ** -7,
+        1.99609375 + 2.0 ** -9 * 1.5: 2.0,        # rounds up across the binade
+        -3.1415926: -3.140625,
+        0.0: 0.0,
+        2.0 ** -133: 2.0 ** -133,                 # smallest subnormal
+        2.0 ** -134 * 1.5: 2.0 ** -133,
+        2.0 ** -134: 0.0,                         # tie to even (zero)
+    }
+    for v, want in cases.items():
+        assert oracle.round_to_bf16(np.array([v]))[0] == want, v
+    rng = np.random.default_rng(5)
+    a = (rng.standard_normal(20000) * np.exp(rng.uniform(-30, 30, 20000))).astype(np.float32)
+    want = workloads.bf16_bits_to_f32(workloads.f32_to_bf16_bits(a)).astype(np.float64)
+    assert np.array_equal(oracle.round_to_bf16(a.astype(np.float64)), want)
+
+
+def test_layer_form_bias_layout_and_output_type():
+    i = _rand(37, 29, 61, 5, seed=12)
+    U, S, V, X = i.U, i.S, i.V, i.X
+    base = oracle.forward(U, S, V, X)
+    bias = np.random.default_rng(13).standard_normal(37).astype(np.float32)
+    # bias: the dense product with a column of ones appended (y = [W b] [x; 1]) is the same map
+    W1 = np.concatenate([_dense(U, S, V), bias.astype(np.float64)[:, None]], axis=1)
+    X1 = np.concatenate([X.astype(np.float64), np.ones((1, X.shape[1]))], axis=0)
+    got = oracle.forward_layer(U, S, V, X, bias=bias)
+    assert np.allclose(got, W1 @ X1, rtol=1e-12, atol=1e-12)
+    assert not np.allclose(got, base)                                    # the bias is not dropped
+    assert np.array_equal(oracle.forward_layer(U * 0, S, V, X, bias=bias), np.repeat(bias.astype(np.float64)[:, None], 5, 1))
+    # token-major activations are the transposed matrix; a non-square X makes a mix-up a shape error
+    assert np.array_equal(oracle.forward_layer(U, S, V, np.ascontiguousarray(X.T), x_layout="token_major"), base)
+    with pytest.raises(ValueError):
+        oracle.forward_layer(U, S, V, X, x_layout="token_major")
+    # bf16 output: within half a unit in the last place (at most 2^-8 relative: 8 significant bits),
+    # exactly representable, idempotent
+    yb = oracle.forward_layer(U, S, V, X, bias=bias, y_dtype="bf16")
+    assert np.all(np.abs(yb - got) <= np.abs(got) * 2.0 ** -8)
+    assert np.max(np.abs(yb - got) / np.abs(got)) > 2.0 ** -11           # and it does round
+    assert np.array_equal(oracle.round_to_bf16(yb), yb)
+    assert np.array_equal(workloads.bf16_bits_to_f32(workloads.f32_to_bf16_bits(yb.astype(np.float32))).astype(np.float64), yb)
