@@ -17,3 +17,36 @@ __device__ __forceinline__ void tsvd_store_y(void* y, size_t idx, float v, int o
     if (out_bf16) static_cast<uint16_t*>(y)[idx] = tsvd_bf16_rne(v);
     else static_cast<float*>(y)[idx] = v;
 }
+
+// bf16 store of two rows of a 16 x 16 result block in the layout of the MFMA result: lane (i, g)
+// holds token col16 + i (col16 a multiple of 16) of rows r and r + 1 (values v0, v1).
+// Neighbouring lanes swap one value (DPP quad_perm [1,0,3,2]), so that an even lane holds tokens
+// (i, i + 1) of row r and the odd lane next to it tokens (i - 1, i) of row r + 1; one packed
+// conversion (nearest even) and one 4-byte store per lane then cover both rows with all 64 lanes
+// active: half the store instructions of the fp32 form for half the bytes.  aligned4 (uniform):
+// the row stride is even and y 4-byte aligned; otherwise the pair is written as two 2-byte stores.
+// Must be called by all 16 lanes of a lane group together.
+__device__ __forceinline__ void tsvd_store_row_pair_bf16(void* y, long long ld, int r, int rows_valid, int col16, int i,
+                                                         int bvalid, float v0, float v1, bool aligned4) {
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    const int odd = i & 1, c = col16 + i - odd;
+    const float send = odd ? v0 : v1;
+    const float recv = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(send), 0xB1, 0xF, 0xF, true));
+    const f32x2_t two = odd ? f32x2_t{recv, v1} : f32x2_t{v0, recv};
+    const uint32_t pk = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2_t));
+    const int row = r + odd;
+    if (row < rows_valid) {
+        uint16_t* dst = static_cast<uint16_t*>(y) + (size_t)row * ld + c;
+        if (c + 1 < bvalid) {
+            if (aligned4) {
+                *reinterpret_cast<uint32_t*>(dst) = pk;
+            } else {
+                dst[0] = (uint16_t)pk;
+                dst[1] = (uint16_t)(pk >> 16);
+            }
+        } else if (c < bvalid) {
+            *dst = (uint16_t)pk;
+        }
+    }
+}

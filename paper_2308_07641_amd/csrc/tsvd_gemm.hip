@@ -218,16 +218,17 @@ __device__ __forceinline__ void publish_column_factor(const gemm_args& p, int co
 }
 
 // Result block layout: lane (i, g) holds token i, weight rows 4 g + v.
-// EX: the variant with the bias and the choice of the output type (instantiated apart so that the
-// plain fp32 epilogue of the tuned kernels stays as it is).
-template <int TM, int TN, bool STAGE2, bool EX = false>
+// EX: the variants with the bias and the choice of the output type (instantiated apart so that the
+// plain fp32 epilogue of the tuned kernels stays as it is): 1 = fp32 with bias, 2 = bf16 (with or
+// without bias), two rows per store.
+template <int TM, int TN, bool STAGE2, int EX = 0>
 __device__ __forceinline__ void gemm_epilogue(const gemm_args& p, f32x4 (&acc)[TM][TN], int strip0, int b0, int tok0,
                                               const float* cs_lds, int i, int g) {
     float cs[TN];
 #pragma unroll
     for (int b = 0; b < TN; ++b) cs[b] = cs_lds[tok0 + b * 16 + i];
     const int col0 = b0 + tok0;
-    float sr[TM][4];
+    float sr[TM][4];                  // stage 1: row scales S; stage 2 with options: the bias
     if constexpr (!STAGE2) {
 #pragma unroll
         for (int a = 0; a < TM; ++a) {
@@ -235,21 +236,57 @@ __device__ __forceinline__ void gemm_epilogue(const gemm_args& p, f32x4 (&acc)[T
             sr[a][0] = q.x; sr[a][1] = q.y; sr[a][2] = q.z; sr[a][3] = q.w;
         }
     }
+    if constexpr (STAGE2 && EX != 0) {
+        // all bias loads first, unconditional (rows clamped), so that no store waits for its own load
+        if (p.bias) {
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) sr[a][v] = p.bias[min((strip0 + a) * 16 + 4 * g + v, p.rows_valid - 1)];
+        } else {
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) sr[a][v] = 0.f;
+        }
+    }
+    if constexpr (STAGE2 && EX == 2) {        // bf16 in pairs: rows two by two, tokens left to right
+        const bool aligned4 = !(p.ld_out & 1) && !(reinterpret_cast<uintptr_t>(p.out) & 3);
+#pragma unroll
+        for (int a = 0; a < TM; ++a) {
+#pragma unroll
+            for (int vp = 0; vp < 4; vp += 2) {
+#pragma unroll
+                for (int b = 0; b < TN; ++b)
+                    tsvd_store_row_pair_bf16(p.out, p.ld_out, (strip0 + a) * 16 + 4 * g + vp, p.rows_valid, col0 + b * 16, i, p.bvalid,
+                                             acc[a][b][vp] * cs[b] + sr[a][vp], acc[a][b][vp + 1] * cs[b] + sr[a][vp + 1], aligned4);
+            }
+        }
+        return;
+    }
+    if constexpr (STAGE2 && EX == 1) {        // fp32 with bias, row by row
+#pragma unroll
+        for (int a = 0; a < TM; ++a) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = (strip0 + a) * 16 + 4 * g + v;
+                if (row < p.rows_valid) {
+#pragma unroll
+                    for (int b = 0; b < TN; ++b) {
+                        const int col = col0 + b * 16 + i;
+                        if (col < p.bvalid) static_cast<float*>(p.out)[(size_t)row * p.ld_out + col] = acc[a][b][v] * cs[b] + sr[a][v];
+                    }
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int a = 0; a < TM; ++a) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int row = (strip0 + a) * 16 + 4 * g + v;
-            if constexpr (STAGE2 && EX) {
-                if (row < p.rows_valid) {
-                    const float br = p.bias ? p.bias[row] : 0.f;
-#pragma unroll
-                    for (int b = 0; b < TN; ++b) {
-                        const int col = col0 + b * 16 + i;
-                        if (col < p.bvalid) tsvd_store_y(p.out, (size_t)row * p.ld_out + col, acc[a][b][v] * cs[b] + br, p.out_bf16);
-                    }
-                }
-            } else if constexpr (STAGE2) {
+            if constexpr (STAGE2) {
                 if (row < p.rows_valid) {
                     float* dst = static_cast<float*>(p.out) + (size_t)row * p.ld_out;
 #pragma unroll
@@ -278,7 +315,7 @@ __device__ __forceinline__ uint32_t buf_load32(__amdgpu_buffer_rsrc_t r, int vof
 // FAST: activation rows are 16-byte aligned, so tiles are fetched with buffer loads whose
 // range check returns zero beyond the last row (no per-element guards, no address arithmetic
 // in the loop: a per-thread offset plus a scalar offset per stage).
-template <int WM, int WN, int TM, int TN, bool STAGE2, bool FAST, bool EX = false>
+template <int WM, int WN, int TM, int TN, bool STAGE2, bool FAST, int EX = 0>
 __global__ void __launch_bounds__(64 * WM * WN)
 tsvd_gemm_kernel(gemm_args p) {
     constexpr int THREADS = 64 * WM * WN;
@@ -447,7 +484,7 @@ __device__ __forceinline__ i32x4 raw_rsrc(const void* base, uint32_t bytes) {
     return i32x4{(int)(uint32_t)a, (int)(uint32_t)(a >> 32), (int)bytes, 0x00020000};
 }
 
-template <int WM, int WN, int TM, int TN, bool STAGE2, bool EX = false>
+template <int WM, int WN, int TM, int TN, bool STAGE2, int EX = 0>
 __global__ void __launch_bounds__(64 * WM * WN, 2)     // two wavefronts per SIMD: at most 256 VGPRs
 tsvd_gemm_pipe_kernel(gemm_args p) {
     constexpr int NW = WM * WN;
@@ -658,7 +695,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 // KG > 1 splits the contraction over KG groups of WM x WN wavefronts: a ring slot then holds KG
 // pairs, group kg multiplies pair KG * P + kg, and the groups' accumulators are added through LDS
 // at the end.  Same tile and same bytes moved, KG times the wavefronts to hide waits with.
-template <int WM, int WN, int TM, int TN, bool STAGE2, int NPB, bool FUSEMAX, int KG, bool EX = false>
+template <int WM, int WN, int TM, int TN, bool STAGE2, int NPB, bool FUSEMAX, int KG, int EX = 0>
 __global__ void __launch_bounds__(64 * WM * WN * KG)
 tsvd_gemm_ring_kernel(gemm_args p) {
     constexpr int NWG = WM * WN, NW = NWG * KG, THREADS = 64 * NW;
@@ -933,9 +970,14 @@ struct panel_args {
 #endif
 #define TSVD_PANEL_MAX_NP 1024
 #define TSVD_PANEL_LDS(NW) (TSVD_PANEL_MAX_KP * 128 + 64 * (NW) * 16 + 2 * 64 * 4 + 64 * (NW) * 4)
+// The variants with output options keep the bias of up to 2048 rows in LDS behind that (read at
+// the end of every unit of phase 2: from global memory each read stalled the wavefront for an L2
+// round trip, +8 us on 12544 tokens x 2048 rows).
+#define TSVD_PANEL_BIAS_ROWS 2048
+#define TSVD_PANEL_LDS_EX(NW) (TSVD_PANEL_LDS(NW) + TSVD_PANEL_BIAS_ROWS * 4)
 
 // NW = 8 wavefronts of 128 rows each (two per SIMD, up to 256 registers) or 16 of 64 rows (four per SIMD).
-template <int NW, bool EX = false>
+template <int NW, int EX = 0>
 __global__ void __launch_bounds__(64 * NW, NW / 4)
 tsvd_panel_kernel(panel_args p) {
     constexpr int TM = 64 / NW, TN = 4, BT = 64, THREADS = 64 * NW;
@@ -955,6 +997,14 @@ tsvd_panel_kernel(panel_args p) {
         if (p.clocks && threadIdx.x == 0 && blockIdx.x < TSVD_GEMV_MAX_GRID) p.clocks[blockIdx.x * 16 + n] = wall_clock64();
     };
     tick(0);
+    const float* bias_lds = nullptr;           // (visible to all after the barriers of phase 1)
+    if constexpr (EX != 0) {
+        if (p.bias && p.M <= TSVD_PANEL_BIAS_ROWS) {
+            float* dst = reinterpret_cast<float*>(smem + TSVD_PANEL_LDS(NW));
+            for (int r = threadIdx.x; r < p.M; r += THREADS) dst[r] = p.bias[r];
+            bias_lds = dst;
+        }
+    }
 
     // (row and swizzle conventions: see tsvd_gemm_kernel; this tile is one wavefront wide)
     const int rsel = i >> 2;
@@ -1192,20 +1242,53 @@ tsvd_panel_kernel(panel_args p) {
                 load_w(min(P + 2, lastp), wa);
                 compute_pair(std::true_type{}, zl + (2 * P + 2) * STAGE_BYTES, zl + (2 * P + 3) * STAGE_BYTES, wb);
             }
+            float br[TM][4];
+            if constexpr (EX != 0) {
+                // one uniform choice of the source, then all reads back to back (rows clamped)
+                auto fill = [&](auto src) {
 #pragma unroll
-            for (int a = 0; a < TM; ++a) {
+                    for (int a = 0; a < TM; ++a)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int row = (strip0 + a) * 16 + 4 * g + v;
-                    if (row < p.M) {
-                        if constexpr (EX) {
-                            const float br = p.bias ? p.bias[row] : 0.f;
+                        for (int v = 0; v < 4; ++v) br[a][v] = src(min((strip0 + a) * 16 + 4 * g + v, p.M - 1));
+                };
+                if (bias_lds) fill([&](int row) { return bias_lds[row]; });
+                else if (p.bias) fill([&](int row) { return p.bias[row]; });
+                else fill([](int) { return 0.f; });
+            }
+            if constexpr (EX == 2) {
+                const bool aligned4 = !(p.ldy & 1) && !(reinterpret_cast<uintptr_t>(p.y) & 3);
+#pragma unroll
+                for (int a = 0; a < TM; ++a) {
+#pragma unroll
+                    for (int vp = 0; vp < 4; vp += 2) {
+#pragma unroll
+                        for (int b = 0; b < TN; ++b)
+                            tsvd_store_row_pair_bf16(p.y, p.ldy, (strip0 + a) * 16 + 4 * g + vp, p.M, b0 + b * 16, i, p.B,
+                                                     acc[a][b][vp] * c2[b] + br[a][vp], acc[a][b][vp + 1] * c2[b] + br[a][vp + 1], aligned4);
+                    }
+                }
+            } else if constexpr (EX == 1) {
+#pragma unroll
+                for (int a = 0; a < TM; ++a) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int row = (strip0 + a) * 16 + 4 * g + v;
+                        if (row < p.M) {
 #pragma unroll
                             for (int b = 0; b < TN; ++b) {
                                 const int col = b0 + b * 16 + i;
-                                if (col < p.B) tsvd_store_y(p.y, (size_t)row * p.ldy + col, acc[a][b][v] * c2[b] + br, p.out_bf16);
+                                if (col < p.B) static_cast<float*>(p.y)[(size_t)row * p.ldy + col] = acc[a][b][v] * c2[b] + br[a][v];
                             }
-                        } else {
+                        }
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int a = 0; a < TM; ++a) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int row = (strip0 + a) * 16 + 4 * g + v;
+                        if (row < p.M) {
                             float* dst = static_cast<float*>(p.y) + (size_t)row * p.ldy;
 #pragma unroll
                             for (int b = 0; b < TN; ++b) {
@@ -1223,15 +1306,26 @@ tsvd_panel_kernel(panel_args p) {
         p.clocks[blockIdx.x * 16 + 8 + wave / (NW / 8)] = wall_clock64();   // end of (one of) the wavefronts of each eighth
 }
 
+// Epilogue variant of a stage-U launch: 0 plain fp32, 1 fp32 with bias, 2 bf16.
+int out_variant(const float* bias, int out_bf16, const void*, long long) {
+    return out_bf16 ? 2 : bias ? 1 : 0;
+}
+
 template <int WM, int WN, int TM, int TN, bool STAGE2>
 hipError_t launch_gemm(const gemm_args& a, bool fast, long long rows, int Bp, hipStream_t stream) {
     constexpr int BT = WN * TN * 16, MT = WM * TM * 16;
     constexpr size_t lds = 2 * KT * BT * 2, cs = BT * 4;      // two stages; the column factors
     const dim3 grid(Bp / BT, (unsigned)(rows / MT)), block(64 * WM * WN);
     if constexpr (STAGE2) {
-        if (a.bias || a.out_bf16) {       // the epilogue with bias / bf16 output
-            if (fast) hipLaunchKernelGGL((tsvd_gemm_pipe_kernel<WM, WN, TM, TN, true, true>), grid, block, 2 * lds + cs, stream, a);
-            else hipLaunchKernelGGL((tsvd_gemm_kernel<WM, WN, TM, TN, true, false, true>), grid, block, lds + cs, stream, a);
+        const int ex = out_variant(a.bias, a.out_bf16, a.out, a.ld_out);    // the epilogues with bias / bf16 output
+        if (ex == 2) {
+            if (fast) hipLaunchKernelGGL((tsvd_gemm_pipe_kernel<WM, WN, TM, TN, true, 2>), grid, block, 2 * lds + cs, stream, a);
+            else hipLaunchKernelGGL((tsvd_gemm_kernel<WM, WN, TM, TN, true, false, 2>), grid, block, lds + cs, stream, a);
+            return hipGetLastError();
+        }
+        if (ex == 1) {
+            if (fast) hipLaunchKernelGGL((tsvd_gemm_pipe_kernel<WM, WN, TM, TN, true, 1>), grid, block, 2 * lds + cs, stream, a);
+            else hipLaunchKernelGGL((tsvd_gemm_kernel<WM, WN, TM, TN, true, false, 1>), grid, block, lds + cs, stream, a);
             return hipGetLastError();
         }
     }
@@ -1248,10 +1342,16 @@ hipError_t init_gemm() {
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 2 * lds + cs);
     if (e != hipSuccess) return e;
     if constexpr (STAGE2) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_pipe_kernel<WM, WN, TM, TN, true, true>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_pipe_kernel<WM, WN, TM, TN, true, 1>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 2 * lds + cs);
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_kernel<WM, WN, TM, TN, true, false, true>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_pipe_kernel<WM, WN, TM, TN, true, 2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * lds + cs);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_kernel<WM, WN, TM, TN, true, false, 1>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds + cs);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_kernel<WM, WN, TM, TN, true, false, 2>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds + cs);
         if (e != hipSuccess) return e;
     }
@@ -1269,10 +1369,10 @@ hipError_t launch_ring(const gemm_args& a, long long rows, int Bp, hipStream_t s
     constexpr size_t lds = ring_lds_bytes<WM, WN, TM, TN, NPB, KG>();
     const dim3 grid(Bp / BT, (unsigned)(rows / MT)), block(64 * WM * WN * KG);
     if constexpr (STAGE2) {
-        if (a.bias || a.out_bf16) {
-            hipLaunchKernelGGL((tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false, KG, true>), grid, block, lds, stream, a);
-            return hipGetLastError();
-        }
+        const int ex = out_variant(a.bias, a.out_bf16, a.out, a.ld_out);
+        if (ex == 2) hipLaunchKernelGGL((tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false, KG, 2>), grid, block, lds, stream, a);
+        if (ex == 1) hipLaunchKernelGGL((tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false, KG, 1>), grid, block, lds, stream, a);
+        if (ex != 0) return hipGetLastError();
     }
     hipLaunchKernelGGL((tsvd_gemm_ring_kernel<WM, WN, TM, TN, STAGE2, NPB, FUSEMAX, KG>), grid, block, lds, stream, a);
     return hipGetLastError();
@@ -1283,7 +1383,10 @@ hipError_t init_ring() {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false, KG>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false, KG, true>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false, KG, 1>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false, KG, 2>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, false, NPB, false, KG>),
@@ -1374,10 +1477,14 @@ hipError_t tsvd_gemm_init() {
                                  TSVD_PANEL_LDS(8))) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_kernel<16>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  TSVD_PANEL_LDS(16))) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_kernel<8, true>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 TSVD_PANEL_LDS(8))) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_kernel<16, true>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 TSVD_PANEL_LDS(16))) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_kernel<8, 1>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 TSVD_PANEL_LDS_EX(8))) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_kernel<16, 1>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 TSVD_PANEL_LDS_EX(16))) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_kernel<8, 2>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 TSVD_PANEL_LDS_EX(8))) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_kernel<16, 2>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 TSVD_PANEL_LDS_EX(16))) != hipSuccess) return e;
 #define TSVD_RING_INIT(id, wm, wn, tm, tn, npb, kg) \
     if ((e = init_ring<wm, wn, tm, tn, npb, kg>()) != hipSuccess) return e;
     TSVD_RING_SHAPES(TSVD_RING_INIT)
@@ -1457,12 +1564,14 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
         pa.out_bf16 = g.out_bf16;
         pa.clocks = g.clocks;
         const dim3 pgrid((unsigned)((g.B + 63) / 64));
-        const bool ex = g.bias || g.out_bf16;
+        const int ex = out_variant(g.bias, g.out_bf16, g.y, g.ldy);
         if (env_cfg("TSVD_PANEL_WAVES", 16) == 16) {   // tuning switch: 16 is about 5 % faster on MI355X
-            if (ex) hipLaunchKernelGGL((tsvd_panel_kernel<16, true>), pgrid, dim3(1024), TSVD_PANEL_LDS(16), stream, pa);
+            if (ex == 2) hipLaunchKernelGGL((tsvd_panel_kernel<16, 2>), pgrid, dim3(1024), TSVD_PANEL_LDS_EX(16), stream, pa);
+            else if (ex == 1) hipLaunchKernelGGL((tsvd_panel_kernel<16, 1>), pgrid, dim3(1024), TSVD_PANEL_LDS_EX(16), stream, pa);
             else hipLaunchKernelGGL((tsvd_panel_kernel<16>), pgrid, dim3(1024), TSVD_PANEL_LDS(16), stream, pa);
         } else {
-            if (ex) hipLaunchKernelGGL((tsvd_panel_kernel<8, true>), pgrid, dim3(512), TSVD_PANEL_LDS(8), stream, pa);
+            if (ex == 2) hipLaunchKernelGGL((tsvd_panel_kernel<8, 2>), pgrid, dim3(512), TSVD_PANEL_LDS_EX(8), stream, pa);
+            else if (ex == 1) hipLaunchKernelGGL((tsvd_panel_kernel<8, 1>), pgrid, dim3(512), TSVD_PANEL_LDS_EX(8), stream, pa);
             else hipLaunchKernelGGL((tsvd_panel_kernel<8>), pgrid, dim3(512), TSVD_PANEL_LDS(8), stream, pa);
         }
         return hipGetLastError();
