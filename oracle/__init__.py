@@ -7,3 +7,4 @@ from .tsvd_oracle import (  # noqa: F401
     build, forward, forward_columns, forward_layer, round_to_bf16, op_counts, acceleration,
     critical_rank, threads,
 )
+from . import transition  # noqa: F401  (Algorithms 1 and 2, Eq. 3, Theorem 1 in fp64 numpy)
