@@ -73,6 +73,8 @@ hipError_t device_init(int device) {
     if (e != hipSuccess) return e;
     e = tsvd_mid_init();
     if (e != hipSuccess) return e;
+    e = tsvd_transition_init();
+    if (e != hipSuccess) return e;
     done[device] = true;
     return hipSuccess;
 }

@@ -78,6 +78,8 @@ struct tsvd_mid_args {
 hipError_t tsvd_mid_init();
 hipError_t tsvd_launch_mid(const tsvd_mid_args& a, bool stage_u, bool vec, hipStream_t stream);
 
+hipError_t tsvd_transition_init();   // kernel attributes of tsvd_transition.hip
+
 // ---- batched path ----------------------------------------------------------------------------
 struct tsvd_blob_header;
 struct tsvd_gemm_problem {

@@ -36,6 +36,12 @@ _PROTOTYPES = {
     "tsvd_workspace_bytes_ex": (_sz, [_vp, _i64, ctypes.c_int, ctypes.c_int]),
     "tsvd_forward_ex": (ctypes.c_int, [_vp, _vp, ctypes.c_int, ctypes.c_int, _i64, _i64, _vp, _vp, ctypes.c_int, _i64,
                                        _vp, _sz, _vp]),
+    "tsvd_ternarize": (ctypes.c_int, [_vp, _i64, _i64, _i64, ctypes.c_double, _vp, _i64, _vp, _vp]),
+    "tsvd_fit_scales_workspace": (_sz, [_i64]),
+    "tsvd_fit_scales": (ctypes.c_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _sz, _vp, _vp]),
+    "tsvd_residual": (ctypes.c_int, [_vp, _vp, _i64, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp]),
+    "tsvd_leading_singular_pair": (ctypes.c_int, [_vp, _i64, _i64, ctypes.c_int32, _vp, _vp, _vp, _vp, _vp]),
+    "tsvd_transition": (ctypes.c_int, [_vp, _i64, _i64, ctypes.c_double, ctypes.c_double, _i64, _vp, _vp, _vp, _pi64, _vp, _vp]),
     "tsvd_free": (None, [_vp]),
     "tsvd_strerror": (ctypes.c_char_p, [ctypes.c_int]),
 }
@@ -237,6 +243,92 @@ def tsvd_forward_ex(h: Handle, x, x_layout=TSVD_FEATURE_MAJOR, bias=None, y=None
     _check(load_library().tsvd_forward_ex(h.ptr, x.data_ptr(), _dtype_code(x), x_layout, B, ldx, bias_ptr, y.data_ptr(),
                                           y_dtype, ldy, ws_ptr, ws_bytes, stream), "tsvd_forward_ex")
     return y
+
+
+# ---- direct transition W -> (U, S, V) (include/tsvd_transition.h); torch CUDA tensors as device buffers
+def _stream(t, stream):
+    import torch
+    return torch.cuda.current_stream(t.device).cuda_stream if stream is None else stream
+
+
+def _need(t, dtype, shape, what):
+    if not t.is_cuda or t.dtype != dtype or tuple(t.shape) != tuple(shape) or not t.is_contiguous():
+        raise ValueError(f"{what} must be a contiguous GPU tensor {dtype} {tuple(shape)}")
+
+
+def tsvd_ternarize(x, theta: float, stream=None):
+    """Algorithm 1 for the rows of x [count, n] (float64): returns (t int8 [count, n], status int32 [count])."""
+    import torch
+    if x.dim() != 2:
+        raise ValueError("x must be [count, n]")
+    _need(x, torch.float64, x.shape, "x")
+    count, n = x.shape
+    t = torch.empty((count, n), dtype=torch.int8, device=x.device)
+    status = torch.empty((count,), dtype=torch.int32, device=x.device)
+    _check(load_library().tsvd_ternarize(x.data_ptr(), n, count, n, float(theta), t.data_ptr(), n, status.data_ptr(),
+                                         _stream(x, stream)), "tsvd_ternarize")
+    return t, status
+
+
+def tsvd_fit_scales(U, V, W, stream=None):
+    """Eq. (3): S [K] float64 for U int8 [M, K], V int8 [K, N], W float64 [M, N]; also returns the solver's iteration count tensor."""
+    import torch
+    M, K = U.shape
+    N = V.shape[1]
+    _need(U, torch.int8, (M, K), "U"); _need(V, torch.int8, (K, N), "V"); _need(W, torch.float64, (M, N), "W")
+    S = torch.empty((K,), dtype=torch.float64, device=W.device)
+    iters = torch.zeros((1,), dtype=torch.int32, device=W.device)
+    nbytes = int(load_library().tsvd_fit_scales_workspace(K))
+    ws = torch.empty((max(nbytes, 256),), dtype=torch.uint8, device=W.device)
+    _check(load_library().tsvd_fit_scales(U.data_ptr(), K, V.data_ptr(), W.data_ptr(), M, K, N, S.data_ptr(), ws.data_ptr(), nbytes,
+                                          iters.data_ptr(), _stream(W, stream)), "tsvd_fit_scales")
+    return S, iters
+
+
+def tsvd_residual(W, U, S, V, stream=None):
+    """R = W - U diag(S) V (float64 [M, N]) and |R|_F^2 (float64 [1])."""
+    import torch
+    M, K = U.shape
+    N = V.shape[1]
+    _need(U, torch.int8, (M, K), "U"); _need(V, torch.int8, (K, N), "V"); _need(W, torch.float64, (M, N), "W")
+    _need(S, torch.float64, (K,), "S")
+    R = torch.empty_like(W)
+    norm2 = torch.empty((1,), dtype=torch.float64, device=W.device)
+    _check(load_library().tsvd_residual(W.data_ptr(), U.data_ptr(), K, S.data_ptr(), V.data_ptr(), M, K, N, R.data_ptr(),
+                                        norm2.data_ptr(), _stream(W, stream)), "tsvd_residual")
+    return R, norm2
+
+
+def tsvd_leading_singular_pair(R, max_iters: int = 4000, stream=None):
+    """(u [M], sigma [1], v [N], iterations [1]) of R float64 [M, N] by power iteration."""
+    import torch
+    M, N = R.shape
+    _need(R, torch.float64, (M, N), "R")
+    u = torch.empty((M,), dtype=torch.float64, device=R.device)
+    v = torch.empty((N,), dtype=torch.float64, device=R.device)
+    sigma = torch.empty((1,), dtype=torch.float64, device=R.device)
+    iters = torch.zeros((1,), dtype=torch.int32, device=R.device)
+    _check(load_library().tsvd_leading_singular_pair(R.data_ptr(), M, N, int(max_iters), u.data_ptr(), v.data_ptr(), sigma.data_ptr(),
+                                                     iters.data_ptr(), _stream(R, stream)), "tsvd_leading_singular_pair")
+    return u, sigma, v, iters
+
+
+def tsvd_transition(W, theta: float, tol: float, max_rank: int, stream=None):
+    """Algorithm 2 (q = 1) for W float64 [M, N]: returns (U int8 [M, K], S float64 [K], V int8 [K, N], errors list)."""
+    import torch
+    M, N = W.shape
+    _need(W, torch.float64, (M, N), "W")
+    U = torch.empty((M, max_rank), dtype=torch.int8, device=W.device)
+    V = torch.empty((max_rank, N), dtype=torch.int8, device=W.device)
+    S = torch.empty((max_rank,), dtype=torch.float64, device=W.device)
+    rank = _i64(0)
+    errors = np.zeros(max_rank, dtype=np.float64)
+    status = load_library().tsvd_transition(W.data_ptr(), M, N, float(theta), float(tol), int(max_rank), U.data_ptr(), S.data_ptr(),
+                                            V.data_ptr(), ctypes.byref(rank), errors.ctypes.data, _stream(W, stream))
+    K = int(rank.value)
+    if status != 0 and not (status == 2 and K > 0):
+        _check(status, "tsvd_transition")
+    return U[:, :K].contiguous(), S[:K].clone(), V[:K, :].contiguous(), errors[:K].tolist(), status
 
 
 def tsvd_free(h: Handle) -> None:

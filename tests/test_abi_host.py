@@ -14,17 +14,22 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "tsvd.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(tsvd_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if header.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", header)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(tsvd_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
     names = _declared_functions()
-    assert {"tsvd_pack", "tsvd_forward", "tsvd_free"} <= set(names)
+    assert {"tsvd_pack", "tsvd_forward", "tsvd_forward_ex", "tsvd_free", "tsvd_ternarize", "tsvd_fit_scales",
+            "tsvd_transition"} <= set(names)
     lib = ctypes.CDLL(tsvd.lib_path())
     for n in names:
-        assert hasattr(lib, n), f"{n} declared in include/tsvd.h but not exported"
+        assert hasattr(lib, n), f"{n} declared in include/*.h but not exported"
 
 
 def test_strerror_covers_all_codes():
