@@ -50,13 +50,19 @@ tsvd_status tsvd_residual(const double* W_dev, const int8_t* U_dev, int64_t ldu,
                           int64_t M, int64_t K, int64_t N, double* R_dev, double* norm2_dev, void* stream);
 
 /* First step of an iteration of Algorithm 2 for q = 1: the leading singular triple of R [M][N]
- * by power iteration on R^T R in fp64 (the paper calls a full SVD and keeps the leading vectors;
- * only those are needed).  Stops when the direction moves by less than 1e-12 or after max_iters
- * iterations.
- *   u_dev [M], v_dev [N] : unit vectors; sigma_dev [1]; iters_dev optional int32[1].
- * The sign of the pair (u, v) is arbitrary, as it is for any SVD routine. */
-tsvd_status tsvd_leading_singular_pair(const double* R_dev, int64_t M, int64_t N, int32_t max_iters, double* u_dev,
-                                       double* v_dev, double* sigma_dev, int32_t* iters_dev, void* stream);
+ * (the paper calls a full SVD and keeps the leading vectors; only those are needed), by
+ * Golub-Kahan-Lanczos bidiagonalisation with full reorthogonalisation in fp64: tens of steps where
+ * a power iteration needs thousands on the close singular values of a random matrix.  The small
+ * bidiagonal problem is solved on the host, so the call SYNCHRONISES with the stream.  Stops when
+ * the residual |R^T u - sigma v| of the pair is below 1e-12 sigma, restarting from the current
+ * estimate every 128 steps, or after max_steps steps in total.
+ *   u_dev [M], v_dev [N] : unit vectors; sigma_dev [1]; steps_dev optional int32[1].
+ *   workspace : device, at least tsvd_leading_singular_pair_workspace(M, N) bytes, 256-byte aligned.
+ * The sign of the pair (u, v) is arbitrary, as it is for any SVD routine.  M, N <= 8192. */
+size_t tsvd_leading_singular_pair_workspace(int64_t M, int64_t N);
+tsvd_status tsvd_leading_singular_pair(const double* R_dev, int64_t M, int64_t N, int32_t max_steps, double* u_dev,
+                                       double* v_dev, double* sigma_dev, int32_t* steps_dev, void* workspace,
+                                       size_t workspace_bytes, void* stream);
 
 /* Algorithm 2 with q = 1, chaining the calls above: until |W - U diag(S) V|_F / |W|_F <= tol or
  * the rank reaches max_rank.  SYNCHRONISES with the stream once per iteration (the exit test

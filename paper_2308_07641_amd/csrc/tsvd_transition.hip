@@ -115,25 +115,27 @@ tsvd_ternarize_kernel(const double* __restrict__ x, long long ldx, int n, int np
 // ---- Eq. (3), left side: G[k][l] = (sum_m U[m][k] U[m][l]) (sum_n V[k][n] V[l][n]) ------------------
 // One thread per (k, l), l fastest (U[m][l] is then read along rows; V[l][n] is strided but V is
 // small and cached).  Integer sums, exact.
+// only_row >= 0: just row and column `only_row` (the component appended last; grid.y = 1).
 __global__ void __launch_bounds__(256)
 tsvd_gram_kernel(const int8_t* __restrict__ U, long long ldu, const int8_t* __restrict__ V, int M, int K, int N,
-                 double* __restrict__ G) {
-    const int l = blockIdx.x * 256 + threadIdx.x, k = blockIdx.y;
+                 double* __restrict__ G, long long ldg, int only_row) {
+    const int l = blockIdx.x * 256 + threadIdx.x, k = only_row >= 0 ? only_row : (int)blockIdx.y;
     if (l >= K) return;
     int uu = 0, vv = 0;
     for (int m = 0; m < M; ++m) uu += (int)U[(size_t)m * ldu + k] * (int)U[(size_t)m * ldu + l];
     const int8_t* vk = V + (size_t)k * N;
     const int8_t* vl = V + (size_t)l * N;
     for (int n = 0; n < N; ++n) vv += (int)vk[n] * (int)vl[n];
-    G[(size_t)k * K + l] = (double)uu * (double)vv;
+    G[(size_t)k * ldg + l] = (double)uu * (double)vv;
+    if (only_row >= 0) G[(size_t)l * ldg + k] = (double)uu * (double)vv;
 }
 
 // ---- Eq. (3), right side: d[k] = sum_m sum_n U[m][k] W[m][n] V[k][n]; one workgroup per k ----------
 __global__ void __launch_bounds__(256)
 tsvd_rhs_kernel(const int8_t* __restrict__ U, long long ldu, const int8_t* __restrict__ V, const double* __restrict__ W, int M,
-                int N, double* __restrict__ d) {
+                int N, double* __restrict__ d, int k_first) {
     __shared__ double red[256];
-    const int k = blockIdx.x;
+    const int k = k_first + blockIdx.x;
     const int8_t* vk = V + (size_t)k * N;
     double acc = 0.0;
     for (int m = 0; m < M; ++m) {
@@ -154,7 +156,10 @@ tsvd_rhs_kernel(const int8_t* __restrict__ U, long long ldu, const int8_t* __res
 // (the pseudo-inverse solution).  Vectors live in LDS; G (K^2 fp64) is re-read from L2 each
 // iteration.  Stops at |r| <= 1e-13 |d| or after 20 K iterations.
 __global__ void __launch_bounds__(1024)
-tsvd_pcg_kernel(const double* __restrict__ G, const double* __restrict__ d, int K, double* __restrict__ s, int* __restrict__ iters) {
+// warm: start from the values found in s instead of zero (any least-squares solution gives the
+// same residual; the loop of Algorithm 2 starts from the previous scales).
+tsvd_pcg_kernel(const double* __restrict__ G, long long ldg, const double* __restrict__ d, int K, double* __restrict__ s, int warm,
+                int* __restrict__ iters) {
     extern __shared__ __align__(16) unsigned char smem[];
     double* xs = reinterpret_cast<double*>(smem);   // [K] solution
     double* r = xs + K;                             // residual
@@ -176,11 +181,26 @@ tsvd_pcg_kernel(const double* __restrict__ G, const double* __restrict__ d, int 
         __syncthreads();
         return out;
     };
+    const int wave = tid >> 6, lane = tid & 63;
+    auto matvec = [&](const double* in, double* out) {          // out = G in: one wavefront per row, lanes along the row
+        for (int k = wave; k < K; k += 16) {
+            const double* row = G + (size_t)k * ldg;
+            double v = 0.0;
+            for (int l = lane; l < K; l += 64) v += row[l] * in[l];
+            for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+            if (lane == 0) out[k] = v;
+        }
+        __syncthreads();
+    };
     for (int k = tid; k < K; k += 1024) {
-        const double g = G[(size_t)k * K + k];
+        const double g = G[(size_t)k * ldg + k];
         dg[k] = g > 0.0 ? 1.0 / g : 1.0;
-        xs[k] = 0.0;
-        r[k] = d[k];
+        xs[k] = warm ? s[k] : 0.0;
+    }
+    __syncthreads();
+    if (warm) matvec(xs, q);
+    for (int k = tid; k < K; k += 1024) {
+        r[k] = d[k] - (warm ? q[k] : 0.0);
         p[k] = r[k] * dg[k];
     }
     __syncthreads();
@@ -189,17 +209,9 @@ tsvd_pcg_kernel(const double* __restrict__ G, const double* __restrict__ d, int 
     int it = 0;
     bool converged = !(dd > 0.0);
     const int max_it = 20 * K + 20;
-    const int wave = tid >> 6, lane = tid & 63;
+    if (dd > 0.0 && dot([&](int k) { return r[k] * r[k]; }) <= 1e-26 * dd) converged = true;    // (a warm start may already fit)
     while (!converged && it < max_it) {
-        // q = G p: one wavefront per row, lanes along the row
-        for (int k = wave; k < K; k += 16) {
-            const double* row = G + (size_t)k * K;
-            double v = 0.0;
-            for (int l = lane; l < K; l += 64) v += row[l] * p[l];
-            for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-            if (lane == 0) q[k] = v;
-        }
-        __syncthreads();
+        matvec(p, q);
         const double pq = dot([&](int k) { return p[k] * q[k]; });
         if (!(pq > 0.0)) break;                                 // direction in the null space: done
         const double alpha = rz / pq;
@@ -258,23 +270,28 @@ tsvd_sum_kernel(const double* __restrict__ partial, int count, double* __restric
     if (threadIdx.x == 0) out[0] = total;
 }
 
-// ---- leading singular pair by power iteration on R^T R, one workgroup -------------------------
-// v <- R^T (R v) / |.| until the direction stops moving.  u and v live in LDS; R is re-read
-// from L2 (row by row with one wavefront per row for R v, column-wise with coalesced rows for
-// R^T y).
+// ---- leading singular pair by Golub-Kahan-Lanczos bidiagonalisation, one workgroup ----------------
+// R V_k = U_k B_k with B_k upper bidiagonal (alpha on the diagonal, beta above it):
+//   u_i = R v_i - beta_{i-1} u_{i-1},  alpha_i = |u_i|;   w = R^T u_i - alpha_i v_i,  beta_i = |w|,  v_{i+1} = w / beta_i,
+// every new vector orthogonalised against all earlier ones (classical Gram-Schmidt, twice).  The
+// leading singular triple of the small B_k (found on the host) gives that of R; for the close
+// singular values of a random matrix this needs tens of steps where the power iteration needs
+// thousands.  Steps k0 .. k1 - 1 of a run are done per launch (v_{k0} must be in vb[k0]); the work
+// vectors live in LDS, the bases ub [kmax][M], vb [kmax + 1][N] in global memory (L2).
+#define GKL_MAX_STEPS 128
 __global__ void __launch_bounds__(1024)
-tsvd_power_kernel(const double* __restrict__ R, int M, int N, int max_iters, double* __restrict__ u_out, double* __restrict__ v_out,
-                  double* __restrict__ sigma_out, int* __restrict__ iters_out) {
+tsvd_gkl_kernel(const double* __restrict__ R, int M, int N, int k0, int k1, int fresh, double* __restrict__ ub,
+                double* __restrict__ vb, double* __restrict__ alpha, double* __restrict__ beta) {
     extern __shared__ __align__(16) unsigned char smem[];
-    double* v = reinterpret_cast<double*>(smem);    // [N]
-    double* y = v + N;                              // [M]  R v
-    double* z = y + M;                              // [N]  R^T y, then the next v
-    double* part = z + N;                           // [4][N] partial column sums
-    double* red = part + 4 * (size_t)N;             // [1024]
+    double* u = reinterpret_cast<double*>(smem);    // [M]
+    double* w = u + M;                              // [N]
+    double* part = w + N;                           // [4][N] partial column sums
+    double* coef = part + 4 * (size_t)N;            // [GKL_MAX_STEPS + 1] projections
+    double* red = coef + GKL_MAX_STEPS + 1;         // [1024]
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    auto dot = [&](auto f, int len) {
+    auto norm2 = [&](const double* x, int len) {
         double a = 0.0;
-        for (int k = tid; k < len; k += 1024) a += f(k);
+        for (int k = tid; k < len; k += 1024) a += x[k] * x[k];
         red[tid] = a;
         __syncthreads();
         for (int st = 512; st > 0; st >>= 1) {
@@ -285,63 +302,187 @@ tsvd_power_kernel(const double* __restrict__ R, int M, int N, int max_iters, dou
         __syncthreads();
         return out;
     };
-    // a fixed start vector with no special symmetry
-    for (int n = tid; n < N; n += 1024) v[n] = 1.0 + 0.5 * sin(1.0 + 0.7 * (double)n);
-    __syncthreads();
-    {
-        const double nv = sqrt(dot([&](int k) { return v[k] * v[k]; }, N));
-        for (int n = tid; n < N; n += 1024) v[n] /= nv;
+    // x (LDS, length len) -= sum_j <basis_j, x> basis_j for j < count, twice
+    auto orthogonalise = [&](double* x, int len, const double* basis, int count) {
+        for (int pass = 0; pass < 2 && count > 0; ++pass) {
+            // four basis vectors per wavefront at a time: their loads overlap (one at a time the loop
+            // waits an L2 round trip per vector)
+            for (int j0 = wave * 4; j0 < count; j0 += 64) {
+                double a[4] = {0.0, 0.0, 0.0, 0.0};
+                for (int e = lane; e < len; e += 64) {
+                    const double xe = x[e];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) a[t] += basis[(size_t)min(j0 + t, count - 1) * len + e] * xe;
+                }
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    for (int o = 32; o > 0; o >>= 1) a[t] += __shfl_xor(a[t], o, 64);
+                    if (lane == 0 && j0 + t < count) coef[j0 + t] = a[t];
+                }
+            }
+            __syncthreads();
+            for (int e = tid; e < len; e += 1024) {
+                double a = x[e];
+                for (int j = 0; j < count; ++j) a -= coef[j] * basis[(size_t)j * len + e];
+                x[e] = a;
+            }
+            __syncthreads();
+        }
+    };
+    if (k0 == 0 && fresh) {      // a fixed start vector with no special symmetry (a restart finds its own in vb[0])
+        for (int n = tid; n < N; n += 1024) w[n] = 1.0 + 0.5 * sin(1.0 + 0.7 * (double)n);
+        __syncthreads();
+        const double nv = sqrt(norm2(w, N));
+        for (int n = tid; n < N; n += 1024) vb[n] = w[n] / nv;
         __syncthreads();
     }
-    int it = 0;
-    double sigma = 0.0;
-    for (; it < max_iters; ++it) {
-        for (int m = wave; m < M; m += 16) {                    // y = R v
-            const double* row = R + (size_t)m * N;
-            double a = 0.0;
-            for (int n = lane; n < N; n += 64) a += row[n] * v[n];
-            for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o, 64);
-            if (lane == 0) y[m] = a;
-        }
-        __syncthreads();
-        {                                                       // z = R^T y: four row groups per column
-            const int grp = tid >> 8, t = tid & 255;
-            const int m0 = (int)(((long long)M * grp) / 4), m1 = (int)(((long long)M * (grp + 1)) / 4);
-            for (int n = t; n < N; n += 256) {
-                double a = 0.0;
-                for (int m = m0; m < m1; ++m) a += R[(size_t)m * N + n] * y[m];
-                part[(size_t)grp * N + n] = a;
+    for (int i = k0; i < k1; ++i) {
+        const double* vi = vb + (size_t)i * N;
+        const double bprev = i > 0 ? beta[i - 1] : 0.0;
+        for (int m0 = wave * 4; m0 < M; m0 += 64) {             // u = R v_i - beta_{i-1} u_{i-1}, four rows at a time
+            double a[4] = {0.0, 0.0, 0.0, 0.0};
+            for (int n = lane; n < N; n += 64) {
+                const double vn = vi[n];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) a[t] += R[(size_t)min(m0 + t, M - 1) * N + n] * vn;
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                for (int o = 32; o > 0; o >>= 1) a[t] += __shfl_xor(a[t], o, 64);
+                const int m = m0 + t;
+                if (lane == 0 && m < M) u[m] = a[t] - (i > 0 ? bprev * ub[(size_t)(i - 1) * M + m] : 0.0);
             }
         }
         __syncthreads();
-        for (int n = tid; n < N; n += 1024) z[n] = (part[n] + part[N + n]) + (part[2 * (size_t)N + n] + part[3 * (size_t)N + n]);
-        __syncthreads();
-        const double nz = sqrt(dot([&](int k) { return z[k] * z[k]; }, N));
-        if (!(nz > 0.0)) break;                                 // R v = 0: R is zero (or v is in its null space)
-        const double move = dot([&](int k) { const double dlt = z[k] / nz - v[k]; return dlt * dlt; }, N);
-        for (int n = tid; n < N; n += 1024) v[n] = z[n] / nz;
-        __syncthreads();
-        if (move < 1e-24) {
-            ++it;
-            break;
+        orthogonalise(u, M, ub, i);
+        const double al = sqrt(norm2(u, M));
+        for (int m = tid; m < M; m += 1024) {
+            const double q = al > 0.0 ? u[m] / al : 0.0;
+            u[m] = q;
+            ub[(size_t)i * M + m] = q;
         }
+        __syncthreads();
+        {                                                       // w = R^T u_i - alpha_i v_i: four row groups per column
+            const int grp = tid >> 8, t = tid & 255;
+            const int m0 = (int)(((long long)M * grp) / 4), m1 = (int)(((long long)M * (grp + 1)) / 4);
+            for (int n = t; n < N; n += 256) {
+                double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;      // independent chains: the loads overlap
+                int m = m0;
+                for (; m + 3 < m1; m += 4) {
+                    a0 += R[(size_t)m * N + n] * u[m];
+                    a1 += R[(size_t)(m + 1) * N + n] * u[m + 1];
+                    a2 += R[(size_t)(m + 2) * N + n] * u[m + 2];
+                    a3 += R[(size_t)(m + 3) * N + n] * u[m + 3];
+                }
+                for (; m < m1; ++m) a0 += R[(size_t)m * N + n] * u[m];
+                part[(size_t)grp * N + n] = (a0 + a1) + (a2 + a3);
+            }
+        }
+        __syncthreads();
+        for (int n = tid; n < N; n += 1024)
+            w[n] = (part[n] + part[N + n]) + (part[2 * (size_t)N + n] + part[3 * (size_t)N + n]) - al * vi[n];
+        __syncthreads();
+        orthogonalise(w, N, vb, i + 1);
+        const double be = sqrt(norm2(w, N));
+        for (int n = tid; n < N; n += 1024) vb[(size_t)(i + 1) * N + n] = be > 0.0 ? w[n] / be : 0.0;
+        if (tid == 0) {
+            alpha[i] = al;
+            beta[i] = be;
+        }
+        __threadfence();
+        __syncthreads();
     }
-    // u = R v / sigma with the final v
-    for (int m = wave; m < M; m += 16) {
-        const double* row = R + (size_t)m * N;
+}
+
+// x = sum_j c_j basis_j (j < count), normalised; one workgroup per output vector (blockIdx.x: 0 = u, 1 = v).
+__global__ void __launch_bounds__(256)
+tsvd_combine_kernel(const double* __restrict__ ub, const double* __restrict__ vb, const double* __restrict__ zc,
+                    const double* __restrict__ yc, int count, int M, int N, double* __restrict__ u_out, double* __restrict__ v_out) {
+    __shared__ double red[256];
+    const bool left = blockIdx.x == 0;
+    const double* basis = left ? ub : vb;
+    const double* c = left ? zc : yc;
+    double* out = left ? u_out : v_out;
+    const int len = left ? M : N;
+    double ss = 0.0;
+    for (int e = threadIdx.x; e < len; e += 256) {
         double a = 0.0;
-        for (int n = lane; n < N; n += 64) a += row[n] * v[n];
-        for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o, 64);
-        if (lane == 0) y[m] = a;
+        for (int j = 0; j < count; ++j) a += c[j] * basis[(size_t)j * len + e];
+        out[e] = a;
+        ss += a * a;
     }
-    __syncthreads();
-    sigma = sqrt(dot([&](int k) { return y[k] * y[k]; }, M));
-    for (int m = tid; m < M; m += 1024) u_out[m] = sigma > 0.0 ? y[m] / sigma : 0.0;
-    for (int n = tid; n < N; n += 1024) v_out[n] = v[n];
-    if (tid == 0) {
-        sigma_out[0] = sigma;
-        if (iters_out) iters_out[0] = it;
+    const double nrm = sqrt(block_sum256(ss, red));
+    for (int e = threadIdx.x; e < len; e += 256) out[e] = nrm > 0.0 ? out[e] / nrm : 0.0;
+}
+
+// Largest eigenpair of the symmetric tridiagonal matrix (diagonal d, off-diagonal e) of order k, on
+// the host: bisection on the Sturm count, then inverse iteration with a pivoted tridiagonal solve.
+double tridiagonal_top_eigenpair(const std::vector<double>& d, const std::vector<double>& e, int k, std::vector<double>& x) {
+    double lo = 0.0, hi = 0.0;
+    for (int i = 0; i < k; ++i) {
+        const double r = (i > 0 ? std::fabs(e[i - 1]) : 0.0) + (i + 1 < k ? std::fabs(e[i]) : 0.0);
+        hi = std::max(hi, d[i] + r);
+        lo = std::min(lo, d[i] - r);
     }
+    auto count_below = [&](double xq) {          // number of eigenvalues < xq
+        int c = 0;
+        double q = 1.0;
+        for (int i = 0; i < k; ++i) {
+            q = d[i] - xq - (i > 0 ? e[i - 1] * e[i - 1] / q : 0.0);
+            if (q == 0.0) q = 1e-300;
+            if (q < 0.0) ++c;
+        }
+        return c;
+    };
+    double a = lo, b = hi;
+    for (int it = 0; it < 200 && b - a > 4e-16 * std::max(std::fabs(a), std::fabs(b)); ++it) {
+        const double mid = 0.5 * (a + b);
+        if (count_below(mid) >= k) b = mid; else a = mid;      // the largest eigenvalue lies in (a, b]
+    }
+    const double lam = 0.5 * (a + b);
+    // inverse iteration: (T - lam I) x = rhs by Gaussian elimination with partial pivoting (band of width 2)
+    x.assign(k, 0.0);
+    std::vector<double> rhs(k);
+    for (int i = 0; i < k; ++i) rhs[i] = 1.0 + 0.3 * std::sin(1.0 + (double)i);
+    const double shift = lam + 1e-13 * std::max(std::fabs(lam), 1e-300);
+    for (int round = 0; round < 4; ++round) {
+        std::vector<double> dl(k, 0.0), dm(k), du(k, 0.0), du2(k, 0.0), bb = rhs;
+        for (int i = 0; i < k; ++i) {
+            dm[i] = d[i] - shift;
+            if (i + 1 < k) { du[i] = e[i]; dl[i] = e[i]; }
+        }
+        for (int i = 0; i + 1 < k; ++i) {
+            if (std::fabs(dm[i]) >= std::fabs(dl[i])) {
+                if (dm[i] == 0.0) dm[i] = 1e-300;
+                const double f = dl[i] / dm[i];
+                dm[i + 1] -= f * du[i];
+                bb[i + 1] -= f * bb[i];
+                dl[i] = 0.0;
+            } else {                                            // swap rows i and i + 1
+                const double f = dm[i] / dl[i];
+                dm[i] = dl[i];
+                const double t1 = dm[i + 1];
+                dm[i + 1] = du[i] - f * t1;
+                du[i] = t1;
+                if (i + 2 < k) {
+                    du2[i] = du[i + 1];
+                    du[i + 1] = -f * du2[i];
+                }
+                std::swap(bb[i], bb[i + 1]);
+                bb[i + 1] -= f * bb[i];
+            }
+        }
+        if (dm[k - 1] == 0.0) dm[k - 1] = 1e-300;
+        x[k - 1] = bb[k - 1] / dm[k - 1];
+        if (k > 1) x[k - 2] = (bb[k - 2] - du[k - 2] * x[k - 1]) / dm[k - 2];
+        for (int i = k - 3; i >= 0; --i) x[i] = (bb[i] - du[i] * x[i + 1] - du2[i] * x[i + 2]) / dm[i];
+        double nrm = 0.0;
+        for (int i = 0; i < k; ++i) nrm += x[i] * x[i];
+        nrm = std::sqrt(nrm);
+        for (int i = 0; i < k; ++i) x[i] /= nrm;
+        rhs = x;
+    }
+    return lam;
 }
 
 int pow2_at_least(int64_t v) {
@@ -379,10 +520,10 @@ extern "C" tsvd_status tsvd_fit_scales(const int8_t* U_dev, int64_t ldu, const i
     double* G = static_cast<double*>(workspace);
     double* d = reinterpret_cast<double*>(static_cast<uint8_t*>(workspace) + round256((size_t)K * (size_t)K * 8));
     hipLaunchKernelGGL(tsvd_gram_kernel, dim3((unsigned)((K + 255) / 256), (unsigned)K), dim3(256), 0, s, U_dev, (long long)ldu,
-                       V_dev, (int)M, (int)K, (int)N, G);
-    hipLaunchKernelGGL(tsvd_rhs_kernel, dim3((unsigned)K), dim3(256), 0, s, U_dev, (long long)ldu, V_dev, W_dev, (int)M, (int)N, d);
+                       V_dev, (int)M, (int)K, (int)N, G, (long long)K, -1);
+    hipLaunchKernelGGL(tsvd_rhs_kernel, dim3((unsigned)K), dim3(256), 0, s, U_dev, (long long)ldu, V_dev, W_dev, (int)M, (int)N, d, 0);
     const size_t lds = (size_t)5 * K * 8 + 1024 * 8;
-    hipLaunchKernelGGL(tsvd_pcg_kernel, dim3(1), dim3(1024), lds, s, G, d, (int)K, S_dev, iters_dev);
+    hipLaunchKernelGGL(tsvd_pcg_kernel, dim3(1), dim3(1024), lds, s, G, (long long)K, d, (int)K, S_dev, 0, iters_dev);
     return hipGetLastError() == hipSuccess ? TSVD_OK : TSVD_EDEVICE;
 }
 
@@ -407,15 +548,75 @@ extern "C" tsvd_status tsvd_residual(const double* W_dev, const int8_t* U_dev, i
     return hipGetLastError() == hipSuccess ? TSVD_OK : TSVD_EDEVICE;
 }
 
-extern "C" tsvd_status tsvd_leading_singular_pair(const double* R_dev, int64_t M, int64_t N, int32_t max_iters, double* u_dev,
-                                                  double* v_dev, double* sigma_dev, int32_t* iters_dev, void* stream) {
-    if (!R_dev || !u_dev || !v_dev || !sigma_dev || M < 1 || N < 1 || M > TERN_MAX_N || N > TERN_MAX_N || max_iters < 1)
+extern "C" size_t tsvd_leading_singular_pair_workspace(int64_t M, int64_t N) {
+    if (M < 1 || N < 1 || M > TERN_MAX_N || N > TERN_MAX_N) return 0;
+    return round256((size_t)GKL_MAX_STEPS * M * 8) + round256((size_t)(GKL_MAX_STEPS + 1) * N * 8) + 4 * round256(GKL_MAX_STEPS * 8);
+}
+
+extern "C" tsvd_status tsvd_leading_singular_pair(const double* R_dev, int64_t M, int64_t N, int32_t max_steps, double* u_dev,
+                                                  double* v_dev, double* sigma_dev, int32_t* steps_dev, void* workspace,
+                                                  size_t workspace_bytes, void* stream) {
+    if (!R_dev || !u_dev || !v_dev || !sigma_dev || !workspace || M < 1 || N < 1 || M > TERN_MAX_N || N > TERN_MAX_N ||
+        max_steps < 1)
         return TSVD_EINVAL;
-    const size_t lds = ((size_t)6 * N + (size_t)M) * 8 + 1024 * 8;
+    if (workspace_bytes < tsvd_leading_singular_pair_workspace(M, N) || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return TSVD_EINVAL;
+    const size_t lds = ((size_t)M + 5 * (size_t)N + GKL_MAX_STEPS + 1 + 1024) * 8;
     if (lds > 150 * 1024) return TSVD_EUNSUPPORTED;
-    hipLaunchKernelGGL(tsvd_power_kernel, dim3(1), dim3(1024), lds, static_cast<hipStream_t>(stream), R_dev, (int)M, (int)N,
-                       (int)max_iters, u_dev, v_dev, sigma_dev, iters_dev);
-    return hipGetLastError() == hipSuccess ? TSVD_OK : TSVD_EDEVICE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t* w8 = static_cast<uint8_t*>(workspace);
+    double* ub = reinterpret_cast<double*>(w8);
+    double* vb = reinterpret_cast<double*>(w8 + round256((size_t)GKL_MAX_STEPS * M * 8));
+    double* alpha = reinterpret_cast<double*>(reinterpret_cast<uint8_t*>(vb) + round256((size_t)(GKL_MAX_STEPS + 1) * N * 8));
+    double* beta = alpha + round256(GKL_MAX_STEPS * 8) / 8;
+    double* zc = beta + round256(GKL_MAX_STEPS * 8) / 8;
+    double* yc = zc + round256(GKL_MAX_STEPS * 8) / 8;
+    const int kmax = (int)std::min<int64_t>(GKL_MAX_STEPS, std::min(M, N));   // the Krylov space cannot outgrow the matrix
+    std::vector<double> ha(GKL_MAX_STEPS), hb(GKL_MAX_STEPS), d, e, y, z;
+    int total = 0, fresh = 1;
+    double theta = 0.0;
+    for (;;) {
+        int k = 0;
+        bool done = false;
+        while (!done) {
+            const int k1 = std::min(kmax, k == 0 ? std::min(32, kmax) : k + 16);
+            hipLaunchKernelGGL(tsvd_gkl_kernel, dim3(1), dim3(1024), lds, s, R_dev, (int)M, (int)N, k, k1, fresh, ub, vb, alpha, beta);
+            if (hipMemcpyAsync(ha.data(), alpha, (size_t)k1 * 8, hipMemcpyDeviceToHost, s) != hipSuccess ||
+                hipMemcpyAsync(hb.data(), beta, (size_t)k1 * 8, hipMemcpyDeviceToHost, s) != hipSuccess ||
+                hipStreamSynchronize(s) != hipSuccess)
+                return TSVD_EDEVICE;
+            total += k1 - k;
+            k = k1;
+            // leading singular triple of the k x k upper bidiagonal B through T = B^T B
+            d.assign(k, 0.0);
+            e.assign(k > 1 ? k - 1 : 0, 0.0);
+            for (int i = 0; i < k; ++i) {
+                d[i] = ha[i] * ha[i] + (i > 0 ? hb[i - 1] * hb[i - 1] : 0.0);
+                if (i + 1 < k) e[i] = ha[i] * hb[i];
+            }
+            const double lam = tridiagonal_top_eigenpair(d, e, k, y);
+            theta = std::sqrt(std::max(lam, 0.0));
+            z.assign(k, 0.0);
+            for (int i = 0; i < k; ++i) z[i] = theta > 0.0 ? (ha[i] * y[i] + (i + 1 < k ? hb[i] * y[i + 1] : 0.0)) / theta : 0.0;
+            const double resid = hb[k - 1] * std::fabs(z[k - 1]);        // |R^T u - theta v| of the Ritz pair
+            done = resid <= 1e-12 * theta || k >= kmax || total >= max_steps || !(theta > 0.0);
+            if (done) {
+                if (hipMemcpyAsync(zc, z.data(), (size_t)k * 8, hipMemcpyHostToDevice, s) != hipSuccess ||
+                    hipMemcpyAsync(yc, y.data(), (size_t)k * 8, hipMemcpyHostToDevice, s) != hipSuccess)
+                    return TSVD_EDEVICE;
+                hipLaunchKernelGGL(tsvd_combine_kernel, dim3(2), dim3(256), 0, s, ub, vb, zc, yc, k, (int)M, (int)N, u_dev, v_dev);
+                if (hipStreamSynchronize(s) != hipSuccess) return TSVD_EDEVICE;    // (z, y are host vectors reused below)
+                if (resid <= 1e-12 * theta || total >= max_steps || !(theta > 0.0) || kmax < GKL_MAX_STEPS) {
+                    if (hipMemcpy(sigma_dev, &theta, 8, hipMemcpyHostToDevice) != hipSuccess) return TSVD_EDEVICE;
+                    if (steps_dev && hipMemcpy(steps_dev, &total, 4, hipMemcpyHostToDevice) != hipSuccess) return TSVD_EDEVICE;
+                    return hipGetLastError() == hipSuccess ? TSVD_OK : TSVD_EDEVICE;
+                }
+            }
+        }
+        // not converged within the basis: restart from the current estimate of v
+        if (hipMemcpyAsync(vb, v_dev, (size_t)N * 8, hipMemcpyDeviceToDevice, s) != hipSuccess) return TSVD_EDEVICE;
+        fresh = 0;
+    }
 }
 
 hipError_t tsvd_transition_init() {
@@ -426,7 +627,7 @@ hipError_t tsvd_transition_init() {
                                  5 * FIT_MAX_K * 8 + 1024 * 8)) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_residual_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  FIT_MAX_K * 8)) != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_power_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gkl_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
 }
 
 extern "C" tsvd_status tsvd_transition(const double* W_dev, int64_t M, int64_t N, double theta, double tol, int64_t max_rank,
@@ -440,8 +641,10 @@ extern "C" tsvd_status tsvd_transition(const double* W_dev, int64_t M, int64_t N
     // scratch: R [M][N], u [M], v [N], t_u [M] int8, sigma, |R|^2, status[2], fit workspace
     const size_t bytes_R = round256((size_t)M * N * 8), bytes_u = round256((size_t)M * 8), bytes_v = round256((size_t)N * 8);
     const size_t bytes_tu = round256((size_t)M), bytes_misc = 256, bytes_fit = tsvd_fit_scales_workspace(max_rank);
+    const size_t bytes_svd = tsvd_leading_singular_pair_workspace(M, N);
     uint8_t* base = nullptr;
-    if (hipMalloc(reinterpret_cast<void**>(&base), bytes_R + bytes_u + bytes_v + bytes_tu + bytes_misc + bytes_fit) != hipSuccess) {
+    if (hipMalloc(reinterpret_cast<void**>(&base), bytes_R + bytes_u + bytes_v + bytes_tu + bytes_misc + bytes_fit + bytes_svd) !=
+        hipSuccess) {
         (void)hipGetLastError();
         return TSVD_EDEVICE;
     }
@@ -451,7 +654,10 @@ extern "C" tsvd_status tsvd_transition(const double* W_dev, int64_t M, int64_t N
     int8_t* tu = reinterpret_cast<int8_t*>(base + bytes_R + bytes_u + bytes_v);
     double* misc = reinterpret_cast<double*>(base + bytes_R + bytes_u + bytes_v + bytes_tu);   // [0] sigma, [1] |R|^2
     int32_t* flags = reinterpret_cast<int32_t*>(misc + 4);                                     // ternarize status x 2
-    void* fit_ws = base + bytes_R + bytes_u + bytes_v + bytes_tu + bytes_misc;
+    uint8_t* fit_ws = base + bytes_R + bytes_u + bytes_v + bytes_tu + bytes_misc;
+    double* G = reinterpret_cast<double*>(fit_ws);                              // [max_rank][max_rank], grown row by row
+    double* dvec = reinterpret_cast<double*>(fit_ws + round256((size_t)max_rank * (size_t)max_rank * 8));
+    void* svd_ws = fit_ws + bytes_fit;
 
     tsvd_status st = TSVD_OK;
     auto ok = [&](hipError_t e) {
@@ -468,7 +674,7 @@ extern "C" tsvd_status tsvd_transition(const double* W_dev, int64_t M, int64_t N
     ok(hipStreamSynchronize(s));
     int64_t K = 0;
     while (st == TSVD_OK && K < max_rank && wnorm2 > 0.0) {
-        st = tsvd_leading_singular_pair(R, M, N, 4000, u, v, misc, nullptr, s);
+        st = tsvd_leading_singular_pair(R, M, N, 4 * GKL_MAX_STEPS, u, v, misc, nullptr, svd_ws, bytes_svd, s);
         if (st != TSVD_OK) break;
         // column K of U (row stride max_rank) is written through a contiguous temporary
         st = tsvd_ternarize(u, M, 1, M, theta, tu, M, flags, s);
@@ -483,8 +689,15 @@ extern "C" tsvd_status tsvd_transition(const double* W_dev, int64_t M, int64_t N
             break;
         }
         ++K;
-        st = tsvd_fit_scales(U_dev, max_rank, V_dev, W_dev, M, K, N, S_dev, fit_ws, bytes_fit, nullptr, s);
-        if (st != TSVD_OK) break;
+        // Eq. (3) with what changed only: row / column K - 1 of the Gram matrix and entry K - 1 of the right
+        // side; the solve starts from the previous scales (the new one at 0, set when S was cleared)
+        hipLaunchKernelGGL(tsvd_gram_kernel, dim3((unsigned)((K + 255) / 256), 1), dim3(256), 0, s, U_dev, (long long)max_rank, V_dev,
+                           (int)M, (int)K, (int)N, G, (long long)max_rank, (int)(K - 1));
+        hipLaunchKernelGGL(tsvd_rhs_kernel, dim3(1), dim3(256), 0, s, U_dev, (long long)max_rank, V_dev, W_dev, (int)M, (int)N, dvec,
+                           (int)(K - 1));
+        hipLaunchKernelGGL(tsvd_pcg_kernel, dim3(1), dim3(1024), (size_t)5 * K * 8 + 1024 * 8, s, G, (long long)max_rank, dvec, (int)K,
+                           S_dev, 1, static_cast<int*>(nullptr));
+        if (!ok(hipGetLastError())) break;
         st = tsvd_residual(W_dev, U_dev, max_rank, S_dev, V_dev, M, K, N, R, misc + 1, s);
         if (st != TSVD_OK) break;
         double rnorm2 = 0.0;

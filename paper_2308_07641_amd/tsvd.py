@@ -40,7 +40,8 @@ _PROTOTYPES = {
     "tsvd_fit_scales_workspace": (_sz, [_i64]),
     "tsvd_fit_scales": (ctypes.c_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _sz, _vp, _vp]),
     "tsvd_residual": (ctypes.c_int, [_vp, _vp, _i64, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp]),
-    "tsvd_leading_singular_pair": (ctypes.c_int, [_vp, _i64, _i64, ctypes.c_int32, _vp, _vp, _vp, _vp, _vp]),
+    "tsvd_leading_singular_pair_workspace": (_sz, [_i64, _i64]),
+    "tsvd_leading_singular_pair": (ctypes.c_int, [_vp, _i64, _i64, ctypes.c_int32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "tsvd_transition": (ctypes.c_int, [_vp, _i64, _i64, ctypes.c_double, ctypes.c_double, _i64, _vp, _vp, _vp, _pi64, _vp, _vp]),
     "tsvd_free": (None, [_vp]),
     "tsvd_strerror": (ctypes.c_char_p, [ctypes.c_int]),
@@ -299,8 +300,8 @@ def tsvd_residual(W, U, S, V, stream=None):
     return R, norm2
 
 
-def tsvd_leading_singular_pair(R, max_iters: int = 4000, stream=None):
-    """(u [M], sigma [1], v [N], iterations [1]) of R float64 [M, N] by power iteration."""
+def tsvd_leading_singular_pair(R, max_iters: int = 512, stream=None):
+    """(u [M], sigma [1], v [N], steps [1]) of R float64 [M, N] by Lanczos bidiagonalisation."""
     import torch
     M, N = R.shape
     _need(R, torch.float64, (M, N), "R")
@@ -308,8 +309,11 @@ def tsvd_leading_singular_pair(R, max_iters: int = 4000, stream=None):
     v = torch.empty((N,), dtype=torch.float64, device=R.device)
     sigma = torch.empty((1,), dtype=torch.float64, device=R.device)
     iters = torch.zeros((1,), dtype=torch.int32, device=R.device)
+    nbytes = int(load_library().tsvd_leading_singular_pair_workspace(M, N))
+    ws = torch.empty((max(nbytes, 256),), dtype=torch.uint8, device=R.device)
     _check(load_library().tsvd_leading_singular_pair(R.data_ptr(), M, N, int(max_iters), u.data_ptr(), v.data_ptr(), sigma.data_ptr(),
-                                                     iters.data_ptr(), _stream(R, stream)), "tsvd_leading_singular_pair")
+                                                     iters.data_ptr(), ws.data_ptr(), nbytes, _stream(R, stream)),
+           "tsvd_leading_singular_pair")
     return u, sigma, v, iters
 
 

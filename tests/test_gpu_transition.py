@@ -82,8 +82,8 @@ def test_fit_scales_minimum_norm_for_duplicated_components(tsvd):
 
 @pytest.mark.parametrize("M,N", [(40, 30), (512, 256), (100, 700)])
 def test_leading_singular_pair(tsvd, M, N):
-    """Against the library SVD on a matrix with a clear leading component (gap 2: the power
-    iteration converges to rounding) and on a plain Laplace matrix (sigma to 1e-6 relative)."""
+    """Against the library SVD on a matrix with a clear leading component and on a plain Laplace
+    matrix, whose leading singular values are close (the Lanczos process must still separate them)."""
     rng = np.random.default_rng(M + N)
     u0 = rng.standard_normal(M); u0 /= np.linalg.norm(u0)
     v0 = rng.standard_normal(N); v0 /= np.linalg.norm(v0)
@@ -93,12 +93,12 @@ def test_leading_singular_pair(tsvd, M, N):
         u, sigma, v, iters = tsvd.tsvd_leading_singular_pair(_dev(R))
         u, sigma, v = u.cpu().numpy(), float(sigma.cpu()[0]), v.cpu().numpy()
         ur, sr, vr = np.linalg.svd(R, full_matrices=False)
-        print(f"case power M={M} N={N} planted={planted}: {int(iters.cpu()[0])} iterations", flush=True)
+        print(f"case leading pair M={M} N={N} planted={planted}: {int(iters.cpu()[0])} steps, gap {1 - sr[1] / sr[0]:.4f}", flush=True)
         assert abs(np.linalg.norm(u) - 1) < 1e-12 and abs(np.linalg.norm(v) - 1) < 1e-12
-        assert abs(sigma - sr[0]) <= (1e-12 if planted else 1e-6) * sr[0]
-        if planted:
-            sign = np.sign(u @ ur[:, 0])
-            assert np.max(np.abs(sign * u - ur[:, 0])) < 1e-9 and np.max(np.abs(sign * v - vr[0, :])) < 1e-9
+        assert abs(sigma - sr[0]) <= 1e-12 * sr[0]
+        sign = np.sign(u @ ur[:, 0])
+        # (the vectors are determined to about rounding / gap)
+        assert np.max(np.abs(sign * u - ur[:, 0])) < 1e-8 and np.max(np.abs(sign * v - vr[0, :])) < 1e-8
 
 
 def test_transition_follows_the_oracle_on_separated_spectra(tsvd):
