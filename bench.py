@@ -207,6 +207,36 @@ def bench_workload(name, steps, warmup, with_cpu=True, cpu_budget_s=4.0):
     return res
 
 
+def bench_transition(max_rank_gpu=64, max_rank_cpu=24):
+    """NEXT row of the scope table: the direct transition W -> (U, S, V) (Algorithm 2) on the
+    paper's random-matrix setting, a [512, 256] Laplace matrix at theta = 0.576.  A bounded number
+    of iterations is timed on the GPU and, beside it, in the numpy oracle (whose cost per
+    iteration grows with the rank: a full SVD of the residual plus a pseudo-inverse of order K)."""
+    import torch
+    import paper_2308_07641_amd as tsvd
+    from oracle import transition as tr
+    W = np.random.default_rng(4).laplace(size=(512, 256))
+    Wd = torch.from_numpy(W).to("cuda:0")
+    tsvd.tsvd_transition(Wd, 0.576, 0.0, 4)                       # warm-up (allocations, code load)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    U, S, V, errs, status = tsvd.tsvd_transition(Wd, 0.576, 0.0, max_rank_gpu)
+    torch.cuda.synchronize()
+    gpu_s = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    Uo, So, Vo, eo = tr.transition(W, 0.576, max_rank=max_rank_cpu)
+    cpu_s = time.perf_counter() - t0
+    k = min(max_rank_gpu, max_rank_cpu)
+    same = all(np.array_equal(U[:, j].cpu().numpy(), Uo[:, j]) or np.array_equal(-U[:, j].cpu().numpy(), Uo[:, j]) for j in range(k))
+    return {"workload": "transition_laplace_512x256: W fp64 [512,256] Laplace, theta=0.576, q=1",
+            "gpu_ms_per_iteration": gpu_s / max_rank_gpu * 1e3, "gpu_iterations": max_rank_gpu,
+            "relative_error_after": errs[-1], "status": status,
+            "nonzero_rate": float((torch.count_nonzero(U) + torch.count_nonzero(V)).item() / (U.numel() + V.numel())),
+            "cpu_baseline": {"value": cpu_s / max_rank_cpu * 1e3, "unit": "ms/iteration", "kind": "oracle",
+                             "sample": f"first {max_rank_cpu} iterations (numpy SVD + pseudo-inverse)"},
+            "first_components_equal_oracle": bool(same), "oracle_error_after": eo[k - 1], "gpu_error_at_same_rank": errs[k - 1]}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -215,6 +245,9 @@ def main():
     ap.add_argument("--workloads",
                     default="bert_ffn_in,tiny,convnext_mlp,opt6b7_fc1_decode,opt6b7_fc1_decode_b16,opt66b_fc1_prefill")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing / parity leg")
+    ap.add_argument("--no-transition", action="store_true", help="skip the transition (Algorithm 2) measurement")
+    ap.add_argument("--transition-only", action="store_true",
+                    help="run only the transition measurement and print its record (for profiling)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -230,6 +263,10 @@ def main():
     torch.cuda.set_device(0)
     import paper_2308_07641_amd as tsvd
     tsvd.load_library()
+
+    if args.transition_only:
+        print(json.dumps(bench_transition()), flush=True)
+        return
 
     if args.copy_calibration:
         src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda:0")
@@ -249,6 +286,10 @@ def main():
                                 cpu_budget_s=12.0 if n == PRIMARY else 3.0)
         per[n]["steps"] = steps
         print(f"[bench] {n}: {json.dumps(per[n])}", file=sys.stderr, flush=True)
+
+    if not args.no_transition and not args.no_cpu:
+        per["transition_laplace_512x256"] = bench_transition()
+        print(f"[bench] transition: {json.dumps(per['transition_laplace_512x256'])}", file=sys.stderr, flush=True)
 
     p = per[PRIMARY]
     w = workloads.WORKLOADS[PRIMARY]
