@@ -8,3 +8,4 @@ from .tsvd_oracle import (  # noqa: F401
     critical_rank, threads,
 )
 from . import transition  # noqa: F401  (Algorithms 1 and 2, Eq. 3, Theorem 1 in fp64 numpy)
+from . import conv  # noqa: F401  (the four convolution forms through the dense kernel)

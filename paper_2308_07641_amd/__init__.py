@@ -8,4 +8,5 @@ from .tsvd import (  # noqa: F401
     tsvd_packed_bytes, tsvd_pack_host, tsvd_unpack_host, tsvd_pack, tsvd_unpack, tsvd_info,
     tsvd_workspace_bytes, tsvd_forward, tsvd_workspace_bytes_ex, tsvd_forward_ex, tsvd_free, tsvd_strerror,
     tsvd_ternarize, tsvd_fit_scales, tsvd_residual, tsvd_leading_singular_pair, tsvd_transition,
+    tsvd_conv2d_forward,
 )

@@ -43,6 +43,8 @@ _PROTOTYPES = {
     "tsvd_leading_singular_pair_workspace": (_sz, [_i64, _i64]),
     "tsvd_leading_singular_pair": (ctypes.c_int, [_vp, _i64, _i64, ctypes.c_int32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "tsvd_transition": (ctypes.c_int, [_vp, _i64, _i64, ctypes.c_double, ctypes.c_double, _i64, _vp, _vp, _vp, _pi64, _vp, _vp]),
+    "tsvd_conv2d_workspace_bytes": (_sz, [_vp, _vp, _i64, _i64, _i64]),
+    "tsvd_conv2d_forward": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, ctypes.c_int, _vp, _sz, _vp]),
     "tsvd_free": (None, [_vp]),
     "tsvd_strerror": (ctypes.c_char_p, [ctypes.c_int]),
 }
@@ -333,6 +335,36 @@ def tsvd_transition(W, theta: float, tol: float, max_rank: int, stream=None):
     if status != 0 and not (status == 2 and K > 0):
         _check(status, "tsvd_transition")
     return U[:, :K].contiguous(), S[:K].clone(), V[:K, :].contiguous(), errors[:K].tolist(), status
+
+
+# ---- convolution forms (include/tsvd_conv.h)
+class ConvGeometry(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("form", "c_in", "c_out", "k1", "k2", "stride1", "stride2", "pad1", "pad2", "dil1", "dil2")]
+
+
+def tsvd_conv2d_forward(h: Handle, form: int, c_in: int, c_out: int, k1: int, k2: int, x, stride=(1, 1), pad=(0, 0), dil=(1, 1),
+                        bias=None, y_dtype=TSVD_F32, stream=None):
+    """y [C_out, images, Ho, Wo] = conv2d(x [C_in, images, H, W] bf16) with the kernel in ternary-SVD form `form`."""
+    import torch
+    if not x.is_cuda or x.dtype != torch.bfloat16 or x.dim() != 4 or x.shape[0] != c_in or not x.is_contiguous():
+        raise ValueError("x must be a contiguous bf16 GPU tensor [C_in, images, H, W]")
+    _, images, H, W = x.shape
+    g = ConvGeometry(form, c_in, c_out, k1, k2, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1])
+    lib = load_library()
+    nbytes = int(lib.tsvd_conv2d_workspace_bytes(h.ptr, ctypes.addressof(g), images, H, W))
+    if nbytes == 0:
+        raise ValueError("geometry does not fit the packed matrix (or is invalid)")
+    Ho = (H + 2 * pad[0] - dil[0] * (k1 - 1) - 1) // stride[0] + 1
+    Wo = (W + 2 * pad[1] - dil[1] * (k2 - 1) - 1) // stride[1] + 1
+    ws = torch.empty((nbytes,), dtype=torch.uint8, device=x.device)
+    y = torch.empty((c_out, images, Ho, Wo), dtype=torch.bfloat16 if y_dtype == TSVD_BF16 else torch.float32, device=x.device)
+    bias_ptr = None
+    if bias is not None:
+        _need(bias, torch.float32, (c_out,), "bias")
+        bias_ptr = bias.data_ptr()
+    _check(lib.tsvd_conv2d_forward(h.ptr, ctypes.addressof(g), x.data_ptr(), images, H, W, bias_ptr, y.data_ptr(), y_dtype,
+                                   ws.data_ptr(), nbytes, _stream(x, stream)), "tsvd_conv2d_forward")
+    return y
 
 
 def tsvd_free(h: Handle) -> None:
