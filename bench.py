@@ -237,6 +237,43 @@ def bench_transition(max_rank_gpu=64, max_rank_cpu=24):
             "first_components_equal_oracle": bool(same), "oracle_error_after": eo[k - 1], "gpu_error_at_same_rank": errs[k - 1]}
 
 
+def bench_conv(steps=50):
+    """NEXT row of the scope table: a convolution in ternary-SVD form (section "TSVD in Convolution
+    Layer"), a 3 x 3, 256 -> 256 channel layer on 32 images of 14 x 14 (a ResNet-50 stage-4 shape), in
+    form 0 (V is the 3 x 3 convolution: gather, then the linear map) and form 1 (U is: map, then
+    tap sum), rank 768, P(0) = 0.7; the oracle (dense kernel, fp64) is timed on one image."""
+    import torch
+    import paper_2308_07641_amd as tsvd
+    from oracle import conv as oc
+    co = ci = 256
+    k, K, images, H = 3, 768, 32, 14
+    rng = np.random.default_rng(23080764 + 7000)
+    out = {"workload": f"conv3x3 {ci}->{co}, {images} images {H}x{H}, pad 1, rank {K}, bf16 x, fp32 y"}
+    for form in (0, 1):
+        rows, cols = (co, ci * k * k) if form == 0 else (co * k * k, ci)
+        U = rng.choice([-1, 0, 1], size=(rows, K), p=[0.15, 0.7, 0.15]).astype(np.int8)
+        V = rng.choice([-1, 0, 1], size=(K, cols), p=[0.15, 0.7, 0.15]).astype(np.int8)
+        S = (np.abs(rng.standard_normal(K)) * 0.02).astype(np.float32)
+        xb = workloads.f32_to_bf16_bits(rng.standard_normal((ci, images, H, H)).astype(np.float32))
+        x = torch.from_numpy(xb.view(np.int16)).to("cuda:0").view(torch.bfloat16)
+        h = tsvd.tsvd_pack(U, S, V)
+        fn = lambda: tsvd.tsvd_conv2d_forward(h, form, ci, co, k, k, x, (1, 1), (1, 1), (1, 1))
+        _, ev_ms = _timed(fn, steps, 5)
+        y = fn()
+        torch.cuda.synchronize()
+        xr = workloads.bf16_bits_to_f32(xb[:, :1]).transpose(1, 0, 2, 3)
+        t0 = time.perf_counter()
+        ref = oc.tsvd_conv2d(xr, U, S, V, form, co, ci, k, k, (1, 1), (1, 1), (1, 1))
+        cpu_s = time.perf_counter() - t0
+        err = float(np.max(np.abs(y[:, 0].float().cpu().numpy() - ref[0])) / np.max(np.abs(ref)))
+        flops = 2.0 * K * (rows + cols) * images * H * H
+        out[f"form{form}"] = {"ms_per_call": ev_ms, "images_per_s": images / (ev_ms * 1e-3), "executed_tflops": flops / (ev_ms * 1e-3) / 1e12,
+                              "parity_rel_err": err,
+                              "cpu_baseline": {"value": 1.0 / cpu_s, "unit": "images/s", "kind": "oracle", "sample": "1 image"}}
+        tsvd.tsvd_free(h)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -246,6 +283,7 @@ def main():
                     default="bert_ffn_in,tiny,convnext_mlp,opt6b7_fc1_decode,opt6b7_fc1_decode_b16,opt66b_fc1_prefill")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing / parity leg")
     ap.add_argument("--no-transition", action="store_true", help="skip the transition (Algorithm 2) measurement")
+    ap.add_argument("--conv-only", action="store_true", help="run only the convolution-form measurement (for profiling)")
     ap.add_argument("--transition-only", action="store_true",
                     help="run only the transition measurement and print its record (for profiling)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -266,6 +304,9 @@ def main():
 
     if args.transition_only:
         print(json.dumps(bench_transition()), flush=True)
+        return
+    if args.conv_only:
+        print(json.dumps(bench_conv()), flush=True)
         return
 
     if args.copy_calibration:
@@ -290,6 +331,8 @@ def main():
     if not args.no_transition and not args.no_cpu:
         per["transition_laplace_512x256"] = bench_transition()
         print(f"[bench] transition: {json.dumps(per['transition_laplace_512x256'])}", file=sys.stderr, flush=True)
+        per["conv3x3_c256"] = bench_conv()
+        print(f"[bench] conv: {json.dumps(per['conv3x3_c256'])}", file=sys.stderr, flush=True)
 
     p = per[PRIMARY]
     w = workloads.WORKLOADS[PRIMARY]

@@ -57,21 +57,38 @@ bool make_plan(const tsvd_conv_geometry& g, int64_t images, int64_t H, int64_t W
 
 // Columns for V: X[(ci, dy, dx)][(img, py, px)] = x[ci][img][iy][ix] (zero outside the image) with
 // iy = py stride1 + dy dil1 - pad1 where V handles dimension 1, else iy = py (dy = 0); ix likewise.
-// grid (ceil(Wv Hv images / 256), rows); consecutive threads walk along px.
+// grid (ceil(ldx / 8 / 256), rows); a thread owns eight consecutive columns (the position is
+// decomposed once and stepped along px) and writes them with one 16-byte store; consecutive
+// threads walk along px, so the reads stay coalesced up to the stride.
 __global__ void __launch_bounds__(256)
 tsvd_unfold_kernel(const uint16_t* __restrict__ x, int images, int H, int W, int kv1, int kv2, int Hv, int Wv, int s1, int s2,
                    int p1, int p2, int d1, int d2, int v_dim1, int v_dim2, long long Bv, long long ldx, uint16_t* __restrict__ X) {
-    const long long col = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (col >= ldx) return;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const long long col0 = ((long long)blockIdx.x * 256 + threadIdx.x) * 8;
+    if (col0 >= ldx) return;
     const int row = blockIdx.y;
     const int dx = row % kv2, dy = (row / kv2) % kv1, ci = row / (kv1 * kv2);
-    uint16_t v = 0;
-    if (col < Bv) {
-        const int px = (int)(col % Wv), py = (int)((col / Wv) % Hv), img = (int)(col / ((long long)Wv * Hv));
-        const int iy = v_dim1 ? py * s1 + dy * d1 - p1 : py, ix = v_dim2 ? px * s2 + dx * d2 - p2 : px;
-        if (iy >= 0 && iy < H && ix >= 0 && ix < W) v = x[(((size_t)ci * images + img) * H + iy) * W + ix];
+    int px = (int)(col0 % Wv), py = (int)((col0 / Wv) % Hv), img = (int)(col0 / ((long long)Wv * Hv));
+    const uint16_t* xc = x + (size_t)ci * images * H * W;
+    uint32_t e[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        uint32_t v = 0;
+        if (col0 + t < Bv) {
+            const int iy = v_dim1 ? py * s1 + dy * d1 - p1 : py, ix = v_dim2 ? px * s2 + dx * d2 - p2 : px;
+            if (iy >= 0 && iy < H && ix >= 0 && ix < W) v = xc[((size_t)img * H + iy) * W + ix];
+        }
+        e[t] = v;
+        if (++px == Wv) {
+            px = 0;
+            if (++py == Hv) {
+                py = 0;
+                ++img;
+            }
+        }
     }
-    X[(size_t)row * ldx + col] = v;
+    *reinterpret_cast<u32x4*>(X + (size_t)row * ldx + col0) =
+        u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
 }
 
 // Taps of U: y[co][img][oy][ox] = bias[co] + sum_{du1, du2} T[(co, du1, du2)][img][ty][tx] with
@@ -131,7 +148,7 @@ extern "C" tsvd_status tsvd_conv2d_forward(const tsvd_handle* h, const tsvd_conv
     if (gather) {
         uint16_t* cols = reinterpret_cast<uint16_t*>(ws);
         ws += round256((size_t)p.rows_v * p.ldx * 2);
-        hipLaunchKernelGGL(tsvd_unfold_kernel, dim3((unsigned)((p.ldx + 255) / 256), (unsigned)p.rows_v), dim3(256), 0, s,
+        hipLaunchKernelGGL(tsvd_unfold_kernel, dim3((unsigned)((p.ldx / 8 + 255) / 256), (unsigned)p.rows_v), dim3(256), 0, s,
                            static_cast<const uint16_t*>(x_dev), (int)images, (int)H, (int)W, p.kv1, p.kv2, p.Hv, p.Wv, g->stride1,
                            g->stride2, g->pad1, g->pad2, g->dil1, g->dil2, (int)p.v_dim1, (int)p.v_dim2, p.Bv, p.ldx, cols);
         if (hipGetLastError() != hipSuccess) return TSVD_EDEVICE;
