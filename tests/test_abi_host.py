@@ -160,3 +160,30 @@ def test_no_gpu_calls_fail_cleanly_without_a_device():
     with pytest.raises(tsvd.TsvdError) as e:
         tsvd.tsvd_pack(i.U, i.S, i.V)
     assert e.value.status == 4
+
+
+def test_new_entry_points_validate_arguments_before_touching_a_device():
+    """Argument checks of the transition and convolution calls come first: null pointers, sizes out
+    of range and misaligned workspaces are TSVD_EINVAL (1) with no device work (this test runs
+    without a GPU)."""
+    lib = tsvd.load_library()
+    buf = (ctypes.c_double * 64)()
+    p = ctypes.addressof(buf)
+    assert lib.tsvd_ternarize(None, 4, 1, 4, 0.5, p, 4, p, None) == 1
+    assert lib.tsvd_ternarize(p, 0, 1, 4, 0.5, p, 4, p, None) == 1
+    assert lib.tsvd_ternarize(p, 9000, 1, 9000, 0.5, p, 9000, p, None) == 1          # n > 8192
+    assert lib.tsvd_ternarize(p, 4, 1, 3, 0.5, p, 4, p, None) == 1                   # stride < n
+    assert lib.tsvd_fit_scales_workspace(0) == 0 and lib.tsvd_fit_scales_workspace(4096) == 0
+    assert lib.tsvd_fit_scales_workspace(100) >= 100 * 100 * 8 + 100 * 8
+    assert lib.tsvd_fit_scales(p, 4, p, p, 4, 4, 4, p, None, 0, None, None) == 1     # no workspace
+    assert lib.tsvd_fit_scales(p, 2, p, p, 4, 4, 4, p, p, 1 << 20, None, None) == 1  # ldu < K
+    assert lib.tsvd_residual(p, p, 4, p, p, 4, 0, 4, p, None, None) == 1             # K = 0
+    assert lib.tsvd_leading_singular_pair_workspace(0, 5) == 0
+    assert lib.tsvd_leading_singular_pair(p, 4, 4, 10, p, p, p, None, None, 0, None) == 1
+    rank = ctypes.c_int64(0)
+    assert lib.tsvd_transition(p, 4, 4, 0.5, 0.1, 0, p, p, p, ctypes.byref(rank), None, None) == 1   # max_rank = 0
+    assert lib.tsvd_transition(p, 4, 4, 0.5, -1.0, 4, p, p, p, ctypes.byref(rank), None, None) == 1  # tol < 0
+    assert lib.tsvd_conv2d_workspace_bytes(None, p, 1, 4, 4) == 0
+    assert lib.tsvd_conv2d_forward(None, p, p, 1, 4, 4, None, p, 0, p, 0, None) == 1
+    assert lib.tsvd_workspace_bytes_ex(None, 4, 0, 0) == 0
+    assert lib.tsvd_forward_ex(None, p, 0, 0, 1, 1, None, p, 0, 1, None, 0, None) == 1
