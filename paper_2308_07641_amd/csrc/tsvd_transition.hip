@@ -285,8 +285,8 @@ tsvd_gkl_kernel(const double* __restrict__ R, int M, int N, int k0, int k1, int 
     extern __shared__ __align__(16) unsigned char smem[];
     double* u = reinterpret_cast<double*>(smem);    // [M]
     double* w = u + M;                              // [N]
-    double* part = w + N;                           // [4][N] partial column sums
-    double* coef = part + 4 * (size_t)N;            // [GKL_MAX_STEPS + 1] projections
+    double* part = w + N;                           // [4][max(M, N)] partial sums (columns of R^T u, projections)
+    double* coef = part + 4 * (size_t)(M > N ? M : N);   // [GKL_MAX_STEPS + 1] projections
     double* red = coef + GKL_MAX_STEPS + 1;         // [1024]
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     auto norm2 = [&](const double* x, int len) {
@@ -321,9 +321,27 @@ tsvd_gkl_kernel(const double* __restrict__ R, int M, int N, int k0, int k1, int 
                 }
             }
             __syncthreads();
+            // x[e] -= sum_j coef[j] basis_j[e]: for short vectors the basis range is split over groups of
+            // threads (partial sums through `part`), so that all 1024 threads have loads in flight
+            const int groups = len <= 256 ? 4 : len <= 512 ? 2 : 1, per = 1024 / groups;
+            const int grp = tid / per, t = tid - grp * per;
+            const int j0 = (count * grp) / groups, j1 = (count * (grp + 1)) / groups;
+            for (int e = t; e < len; e += per) {
+                double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+                int j = j0;
+                for (; j + 3 < j1; j += 4) {
+                    a0 += coef[j] * basis[(size_t)j * len + e];
+                    a1 += coef[j + 1] * basis[(size_t)(j + 1) * len + e];
+                    a2 += coef[j + 2] * basis[(size_t)(j + 2) * len + e];
+                    a3 += coef[j + 3] * basis[(size_t)(j + 3) * len + e];
+                }
+                for (; j < j1; ++j) a0 += coef[j] * basis[(size_t)j * len + e];
+                part[(size_t)grp * len + e] = (a0 + a1) + (a2 + a3);
+            }
+            __syncthreads();
             for (int e = tid; e < len; e += 1024) {
                 double a = x[e];
-                for (int j = 0; j < count; ++j) a -= coef[j] * basis[(size_t)j * len + e];
+                for (int gq = 0; gq < groups; ++gq) a -= part[(size_t)gq * len + e];
                 x[e] = a;
             }
             __syncthreads();
@@ -366,16 +384,14 @@ tsvd_gkl_kernel(const double* __restrict__ R, int M, int N, int k0, int k1, int 
             const int grp = tid >> 8, t = tid & 255;
             const int m0 = (int)(((long long)M * grp) / 4), m1 = (int)(((long long)M * (grp + 1)) / 4);
             for (int n = t; n < N; n += 256) {
-                double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;      // independent chains: the loads overlap
+                double a[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};      // independent chains: the loads overlap
                 int m = m0;
-                for (; m + 3 < m1; m += 4) {
-                    a0 += R[(size_t)m * N + n] * u[m];
-                    a1 += R[(size_t)(m + 1) * N + n] * u[m + 1];
-                    a2 += R[(size_t)(m + 2) * N + n] * u[m + 2];
-                    a3 += R[(size_t)(m + 3) * N + n] * u[m + 3];
+                for (; m + 7 < m1; m += 8) {
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) a[q] += R[(size_t)(m + q) * N + n] * u[m + q];
                 }
-                for (; m < m1; ++m) a0 += R[(size_t)m * N + n] * u[m];
-                part[(size_t)grp * N + n] = (a0 + a1) + (a2 + a3);
+                for (; m < m1; ++m) a[0] += R[(size_t)m * N + n] * u[m];
+                part[(size_t)grp * N + n] = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
             }
         }
         __syncthreads();
@@ -561,7 +577,7 @@ extern "C" tsvd_status tsvd_leading_singular_pair(const double* R_dev, int64_t M
         return TSVD_EINVAL;
     if (workspace_bytes < tsvd_leading_singular_pair_workspace(M, N) || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return TSVD_EINVAL;
-    const size_t lds = ((size_t)M + 5 * (size_t)N + GKL_MAX_STEPS + 1 + 1024) * 8;
+    const size_t lds = ((size_t)M + (size_t)N + 4 * (size_t)std::max(M, N) + GKL_MAX_STEPS + 1 + 1024) * 8;
     if (lds > 150 * 1024) return TSVD_EUNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t* w8 = static_cast<uint8_t*>(workspace);
