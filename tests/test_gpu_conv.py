@@ -96,6 +96,23 @@ def test_depthwise_7x7_as_a_block_diagonal_map(tsvd):
     assert np.max(np.abs(got - ref)) <= 2e-3 * np.max(np.abs(ref))
 
 
+def test_conv_single_image_odd_sizes_and_1x1(tsvd):
+    """Column counts that are not multiples of 8 (the gathered matrix pads its rows), a 1 x 1 kernel
+    with stride 2 (every form then degenerates to the same map), one image."""
+    import paper_2308_07641_amd as t
+    rng = np.random.default_rng(88)
+    co, ci, K = 10, 6, 12
+    U = rng.choice([-1, 0, 1], size=(co, K)).astype(np.int8)
+    V = rng.choice([-1, 0, 1], size=(K, ci)).astype(np.int8)
+    S = rng.integers(-2, 3, size=K).astype(np.float32)
+    xi = rng.integers(-2, 3, size=(1, ci, 7, 5)).astype(np.float32)
+    geom = ((2, 2), (0, 0), (1, 1))
+    ref = oc.tsvd_conv2d(xi, U, S, V, 0, co, ci, 1, 1, *geom)
+    for form in range(4):
+        got = _run(tsvd, U, S, V, form, co, ci, 1, 1, workloads.f32_to_bf16_bits(xi), geom, None, t.TSVD_F32)
+        assert np.array_equal(got, ref), form
+
+
 def test_conv_rejects_mismatched_geometry(tsvd):
     import torch
     rng = np.random.default_rng(1)

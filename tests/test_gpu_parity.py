@@ -166,6 +166,16 @@ def test_few_token_kernel(tsvd, M, N, K, B, kwlog2, resident, monkeypatch):
     assert rel_err(y3, ref) <= 1e-5 and rel_err(y, y3) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("K", [4096, 4097])
+def test_few_token_kernel_at_the_resident_limit(tsvd, K):
+    """A contraction of exactly two LDS slabs stays resident; one index more takes the hand-over loop."""
+    i = workloads.make_integer_inputs(48, 4096 if K == 4096 else 4100, K, 11, 0.5, "bf16", seed=K)
+    print(f"case few-token resident limit K={K}", flush=True)
+    y, h = run_forward(i)
+    tsvd.tsvd_free(h)
+    assert np.array_equal(y, oracle.forward(i.U, i.S, i.V, i.X))
+
+
 @pytest.mark.parametrize("B", [17, 40, 64])
 def test_few_token_kernel_in_groups(tsvd, B, monkeypatch):
     """Up to 64 tokens go through the few-token kernel in groups of 16 when the weights are large;

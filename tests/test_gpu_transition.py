@@ -122,6 +122,35 @@ def test_transition_follows_the_oracle_on_separated_spectra(tsvd):
     assert np.max(np.abs(np.array(errs) - np.array(eo))) <= 1e-9
 
 
+def test_transition_wide_matrix_and_rank_limit(tsvd):
+    """M < N, exit by the rank limit, status and shapes; the first components equal the oracle's."""
+    W = np.random.default_rng(12).laplace(size=(48, 160))
+    Uo, So, Vo, eo = tr.transition(W, THETA, max_rank=6)
+    U, S, V, errs, status = tsvd.tsvd_transition(_dev(W), THETA, 0.0, 6)
+    assert status == 0 and U.shape == (48, 6) and V.shape == (6, 160) and len(errs) == 6
+    U, V = U.cpu().numpy(), V.cpu().numpy()
+    for k in range(6):
+        sign = 1 if np.array_equal(U[:, k], Uo[:, k]) else -1
+        assert np.array_equal(sign * U[:, k], Uo[:, k]) and np.array_equal(sign * V[k, :], Vo[k, :]), k
+    assert np.max(np.abs(np.array(errs) - np.array(eo))) <= 1e-9
+
+
+def test_transition_reports_a_vector_without_ternary_neighbour(tsvd):
+    """At a tiny theta no ternary vector is close enough: the oracle raises, the GPU call returns
+    the value error with rank 0."""
+    W = np.random.default_rng(13).laplace(size=(40, 30))
+    with pytest.raises(ValueError):
+        tr.transition(W, 0.05, max_rank=3)
+    lib = tsvd.load_library()
+    import ctypes, torch
+    Wd = _dev(W)
+    U = torch.zeros((40, 3), dtype=torch.int8, device="cuda:0"); V = torch.zeros((3, 30), dtype=torch.int8, device="cuda:0")
+    S = torch.zeros((3,), dtype=torch.float64, device="cuda:0")
+    rank = ctypes.c_int64(-1)
+    st = lib.tsvd_transition(Wd.data_ptr(), 40, 30, 0.05, 0.0, 3, U.data_ptr(), S.data_ptr(), V.data_ptr(), ctypes.byref(rank), None, None)
+    assert st == 2 and rank.value == 0
+
+
 def test_transition_on_a_laplace_matrix(tsvd):
     """The paper's random-matrix setting (Laplace entries, theta = 0.576), [128, 64] to tolerance
     7 %: neighbouring singular values are close there, so the leading pair is not unique to
