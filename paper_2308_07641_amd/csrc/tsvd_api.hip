@@ -117,6 +117,21 @@ bool try_gemv(const tsvd_handle* h, const void* x, tsvd_dtype x_dtype, int64_t l
     const tsvd_blob_header& hd = h->hd;
     if (env_int("TSVD_GEMV", 1) == 0 || !tsvd_gemv_fits(hd.Np, hd.Kp)) return false;
     const int mask = tsvd_stage_mask();
+    if (mask == 7 && env_int("TSVD_GEMV_FUSED", 1) != 0 && tsvd_gemv_fused_fits(hd.Mp, hd.Kp, hd.Np)) {
+        // a small matrix: both stages in one launch of one workgroup
+        tsvd_gemv_fused_args f;
+        std::memset(&f, 0, sizeof f);
+        f.tiles_v = h->blob + hd.off_V; f.strips_v = (int)(hd.Kp / 16); f.nkt_v = (int)(hd.Np / 256);
+        f.tiles_u = h->blob + hd.off_U; f.strips_u = (int)((hd.M + 15) / 16); f.nkt_u = (int)(hd.Kp / 256);
+        f.N = (int)hd.N; f.Np = (int)hd.Np; f.Kp = (int)hd.Kp; f.M = (int)hd.M;
+        f.x = x; f.x_is_bf16 = x_dtype == TSVD_BF16; f.ldx = ldx;
+        f.x_vec = ldx == 1 && hd.N % 4 == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
+        f.S = reinterpret_cast<const float*>(h->blob + hd.off_S);
+        f.bound_V = h->bound_V;
+        f.y = y; f.ldy = ldy; f.bias = oo.bias; f.out_bf16 = oo.out_bf16;
+        *st = tsvd_launch_gemv_fused(f, stream) == hipSuccess ? TSVD_OK : TSVD_EDEVICE;
+        return true;
+    }
     // sw strips x kw splits = 16 wavefronts; about one workgroup per compute unit for large matrices
     auto shape = [&](tsvd_gemv_args& a) {
         int sw = 1;

@@ -295,6 +295,149 @@ tsvd_gemv_kernel(tsvd_gemv_args p) {
     TICK(4);
 }
 
+// ---- both stages in one launch of one workgroup (small matrices) ---------------------------------
+// For a matrix of a few dozen tiles a call is nothing but latency: two launches, each with its own
+// round trips for x / z and the weights.  Here one workgroup issues ALL its loads at entry (x, then
+// the tiles of V and of U: at most four per wavefront and stage, held in registers), runs stage V
+// with wavefront w on strips w, w + 16, ..., digitises z straight into LDS, and runs stage U
+// from there: one launch, z never leaves the compute unit, and the U tiles arrive while stage V
+// computes.  Same arithmetic as tsvd_gemv_kernel (exact integer sums, fp64 recombination).
+#define FUSED_MAX_ITEMS 4      // tiles per wavefront and stage
+__global__ void __launch_bounds__(1024)
+tsvd_gemv_fused_kernel(tsvd_gemv_fused_args p) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 15, g = lane >> 4;
+    const int xstride = p.Np + 16, zstride = p.Kp + 16;
+    unsigned char* xplanes = smem;                                              // [8][Np + 16]
+    unsigned char* zplanes = smem + (((size_t)8 * xstride + 255) & ~(size_t)255);   // [8][Kp + 16]
+    float* wred = reinterpret_cast<float*>(zplanes + (((size_t)8 * zstride + 255) & ~(size_t)255));   // [16][16][8]
+    float* scratch = wred + 16 * 128;
+
+    // ---- every load, in the order of need
+    float xv[4];
+    {
+        const int k = 4 * threadIdx.x;
+        if (p.x_vec) {
+            const int kc = min(k, p.N - 4);
+            if (p.x_is_bf16) {
+                const u32x2 v = *reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(p.x) + kc);
+                xv[0] = __uint_as_float(v.x << 16); xv[1] = __uint_as_float(v.x & 0xFFFF0000u);
+                xv[2] = __uint_as_float(v.y << 16); xv[3] = __uint_as_float(v.y & 0xFFFF0000u);
+            } else {
+                const f32x4 v = *reinterpret_cast<const f32x4*>(static_cast<const float*>(p.x) + kc);
+                xv[0] = v.x; xv[1] = v.y; xv[2] = v.z; xv[3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const size_t off = (size_t)min(k + e, p.N - 1) * p.ldx;
+                xv[e] = p.x_is_bf16 ? __uint_as_float(((uint32_t) static_cast<const uint16_t*>(p.x)[off]) << 16)
+                                    : static_cast<const float*>(p.x)[off];
+            }
+        }
+    }
+    // item j of a stage: strip wave + 16 (j / nkt), tile j % nkt (clamped loads; unused items are never consumed)
+    const int rounds_v = (p.strips_v + 15) / 16, rounds_u = (p.strips_u + 15) / 16;
+    u32x4 pv[FUSED_MAX_ITEMS], pu[FUSED_MAX_ITEMS];
+#pragma unroll
+    for (int j = 0; j < FUSED_MAX_ITEMS; ++j) {
+        const int strip = min(wave + 16 * (j / p.nkt_v), p.strips_v - 1), T = j % p.nkt_v;
+        pv[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.tiles_v) + ((size_t)strip * p.nkt_v + T) * 64 + lane);
+    }
+#pragma unroll
+    for (int j = 0; j < FUSED_MAX_ITEMS; ++j) {
+        const int strip = min(wave + 16 * (j / p.nkt_u), p.strips_u - 1), T = j % p.nkt_u;
+        pu[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.tiles_u) + ((size_t)strip * p.nkt_u + T) * 64 + lane);
+    }
+
+    // ---- x -> digit planes in LDS
+    float m = 0.f;
+    {
+        const int k = 4 * threadIdx.x;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            xv[e] = k + e < p.N ? xv[e] : 0.f;
+            m = fmaxf(m, fabsf(xv[e]));
+        }
+    }
+    m = wave_max(m);
+    if (lane == 0) scratch[wave] = m;
+    __syncthreads();
+    m = wave_max(scratch[lane & 15]);
+    const int ex_x = bound_exponent(m);
+    const int ex_z = bound_exponent(p.bound_V * m) + 1;
+    {
+        const int k = 4 * threadIdx.x;
+        if (k < p.Np) {
+            uint32_t ev[4], od[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) digit_codes(xv[e], ex_x, ev[e], od[e]);
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const uint32_t we = ((ev[0] >> (8 * d)) & 0xFFu) | (((ev[1] >> (8 * d)) & 0xFFu) << 8) |
+                                    (((ev[2] >> (8 * d)) & 0xFFu) << 16) | (((ev[3] >> (8 * d)) & 0xFFu) << 24);
+                const uint32_t wo = ((od[0] >> (8 * d)) & 0xFFu) | (((od[1] >> (8 * d)) & 0xFFu) << 8) |
+                                    (((od[2] >> (8 * d)) & 0xFFu) << 16) | (((od[3] >> (8 * d)) & 0xFFu) << 24);
+                *reinterpret_cast<uint32_t*>(xplanes + (size_t)(2 * d) * xstride + k) = we;
+                *reinterpret_cast<uint32_t*>(xplanes + (size_t)(2 * d + 1) * xstride + k) = wo;
+            }
+        }
+    }
+    __syncthreads();
+
+    // One round of a stage: wavefront w multiplies strip w + 16 r with the planes, the 256 rows of
+    // the round are finished by threads 0..255 (row t of the round) from the plane sums in LDS.
+    auto round_sums = [&](const u32x4 (&tiles)[FUSED_MAX_ITEMS], int r, int nkt, const unsigned char* planes, int pstride) {
+        const unsigned char* xlane = planes + (size_t)(i & 7) * pstride + 32 * g;
+        f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < FUSED_MAX_ITEMS; ++j)
+            if (j / nkt == r) tile_steps(tiles[j], xlane + (j % nkt) * 256, acc0, acc1);
+        if (i < 8) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) wred[wave * 128 + (4 * g + v) * 8 + i] = acc0[v] + acc1[v];
+        }
+    };
+    // ---- stage V: z = S * (V x), digitised into LDS
+    for (int r = 0; r < rounds_v; ++r) {
+        round_sums(pv, r, p.nkt_v, xplanes, xstride);
+        __syncthreads();
+        if (threadIdx.x < 256) {
+            const int row = 256 * r + threadIdx.x;
+            if (row < p.Kp) {
+                const double val = combine_planes(wred + threadIdx.x * 8) * pow2(ex_x - 31);
+                const float z = (float)((double)p.S[row] * val);
+                uint32_t ev, od;
+                digit_codes(z, ex_z, ev, od);
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    zplanes[(size_t)(2 * d) * zstride + row] = (unsigned char)(ev >> (8 * d));
+                    zplanes[(size_t)(2 * d + 1) * zstride + row] = (unsigned char)(od >> (8 * d));
+                }
+            }
+        }
+        __syncthreads();
+    }
+    // ---- stage U: y = U z
+    for (int r = 0; r < rounds_u; ++r) {
+        round_sums(pu, r, p.nkt_u, zplanes, zstride);
+        __syncthreads();
+        if (threadIdx.x < 256) {
+            const int row = 256 * r + threadIdx.x;
+            if (row < p.M) {
+                const double val = combine_planes(wred + threadIdx.x * 8) * pow2(ex_z - 31);
+                tsvd_store_y(p.y, (size_t)row * p.ldy, (float)(p.bias ? val + (double)p.bias[row] : val), p.out_bf16);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+size_t gemv_fused_lds_bytes(long long Np, long long Kp) {
+    return ((8 * (size_t)(Np + 16) + 255) & ~(size_t)255) + ((8 * (size_t)(Kp + 16) + 255) & ~(size_t)255) + (16 * 128 + 64) * sizeof(float);
+}
+
 namespace {
 template <bool STAGE_U, int ROUNDS>
 hipError_t init_one() {
@@ -306,8 +449,25 @@ size_t gemv_lds_bytes(long long kdim) {
 }
 }  // namespace
 
+bool tsvd_gemv_fused_fits(long long Mp, long long Kp, long long Np) {
+    // at most FUSED_MAX_ITEMS tiles per wavefront and stage; x in one load round
+    const long long rounds_v = (Kp / 16 + 15) / 16, rounds_u = (Mp / 16 + 15) / 16;
+    return Np <= 4096 && rounds_v * (Np / 256) <= FUSED_MAX_ITEMS && rounds_u * (Kp / 256) <= FUSED_MAX_ITEMS &&
+           gemv_fused_lds_bytes(Np, Kp) <= TSVD_SKINNY_MAX_LDS;
+}
+
+hipError_t tsvd_launch_gemv_fused(const tsvd_gemv_fused_args& a, hipStream_t stream) {
+    if (a.strips_v < 1 || a.strips_u < 1 || a.nkt_v < 1 || a.nkt_u < 1 || a.Np > 4096 ||
+        ((a.strips_v + 15) / 16) * a.nkt_v > FUSED_MAX_ITEMS || ((a.strips_u + 15) / 16) * a.nkt_u > FUSED_MAX_ITEMS)
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL(tsvd_gemv_fused_kernel, dim3(1), dim3(1024), gemv_fused_lds_bytes(a.Np, a.Kp), stream, a);
+    return hipGetLastError();
+}
+
 hipError_t tsvd_gemv_init() {
     hipError_t e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemv_fused_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 TSVD_SKINNY_MAX_LDS)) != hipSuccess) return e;
     if ((e = init_one<false, 1>()) != hipSuccess) return e;
     if ((e = init_one<false, 2>()) != hipSuccess) return e;
     if ((e = init_one<false, 4>()) != hipSuccess) return e;

@@ -54,6 +54,18 @@ struct tsvd_gemv_args {
     int* meta;                            // fixed-point exponent of z (written by V, read by U)
     long long* clocks;                    // optional tuning aid: [grid][16] phase timestamps, or null
 };
+// Both stages of a single token in ONE launch of ONE workgroup, for matrices of at most 64 tiles
+// per stage (tsvd_gemv.hip): z never leaves LDS.
+struct tsvd_gemv_fused_args {
+    const void* tiles_v; int strips_v, nkt_v;     // V: Kp/16 strips, Np/256 tiles
+    const void* tiles_u; int strips_u, nkt_u;     // U: ceil(M/16) strips, Kp/256 tiles
+    int N, Np, Kp, M;
+    const void* x; int x_is_bf16; int x_vec; long long ldx;
+    const float* S; float bound_V;
+    void* y; long long ldy; const float* bias; int out_bf16;
+};
+bool tsvd_gemv_fused_fits(long long Mp, long long Kp, long long Np);
+hipError_t tsvd_launch_gemv_fused(const tsvd_gemv_fused_args& a, hipStream_t stream);
 hipError_t tsvd_gemv_init();
 bool tsvd_gemv_fits(long long Np, long long Kp);
 hipError_t tsvd_launch_gemv(const tsvd_gemv_args& a, bool stage_u, hipStream_t stream);

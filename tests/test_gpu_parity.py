@@ -227,6 +227,29 @@ def test_activation_scale_extremes_batched(tsvd):
     assert np.all(per_token <= 2e-3)
 
 
+@pytest.mark.parametrize("fused", ["1", "0"])
+@pytest.mark.parametrize("x_dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("M,N,K", [(256, 256, 512), (1, 1, 1), (37, 29, 61), (500, 300, 250), (1000, 700, 200), (100, 1000, 260)])
+def test_small_single_token_fused_launch(tsvd, M, N, K, x_dtype, fused, monkeypatch):
+    """Small matrices run both stages in one launch of one workgroup ("1"); the two-launch kernels
+    must give the same exact results on them ("0")."""
+    monkeypatch.setenv("TSVD_GEMV_FUSED", fused)
+    i = workloads.make_integer_inputs(M, N, K, 1, 0.5, x_dtype, seed=3 * M + N + K)
+    print(f"case small single token M={M} N={N} K={K} {x_dtype} fused={fused}", flush=True)
+    y, h = run_forward(i)
+    tsvd.tsvd_free(h)
+    assert not np.isnan(y).any()
+    assert np.array_equal(y, oracle.forward(i.U, i.S, i.V, i.X))
+    i = workloads.make_inputs(M, N, K, 1, 0.6, 0.02, x_dtype, seed=4 * M + N + K)
+    y, h = run_forward(i)
+    tsvd.tsvd_free(h)
+    ref = oracle.forward(i.U, i.S, i.V, i.X)
+    if np.any(ref):
+        assert rel_err(y, ref) <= 1e-5          # the single-token arithmetic is exact to fp32 rounding
+    else:
+        assert not np.any(y)
+
+
 def test_general_single_token_kernel(tsvd, monkeypatch):
     """The slab kernel that serves contraction lengths beyond the fast single-token kernel's
     limits, forced on ordinary sizes (exact instance, then a random one per activation type)."""
@@ -285,7 +308,8 @@ def test_degenerate_inputs(tsvd, B):
 # ---- integer, so the fp32 output must equal the oracle and the bf16 output its exact rounding.
 LAYER_CASES = [
     # M, N, K, B, environment that routes the call
-    (300, 513, 270, 1, {}),                                   # single-token kernels
+    (250, 200, 500, 1, {}),                                   # single token, small matrix: one fused launch
+    (300, 513, 270, 1, {}),                                   # single-token kernels, two launches
     (300, 513, 270, 2, {"TSVD_GEMV": "0", "TSVD_MID": "0"}),  # general slab kernel, two tokens per pass
     (100, 2300, 4500, 13, {}),                                # few-token kernel
     (130, 64, 520, 257, {}),                                  # ring kernels (unaligned rows: large-tile fallback)
