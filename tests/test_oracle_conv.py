@@ -100,3 +100,69 @@ def test_forms_equal_two_small_convolutions(form, stride, pad, dil):
     back = {0: W4.reshape(co, -1), 1: W4.transpose(0, 2, 3, 1).reshape(co * k1 * k2, ci),
             2: W4.transpose(0, 2, 1, 3).reshape(co * k1, ci * k2), 3: W4.transpose(0, 3, 1, 2).reshape(co * k2, ci * k1)}[form]
     assert np.array_equal(back, Wm)
+
+
+# ---- grouped / depth-wise convolutions (form 0 with groups, as the paper's converted ConvNeXt lists them)
+@pytest.mark.parametrize("groups,cg,mg", [(4, 1, 1), (4, 1, 2), (3, 2, 2), (2, 3, 1)])
+@pytest.mark.parametrize("stride,pad,dil", GEOMS)
+def test_grouped_definition_against_library_and_block_diagonal(groups, cg, mg, stride, pad, dil):
+    rng = np.random.default_rng(groups + 5 * cg + 11 * mg + sum(stride) + 3 * sum(pad))
+    ci, co = groups * cg, groups * mg
+    x = rng.standard_normal((2, ci, 8, 9))
+    W4 = rng.standard_normal((co, cg, 3, 2))
+    bias = rng.standard_normal(co)
+    got = oc.conv2d(x, W4, stride, pad, dil, bias, groups)
+    lib = torch.nn.functional.conv2d(torch.from_numpy(x), torch.from_numpy(W4), torch.from_numpy(bias), stride, pad, dil, groups)
+    assert np.allclose(got, lib.numpy(), atol=1e-12)
+    # a grouped convolution is an ordinary one whose kernel is zero across groups (explicit loops)
+    full = np.zeros((co, ci, 3, 2))
+    for o in range(co):
+        g = o // mg
+        full[o, g * cg:(g + 1) * cg] = W4[o]
+    assert np.allclose(got, _loops(x, full, stride, pad, dil, bias), atol=1e-12)
+
+
+def test_grouped_factors_equal_block_diagonal_factors():
+    """Per-group factors (U rows of the group x its rank block, V_g stacked) give the same kernel as
+    the ungrouped form 0 with block-diagonal U and V; and each group alone is form 0 of its block."""
+    rng = np.random.default_rng(5)
+    groups, cg, mg, kg, k1, k2 = 3, 2, 2, 4, 3, 3
+    co, ci, K, ng = groups * mg, groups * cg, groups * kg, cg * k1 * k2
+    U = np.zeros((co, K), dtype=np.int8)
+    Vs = rng.integers(-1, 2, size=(K, ng)).astype(np.int8)
+    Vbd = np.zeros((K, ci * k1 * k2), dtype=np.int8)
+    for g in range(groups):
+        U[g * mg:(g + 1) * mg, g * kg:(g + 1) * kg] = rng.integers(-1, 2, size=(mg, kg))
+        Vbd[g * kg:(g + 1) * kg, g * ng:(g + 1) * ng] = Vs[g * kg:(g + 1) * kg]
+    S = rng.standard_normal(K).astype(np.float32)
+    W4g = oc.dense_kernel_grouped(U, S, Vs, groups, co, ci, k1, k2)
+    W4f = oc.dense_kernel(U, S, Vbd, 0, co, ci, k1, k2)
+    for o in range(co):
+        g = o // mg
+        assert np.array_equal(W4f[o, g * cg:(g + 1) * cg], W4g[o])
+        W4f[o, g * cg:(g + 1) * cg] = 0
+    assert not W4f.any()
+    g = 1
+    alone = oc.dense_kernel(U[g * mg:(g + 1) * mg, g * kg:(g + 1) * kg], S[g * kg:(g + 1) * kg], Vs[g * kg:(g + 1) * kg], 0, mg, cg, k1, k2)
+    assert np.array_equal(alone, W4g[g * mg:(g + 1) * mg])
+    # entries of U outside the rank block of the row's group take no part
+    U2 = U.copy()
+    U2[0, kg:] = 1
+    assert np.array_equal(oc.dense_kernel_grouped(U2, S, Vs, groups, co, ci, k1, k2), W4g)
+    x = rng.standard_normal((2, ci, 6, 7))
+    a = oc.tsvd_conv2d(x, U, S, Vs, 0, co, ci, k1, k2, (1, 1), (1, 1), (1, 1), None, groups)
+    b = oc.tsvd_conv2d(x, U, S, Vbd, 0, co, ci, k1, k2, (1, 1), (1, 1), (1, 1))
+    assert np.allclose(a, b, atol=1e-12)
+
+
+def test_depthwise_identity_tap():
+    """Depth-wise 7 x 7 whose only tap is the centre with weight s_c: y = s_c x (same padding)."""
+    rng = np.random.default_rng(6)
+    C, k = 5, 7
+    U = np.eye(C, dtype=np.int8)                       # rank 1 per channel
+    V = np.zeros((C, k * k), dtype=np.int8)
+    V[:, (k // 2) * k + k // 2] = -1
+    S = rng.standard_normal(C).astype(np.float32)
+    x = rng.standard_normal((2, C, 9, 8))
+    y = oc.tsvd_conv2d(x, U, S, V, 0, C, C, k, k, (1, 1), (3, 3), (1, 1), None, C)
+    assert np.allclose(y, -S.astype(np.float64)[None, :, None, None] * x, atol=1e-13)
