@@ -569,6 +569,11 @@ extern "C" int tsvd_internal_tile_shapes(const tsvd_handle* h, long long B, int*
     return 0;
 }
 
+const uint8_t* tsvd_internal_blob(const tsvd_handle* h, const tsvd_blob_header** hd) {
+    *hd = &h->hd;
+    return h->blob;
+}
+
 extern "C" int tsvd_internal_read_clocks(const tsvd_handle* h, long long* out, int workgroups) {
     if (!h || !h->clocks || !out || workgroups < 1 || workgroups > TSVD_GEMV_MAX_GRID) return 1;
     return hipMemcpy(out, h->clocks, (size_t)workgroups * 16 * sizeof(long long), hipMemcpyDeviceToHost) == hipSuccess ? 0 : 4;

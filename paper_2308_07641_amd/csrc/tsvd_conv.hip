@@ -5,6 +5,14 @@
 // (one row per (input channel, tap), one column per position V produces) and summing the taps of
 // U's kernel after it.  Both are plain HBM-bound copies with coalesced accesses along the
 // innermost image dimension.
+//
+// Grouped convolutions (form 0 with groups; the paper's converted ConvNeXt lists its depth-wise
+// 7 x 7 layers this way, rank 5 per channel) have per-group factors of a few hundred codes: a
+// matrix-core map would multiply zeros almost everywhere.  tsvd_grouped_conv_kernel does the three
+// steps directly: the window of the group's input channels is staged in LDS, V_g is turned into a
+// list of its non-zero taps per rank, and every output position adds / subtracts the listed values
+// (the additions of the method, zeros skipped), multiplies by S and combines the ranks with the
+// signs of U: x is read once and y written once, z stays in registers.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -12,6 +20,8 @@
 
 #include "../../include/tsvd_conv.h"
 #include "tsvd_epilogue.h"
+#include "tsvd_kernels.h"
+#include "tsvd_layout.h"
 
 namespace {
 
@@ -26,10 +36,11 @@ struct conv_plan {
     long long rows_v, rows_u;      // N and M of the packed matrix
     long long Bv, Bo;              // columns of the linear map, output positions (all images)
     long long ldx;                 // row stride of the gathered columns (multiple of 8)
+    bool fits;                     // within the index limits of the gather / map / tap-sum path
 };
 
 bool make_plan(const tsvd_conv_geometry& g, int64_t images, int64_t H, int64_t W, conv_plan* p) {
-    if (g.form < 0 || g.form > 3 || g.c_in < 1 || g.c_out < 1 || g.k1 < 1 || g.k2 < 1 || g.stride1 < 1 || g.stride2 < 1 ||
+    if (g.groups < 0 || g.form < 0 || g.form > 3 || g.c_in < 1 || g.c_out < 1 || g.k1 < 1 || g.k2 < 1 || g.stride1 < 1 || g.stride2 < 1 ||
         g.pad1 < 0 || g.pad2 < 0 || g.dil1 < 1 || g.dil2 < 1 || images < 1 || H < 1 || W < 1)
         return false;
     const long long ho = ((long long)H + 2LL * g.pad1 - (long long)g.dil1 * (g.k1 - 1) - 1) / g.stride1 + 1;
@@ -52,7 +63,8 @@ bool make_plan(const tsvd_conv_geometry& g, int64_t images, int64_t H, int64_t W
     p->Bo = images * ho * wo;
     p->ldx = (p->Bv + 7) / 8 * 8;
     // (grid.y carries the rows of the gather and the output channels of the tap sum)
-    return p->Bv < (1LL << 24) && p->Bo < (1LL << 31) && images * H * W < (1LL << 31) && p->rows_v <= 65535 && g.c_out <= 65535;
+    p->fits = p->Bv < (1LL << 24) && p->Bo < (1LL << 31) && images * H * W < (1LL << 31) && p->rows_v <= 65535 && g.c_out <= 65535;
+    return true;
 }
 
 // Columns for V: X[(ci, dy, dx)][(img, py, px)] = x[ci][img][iy][ix] (zero outside the image) with
@@ -115,6 +127,177 @@ tsvd_fold_kernel(const float* __restrict__ T, long long ldt, int images, int Hv,
     tsvd_store_y(y, (size_t)co * Bo + col, acc, out_bf16);
 }
 
+
+// ---- grouped form 0 ------------------------------------------------------------------------------
+#define GROUPED_MAX_MG 8            // output channels per group
+#define GROUPED_MAX_KG 64           // ranks per group
+#define GROUPED_MAX_ENTRIES 4096    // ranks per group x (taps per group rounded up to 4)
+#define GROUPED_MAX_LDS (64 * 1024)
+
+struct grouped_args {
+    const uint32_t* U; int u_tps;        // code words of U, tiles per 16-row strip (Kp / 256)
+    const uint32_t* V; int v_tps;        // code words of V, tiles per strip (Np / 256)
+    const float* S;
+    const uint16_t* x; void* y; const float* bias; int out_bf16;
+    int cg, mg, kg, ng;                  // per group: input channels, output channels, ranks, taps (cg k1 k2)
+    int images, H, W, Ho, Wo, k1, k2, s1, s2, p1, p2, d1, d2;
+    int rb, bpp;                         // output rows per workgroup, workgroups per plane
+    int ipb;                             // images per workgroup (the tap lists are built once per workgroup)
+    int rows_in, win;                    // staged window per input channel: rows, columns
+};
+
+// 2-bit code of element (r, c) of a packed matrix with tps tiles per strip.
+__device__ __forceinline__ int code_at(const uint32_t* words, int tps, int r, int c) {
+    int word, bit;
+    tsvd_code_position(r & 15, c & 255, &word, &bit);
+    return (int)(words[((size_t)(r >> 4) * tps + (c >> 8)) * 256 + word] >> bit) & 3;
+}
+
+// grid (bpp * ceil(images / ipb), groups), block 64..256.  Workgroup = group g, output rows
+// [r0, r0 + rb) of ipb images, one after the other.  LDS: window [cg][rows_in][win] fp32, tap lists
+// [kg][stride] (entry = 2 * offset of the tap in the window + 1 if negative), their lengths, the
+// signs of U [mg][kg] as +-1 / 0, S [kg].
+template <int MG>
+__global__ void __launch_bounds__(256)
+tsvd_grouped_conv_kernel(grouped_args p) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int tile_elems = p.cg * p.rows_in * p.win, stride = (p.ng + 3) & ~3;
+    float* tile = reinterpret_cast<float*>(smem);
+    int* entries = reinterpret_cast<int*>(tile + ((tile_elems + 3) & ~3));
+    int* counts = entries + p.kg * stride;
+    float* ucode = reinterpret_cast<float*>(counts + ((p.kg + 3) & ~3));
+    float* sval = ucode + MG * p.kg;
+    const int g = blockIdx.y;
+    const int rblk = blockIdx.x % p.bpp, iblk = blockIdx.x / p.bpp;
+    const int r0 = rblk * p.rb, nrows = min(p.rb, p.Ho - r0);
+
+    // ---- V_g -> lists of non-zero taps, one rank per wavefront at a time
+    for (int k = wave; k < p.kg; k += nwaves) {
+        int cnt = 0;
+        for (int j0 = 0; j0 < p.ng; j0 += 64) {
+            const int j = j0 + lane;
+            const int code = j < p.ng ? code_at(p.V, p.v_tps, g * p.kg + k, j) : 0;
+            const unsigned long long mask = __ballot(code & 1);
+            if (code & 1) {
+                const int dx = j % p.k2, dy = (j / p.k2) % p.k1, c = j / (p.k1 * p.k2);
+                const int off = (c * p.rows_in + dy * p.d1) * p.win + dx * p.d2;
+                entries[k * stride + cnt + __popcll(mask & ((1ull << lane) - 1))] = 2 * off + (code >> 1);
+            }
+            cnt += __popcll(mask);
+        }
+        if (lane == 0) counts[k] = cnt;
+    }
+    for (int idx = threadIdx.x; idx < MG * p.kg; idx += blockDim.x) {
+        const int m = idx / p.kg, k = idx % p.kg;
+        const int code = m < p.mg ? code_at(p.U, p.u_tps, g * p.mg + m, g * p.kg + k) : 0;
+        ucode[idx] = code == 1 ? 1.f : code == 3 ? -1.f : 0.f;
+    }
+    for (int k = threadIdx.x; k < p.kg; k += blockDim.x) sval[k] = p.S[g * p.kg + k];
+
+    const int iy0 = r0 * p.s1 - p.p1;
+    const size_t plane_in = (size_t)p.H * p.W, plane_out = (size_t)p.Ho * p.Wo;
+    for (int img = iblk * p.ipb; img < min((iblk + 1) * p.ipb, p.images); ++img) {
+        __syncthreads();            // the previous image's window is no longer read (first pass: nothing to wait for)
+        // ---- window of the group's input channels, zero outside the image
+        for (int idx = threadIdx.x; idx < tile_elems; idx += blockDim.x) {
+            const int cc = idx % p.win, rr = (idx / p.win) % p.rows_in, c = idx / (p.win * p.rows_in);
+            const int iy = iy0 + rr, ix = cc - p.p2;
+            float v = 0.f;
+            if (iy >= 0 && iy < p.H && ix >= 0 && ix < p.W)
+                v = __uint_as_float((uint32_t)p.x[((size_t)(g * p.cg + c) * p.images + img) * plane_in + (size_t)iy * p.W + ix] << 16);
+            tile[idx] = v;
+        }
+        __syncthreads();
+        // ---- per output position: t_k = sum of the listed taps, z_k = S_k t_k, y_m = sum_k U[m][k] z_k
+        for (int o = threadIdx.x; o < nrows * p.Wo; o += blockDim.x) {
+            const int oy = o / p.Wo, ox = o % p.Wo;
+            const float* base = tile + (oy * p.s1) * p.win + ox * p.s2;
+            float acc[MG];
+#pragma unroll
+            for (int m = 0; m < MG; ++m) acc[m] = 0.f;
+            for (int k = 0; k < p.kg; ++k) {
+                const int cnt = counts[k];
+                const int* e = entries + k * stride;
+                float t = 0.f;
+                int n = 0;
+                for (; n + 4 <= cnt; n += 4) {
+                    const int4 q = *reinterpret_cast<const int4*>(e + n);
+                    const float v0 = base[q.x >> 1], v1 = base[q.y >> 1], v2 = base[q.z >> 1], v3 = base[q.w >> 1];
+                    t += (q.x & 1) ? -v0 : v0;
+                    t += (q.y & 1) ? -v1 : v1;
+                    t += (q.z & 1) ? -v2 : v2;
+                    t += (q.w & 1) ? -v3 : v3;
+                }
+                for (; n < cnt; ++n) {
+                    const int q = e[n];
+                    const float v = base[q >> 1];
+                    t += (q & 1) ? -v : v;
+                }
+                const float z = sval[k] * t;
+#pragma unroll
+                for (int m = 0; m < MG; ++m) acc[m] += ucode[m * p.kg + k] * z;
+            }
+#pragma unroll
+            for (int m = 0; m < MG; ++m) {
+                if (m < p.mg) {
+                    const int co = g * p.mg + m;
+                    tsvd_store_y(p.y, ((size_t)co * p.images + img) * plane_out + (size_t)(r0 + oy) * p.Wo + ox,
+                                 acc[m] + (p.bias ? p.bias[co] : 0.f), p.out_bf16);
+                }
+            }
+        }
+    }
+}
+
+size_t grouped_lds_bytes(const grouped_args& a, int MG) {
+    const size_t tile = ((size_t)a.cg * a.rows_in * a.win + 3) & ~(size_t)3, stride = ((size_t)a.ng + 3) & ~(size_t)3;
+    return 4 * (tile + a.kg * stride + (((size_t)a.kg + 3) & ~(size_t)3) + (size_t)MG * a.kg + a.kg);
+}
+
+// Fills the launch shape of the grouped kernel; false when the sizes exceed its limits.
+bool plan_grouped(const tsvd_conv_geometry& g, const tsvd_blob_header& hd, int64_t images, int64_t H, int64_t W, grouped_args* a,
+                  int* MG, int* threads) {
+    const int G = g.groups;
+    if (g.c_in % G || g.c_out % G || hd.K % G) return false;
+    a->cg = g.c_in / G; a->mg = g.c_out / G; a->kg = (int)(hd.K / G); a->ng = a->cg * g.k1 * g.k2;
+    if (hd.M != g.c_out || hd.N != a->ng) return false;
+    if (a->mg > GROUPED_MAX_MG || a->kg > GROUPED_MAX_KG || (long long)a->kg * ((a->ng + 3) & ~3) > GROUPED_MAX_ENTRIES || G > 65535)
+        return false;
+    *MG = a->mg <= 1 ? 1 : a->mg <= 2 ? 2 : a->mg <= 4 ? 4 : 8;
+    a->images = (int)images; a->H = (int)H; a->W = (int)W;
+    a->k1 = g.k1; a->k2 = g.k2; a->s1 = g.stride1; a->s2 = g.stride2; a->p1 = g.pad1; a->p2 = g.pad2; a->d1 = g.dil1; a->d2 = g.dil2;
+    a->Ho = (int)(((long long)H + 2LL * g.pad1 - (long long)g.dil1 * (g.k1 - 1) - 1) / g.stride1 + 1);
+    a->Wo = (int)(((long long)W + 2LL * g.pad2 - (long long)g.dil2 * (g.k2 - 1) - 1) / g.stride2 + 1);
+    a->win = (a->Wo - 1) * g.stride2 + (g.k2 - 1) * g.dil2 + 1;
+    // rows per workgroup: the split of the plane that wastes the fewest lanes (passes of 256
+    // positions), a workgroup's fixed cost (tap lists, window) counted as one pass
+    long long best = -1;
+    for (int rb = 1; rb <= a->Ho && rb <= 128; ++rb) {
+        a->rb = rb;
+        a->rows_in = (rb - 1) * g.stride1 + (g.k1 - 1) * g.dil1 + 1;
+        if (grouped_lds_bytes(*a, *MG) > GROUPED_MAX_LDS) break;
+        const int bpp = (a->Ho + rb - 1) / rb, last = a->Ho - (bpp - 1) * rb;
+        const long long cost = (long long)(bpp - 1) * (((long long)rb * a->Wo + 255) / 256 + 1) + (((long long)last * a->Wo + 255) / 256 + 1);
+        if (best < 0 || cost <= best) { best = cost; a->bpp = bpp; }
+    }
+    if (best < 0) return false;
+    a->rb = (a->Ho + a->bpp - 1) / a->bpp;
+    a->bpp = (a->Ho + a->rb - 1) / a->rb;
+    a->rows_in = (a->rb - 1) * g.stride1 + (g.k1 - 1) * g.dil1 + 1;
+    const long long per_block = (long long)a->rb * a->Wo;
+    *threads = (int)std::min<long long>(256, (per_block + 63) / 64 * 64);
+    a->ipb = (int)std::max<long long>(1, std::min<long long>(images, 1024 / per_block));
+    const long long blocks = (long long)a->bpp * ((images + a->ipb - 1) / a->ipb);
+    return blocks < (1LL << 31) && images * H * W < (1LL << 31) && images * (long long)a->Ho * a->Wo < (1LL << 31);
+}
+
+template <int MG>
+void launch_grouped(const grouped_args& a, int groups, int threads, hipStream_t s) {
+    const unsigned blocks = (unsigned)(a.bpp * ((a.images + a.ipb - 1) / a.ipb));
+    hipLaunchKernelGGL(tsvd_grouped_conv_kernel<MG>, dim3(blocks, (unsigned)groups), dim3(threads), grouped_lds_bytes(a, MG), s, a);
+}
+
 bool shapes_match(const tsvd_handle* h, const conv_plan& p) {
     int64_t M = 0, K = 0, N = 0, a = 0, b = 0;
     return tsvd_info(h, &M, &K, &N, &a, &b) == TSVD_OK && M == p.rows_u && N == p.rows_v;
@@ -125,7 +308,15 @@ bool shapes_match(const tsvd_handle* h, const conv_plan& p) {
 extern "C" size_t tsvd_conv2d_workspace_bytes(const tsvd_handle* h, const tsvd_conv_geometry* g, int64_t images, int64_t H,
                                               int64_t W) {
     conv_plan p;
-    if (!h || !g || !make_plan(*g, images, H, W, &p) || !shapes_match(h, p)) return 0;
+    if (!h || !g || !make_plan(*g, images, H, W, &p)) return 0;
+    if (g->groups > 1) {
+        const tsvd_blob_header* hd;
+        grouped_args a;
+        int MG, threads;
+        (void)tsvd_internal_blob(h, &hd);
+        return g->form == 0 && plan_grouped(*g, *hd, images, H, W, &a, &MG, &threads) ? 256 : 0;   // no scratch is used
+    }
+    if (!p.fits || !shapes_match(h, p)) return 0;
     const size_t cols = g->form == 1 ? 0 : round256((size_t)p.rows_v * p.ldx * 2);
     const size_t taps = g->form == 0 ? 0 : round256((size_t)p.rows_u * p.Bv * 4);
     return cols + taps + tsvd_workspace_bytes_ex(h, p.Bv, TSVD_BF16, TSVD_FEATURE_MAJOR);
@@ -137,7 +328,29 @@ extern "C" tsvd_status tsvd_conv2d_forward(const tsvd_handle* h, const tsvd_conv
     conv_plan p;
     if (!h || !g || !x_dev || !y_dev || !workspace) return TSVD_EINVAL;
     if (y_dtype != TSVD_F32 && y_dtype != TSVD_BF16) return TSVD_EINVAL;
-    if (!make_plan(*g, images, H, W, &p) || !shapes_match(h, p)) return TSVD_EINVAL;
+    if (!make_plan(*g, images, H, W, &p)) return TSVD_EINVAL;
+    if (g->groups > 1) {
+        if (g->form != 0) return TSVD_EUNSUPPORTED;
+        const tsvd_blob_header* hd;
+        const uint8_t* blob = tsvd_internal_blob(h, &hd);
+        grouped_args a;
+        int MG, threads;
+        if (g->c_in % g->groups || g->c_out % g->groups || hd->K % g->groups || hd->M != g->c_out ||
+            hd->N != (int64_t)(g->c_in / g->groups) * g->k1 * g->k2)
+            return TSVD_EINVAL;
+        if (!plan_grouped(*g, *hd, images, H, W, &a, &MG, &threads)) return TSVD_EUNSUPPORTED;
+        a.U = reinterpret_cast<const uint32_t*>(blob + hd->off_U); a.u_tps = (int)(hd->Kp / TSVD_TILE_COLS);
+        a.V = reinterpret_cast<const uint32_t*>(blob + hd->off_V); a.v_tps = (int)(hd->Np / TSVD_TILE_COLS);
+        a.S = reinterpret_cast<const float*>(blob + hd->off_S);
+        a.x = static_cast<const uint16_t*>(x_dev); a.y = y_dev; a.bias = bias_dev; a.out_bf16 = y_dtype == TSVD_BF16;
+        hipStream_t gs = static_cast<hipStream_t>(stream);
+        if (MG == 1) launch_grouped<1>(a, g->groups, threads, gs);
+        else if (MG == 2) launch_grouped<2>(a, g->groups, threads, gs);
+        else if (MG == 4) launch_grouped<4>(a, g->groups, threads, gs);
+        else launch_grouped<8>(a, g->groups, threads, gs);
+        return hipGetLastError() == hipSuccess ? TSVD_OK : TSVD_EDEVICE;
+    }
+    if (!p.fits || !shapes_match(h, p)) return TSVD_EINVAL;
     const size_t need = tsvd_conv2d_workspace_bytes(h, g, images, H, W);
     if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return TSVD_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);

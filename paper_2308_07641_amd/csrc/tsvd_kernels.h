@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #define TSVD_SKINNY_MAX_LDS (150 * 1024)
+struct tsvd_blob_header;
 
 // One stage of the skinny path: out = A . in for a packed ternary A and one or two tokens.
 #define TSVD_SKINNY_STAGE_V 0   // in: raw activations; out: digit planes of z = S * (V x)
@@ -90,10 +91,14 @@ struct tsvd_mid_args {
 hipError_t tsvd_mid_init();
 hipError_t tsvd_launch_mid(const tsvd_mid_args& a, bool stage_u, bool vec, hipStream_t stream);
 
+// Device blob of a handle and the host copy of its header (for kernels outside tsvd_api.hip that
+// read code words themselves).
+struct tsvd_handle;
+const uint8_t* tsvd_internal_blob(const tsvd_handle* h, const struct tsvd_blob_header** hd);
+
 hipError_t tsvd_transition_init();   // kernel attributes of tsvd_transition.hip
 
 // ---- batched path ----------------------------------------------------------------------------
-struct tsvd_blob_header;
 struct tsvd_gemm_problem {
     const uint8_t* blob;            // device blob
     const tsvd_blob_header* hd;     // host copy of its header

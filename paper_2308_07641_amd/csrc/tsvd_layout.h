@@ -23,6 +23,7 @@
 // 0x4000 (+2), 0xC000 (-2) (same patterns in bf16 and fp16) and the activation rows are fetched
 // in the matching order.  The factor 2 per stage is removed exactly by the epilogues.
 #pragma once
+#include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
 
@@ -53,7 +54,7 @@ static inline int tsvd_step_column(int g, int e) { return 64 * (g & 1) + 32 * (e
 
 // Bit position of element (row r, column c) inside its tile: returns the lane's 32-bit word
 // index (0..255 within the tile) in *word and the bit offset of the 2-bit code.
-static inline void tsvd_code_position(int r_in_tile, int c_in_tile, int* word, int* bit) {
+__host__ __device__ static inline void tsvd_code_position(int r_in_tile, int c_in_tile, int* word, int* bit) {
     const int i = r_in_tile;                 // 0..15
     const int h = c_in_tile >> 7;            // MFMA step of 128 columns
     const int kk = c_in_tile & 127;

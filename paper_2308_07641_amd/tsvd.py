@@ -339,17 +339,18 @@ def tsvd_transition(W, theta: float, tol: float, max_rank: int, stream=None):
 
 # ---- convolution forms (include/tsvd_conv.h)
 class ConvGeometry(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("form", "c_in", "c_out", "k1", "k2", "stride1", "stride2", "pad1", "pad2", "dil1", "dil2")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("form", "c_in", "c_out", "k1", "k2", "stride1", "stride2", "pad1", "pad2", "dil1", "dil2", "groups")]
 
 
 def tsvd_conv2d_forward(h: Handle, form: int, c_in: int, c_out: int, k1: int, k2: int, x, stride=(1, 1), pad=(0, 0), dil=(1, 1),
-                        bias=None, y_dtype=TSVD_F32, stream=None):
-    """y [C_out, images, Ho, Wo] = conv2d(x [C_in, images, H, W] bf16) with the kernel in ternary-SVD form `form`."""
+                        bias=None, y_dtype=TSVD_F32, stream=None, groups=1):
+    """y [C_out, images, Ho, Wo] = conv2d(x [C_in, images, H, W] bf16) with the kernel in ternary-SVD form `form`
+    (groups > 1: form 0 with per-group factors, see include/tsvd_conv.h)."""
     import torch
     if not x.is_cuda or x.dtype != torch.bfloat16 or x.dim() != 4 or x.shape[0] != c_in or not x.is_contiguous():
         raise ValueError("x must be a contiguous bf16 GPU tensor [C_in, images, H, W]")
     _, images, H, W = x.shape
-    g = ConvGeometry(form, c_in, c_out, k1, k2, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1])
+    g = ConvGeometry(form, c_in, c_out, k1, k2, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1], groups)
     lib = load_library()
     nbytes = int(lib.tsvd_conv2d_workspace_bytes(h.ptr, ctypes.addressof(g), images, H, W))
     if nbytes == 0:
