@@ -271,6 +271,34 @@ def bench_conv(steps=50):
                               "parity_rel_err": err,
                               "cpu_baseline": {"value": 1.0 / cpu_s, "unit": "images/s", "kind": "oracle", "sample": "1 image"}}
         tsvd.tsvd_free(h)
+    # depth-wise 7 x 7 with rank 5 per channel (how the paper's converted ConvNeXt lists its dwconv
+    # layers; first-stage shape: 96 channels, 56 x 56), 32 images, non-zero rate 0.235
+    C, k, kg, H = 96, 7, 5, 56
+    U = np.zeros((C, C * kg), dtype=np.int8)
+    for c in range(C):
+        U[c, c * kg:(c + 1) * kg] = rng.choice([-1, 1], size=kg)
+    V = rng.choice([-1, 0, 1], size=(C * kg, k * k), p=[0.1175, 0.765, 0.1175]).astype(np.int8)
+    S = (np.abs(rng.standard_normal(C * kg)) * 0.05).astype(np.float32)
+    xb = workloads.f32_to_bf16_bits(rng.standard_normal((C, images, H, H)).astype(np.float32))
+    x = torch.from_numpy(xb.view(np.int16)).to("cuda:0").view(torch.bfloat16)
+    h = tsvd.tsvd_pack(U, S, V)
+    fn = lambda: tsvd.tsvd_conv2d_forward(h, 0, C, C, k, k, x, (1, 1), (3, 3), (1, 1), groups=C)
+    _, ev_ms = _timed(fn, steps, 5)
+    y = fn()
+    torch.cuda.synchronize()
+    xr = workloads.bf16_bits_to_f32(xb[:, :1]).transpose(1, 0, 2, 3)
+    t0 = time.perf_counter()
+    ref = oc.tsvd_conv2d(xr, U, S, V, 0, C, C, k, k, (1, 1), (3, 3), (1, 1), None, C)
+    cpu_s = time.perf_counter() - t0
+    err = float(np.max(np.abs(y[:, 0].float().cpu().numpy() - ref[0])) / np.max(np.abs(ref)))
+    moved = C * images * H * H * (2 + 4)            # x bf16 read once, y fp32 written once
+    adds = (np.count_nonzero(V) + np.count_nonzero(U)) * images * H * H
+    out["depthwise7x7"] = {"workload": f"depth-wise 7x7, {C} channels, rank {kg} per channel, {images} images {H}x{H}, pad 3",
+                           "ms_per_call": ev_ms, "images_per_s": images / (ev_ms * 1e-3),
+                           "hbm_gbs": moved / (ev_ms * 1e-3) / 1e9, "hbm_frac": moved / (ev_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                           "additions_per_s": adds / (ev_ms * 1e-3), "parity_rel_err": err,
+                           "cpu_baseline": {"value": 1.0 / cpu_s, "unit": "images/s", "kind": "oracle", "sample": "1 image"}}
+    tsvd.tsvd_free(h)
     return out
 
 

@@ -154,39 +154,37 @@ __device__ __forceinline__ int code_at(const uint32_t* words, int tps, int r, in
 }
 
 // grid (bpp * ceil(images / ipb), groups), block 64..256.  Workgroup = group g, output rows
-// [r0, r0 + rb) of ipb images, one after the other.  LDS: window [cg][rows_in][win] fp32, tap lists
-// [kg][stride] (entry = 2 * offset of the tap in the window + 1 if negative), their lengths, the
-// signs of U [mg][kg] as +-1 / 0, S [kg].
-template <int MG>
+// [r0, r0 + rb) of ipb images, one after the other.  A thread owns ROWS vertically adjacent
+// positions (ROWS = 4 needs stride1 = 1 and a compile-time row pitch P of the window: the four
+// values of a tap are then one address plus constant offsets); consecutive lanes own consecutive
+// columns, so every LDS read of a wavefront touches consecutive words (a thread owning four
+// horizontally adjacent positions made lanes 16 words apart: four-way bank conflicts, 3 x slower).
+// LDS: window [cg][rows_in][pitch] fp32, tap lists [kg][stride] as offsets into the window and signs
+// +-1.0 (padded to a multiple of four with sign 0), their lengths, the signs of U [MG][kg] as
+// +-1 / 0, S [kg], and for the prologue the codes of V_g.
+template <int MG, int ROWS, int P>
 __global__ void __launch_bounds__(256)
 tsvd_grouped_conv_kernel(grouped_args p) {
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
-    const int tile_elems = p.cg * p.rows_in * p.win, stride = (p.ng + 3) & ~3;
+    const int pitch = P ? P : p.win;
+    const int tile_elems = p.cg * p.rows_in * pitch, stride = (p.ng + 3) & ~3;
     float* tile = reinterpret_cast<float*>(smem);
-    int* entries = reinterpret_cast<int*>(tile + ((tile_elems + 3) & ~3));
-    int* counts = entries + p.kg * stride;
+    int* offs = reinterpret_cast<int*>(tile + ((tile_elems + 3) & ~3));
+    float* sgns = reinterpret_cast<float*>(offs + p.kg * stride);
+    int* counts = reinterpret_cast<int*>(sgns + p.kg * stride);
     float* ucode = reinterpret_cast<float*>(counts + ((p.kg + 3) & ~3));
     float* sval = ucode + MG * p.kg;
+    unsigned char* codes = reinterpret_cast<unsigned char*>(sval + p.kg);      // [kg][stride], prologue only
     const int g = blockIdx.y;
     const int rblk = blockIdx.x % p.bpp, iblk = blockIdx.x / p.bpp;
     const int r0 = rblk * p.rb, nrows = min(p.rb, p.Ho - r0);
 
-    // ---- V_g -> lists of non-zero taps, one rank per wavefront at a time
-    for (int k = wave; k < p.kg; k += nwaves) {
-        int cnt = 0;
-        for (int j0 = 0; j0 < p.ng; j0 += 64) {
-            const int j = j0 + lane;
-            const int code = j < p.ng ? code_at(p.V, p.v_tps, g * p.kg + k, j) : 0;
-            const unsigned long long mask = __ballot(code & 1);
-            if (code & 1) {
-                const int dx = j % p.k2, dy = (j / p.k2) % p.k1, c = j / (p.k1 * p.k2);
-                const int off = (c * p.rows_in + dy * p.d1) * p.win + dx * p.d2;
-                entries[k * stride + cnt + __popcll(mask & ((1ull << lane) - 1))] = 2 * off + (code >> 1);
-            }
-            cnt += __popcll(mask);
-        }
-        if (lane == 0) counts[k] = cnt;
+    // ---- the codes of V_g, all loads in flight at once, then per rank (one wavefront each) the list of its non-zero taps
+    for (int idx = threadIdx.x; idx < p.kg * p.ng; idx += blockDim.x) {
+        const int k = idx / p.ng, j = idx - k * p.ng;
+        codes[k * stride + j] = (unsigned char)code_at(p.V, p.v_tps, g * p.kg + k, j);
     }
     for (int idx = threadIdx.x; idx < MG * p.kg; idx += blockDim.x) {
         const int m = idx / p.kg, k = idx % p.kg;
@@ -194,70 +192,117 @@ tsvd_grouped_conv_kernel(grouped_args p) {
         ucode[idx] = code == 1 ? 1.f : code == 3 ? -1.f : 0.f;
     }
     for (int k = threadIdx.x; k < p.kg; k += blockDim.x) sval[k] = p.S[g * p.kg + k];
+    __syncthreads();
+    for (int k = wave; k < p.kg; k += nwaves) {
+        int cnt = 0;
+        for (int j0 = 0; j0 < p.ng; j0 += 64) {
+            const int j = j0 + lane;
+            const int code = j < p.ng ? codes[k * stride + j] : 0;
+            const unsigned long long mask = __ballot(code & 1);
+            if (code & 1) {
+                const int dx = j % p.k2, dy = (j / p.k2) % p.k1, c = j / (p.k1 * p.k2);
+                const int at = k * stride + cnt + __popcll(mask & ((1ull << lane) - 1));
+                offs[at] = (c * p.rows_in + dy * p.d1) * pitch + dx * p.d2;
+                sgns[at] = code == 3 ? -1.f : 1.f;
+            }
+            cnt += __popcll(mask);
+        }
+        const int padded = (cnt + 3) & ~3;                 // <= stride
+        if (lane < padded - cnt) {
+            offs[k * stride + cnt + lane] = 0;             // a tap of weight zero at the position itself
+            sgns[k * stride + cnt + lane] = 0.f;
+        }
+        if (lane == 0) counts[k] = padded;
+    }
 
     const int iy0 = r0 * p.s1 - p.p1;
+    const int units = ((nrows + ROWS - 1) / ROWS) * p.Wo;   // a unit = ROWS rows x one column
     const size_t plane_in = (size_t)p.H * p.W, plane_out = (size_t)p.Ho * p.Wo;
     for (int img = iblk * p.ipb; img < min((iblk + 1) * p.ipb, p.images); ++img) {
-        __syncthreads();            // the previous image's window is no longer read (first pass: nothing to wait for)
-        // ---- window of the group's input channels, zero outside the image
-        for (int idx = threadIdx.x; idx < tile_elems; idx += blockDim.x) {
-            const int cc = idx % p.win, rr = (idx / p.win) % p.rows_in, c = idx / (p.win * p.rows_in);
-            const int iy = iy0 + rr, ix = cc - p.p2;
-            float v = 0.f;
-            if (iy >= 0 && iy < p.H && ix >= 0 && ix < p.W)
-                v = __uint_as_float((uint32_t)p.x[((size_t)(g * p.cg + c) * p.images + img) * plane_in + (size_t)iy * p.W + ix] << 16);
-            tile[idx] = v;
+        __syncthreads();            // lists complete / the previous image's window is no longer read
+        // ---- window of the group's input channels, zero outside the image: 16 rows per wavefront in
+        // flight at a time (unconditional loads from clamped addresses, so that none waits for another)
+        const int nrow_tot = p.cg * p.rows_in;
+        for (int row0 = wave * 16; row0 < nrow_tot; row0 += nwaves * 16) {
+            for (int cc = lane; cc < p.win; cc += 64) {
+                const int ix = cc - p.p2, ixc = min(max(ix, 0), p.W - 1);
+                uint32_t raw[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = min(row0 + r, nrow_tot - 1), c = row / p.rows_in;
+                    const int iyc = min(max(iy0 + row - c * p.rows_in, 0), p.H - 1);
+                    raw[r] = p.x[((size_t)(g * p.cg + c) * p.images + img) * plane_in + (size_t)iyc * p.W + ixc];
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = row0 + r, c = row / p.rows_in, iy = iy0 + row - c * p.rows_in;
+                    if (row < nrow_tot) tile[row * pitch + cc] = iy >= 0 && iy < p.H && ix == ixc ? __uint_as_float(raw[r] << 16) : 0.f;
+                }
+            }
         }
         __syncthreads();
         // ---- per output position: t_k = sum of the listed taps, z_k = S_k t_k, y_m = sum_k U[m][k] z_k
-        for (int o = threadIdx.x; o < nrows * p.Wo; o += blockDim.x) {
-            const int oy = o / p.Wo, ox = o % p.Wo;
-            const float* base = tile + (oy * p.s1) * p.win + ox * p.s2;
-            float acc[MG];
+        for (int u = threadIdx.x; u < units; u += blockDim.x) {
+            const int q = u / p.Wo, ox = u - q * p.Wo, oy0 = q * ROWS;
+            const float* base = tile + (oy0 * p.s1) * pitch + ox * p.s2;
+            float acc[MG][ROWS];
 #pragma unroll
-            for (int m = 0; m < MG; ++m) acc[m] = 0.f;
+            for (int m = 0; m < MG; ++m)
+#pragma unroll
+                for (int j = 0; j < ROWS; ++j) acc[m][j] = 0.f;
             for (int k = 0; k < p.kg; ++k) {
                 const int cnt = counts[k];
-                const int* e = entries + k * stride;
-                float t = 0.f;
-                int n = 0;
-                for (; n + 4 <= cnt; n += 4) {
-                    const int4 q = *reinterpret_cast<const int4*>(e + n);
-                    const float v0 = base[q.x >> 1], v1 = base[q.y >> 1], v2 = base[q.z >> 1], v3 = base[q.w >> 1];
-                    t += (q.x & 1) ? -v0 : v0;
-                    t += (q.y & 1) ? -v1 : v1;
-                    t += (q.z & 1) ? -v2 : v2;
-                    t += (q.w & 1) ? -v3 : v3;
-                }
-                for (; n < cnt; ++n) {
-                    const int q = e[n];
-                    const float v = base[q >> 1];
-                    t += (q & 1) ? -v : v;
-                }
-                const float z = sval[k] * t;
+                const int* eo = offs + k * stride;
+                const float* es = sgns + k * stride;
+                float t[ROWS];
 #pragma unroll
-                for (int m = 0; m < MG; ++m) acc[m] += ucode[m * p.kg + k] * z;
+                for (int j = 0; j < ROWS; ++j) t[j] = 0.f;
+                auto tap = [&](int off, float sg) {
+#pragma unroll
+                    for (int j = 0; j < ROWS; ++j) t[j] += sg * base[off + j * P];      // ROWS > 1 only with P > 0 and stride1 = 1
+                };
+                for (int n = 0; n < cnt; n += 4) {
+                    const int4 e4 = *reinterpret_cast<const int4*>(eo + n);
+                    const f32x4 sg = *reinterpret_cast<const f32x4*>(es + n);
+                    tap(e4.x, sg.x); tap(e4.y, sg.y); tap(e4.z, sg.z); tap(e4.w, sg.w);
+                }
+                const float sk = sval[k];
+#pragma unroll
+                for (int m = 0; m < MG; ++m) {
+                    const float um = ucode[m * p.kg + k];
+#pragma unroll
+                    for (int j = 0; j < ROWS; ++j) acc[m][j] += um * (sk * t[j]);
+                }
             }
 #pragma unroll
             for (int m = 0; m < MG; ++m) {
                 if (m < p.mg) {
                     const int co = g * p.mg + m;
-                    tsvd_store_y(p.y, ((size_t)co * p.images + img) * plane_out + (size_t)(r0 + oy) * p.Wo + ox,
-                                 acc[m] + (p.bias ? p.bias[co] : 0.f), p.out_bf16);
+                    const float bv = p.bias ? p.bias[co] : 0.f;
+                    const size_t at = ((size_t)co * p.images + img) * plane_out + (size_t)(r0 + oy0) * p.Wo + ox;
+#pragma unroll
+                    for (int j = 0; j < ROWS; ++j)
+                        if (oy0 + j < nrows) tsvd_store_y(p.y, at + (size_t)j * p.Wo, acc[m][j] + bv, p.out_bf16);
                 }
             }
         }
     }
 }
 
-size_t grouped_lds_bytes(const grouped_args& a, int MG) {
-    const size_t tile = ((size_t)a.cg * a.rows_in * a.win + 3) & ~(size_t)3, stride = ((size_t)a.ng + 3) & ~(size_t)3;
-    return 4 * (tile + a.kg * stride + (((size_t)a.kg + 3) & ~(size_t)3) + (size_t)MG * a.kg + a.kg);
+// rows of the staged window for rb output rows (ROWS-row units may read past the last output row)
+int grouped_rows_in(const tsvd_conv_geometry& g, int rb, int ROWS) {
+    const int rows = (rb + ROWS - 1) / ROWS * ROWS;
+    return (rows - 1) * g.stride1 + (g.k1 - 1) * g.dil1 + 1;
+}
+
+size_t grouped_lds_bytes(const grouped_args& a, int MG, int P) {
+    const size_t tile = ((size_t)a.cg * a.rows_in * (P ? P : a.win) + 3) & ~(size_t)3, stride = ((size_t)a.ng + 3) & ~(size_t)3;
+    return 4 * (tile + 2 * a.kg * stride + (((size_t)a.kg + 3) & ~(size_t)3) + (size_t)MG * a.kg + a.kg) + a.kg * stride;
 }
 
 // Fills the launch shape of the grouped kernel; false when the sizes exceed its limits.
 bool plan_grouped(const tsvd_conv_geometry& g, const tsvd_blob_header& hd, int64_t images, int64_t H, int64_t W, grouped_args* a,
-                  int* MG, int* threads) {
+                  int* MG, int* ROWS, int* P, int* threads) {
     const int G = g.groups;
     if (g.c_in % G || g.c_out % G || hd.K % G) return false;
     a->cg = g.c_in / G; a->mg = g.c_out / G; a->kg = (int)(hd.K / G); a->ng = a->cg * g.k1 * g.k2;
@@ -270,32 +315,50 @@ bool plan_grouped(const tsvd_conv_geometry& g, const tsvd_blob_header& hd, int64
     a->Ho = (int)(((long long)H + 2LL * g.pad1 - (long long)g.dil1 * (g.k1 - 1) - 1) / g.stride1 + 1);
     a->Wo = (int)(((long long)W + 2LL * g.pad2 - (long long)g.dil2 * (g.k2 - 1) - 1) / g.stride2 + 1);
     a->win = (a->Wo - 1) * g.stride2 + (g.k2 - 1) * g.dil2 + 1;
+    // four rows per thread where the window rows are one compile-time pitch apart
+    *ROWS = g.stride1 == 1 && a->win <= 256 && a->Ho >= 4 && *MG <= 4 ? 4 : 1;
+    *P = *ROWS == 1 ? 0 : a->win <= 64 ? 64 : a->win <= 128 ? 128 : 256;
     // rows per workgroup: the split of the plane that wastes the fewest lanes (passes of 256
-    // positions), a workgroup's fixed cost (tap lists, window) counted as one pass
+    // units), a workgroup's fixed cost (tap lists, window) counted as one pass
     long long best = -1;
-    for (int rb = 1; rb <= a->Ho && rb <= 128; ++rb) {
+    for (int rb = 1; rb <= a->Ho && rb <= 256; ++rb) {
         a->rb = rb;
-        a->rows_in = (rb - 1) * g.stride1 + (g.k1 - 1) * g.dil1 + 1;
-        if (grouped_lds_bytes(*a, *MG) > GROUPED_MAX_LDS) break;
+        a->rows_in = grouped_rows_in(g, rb, *ROWS);
+        if (grouped_lds_bytes(*a, *MG, *P) > GROUPED_MAX_LDS) break;
         const int bpp = (a->Ho + rb - 1) / rb, last = a->Ho - (bpp - 1) * rb;
-        const long long cost = (long long)(bpp - 1) * (((long long)rb * a->Wo + 255) / 256 + 1) + (((long long)last * a->Wo + 255) / 256 + 1);
+        const long long ub = (long long)((rb + *ROWS - 1) / *ROWS) * a->Wo, ul = (long long)((last + *ROWS - 1) / *ROWS) * a->Wo;
+        const long long cost = (long long)(bpp - 1) * ((ub + 255) / 256 + 1) + ((ul + 255) / 256 + 1);
         if (best < 0 || cost <= best) { best = cost; a->bpp = bpp; }
     }
     if (best < 0) return false;
     a->rb = (a->Ho + a->bpp - 1) / a->bpp;
     a->bpp = (a->Ho + a->rb - 1) / a->rb;
-    a->rows_in = (a->rb - 1) * g.stride1 + (g.k1 - 1) * g.dil1 + 1;
-    const long long per_block = (long long)a->rb * a->Wo;
-    *threads = (int)std::min<long long>(256, (per_block + 63) / 64 * 64);
+    a->rows_in = grouped_rows_in(g, a->rb, *ROWS);
+    const long long per_block = (long long)((a->rb + *ROWS - 1) / *ROWS) * a->Wo;
+    // workgroup size: the one of 256 / 192 / 128 that pads the units least (64 for tiny blocks)
+    *threads = 64;
+    if (per_block > 64) {
+        long long padded = -1;
+        for (int t = 256; t >= 128; t -= 64) {
+            const long long pt = (per_block + t - 1) / t * t;
+            if (padded < 0 || pt < padded) { padded = pt; *threads = t; }
+        }
+    }
     a->ipb = (int)std::max<long long>(1, std::min<long long>(images, 1024 / per_block));
     const long long blocks = (long long)a->bpp * ((images + a->ipb - 1) / a->ipb);
     return blocks < (1LL << 31) && images * H * W < (1LL << 31) && images * (long long)a->Ho * a->Wo < (1LL << 31);
 }
 
 template <int MG>
-void launch_grouped(const grouped_args& a, int groups, int threads, hipStream_t s) {
-    const unsigned blocks = (unsigned)(a.bpp * ((a.images + a.ipb - 1) / a.ipb));
-    hipLaunchKernelGGL(tsvd_grouped_conv_kernel<MG>, dim3(blocks, (unsigned)groups), dim3(threads), grouped_lds_bytes(a, MG), s, a);
+void launch_grouped(const grouped_args& a, int ROWS, int P, int groups, int threads, hipStream_t s) {
+    const dim3 grid((unsigned)(a.bpp * ((a.images + a.ipb - 1) / a.ipb)), (unsigned)groups), block(threads);
+    const size_t lds = grouped_lds_bytes(a, MG, P);
+    if constexpr (MG <= 4) {
+        if (ROWS == 4 && P == 64) { hipLaunchKernelGGL((tsvd_grouped_conv_kernel<MG, 4, 64>), grid, block, lds, s, a); return; }
+        if (ROWS == 4 && P == 128) { hipLaunchKernelGGL((tsvd_grouped_conv_kernel<MG, 4, 128>), grid, block, lds, s, a); return; }
+        if (ROWS == 4 && P == 256) { hipLaunchKernelGGL((tsvd_grouped_conv_kernel<MG, 4, 256>), grid, block, lds, s, a); return; }
+    }
+    hipLaunchKernelGGL((tsvd_grouped_conv_kernel<MG, 1, 0>), grid, block, lds, s, a);
 }
 
 bool shapes_match(const tsvd_handle* h, const conv_plan& p) {
@@ -312,9 +375,9 @@ extern "C" size_t tsvd_conv2d_workspace_bytes(const tsvd_handle* h, const tsvd_c
     if (g->groups > 1) {
         const tsvd_blob_header* hd;
         grouped_args a;
-        int MG, threads;
+        int MG, ROWS, P, threads;
         (void)tsvd_internal_blob(h, &hd);
-        return g->form == 0 && plan_grouped(*g, *hd, images, H, W, &a, &MG, &threads) ? 256 : 0;   // no scratch is used
+        return g->form == 0 && plan_grouped(*g, *hd, images, H, W, &a, &MG, &ROWS, &P, &threads) ? 256 : 0;   // no scratch is used
     }
     if (!p.fits || !shapes_match(h, p)) return 0;
     const size_t cols = g->form == 1 ? 0 : round256((size_t)p.rows_v * p.ldx * 2);
@@ -334,20 +397,20 @@ extern "C" tsvd_status tsvd_conv2d_forward(const tsvd_handle* h, const tsvd_conv
         const tsvd_blob_header* hd;
         const uint8_t* blob = tsvd_internal_blob(h, &hd);
         grouped_args a;
-        int MG, threads;
+        int MG, ROWS, P, threads;
         if (g->c_in % g->groups || g->c_out % g->groups || hd->K % g->groups || hd->M != g->c_out ||
             hd->N != (int64_t)(g->c_in / g->groups) * g->k1 * g->k2)
             return TSVD_EINVAL;
-        if (!plan_grouped(*g, *hd, images, H, W, &a, &MG, &threads)) return TSVD_EUNSUPPORTED;
+        if (!plan_grouped(*g, *hd, images, H, W, &a, &MG, &ROWS, &P, &threads)) return TSVD_EUNSUPPORTED;
         a.U = reinterpret_cast<const uint32_t*>(blob + hd->off_U); a.u_tps = (int)(hd->Kp / TSVD_TILE_COLS);
         a.V = reinterpret_cast<const uint32_t*>(blob + hd->off_V); a.v_tps = (int)(hd->Np / TSVD_TILE_COLS);
         a.S = reinterpret_cast<const float*>(blob + hd->off_S);
         a.x = static_cast<const uint16_t*>(x_dev); a.y = y_dev; a.bias = bias_dev; a.out_bf16 = y_dtype == TSVD_BF16;
         hipStream_t gs = static_cast<hipStream_t>(stream);
-        if (MG == 1) launch_grouped<1>(a, g->groups, threads, gs);
-        else if (MG == 2) launch_grouped<2>(a, g->groups, threads, gs);
-        else if (MG == 4) launch_grouped<4>(a, g->groups, threads, gs);
-        else launch_grouped<8>(a, g->groups, threads, gs);
+        if (MG == 1) launch_grouped<1>(a, ROWS, P, g->groups, threads, gs);
+        else if (MG == 2) launch_grouped<2>(a, ROWS, P, g->groups, threads, gs);
+        else if (MG == 4) launch_grouped<4>(a, ROWS, P, g->groups, threads, gs);
+        else launch_grouped<8>(a, ROWS, P, g->groups, threads, gs);
         return hipGetLastError() == hipSuccess ? TSVD_OK : TSVD_EDEVICE;
     }
     if (!p.fits || !shapes_match(h, p)) return TSVD_EINVAL;
