@@ -17,6 +17,7 @@
 #include <stdint.h>
 
 #include <algorithm>
+#include <cstdlib>
 
 #include "../../include/tsvd_conv.h"
 #include "tsvd_epilogue.h"
@@ -162,10 +163,18 @@ __device__ __forceinline__ int code_at(const uint32_t* words, int tps, int r, in
 // LDS: window [cg][rows_in][pitch] fp32, tap lists [kg][stride] as offsets into the window and signs
 // +-1.0 (padded to a multiple of four with sign 0), their lengths, the signs of U [MG][kg] as
 // +-1 / 0, S [kg], and for the prologue the codes of V_g.
-template <int MG, int ROWS, int P>
+// PAIR (stride1 = stride2 = 1, ROWS = 4): the window keeps the activations as they come, bf16, in
+// two copies per row: words (x[2w], x[2w+1]) and words (x[2w+1], x[2w+2]); a thread owns 4 rows x 2
+// adjacent columns and one 32-bit read gives it both values of a tap, whatever its column offset
+// (even offsets in the first copy, odd ones in the second).  v_dot2c_f32_bf16 with the sign pairs
+// (+-1, 0) and (0, +-1) adds each half to its position's fp32 sum: half the LDS bytes per tap, the
+// same one instruction per position and tap.
+template <int MG, int ROWS, int P, bool PAIR>
 __global__ void __launch_bounds__(256)
 tsvd_grouped_conv_kernel(grouped_args p) {
     typedef float f32x4 __attribute__((ext_vector_type(4)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    static_assert(!PAIR || (ROWS == 4 && P >= 64), "the paired form owns 4 rows and needs a compile-time pitch");
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     const int pitch = P ? P : p.win;
@@ -202,8 +211,14 @@ tsvd_grouped_conv_kernel(grouped_args p) {
             if (code & 1) {
                 const int dx = j % p.k2, dy = (j / p.k2) % p.k1, c = j / (p.k1 * p.k2);
                 const int at = k * stride + cnt + __popcll(mask & ((1ull << lane) - 1));
-                offs[at] = (c * p.rows_in + dy * p.d1) * pitch + dx * p.d2;
-                sgns[at] = code == 3 ? -1.f : 1.f;
+                if constexpr (PAIR) {
+                    const int dxd = dx * p.d2;
+                    offs[at] = (c * p.rows_in + dy * p.d1) * P + (dxd & 1) * (P / 2) + (dxd >> 1);
+                    sgns[at] = __uint_as_float(code == 3 ? 0xBF80u : 0x3F80u);        // bf16 -1 / +1 in the low half
+                } else {
+                    offs[at] = (c * p.rows_in + dy * p.d1) * pitch + dx * p.d2;
+                    sgns[at] = code == 3 ? -1.f : 1.f;
+                }
             }
             cnt += __popcll(mask);
         }
@@ -216,7 +231,8 @@ tsvd_grouped_conv_kernel(grouped_args p) {
     }
 
     const int iy0 = r0 * p.s1 - p.p1;
-    const int units = ((nrows + ROWS - 1) / ROWS) * p.Wo;   // a unit = ROWS rows x one column
+    const int wcols = PAIR ? (p.Wo + 1) / 2 : p.Wo;         // units per row of units
+    const int units = ((nrows + ROWS - 1) / ROWS) * wcols;  // a unit = ROWS rows x one column (PAIR: two columns)
     const size_t plane_in = (size_t)p.H * p.W, plane_out = (size_t)p.Ho * p.Wo;
     for (int img = iblk * p.ipb; img < min((iblk + 1) * p.ipb, p.images); ++img) {
         __syncthreads();            // lists complete / the previous image's window is no longer read
@@ -224,7 +240,7 @@ tsvd_grouped_conv_kernel(grouped_args p) {
         // flight at a time (unconditional loads from clamped addresses, so that none waits for another)
         const int nrow_tot = p.cg * p.rows_in;
         for (int row0 = wave * 16; row0 < nrow_tot; row0 += nwaves * 16) {
-            for (int cc = lane; cc < p.win; cc += 64) {
+            for (int cc = lane; cc < p.win + (PAIR ? 1 : 0); cc += 64) {      // PAIR: one more column for a ragged last pair
                 const int ix = cc - p.p2, ixc = min(max(ix, 0), p.W - 1);
                 uint32_t raw[16];
 #pragma unroll
@@ -236,30 +252,54 @@ tsvd_grouped_conv_kernel(grouped_args p) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int row = row0 + r, c = row / p.rows_in, iy = iy0 + row - c * p.rows_in;
-                    if (row < nrow_tot) tile[row * pitch + cc] = iy >= 0 && iy < p.H && ix == ixc ? __uint_as_float(raw[r] << 16) : 0.f;
+                    const uint32_t v = iy >= 0 && iy < p.H && ix == ixc ? raw[r] : 0u;
+                    if constexpr (PAIR) {
+                        uint16_t* row16 = reinterpret_cast<uint16_t*>(tile + row * P);
+                        if (row < nrow_tot) {
+                            row16[cc] = (uint16_t)v;                       // copy of even offsets
+                            if (cc > 0) row16[P + cc - 1] = (uint16_t)v;   // copy of odd offsets, one element to the left
+                        }
+                    } else {
+                        if (row < nrow_tot) tile[row * pitch + cc] = __uint_as_float(v << 16);
+                    }
                 }
             }
         }
         __syncthreads();
         // ---- per output position: t_k = sum of the listed taps, z_k = S_k t_k, y_m = sum_k U[m][k] z_k
         for (int u = threadIdx.x; u < units; u += blockDim.x) {
-            const int q = u / p.Wo, ox = u - q * p.Wo, oy0 = q * ROWS;
-            const float* base = tile + (oy0 * p.s1) * pitch + ox * p.s2;
-            float acc[MG][ROWS];
+            constexpr int COLS = PAIR ? 2 : 1;
+            const int q = u / wcols, oc = u - q * wcols, ox = oc * COLS, oy0 = q * ROWS;
+            const float* base = tile + (oy0 * p.s1) * pitch + (PAIR ? oc : ox * p.s2);
+            float acc[MG][ROWS][COLS];
 #pragma unroll
             for (int m = 0; m < MG; ++m)
 #pragma unroll
-                for (int j = 0; j < ROWS; ++j) acc[m][j] = 0.f;
+                for (int j = 0; j < ROWS; ++j)
+#pragma unroll
+                    for (int c = 0; c < COLS; ++c) acc[m][j][c] = 0.f;
             for (int k = 0; k < p.kg; ++k) {
                 const int cnt = counts[k];
                 const int* eo = offs + k * stride;
                 const float* es = sgns + k * stride;
-                float t[ROWS];
+                float t[ROWS][COLS];
 #pragma unroll
-                for (int j = 0; j < ROWS; ++j) t[j] = 0.f;
+                for (int j = 0; j < ROWS; ++j)
+#pragma unroll
+                    for (int c = 0; c < COLS; ++c) t[j][c] = 0.f;
                 auto tap = [&](int off, float sg) {
+                    if constexpr (PAIR) {
+                        const uint32_t slo = __float_as_uint(sg), shi = slo << 16;
 #pragma unroll
-                    for (int j = 0; j < ROWS; ++j) t[j] += sg * base[off + j * P];      // ROWS > 1 only with P > 0 and stride1 = 1
+                        for (int j = 0; j < ROWS; ++j) {
+                            const bf16x2 v = __builtin_bit_cast(bf16x2, __float_as_uint(base[off + j * P]));
+                            t[j][0] = __builtin_amdgcn_fdot2_f32_bf16(v, __builtin_bit_cast(bf16x2, slo), t[j][0], false);
+                            t[j][COLS - 1] = __builtin_amdgcn_fdot2_f32_bf16(v, __builtin_bit_cast(bf16x2, shi), t[j][COLS - 1], false);
+                        }
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < ROWS; ++j) t[j][0] += sg * base[off + j * P];   // ROWS > 1 only with P > 0 and stride1 = 1
+                    }
                 };
                 for (int n = 0; n < cnt; n += 4) {
                     const int4 e4 = *reinterpret_cast<const int4*>(eo + n);
@@ -271,7 +311,9 @@ tsvd_grouped_conv_kernel(grouped_args p) {
                 for (int m = 0; m < MG; ++m) {
                     const float um = ucode[m * p.kg + k];
 #pragma unroll
-                    for (int j = 0; j < ROWS; ++j) acc[m][j] += um * (sk * t[j]);
+                    for (int j = 0; j < ROWS; ++j)
+#pragma unroll
+                        for (int c = 0; c < COLS; ++c) acc[m][j][c] += um * (sk * t[j][c]);
                 }
             }
 #pragma unroll
@@ -282,7 +324,9 @@ tsvd_grouped_conv_kernel(grouped_args p) {
                     const size_t at = ((size_t)co * p.images + img) * plane_out + (size_t)(r0 + oy0) * p.Wo + ox;
 #pragma unroll
                     for (int j = 0; j < ROWS; ++j)
-                        if (oy0 + j < nrows) tsvd_store_y(p.y, at + (size_t)j * p.Wo, acc[m][j] + bv, p.out_bf16);
+#pragma unroll
+                        for (int c = 0; c < COLS; ++c)
+                            if (oy0 + j < nrows && ox + c < p.Wo) tsvd_store_y(p.y, at + (size_t)j * p.Wo + c, acc[m][j][c] + bv, p.out_bf16);
                 }
             }
         }
@@ -302,7 +346,7 @@ size_t grouped_lds_bytes(const grouped_args& a, int MG, int P) {
 
 // Fills the launch shape of the grouped kernel; false when the sizes exceed its limits.
 bool plan_grouped(const tsvd_conv_geometry& g, const tsvd_blob_header& hd, int64_t images, int64_t H, int64_t W, grouped_args* a,
-                  int* MG, int* ROWS, int* P, int* threads) {
+                  int* MG, int* ROWS, int* P, int* PAIR, int* threads) {
     const int G = g.groups;
     if (g.c_in % G || g.c_out % G || hd.K % G) return false;
     a->cg = g.c_in / G; a->mg = g.c_out / G; a->kg = (int)(hd.K / G); a->ng = a->cg * g.k1 * g.k2;
@@ -317,7 +361,11 @@ bool plan_grouped(const tsvd_conv_geometry& g, const tsvd_blob_header& hd, int64
     a->win = (a->Wo - 1) * g.stride2 + (g.k2 - 1) * g.dil2 + 1;
     // four rows per thread where the window rows are one compile-time pitch apart
     *ROWS = g.stride1 == 1 && a->win <= 256 && a->Ho >= 4 && *MG <= 4 ? 4 : 1;
-    *P = *ROWS == 1 ? 0 : a->win <= 64 ? 64 : a->win <= 128 ? 128 : 256;
+    // ... and two columns where the columns are one element apart (the pitch holds two bf16 copies of win + 1 elements)
+    *PAIR = *ROWS == 4 && g.stride2 == 1 && a->win <= 255;
+    const int need = a->win + (*PAIR ? 1 : 0);
+    *P = *ROWS == 1 ? 0 : need <= 64 ? 64 : need <= 128 ? 128 : 256;
+    const int cols = *PAIR ? (a->Wo + 1) / 2 : a->Wo;       // units per row of units
     // rows per workgroup: the split of the plane that wastes the fewest lanes (passes of 256
     // units), a workgroup's fixed cost (tap lists, window) counted as one pass
     long long best = -1;
@@ -326,7 +374,7 @@ bool plan_grouped(const tsvd_conv_geometry& g, const tsvd_blob_header& hd, int64
         a->rows_in = grouped_rows_in(g, rb, *ROWS);
         if (grouped_lds_bytes(*a, *MG, *P) > GROUPED_MAX_LDS) break;
         const int bpp = (a->Ho + rb - 1) / rb, last = a->Ho - (bpp - 1) * rb;
-        const long long ub = (long long)((rb + *ROWS - 1) / *ROWS) * a->Wo, ul = (long long)((last + *ROWS - 1) / *ROWS) * a->Wo;
+        const long long ub = (long long)((rb + *ROWS - 1) / *ROWS) * cols, ul = (long long)((last + *ROWS - 1) / *ROWS) * cols;
         const long long cost = (long long)(bpp - 1) * ((ub + 255) / 256 + 1) + ((ul + 255) / 256 + 1);
         if (best < 0 || cost <= best) { best = cost; a->bpp = bpp; }
     }
@@ -334,7 +382,7 @@ bool plan_grouped(const tsvd_conv_geometry& g, const tsvd_blob_header& hd, int64
     a->rb = (a->Ho + a->bpp - 1) / a->bpp;
     a->bpp = (a->Ho + a->rb - 1) / a->rb;
     a->rows_in = grouped_rows_in(g, a->rb, *ROWS);
-    const long long per_block = (long long)((a->rb + *ROWS - 1) / *ROWS) * a->Wo;
+    const long long per_block = (long long)((a->rb + *ROWS - 1) / *ROWS) * cols;
     // workgroup size: the one of 256 / 192 / 128 that pads the units least (64 for tiny blocks)
     *threads = 64;
     if (per_block > 64) {
@@ -344,21 +392,32 @@ bool plan_grouped(const tsvd_conv_geometry& g, const tsvd_blob_header& hd, int64
             if (padded < 0 || pt < padded) { padded = pt; *threads = t; }
         }
     }
-    a->ipb = (int)std::max<long long>(1, std::min<long long>(images, 1024 / per_block));
+    // several images per workgroup only for tiny planes (measured: with 392 units per plane, two
+    // images per workgroup cost 81 us against 75 us for one, four 113 us: more workgroups hide more latency)
+    a->ipb = (int)std::max<long long>(1, std::min<long long>(images, 256 / per_block));
     const long long blocks = (long long)a->bpp * ((images + a->ipb - 1) / a->ipb);
     return blocks < (1LL << 31) && images * H * W < (1LL << 31) && images * (long long)a->Ho * a->Wo < (1LL << 31);
 }
 
 template <int MG>
-void launch_grouped(const grouped_args& a, int ROWS, int P, int groups, int threads, hipStream_t s) {
+void launch_grouped(const grouped_args& a, int ROWS, int P, int PAIR, int groups, int threads, hipStream_t s) {
     const dim3 grid((unsigned)(a.bpp * ((a.images + a.ipb - 1) / a.ipb)), (unsigned)groups), block(threads);
     const size_t lds = grouped_lds_bytes(a, MG, P);
     if constexpr (MG <= 4) {
-        if (ROWS == 4 && P == 64) { hipLaunchKernelGGL((tsvd_grouped_conv_kernel<MG, 4, 64>), grid, block, lds, s, a); return; }
-        if (ROWS == 4 && P == 128) { hipLaunchKernelGGL((tsvd_grouped_conv_kernel<MG, 4, 128>), grid, block, lds, s, a); return; }
-        if (ROWS == 4 && P == 256) { hipLaunchKernelGGL((tsvd_grouped_conv_kernel<MG, 4, 256>), grid, block, lds, s, a); return; }
+        if (ROWS == 4 && PAIR) {
+            if (P == 64) hipLaunchKernelGGL((tsvd_grouped_conv_kernel<MG, 4, 64, true>), grid, block, lds, s, a);
+            else if (P == 128) hipLaunchKernelGGL((tsvd_grouped_conv_kernel<MG, 4, 128, true>), grid, block, lds, s, a);
+            else hipLaunchKernelGGL((tsvd_grouped_conv_kernel<MG, 4, 256, true>), grid, block, lds, s, a);
+            return;
+        }
+        if (ROWS == 4) {
+            if (P == 64) hipLaunchKernelGGL((tsvd_grouped_conv_kernel<MG, 4, 64, false>), grid, block, lds, s, a);
+            else if (P == 128) hipLaunchKernelGGL((tsvd_grouped_conv_kernel<MG, 4, 128, false>), grid, block, lds, s, a);
+            else hipLaunchKernelGGL((tsvd_grouped_conv_kernel<MG, 4, 256, false>), grid, block, lds, s, a);
+            return;
+        }
     }
-    hipLaunchKernelGGL((tsvd_grouped_conv_kernel<MG, 1, 0>), grid, block, lds, s, a);
+    hipLaunchKernelGGL((tsvd_grouped_conv_kernel<MG, 1, 0, false>), grid, block, lds, s, a);
 }
 
 bool shapes_match(const tsvd_handle* h, const conv_plan& p) {
@@ -375,9 +434,9 @@ extern "C" size_t tsvd_conv2d_workspace_bytes(const tsvd_handle* h, const tsvd_c
     if (g->groups > 1) {
         const tsvd_blob_header* hd;
         grouped_args a;
-        int MG, ROWS, P, threads;
+        int MG, ROWS, P, PAIR, threads;
         (void)tsvd_internal_blob(h, &hd);
-        return g->form == 0 && plan_grouped(*g, *hd, images, H, W, &a, &MG, &ROWS, &P, &threads) ? 256 : 0;   // no scratch is used
+        return g->form == 0 && plan_grouped(*g, *hd, images, H, W, &a, &MG, &ROWS, &P, &PAIR, &threads) ? 256 : 0;   // no scratch is used
     }
     if (!p.fits || !shapes_match(h, p)) return 0;
     const size_t cols = g->form == 1 ? 0 : round256((size_t)p.rows_v * p.ldx * 2);
@@ -397,20 +456,21 @@ extern "C" tsvd_status tsvd_conv2d_forward(const tsvd_handle* h, const tsvd_conv
         const tsvd_blob_header* hd;
         const uint8_t* blob = tsvd_internal_blob(h, &hd);
         grouped_args a;
-        int MG, ROWS, P, threads;
+        int MG, ROWS, P, PAIR, threads;
         if (g->c_in % g->groups || g->c_out % g->groups || hd->K % g->groups || hd->M != g->c_out ||
             hd->N != (int64_t)(g->c_in / g->groups) * g->k1 * g->k2)
             return TSVD_EINVAL;
-        if (!plan_grouped(*g, *hd, images, H, W, &a, &MG, &ROWS, &P, &threads)) return TSVD_EUNSUPPORTED;
+        if (!plan_grouped(*g, *hd, images, H, W, &a, &MG, &ROWS, &P, &PAIR, &threads)) return TSVD_EUNSUPPORTED;
+        if (std::getenv("TSVD_GROUPED_PAIR") && std::atoi(std::getenv("TSVD_GROUPED_PAIR")) == 0) PAIR = 0;   // tuning switch: fp32 window
         a.U = reinterpret_cast<const uint32_t*>(blob + hd->off_U); a.u_tps = (int)(hd->Kp / TSVD_TILE_COLS);
         a.V = reinterpret_cast<const uint32_t*>(blob + hd->off_V); a.v_tps = (int)(hd->Np / TSVD_TILE_COLS);
         a.S = reinterpret_cast<const float*>(blob + hd->off_S);
         a.x = static_cast<const uint16_t*>(x_dev); a.y = y_dev; a.bias = bias_dev; a.out_bf16 = y_dtype == TSVD_BF16;
         hipStream_t gs = static_cast<hipStream_t>(stream);
-        if (MG == 1) launch_grouped<1>(a, ROWS, P, g->groups, threads, gs);
-        else if (MG == 2) launch_grouped<2>(a, ROWS, P, g->groups, threads, gs);
-        else if (MG == 4) launch_grouped<4>(a, ROWS, P, g->groups, threads, gs);
-        else launch_grouped<8>(a, ROWS, P, g->groups, threads, gs);
+        if (MG == 1) launch_grouped<1>(a, ROWS, P, PAIR, g->groups, threads, gs);
+        else if (MG == 2) launch_grouped<2>(a, ROWS, P, PAIR, g->groups, threads, gs);
+        else if (MG == 4) launch_grouped<4>(a, ROWS, P, PAIR, g->groups, threads, gs);
+        else launch_grouped<8>(a, ROWS, P, PAIR, g->groups, threads, gs);
         return hipGetLastError() == hipSuccess ? TSVD_OK : TSVD_EDEVICE;
     }
     if (!p.fits || !shapes_match(h, p)) return TSVD_EINVAL;
