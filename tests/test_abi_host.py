@@ -86,6 +86,32 @@ def test_two_bit_codes_and_counts():
     assert s["off_nnzU"] - s["off_V"] == s["Kp"] * s["Np"] // 4
 
 
+def _code_at(words, tiles_per_strip, r, c):
+    """Element (r, c) of a packed matrix from the documented position rule: tile (r / 16, c / 256) of
+    256 words; inside it lane 16 g + i (i = row in the tile), word 2 h + v / 2 of the lane and bit
+    2 (2 n + v % 2), where h = step of 128 columns, kk = column in the step, g = bit 6 of kk + 2 x bit 4,
+    operand element e = 16 x bit 5 + low four bits, v = e / 8, n = e % 8."""
+    i, cc = r & 15, c & 255
+    h, kk = cc >> 7, cc & 127
+    g = ((kk >> 6) & 1) | (((kk >> 4) & 1) << 1)
+    e = (((kk >> 5) & 1) << 4) | (kk & 15)
+    v, n = e >> 3, e & 7
+    word = (16 * g + i) * 4 + 2 * h + (v >> 1)
+    return (int(words[((r >> 4) * tiles_per_strip + (c >> 8)) * 256 + word]) >> (2 * (2 * n + (v & 1)))) & 3
+
+
+def test_element_position_rule_of_the_tile_format():
+    """Kernels that read single codes (the grouped convolution) use this rule; it must agree with the packer."""
+    i = workloads.make_inputs(40, 300, 70, 1, 0.6, 0.02, "f32", seed=5)
+    blob = tsvd.tsvd_pack_host(i.U, i.S, i.V)
+    s = _sections(blob)
+    Uw = np.frombuffer(blob[s["off_U"]:s["off_V"]].tobytes(), dtype=np.uint32)
+    Vw = np.frombuffer(blob[s["off_V"]:s["off_nnzU"]].tobytes(), dtype=np.uint32)
+    value = {0: 0, 1: 1, 3: -1}
+    assert all(value[_code_at(Uw, s["Kp"] // 256, r, c)] == i.U[r, c] for r in range(40) for c in range(70))
+    assert all(value[_code_at(Vw, s["Np"] // 256, r, c)] == i.V[r, c] for r in range(70) for c in range(0, 300, 7))
+
+
 def test_single_element_sets_exactly_its_code():
     U = np.zeros((20, 300), dtype=np.int8)
     V = np.zeros((300, 10), dtype=np.int8)
