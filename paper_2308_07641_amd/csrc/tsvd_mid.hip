@@ -140,12 +140,21 @@ tsvd_mid_kernel(tsvd_mid_args p) {
             if constexpr (VEC) {
                 xr[j] = __builtin_amdgcn_raw_buffer_load_b128(act_rsrc, x_voff, (s * 2048 + 512 * j) * (int)p.ld * 2, 0);
             } else {
+                // unconditional loads from clamped addresses (a load under a divergent condition makes
+                // the compiler wait for the weight tiles in flight), and none at all for token
+                // positions that no thread needs (uniform bound: with two tokens, 2 loads instead of 8)
                 const int k = s * 2048 + 512 * j + kk;
+                const uint16_t* row = p.act + (size_t)min(k, p.kvalid - 1) * p.ld;
+                const int tb = min(p.bvalid, 8);
                 uint32_t e[8];
 #pragma unroll
                 for (int t = 0; t < 8; ++t) {
-                    const bool ok = k < p.kvalid && 8 * half + t < p.bvalid;
-                    e[t] = ok ? (uint32_t)p.act[(size_t)(ok ? k : 0) * p.ld + (ok ? 8 * half + t : 0)] : 0u;
+                    uint32_t v = 0u;
+                    if (t < tb) {
+                        v = row[min(8 * half + t, p.bvalid - 1)];
+                        v = k < p.kvalid && 8 * half + t < p.bvalid ? v : 0u;
+                    }
+                    e[t] = v;
                 }
                 xr[j] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
             }
