@@ -313,6 +313,7 @@ tsvd_status forward_mid(const tsvd_handle* h, const void* x, int64_t B, int64_t 
         a.rows_valid = (int)hd.Kp;
         shape(a);
         const bool vec = ldx % 8 == 0 && (reinterpret_cast<uintptr_t>(a.act) & 15u) == 0;
+        a.pairs = ldx % 2 == 0 && (reinterpret_cast<uintptr_t>(a.act) & 3u) == 0;
         if (tsvd_launch_mid(a, false, vec, stream) != hipSuccess) return TSVD_EDEVICE;
     }
     if (mask & 4) {

@@ -80,6 +80,7 @@ struct tsvd_mid_args {
     long long ld;
     int kvalid, bvalid;                   // rows of act that exist (stage V: N), tokens (<= 16)
     unsigned act_bytes;                   // extent of act in bytes (reads beyond it give zero)
+    int pairs;                            // gathered path: rows start on 4-byte boundaries (two tokens per load)
     const float* S; float bound_V;        // stage V: row scales (zero beyond K); |z| <= bound_V * max|x|
     float* colmax;                        // [16] per-token max |x| (stage V writes, stage U reads)
     void* out; long long ld_out;          // stage V: z fp16 [Kp][16]; stage U: y fp32 (or bf16) [M][ld_out]

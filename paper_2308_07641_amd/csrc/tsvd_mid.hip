@@ -140,22 +140,34 @@ tsvd_mid_kernel(tsvd_mid_args p) {
             if constexpr (VEC) {
                 xr[j] = __builtin_amdgcn_raw_buffer_load_b128(act_rsrc, x_voff, (s * 2048 + 512 * j) * (int)p.ld * 2, 0);
             } else {
-                // unconditional loads from clamped addresses (a load under a divergent condition makes
-                // the compiler wait for the weight tiles in flight), and none at all for token
-                // positions that no thread needs (uniform bound: with two tokens, 2 loads instead of 8)
+                // unconditional loads (a load under a divergent condition makes the compiler wait for
+                // it, and for the weight tiles in flight, right there), and none at all for token
+                // positions that no thread needs: the bound is wave-uniform, so the skip is a scalar
+                // branch.  The masks are applied only when the values are packed.
                 const int k = s * 2048 + 512 * j + kk;
-                const uint16_t* row = p.act + (size_t)min(k, p.kvalid - 1) * p.ld;
-                const int tb = min(p.bvalid, 8);
+                const int tb = __builtin_amdgcn_readfirstlane(min(p.bvalid, 8));
                 uint32_t e[8];
+                if (p.pairs) {
+                    // rows start on 4-byte boundaries: two tokens per range-checked 4-byte load (zero
+                    // beyond the last row; with two tokens, one load per chunk instead of eight)
 #pragma unroll
-                for (int t = 0; t < 8; ++t) {
-                    uint32_t v = 0u;
-                    if (t < tb) {
-                        v = row[min(8 * half + t, p.bvalid - 1)];
-                        v = k < p.kvalid && 8 * half + t < p.bvalid ? v : 0u;
+                    for (int t = 0; t < 8; t += 2) {
+                        uint32_t v = 0u;
+                        if (t < tb) v = __builtin_amdgcn_raw_buffer_load_b32(act_rsrc, k * (int)p.ld * 2 + (8 * half + t) * 2, 0, 0);
+                        e[t] = v & 0xFFFFu;
+                        e[t + 1] = v >> 16;
                     }
-                    e[t] = v;
+                } else {
+                    const uint16_t* row = p.act + (size_t)min(k, p.kvalid - 1) * p.ld;
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        e[t] = 0u;
+                        if (t < tb) e[t] = row[min(8 * half + t, p.bvalid - 1)];
+                    }
                 }
+                const bool krow = k < p.kvalid;
+#pragma unroll
+                for (int t = 0; t < 8; ++t) e[t] = krow && 8 * half + t < p.bvalid ? e[t] : 0u;
                 xr[j] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
             }
         }

@@ -166,6 +166,23 @@ def test_few_token_kernel(tsvd, M, N, K, B, kwlog2, resident, monkeypatch):
     assert rel_err(y3, ref) <= 1e-5 and rel_err(y, y3) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("B,ld,col0", [(3, 10, 0), (5, 10, 2), (4, 9, 0), (6, 12, 1), (2, 2, 0), (7, 20, 4)])
+def test_few_token_gather_layouts(tsvd, B, ld, col0):
+    """Rows that are not 16-byte aligned are gathered: two tokens per 4-byte load when rows start on
+    4-byte boundaries (even stride, even first column), one by one otherwise.  The tokens are columns
+    col0 .. col0 + B - 1 of a wider matrix whose other columns hold large values that must not leak in."""
+    import torch
+    M, N, K = 90, 2500, 700
+    i = workloads.make_integer_inputs(M, N, K, B, 0.5, "bf16", seed=77 + B + ld)
+    print(f"case few-token gather B={B} ld={ld} col0={col0}", flush=True)
+    xfull = torch.full((N, ld), 300.0, dtype=torch.bfloat16, device="cuda:0")
+    xfull[:, col0:col0 + B] = to_device(i)
+    h = tsvd.tsvd_pack(i.U, i.S, i.V)
+    y = tsvd.tsvd_forward(h, xfull[:, col0:col0 + B]).cpu().numpy().astype(np.float64)
+    tsvd.tsvd_free(h)
+    assert np.array_equal(y, oracle.forward(i.U, i.S, i.V, i.X))
+
+
 @pytest.mark.parametrize("K", [4096, 4097])
 def test_few_token_kernel_at_the_resident_limit(tsvd, K):
     """A contraction of exactly two LDS slabs stays resident; one index more takes the hand-over loop."""
