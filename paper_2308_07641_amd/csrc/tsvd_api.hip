@@ -345,7 +345,10 @@ bool use_gemm(const tsvd_handle*, int64_t B, tsvd_dtype x_dtype) {
 size_t gemm_workspace(const tsvd_handle* h, int64_t B) {
     // partial column maxima [PARTS][Bp] fp32, then Z as fp16 [Kp][Bp]
     const int64_t Bp = tsvd_round_up(B, 256);
-    return round256((size_t)(TSVD_COLMAX_PARTS + 1) * Bp * 4) + round256((size_t)h->hd.Kp * (size_t)Bp * 2);
+    size_t bytes = round256((size_t)(TSVD_COLMAX_PARTS + 1) * Bp * 4) + round256((size_t)h->hd.Kp * (size_t)Bp * 2);
+    // (the rule is asked as for aligned rows: a caller with unaligned rows then reserves a little too much)
+    if (tsvd_gemm_use_fp6(h->hd.Mp, h->hd.Kp, h->hd.Np, B, h->cu_count, true)) bytes += round256(tsvd_gemm_fp6_bytes(h->hd.Kp, Bp));
+    return bytes;
 }
 
 }  // namespace

@@ -662,6 +662,208 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
     tick(5);
 }
 
+// ---- stage U on fp4 codes x three fp6 planes of Z (large shapes) -------------------------------
+// v_mfma_scale_f32_16x16x128_f8f6f4 with an fp4 A operand and an fp6 (E2M3) B operand issues at the
+// rate of v_mfma_f32_16x16x32_f16 and contracts four times as many indices; the codes become fp4
+// with 6 operations per 16 rows x 128 indices (against 32 for the 16-bit form).  Z is given as three
+// planes (a value, the residual of its rounding, the residual of that), each with its own
+// power-of-two scale per lane and block of 32 indices, which is the block-scale operand of the
+// instruction: byte `plane` of the scale register of the lane that holds the block.  Three planes
+// resolve about 2^-13 of a block's largest magnitude.  A separate pass (tsvd_z_planes_kernel) turns
+// the fp16 Z of stage V into planes in the operand order of this kernel, so the loads into LDS
+// are plain copies and the operand reads plain 16- and 8-byte reads.
+// Status: same accuracy as the 16-bit path, not yet faster (switch TSVD_FP6=1, off by default).
+// Measured on MI355X, 36864 x 18432 weights, 2048 tokens: this kernel 1.60 ms + 0.16 ms for the
+// planes against 1.78 ms for the 16-bit stage U; its MFMAs alone would take 0.9 ms.  A wavefront's
+// 96 MFMAs per block last 0.7 us while a request to the L2s takes 1.4 us under this load, so with
+// blocks requested one iteration ahead every barrier waits about a microsecond: the ring has to be
+// three or four blocks deep, with every load under explicit wait counts.
+//
+// Record of one (16-token tile, 128-index block): planes' first 16 bytes per lane [3][64][16], last
+// 8 bytes per lane [3][64][8], scale words [64][4] = 4864 bytes; lane (i, g) holds, for token i of
+// the tile, the indices that meet elements 0..31 of lane group g of the A operand built from the
+// tile format (tsvd_step_column).  Records are stored [128-token group][block][tile in group].
+#define FP6_REC_BYTES 4864
+#define FP6_PAIR_BYTES (8 * FP6_REC_BYTES)      // one block of one 128-token group: 38 KiB exactly
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+
+// grid (Bp / 128, Kp / 128), block 512 = 8 tiles x 64 lanes.  The [128 indices][128 tokens] block of Z
+// is read row by row (256 contiguous bytes each) into LDS, from where every thread picks the 32
+// values of its lane of the operand (row pitch 129 words: the picks of a wavefront, 16 tokens x 4
+// different rows, fall on different banks).
+__global__ void __launch_bounds__(512)
+tsvd_z_planes_kernel(const _Float16* __restrict__ Z, int Bp, int nblocks, unsigned char* __restrict__ planes) {
+    __shared__ uint32_t zt[128 * 65];                 // [index][token pair], pitch 65 words
+    const int tt = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, g = lane >> 4;
+    {
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(Z + (size_t)blockIdx.y * 128 * Bp + blockIdx.x * 128);
+        uint32_t r[16];
+#pragma unroll
+        for (int n = 0; n < 16; ++n) {                // 128 rows x 64 words = 8192 words, 16 per thread
+            const int idx = n * 512 + threadIdx.x, row = idx >> 6, col = idx & 63;
+            r[n] = src[(size_t)row * (Bp / 2) + col];
+        }
+#pragma unroll
+        for (int n = 0; n < 16; ++n) {
+            const int idx = n * 512 + threadIdx.x;
+            zt[(idx >> 6) * 65 + (idx & 63)] = r[n];
+        }
+    }
+    __syncthreads();
+    const int tok = tt * 16 + i;                      // token within the block's 128
+    const int k0 = 64 * (g & 1) + 16 * (g >> 1);
+    float v[32];
+#pragma unroll
+    for (int e = 0; e < 32; ++e) {
+        const uint32_t w = zt[(k0 + 32 * (e >> 4) + (e & 15)) * 65 + (tok >> 1)];
+        const uint16_t h = (tok & 1) ? (uint16_t)(w >> 16) : (uint16_t)(w & 0xFFFFu);
+        v[e] = (float)__builtin_bit_cast(_Float16, h);
+    }
+    unsigned char* rec = planes + ((size_t)(blockIdx.x * nblocks + blockIdx.y) * 8 + tt) * FP6_REC_BYTES;
+    uint32_t scales = 0;
+#pragma unroll
+    for (int pl = 0; pl < 3; ++pl) {
+        float m = 0.f;
+#pragma unroll
+        for (int e = 0; e < 32; ++e) m = fmaxf(m, fabsf(v[e]));
+        // exponent ex with m 2^-ex <= 7.5, the largest E2M3 magnitude (m = f 2^x, 0.5 <= f < 1)
+        int x = 0;
+        const float f = frexpf(m, &x);
+        int ex = m > 0.f ? (f <= 0.9375f ? x - 3 : x - 2) : 0;
+        ex = max(-126, min(126, ex));
+        scales |= (uint32_t)(127 + ex) << (8 * pl);
+        const float inv = ldexpf(1.0f, -ex), unit = ldexpf(1.0f, ex);
+        uint32_t w[7] = {0u, 0u, 0u, 0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int e = 0; e < 32; ++e) {
+            const float a = fminf(fabsf(v[e]) * inv, 7.5f);
+            const float step = a < 2.f ? 0.125f : a < 4.f ? 0.25f : 0.5f;
+            const float q = rintf(a / step) * step;                    // on the E2M3 grid, <= 7.5
+            const int ee = q < 1.f ? 0 : q < 2.f ? 1 : q < 4.f ? 2 : 3;
+            const int mant = ee == 0 ? (int)(q * 8.f) : (int)((q * (ee == 1 ? 1.f : ee == 2 ? 0.5f : 0.25f) - 1.f) * 8.f);
+            const uint32_t code = (q > 0.f && v[e] < 0.f ? 32u : 0u) | (uint32_t)(ee << 3) | (uint32_t)mant;
+            v[e] -= copysignf(q * unit, v[e]);                         // exact: the next plane codes this residual
+            const int bit = 6 * e, wd = bit >> 5, sh = bit & 31;
+            w[wd] |= code << sh;
+            if (sh > 26) w[wd + 1] |= code >> (32 - sh);
+        }
+        *reinterpret_cast<u32x4*>(rec + pl * 1024 + lane * 16) = u32x4{w[0], w[1], w[2], w[3]};
+        *reinterpret_cast<u32x2*>(rec + 3072 + pl * 512 + lane * 8) = u32x2{w[4], w[5]};
+    }
+    *reinterpret_cast<uint32_t*>(rec + 4608 + lane * 4) = scales;
+}
+
+template <int PL>
+__device__ __forceinline__ f32x4 mfma_fp6(const u32x4& a, const u32x4& lo, const u32x2& hi, uint32_t scale, f32x4 acc) {
+    const i32x8 av = {(int)a.x, (int)a.y, (int)a.z, (int)a.w, 0, 0, 0, 0};
+    const i32x8 bv = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+    // cbsz = 4: A is fp4 (E2M1); blgp = 2: B is fp6 (E2M3); A scale 2^0; B scale = byte PL of `scale`
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(av, bv, acc, 4, 2, 0, 0x7F7F7F7F, PL, (int)scale);
+}
+
+// 256 rows x 128 tokens per workgroup, 2 x 2 wavefronts of 8 x 4 blocks, two workgroups per compute
+// unit; two LDS buffers of one 128-index block each; code words straight from global memory to
+// registers, one block ahead.
+template <int EX>
+__global__ void __launch_bounds__(256, 2)
+tsvd_gemm_fp6_kernel(gemm_args p) {
+    constexpr int WM = 2, WN = 2, TM = 8, TN = 4, BT = 128;
+    extern __shared__ __align__(16) unsigned char smem[];   // 2 x FP6_PAIR_BYTES, then BT column factors
+    float* cs_lds = reinterpret_cast<float*>(smem + 2 * FP6_PAIR_BYTES);
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave / WN, wn = wave - wm * WN;
+    const int i = lane & 15, g = lane >> 4;
+    const int b0 = blockIdx.x * BT;
+    const int strip0 = (blockIdx.y * WM + wm) * TM;
+    const int nblocks = p.nkt * 2, lastb = nblocks - 1;
+
+    const i32x4 act_rsrc = raw_rsrc(p.act, p.act_bytes);
+    const __amdgpu_buffer_rsrc_t w_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(p.tiles), 0, p.tile_bytes, 0x00020000);
+    typedef __attribute__((address_space(3))) unsigned char* lds_byte_ptr;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_byte_ptr)smem;
+
+    f32x4 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // one block of this workgroup's 128 tokens = 38 pieces of 1 KiB; wavefront w copies pieces
+    // w, w + 4, ... (the two wavefronts whose tenth piece would be 38 or 39 copy piece 37 again)
+    auto issue = [&](int blk, int buf) {
+        const int rec0 = (blockIdx.x * nblocks + blk) * FP6_PAIR_BYTES;
+#pragma unroll
+        for (int c = 0; c < 10; ++c) {
+            const int piece = min(c * 4 + wave, 37);
+            buf_load128_to_lds(act_rsrc, lds_base + buf * FP6_PAIR_BYTES + piece * 1024, lane * 16, rec0 + piece * 1024);
+        }
+    };
+    const int w_voff = lane * 16;
+    auto load_w = [&](int blk, u32x2 (&w)[TM]) {
+        const int soff = (strip0 * p.nkt + (blk >> 1)) * 1024 + (blk & 1) * 8;
+#pragma unroll
+        for (int a = 0; a < TM; ++a) w[a] = __builtin_amdgcn_raw_buffer_load_b64(w_rsrc, w_voff, soff + a * p.nkt * 1024, 0);
+    };
+    auto compute = [&](int buf, const u32x2 (&w)[TM]) {
+        u32x4 av[TM];
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+            av[a] = u32x4{(w[a].x << 2) & 0xCCCCCCCCu, w[a].x & 0xCCCCCCCCu, (w[a].y << 2) & 0xCCCCCCCCu, w[a].y & 0xCCCCCCCCu};
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+            const unsigned char* rec = smem + buf * FP6_PAIR_BYTES + (wn * TN + b) * FP6_REC_BYTES;
+            const uint32_t sc = *reinterpret_cast<const uint32_t*>(rec + 4608 + lane * 4);
+            u32x4 lo[3];
+            u32x2 hi[3];
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl) {
+                lo[pl] = *reinterpret_cast<const u32x4*>(rec + pl * 1024 + lane * 16);
+                hi[pl] = *reinterpret_cast<const u32x2*>(rec + 3072 + pl * 512 + lane * 8);
+            }
+            // plane by plane over the eight row blocks: consecutive MFMAs never wait for each other's result
+#pragma unroll
+            for (int a = 0; a < TM; ++a) acc[a][b] = mfma_fp6<0>(av[a], lo[0], hi[0], sc, acc[a][b]);
+#pragma unroll
+            for (int a = 0; a < TM; ++a) acc[a][b] = mfma_fp6<1>(av[a], lo[1], hi[1], sc, acc[a][b]);
+#pragma unroll
+            for (int a = 0; a < TM; ++a) acc[a][b] = mfma_fp6<2>(av[a], lo[2], hi[2], sc, acc[a][b]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto touch = [&](const u32x2 (&w)[TM]) {
+#pragma unroll
+        for (int a = 0; a < TM; ++a) asm volatile("" :: "v"(w[a].x), "v"(w[a].y));
+    };
+
+    u32x2 wa[TM], wb[TM];
+    float cmax = 0.f;
+    if (threadIdx.x < BT) cmax = load_column_max<true>(p, b0 + threadIdx.x);
+    load_w(0, wa);
+    issue(0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    touch(wa);
+    if (threadIdx.x < BT) publish_column_factor<true>(p, b0 + threadIdx.x, cmax, cs_lds, threadIdx.x);
+    __syncthreads();
+    for (int P = 0; P < nblocks; P += 2) {
+        int nx = min(P + 1, lastb);
+        load_w(nx, wb);
+        issue(nx, 1);
+        compute(0, wa);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // block P + 1 has landed (this wavefront's part)
+        touch(wb);
+        __syncthreads();
+        nx = min(P + 2, lastb);
+        load_w(nx, wa);
+        issue(nx, 0);
+        compute(1, wb);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        touch(wa);
+        __syncthreads();
+    }
+    gemm_epilogue<TM, TN, true, EX>(p, acc, strip0, b0, wn * TN * 16, cs_lds, i, g);
+}
+
 // ---- ring variant for small problems -----------------------------------------------------------
 // A launch with about one workgroup per compute unit cannot lean on other workgroups to hide its
 // waits, and the 256-row tiles above would leave most compute units idle.  This variant uses small
@@ -1463,8 +1665,27 @@ bool tsvd_gemm_use_panel(long long Mp, long long Kp, long long Np, long long B, 
     return (Mp + Np) * Kp / 4 <= (8ll << 20) && 10 * n >= 6 * rounds * cus;
 }
 
+// Stage U through fp6 planes of Z (tsvd_gemm_fp6_kernel): TSVD_FP6 = 0 never, 1 whenever the sizes
+// allow, default by rule.  The planes of Z need tsvd_gemm_fp6_bytes more workspace.
+size_t tsvd_gemm_fp6_bytes(long long Kp, long long Bp) { return (size_t)(Bp / 128) * (size_t)(Kp / 128) * FP6_PAIR_BYTES; }
+bool tsvd_gemm_use_fp6(long long Mp, long long Kp, long long Np, long long B, long long cus, bool aligned) {
+    const char* v = getenv("TSVD_FP6");
+    const int mode = (v && *v) ? atoi(v) : -1;
+    const long long Bp = tsvd_round_up(B, 256);
+    if (mode == 0 || tsvd_gemm_fp6_bytes(Kp, Bp) >= (1ull << 31)) return false;
+    (void)Mp; (void)Np; (void)cus; (void)aligned;
+    if (mode == 1) return true;
+    return false;
+}
+
 hipError_t tsvd_gemm_init() {
     hipError_t e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<0>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 2 * FP6_PAIR_BYTES + 512)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 2 * FP6_PAIR_BYTES + 512)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 2 * FP6_PAIR_BYTES + 512)) != hipSuccess) return e;
     if ((e = init_gemm<2, 4, 8, 4, false>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 4, 8, 4, true>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 2, 8, 4, false>()) != hipSuccess) return e;
@@ -1598,6 +1819,22 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     if (mask & 2) e = fuse ? launch_cfg<false, true>(cfg1, a1, fast1, hd.Kp, Bp, stream)
                            : launch_cfg<false, false>(cfg1, a1, fast1, hd.Kp, Bp, stream);
     if (e != hipSuccess) return e;
+    if ((mask & 4) && tsvd_gemm_use_fp6(hd.Mp, hd.Kp, hd.Np, g.B, g.cu_count, fast1)) {
+        // Z (fp16) -> three fp6 planes in operand order, then stage U on fp4 x fp6
+        unsigned char* planes = reinterpret_cast<unsigned char*>(Z) + (((size_t)hd.Kp * Bp * 2 + 255) & ~(size_t)255);
+        hipLaunchKernelGGL(tsvd_z_planes_kernel, dim3(Bp / 128, (unsigned)(hd.Kp / 128)), dim3(512), 0, stream, Z, Bp, (int)(hd.Kp / 128), planes);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        gemm_args a3 = a2;
+        a3.act = reinterpret_cast<const uint16_t*>(planes);
+        a3.act_bytes = (unsigned)tsvd_gemm_fp6_bytes(hd.Kp, Bp);
+        const int ex = out_variant(a3.bias, a3.out_bf16, a3.out, a3.ld_out);
+        const size_t lds = 2 * FP6_PAIR_BYTES + 512;
+        const dim3 grid(Bp / 128, (unsigned)(hd.Mp / 256)), block(256);
+        if (ex == 2) hipLaunchKernelGGL(tsvd_gemm_fp6_kernel<2>, grid, block, lds, stream, a3);
+        else if (ex == 1) hipLaunchKernelGGL(tsvd_gemm_fp6_kernel<1>, grid, block, lds, stream, a3);
+        else hipLaunchKernelGGL(tsvd_gemm_fp6_kernel<0>, grid, block, lds, stream, a3);
+        return hipGetLastError();
+    }
     if (mask & 4) e = launch_cfg<true, false>(cfg2, a2, true, hd.Mp, Bp, stream);
     return e;
 }

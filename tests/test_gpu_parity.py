@@ -469,3 +469,32 @@ def test_repeated_calls_are_bit_identical(tsvd):
         ys = [tsvd.tsvd_forward(h, x).cpu().numpy() for _ in range(3)]
         assert np.array_equal(ys[0], ys[1]) and np.array_equal(ys[0], ys[2])
         tsvd.tsvd_free(h)
+
+
+# ---- stage U on fp4 codes x three fp6 planes of Z (experimental switch TSVD_FP6=1)
+@pytest.mark.parametrize("M,N,K,B", [(300, 200, 270, 100), (515, 300, 777, 130), (1024, 512, 768, 512), (130, 64, 2100, 257)])
+def test_fp6_planes_stage_u(tsvd, M, N, K, B, monkeypatch):
+    """Z as three E2M3 planes with per-lane block scales, multiplied with the codes as fp4 on the scaled
+    128-deep MFMA: exact on integer instances (small integers need one plane), within the tolerance
+    of the 16-bit path on random ones and next to identical to it; bias and bf16 output included."""
+    import torch
+    monkeypatch.setenv("TSVD_FP6", "1")
+    i = workloads.make_integer_inputs(M, N, K, B, 0.5, "bf16", seed=606 + B)
+    print(f"case fp6 int M={M} N={N} K={K} B={B}", flush=True)
+    y, h = run_forward(i)
+    tsvd.tsvd_free(h)
+    assert np.array_equal(y, oracle.forward(i.U, i.S, i.V, i.X))
+    j = workloads.make_inputs(M, N, K, B, 0.6, 0.02, "bf16", seed=607 + B)
+    print(f"case fp6 rand M={M} N={N} K={K} B={B}", flush=True)
+    ref = oracle.forward(j.U, j.S, j.V, j.X)
+    y1, h = run_forward(j)
+    assert not np.isnan(y1).any()
+    assert rel_err(y1, ref) <= TOL["bf16"]
+    bias = torch.linspace(-1.0, 1.0, M, device="cuda:0")
+    yb = tsvd.tsvd_forward_ex(h, to_device(j), bias=bias, y_dtype=tsvd.TSVD_BF16).float().cpu().numpy().astype(np.float64)
+    refb = ref + bias.cpu().numpy().astype(np.float64)[:, None]
+    assert np.all(np.abs(yb - refb) <= TOL["bf16"] * np.max(np.abs(ref)) + 2.0 ** -8 * np.abs(refb))
+    monkeypatch.setenv("TSVD_FP6", "0")
+    y0 = tsvd.tsvd_forward(h, to_device(j)).cpu().numpy().astype(np.float64)
+    tsvd.tsvd_free(h)
+    assert rel_err(y0, y1) <= 5e-4        # both round Z to about 12 bits, differently
