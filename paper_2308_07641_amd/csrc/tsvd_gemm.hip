@@ -676,8 +676,10 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
 // Measured on MI355X, 36864 x 18432 weights, 2048 tokens: this kernel 1.60 ms + 0.16 ms for the
 // planes against 1.78 ms for the 16-bit stage U; its MFMAs alone would take 0.9 ms.  A wavefront's
 // 96 MFMAs per block last 0.7 us while a request to the L2s takes 1.4 us under this load, so with
-// blocks requested one iteration ahead every barrier waits about a microsecond: the ring has to be
-// three or four blocks deep, with every load under explicit wait counts.
+// blocks requested one iteration ahead every barrier waits about a microsecond.  A ring of three
+// blocks with every load under explicit wait counts was tried in a 256 x 128 tile of eight
+// wavefronts (one workgroup per compute unit): 1.78 - 1.83 ms, slower, with a barrier for every
+// 0.35 us of MFMAs per wavefront.
 //
 // Record of one (16-token tile, 128-index block): planes' first 16 bytes per lane [3][64][16], last
 // 8 bytes per lane [3][64][8], scale words [64][4] = 4864 bytes; lane (i, g) holds, for token i of
