@@ -28,13 +28,15 @@ import workloads  # noqa: E402
 
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_TFLOPS = 2500.0
+PEAK_MFMA_FP6_TFLOPS = 10100.0      # dense fp6 / fp4 MFMA
 PRIMARY = "bert_ffn_in"
 # HBM bytes per launch of the stage-U kernel (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors a
 # plain 256 MiB copy gives), from profiles/hbm_traffic_fetch_write_size.md.  Counters cannot be read
 # inside this process; the figures belong to the launch shapes bench.py uses.
 PANEL_TRAFFIC_BYTES = {"convnext_mlp": 18.4e6 + 102.8e6}   # token-panel launches, same profile
 STAGE_U_TRAFFIC_BYTES = {"bert_ffn_in": 11.1e6 + 6.29e6, "convnext_mlp": 186e6 + 102.8e6,
-                         "opt66b_fc1_prefill": 2021e6 + 302.0e6, "opt6b7_fc1_decode": 34.2e6 + 0.066e6,
+                         "opt66b_fc1_prefill": 2138.5e6 + 302.0e6 + 75.6e6 + 89.7e6,   # fp6 kernel fetch + write, planes pass fetch + write
+                         "opt6b7_fc1_decode": 34.2e6 + 0.066e6,
                          "opt6b7_fc1_decode_b16": 35.9e6 + 1.05e6}
 
 
@@ -74,6 +76,8 @@ def _stage_u_kernel_name(tsvd, handle, B):
         return "batched stage-U kernel"
     if su.value == 32:
         return "tsvd_panel_kernel"
+    if su.value == 40:
+        return "tsvd_gemm_fp6_kernel"
     return "tsvd_gemm_ring_kernel" if su.value >= 14 else "tsvd_gemm_pipe_kernel"
 
 
@@ -173,6 +177,19 @@ def bench_workload(name, steps, warmup, with_cpu=True, cpu_budget_s=4.0):
                            "frac": res["executed_tflops"] / PEAK_MFMA_TFLOPS,
                            "traffic": PANEL_TRAFFIC_BYTES.get(name),
                            "whole_path_frac": res["executed_tflops"] / PEAK_MFMA_TFLOPS}
+    elif batched and kernel_name == "tsvd_gemm_fp6_kernel":
+        # stage U = planes pass + fp4 x fp6 kernel.  Achieved = ALGORITHMIC flops (2 M K B) per second; the
+        # kernel executes three times as many (three planes) on the fp4 / fp6 MFMA path, whose dense
+        # peak is 10.1 PFLOP/s; the fraction of the 2.5 PFLOP/s fp16 peak is given beside it because that
+        # is what every other batched kernel here is priced against.
+        fl_u = 2.0 * w.K * w.M * w.B
+        ach = fl_u / (u_ms * 1e-3) / 1e12
+        res["roofline"] = {"bound": "mfma", "kernel": "tsvd_z_planes_kernel + tsvd_gemm_fp6_kernel (stage U, fp4 x fp6 MFMA, 3 planes)",
+                           "achieved": ach, "peak": PEAK_MFMA_FP6_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_MFMA_FP6_TFLOPS,
+                           "executed_tflops": 3.0 * ach, "executed_frac": 3.0 * ach / PEAK_MFMA_FP6_TFLOPS,
+                           "frac_of_fp16_peak": ach / PEAK_MFMA_TFLOPS,
+                           "traffic": STAGE_U_TRAFFIC_BYTES.get(name),
+                           "whole_path_frac_of_fp16_peak": res["executed_tflops"] / PEAK_MFMA_TFLOPS}
     elif batched:
         fl_u = 2.0 * w.K * w.M * w.B
         res["roofline"] = {"bound": "mfma", "kernel": kernel_name + " (stage U, fp16 MFMA)",
