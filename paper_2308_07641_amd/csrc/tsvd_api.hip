@@ -347,7 +347,8 @@ size_t gemm_workspace(const tsvd_handle* h, int64_t B) {
     const int64_t Bp = tsvd_round_up(B, 256);
     size_t bytes = round256((size_t)(TSVD_COLMAX_PARTS + 1) * Bp * 4) + round256((size_t)h->hd.Kp * (size_t)Bp * 2);
     // (the rule is asked as for aligned rows: a caller with unaligned rows then reserves a little too much)
-    if (tsvd_gemm_use_fp6(h->hd.Mp, h->hd.Kp, h->hd.Np, B, h->cu_count, true)) bytes += round256(tsvd_gemm_fp6_bytes(h->hd.Kp, Bp));
+    if (tsvd_gemm_use_fp6(h->hd.Mp, h->hd.Kp, h->hd.Np, B, h->cu_count, true))      // planes of Z, and of X for stage V
+        bytes += round256(tsvd_gemm_fp6_bytes(h->hd.Kp, Bp)) + round256(tsvd_gemm_fp6_bytes(h->hd.Np, Bp));
     return bytes;
 }
 
@@ -569,6 +570,7 @@ extern "C" int tsvd_internal_tile_shapes(const tsvd_handle* h, long long B, int*
             *shape_v = tsvd_gemm_tile_shape(h->hd.Kp, Bp, h->cu_count, true);
             *shape_u = tsvd_gemm_tile_shape(h->hd.Mp, Bp, h->cu_count, true);
             if (tsvd_gemm_use_fp6(h->hd.Mp, h->hd.Kp, h->hd.Np, B, h->cu_count, true)) *shape_u = 40;   // fp4 x fp6 planes
+            if (tsvd_gemm_use_fp6_v(h->hd.Mp, h->hd.Kp, h->hd.Np, B, h->cu_count, true) && *shape_v < 10) *shape_v = 40;
         }
     }
     return 0;

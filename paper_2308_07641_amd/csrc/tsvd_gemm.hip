@@ -694,17 +694,23 @@ typedef int i32x8 __attribute__((ext_vector_type(8)));
 // is read row by row (256 contiguous bytes each) into LDS, from where every thread picks the 32
 // values of its lane of the operand (row pitch 129 words: the picks of a wavefront, 16 tokens x 4
 // different rows, fall on different banks).
+template <bool BF16>
 __global__ void __launch_bounds__(512)
-tsvd_z_planes_kernel(const _Float16* __restrict__ Z, int Bp, int nblocks, unsigned char* __restrict__ planes) {
+tsvd_z_planes_kernel(const uint16_t* __restrict__ Z, long long ld, int rows_valid, int cols_valid, int nblocks,
+                     unsigned char* __restrict__ planes) {
     __shared__ uint32_t zt[128 * 65];                 // [index][token pair], pitch 65 words
     const int tt = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, g = lane >> 4;
     {
-        const uint32_t* src = reinterpret_cast<const uint32_t*>(Z + (size_t)blockIdx.y * 128 * Bp + blockIdx.x * 128);
+        // (ld is even and the matrix 4-byte aligned; rows and columns beyond the matrix read as zero:
+        // clamped addresses, masked afterwards)
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(Z);
         uint32_t r[16];
 #pragma unroll
         for (int n = 0; n < 16; ++n) {                // 128 rows x 64 words = 8192 words, 16 per thread
-            const int idx = n * 512 + threadIdx.x, row = idx >> 6, col = idx & 63;
-            r[n] = src[(size_t)row * (Bp / 2) + col];
+            const int idx = n * 512 + threadIdx.x, row = blockIdx.y * 128 + (idx >> 6), col = blockIdx.x * 128 + 2 * (idx & 63);
+            uint32_t v = src[((size_t)min(row, rows_valid - 1) * ld + min(col, cols_valid - 1)) / 2];
+            if (col + 1 >= cols_valid) v &= 0xFFFFu;
+            r[n] = row < rows_valid && col < cols_valid ? v : 0u;
         }
 #pragma unroll
         for (int n = 0; n < 16; ++n) {
@@ -720,7 +726,7 @@ tsvd_z_planes_kernel(const _Float16* __restrict__ Z, int Bp, int nblocks, unsign
     for (int e = 0; e < 32; ++e) {
         const uint32_t w = zt[(k0 + 32 * (e >> 4) + (e & 15)) * 65 + (tok >> 1)];
         const uint16_t h = (tok & 1) ? (uint16_t)(w >> 16) : (uint16_t)(w & 0xFFFFu);
-        v[e] = (float)__builtin_bit_cast(_Float16, h);
+        v[e] = BF16 ? __uint_as_float((uint32_t)h << 16) : (float)__builtin_bit_cast(_Float16, h);
     }
     unsigned char* rec = planes + ((size_t)(blockIdx.x * nblocks + blockIdx.y) * 8 + tt) * FP6_REC_BYTES;
     typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -769,7 +775,7 @@ __device__ __forceinline__ f32x4 mfma_fp6(const u32x4& a, const u32x4& lo, const
 // 256 rows x 128 tokens per workgroup, 2 x 2 wavefronts of 8 x 4 blocks, two workgroups per compute
 // unit; two LDS buffers of one 128-index block each; code words straight from global memory to
 // registers, one block ahead.
-template <int EX>
+template <bool STAGE2, int EX>
 __global__ void __launch_bounds__(256, 2)
 tsvd_gemm_fp6_kernel(gemm_args p) {
     constexpr int WM = 2, WN = 2, TM = 8, TN = 4, BT = 128;
@@ -843,12 +849,12 @@ tsvd_gemm_fp6_kernel(gemm_args p) {
 
     u32x2 wa[TM], wb[TM];
     float cmax = 0.f;
-    if (threadIdx.x < BT) cmax = load_column_max<true>(p, b0 + threadIdx.x);
+    if (threadIdx.x < BT) cmax = load_column_max<STAGE2>(p, b0 + threadIdx.x);
     load_w(0, wa);
     issue(0, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     touch(wa);
-    if (threadIdx.x < BT) publish_column_factor<true>(p, b0 + threadIdx.x, cmax, cs_lds, threadIdx.x);
+    if (threadIdx.x < BT) publish_column_factor<STAGE2>(p, b0 + threadIdx.x, cmax, cs_lds, threadIdx.x);
     __syncthreads();
     for (int P = 0; P < nblocks; P += 2) {
         int nx = min(P + 1, lastb);
@@ -866,7 +872,7 @@ tsvd_gemm_fp6_kernel(gemm_args p) {
         touch(wa);
         __syncthreads();
     }
-    gemm_epilogue<TM, TN, true, EX>(p, acc, strip0, b0, wn * TN * 16, cs_lds, i, g);
+    gemm_epilogue<TM, TN, STAGE2, EX>(p, acc, strip0, b0, wn * TN * 16, cs_lds, i, g);
 }
 
 // ---- ring variant for small problems -----------------------------------------------------------
@@ -1687,13 +1693,28 @@ bool tsvd_gemm_use_fp6(long long Mp, long long Kp, long long Np, long long B, lo
     return Kp >= 2048 && 2 * (Mp / 256) * (Bp / 128) >= cus;
 }
 
+// The same for stage V (planes of x), only together with the fp6 stage U (the workspace holds both
+// sets of planes then): TSVD_FP6_V = 0 never, 1 whenever possible, default by the rule of stage U
+// applied to stage V's own sizes.  Needs x with an even row pitch at a 4-byte aligned address.
+bool tsvd_gemm_use_fp6_v(long long Mp, long long Kp, long long Np, long long B, long long cus, bool aligned) {
+    if (!aligned || !tsvd_gemm_use_fp6(Mp, Kp, Np, B, cus, aligned)) return false;
+    const char* v = getenv("TSVD_FP6_V");
+    const int mode = (v && *v) ? atoi(v) : -1;
+    const long long Bp = tsvd_round_up(B, 256);
+    if (mode == 0 || tsvd_gemm_fp6_bytes(Np, Bp) >= (1ull << 31)) return false;
+    if (mode == 1) return true;
+    return Np >= 2048 && 2 * (Kp / 256) * (Bp / 128) >= cus;
+}
+
 hipError_t tsvd_gemm_init() {
     hipError_t e;
-    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<0>), hipFuncAttributeMaxDynamicSharedMemorySize,
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 0>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  2 * FP6_PAIR_BYTES + 512)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize,
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<false, 0>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  2 * FP6_PAIR_BYTES + 512)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize,
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 1>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 2 * FP6_PAIR_BYTES + 512)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 2>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  2 * FP6_PAIR_BYTES + 512)) != hipSuccess) return e;
     if ((e = init_gemm<2, 4, 8, 4, false>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 4, 8, 4, true>()) != hipSuccess) return e;
@@ -1825,13 +1846,27 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    if (mask & 2) e = fuse ? launch_cfg<false, true>(cfg1, a1, fast1, hd.Kp, Bp, stream)
+    // stage V on fp4 x fp6 as well when its own contraction (N) is long: X -> planes (after Z's planes in the workspace)
+    const bool fp6_v = !fuse && tsvd_gemm_use_fp6_v(hd.Mp, hd.Kp, hd.Np, g.B, g.cu_count, fast1);
+    if ((mask & 2) && fp6_v) {
+        unsigned char* xplanes = reinterpret_cast<unsigned char*>(Z) + (((size_t)hd.Kp * Bp * 2 + 255) & ~(size_t)255) +
+                                 ((tsvd_gemm_fp6_bytes(hd.Kp, Bp) + 255) & ~(size_t)255);
+        hipLaunchKernelGGL(tsvd_z_planes_kernel<true>, dim3(Bp / 128, (unsigned)(hd.Np / 128)), dim3(512), 0, stream,
+                           static_cast<const uint16_t*>(g.x), (long long)g.ldx, (int)hd.N, (int)g.B, (int)(hd.Np / 128), xplanes);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        gemm_args a4 = a1;
+        a4.act = reinterpret_cast<const uint16_t*>(xplanes);
+        a4.act_bytes = (unsigned)tsvd_gemm_fp6_bytes(hd.Np, Bp);
+        hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<false, 0>), dim3(Bp / 128, (unsigned)(hd.Kp / 256)), dim3(256), 2 * FP6_PAIR_BYTES + 512, stream, a4);
+        e = hipGetLastError();
+    } else if (mask & 2) e = fuse ? launch_cfg<false, true>(cfg1, a1, fast1, hd.Kp, Bp, stream)
                            : launch_cfg<false, false>(cfg1, a1, fast1, hd.Kp, Bp, stream);
     if (e != hipSuccess) return e;
     if ((mask & 4) && tsvd_gemm_use_fp6(hd.Mp, hd.Kp, hd.Np, g.B, g.cu_count, fast1)) {
         // Z (fp16) -> three fp6 planes in operand order, then stage U on fp4 x fp6
         unsigned char* planes = reinterpret_cast<unsigned char*>(Z) + (((size_t)hd.Kp * Bp * 2 + 255) & ~(size_t)255);
-        hipLaunchKernelGGL(tsvd_z_planes_kernel, dim3(Bp / 128, (unsigned)(hd.Kp / 128)), dim3(512), 0, stream, Z, Bp, (int)(hd.Kp / 128), planes);
+        hipLaunchKernelGGL(tsvd_z_planes_kernel<false>, dim3(Bp / 128, (unsigned)(hd.Kp / 128)), dim3(512), 0, stream,
+                           reinterpret_cast<const uint16_t*>(Z), (long long)Bp, (int)hd.Kp, Bp, (int)(hd.Kp / 128), planes);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         gemm_args a3 = a2;
         a3.act = reinterpret_cast<const uint16_t*>(planes);
@@ -1839,9 +1874,9 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
         const int ex = out_variant(a3.bias, a3.out_bf16, a3.out, a3.ld_out);
         const size_t lds = 2 * FP6_PAIR_BYTES + 512;
         const dim3 grid(Bp / 128, (unsigned)(hd.Mp / 256)), block(256);
-        if (ex == 2) hipLaunchKernelGGL(tsvd_gemm_fp6_kernel<2>, grid, block, lds, stream, a3);
-        else if (ex == 1) hipLaunchKernelGGL(tsvd_gemm_fp6_kernel<1>, grid, block, lds, stream, a3);
-        else hipLaunchKernelGGL(tsvd_gemm_fp6_kernel<0>, grid, block, lds, stream, a3);
+        if (ex == 2) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 2>), grid, block, lds, stream, a3);
+        else if (ex == 1) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 1>), grid, block, lds, stream, a3);
+        else hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 0>), grid, block, lds, stream, a3);
         return hipGetLastError();
     }
     if (mask & 4) e = launch_cfg<true, false>(cfg2, a2, true, hd.Mp, Bp, stream);

@@ -124,5 +124,7 @@ bool tsvd_gemm_use_panel(long long Mp, long long Kp, long long Np, long long B, 
 // Stage U through fp6 planes of Z: whether a call takes it, and the extra workspace it needs after Z.
 bool tsvd_gemm_use_fp6(long long Mp, long long Kp, long long Np, long long B, long long cus, bool aligned);
 size_t tsvd_gemm_fp6_bytes(long long Kp, long long Bp);
+// Stage V through fp6 planes of x (only together with the above; its planes follow those of Z).
+bool tsvd_gemm_use_fp6_v(long long Mp, long long Kp, long long Np, long long B, long long cus, bool aligned);
 #define TSVD_COLMAX_PARTS 16
 int tsvd_stage_mask();   // profiling switch read from the environment (default 7 = everything)

@@ -472,13 +472,19 @@ def test_repeated_calls_are_bit_identical(tsvd):
 
 
 # ---- stage U on fp4 codes x three fp6 planes of Z (experimental switch TSVD_FP6=1)
+@pytest.mark.parametrize("stage_v", [False, True])
 @pytest.mark.parametrize("M,N,K,B", [(300, 200, 270, 100), (515, 300, 777, 130), (1024, 512, 768, 512), (130, 64, 2100, 257)])
-def test_fp6_planes_stage_u(tsvd, M, N, K, B, monkeypatch):
+def test_fp6_planes_stage_u(tsvd, M, N, K, B, stage_v, monkeypatch):
     """Z as three E2M3 planes with per-lane block scales, multiplied with the codes as fp4 on the scaled
     128-deep MFMA: exact on integer instances (small integers need one plane), within the tolerance
-    of the 16-bit path on random ones and next to identical to it; bias and bf16 output included."""
+    of the 16-bit path on random ones and next to identical to it; bias and bf16 output included.
+    stage_v: x goes through planes as well (stage V on the same kernel; forced here, with the
+    two-kernel form of stage V that it replaces)."""
     import torch
     monkeypatch.setenv("TSVD_FP6", "1")
+    monkeypatch.setenv("TSVD_FP6_V", "1" if stage_v else "0")
+    if stage_v:
+        monkeypatch.setenv("TSVD_GEMM_CFG_V", "3")
     i = workloads.make_integer_inputs(M, N, K, B, 0.5, "bf16", seed=606 + B)
     print(f"case fp6 int M={M} N={N} K={K} B={B}", flush=True)
     y, h = run_forward(i)
