@@ -772,15 +772,19 @@ __device__ __forceinline__ f32x4 mfma_fp6(const u32x4& a, const u32x4& lo, const
     return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(av, bv, acc, 4, 2, 0, 0x7F7F7F7F, PL, (int)scale);
 }
 
-// 256 rows x 128 tokens per workgroup, 2 x 2 wavefronts of 8 x 4 blocks, two workgroups per compute
-// unit; two LDS buffers of one 128-index block each; code words straight from global memory to
+// WM x WN = 2 x 2 wavefronts (256 rows x 128 tokens per workgroup) or 4 x 1 (512 x 64) of 8 x 4 blocks
+// each, two workgroups per compute unit; two LDS buffers of one 128-index block each; code words straight from global memory to
 // registers, one block ahead.
-template <bool STAGE2, int EX>
+template <bool STAGE2, int EX, int WM = 2, int WN = 2>
 __global__ void __launch_bounds__(256, 2)
 tsvd_gemm_fp6_kernel(gemm_args p) {
-    constexpr int WM = 2, WN = 2, TM = 8, TN = 4, BT = 128;
-    extern __shared__ __align__(16) unsigned char smem[];   // 2 x FP6_PAIR_BYTES, then BT column factors
-    float* cs_lds = reinterpret_cast<float*>(smem + 2 * FP6_PAIR_BYTES);
+    static_assert(WM * WN == 4, "four wavefronts");
+    constexpr int TM = 8, TN = 4, BT = WN * 64;
+    constexpr int BLK_BYTES = BT / 16 * FP6_REC_BYTES;      // one 128-index block of this workgroup's tokens
+    constexpr int PIECES = BLK_BYTES / 1024;                // 38 or 19 pieces of 1 KiB
+    static_assert(BLK_BYTES % 1024 == 0, "whole pieces");
+    extern __shared__ __align__(16) unsigned char smem[];   // 2 x BLK_BYTES, then BT column factors
+    float* cs_lds = reinterpret_cast<float*>(smem + 2 * BLK_BYTES);
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave / WN, wn = wave - wm * WN;
     const int i = lane & 15, g = lane >> 4;
@@ -800,14 +804,14 @@ tsvd_gemm_fp6_kernel(gemm_args p) {
 #pragma unroll
         for (int b = 0; b < TN; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // one block of this workgroup's 128 tokens = 38 pieces of 1 KiB; wavefront w copies pieces
-    // w, w + 4, ... (the two wavefronts whose tenth piece would be 38 or 39 copy piece 37 again)
+    // one block of this workgroup's tokens = PIECES pieces of 1 KiB; wavefront w copies pieces
+    // w, w + 4, ... (a wavefront whose last piece would lie beyond the block copies the last one again)
     auto issue = [&](int blk, int buf) {
-        const int rec0 = (blockIdx.x * nblocks + blk) * FP6_PAIR_BYTES;
+        const int rec0 = ((b0 >> 7) * nblocks + blk) * FP6_PAIR_BYTES + ((b0 & 127) >> 4) * FP6_REC_BYTES;
 #pragma unroll
-        for (int c = 0; c < 10; ++c) {
-            const int piece = min(c * 4 + wave, 37);
-            buf_load128_to_lds(act_rsrc, lds_base + buf * FP6_PAIR_BYTES + piece * 1024, lane * 16, rec0 + piece * 1024);
+        for (int c = 0; c < (PIECES + 3) / 4; ++c) {
+            const int piece = min(c * 4 + wave, PIECES - 1);
+            buf_load128_to_lds(act_rsrc, lds_base + buf * BLK_BYTES + piece * 1024, lane * 16, rec0 + piece * 1024);
         }
     };
     const int w_voff = lane * 16;
@@ -823,7 +827,7 @@ tsvd_gemm_fp6_kernel(gemm_args p) {
             av[a] = u32x4{(w[a].x << 2) & 0xCCCCCCCCu, w[a].x & 0xCCCCCCCCu, (w[a].y << 2) & 0xCCCCCCCCu, w[a].y & 0xCCCCCCCCu};
 #pragma unroll
         for (int b = 0; b < TN; ++b) {
-            const unsigned char* rec = smem + buf * FP6_PAIR_BYTES + (wn * TN + b) * FP6_REC_BYTES;
+            const unsigned char* rec = smem + buf * BLK_BYTES + (wn * TN + b) * FP6_REC_BYTES;
             const uint32_t sc = *reinterpret_cast<const uint32_t*>(rec + 4608 + lane * 4);
             u32x4 lo[3];
             u32x2 hi[3];
@@ -1706,16 +1710,36 @@ bool tsvd_gemm_use_fp6_v(long long Mp, long long Kp, long long Np, long long B, 
     return Np >= 2048 && 2 * (Kp / 256) * (Bp / 128) >= cus;
 }
 
+template <int WM, int WN>
+hipError_t init_fp6() {
+    constexpr int lds = 2 * (WN * 4 * FP6_REC_BYTES) + 512;
+    hipError_t e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 0, WM, WN>), hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 1, WM, WN>), hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 2, WM, WN>), hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<false, 0, WM, WN>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+}
+// rows_p: padded rows of the stage's weights; ex: output variant (stage U only)
+template <int WM, int WN>
+hipError_t launch_fp6(bool stage2, const gemm_args& a, long long rows_p, int Bp, int ex, hipStream_t stream) {
+    constexpr int lds = 2 * (WN * 4 * FP6_REC_BYTES) + 512;
+    const dim3 grid(Bp / (WN * 64), (unsigned)(rows_p / (WM * 128))), block(256);
+    if (!stage2) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<false, 0, WM, WN>), grid, block, lds, stream, a);
+    else if (ex == 2) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 2, WM, WN>), grid, block, lds, stream, a);
+    else if (ex == 1) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 1, WM, WN>), grid, block, lds, stream, a);
+    else hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 0, WM, WN>), grid, block, lds, stream, a);
+    return hipGetLastError();
+}
+// 512 x 64 tiles (4 x 1 wavefronts) when the rows allow: half the traffic of the planes, twice that of the codes
+hipError_t launch_fp6_any(bool stage2, const gemm_args& a, long long rows_p, int Bp, int ex, hipStream_t stream) {
+    if (rows_p % 512 == 0 && env_cfg("TSVD_FP6_TALL", 1) != 0) return launch_fp6<4, 1>(stage2, a, rows_p, Bp, ex, stream);
+    return launch_fp6<2, 2>(stage2, a, rows_p, Bp, ex, stream);
+}
+
 hipError_t tsvd_gemm_init() {
     hipError_t e;
-    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 0>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 2 * FP6_PAIR_BYTES + 512)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<false, 0>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 2 * FP6_PAIR_BYTES + 512)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 1>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 2 * FP6_PAIR_BYTES + 512)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 2>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 2 * FP6_PAIR_BYTES + 512)) != hipSuccess) return e;
+    if ((e = init_fp6<2, 2>()) != hipSuccess) return e;
+    if ((e = init_fp6<4, 1>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 4, 8, 4, false>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 4, 8, 4, true>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 2, 8, 4, false>()) != hipSuccess) return e;
@@ -1857,8 +1881,7 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
         gemm_args a4 = a1;
         a4.act = reinterpret_cast<const uint16_t*>(xplanes);
         a4.act_bytes = (unsigned)tsvd_gemm_fp6_bytes(hd.Np, Bp);
-        hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<false, 0>), dim3(Bp / 128, (unsigned)(hd.Kp / 256)), dim3(256), 2 * FP6_PAIR_BYTES + 512, stream, a4);
-        e = hipGetLastError();
+        e = launch_fp6_any(false, a4, hd.Kp, Bp, 0, stream);
     } else if (mask & 2) e = fuse ? launch_cfg<false, true>(cfg1, a1, fast1, hd.Kp, Bp, stream)
                            : launch_cfg<false, false>(cfg1, a1, fast1, hd.Kp, Bp, stream);
     if (e != hipSuccess) return e;
@@ -1871,13 +1894,7 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
         gemm_args a3 = a2;
         a3.act = reinterpret_cast<const uint16_t*>(planes);
         a3.act_bytes = (unsigned)tsvd_gemm_fp6_bytes(hd.Kp, Bp);
-        const int ex = out_variant(a3.bias, a3.out_bf16, a3.out, a3.ld_out);
-        const size_t lds = 2 * FP6_PAIR_BYTES + 512;
-        const dim3 grid(Bp / 128, (unsigned)(hd.Mp / 256)), block(256);
-        if (ex == 2) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 2>), grid, block, lds, stream, a3);
-        else if (ex == 1) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 1>), grid, block, lds, stream, a3);
-        else hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 0>), grid, block, lds, stream, a3);
-        return hipGetLastError();
+        return launch_fp6_any(true, a3, hd.Mp, Bp, out_variant(a3.bias, a3.out_bf16, a3.out, a3.ld_out), stream);
     }
     if (mask & 4) e = launch_cfg<true, false>(cfg2, a2, true, hd.Mp, Bp, stream);
     return e;

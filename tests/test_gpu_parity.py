@@ -473,7 +473,8 @@ def test_repeated_calls_are_bit_identical(tsvd):
 
 # ---- stage U on fp4 codes x three fp6 planes of Z (experimental switch TSVD_FP6=1)
 @pytest.mark.parametrize("stage_v", [False, True])
-@pytest.mark.parametrize("M,N,K,B", [(300, 200, 270, 100), (515, 300, 777, 130), (1024, 512, 768, 512), (130, 64, 2100, 257)])
+@pytest.mark.parametrize("M,N,K,B", [(300, 200, 270, 100), (515, 300, 777, 130), (1024, 512, 768, 512), (130, 64, 2100, 257),
+                                     (512, 300, 1024, 200)])
 def test_fp6_planes_stage_u(tsvd, M, N, K, B, stage_v, monkeypatch):
     """Z as three E2M3 planes with per-lane block scales, multiplied with the codes as fp4 on the scaled
     128-deep MFMA: exact on integer instances (small integers need one plane), within the tolerance
