@@ -672,21 +672,28 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
 // resolve about 2^-13 of a block's largest magnitude.  A separate pass (tsvd_z_planes_kernel) turns
 // the fp16 Z of stage V into planes in the operand order of this kernel, so the loads into LDS
 // are plain copies and the operand reads plain 16- and 8-byte reads.
-// Status: same accuracy as the 16-bit path and 5 - 20 % faster per call on long contractions with
-// many tiles, where it is used (tsvd_gemm_use_fp6; TSVD_FP6=0 / 1 forces it off / on).
-// Measured on MI355X, 36864 x 18432 weights, 2048 tokens: this kernel 1.58 ms + 0.03 ms for the
-// planes against 1.78 ms for the 16-bit stage U; its MFMAs alone would take 0.9 ms.  A wavefront's
-// 96 MFMAs per block last 0.7 us while a request to the L2s takes 1.4 us under this load, so with
-// blocks requested one iteration ahead every barrier waits about a microsecond.  A ring of three
-// blocks with every load under explicit wait counts was tried in a 256 x 128 tile of eight
-// wavefronts (one workgroup per compute unit): 1.78 - 1.83 ms, slower, with a barrier for every
-// 0.35 us of MFMAs per wavefront.
+// Status: same accuracy as the 16-bit path and 10 - 25 % faster per call on long contractions with
+// many tiles, where it is used for both stages (tsvd_gemm_use_fp6, tsvd_gemm_use_fp6_v; TSVD_FP6 and
+// TSVD_FP6_V = 0 / 1 force it off / on).
+// Measured on MI355X, 36864 x 18432 weights, 2048 tokens: this kernel 1.50 ms + 0.03 ms for the
+// planes against 1.78 ms for the 16-bit stage U; its MFMAs alone would take 0.87 ms at 2.4 GHz.  The
+// counters show the matrix pipes busy 80 % of the compute units' busy cycles, 16 cycles per MFMA,
+// and a sustained clock of 1.82 GHz under this load (2.08 GHz under the 16-bit kernel): what is left
+// to gain in software is the last fifth of the pipe's cycles, the rest of the gap to the nominal
+// peak is the clock.  Timing probes with every load redirected to two cached blocks (1.50 ms) and
+// with no operand read ahead (1.53 ms) moved little: neither the L2 nor LDS latency bounds it.
+// Tried and dropped: a ring of three blocks with every load under explicit wait counts in a
+// 256 x 128 tile of eight wavefronts (1.78 - 1.83 ms, a barrier for every 0.35 us of MFMAs per
+// wavefront); a 512 x 128 tile with 256 indices per barrier (register spills, 2.0 ms).
 //
 // Record of one (16-token tile, 128-index block): planes' first 16 bytes per lane [3][64][16], last
 // 8 bytes per lane [3][64][8], scale words [64][4] = 4864 bytes; lane (i, g) holds, for token i of
 // the tile, the indices that meet elements 0..31 of lane group g of the A operand built from the
 // tile format (tsvd_step_column).  Records are stored [128-token group][block][tile in group].
 #define FP6_REC_BYTES 4864
+#ifndef FP6_LDS_DEPTH
+#define FP6_LDS_DEPTH 2                            // operand reads ahead of the MFMAs, in steps of eight MFMAs
+#endif
 #define FP6_PAIR_BYTES (8 * FP6_REC_BYTES)      // one block of one 128-token group: 38 KiB exactly
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 
@@ -825,24 +832,38 @@ tsvd_gemm_fp6_kernel(gemm_args p) {
 #pragma unroll
         for (int a = 0; a < TM; ++a)
             av[a] = u32x4{(w[a].x << 2) & 0xCCCCCCCCu, w[a].x & 0xCCCCCCCCu, (w[a].y << 2) & 0xCCCCCCCCu, w[a].y & 0xCCCCCCCCu};
+        // 12 steps (token tile b = s / 3, plane s % 3) of eight MFMAs each; the operands of step s + DEPTH
+        // are read from LDS before the MFMAs of step s are issued (the scheduler is held to this order:
+        // left to itself it reads every operand right before its use and the wavefront waits for LDS
+        // ten times per block)
+        constexpr int DEPTH = FP6_LDS_DEPTH, NSET = DEPTH + 1;
+        u32x4 lo[NSET];
+        u32x2 hi[NSET];
+        uint32_t sc[2];
+        auto read_step = [&](int st) {
+            const unsigned char* rec = smem + buf * BLK_BYTES + (wn * TN + st / 3) * FP6_REC_BYTES;
+            const int pl = st % 3;
+            lo[st % NSET] = *reinterpret_cast<const u32x4*>(rec + pl * 1024 + lane * 16);
+            hi[st % NSET] = *reinterpret_cast<const u32x2*>(rec + 3072 + pl * 512 + lane * 8);
+            if (pl == 0) sc[(st / 3) & 1] = *reinterpret_cast<const uint32_t*>(rec + 4608 + lane * 4);
+        };
 #pragma unroll
-        for (int b = 0; b < TN; ++b) {
-            const unsigned char* rec = smem + buf * BLK_BYTES + (wn * TN + b) * FP6_REC_BYTES;
-            const uint32_t sc = *reinterpret_cast<const uint32_t*>(rec + 4608 + lane * 4);
-            u32x4 lo[3];
-            u32x2 hi[3];
+        for (int st = 0; st < DEPTH; ++st) read_step(st);
 #pragma unroll
-            for (int pl = 0; pl < 3; ++pl) {
-                lo[pl] = *reinterpret_cast<const u32x4*>(rec + pl * 1024 + lane * 16);
-                hi[pl] = *reinterpret_cast<const u32x2*>(rec + 3072 + pl * 512 + lane * 8);
+        for (int st = 0; st < 3 * TN; ++st) {
+            if (st + DEPTH < 3 * TN) read_step(st + DEPTH);
+            __builtin_amdgcn_sched_barrier(0);
+            const int b = st / 3, q = st % NSET;
+            // the eight row blocks of one plane: consecutive MFMAs never wait for each other's result
+#pragma unroll
+            for (int a = 0; a < TM; ++a) {
+                switch (st % 3) {
+                    case 0: acc[a][b] = mfma_fp6<0>(av[a], lo[q], hi[q], sc[b & 1], acc[a][b]); break;
+                    case 1: acc[a][b] = mfma_fp6<1>(av[a], lo[q], hi[q], sc[b & 1], acc[a][b]); break;
+                    default: acc[a][b] = mfma_fp6<2>(av[a], lo[q], hi[q], sc[b & 1], acc[a][b]); break;
+                }
             }
-            // plane by plane over the eight row blocks: consecutive MFMAs never wait for each other's result
-#pragma unroll
-            for (int a = 0; a < TM; ++a) acc[a][b] = mfma_fp6<0>(av[a], lo[0], hi[0], sc, acc[a][b]);
-#pragma unroll
-            for (int a = 0; a < TM; ++a) acc[a][b] = mfma_fp6<1>(av[a], lo[1], hi[1], sc, acc[a][b]);
-#pragma unroll
-            for (int a = 0; a < TM; ++a) acc[a][b] = mfma_fp6<2>(av[a], lo[2], hi[2], sc, acc[a][b]);
+            __builtin_amdgcn_sched_barrier(0);
         }
         __builtin_amdgcn_sched_barrier(0);
     };
