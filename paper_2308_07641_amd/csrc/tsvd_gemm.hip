@@ -1714,8 +1714,9 @@ bool tsvd_gemm_use_fp6(long long Mp, long long Kp, long long Np, long long B, lo
     // measured on MI355X against the 16-bit stage U (whole call): 36864 x 9216 x 18432 at 2048 tokens
     // 2.29 -> 2.18 ms, 16384 x 4096 x 8192 at 512 tokens 191 -> 153 us, 8192 x 2048 x 4096 at 1024 tokens
     // 108 -> 93 us, 4096 x 1024 x 2048 at 2048 tokens 64 -> 58 us; 3072 x 768 x 1536 at 4096 tokens 66 -> 67 us
-    // and at 512 tokens 17 -> 50 us: long contractions with enough 256 x 128 tiles for half the compute units
-    return Kp >= 2048 && 2 * (Mp / 256) * (Bp / 128) >= cus;
+    // and at 512 tokens 17 -> 50 us; 4096 x 1024 x 2048 at 1024 tokens (128 tiles) 39 -> 47 us, 12288 x 3072 x 6144 at
+    // 256 tokens (96 tiles) 78 -> 89 us: long contractions with a 256 x 128 tile for every compute unit
+    return Kp >= 2048 && (Mp / 256) * (Bp / 128) >= cus;
 }
 
 // The same for stage V (planes of x), only together with the fp6 stage U (the workspace holds both
@@ -1728,7 +1729,7 @@ bool tsvd_gemm_use_fp6_v(long long Mp, long long Kp, long long Np, long long B, 
     const long long Bp = tsvd_round_up(B, 256);
     if (mode == 0 || tsvd_gemm_fp6_bytes(Np, Bp) >= (1ull << 31)) return false;
     if (mode == 1) return true;
-    return Np >= 2048 && 2 * (Kp / 256) * (Bp / 128) >= cus;
+    return Np >= 2048 && (Kp / 256) * (Bp / 128) >= cus;
 }
 
 template <int WM, int WN>
