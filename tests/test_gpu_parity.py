@@ -505,3 +505,23 @@ def test_fp6_planes_stage_u(tsvd, M, N, K, B, stage_v, monkeypatch):
     y0 = tsvd.tsvd_forward(h, to_device(j)).cpu().numpy().astype(np.float64)
     tsvd.tsvd_free(h)
     assert rel_err(y0, y1) <= 5e-4        # both round Z to about 12 bits, differently
+
+
+@pytest.mark.parametrize("mode", ["fp16", "fp6"])
+def test_outlier_features(tsvd, mode, monkeypatch):
+    """Activations with outlier features (1 % of the features 300 times larger, as in transformer
+    layers): the per-token scaling of z and, on the fp4 x fp6 kernels, the block scales of the planes of
+    both stages keep the error at the level of ordinary inputs."""
+    monkeypatch.setenv("TSVD_FP6", "1" if mode == "fp6" else "0")
+    if mode == "fp6":
+        monkeypatch.setenv("TSVD_FP6_V", "1")
+        monkeypatch.setenv("TSVD_GEMM_CFG_V", "3")
+    i = workloads.make_outlier_inputs(512, 1280, 1024, 300, 0.6, 0.02, seed=77, factor=300.0, share=0.01)
+    assert np.max(np.abs(i.X)) > 100.0
+    print(f"case outliers {mode}", flush=True)
+    ref = oracle.forward(i.U, i.S, i.V, i.X)
+    y, h = run_forward(i)
+    tsvd.tsvd_free(h)
+    assert rel_err(y, ref) <= 0.5 * TOL["bf16"]
+    rows = np.max(np.abs(y - ref), axis=1) / np.max(np.abs(ref), axis=1)
+    assert np.median(rows) <= 0.5 * TOL["bf16"]

@@ -103,6 +103,19 @@ def make_inputs(M: int, N: int, K: int, B: int, p0: float, s_scale: float,
     return Inputs(U, S, V, X, bits, x_dtype)
 
 
+def make_outlier_inputs(M: int, N: int, K: int, B: int, p0: float, s_scale: float, seed: int,
+                        factor: float, share: float) -> Inputs:
+    """make_inputs with bf16 activations whose features (rows of X) are multiplied by `factor` with
+    probability `share`: the outlier channels of transformer activations (a few features two or
+    three orders of magnitude above the rest, in every token)."""
+    base = make_inputs(M, N, K, B, p0, s_scale, "f32", seed)
+    rng = np.random.Generator(np.random.PCG64(seed + 1))
+    X = base.X.copy()
+    X[rng.random(N) < share] *= np.float32(factor)
+    bits = f32_to_bf16_bits(X)
+    return Inputs(base.U, base.S, base.V, bf16_bits_to_f32(bits), bits, "bf16")
+
+
 def make_workload(name: str, B: int | None = None) -> Inputs:
     """Inputs of a named workload; B overrides the token count (same seed)."""
     w = WORKLOADS[name]
