@@ -179,9 +179,12 @@ struct gemm_args {
     long long* clocks;        // tuning aid: phase timestamps per workgroup (stage 1: 0..7, stage 2: 8..15), or null
 };
 
-// One MFMA block with the activations as the row operand and the decoded weights as the column
-// operand: the result block is [16 tokens][16 weight rows], so a lane (i, g) ends up with the four
-// adjacent tokens 4 g .. 4 g + 3 of weight row i, which it can store with one vector write.
+// One MFMA block: decoded weights as the row operand, activations as the column operand, so a lane
+// (i, g) of the result holds token i of the weight rows 4 g .. 4 g + 3.  (Both operands have the same
+// register layout, so swapping them gives the transposed result, four adjacent tokens of one weight
+// row per lane and one vector store per block: measured in the ring kernel on a 3072 x 1536 factor at
+// 512 tokens, the stores of a workgroup then issue in 0.6 instead of 1.3 us but the call stays at
+// 17.1 us, so the plain layout was kept.)
 template <bool STAGE2>
 __device__ __forceinline__ f32x4 mfma16(const u32x4& w, const u32x2& xlo, const u32x2& xhi, f32x4 acc) {
     u32x4 x = {xlo.x, xlo.y, xhi.x, xhi.y};
@@ -947,12 +950,12 @@ tsvd_gemm_ring_kernel(gemm_args p) {
     constexpr int RPS = 64 / CPR;                    // rows per piece
     constexpr int WSTRIPS = WM * TM;                 // 16-row strips of the workgroup tile
     constexpr int W_BYTES = WSTRIPS * 512;           // code words of one pair
-    constexpr int WOPS = WSTRIPS * 2 / NW;           // code-word loads per wavefront and pair
+    constexpr int WOPS = (WSTRIPS * 2 + NW - 1) / NW; // code-word loads per wavefront and pair (a load past the last strip repeats it)
     constexpr int SUB_BYTES = 2 * STAGE_BYTES + W_BYTES;   // one pair
     constexpr int SLOT_BYTES = KG * SUB_BYTES;       // one ring slot: KG pairs
     constexpr int OPS = KG * (2 * SPW + WOPS);       // loads per wavefront and slot
     constexpr int CPT = KT * CPR / THREADS;          // FUSEMAX: chunks per thread and stage
-    static_assert(SLOTS % NW == 0 && 64 % CPR == 0 && (WSTRIPS * 2) % NW == 0 && NW % 2 == 0, "tile/wavefront mismatch");
+    static_assert(SLOTS % NW == 0 && 64 % CPR == 0 && NW % 2 == 0, "tile/wavefront mismatch");
     static_assert(NPB >= 2 && (NPB - 2) * OPS <= 63, "ring too deep for the load counter");
     static_assert(BT <= THREADS && (KT * CPR) % THREADS == 0 && THREADS % CPR == 0, "one thread per token of the tile");
     static_assert(!(FUSEMAX && STAGE2), "column maxima belong to stage 1");
@@ -995,10 +998,10 @@ tsvd_gemm_ring_kernel(gemm_args p) {
     typedef __attribute__((address_space(3))) unsigned char* lds_byte_ptr;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_byte_ptr)smem;
     const uint32_t lds_x = lds_base + wave * 1024;
-    // code-word load q of this wavefront: strip q * (NW / 2) + (wave >> 1), word wave & 1
-    const uint32_t lds_w = lds_base + 2 * STAGE_BYTES + (wave >> 1) * 512 + (wave & 1) * 256;
+    // code-word load q of this wavefront: strip min(q * (NW / 2) + (wave >> 1), WSTRIPS - 1), word wave & 1
+    const uint32_t lds_w = lds_base + 2 * STAGE_BYTES + (wave & 1) * 256;
     const int w_voff = lane * 16 + (wave & 1) * 4;
-    const int w_soff0 = (blockIdx.y * WSTRIPS + (wave >> 1)) * p.nkt * 1024;
+    const int w_soff0 = blockIdx.y * WSTRIPS * p.nkt * 1024;
 
     f32x4 acc[TM][TN];
 #pragma unroll
@@ -1027,9 +1030,11 @@ tsvd_gemm_ring_kernel(gemm_args p) {
             const int soff_w = w_soff0 + (pair >> 1) * 1024 + (pair & 1) * 8;
 #pragma unroll
             for (int q = 0; q < WOPS; ++q)
-                if (part < 0 || ((KG * 2 * SPW + s * WOPS + q) & 3) == part)
-                    buf_load32_to_lds(w_rsrc, lds_w + slot * SLOT_BYTES + s * SUB_BYTES + q * (NW / 2) * 512, w_voff,
-                                      soff_w + q * (NW / 2) * p.nkt * 1024);
+                if (part < 0 || ((KG * 2 * SPW + s * WOPS + q) & 3) == part) {
+                    const int strip = min(q * (NW / 2) + (wave >> 1), WSTRIPS - 1);
+                    buf_load32_to_lds(w_rsrc, lds_w + slot * SLOT_BYTES + s * SUB_BYTES + strip * 512, w_voff,
+                                      soff_w + strip * p.nkt * 1024);
+                }
         }
     };
     auto load_frags = [&](const unsigned char* stage_base, int hh, u32x2 (&lo)[TN], u32x2 (&hi)[TN]) {
@@ -1605,6 +1610,7 @@ template <int WM, int WN, int TM, int TN, bool STAGE2, int NPB, bool FUSEMAX, in
 hipError_t launch_ring(const gemm_args& a, long long rows, int Bp, hipStream_t stream) {
     constexpr int BT = WN * TN * 16, MT = WM * TM * 16;
     constexpr size_t lds = ring_lds_bytes<WM, WN, TM, TN, NPB, KG>();
+    if (rows % MT) return hipErrorInvalidValue;      // (96-row tiles: the rule asks for them only when they divide the rows)
     const dim3 grid(Bp / BT, (unsigned)(rows / MT)), block(64 * WM * WN * KG);
     if constexpr (STAGE2) {
         const int ex = out_variant(a.bias, a.out_bf16, a.out, a.ld_out);
@@ -1642,8 +1648,10 @@ hipError_t init_ring() {
 // Ring-kernel shapes for launches of few workgroups (ring of 3 or 2 slots, small enough in LDS and
 // registers for two to three workgroups per compute unit):
 //   14:  64 x 64, 4 wavefronts     15: 128 x 64, 4 wavefronts
-//   16:  64 x 64, 8 wavefronts: the contraction split over two groups of four
-#define TSVD_RING_SHAPES(X) X(14, 2, 2, 2, 2, 3, 1) X(15, 2, 2, 4, 2, 3, 1) X(16, 2, 2, 2, 2, 2, 2)
+//   16:  64 x 64, 8 wavefronts: the contraction split over two groups of four     17: 96 x 64, likewise
+// (96 x 64 with rings of three and four slots, one workgroup per compute unit either way: 10.8 and 11.6 us
+// against 10.5 us for stage U of a 3072 x 1536 factor at 512 tokens)
+#define TSVD_RING_SHAPES(X) X(14, 2, 2, 2, 2, 3, 1) X(15, 2, 2, 4, 2, 3, 1) X(16, 2, 2, 2, 2, 2, 2) X(17, 2, 2, 3, 2, 2, 2)
 constexpr bool is_ring(int cfg) { return cfg >= 10; }
 
 template <bool STAGE2, bool FUSEMAX>
@@ -1686,7 +1694,12 @@ int tsvd_gemm_tile_shape(long long rows, long long Bp, long long cus, bool align
         return c0 < c1 ? 0 : 1;
     }
     if (!aligned) return t2 >= cus ? 2 : 3;
-    return (rows / 128) * (Bp / 64) >= cus ? 15 : 16;
+    if ((rows / 128) * (Bp / 64) >= cus) return 15;
+    // 96 x 64 tiles when they give (nearly) every compute unit exactly one workgroup where 64 x 64
+    // tiles would give half of them two
+    const long long t96 = (rows / 96) * (Bp / 64);
+    if (rows % 96 == 0 && t96 <= cus && 4 * t96 > 3 * cus && (rows / 64) * (Bp / 64) > cus) return 17;
+    return 16;
 }
 
 // The token-panel kernel serves 16-byte-aligned activations, K <= 1024, N <= 1024, code words of both factors

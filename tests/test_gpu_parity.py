@@ -94,6 +94,27 @@ def test_every_tile_shape_batched(tsvd, cfg, fuse, monkeypatch):
     assert rel_err(y, ref) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("fuse", ["1", "0"])
+def test_tile_shape_of_96_rows(tsvd, fuse, monkeypatch):
+    """The 96 x 64 ring tiles need padded row counts that 96 divides (the shape rule asks for them
+    only then): forced here on both stages of instances with 768 and 1536 padded rows."""
+    monkeypatch.setenv("TSVD_GEMM_CFG_V", "17")
+    monkeypatch.setenv("TSVD_GEMM_CFG_U", "17")
+    monkeypatch.setenv("TSVD_FUSEMAX", fuse)
+    monkeypatch.setenv("TSVD_PANEL", "0")
+    print(f"case tile shape 17 fuse {fuse}", flush=True)
+    i = workloads.make_integer_inputs(700, 200, 760, 300, 0.5, "bf16", seed=1717)
+    y, h = run_forward(i)
+    tsvd.tsvd_free(h)
+    assert np.array_equal(y, oracle.forward(i.U, i.S, i.V, i.X))
+    j = workloads.make_inputs(1500, 300, 1300, 600, 0.6, 0.02, "bf16", seed=1718)
+    ref = oracle.forward(j.U, j.S, j.V, j.X)
+    y, h = run_forward(j)
+    tsvd.tsvd_free(h)
+    assert not np.isnan(y).any()
+    assert rel_err(y, ref) <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("waves", ["16", "8"])
 @pytest.mark.parametrize("M,N,K,B", [(300, 200, 520, 300), (64, 48, 200, 17), (1030, 100, 1000, 70), (2048, 512, 1024, 1000)])
 def test_token_panel_kernel(tsvd, M, N, K, B, waves, monkeypatch):
@@ -336,6 +357,7 @@ LAYER_CASES = [
     (300, 200, 520, 304, {"TSVD_PANEL": "1"}),                            # token-panel kernel, 16 wavefronts
     (300, 200, 520, 304, {"TSVD_PANEL": "1", "TSVD_PANEL_WAVES": "8"}),   # token-panel kernel, 8 wavefronts
     (300, 200, 520, 304, {"TSVD_PANEL": "0", "TSVD_GEMM_CFG_U": "14", "TSVD_GEMM_CFG_V": "15"}),   # ring kernels, other shapes
+    (700, 200, 760, 304, {"TSVD_PANEL": "0", "TSVD_GEMM_CFG_U": "17", "TSVD_GEMM_CFG_V": "17"}),   # ring kernels, 96-row tiles
 ]
 
 
