@@ -782,14 +782,14 @@ __device__ __forceinline__ f32x4 mfma_fp6(const u32x4& a, const u32x4& lo, const
     return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(av, bv, acc, 4, 2, 0, 0x7F7F7F7F, PL, (int)scale);
 }
 
-// WM x WN = 2 x 2 wavefronts (256 rows x 128 tokens per workgroup) or 4 x 1 (512 x 64) of 8 x 4 blocks
-// each, two workgroups per compute unit; two LDS buffers of one 128-index block each; code words straight from global memory to
+// WM x WN = 2 x 2 wavefronts (256 rows x 128 tokens per workgroup) or 4 x 1 (512 x 64) of TM x 4 = 8 x 4 blocks
+// each, two workgroups per compute unit, or 4 x 1 of 4 x 4 blocks (256 x 64), three; two LDS buffers of one 128-index block each; code words straight from global memory to
 // registers, one block ahead.
-template <bool STAGE2, int EX, int WM = 2, int WN = 2>
+template <bool STAGE2, int EX, int WM = 2, int WN = 2, int TM = 8>
 __global__ void __launch_bounds__(256, 2)
 tsvd_gemm_fp6_kernel(gemm_args p) {
     static_assert(WM * WN == 4, "four wavefronts");
-    constexpr int TM = 8, TN = 4, BT = WN * 64;
+    constexpr int TN = 4, BT = WN * 64;
     constexpr int BLK_BYTES = BT / 16 * FP6_REC_BYTES;      // one 128-index block of this workgroup's tokens
     constexpr int PIECES = BLK_BYTES / 1024;                // 38 or 19 pieces of 1 KiB
     static_assert(BLK_BYTES % 1024 == 0, "whole pieces");
@@ -1728,8 +1728,13 @@ bool tsvd_gemm_use_fp6(long long Mp, long long Kp, long long Np, long long B, lo
     // 2.29 -> 2.18 ms, 16384 x 4096 x 8192 at 512 tokens 191 -> 153 us, 8192 x 2048 x 4096 at 1024 tokens
     // 108 -> 93 us, 4096 x 1024 x 2048 at 2048 tokens 64 -> 58 us; 3072 x 768 x 1536 at 4096 tokens 66 -> 67 us
     // and at 512 tokens 17 -> 50 us; 4096 x 1024 x 2048 at 1024 tokens (128 tiles) 39 -> 47 us, 12288 x 3072 x 6144 at
-    // 256 tokens (96 tiles) 78 -> 89 us: long contractions with a 256 x 128 tile for every compute unit
-    return Kp >= 2048 && (Mp / 256) * (Bp / 128) >= cus;
+    // 256 tokens (96 tiles) 78 -> 89 us: long contractions with a 256 x 128 tile for every compute unit.  With
+    // fewer, 256 x 64 tiles (three workgroups per compute unit), same comparison: 16384 x 4096 x 8192 at 256 tokens
+    // (256 tiles of 256 x 64) 113 -> 98 us, 12288 x 3072 x 6144 at 256 (192) 75 -> 64 us, 8192 x 2048 x 4096 at 512 (256)
+    // 65 -> 57 us, 6144 x 1536 x 3072 at 512 (192) 45 -> 40 us, 4096 x 1024 x 2048 at 1024 (256) 39.0 -> 38.4 us;
+    // 8192 x 2048 x 4096 at 256 (128) 45 -> 45 us, 4096 x 1024 x 2048 at 512 (128) 27 -> 29 us: three quarters of the
+    // compute units must get a 256 x 64 tile
+    return Kp >= 2048 && 4 * (Mp / 256) * (Bp / 64) >= 3 * cus;
 }
 
 // The same for stage V (planes of x), only together with the fp6 stage U (the workspace holds both
@@ -1742,39 +1747,44 @@ bool tsvd_gemm_use_fp6_v(long long Mp, long long Kp, long long Np, long long B, 
     const long long Bp = tsvd_round_up(B, 256);
     if (mode == 0 || tsvd_gemm_fp6_bytes(Np, Bp) >= (1ull << 31)) return false;
     if (mode == 1) return true;
-    return Np >= 2048 && (Kp / 256) * (Bp / 128) >= cus;
+    return Np >= 2048 && (Kp / 256) * (Bp / 128) >= cus;    // (with fewer tiles stage V runs on the ring kernel, which has its column maxima fused in)
 }
 
-template <int WM, int WN>
+template <int WM, int WN, int TM>
 hipError_t init_fp6() {
     constexpr int lds = 2 * (WN * 4 * FP6_REC_BYTES) + 512;
     hipError_t e;
-    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 0, WM, WN>), hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 1, WM, WN>), hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 2, WM, WN>), hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<false, 0, WM, WN>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 0, WM, WN, TM>), hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 1, WM, WN, TM>), hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 2, WM, WN, TM>), hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<false, 0, WM, WN, TM>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
 }
 // rows_p: padded rows of the stage's weights; ex: output variant (stage U only)
-template <int WM, int WN>
+template <int WM, int WN, int TM>
 hipError_t launch_fp6(bool stage2, const gemm_args& a, long long rows_p, int Bp, int ex, hipStream_t stream) {
     constexpr int lds = 2 * (WN * 4 * FP6_REC_BYTES) + 512;
-    const dim3 grid(Bp / (WN * 64), (unsigned)(rows_p / (WM * 128))), block(256);
-    if (!stage2) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<false, 0, WM, WN>), grid, block, lds, stream, a);
-    else if (ex == 2) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 2, WM, WN>), grid, block, lds, stream, a);
-    else if (ex == 1) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 1, WM, WN>), grid, block, lds, stream, a);
-    else hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 0, WM, WN>), grid, block, lds, stream, a);
+    if (rows_p % (WM * TM * 16)) return hipErrorInvalidValue;
+    const dim3 grid(Bp / (WN * 64), (unsigned)(rows_p / (WM * TM * 16))), block(256);
+    if (!stage2) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<false, 0, WM, WN, TM>), grid, block, lds, stream, a);
+    else if (ex == 2) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 2, WM, WN, TM>), grid, block, lds, stream, a);
+    else if (ex == 1) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 1, WM, WN, TM>), grid, block, lds, stream, a);
+    else hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 0, WM, WN, TM>), grid, block, lds, stream, a);
     return hipGetLastError();
 }
-// 512 x 64 tiles (4 x 1 wavefronts) when the rows allow: half the traffic of the planes, twice that of the codes
-hipError_t launch_fp6_any(bool stage2, const gemm_args& a, long long rows_p, int Bp, int ex, hipStream_t stream) {
-    if (rows_p % 512 == 0 && env_cfg("TSVD_FP6_TALL", 1) != 0) return launch_fp6<4, 1>(stage2, a, rows_p, Bp, ex, stream);
-    return launch_fp6<2, 2>(stage2, a, rows_p, Bp, ex, stream);
+// 512 x 64 tiles (4 x 1 wavefronts) when the rows allow: half the traffic of the planes, twice that of the codes;
+// 256 x 64 (four row blocks per wavefront) when those would leave compute units without a tile
+hipError_t launch_fp6_any(bool stage2, const gemm_args& a, long long rows_p, int Bp, int ex, long long cus, hipStream_t stream) {
+    const int tall = env_cfg("TSVD_FP6_TALL", -1);       // 0: 256 x 128, 1: 512 x 64, 2: 256 x 64, default by rule
+    if (tall == 2 || (tall < 0 && (rows_p / 256) * (Bp / 128) < cus)) return launch_fp6<4, 1, 4>(stage2, a, rows_p, Bp, ex, stream);
+    if (rows_p % 512 == 0 && tall != 0) return launch_fp6<4, 1, 8>(stage2, a, rows_p, Bp, ex, stream);
+    return launch_fp6<2, 2, 8>(stage2, a, rows_p, Bp, ex, stream);
 }
 
 hipError_t tsvd_gemm_init() {
     hipError_t e;
-    if ((e = init_fp6<2, 2>()) != hipSuccess) return e;
-    if ((e = init_fp6<4, 1>()) != hipSuccess) return e;
+    if ((e = init_fp6<2, 2, 8>()) != hipSuccess) return e;
+    if ((e = init_fp6<4, 1, 8>()) != hipSuccess) return e;
+    if ((e = init_fp6<4, 1, 4>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 4, 8, 4, false>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 4, 8, 4, true>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 2, 8, 4, false>()) != hipSuccess) return e;
@@ -1916,7 +1926,7 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
         gemm_args a4 = a1;
         a4.act = reinterpret_cast<const uint16_t*>(xplanes);
         a4.act_bytes = (unsigned)tsvd_gemm_fp6_bytes(hd.Np, Bp);
-        e = launch_fp6_any(false, a4, hd.Kp, Bp, 0, stream);
+        e = launch_fp6_any(false, a4, hd.Kp, Bp, 0, g.cu_count, stream);
     } else if (mask & 2) e = fuse ? launch_cfg<false, true>(cfg1, a1, fast1, hd.Kp, Bp, stream)
                            : launch_cfg<false, false>(cfg1, a1, fast1, hd.Kp, Bp, stream);
     if (e != hipSuccess) return e;
@@ -1929,7 +1939,7 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
         gemm_args a3 = a2;
         a3.act = reinterpret_cast<const uint16_t*>(planes);
         a3.act_bytes = (unsigned)tsvd_gemm_fp6_bytes(hd.Kp, Bp);
-        return launch_fp6_any(true, a3, hd.Mp, Bp, out_variant(a3.bias, a3.out_bf16, a3.out, a3.ld_out), stream);
+        return launch_fp6_any(true, a3, hd.Mp, Bp, out_variant(a3.bias, a3.out_bf16, a3.out, a3.ld_out), g.cu_count, stream);
     }
     if (mask & 4) e = launch_cfg<true, false>(cfg2, a2, true, hd.Mp, Bp, stream);
     return e;

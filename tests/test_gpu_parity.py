@@ -494,10 +494,11 @@ def test_repeated_calls_are_bit_identical(tsvd):
 
 
 # ---- stage U on fp4 codes x three fp6 planes of Z (experimental switch TSVD_FP6=1)
+@pytest.mark.parametrize("tile", ["0", "1", "2"])        # 256 x 128, 512 x 64 (where 512 divides the padded rows), 256 x 64
 @pytest.mark.parametrize("stage_v", [False, True])
 @pytest.mark.parametrize("M,N,K,B", [(300, 200, 270, 100), (515, 300, 777, 130), (1024, 512, 768, 512), (130, 64, 2100, 257),
                                      (512, 300, 1024, 200)])
-def test_fp6_planes_stage_u(tsvd, M, N, K, B, stage_v, monkeypatch):
+def test_fp6_planes_stage_u(tsvd, M, N, K, B, stage_v, tile, monkeypatch):
     """Z as three E2M3 planes with per-lane block scales, multiplied with the codes as fp4 on the scaled
     128-deep MFMA: exact on integer instances (small integers need one plane), within the tolerance
     of the 16-bit path on random ones and next to identical to it; bias and bf16 output included.
@@ -506,6 +507,7 @@ def test_fp6_planes_stage_u(tsvd, M, N, K, B, stage_v, monkeypatch):
     import torch
     monkeypatch.setenv("TSVD_FP6", "1")
     monkeypatch.setenv("TSVD_FP6_V", "1" if stage_v else "0")
+    monkeypatch.setenv("TSVD_FP6_TALL", tile)
     if stage_v:
         monkeypatch.setenv("TSVD_GEMM_CFG_V", "3")
     i = workloads.make_integer_inputs(M, N, K, B, 0.5, "bf16", seed=606 + B)
