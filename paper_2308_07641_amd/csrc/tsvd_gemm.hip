@@ -783,7 +783,7 @@ __device__ __forceinline__ f32x4 mfma_fp6(const u32x4& a, const u32x4& lo, const
 }
 
 // WM x WN = 2 x 2 wavefronts (256 rows x 128 tokens per workgroup) or 4 x 1 (512 x 64) of TM x 4 = 8 x 4 blocks
-// each, two workgroups per compute unit, or 4 x 1 of 4 x 4 blocks (256 x 64), three; two LDS buffers of one 128-index block each; code words straight from global memory to
+// each, two workgroups per compute unit, or 4 x 1 of 4 x 4 blocks (256 x 64), three, or of 2 x 4 blocks (128 x 64), four; two LDS buffers of one 128-index block each; code words straight from global memory to
 // registers, one block ahead.
 template <bool STAGE2, int EX, int WM = 2, int WN = 2, int TM = 8>
 __global__ void __launch_bounds__(256, 2)
@@ -1732,9 +1732,12 @@ bool tsvd_gemm_use_fp6(long long Mp, long long Kp, long long Np, long long B, lo
     // fewer, 256 x 64 tiles (three workgroups per compute unit), same comparison: 16384 x 4096 x 8192 at 256 tokens
     // (256 tiles of 256 x 64) 113 -> 98 us, 12288 x 3072 x 6144 at 256 (192) 75 -> 64 us, 8192 x 2048 x 4096 at 512 (256)
     // 65 -> 57 us, 6144 x 1536 x 3072 at 512 (192) 45 -> 40 us, 4096 x 1024 x 2048 at 1024 (256) 39.0 -> 38.4 us;
-    // 8192 x 2048 x 4096 at 256 (128) 45 -> 45 us, 4096 x 1024 x 2048 at 512 (128) 27 -> 29 us: three quarters of the
-    // compute units must get a 256 x 64 tile
-    return Kp >= 2048 && 4 * (Mp / 256) * (Bp / 64) >= 3 * cus;
+    // 8192 x 2048 x 4096 at 256 (128) 45 -> 45 us, 4096 x 1024 x 2048 at 512 (128) 27 -> 29 us: those tiles where three
+    // quarters of the compute units get one.  Below that, 128 x 64 tiles (four workgroups per compute unit): the last
+    // two shapes 45 -> 39 us and 27 -> 26 us; 6144 x 1536 x 3072 at 256 tokens (192 tiles of 128 x 64) 28 -> 31 us:
+    // every compute unit must get a 128 x 64 tile.  Contractions of 1024 - 1536 indices: no gain with any tile
+    // (3072 x 768 x 1536 at 512 tokens 17 -> 22 us, at 1024 tokens 28 -> 28.5 us)
+    return Kp >= 2048 && (Mp / 128) * (Bp / 64) >= cus;
 }
 
 // The same for stage V (planes of x), only together with the fp6 stage U (the workspace holds both
@@ -1772,10 +1775,13 @@ hipError_t launch_fp6(bool stage2, const gemm_args& a, long long rows_p, int Bp,
     return hipGetLastError();
 }
 // 512 x 64 tiles (4 x 1 wavefronts) when the rows allow: half the traffic of the planes, twice that of the codes;
-// 256 x 64 (four row blocks per wavefront) when those would leave compute units without a tile
+// 256 x 64 (four row blocks per wavefront) when those would leave compute units without a tile, 128 x 64 (two)
+// when even those would leave more than a quarter of them without
 hipError_t launch_fp6_any(bool stage2, const gemm_args& a, long long rows_p, int Bp, int ex, long long cus, hipStream_t stream) {
-    const int tall = env_cfg("TSVD_FP6_TALL", -1);       // 0: 256 x 128, 1: 512 x 64, 2: 256 x 64, default by rule
-    if (tall == 2 || (tall < 0 && (rows_p / 256) * (Bp / 128) < cus)) return launch_fp6<4, 1, 4>(stage2, a, rows_p, Bp, ex, stream);
+    const int tall = env_cfg("TSVD_FP6_TALL", -1);       // 0: 256 x 128, 1: 512 x 64, 2: 256 x 64, 3: 128 x 64, default by rule
+    const bool small = tall < 0 && (rows_p / 256) * (Bp / 128) < cus;
+    if (tall == 3 || (small && 4 * (rows_p / 256) * (Bp / 64) < 3 * cus)) return launch_fp6<4, 1, 2>(stage2, a, rows_p, Bp, ex, stream);
+    if (tall == 2 || small) return launch_fp6<4, 1, 4>(stage2, a, rows_p, Bp, ex, stream);
     if (rows_p % 512 == 0 && tall != 0) return launch_fp6<4, 1, 8>(stage2, a, rows_p, Bp, ex, stream);
     return launch_fp6<2, 2, 8>(stage2, a, rows_p, Bp, ex, stream);
 }
@@ -1785,6 +1791,7 @@ hipError_t tsvd_gemm_init() {
     if ((e = init_fp6<2, 2, 8>()) != hipSuccess) return e;
     if ((e = init_fp6<4, 1, 8>()) != hipSuccess) return e;
     if ((e = init_fp6<4, 1, 4>()) != hipSuccess) return e;
+    if ((e = init_fp6<4, 1, 2>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 4, 8, 4, false>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 4, 8, 4, true>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 2, 8, 4, false>()) != hipSuccess) return e;

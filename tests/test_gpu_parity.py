@@ -494,7 +494,7 @@ def test_repeated_calls_are_bit_identical(tsvd):
 
 
 # ---- stage U on fp4 codes x three fp6 planes of Z (experimental switch TSVD_FP6=1)
-@pytest.mark.parametrize("tile", ["0", "1", "2"])        # 256 x 128, 512 x 64 (where 512 divides the padded rows), 256 x 64
+@pytest.mark.parametrize("tile", ["0", "1", "2", "3"])   # 256 x 128, 512 x 64 (where 512 divides the padded rows), 256 x 64, 128 x 64
 @pytest.mark.parametrize("stage_v", [False, True])
 @pytest.mark.parametrize("M,N,K,B", [(300, 200, 270, 100), (515, 300, 777, 130), (1024, 512, 768, 512), (130, 64, 2100, 257),
                                      (512, 300, 1024, 200)])
