@@ -570,7 +570,7 @@ extern "C" int tsvd_internal_tile_shapes(const tsvd_handle* h, long long B, int*
             *shape_v = tsvd_gemm_tile_shape(h->hd.Kp, Bp, h->cu_count, true);
             *shape_u = tsvd_gemm_tile_shape(h->hd.Mp, Bp, h->cu_count, true);
             if (tsvd_gemm_use_fp6(h->hd.Mp, h->hd.Kp, h->hd.Np, B, h->cu_count, true)) *shape_u = 40;   // fp4 x fp6 planes
-            if (tsvd_gemm_use_fp6_v(h->hd.Mp, h->hd.Kp, h->hd.Np, B, h->cu_count, true) && *shape_v < 10) *shape_v = 40;
+            if (tsvd_gemm_use_fp6_v(h->hd.Mp, h->hd.Kp, h->hd.Np, B, h->cu_count, true)) *shape_v = 40;
         }
     }
     return 0;

@@ -1750,7 +1750,12 @@ bool tsvd_gemm_use_fp6_v(long long Mp, long long Kp, long long Np, long long B, 
     const long long Bp = tsvd_round_up(B, 256);
     if (mode == 0 || tsvd_gemm_fp6_bytes(Np, Bp) >= (1ull << 31)) return false;
     if (mode == 1) return true;
-    return Np >= 2048 && (Kp / 256) * (Bp / 128) >= cus;    // (with fewer tiles stage V runs on the ring kernel, which has its column maxima fused in)
+    // With a 256 x 128 tile for every compute unit (where stage V would run on the large-tile kernel): measured
+    // 18432 x 9216 at 2048 tokens 480 -> 17 + 406 us.  With fewer tiles stage V would run on the ring kernel, which
+    // has its column maxima fused in; planes, a separate column-maximum launch and 128 x 64 or 256 x 64 tiles beat
+    // it for contractions of 4096 (whole call 97 -> 92 us on 16384 x 4096 x 8192 at 256 tokens, 73 -> 68 us on
+    // 8192 x 4096 x 4096 at 512) but not of 3072 (64 -> 70 us on 12288 x 3072 x 6144 at 256) or 2048 (58 -> 58 us)
+    return (Np >= 2048 && (Kp / 256) * (Bp / 128) >= cus) || (Np >= 4096 && (Kp / 128) * (Bp / 64) >= cus);
 }
 
 template <int WM, int WN, int TM>
@@ -1906,7 +1911,8 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     int cfg1 = env_cfg("TSVD_GEMM_CFG_V", tsvd_gemm_tile_shape(hd.Kp, Bp, g.cu_count, fast1));
     int cfg2 = env_cfg("TSVD_GEMM_CFG_U", tsvd_gemm_tile_shape(hd.Mp, Bp, g.cu_count, true));
     if (is_ring(cfg1) && !fast1) cfg1 = 3;
-    const bool fuse = is_ring(cfg1) && env_cfg("TSVD_FUSEMAX", 1) != 0;
+    const bool fp6_v = tsvd_gemm_use_fp6_v(hd.Mp, hd.Kp, hd.Np, g.B, g.cu_count, fast1);   // stage V on planes of x (needs the column maxima)
+    const bool fuse = is_ring(cfg1) && env_cfg("TSVD_FUSEMAX", 1) != 0 && !fp6_v;
 
     // Profiling switch: TSVD_STAGE_MASK selects the kernels to launch (1 column maxima,
     // 2 stage V, 4 stage U; default all).  Skipped kernels leave the workspace as it is.
@@ -1923,7 +1929,6 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
         if (e != hipSuccess) return e;
     }
     // stage V on fp4 x fp6 as well when its own contraction (N) is long: X -> planes (after Z's planes in the workspace)
-    const bool fp6_v = !fuse && tsvd_gemm_use_fp6_v(hd.Mp, hd.Kp, hd.Np, g.B, g.cu_count, fast1);
     if ((mask & 2) && fp6_v) {
         unsigned char* xplanes = reinterpret_cast<unsigned char*>(Z) + (((size_t)hd.Kp * Bp * 2 + 255) & ~(size_t)255) +
                                  ((tsvd_gemm_fp6_bytes(hd.Kp, Bp) + 255) & ~(size_t)255);
