@@ -260,12 +260,16 @@ bool use_mid(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype, int64_t ldx) {
     if (B <= 16) return true;
     const int forced = env_int("TSVD_MID_MAX_B", 0);       // tuning switch: largest B served here
     if (forced > 0) return B <= forced;
-    // measured break-even against the batched kernels (aligned rows): 2, 3, 4 groups pay off from
-    // about 4, 11 and 20 MB of packed weights; unaligned rows take a slower batched kernel
-    static const double min_bytes[5] = {0.0, 0.0, 4.2e6, 11.2e6, 20.0e6};
+    // Measured break-even against the batched kernels, which launch only the 64-token tiles that hold tokens.
+    // Aligned rows: two groups of 16 pay off between about 4 and 60 MB of packed weights (10.5 MB: 21.5 against
+    // 27 us; 42 MB: 39 against 49 us; 94 MB: 95 against 82 us; 255 MB: 194 against 142 us), three and four
+    // groups never (24 MB at 48 tokens: 65 against 38 us; 42 MB: 61 against 50 us; 255 MB: 299 against 140 us).
+    // Unaligned rows take a slower batched kernel: 2, 3, 4 groups pay off from about 1.7, 4.5 and 8 MB.
     const double code_bytes = (double)h->hd.Kp * (double)(h->hd.Mp + h->hd.Np) / 4.0;
-    const bool aligned = ldx % 8 == 0;
-    return code_bytes >= min_bytes[(B + 15) / 16] * (aligned ? 1.0 : 0.4);
+    const int groups = (int)((B + 15) / 16);
+    if (ldx % 8 == 0) return groups == 2 && code_bytes >= 4.2e6 && code_bytes < 60.0e6;
+    static const double min_bytes[5] = {0.0, 0.0, 4.2e6, 11.2e6, 20.0e6};
+    return code_bytes >= min_bytes[groups] * 0.4;
 }
 
 size_t mid_workspace(const tsvd_handle* h) {
@@ -563,12 +567,11 @@ extern "C" int tsvd_internal_tile_shapes(const tsvd_handle* h, long long B, int*
     *shape_v = *shape_u = -1;
     if (use_mid(h, B, TSVD_BF16, tsvd_round_up(B, 8))) return 0;
     if (use_gemm(h, B, TSVD_BF16)) {
-        const long long Bp = (long long)tsvd_round_up(B, 256);
         if (tsvd_gemm_use_panel(h->hd.Mp, h->hd.Kp, h->hd.Np, B, h->cu_count, true)) {
             *shape_v = *shape_u = 32;                 // one token-panel launch
         } else {
-            *shape_v = tsvd_gemm_tile_shape(h->hd.Kp, Bp, h->cu_count, true);
-            *shape_u = tsvd_gemm_tile_shape(h->hd.Mp, Bp, h->cu_count, true);
+            *shape_v = tsvd_gemm_tile_shape(h->hd.Kp, B, h->cu_count, true);
+            *shape_u = tsvd_gemm_tile_shape(h->hd.Mp, B, h->cu_count, true);
             if (tsvd_gemm_use_fp6(h->hd.Mp, h->hd.Kp, h->hd.Np, B, h->cu_count, true)) *shape_u = 40;   // fp4 x fp6 planes
             if (tsvd_gemm_use_fp6_v(h->hd.Mp, h->hd.Kp, h->hd.Np, B, h->cu_count, true)) *shape_v = 40;
         }

@@ -1558,7 +1558,8 @@ template <int WM, int WN, int TM, int TN, bool STAGE2>
 hipError_t launch_gemm(const gemm_args& a, bool fast, long long rows, int Bp, hipStream_t stream) {
     constexpr int BT = WN * TN * 16, MT = WM * TM * 16;
     constexpr size_t lds = 2 * KT * BT * 2, cs = BT * 4;      // two stages; the column factors
-    const dim3 grid(Bp / BT, (unsigned)(rows / MT)), block(64 * WM * WN);
+    // (token tiles that lie wholly beyond the last token are not launched: nothing reads what they would write)
+    const dim3 grid((a.bvalid + BT - 1) / BT, (unsigned)(rows / MT)), block(64 * WM * WN);
     if constexpr (STAGE2) {
         const int ex = out_variant(a.bias, a.out_bf16, a.out, a.ld_out);    // the epilogues with bias / bf16 output
         if (ex == 2) {
@@ -1611,7 +1612,7 @@ hipError_t launch_ring(const gemm_args& a, long long rows, int Bp, hipStream_t s
     constexpr int BT = WN * TN * 16, MT = WM * TM * 16;
     constexpr size_t lds = ring_lds_bytes<WM, WN, TM, TN, NPB, KG>();
     if (rows % MT) return hipErrorInvalidValue;      // (96-row tiles: the rule asks for them only when they divide the rows)
-    const dim3 grid(Bp / BT, (unsigned)(rows / MT)), block(64 * WM * WN * KG);
+    const dim3 grid((a.bvalid + BT - 1) / BT, (unsigned)(rows / MT)), block(64 * WM * WN * KG);
     if constexpr (STAGE2) {
         const int ex = out_variant(a.bias, a.out_bf16, a.out, a.ld_out);
         if (ex == 2) hipLaunchKernelGGL((tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false, KG, 2>), grid, block, lds, stream, a);
@@ -1687,18 +1688,20 @@ int tsvd_stage_mask() {
 // workgroups than about 1.5 per compute unit even at 256 x 128): the ring kernel, 128 x 64 tiles
 // if they still give every compute unit a workgroup, else 64 x 64 with the contraction split
 // over two groups of wavefronts; it needs 16-byte-aligned rows.
-int tsvd_gemm_tile_shape(long long rows, long long Bp, long long cus, bool aligned) {
-    const long long t0 = (rows / 256) * (Bp / 256), t1 = (rows / 256) * (Bp / 128), t2 = (rows / 128) * (Bp / 128);
+int tsvd_gemm_tile_shape(long long rows, long long B, long long cus, bool aligned) {
+    // token tiles of 256, 128 and 64 that hold at least one token (the others are not launched)
+    const long long c256 = (B + 255) / 256, c128 = (B + 127) / 128, c64 = (B + 63) / 64;
+    const long long t0 = (rows / 256) * c256, t1 = (rows / 256) * c128, t2 = (rows / 128) * c128;
     if (2 * t1 >= 3 * cus) {
         const double c0 = (double)((t0 + cus - 1) / cus) / 0.97, c1 = 0.5 * (double)((t1 + cus - 1) / cus);
         return c0 < c1 ? 0 : 1;
     }
     if (!aligned) return t2 >= cus ? 2 : 3;
-    if ((rows / 128) * (Bp / 64) >= cus) return 15;
+    if ((rows / 128) * c64 >= cus) return 15;
     // 96 x 64 tiles when they give (nearly) every compute unit exactly one workgroup where 64 x 64
     // tiles would give half of them two
-    const long long t96 = (rows / 96) * (Bp / 64);
-    if (rows % 96 == 0 && t96 <= cus && 4 * t96 > 3 * cus && (rows / 64) * (Bp / 64) > cus) return 17;
+    const long long t96 = (rows / 96) * c64;
+    if (rows % 96 == 0 && t96 <= cus && 4 * t96 > 3 * cus && (rows / 64) * c64 > cus) return 17;
     return 16;
 }
 
@@ -1737,7 +1740,7 @@ bool tsvd_gemm_use_fp6(long long Mp, long long Kp, long long Np, long long B, lo
     // two shapes 45 -> 39 us and 27 -> 26 us; 6144 x 1536 x 3072 at 256 tokens (192 tiles of 128 x 64) 28 -> 31 us:
     // every compute unit must get a 128 x 64 tile.  Contractions of 1024 - 1536 indices: no gain with any tile
     // (3072 x 768 x 1536 at 512 tokens 17 -> 22 us, at 1024 tokens 28 -> 28.5 us)
-    return Kp >= 2048 && (Mp / 128) * (Bp / 64) >= cus;
+    return Kp >= 2048 && (Mp / 128) * ((B + 63) / 64) >= cus;
 }
 
 // The same for stage V (planes of x), only together with the fp6 stage U (the workspace holds both
@@ -1755,7 +1758,7 @@ bool tsvd_gemm_use_fp6_v(long long Mp, long long Kp, long long Np, long long B, 
     // has its column maxima fused in; planes, a separate column-maximum launch and 128 x 64 or 256 x 64 tiles beat
     // it for contractions of 4096 (whole call 97 -> 92 us on 16384 x 4096 x 8192 at 256 tokens, 73 -> 68 us on
     // 8192 x 4096 x 4096 at 512) but not of 3072 (64 -> 70 us on 12288 x 3072 x 6144 at 256) or 2048 (58 -> 58 us)
-    return (Np >= 2048 && (Kp / 256) * (Bp / 128) >= cus) || (Np >= 4096 && (Kp / 128) * (Bp / 64) >= cus);
+    return (Np >= 2048 && (Kp / 256) * ((B + 127) / 128) >= cus) || (Np >= 4096 && (Kp / 128) * ((B + 63) / 64) >= cus);
 }
 
 template <int WM, int WN, int TM>
@@ -1772,7 +1775,7 @@ template <int WM, int WN, int TM>
 hipError_t launch_fp6(bool stage2, const gemm_args& a, long long rows_p, int Bp, int ex, hipStream_t stream) {
     constexpr int lds = 2 * (WN * 4 * FP6_REC_BYTES) + 512;
     if (rows_p % (WM * TM * 16)) return hipErrorInvalidValue;
-    const dim3 grid(Bp / (WN * 64), (unsigned)(rows_p / (WM * TM * 16))), block(256);
+    const dim3 grid((a.bvalid + WN * 64 - 1) / (WN * 64), (unsigned)(rows_p / (WM * TM * 16))), block(256);
     if (!stage2) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<false, 0, WM, WN, TM>), grid, block, lds, stream, a);
     else if (ex == 2) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 2, WM, WN, TM>), grid, block, lds, stream, a);
     else if (ex == 1) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 1, WM, WN, TM>), grid, block, lds, stream, a);
@@ -1784,8 +1787,9 @@ hipError_t launch_fp6(bool stage2, const gemm_args& a, long long rows_p, int Bp,
 // when even those would leave more than a quarter of them without
 hipError_t launch_fp6_any(bool stage2, const gemm_args& a, long long rows_p, int Bp, int ex, long long cus, hipStream_t stream) {
     const int tall = env_cfg("TSVD_FP6_TALL", -1);       // 0: 256 x 128, 1: 512 x 64, 2: 256 x 64, 3: 128 x 64, default by rule
-    const bool small = tall < 0 && (rows_p / 256) * (Bp / 128) < cus;
-    if (tall == 3 || (small && 4 * (rows_p / 256) * (Bp / 64) < 3 * cus)) return launch_fp6<4, 1, 2>(stage2, a, rows_p, Bp, ex, stream);
+    const long long c128 = (a.bvalid + 127) / 128, c64 = (a.bvalid + 63) / 64;   // token tiles that are launched
+    const bool small = tall < 0 && (rows_p / 256) * c128 < cus;
+    if (tall == 3 || (small && 4 * (rows_p / 256) * c64 < 3 * cus)) return launch_fp6<4, 1, 2>(stage2, a, rows_p, Bp, ex, stream);
     if (tall == 2 || small) return launch_fp6<4, 1, 4>(stage2, a, rows_p, Bp, ex, stream);
     if (rows_p % 512 == 0 && tall != 0) return launch_fp6<4, 1, 8>(stage2, a, rows_p, Bp, ex, stream);
     return launch_fp6<2, 2, 8>(stage2, a, rows_p, Bp, ex, stream);
@@ -1908,8 +1912,8 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
         }
         return hipGetLastError();
     }
-    int cfg1 = env_cfg("TSVD_GEMM_CFG_V", tsvd_gemm_tile_shape(hd.Kp, Bp, g.cu_count, fast1));
-    int cfg2 = env_cfg("TSVD_GEMM_CFG_U", tsvd_gemm_tile_shape(hd.Mp, Bp, g.cu_count, true));
+    int cfg1 = env_cfg("TSVD_GEMM_CFG_V", tsvd_gemm_tile_shape(hd.Kp, g.B, g.cu_count, fast1));
+    int cfg2 = env_cfg("TSVD_GEMM_CFG_U", tsvd_gemm_tile_shape(hd.Mp, g.B, g.cu_count, true));
     if (is_ring(cfg1) && !fast1) cfg1 = 3;
     const bool fp6_v = tsvd_gemm_use_fp6_v(hd.Mp, hd.Kp, hd.Np, g.B, g.cu_count, fast1);   // stage V on planes of x (needs the column maxima)
     const bool fuse = is_ring(cfg1) && env_cfg("TSVD_FUSEMAX", 1) != 0 && !fp6_v;
@@ -1932,7 +1936,7 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     if ((mask & 2) && fp6_v) {
         unsigned char* xplanes = reinterpret_cast<unsigned char*>(Z) + (((size_t)hd.Kp * Bp * 2 + 255) & ~(size_t)255) +
                                  ((tsvd_gemm_fp6_bytes(hd.Kp, Bp) + 255) & ~(size_t)255);
-        hipLaunchKernelGGL(tsvd_z_planes_kernel<true>, dim3(Bp / 128, (unsigned)(hd.Np / 128)), dim3(512), 0, stream,
+        hipLaunchKernelGGL(tsvd_z_planes_kernel<true>, dim3((unsigned)((g.B + 127) / 128), (unsigned)(hd.Np / 128)), dim3(512), 0, stream,
                            static_cast<const uint16_t*>(g.x), (long long)g.ldx, (int)hd.N, (int)g.B, (int)(hd.Np / 128), xplanes);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         gemm_args a4 = a1;
@@ -1945,7 +1949,7 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     if ((mask & 4) && tsvd_gemm_use_fp6(hd.Mp, hd.Kp, hd.Np, g.B, g.cu_count, fast1)) {
         // Z (fp16) -> three fp6 planes in operand order, then stage U on fp4 x fp6
         unsigned char* planes = reinterpret_cast<unsigned char*>(Z) + (((size_t)hd.Kp * Bp * 2 + 255) & ~(size_t)255);
-        hipLaunchKernelGGL(tsvd_z_planes_kernel<false>, dim3(Bp / 128, (unsigned)(hd.Kp / 128)), dim3(512), 0, stream,
+        hipLaunchKernelGGL(tsvd_z_planes_kernel<false>, dim3((unsigned)((g.B + 127) / 128), (unsigned)(hd.Kp / 128)), dim3(512), 0, stream,
                            reinterpret_cast<const uint16_t*>(Z), (long long)Bp, (int)hd.Kp, Bp, (int)(hd.Kp / 128), planes);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         gemm_args a3 = a2;

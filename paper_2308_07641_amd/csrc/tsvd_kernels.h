@@ -118,7 +118,7 @@ hipError_t tsvd_gemm_init();
 hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream);
 // Tile shape of a batched stage (rows = padded output rows of the stage, Bp = padded tokens):
 // 0..3 large-tile kernel (256x256, 256x128, 128x128, 64x128), 14..16 ring kernel.
-int tsvd_gemm_tile_shape(long long rows, long long Bp, long long cus, bool aligned);
+int tsvd_gemm_tile_shape(long long rows, long long B, long long cus, bool aligned);
 // True when a batched call runs as ONE token-panel launch (both stages, z kept in LDS).
 bool tsvd_gemm_use_panel(long long Mp, long long Kp, long long Np, long long B, long long cus, bool aligned);
 // Stage U through fp6 planes of Z: whether a call takes it, and the extra workspace it needs after Z.
