@@ -88,7 +88,10 @@ tsvd_status tsvd_info(const tsvd_handle* h, int64_t* M, int64_t* K, int64_t* N,
  * Y = U (diag(S) (V X)) for B tokens (columns), following the three steps of the paper's
  * identity: t = V x (additions), z = S * t (the K multiplications), y = U z (additions).
  *
- *   x_dev : device, [N][B] row-major with row stride ldx >= B elements of x_dtype.
+ *   x_dev : device, [N][B] row-major with row stride ldx >= B elements of x_dtype.  Any stride and
+ *           alignment is accepted; bf16 rows that start on 16-byte boundaries (ldx a multiple of 8, base
+ *           16-byte aligned) are read in place, others are first copied to such rows inside the
+ *           workspace when B > 16 (one extra pass over x).
  *   y_dev : device, [M][B] row-major with row stride ldy >= B elements of y_dtype (TSVD_F32, or
  *           TSVD_BF16: the fp32 result rounded to nearest even).
  *   workspace : device scratch for the intermediate z, at least

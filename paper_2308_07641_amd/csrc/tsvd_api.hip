@@ -60,6 +60,15 @@ tsvd_transpose_kernel(const T* __restrict__ x, long long ldx, int B, int N, T* _
     }
 }
 
+// Feature-major activations with unaligned rows [N][ldx] -> [N][ldt] (ldt a multiple of 8 elements, the padding
+// columns zero): one thread per element, consecutive threads along a row.
+__global__ void __launch_bounds__(256)
+tsvd_realign_kernel(const uint16_t* __restrict__ x, long long ldx, int B, uint16_t* __restrict__ xt, long long ldt) {
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    const size_t n = blockIdx.y;
+    if (b < ldt) xt[n * ldt + b] = b < B ? x[n * ldx + b] : (uint16_t)0;
+}
+
 // One-time, per-device kernel attribute setup.
 hipError_t device_init(int device) {
     static bool done[64] = {};
@@ -471,7 +480,10 @@ size_t transposed_bytes(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype) {
 extern "C" size_t tsvd_workspace_bytes_ex(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype, tsvd_layout x_layout) {
     if (!h || B <= 0 || (x_dtype != TSVD_F32 && x_dtype != TSVD_BF16)) return 0;
     if (x_layout != TSVD_FEATURE_MAJOR && x_layout != TSVD_TOKEN_MAJOR) return 0;
-    return base_workspace(h, B, x_dtype) + (x_layout == TSVD_TOKEN_MAJOR ? transposed_bytes(h, B, x_dtype) : 0);
+    // (feature-major rows that are not 16-byte aligned are copied too, when the call goes to the batched kernels:
+    // the alignment is not known here, so the room is always there)
+    const bool copy = x_layout == TSVD_TOKEN_MAJOR || use_gemm(h, B, x_dtype);
+    return base_workspace(h, B, x_dtype) + (copy ? transposed_bytes(h, B, x_dtype) : 0);
 }
 
 extern "C" size_t tsvd_workspace_bytes(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype) {
@@ -525,6 +537,18 @@ extern "C" tsvd_status tsvd_forward_ex(const tsvd_handle* h, const void* x_dev, 
         else
             hipLaunchKernelGGL(tsvd_transpose_kernel<uint32_t>, grid, dim3(256), 0, s, static_cast<const uint32_t*>(x_dev), ldx,
                                (int)B, (int)h->hd.N, static_cast<uint32_t*>(ws), ldt);
+        if (hipGetLastError() != hipSuccess) return TSVD_EDEVICE;
+        x_dev = ws;
+        ldx = ldt;
+        ws = static_cast<uint8_t*>(ws) + transposed_bytes(h, B, x_dtype);
+    } else if (use_gemm(h, B, x_dtype) && (ldx % 8 != 0 || (reinterpret_cast<uintptr_t>(x_dev) & 15u)) && env_int("TSVD_REALIGN", 1) != 0 &&
+             h->hd.N <= 65535) {
+        // more than 16 tokens in rows that are not 16-byte aligned: one pass that copies them to aligned rows costs
+        // less than the element-wise gathers of the kernels that take such rows (stage V of a 4096 x 8192
+        // factor at 300 tokens: 251 us gathered, 3 + 35 us copied); TSVD_REALIGN=0 keeps the gathers
+        const int64_t ldt = tsvd_round_up(B, 8);
+        hipLaunchKernelGGL(tsvd_realign_kernel, dim3((unsigned)((ldt + 255) / 256), (unsigned)h->hd.N), dim3(256), 0, s,
+                           static_cast<const uint16_t*>(x_dev), (long long)ldx, (int)B, static_cast<uint16_t*>(ws), (long long)ldt);
         if (hipGetLastError() != hipSuccess) return TSVD_EDEVICE;
         x_dev = ws;
         ldx = ldt;

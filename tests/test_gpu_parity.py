@@ -94,6 +94,24 @@ def test_every_tile_shape_batched(tsvd, cfg, fuse, monkeypatch):
     assert rel_err(y, ref) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3])
+def test_unaligned_rows_gather_kernels(tsvd, cfg, monkeypatch):
+    """Rows of x that are not 16-byte aligned are copied to aligned rows before the batched kernels;
+    with that copy switched off the large-tile kernels gather them element by element."""
+    monkeypatch.setenv("TSVD_REALIGN", "0")
+    monkeypatch.setenv("TSVD_GEMM_CFG_V", str(cfg))
+    monkeypatch.setenv("TSVD_GEMM_CFG_U", str(cfg))
+    print(f"case gather tile shape {cfg}", flush=True)
+    i = workloads.make_integer_inputs(300, 200, 520, 301, 0.5, "bf16", seed=4343 + cfg)
+    y, h = run_forward(i)
+    tsvd.tsvd_free(h)
+    assert np.array_equal(y, oracle.forward(i.U, i.S, i.V, i.X))
+    j = workloads.make_inputs(515, 300, 777, 603, 0.6, 0.02, "bf16", seed=787 + cfg)
+    y, h = run_forward(j)
+    tsvd.tsvd_free(h)
+    assert rel_err(y, oracle.forward(j.U, j.S, j.V, j.X)) <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("fuse", ["1", "0"])
 def test_tile_shape_of_96_rows(tsvd, fuse, monkeypatch):
     """The 96 x 64 ring tiles need padded row counts that 96 divides (the shape rule asks for them
@@ -350,7 +368,8 @@ LAYER_CASES = [
     (300, 513, 270, 1, {}),                                   # single-token kernels, two launches
     (300, 513, 270, 2, {"TSVD_GEMV": "0", "TSVD_MID": "0"}),  # general slab kernel, two tokens per pass
     (100, 2300, 4500, 13, {}),                                # few-token kernel
-    (130, 64, 520, 257, {}),                                  # ring kernels (unaligned rows: large-tile fallback)
+    (130, 64, 520, 257, {}),                                  # unaligned rows: copied to aligned rows, ring kernels
+    (130, 64, 520, 257, {"TSVD_REALIGN": "0"}),               # unaligned rows gathered: large-tile fallback
     (130, 64, 520, 264, {}),                                  # ring kernels (aligned rows)
     (300, 200, 270, 72, {"TSVD_MID": "0", "TSVD_GEMM_CFG_U": "0", "TSVD_GEMM_CFG_V": "1"}),   # pipelined large tiles
     (300, 200, 270, 72, {"TSVD_MID": "0", "TSVD_GEMM_CFG_U": "2", "TSVD_GEMM_CFG_V": "3"}),
