@@ -336,7 +336,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus above 1 is not supported "
-              "(the path would shard over tokens or rank slices, see DESIGN.md)", file=sys.stderr)
+              "(the path would shard over tokens or over rank slices with one all-reduce of y)", file=sys.stderr)
         sys.exit(2)
 
     import torch
