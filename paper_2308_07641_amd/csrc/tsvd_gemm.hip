@@ -785,7 +785,9 @@ __device__ __forceinline__ f32x4 mfma_fp6(const u32x4& a, const u32x4& lo, const
 // WM x WN = 2 x 2 wavefronts (256 rows x 128 tokens per workgroup) or 4 x 1 (512 x 64) of TM x 4 = 8 x 4 blocks
 // each, two workgroups per compute unit, or 4 x 1 of 4 x 4 blocks (256 x 64), three, or of 2 x 4 blocks (128 x 64), four; two LDS buffers of one 128-index block each; code words straight from global memory to
 // registers, one block ahead.
-template <bool STAGE2, int EX, int WM = 2, int WN = 2, int TM = 8>
+// NPL: planes multiplied, 3 or (switch TSVD_FP6_PLANES=2, never by default) the first two: two thirds of the MFMAs
+// for activations exact to 2^-9.8 instead of 2^-14.7 of a block's largest magnitude.
+template <bool STAGE2, int EX, int WM = 2, int WN = 2, int TM = 8, int NPL = 3>
 __global__ void __launch_bounds__(256, 2)
 tsvd_gemm_fp6_kernel(gemm_args p) {
     static_assert(WM * WN == 4, "four wavefronts");
@@ -835,7 +837,7 @@ tsvd_gemm_fp6_kernel(gemm_args p) {
 #pragma unroll
         for (int a = 0; a < TM; ++a)
             av[a] = u32x4{(w[a].x << 2) & 0xCCCCCCCCu, w[a].x & 0xCCCCCCCCu, (w[a].y << 2) & 0xCCCCCCCCu, w[a].y & 0xCCCCCCCCu};
-        // 12 steps (token tile b = s / 3, plane s % 3) of eight MFMAs each; the operands of step s + DEPTH
+        // NPL x 4 steps (token tile b = s / NPL, plane s % NPL) of TM MFMAs each; the operands of step s + DEPTH
         // are read from LDS before the MFMAs of step s are issued (the scheduler is held to this order:
         // left to itself it reads every operand right before its use and the wavefront waits for LDS
         // ten times per block)
@@ -844,23 +846,23 @@ tsvd_gemm_fp6_kernel(gemm_args p) {
         u32x2 hi[NSET];
         uint32_t sc[2];
         auto read_step = [&](int st) {
-            const unsigned char* rec = smem + buf * BLK_BYTES + (wn * TN + st / 3) * FP6_REC_BYTES;
-            const int pl = st % 3;
+            const unsigned char* rec = smem + buf * BLK_BYTES + (wn * TN + st / NPL) * FP6_REC_BYTES;
+            const int pl = st % NPL;
             lo[st % NSET] = *reinterpret_cast<const u32x4*>(rec + pl * 1024 + lane * 16);
             hi[st % NSET] = *reinterpret_cast<const u32x2*>(rec + 3072 + pl * 512 + lane * 8);
-            if (pl == 0) sc[(st / 3) & 1] = *reinterpret_cast<const uint32_t*>(rec + 4608 + lane * 4);
+            if (pl == 0) sc[(st / NPL) & 1] = *reinterpret_cast<const uint32_t*>(rec + 4608 + lane * 4);
         };
 #pragma unroll
         for (int st = 0; st < DEPTH; ++st) read_step(st);
 #pragma unroll
-        for (int st = 0; st < 3 * TN; ++st) {
-            if (st + DEPTH < 3 * TN) read_step(st + DEPTH);
+        for (int st = 0; st < NPL * TN; ++st) {
+            if (st + DEPTH < NPL * TN) read_step(st + DEPTH);
             __builtin_amdgcn_sched_barrier(0);
-            const int b = st / 3, q = st % NSET;
+            const int b = st / NPL, q = st % NSET;
             // the eight row blocks of one plane: consecutive MFMAs never wait for each other's result
 #pragma unroll
             for (int a = 0; a < TM; ++a) {
-                switch (st % 3) {
+                switch (st % NPL) {
                     case 0: acc[a][b] = mfma_fp6<0>(av[a], lo[q], hi[q], sc[b & 1], acc[a][b]); break;
                     case 1: acc[a][b] = mfma_fp6<1>(av[a], lo[q], hi[q], sc[b & 1], acc[a][b]); break;
                     default: acc[a][b] = mfma_fp6<2>(av[a], lo[q], hi[q], sc[b & 1], acc[a][b]); break;
@@ -1761,25 +1763,25 @@ bool tsvd_gemm_use_fp6_v(long long Mp, long long Kp, long long Np, long long B, 
     return (Np >= 2048 && (Kp / 256) * ((B + 127) / 128) >= cus) || (Np >= 4096 && (Kp / 128) * ((B + 63) / 64) >= cus);
 }
 
-template <int WM, int WN, int TM>
+template <int WM, int WN, int TM, int NPL = 3>
 hipError_t init_fp6() {
     constexpr int lds = 2 * (WN * 4 * FP6_REC_BYTES) + 512;
     hipError_t e;
-    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 0, WM, WN, TM>), hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 1, WM, WN, TM>), hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 2, WM, WN, TM>), hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<false, 0, WM, WN, TM>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 0, WM, WN, TM, NPL>), hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 1, WM, WN, TM, NPL>), hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 2, WM, WN, TM, NPL>), hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<false, 0, WM, WN, TM, NPL>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
 }
 // rows_p: padded rows of the stage's weights; ex: output variant (stage U only)
-template <int WM, int WN, int TM>
+template <int WM, int WN, int TM, int NPL = 3>
 hipError_t launch_fp6(bool stage2, const gemm_args& a, long long rows_p, int Bp, int ex, hipStream_t stream) {
     constexpr int lds = 2 * (WN * 4 * FP6_REC_BYTES) + 512;
     if (rows_p % (WM * TM * 16)) return hipErrorInvalidValue;
     const dim3 grid((a.bvalid + WN * 64 - 1) / (WN * 64), (unsigned)(rows_p / (WM * TM * 16))), block(256);
-    if (!stage2) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<false, 0, WM, WN, TM>), grid, block, lds, stream, a);
-    else if (ex == 2) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 2, WM, WN, TM>), grid, block, lds, stream, a);
-    else if (ex == 1) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 1, WM, WN, TM>), grid, block, lds, stream, a);
-    else hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 0, WM, WN, TM>), grid, block, lds, stream, a);
+    if (!stage2) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<false, 0, WM, WN, TM, NPL>), grid, block, lds, stream, a);
+    else if (ex == 2) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 2, WM, WN, TM, NPL>), grid, block, lds, stream, a);
+    else if (ex == 1) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 1, WM, WN, TM, NPL>), grid, block, lds, stream, a);
+    else hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 0, WM, WN, TM, NPL>), grid, block, lds, stream, a);
     return hipGetLastError();
 }
 // 512 x 64 tiles (4 x 1 wavefronts) when the rows allow: half the traffic of the planes, twice that of the codes;
@@ -1787,6 +1789,10 @@ hipError_t launch_fp6(bool stage2, const gemm_args& a, long long rows_p, int Bp,
 // when even those would leave more than a quarter of them without
 hipError_t launch_fp6_any(bool stage2, const gemm_args& a, long long rows_p, int Bp, int ex, long long cus, hipStream_t stream) {
     const int tall = env_cfg("TSVD_FP6_TALL", -1);       // 0: 256 x 128, 1: 512 x 64, 2: 256 x 64, 3: 128 x 64, default by rule
+    if (env_cfg("TSVD_FP6_PLANES", 3) == 2) {            // accuracy / speed switch (512 x 64 and 256 x 64 tiles only)
+        if (rows_p % 512 == 0 && (rows_p / 256) * ((a.bvalid + 127) / 128) >= cus) return launch_fp6<4, 1, 8, 2>(stage2, a, rows_p, Bp, ex, stream);
+        return launch_fp6<4, 1, 4, 2>(stage2, a, rows_p, Bp, ex, stream);
+    }
     const long long c128 = (a.bvalid + 127) / 128, c64 = (a.bvalid + 63) / 64;   // token tiles that are launched
     const bool small = tall < 0 && (rows_p / 256) * c128 < cus;
     if (tall == 3 || (small && 4 * (rows_p / 256) * c64 < 3 * cus)) return launch_fp6<4, 1, 2>(stage2, a, rows_p, Bp, ex, stream);
@@ -1801,6 +1807,8 @@ hipError_t tsvd_gemm_init() {
     if ((e = init_fp6<4, 1, 8>()) != hipSuccess) return e;
     if ((e = init_fp6<4, 1, 4>()) != hipSuccess) return e;
     if ((e = init_fp6<4, 1, 2>()) != hipSuccess) return e;
+    if ((e = init_fp6<4, 1, 8, 2>()) != hipSuccess) return e;
+    if ((e = init_fp6<4, 1, 4, 2>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 4, 8, 4, false>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 4, 8, 4, true>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 2, 8, 4, false>()) != hipSuccess) return e;

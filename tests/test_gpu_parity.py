@@ -568,3 +568,20 @@ def test_outlier_features(tsvd, mode, monkeypatch):
     assert rel_err(y, ref) <= 0.5 * TOL["bf16"]
     rows = np.max(np.abs(y - ref), axis=1) / np.max(np.abs(ref), axis=1)
     assert np.median(rows) <= 0.5 * TOL["bf16"]
+
+
+@pytest.mark.parametrize("M,N,K,B", [(1024, 512, 768, 512), (512, 300, 1024, 200), (700, 2100, 2300, 130)])
+def test_fp6_two_planes_switch(tsvd, M, N, K, B, monkeypatch):
+    """The accuracy / speed switch of the fp4 x fp6 kernels (two planes instead of three, never chosen by
+    default): still within the tolerance of bf16 activations, at about five times the error."""
+    monkeypatch.setenv("TSVD_FP6", "1")
+    monkeypatch.setenv("TSVD_FP6_V", "1")
+    monkeypatch.setenv("TSVD_GEMM_CFG_V", "3")
+    monkeypatch.setenv("TSVD_FP6_PLANES", "2")
+    j = workloads.make_inputs(M, N, K, B, 0.6, 0.02, "bf16", seed=909 + B)
+    print(f"case fp6 two planes M={M} N={N} K={K} B={B}", flush=True)
+    ref = oracle.forward(j.U, j.S, j.V, j.X)
+    y, h = run_forward(j)
+    tsvd.tsvd_free(h)
+    assert not np.isnan(y).any()
+    assert rel_err(y, ref) <= TOL["bf16"]
