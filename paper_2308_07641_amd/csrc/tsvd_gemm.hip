@@ -687,7 +687,8 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
 // with no operand read ahead (1.53 ms) moved little: neither the L2 nor LDS latency bounds it.
 // Tried and dropped: a ring of three blocks with every load under explicit wait counts in a
 // 256 x 128 tile of eight wavefronts (1.78 - 1.83 ms, a barrier for every 0.35 us of MFMAs per
-// wavefront); a 512 x 128 tile with 256 indices per barrier (register spills, 2.0 ms).
+// wavefront); a 512 x 128 tile with 256 indices per barrier (register spills, 2.0 ms); a raised wavefront
+// priority (s_setprio 1 or 2) during the MFMA steps of a block (1.51 against 1.49 - 1.50 ms).
 //
 // Record of one (16-token tile, 128-index block): planes' first 16 bytes per lane [3][64][16], last
 // 8 bytes per lane [3][64][8], scale words [64][4] = 4864 bytes; lane (i, g) holds, for token i of
