@@ -325,7 +325,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workloads",
-                    default="bert_ffn_in,tiny,convnext_mlp,opt6b7_fc1_decode,opt6b7_fc1_decode_b16,opt66b_fc1_prefill")
+                    default="bert_ffn_in,tiny,convnext_mlp,opt6b7_fc1_decode,opt6b7_fc1_decode_b16,opt6b7_fc1_prefill_b256,opt66b_fc1_prefill")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing / parity leg")
     ap.add_argument("--no-transition", action="store_true", help="skip the transition (Algorithm 2) measurement")
     ap.add_argument("--conv-only", action="store_true", help="run only the convolution-form measurement (for profiling)")

@@ -27,6 +27,7 @@ def _columns(B, count, seed):
     ("opt6b7_fc1_decode", None, 2e-3),
     ("opt66b_fc1_prefill", 24, 2e-3),
     ("opt6b7_fc1_decode_b16", None, 2e-3),
+    ("opt6b7_fc1_prefill_b256", 64, 2e-3),
 ])
 def test_named_workload(name, ncols, tol):
     import paper_2308_07641_amd as tsvd

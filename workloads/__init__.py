@@ -45,6 +45,8 @@ WORKLOADS = {
         Workload("opt66b_fc1_prefill", 5, 36864, 9216, 18432, 2048, 0.6, 0.01, "bf16"),
         # the decode layer with a small batch of tokens (measurement case of the few-token path)
         Workload("opt6b7_fc1_decode_b16", 6, 16384, 4096, 8192, 16, 0.6, 0.01, "bf16"),
+        # the same layer on a prefill chunk of 256 tokens (measurement case of the small tiles of the batched path)
+        Workload("opt6b7_fc1_prefill_b256", 7, 16384, 4096, 8192, 256, 0.6, 0.01, "bf16"),
     )
 }
 
