@@ -31,7 +31,8 @@ typedef enum {
     TSVD_EVALUE = 2,       /* an entry of U or V is not -1, 0 or +1 (or a packed code is corrupt)  */
     TSVD_ENOMEM = 3,       /* host allocation failed                                               */
     TSVD_EDEVICE = 4,      /* a HIP call failed (no device, out of device memory, launch error)    */
-    TSVD_EUNSUPPORTED = 5  /* valid request this build does not implement                          */
+    TSVD_EUNSUPPORTED = 5, /* valid request this build does not implement                          */
+    TSVD_ETOOLARGE = 6     /* tsvd_forward_noalloc: the call needs more than TSVD_NOALLOC_MAX_WORKSPACE */
 } tsvd_status;
 
 typedef enum { TSVD_F32 = 0, TSVD_BF16 = 1 } tsvd_dtype;
@@ -135,6 +136,28 @@ size_t tsvd_workspace_bytes_ex(const tsvd_handle* h, int64_t B, tsvd_dtype x_dty
 tsvd_status tsvd_forward_ex(const tsvd_handle* h, const void* x_dev, tsvd_dtype x_dtype, tsvd_layout x_layout,
                             int64_t B, int64_t ldx, const float* bias_dev, void* y_dev, tsvd_dtype y_dtype,
                             int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- forward for callers that cannot allocate -------------------------------------------
+ *
+ * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc:
+ * tsvd_forward_ex with the intermediate z (and the re-laid-out copy of x, where one is made) in a
+ * fixed array of TSVD_NOALLOC_MAX_WORKSPACE bytes that the loaded library holds on every GPU it has
+ * been used on, until the process ends.  The call allocates and frees nothing, on the host or on the
+ * device, and takes no workspace argument; x, bias and y are the caller's as before.
+ *   - Returns TSVD_ETOOLARGE (nothing enqueued, y untouched) when
+ *     tsvd_workspace_bytes_ex(h, B, x_dtype, x_layout) exceeds TSVD_NOALLOC_MAX_WORKSPACE
+ *     (16 MiB: any single-token or few-token call, and batched calls whose fp16 z [K][B rounded up to
+ *     256] plus a copy of x fit, e.g. 512 tokens at K = 1536, N = 768 need 2.4 MB).
+ *   - All calls on one GPU share that GPU's array, whatever the handle or stream: calls that
+ *     overlap in time on one GPU race on z and give wrong results.  Order them on one stream (or with
+ *     events).  The array keeps the previous call's contents; no kernel depends on them.
+ *   - h must have been packed on the GPU the call runs on (tsvd_pack looks up that GPU's array).
+ * Everything else is as for tsvd_forward_ex.
+ */
+#define TSVD_NOALLOC_MAX_WORKSPACE (16u << 20)
+tsvd_status tsvd_forward_noalloc(const tsvd_handle* h, const void* x_dev, tsvd_dtype x_dtype, tsvd_layout x_layout,
+                                 int64_t B, int64_t ldx, const float* bias_dev, void* y_dev, tsvd_dtype y_dtype,
+                                 int64_t ldy, void* stream);
 
 /* Releases the handle and whatever device memory it owns.  NULL is allowed. */
 void tsvd_free(tsvd_handle* h);

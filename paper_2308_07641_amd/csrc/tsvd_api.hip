@@ -24,6 +24,12 @@ struct tsvd_handle {
     long long* clocks;      // tuning aid (TSVD_CLOCKS=1 at pack time): phase timestamps of the B <= 2 kernel
 };
 
+// Workspace of tsvd_forward_noalloc: one array per GPU inside the loaded code object, so the entry point
+// never allocates.  The name below is a host-side stand-in; the array's device address differs per GPU
+// and is looked up once per device in device_init (noalloc_ptr), which is what host code passes on.
+static __device__ __align__(256) unsigned char scratch[TSVD_NOALLOC_MAX_WORKSPACE];
+static void* noalloc_ptr[64] = {};
+
 namespace {
 
 int env_int(const char* name, int fallback) {
@@ -69,12 +75,17 @@ tsvd_realign_kernel(const uint16_t* __restrict__ x, long long ldx, int B, uint16
     if (b < ldt) xt[n * ldt + b] = b < B ? x[n * ldx + b] : (uint16_t)0;
 }
 
-// One-time, per-device kernel attribute setup.
+// One-time, per-device setup (the device is current): kernel attributes, address of the static workspace.
 hipError_t device_init(int device) {
     static bool done[64] = {};
     if (device < 0 || device >= 64) return hipErrorInvalidDevice;
     if (done[device]) return hipSuccess;
-    hipError_t e = tsvd_skinny_init();
+    void* sp = nullptr;
+    hipError_t e = hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!sp || (reinterpret_cast<uintptr_t>(sp) & 255u)) return hipErrorInvalidSymbol;
+    noalloc_ptr[device] = sp;
+    e = tsvd_skinny_init();
     if (e != hipSuccess) return e;
     e = tsvd_gemm_init();
     if (e != hipSuccess) return e;
@@ -582,7 +593,20 @@ extern "C" tsvd_status tsvd_forward(const tsvd_handle* h, const void* x_dev, tsv
                            workspace_bytes, stream);
 }
 
-// Tuning aid, not part of the public header: copies the phase timestamps of the last B <= 2 launch.
+extern "C" tsvd_status tsvd_forward_noalloc(const tsvd_handle* h, const void* x_dev, tsvd_dtype x_dtype, tsvd_layout x_layout,
+                                            int64_t B, int64_t ldx, const float* bias_dev, void* y_dev, tsvd_dtype y_dtype,
+                                            int64_t ldy, void* stream) {
+    if (!h || B <= 0) return TSVD_EINVAL;
+    if (x_dtype != TSVD_F32 && x_dtype != TSVD_BF16) return TSVD_EINVAL;
+    if (x_layout != TSVD_FEATURE_MAJOR && x_layout != TSVD_TOKEN_MAJOR) return TSVD_EINVAL;
+    if (tsvd_workspace_bytes_ex(h, B, x_dtype, x_layout) > (size_t)TSVD_NOALLOC_MAX_WORKSPACE) return TSVD_ETOOLARGE;
+    if (h->device < 0 || h->device >= 64 || !noalloc_ptr[h->device]) return TSVD_EDEVICE;
+    // the workspace contents are undefined on entry for every kernel family (each writes z before it
+    // reads it), so nothing has to be cleared between calls
+    return tsvd_forward_ex(h, x_dev, x_dtype, x_layout, B, ldx, bias_dev, y_dev, y_dtype, ldy, noalloc_ptr[h->device],
+                           (size_t)TSVD_NOALLOC_MAX_WORKSPACE, stream);
+}
+
 // Tuning aid, not part of the public header: the tile shapes tsvd_forward picks for B tokens of
 // 16-byte-aligned bf16 activations (stage V, stage U); 32 for both when the call is one token-panel
 // launch; -1 where the batched kernels are not used.

@@ -232,6 +232,7 @@ extern "C" const char* tsvd_strerror(tsvd_status s) {
         case TSVD_ENOMEM: return "host memory allocation failed";
         case TSVD_EDEVICE: return "HIP call failed";
         case TSVD_EUNSUPPORTED: return "unsupported request";
+        case TSVD_ETOOLARGE: return "the call needs more workspace than the fixed array of tsvd_forward_noalloc holds";
     }
     return "unknown status";
 }

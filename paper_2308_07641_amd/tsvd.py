@@ -36,6 +36,7 @@ _PROTOTYPES = {
     "tsvd_workspace_bytes_ex": (_sz, [_vp, _i64, ctypes.c_int, ctypes.c_int]),
     "tsvd_forward_ex": (ctypes.c_int, [_vp, _vp, ctypes.c_int, ctypes.c_int, _i64, _i64, _vp, _vp, ctypes.c_int, _i64,
                                        _vp, _sz, _vp]),
+    "tsvd_forward_noalloc": (ctypes.c_int, [_vp, _vp, ctypes.c_int, ctypes.c_int, _i64, _i64, _vp, _vp, ctypes.c_int, _i64, _vp]),
     "tsvd_ternarize": (ctypes.c_int, [_vp, _i64, _i64, _i64, ctypes.c_double, _vp, _i64, _vp, _vp]),
     "tsvd_fit_scales_workspace": (_sz, [_i64]),
     "tsvd_fit_scales": (ctypes.c_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _sz, _vp, _vp]),
@@ -245,6 +246,35 @@ def tsvd_forward_ex(h: Handle, x, x_layout=TSVD_FEATURE_MAJOR, bias=None, y=None
         stream = torch.cuda.current_stream(x.device).cuda_stream
     _check(load_library().tsvd_forward_ex(h.ptr, x.data_ptr(), _dtype_code(x), x_layout, B, ldx, bias_ptr, y.data_ptr(),
                                           y_dtype, ldy, ws_ptr, ws_bytes, stream), "tsvd_forward_ex")
+    return y
+
+
+TSVD_NOALLOC_MAX_WORKSPACE = 16 << 20
+
+
+def tsvd_forward_noalloc(h: Handle, x, y, x_layout=TSVD_FEATURE_MAJOR, bias=None, y_dtype=TSVD_F32, stream=None):
+    """tsvd_forward_ex on the library's fixed per-GPU workspace; y must be given (nothing is allocated)."""
+    import torch
+    if not x.is_cuda or x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be a 2-d GPU tensor with unit inner stride")
+    token_major = x_layout == TSVD_TOKEN_MAJOR
+    B, feat = (x.shape[0], x.shape[1]) if token_major else (x.shape[1], x.shape[0])
+    if feat != h.N:
+        raise ValueError("x does not have N features")
+    ldx = x.stride(0) if x.shape[0] > 1 else max(x.shape[1], x.stride(0))
+    ydt = torch.bfloat16 if y_dtype == TSVD_BF16 else torch.float32
+    if y.dtype != ydt or y.shape != (h.M, B) or y.stride(1) != 1 or not y.is_cuda:
+        raise ValueError("y must be a GPU tensor [M,B] of the requested type with unit column stride")
+    ldy = y.stride(0) if y.shape[0] > 1 else max(B, y.stride(0))
+    bias_ptr = None
+    if bias is not None:
+        if bias.dtype != torch.float32 or bias.shape != (h.M,) or not bias.is_cuda or not bias.is_contiguous():
+            raise ValueError("bias must be a contiguous float32 GPU tensor [M]")
+        bias_ptr = bias.data_ptr()
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    _check(load_library().tsvd_forward_noalloc(h.ptr, x.data_ptr(), _dtype_code(x), x_layout, B, ldx, bias_ptr, y.data_ptr(),
+                                               y_dtype, ldy, stream), "tsvd_forward_noalloc")
     return y
 
 
