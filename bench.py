@@ -66,27 +66,18 @@ def _timed(fn, steps, warmup):
 
 def _stage_u_kernel_name(tsvd, handle, B):
     """Name of the batched stage-U kernel the library picks (its tile-shape rule, asked through the
-    tuning helper that the library exports beside the public entry points)."""
-    import ctypes
-    sv, su = ctypes.c_int(-1), ctypes.c_int(-1)
-    lib = tsvd.load_library()
-    lib.tsvd_internal_tile_shapes.restype = ctypes.c_int
-    rc = lib.tsvd_internal_tile_shapes(ctypes.c_void_p(handle.ptr), ctypes.c_longlong(B), ctypes.byref(sv), ctypes.byref(su))
-    if rc != 0 or su.value < 0:
+    diagnostic interface include/tsvd_tuning.h)."""
+    try:
+        _, su = tsvd.tsvd_tuning_tile_shapes(handle, B)
+    except ValueError:
         return "batched stage-U kernel"
-    if su.value == 32:
+    if su < 0:
+        return "batched stage-U kernel"
+    if su == 32:
         return "tsvd_panel_kernel"
-    if su.value == 40:
+    if su == 40:
         return "tsvd_gemm_fp6_kernel"
-    return "tsvd_gemm_ring_kernel" if su.value >= 14 else "tsvd_gemm_pipe_kernel"
-
-
-def _set_stage_mask(mask):
-    """Library debug switch: which kernels of the batched path run (1 colmax, 2 stage V, 4 stage U)."""
-    if mask is None:
-        os.environ.pop("TSVD_STAGE_MASK", None)
-    else:
-        os.environ["TSVD_STAGE_MASK"] = str(mask)
+    return "tsvd_gemm_ring_kernel" if su >= 14 else "tsvd_gemm_pipe_kernel"
 
 
 def cpu_baseline(w, inputs, budget_s):
@@ -137,12 +128,15 @@ def bench_workload(name, steps, warmup, with_cpu=True, cpu_budget_s=4.0):
     info = tsvd.tsvd_info(handles[0])
     print(f"[bench] {name}: packed {blob_bytes / 1e6:.1f} MB x {ncopies}", file=sys.stderr, flush=True)
 
-    state = {"i": 0}
+    state = {"i": 0, "mask": 7}
 
     def step_rot():
         h = handles[state["i"] % ncopies]
         state["i"] += 1
-        tsvd.tsvd_forward(h, x, y, workspace=ws)
+        if state["mask"] == 7:
+            tsvd.tsvd_forward(h, x, y, workspace=ws)
+        else:       # one stage alone, on the z an earlier full call left in the workspace (diagnostic entry point)
+            tsvd.tsvd_tuning_forward_stages(h, x, y, state["mask"], workspace=ws)
 
     def step_one():
         tsvd.tsvd_forward(handles[0], x, y, workspace=ws)
@@ -158,12 +152,12 @@ def bench_workload(name, steps, warmup, with_cpu=True, cpu_budget_s=4.0):
     res["dense_equiv_tflops"] = flops_dense / (ev_ms * 1e-3) / 1e12
 
     # dominant kernel: stage U (M/(M+N) of the work), timed alone on the z left in the workspace
-    # by the full passes above; TSVD_STAGE_MASK is the library's profiling switch
-    _set_stage_mask(4)
+    # by the full passes above (tsvd_tuning_forward_stages)
+    state["mask"] = 4
     _, u_ms = _timed(step_rot, steps, max(2, warmup // 2))
-    _set_stage_mask(2)
+    state["mask"] = 2
     _, v_ms = _timed(step_rot, steps, max(2, warmup // 2))
-    _set_stage_mask(None)
+    state["mask"] = 7
     step_rot()                      # a full pass again: y is compared with the oracle below
     torch.cuda.synchronize()
     res["stage_ms"] = {"V": v_ms, "U": u_ms}

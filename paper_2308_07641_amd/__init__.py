@@ -9,4 +9,5 @@ from .tsvd import (  # noqa: F401
     tsvd_workspace_bytes, tsvd_forward, tsvd_workspace_bytes_ex, tsvd_forward_ex, tsvd_forward_noalloc, TSVD_NOALLOC_MAX_WORKSPACE, tsvd_free, tsvd_strerror,
     tsvd_ternarize, tsvd_fit_scales, tsvd_residual, tsvd_leading_singular_pair, tsvd_transition,
     tsvd_conv2d_forward,
+    tsvd_tuning_set, tsvd_tuning_reset, tsvd_tuning_forward_stages, tsvd_tuning_tile_shapes, tsvd_tuning_read_clocks,
 )

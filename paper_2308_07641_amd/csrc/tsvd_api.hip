@@ -9,6 +9,7 @@
 #include <new>
 
 #include "../../include/tsvd.h"
+#include "../../include/tsvd_tuning.h"
 #include "tsvd_kernels.h"
 #include "tsvd_layout.h"
 
@@ -32,10 +33,7 @@ static void* noalloc_ptr[64] = {};
 
 namespace {
 
-int env_int(const char* name, int fallback) {
-    const char* v = std::getenv(name);
-    return (v && *v) ? std::atoi(v) : fallback;
-}
+int env_int(const char* name, int fallback) { return tsvd_tune(name, fallback); }
 
 size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 
@@ -607,10 +605,58 @@ extern "C" tsvd_status tsvd_forward_noalloc(const tsvd_handle* h, const void* x_
                            (size_t)TSVD_NOALLOC_MAX_WORKSPACE, stream);
 }
 
-// Tuning aid, not part of the public header: the tile shapes tsvd_forward picks for B tokens of
-// 16-byte-aligned bf16 activations (stage V, stage U); 32 for both when the call is one token-panel
-// launch; -1 where the batched kernels are not used.
-extern "C" int tsvd_internal_tile_shapes(const tsvd_handle* h, long long B, int* shape_v, int* shape_u) {
+// ---- diagnostic interface (include/tsvd_tuning.h) ------------------------------------------------
+namespace {
+const char* const tuning_names[] = {
+    "TSVD_GEMV", "TSVD_GEMV_FUSED", "TSVD_GEMV_ONEPASS", "TSVD_GEMV_SW", "TSVD_GEMV_KWLOG2", "TSVD_SKINNY_SW", "TSVD_SKINNY_KW",
+    "TSVD_MID", "TSVD_MID_MAX_B", "TSVD_MID_SW", "TSVD_MID_KWLOG2", "TSVD_MID_RESIDENT", "TSVD_GEMM_MIN_B",
+    "TSVD_GEMM_CFG_V", "TSVD_GEMM_CFG_U", "TSVD_FUSEMAX", "TSVD_COLMAX_SCALAR", "TSVD_REALIGN", "TSVD_PANEL",
+    "TSVD_PANEL_WAVES", "TSVD_FP6", "TSVD_FP6_V", "TSVD_FP6_TALL", "TSVD_FP6_PLANES", "TSVD_GROUPED_PAIR", "TSVD_CLOCKS",
+    "TSVD_SPIN_LIMIT"};
+constexpr int tuning_count = (int)(sizeof tuning_names / sizeof tuning_names[0]);
+int tuning_value[tuning_count];
+bool tuning_is_set[tuning_count];
+int tuning_active = 0;                 // number of switches set: 0 in every process that never calls tsvd_tuning_set
+thread_local int stage_mask_now = 7;
+}  // namespace
+
+int tsvd_tune(const char* name, int fallback) {
+    if (tuning_active == 0) return fallback;
+    for (int i = 0; i < tuning_count; ++i)
+        if (tuning_is_set[i] && std::strcmp(name, tuning_names[i]) == 0) return tuning_value[i];
+    return fallback;
+}
+int tsvd_stage_mask() { return stage_mask_now; }
+
+extern "C" int tsvd_tuning_set(const char* name, int value) {
+    if (!name) return 1;
+    for (int i = 0; i < tuning_count; ++i)
+        if (std::strcmp(name, tuning_names[i]) == 0) {
+            if (!tuning_is_set[i]) ++tuning_active;
+            tuning_is_set[i] = true;
+            tuning_value[i] = value;
+            return 0;
+        }
+    return 1;
+}
+
+extern "C" void tsvd_tuning_reset(void) {
+    for (int i = 0; i < tuning_count; ++i) tuning_is_set[i] = false;
+    tuning_active = 0;
+}
+
+extern "C" tsvd_status tsvd_tuning_forward_stages(const tsvd_handle* h, const void* x_dev, tsvd_dtype x_dtype, tsvd_layout x_layout,
+                                                  int64_t B, int64_t ldx, const float* bias_dev, void* y_dev, tsvd_dtype y_dtype,
+                                                  int64_t ldy, void* workspace, size_t workspace_bytes, void* stream, int stage_mask) {
+    if (stage_mask < 1 || stage_mask > 7) return TSVD_EINVAL;
+    stage_mask_now = stage_mask;
+    const tsvd_status st = tsvd_forward_ex(h, x_dev, x_dtype, x_layout, B, ldx, bias_dev, y_dev, y_dtype, ldy, workspace,
+                                           workspace_bytes, stream);
+    stage_mask_now = 7;
+    return st;
+}
+
+extern "C" int tsvd_tuning_tile_shapes(const tsvd_handle* h, long long B, int* shape_v, int* shape_u) {
     if (!h || !shape_v || !shape_u || B < 1) return 1;
     *shape_v = *shape_u = -1;
     if (use_mid(h, B, TSVD_BF16, tsvd_round_up(B, 8))) return 0;
@@ -632,7 +678,7 @@ const uint8_t* tsvd_internal_blob(const tsvd_handle* h, const tsvd_blob_header**
     return h->blob;
 }
 
-extern "C" int tsvd_internal_read_clocks(const tsvd_handle* h, long long* out, int workgroups) {
+extern "C" int tsvd_tuning_read_clocks(const tsvd_handle* h, long long* out, int workgroups) {
     if (!h || !h->clocks || !out || workgroups < 1 || workgroups > TSVD_GEMV_MAX_GRID) return 1;
     return hipMemcpy(out, h->clocks, (size_t)workgroups * 16 * sizeof(long long), hipMemcpyDeviceToHost) == hipSuccess ? 0 : 4;
 }

@@ -461,7 +461,7 @@ extern "C" tsvd_status tsvd_conv2d_forward(const tsvd_handle* h, const tsvd_conv
             hd->N != (int64_t)(g->c_in / g->groups) * g->k1 * g->k2)
             return TSVD_EINVAL;
         if (!plan_grouped(*g, *hd, images, H, W, &a, &MG, &ROWS, &P, &PAIR, &threads)) return TSVD_EUNSUPPORTED;
-        if (std::getenv("TSVD_GROUPED_PAIR") && std::atoi(std::getenv("TSVD_GROUPED_PAIR")) == 0) PAIR = 0;   // tuning switch: fp32 window
+        if (tsvd_tune("TSVD_GROUPED_PAIR", 1) == 0) PAIR = 0;   // tuning switch: fp32 window
         a.U = reinterpret_cast<const uint32_t*>(blob + hd->off_U); a.u_tps = (int)(hd->Kp / TSVD_TILE_COLS);
         a.V = reinterpret_cast<const uint32_t*>(blob + hd->off_V); a.v_tps = (int)(hd->Np / TSVD_TILE_COLS);
         a.S = reinterpret_cast<const float*>(blob + hd->off_S);

@@ -1673,17 +1673,9 @@ hipError_t launch_cfg(int cfg, const gemm_args& a, bool fast, long long rows, in
     }
 }
 
-int env_cfg(const char* name, int fallback) {
-    const char* v = getenv(name);
-    return (v && *v) ? atoi(v) : fallback;
-}
+int env_cfg(const char* name, int fallback) { return tsvd_tune(name, fallback); }
 
 }  // namespace
-
-int tsvd_stage_mask() {
-    const char* v = getenv("TSVD_STAGE_MASK");
-    return (v && *v) ? atoi(v) : 7;
-}
 
 // Tile shape per stage.  Large problems: 256 x 256 (one workgroup per compute unit) or 256 x 128
 // (two, with independent barriers), whichever needs less time in rounds of workgroups; the
@@ -1712,8 +1704,7 @@ int tsvd_gemm_tile_shape(long long rows, long long B, long long cus, bool aligne
 // small enough to stay in every L2 (each workgroup reads all of them), and a token count whose
 // 64-token panels fill at least 60 % of the compute units of their last round.
 bool tsvd_gemm_use_panel(long long Mp, long long Kp, long long Np, long long B, long long cus, bool aligned) {
-    const char* v = getenv("TSVD_PANEL");
-    const int mode = (v && *v) ? atoi(v) : -1;       // 0 never, 1 whenever the shape allows, default: by rule
+    const int mode = tsvd_tune("TSVD_PANEL", -1);       // 0 never, 1 whenever the shape allows, default: by rule
     if (!aligned || Kp > TSVD_PANEL_MAX_KP || Np > TSVD_PANEL_MAX_NP || mode == 0) return false;
     if (mode == 1) return true;
     const long long n = (B + 63) / 64, rounds = (n + cus - 1) / cus;
@@ -1724,8 +1715,7 @@ bool tsvd_gemm_use_panel(long long Mp, long long Kp, long long Np, long long B, 
 // allow, default by rule.  The planes of Z need tsvd_gemm_fp6_bytes more workspace.
 size_t tsvd_gemm_fp6_bytes(long long Kp, long long Bp) { return (size_t)(Bp / 128) * (size_t)(Kp / 128) * FP6_PAIR_BYTES; }
 bool tsvd_gemm_use_fp6(long long Mp, long long Kp, long long Np, long long B, long long cus, bool aligned) {
-    const char* v = getenv("TSVD_FP6");
-    const int mode = (v && *v) ? atoi(v) : -1;
+    const int mode = tsvd_tune("TSVD_FP6", -1);
     const long long Bp = tsvd_round_up(B, 256);
     if (mode == 0 || tsvd_gemm_fp6_bytes(Kp, Bp) >= (1ull << 31)) return false;
     (void)Np; (void)aligned;
@@ -1751,8 +1741,7 @@ bool tsvd_gemm_use_fp6(long long Mp, long long Kp, long long Np, long long B, lo
 // applied to stage V's own sizes.  Needs x with an even row pitch at a 4-byte aligned address.
 bool tsvd_gemm_use_fp6_v(long long Mp, long long Kp, long long Np, long long B, long long cus, bool aligned) {
     if (!aligned || !tsvd_gemm_use_fp6(Mp, Kp, Np, B, cus, aligned)) return false;
-    const char* v = getenv("TSVD_FP6_V");
-    const int mode = (v && *v) ? atoi(v) : -1;
+    const int mode = tsvd_tune("TSVD_FP6_V", -1);
     const long long Bp = tsvd_round_up(B, 256);
     if (mode == 0 || tsvd_gemm_fp6_bytes(Np, Bp) >= (1ull << 31)) return false;
     if (mode == 1) return true;

@@ -127,4 +127,7 @@ size_t tsvd_gemm_fp6_bytes(long long Kp, long long Bp);
 // Stage V through fp6 planes of x (only together with the above; its planes follow those of Z).
 bool tsvd_gemm_use_fp6_v(long long Mp, long long Kp, long long Np, long long B, long long cus, bool aligned);
 #define TSVD_COLMAX_PARTS 16
-int tsvd_stage_mask();   // profiling switch read from the environment (default 7 = everything)
+// Diagnostic switches (include/tsvd_tuning.h): value set by tsvd_tuning_set in this process, else the
+// fallback.  The library never reads the environment.
+int tsvd_tune(const char* name, int fallback);
+int tsvd_stage_mask();   // stages the current call runs (7 = all; partial only inside tsvd_tuning_forward_stages)

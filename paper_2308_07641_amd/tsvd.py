@@ -37,6 +37,12 @@ _PROTOTYPES = {
     "tsvd_forward_ex": (ctypes.c_int, [_vp, _vp, ctypes.c_int, ctypes.c_int, _i64, _i64, _vp, _vp, ctypes.c_int, _i64,
                                        _vp, _sz, _vp]),
     "tsvd_forward_noalloc": (ctypes.c_int, [_vp, _vp, ctypes.c_int, ctypes.c_int, _i64, _i64, _vp, _vp, ctypes.c_int, _i64, _vp]),
+    "tsvd_tuning_set": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_int]),
+    "tsvd_tuning_reset": (None, []),
+    "tsvd_tuning_forward_stages": (ctypes.c_int, [_vp, _vp, ctypes.c_int, ctypes.c_int, _i64, _i64, _vp, _vp, ctypes.c_int, _i64,
+                                                  _vp, _sz, _vp, ctypes.c_int]),
+    "tsvd_tuning_tile_shapes": (ctypes.c_int, [_vp, ctypes.c_longlong, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]),
+    "tsvd_tuning_read_clocks": (ctypes.c_int, [_vp, _vp, ctypes.c_int]),
     "tsvd_ternarize": (ctypes.c_int, [_vp, _i64, _i64, _i64, ctypes.c_double, _vp, _i64, _vp, _vp]),
     "tsvd_fit_scales_workspace": (_sz, [_i64]),
     "tsvd_fit_scales": (ctypes.c_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _sz, _vp, _vp]),
@@ -276,6 +282,48 @@ def tsvd_forward_noalloc(h: Handle, x, y, x_layout=TSVD_FEATURE_MAJOR, bias=None
     _check(load_library().tsvd_forward_noalloc(h.ptr, x.data_ptr(), _dtype_code(x), x_layout, B, ldx, bias_ptr, y.data_ptr(),
                                                y_dtype, ldy, stream), "tsvd_forward_noalloc")
     return y
+
+
+# ---- diagnostic interface (include/tsvd_tuning.h): for the tests and the benchmark only
+def tsvd_tuning_set(name: str, value: int) -> None:
+    if load_library().tsvd_tuning_set(name.encode(), int(value)) != 0:
+        raise ValueError(f"unknown tuning switch {name!r}")
+
+
+def tsvd_tuning_reset() -> None:
+    load_library().tsvd_tuning_reset()
+
+
+def tsvd_tuning_forward_stages(h: Handle, x, y, stage_mask: int, workspace=None, stream=None):
+    """tsvd_forward restricted to the kernels in stage_mask (1 column maxima, 2 stage V, 4 stage U)."""
+    import torch
+    x2 = x if x.dim() == 2 else x.unsqueeze(1)
+    B = x2.shape[1]
+    ldx = x2.stride(0) if x2.shape[0] > 1 else max(B, x2.stride(0))
+    ldy = y.stride(0) if y.shape[0] > 1 else max(B, y.stride(0))
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    _check(load_library().tsvd_tuning_forward_stages(h.ptr, x2.data_ptr(), _dtype_code(x2), TSVD_FEATURE_MAJOR, B, ldx, None,
+                                                     y.data_ptr(), TSVD_F32, ldy, ws_ptr, ws_bytes, stream, int(stage_mask)),
+           "tsvd_tuning_forward_stages")
+    return y
+
+
+def tsvd_tuning_tile_shapes(h: Handle, B: int):
+    sv, su = ctypes.c_int(-1), ctypes.c_int(-1)
+    if load_library().tsvd_tuning_tile_shapes(h.ptr, B, ctypes.byref(sv), ctypes.byref(su)) != 0:
+        raise ValueError("tsvd_tuning_tile_shapes")
+    return sv.value, su.value
+
+
+def tsvd_tuning_read_clocks(h: Handle, workgroups: int) -> np.ndarray:
+    out = np.zeros((workgroups, 16), dtype=np.int64)
+    if load_library().tsvd_tuning_read_clocks(h.ptr, out.ctypes.data, workgroups) != 0:
+        raise ValueError("tsvd_tuning_read_clocks: the handle was not packed with TSVD_CLOCKS = 1")
+    return out
 
 
 # ---- direct transition W -> (U, S, V) (include/tsvd_transition.h); torch CUDA tensors as device buffers

@@ -15,3 +15,12 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+@pytest.fixture(autouse=True)
+def _reset_tuning_switches():
+    """Tests route calls to a kernel family with tsvd_tuning_set; every test starts from the library's own rules."""
+    yield
+    import paper_2308_07641_amd.tsvd as binding
+    if binding._lib is not None:
+        binding._lib.tsvd_tuning_reset()

@@ -32,9 +32,22 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, n), f"{n} declared in include/*.h but not exported"
 
 
+def test_tuning_switches_are_explicit_and_the_library_ignores_the_environment(monkeypatch):
+    """The selection rules can only be overridden by tsvd_tuning_set in this process; unknown names are refused."""
+    lib = tsvd.load_library()
+    assert lib.tsvd_tuning_set(b"TSVD_NO_SUCH_SWITCH", 1) == 1
+    with pytest.raises(ValueError):
+        tsvd.tsvd_tuning_set("TSVD_STAGE_MASK", 4)          # the stage mask is an argument of the diagnostic forward only
+    tsvd.tsvd_tuning_set("TSVD_FP6", 0)
+    tsvd.tsvd_tuning_reset()
+    src = "".join(open(os.path.join(ROOT, "paper_2308_07641_amd", "csrc", f)).read()
+                  for f in os.listdir(os.path.join(ROOT, "paper_2308_07641_amd", "csrc")))
+    assert "getenv" not in src
+
+
 def test_strerror_covers_all_codes():
-    texts = [tsvd.tsvd_strerror(s) for s in range(6)]
-    assert texts[0] == "ok" and len(set(texts)) == 6
+    texts = [tsvd.tsvd_strerror(s) for s in range(7)]
+    assert texts[0] == "ok" and len(set(texts)) == 7
 
 
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (4, 4, 4), (3, 5, 7), (16, 256, 16), (17, 257, 33),

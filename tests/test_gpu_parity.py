@@ -67,18 +67,18 @@ def test_random_instances_within_tolerance(tsvd, M, N, K, B, p0, x_dtype):
     assert rel_err(y, ref) <= TOL[x_dtype]
 
 
-# ---- every tile shape of the batched kernels on the same ragged instance.  The library reads
-# ---- these tuning switches per call; normally the shape follows from the problem size, so the
+# ---- every tile shape of the batched kernels on the same ragged instance.  The tuning switches
+# ---- (include/tsvd_tuning.h) are looked up per call; normally the shape follows from the problem size, so the
 # ---- small test instances above would never reach the large-tile kernels.
 TILE_SHAPES = [0, 1, 2, 3, 14, 15, 16]
 
 
 @pytest.mark.parametrize("fuse", ["1", "0"])
 @pytest.mark.parametrize("cfg", TILE_SHAPES)
-def test_every_tile_shape_batched(tsvd, cfg, fuse, monkeypatch):
-    monkeypatch.setenv("TSVD_GEMM_CFG_V", str(cfg))
-    monkeypatch.setenv("TSVD_GEMM_CFG_U", str(cfg))
-    monkeypatch.setenv("TSVD_FUSEMAX", fuse)
+def test_every_tile_shape_batched(tsvd, cfg, fuse):
+    tsvd.tsvd_tuning_set("TSVD_GEMM_CFG_V", cfg)
+    tsvd.tsvd_tuning_set("TSVD_GEMM_CFG_U", cfg)
+    tsvd.tsvd_tuning_set("TSVD_FUSEMAX", int(fuse))
     print(f"case tile shape {cfg} fuse {fuse}", flush=True)
     i = workloads.make_integer_inputs(300, 200, 520, 300, 0.5, "bf16", seed=4242 + cfg)
     ref = oracle.forward(i.U, i.S, i.V, i.X)
@@ -95,12 +95,12 @@ def test_every_tile_shape_batched(tsvd, cfg, fuse, monkeypatch):
 
 
 @pytest.mark.parametrize("cfg", [0, 1, 2, 3])
-def test_unaligned_rows_gather_kernels(tsvd, cfg, monkeypatch):
+def test_unaligned_rows_gather_kernels(tsvd, cfg):
     """Rows of x that are not 16-byte aligned are copied to aligned rows before the batched kernels;
     with that copy switched off the large-tile kernels gather them element by element."""
-    monkeypatch.setenv("TSVD_REALIGN", "0")
-    monkeypatch.setenv("TSVD_GEMM_CFG_V", str(cfg))
-    monkeypatch.setenv("TSVD_GEMM_CFG_U", str(cfg))
+    tsvd.tsvd_tuning_set("TSVD_REALIGN", 0)
+    tsvd.tsvd_tuning_set("TSVD_GEMM_CFG_V", cfg)
+    tsvd.tsvd_tuning_set("TSVD_GEMM_CFG_U", cfg)
     print(f"case gather tile shape {cfg}", flush=True)
     i = workloads.make_integer_inputs(300, 200, 520, 301, 0.5, "bf16", seed=4343 + cfg)
     y, h = run_forward(i)
@@ -113,13 +113,13 @@ def test_unaligned_rows_gather_kernels(tsvd, cfg, monkeypatch):
 
 
 @pytest.mark.parametrize("fuse", ["1", "0"])
-def test_tile_shape_of_96_rows(tsvd, fuse, monkeypatch):
+def test_tile_shape_of_96_rows(tsvd, fuse):
     """The 96 x 64 ring tiles need padded row counts that 96 divides (the shape rule asks for them
     only then): forced here on both stages of instances with 768 and 1536 padded rows."""
-    monkeypatch.setenv("TSVD_GEMM_CFG_V", "17")
-    monkeypatch.setenv("TSVD_GEMM_CFG_U", "17")
-    monkeypatch.setenv("TSVD_FUSEMAX", fuse)
-    monkeypatch.setenv("TSVD_PANEL", "0")
+    tsvd.tsvd_tuning_set("TSVD_GEMM_CFG_V", 17)
+    tsvd.tsvd_tuning_set("TSVD_GEMM_CFG_U", 17)
+    tsvd.tsvd_tuning_set("TSVD_FUSEMAX", int(fuse))
+    tsvd.tsvd_tuning_set("TSVD_PANEL", 0)
     print(f"case tile shape 17 fuse {fuse}", flush=True)
     i = workloads.make_integer_inputs(700, 200, 760, 300, 0.5, "bf16", seed=1717)
     y, h = run_forward(i)
@@ -135,13 +135,13 @@ def test_tile_shape_of_96_rows(tsvd, fuse, monkeypatch):
 
 @pytest.mark.parametrize("waves", ["16", "8"])
 @pytest.mark.parametrize("M,N,K,B", [(300, 200, 520, 300), (64, 48, 200, 17), (1030, 100, 1000, 70), (2048, 512, 1024, 1000)])
-def test_token_panel_kernel(tsvd, M, N, K, B, waves, monkeypatch):
+def test_token_panel_kernel(tsvd, M, N, K, B, waves):
     """Both stages in one launch with z kept in LDS (K <= 1024), forced on small instances: exact
     integers bit for bit, random values within tolerance, and next to identical to the two-launch path."""
     print(f"case panel M={M} N={N} K={K} B={B}", flush=True)
     i = workloads.make_integer_inputs(M, N, K, B, 0.5, "bf16", seed=5150 + B)
-    monkeypatch.setenv("TSVD_PANEL", "1")
-    monkeypatch.setenv("TSVD_PANEL_WAVES", waves)
+    tsvd.tsvd_tuning_set("TSVD_PANEL", 1)
+    tsvd.tsvd_tuning_set("TSVD_PANEL_WAVES", int(waves))
     y, h = run_forward(i)
     tsvd.tsvd_free(h)
     assert not np.isnan(y).any()
@@ -152,7 +152,7 @@ def test_token_panel_kernel(tsvd, M, N, K, B, waves, monkeypatch):
     tsvd.tsvd_free(h)
     assert not np.isnan(y1).any()
     assert rel_err(y1, ref) <= TOL["bf16"]
-    monkeypatch.setenv("TSVD_PANEL", "0")
+    tsvd.tsvd_tuning_set("TSVD_PANEL", 0)
     y0, h = run_forward(j)
     tsvd.tsvd_free(h)
     # same products; only the fp32 summation order differs between the kernels (a different order in
@@ -177,11 +177,11 @@ def test_larger_small_problem_uses_wider_ring_tiles(tsvd):
 @pytest.mark.parametrize("resident", ["1", "0"])
 @pytest.mark.parametrize("kwlog2", ["0", "1", "2", "3"])
 @pytest.mark.parametrize("M,N,K,B", [(100, 2300, 4500, 16), (530, 270, 5000, 8), (70, 6000, 300, 7), (200, 4100, 2049, 2)])
-def test_few_token_kernel(tsvd, M, N, K, B, kwlog2, resident, monkeypatch):
+def test_few_token_kernel(tsvd, M, N, K, B, kwlog2, resident):
     import torch
-    monkeypatch.setenv("TSVD_MID_RESIDENT", resident)
-    monkeypatch.setenv("TSVD_MID_KWLOG2", kwlog2)
-    monkeypatch.setenv("TSVD_MID_SW", "2")
+    tsvd.tsvd_tuning_set("TSVD_MID_RESIDENT", int(resident))
+    tsvd.tsvd_tuning_set("TSVD_MID_KWLOG2", int(kwlog2))
+    tsvd.tsvd_tuning_set("TSVD_MID_SW", 2)
     i = workloads.make_integer_inputs(M, N, K, B, 0.5, "bf16", seed=31 + M + B)
     print(f"case few-token int M={M} N={N} K={K} B={B} kw=2^{kwlog2}", flush=True)
     y, h = run_forward(i)
@@ -199,7 +199,7 @@ def test_few_token_kernel(tsvd, M, N, K, B, kwlog2, resident, monkeypatch):
     y2 = tsvd.tsvd_forward(h, xfull[:, :B]).cpu().numpy().astype(np.float64)
     assert np.array_equal(y2, y)
     # and against the one-token-at-a-time path
-    monkeypatch.setenv("TSVD_MID", "0")
+    tsvd.tsvd_tuning_set("TSVD_MID", 0)
     y3 = tsvd.tsvd_forward(h, to_device(i)).cpu().numpy().astype(np.float64)
     tsvd.tsvd_free(h)
     assert rel_err(y3, ref) <= 1e-5 and rel_err(y, y3) <= TOL["bf16"]
@@ -233,10 +233,10 @@ def test_few_token_kernel_at_the_resident_limit(tsvd, K):
 
 
 @pytest.mark.parametrize("B", [17, 40, 64])
-def test_few_token_kernel_in_groups(tsvd, B, monkeypatch):
+def test_few_token_kernel_in_groups(tsvd, B):
     """Up to 64 tokens go through the few-token kernel in groups of 16 when the weights are large;
     forced here on a small instance (exact, then random against the oracle and the batched path)."""
-    monkeypatch.setenv("TSVD_MID_MAX_B", "64")
+    tsvd.tsvd_tuning_set("TSVD_MID_MAX_B", 64)
     i = workloads.make_integer_inputs(150, 300, 2100, B, 0.5, "bf16", seed=41 + B)
     print(f"case few-token groups int B={B}", flush=True)
     y, h = run_forward(i)
@@ -248,7 +248,7 @@ def test_few_token_kernel_in_groups(tsvd, B, monkeypatch):
     y, h = run_forward(i)
     assert not np.isnan(y).any()
     assert rel_err(y, ref) <= TOL["bf16"]
-    monkeypatch.setenv("TSVD_MID_MAX_B", "16")
+    tsvd.tsvd_tuning_set("TSVD_MID_MAX_B", 16)
     y2 = tsvd.tsvd_forward(h, to_device(i)).cpu().numpy().astype(np.float64)
     tsvd.tsvd_free(h)
     assert rel_err(y2, ref) <= TOL["bf16"] and rel_err(y, y2) <= 1e-5    # same arithmetic, other summation order
@@ -286,10 +286,10 @@ def test_activation_scale_extremes_batched(tsvd):
 @pytest.mark.parametrize("fused", ["1", "0"])
 @pytest.mark.parametrize("x_dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("M,N,K", [(256, 256, 512), (1, 1, 1), (37, 29, 61), (500, 300, 250), (1000, 700, 200), (100, 1000, 260)])
-def test_small_single_token_fused_launch(tsvd, M, N, K, x_dtype, fused, monkeypatch):
+def test_small_single_token_fused_launch(tsvd, M, N, K, x_dtype, fused):
     """Small matrices run both stages in one launch of one workgroup ("1"); the two-launch kernels
     must give the same exact results on them ("0")."""
-    monkeypatch.setenv("TSVD_GEMV_FUSED", fused)
+    tsvd.tsvd_tuning_set("TSVD_GEMV_FUSED", int(fused))
     i = workloads.make_integer_inputs(M, N, K, 1, 0.5, x_dtype, seed=3 * M + N + K)
     print(f"case small single token M={M} N={N} K={K} {x_dtype} fused={fused}", flush=True)
     y, h = run_forward(i)
@@ -306,10 +306,10 @@ def test_small_single_token_fused_launch(tsvd, M, N, K, x_dtype, fused, monkeypa
         assert not np.any(y)
 
 
-def test_general_single_token_kernel(tsvd, monkeypatch):
+def test_general_single_token_kernel(tsvd):
     """The slab kernel that serves contraction lengths beyond the fast single-token kernel's
     limits, forced on ordinary sizes (exact instance, then a random one per activation type)."""
-    monkeypatch.setenv("TSVD_GEMV", "0")
+    tsvd.tsvd_tuning_set("TSVD_GEMV", 0)
     for B in (1, 2, 5):
         i = workloads.make_integer_inputs(300, 513, 270, B, 0.5, "bf16", seed=900 + B)
         print(f"case general kernel int B={B}", flush=True)
@@ -363,7 +363,7 @@ def test_degenerate_inputs(tsvd, B):
 # ---- kernel family.  Exact instances: an integer bias keeps every value an exactly representable
 # ---- integer, so the fp32 output must equal the oracle and the bf16 output its exact rounding.
 LAYER_CASES = [
-    # M, N, K, B, environment that routes the call
+    # M, N, K, B, tuning switches that route the call
     (250, 200, 500, 1, {}),                                   # single token, small matrix: one fused launch
     (300, 513, 270, 1, {}),                                   # single-token kernels, two launches
     (300, 513, 270, 2, {"TSVD_GEMV": "0", "TSVD_MID": "0"}),  # general slab kernel, two tokens per pass
@@ -381,10 +381,10 @@ LAYER_CASES = [
 
 
 @pytest.mark.parametrize("M,N,K,B,env", LAYER_CASES)
-def test_layer_form_every_kernel_family(tsvd, M, N, K, B, env, monkeypatch):
+def test_layer_form_every_kernel_family(tsvd, M, N, K, B, env):
     import torch
     for k, v in env.items():
-        monkeypatch.setenv(k, v)
+        tsvd.tsvd_tuning_set(k, int(v))
     dev = "cuda:0"
     rng = np.random.default_rng(M + B)
 
@@ -517,18 +517,18 @@ def test_repeated_calls_are_bit_identical(tsvd):
 @pytest.mark.parametrize("stage_v", [False, True])
 @pytest.mark.parametrize("M,N,K,B", [(300, 200, 270, 100), (515, 300, 777, 130), (1024, 512, 768, 512), (130, 64, 2100, 257),
                                      (512, 300, 1024, 200)])
-def test_fp6_planes_stage_u(tsvd, M, N, K, B, stage_v, tile, monkeypatch):
+def test_fp6_planes_stage_u(tsvd, M, N, K, B, stage_v, tile):
     """Z as three E2M3 planes with per-lane block scales, multiplied with the codes as fp4 on the scaled
     128-deep MFMA: exact on integer instances (small integers need one plane), within the tolerance
     of the 16-bit path on random ones and next to identical to it; bias and bf16 output included.
     stage_v: x goes through planes as well (stage V on the same kernel; forced here, with the
     two-kernel form of stage V that it replaces)."""
     import torch
-    monkeypatch.setenv("TSVD_FP6", "1")
-    monkeypatch.setenv("TSVD_FP6_V", "1" if stage_v else "0")
-    monkeypatch.setenv("TSVD_FP6_TALL", tile)
+    tsvd.tsvd_tuning_set("TSVD_FP6", 1)
+    tsvd.tsvd_tuning_set("TSVD_FP6_V", 1 if stage_v else 0)
+    tsvd.tsvd_tuning_set("TSVD_FP6_TALL", int(tile))
     if stage_v:
-        monkeypatch.setenv("TSVD_GEMM_CFG_V", "3")
+        tsvd.tsvd_tuning_set("TSVD_GEMM_CFG_V", 3)
     i = workloads.make_integer_inputs(M, N, K, B, 0.5, "bf16", seed=606 + B)
     print(f"case fp6 int M={M} N={N} K={K} B={B}", flush=True)
     y, h = run_forward(i)
@@ -544,21 +544,21 @@ def test_fp6_planes_stage_u(tsvd, M, N, K, B, stage_v, tile, monkeypatch):
     yb = tsvd.tsvd_forward_ex(h, to_device(j), bias=bias, y_dtype=tsvd.TSVD_BF16).float().cpu().numpy().astype(np.float64)
     refb = ref + bias.cpu().numpy().astype(np.float64)[:, None]
     assert np.all(np.abs(yb - refb) <= TOL["bf16"] * np.max(np.abs(ref)) + 2.0 ** -8 * np.abs(refb))
-    monkeypatch.setenv("TSVD_FP6", "0")
+    tsvd.tsvd_tuning_set("TSVD_FP6", 0)
     y0 = tsvd.tsvd_forward(h, to_device(j)).cpu().numpy().astype(np.float64)
     tsvd.tsvd_free(h)
     assert rel_err(y0, y1) <= 5e-4        # both round Z to about 12 bits, differently
 
 
 @pytest.mark.parametrize("mode", ["fp16", "fp6"])
-def test_outlier_features(tsvd, mode, monkeypatch):
+def test_outlier_features(tsvd, mode):
     """Activations with outlier features (1 % of the features 300 times larger, as in transformer
     layers): the per-token scaling of z and, on the fp4 x fp6 kernels, the block scales of the planes of
     both stages keep the error at the level of ordinary inputs."""
-    monkeypatch.setenv("TSVD_FP6", "1" if mode == "fp6" else "0")
+    tsvd.tsvd_tuning_set("TSVD_FP6", 1 if mode == "fp6" else 0)
     if mode == "fp6":
-        monkeypatch.setenv("TSVD_FP6_V", "1")
-        monkeypatch.setenv("TSVD_GEMM_CFG_V", "3")
+        tsvd.tsvd_tuning_set("TSVD_FP6_V", 1)
+        tsvd.tsvd_tuning_set("TSVD_GEMM_CFG_V", 3)
     i = workloads.make_outlier_inputs(512, 1280, 1024, 300, 0.6, 0.02, seed=77, factor=300.0, share=0.01)
     assert np.max(np.abs(i.X)) > 100.0
     print(f"case outliers {mode}", flush=True)
@@ -571,13 +571,13 @@ def test_outlier_features(tsvd, mode, monkeypatch):
 
 
 @pytest.mark.parametrize("M,N,K,B", [(1024, 512, 768, 512), (512, 300, 1024, 200), (700, 2100, 2300, 130)])
-def test_fp6_two_planes_switch(tsvd, M, N, K, B, monkeypatch):
+def test_fp6_two_planes_switch(tsvd, M, N, K, B):
     """The accuracy / speed switch of the fp4 x fp6 kernels (two planes instead of three, never chosen by
     default): still within the tolerance of bf16 activations, at about five times the error."""
-    monkeypatch.setenv("TSVD_FP6", "1")
-    monkeypatch.setenv("TSVD_FP6_V", "1")
-    monkeypatch.setenv("TSVD_GEMM_CFG_V", "3")
-    monkeypatch.setenv("TSVD_FP6_PLANES", "2")
+    tsvd.tsvd_tuning_set("TSVD_FP6", 1)
+    tsvd.tsvd_tuning_set("TSVD_FP6_V", 1)
+    tsvd.tsvd_tuning_set("TSVD_GEMM_CFG_V", 3)
+    tsvd.tsvd_tuning_set("TSVD_FP6_PLANES", 2)
     j = workloads.make_inputs(M, N, K, B, 0.6, 0.02, "bf16", seed=909 + B)
     print(f"case fp6 two planes M={M} N={N} K={K} B={B}", flush=True)
     ref = oracle.forward(j.U, j.S, j.V, j.X)
