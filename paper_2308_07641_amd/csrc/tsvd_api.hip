@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -23,6 +24,12 @@ struct tsvd_handle {
     float bound_V;          // max_k |S_k| * nnz(V[k,:]) : |z_k| <= bound_V * max|x| for every token
     int cu_count;           // compute units of the device
     long long* clocks;      // tuning aid (TSVD_CLOCKS=1 at pack time): phase timestamps of the B <= 2 kernel
+    // One-launch single-token path: [counter: 256 B][z as tagged 64-bit words: Kp], device, zeroed at pack
+    // (counter = 1); null when the shape does not fit that kernel.  The path belongs to the first stream
+    // that uses it: calls on one stream never overlap, calls on other streams take the two-launch kernels.
+    uint8_t* sync;
+    std::atomic<int> sync_claimed;
+    void* sync_stream;
 };
 
 // Workspace of tsvd_forward_noalloc: one array per GPU inside the loaded code object, so the entry point
@@ -149,6 +156,30 @@ bool try_gemv(const tsvd_handle* h, const void* x, tsvd_dtype x_dtype, int64_t l
         f.y = y; f.ldy = ldy; f.bias = oo.bias; f.out_bf16 = oo.out_bf16;
         *st = tsvd_launch_gemv_fused(f, stream) == hipSuccess ? TSVD_OK : TSVD_EDEVICE;
         return true;
+    }
+    if (mask == 7 && h->sync && env_int("TSVD_GEMV_ONEPASS", 0) != 0) {
+        // both stages in one launch (z handed over between workgroups through the handle's tagged buffer)
+        tsvd_handle* hm = const_cast<tsvd_handle*>(h);
+        int expected = 0;
+        if (hm->sync_claimed.compare_exchange_strong(expected, 1)) hm->sync_stream = stream;
+        tsvd_gemv_onepass_args f;
+        std::memset(&f, 0, sizeof f);
+        if (hm->sync_stream == (void*)stream && tsvd_gemv_onepass_shape(hd.M, hd.Mp, hd.Kp, hd.Np, h->cu_count, &f)) {
+            f.tiles_v = h->blob + hd.off_V;
+            f.tiles_u = h->blob + hd.off_U;
+            f.N = (int)hd.N; f.Np = (int)hd.Np; f.Kp = (int)hd.Kp; f.M = (int)hd.M;
+            f.x = x; f.x_is_bf16 = x_dtype == TSVD_BF16; f.ldx = ldx;
+            f.x_vec = ldx == 1 && hd.N % 4 == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
+            f.S = reinterpret_cast<const float*>(h->blob + hd.off_S);
+            f.bound_V = h->bound_V;
+            f.counter = reinterpret_cast<unsigned*>(h->sync);
+            f.zbuf = reinterpret_cast<unsigned long long*>(h->sync + 256);
+            f.spin_limit = env_int("TSVD_SPIN_LIMIT", 256);
+            f.y = y; f.ldy = ldy; f.bias = oo.bias; f.out_bf16 = oo.out_bf16;
+            f.clocks = h->clocks;
+            *st = tsvd_launch_gemv_onepass(f, stream) == hipSuccess ? TSVD_OK : TSVD_EDEVICE;
+            return true;
+        }
     }
     // sw strips x kw splits = 16 wavefronts; about one workgroup per compute unit for large matrices
     auto shape = [&](tsvd_gemv_args& a) {
@@ -409,6 +440,9 @@ extern "C" tsvd_status tsvd_pack(const int8_t* U, const float* S, const int8_t* 
     h->scratch_bytes = 0;
     h->clocks = nullptr;
     h->cu_count = 256;
+    h->sync = nullptr;
+    h->sync_claimed.store(0);
+    h->sync_stream = nullptr;
 
     bool ok = hipGetDevice(&h->device) == hipSuccess && device_init(h->device) == hipSuccess;
     if (ok) {
@@ -428,6 +462,17 @@ extern "C" tsvd_status tsvd_pack(const int8_t* U, const float* S, const int8_t* 
             int cus = 0;
             if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device) == hipSuccess && cus > 0)
                 h->cu_count = cus;
+            if (env_int("TSVD_GEMV_ONEPASS", 0) != 0 && tsvd_gemv_onepass_shape(h->hd.M, h->hd.Mp, h->hd.Kp, h->hd.Np, h->cu_count, nullptr)) {
+                // hand-over buffer of the one-launch single-token path (small: 8 bytes per rank index)
+                const size_t sb = 256 + (size_t)h->hd.Kp * 8;
+                void* d = nullptr;
+                const unsigned one = 1u;
+                ok = hipMalloc(&d, sb) == hipSuccess;
+                if (ok) {
+                    h->sync = static_cast<uint8_t*>(d);
+                    ok = hipMemset(d, 0, sb) == hipSuccess && hipMemcpy(d, &one, sizeof one, hipMemcpyHostToDevice) == hipSuccess;
+                }
+            }
             if (ok && env_int("TSVD_CLOCKS", 0)) {
                 void* c = nullptr;
                 if (hipMalloc(&c, TSVD_GEMV_MAX_GRID * 16 * sizeof(long long)) == hipSuccess) {
@@ -440,6 +485,7 @@ extern "C" tsvd_status tsvd_pack(const int8_t* U, const float* S, const int8_t* 
     std::free(host);
     if (!ok) {
         if (h->owns_blob && h->blob) (void)hipFree(h->blob);
+        if (h->sync) (void)hipFree(h->sync);
         delete h;
         (void)hipGetLastError();
         return TSVD_EDEVICE;
@@ -687,6 +733,7 @@ extern "C" void tsvd_free(tsvd_handle* h) {
     if (!h) return;
     if (h->scratch) (void)hipFree(h->scratch);
     if (h->clocks) (void)hipFree(h->clocks);
+    if (h->sync) (void)hipFree(h->sync);
     if (h->owns_blob && h->blob) (void)hipFree(h->blob);
     delete h;
 }

@@ -28,6 +28,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+
 #include "tsvd_epilogue.h"
 #include "tsvd_kernels.h"
 
@@ -76,12 +78,62 @@ __device__ __forceinline__ uint32_t fp8_of_nibbles(uint32_t v) {
 
 // Digit planes of one activation: sign-magnitude fixed point, |v| < 2^ex -> magnitude <= 2^30.
 // even: digits 0,2,4,6 (one per byte), odd: digits 1,3,5,7, as fp8 codes with the sign applied.
-__device__ __forceinline__ void digit_codes(float v, int ex, uint32_t& even, uint32_t& odd) {
-    const uint32_t mag = (uint32_t)rintf(ldexpf(fabsf(v), 30 - ex));
-    const uint32_t sign = v < 0.f ? 0x80808080u : 0u;
+__device__ __forceinline__ uint32_t fixed_magnitude(float v, int ex) { return (uint32_t)rintf(ldexpf(fabsf(v), 30 - ex)); }
+__device__ __forceinline__ void codes_of_fixed(uint32_t mag, bool negative, uint32_t& even, uint32_t& odd) {
+    const uint32_t sign = negative ? 0x80808080u : 0u;
     even = fp8_of_nibbles(mag & 0x0F0F0F0Fu) | sign;
     odd = fp8_of_nibbles((mag >> 4) & 0x0F0F0F0Fu) | sign;
 }
+__device__ __forceinline__ void digit_codes(float v, int ex, uint32_t& even, uint32_t& odd) {
+    codes_of_fixed(fixed_magnitude(v, ex), v < 0.f, even, odd);
+}
+// Four consecutive activations' codes (even[e], odd[e]) -> one 32-bit word per digit plane in LDS.
+__device__ __forceinline__ void store_plane_words(unsigned char* planes, int pstride, int k, const uint32_t (&ev)[4], const uint32_t (&od)[4]) {
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const uint32_t we = ((ev[0] >> (8 * d)) & 0xFFu) | (((ev[1] >> (8 * d)) & 0xFFu) << 8) |
+                            (((ev[2] >> (8 * d)) & 0xFFu) << 16) | (((ev[3] >> (8 * d)) & 0xFFu) << 24);
+        const uint32_t wo = ((od[0] >> (8 * d)) & 0xFFu) | (((od[1] >> (8 * d)) & 0xFFu) << 8) |
+                            (((od[2] >> (8 * d)) & 0xFFu) << 16) | (((od[3] >> (8 * d)) & 0xFFu) << 24);
+        *reinterpret_cast<uint32_t*>(planes + (size_t)(2 * d) * pstride + k) = we;
+        *reinterpret_cast<uint32_t*>(planes + (size_t)(2 * d + 1) * pstride + k) = wo;
+    }
+}
+
+// 4 x 4 byte transposition: out[d] byte e = in[e] byte d (eight byte permutes).
+__device__ __forceinline__ void transpose_bytes(const uint32_t (&in)[4], uint32_t (&out)[4]) {
+    const uint32_t t0 = __builtin_amdgcn_perm(in[1], in[0], 0x05010400u);    // in0.b0 in1.b0 in0.b1 in1.b1
+    const uint32_t t1 = __builtin_amdgcn_perm(in[1], in[0], 0x07030602u);    // in0.b2 in1.b2 in0.b3 in1.b3
+    const uint32_t t2 = __builtin_amdgcn_perm(in[3], in[2], 0x05010400u);
+    const uint32_t t3 = __builtin_amdgcn_perm(in[3], in[2], 0x07030602u);
+    out[0] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);
+    out[1] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
+    out[2] = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
+    out[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
+}
+
+// Digit planes of four consecutive activations given as sign-magnitude fixed point (bit 31 sign, magnitude
+// <= 2^30): eight 32-bit words, one per plane, written at column k of the planes in LDS.  The digits are
+// transposed first (nibbles of the four magnitudes -> one word of four digits per plane), so that the
+// fp8 conversion and the sign run once per plane word.  Same codes as digit_codes element by element.
+__device__ __forceinline__ void store_planes_of_fixed(unsigned char* planes, int pstride, int k, const uint32_t (&w)[4]) {
+    uint32_t even[4], odd[4], te[4], to[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        even[e] = w[e] & 0x0F0F0F0Fu;              // digits 0, 2, 4, 6
+        odd[e] = (w[e] >> 4) & 0x070F0F0Fu;        // digits 1, 3, 5, 7 (bit 31 is the sign; the top digit is below 8)
+    }
+    transpose_bytes(even, te);
+    transpose_bytes(odd, to);
+    // sign bytes: 0x80 in byte e for a negative element e
+    const uint32_t sign = ((w[0] >> 24) & 0x80u) | ((w[1] >> 16) & 0x8000u) | ((w[2] >> 8) & 0x800000u) | (w[3] & 0x80000000u);
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        *reinterpret_cast<uint32_t*>(planes + (size_t)(2 * d) * pstride + k) = fp8_of_nibbles(te[d]) | sign;
+        *reinterpret_cast<uint32_t*>(planes + (size_t)(2 * d + 1) * pstride + k) = fp8_of_nibbles(to[d]) | sign;
+    }
+}
+__device__ __forceinline__ uint32_t fixed_word(float v, int ex) { return fixed_magnitude(v, ex) | (v < 0.f ? 0x80000000u : 0u); }
 
 // exponent ex with m < 2^ex (m >= 0 finite); 0 for m == 0
 __device__ __forceinline__ int bound_exponent(float m) {
@@ -152,6 +204,12 @@ tsvd_gemv_kernel(tsvd_gemv_args p) {
     float xv[ROUNDS][4];
     u32x4 zv[ROUNDS];
     int ex_in = 0, ex_z = 0;
+    // the scale (stage V) or bias (stage U) of the row this thread finishes, requested first: a load issued in the
+    // epilogue would cost a full round trip to memory at the very end of the launch
+    const int row_own = min((int)blockIdx.x * p.sw * 16 + (int)(threadIdx.x & 255), p.rows_out - 1);
+    float tail_own = 0.f;
+    if constexpr (STAGE_U) { if (p.bias) tail_own = p.bias[row_own]; }
+    else tail_own = p.S[row_own];
     if constexpr (STAGE_U) {
         ex_in = p.meta[0];
         // plane c is copied by threads c * 128 .. c * 128 + 127, 16 bytes each per round
@@ -225,18 +283,10 @@ tsvd_gemv_kernel(tsvd_gemv_args p) {
             const int k = 4 * (threadIdx.x + 1024 * r);
             if (k < p.Np) {
                 // four consecutive activations -> one 32-bit word per plane
-                uint32_t ev[4], od[4];
+                uint32_t w[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) digit_codes(xv[r][e], ex_in, ev[e], od[e]);
-#pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    const uint32_t we = ((ev[0] >> (8 * d)) & 0xFFu) | (((ev[1] >> (8 * d)) & 0xFFu) << 8) |
-                                        (((ev[2] >> (8 * d)) & 0xFFu) << 16) | (((ev[3] >> (8 * d)) & 0xFFu) << 24);
-                    const uint32_t wo = ((od[0] >> (8 * d)) & 0xFFu) | (((od[1] >> (8 * d)) & 0xFFu) << 8) |
-                                        (((od[2] >> (8 * d)) & 0xFFu) << 16) | (((od[3] >> (8 * d)) & 0xFFu) << 24);
-                    *reinterpret_cast<uint32_t*>(planes + (size_t)(2 * d) * pstride + k) = we;
-                    *reinterpret_cast<uint32_t*>(planes + (size_t)(2 * d + 1) * pstride + k) = wo;
-                }
+                for (int e = 0; e < 4; ++e) w[e] = fixed_word(xv[r][e], ex_in);
+                store_planes_of_fixed(planes, pstride, k, w);
             }
         }
     }
@@ -283,9 +333,9 @@ tsvd_gemv_kernel(tsvd_gemv_args p) {
         // acc = 2 * sum_k A[row][k] * fixed(in[k]): undo the factor 2 and the fixed-point scale
         const double val = combine_planes(sums + rl * 8) * pow2(ex_in - 31);
         if constexpr (STAGE_U) {
-            tsvd_store_y(p.y, (size_t)row * p.ldy, (float)(p.bias ? val + (double)p.bias[row] : val), p.out_bf16);
+            tsvd_store_y(p.y, (size_t)row * p.ldy, (float)(p.bias ? val + (double)tail_own : val), p.out_bf16);
         } else {
-            const float z = (float)((double)p.S[row] * val);
+            const float z = (float)((double)tail_own * val);
             uint32_t ev, od;
             digit_codes(z, ex_z, ev, od);
             unsigned char* dst = p.planes_out + row;
@@ -438,6 +488,358 @@ tsvd_gemv_fused_kernel(tsvd_gemv_fused_args p) {
     }
 }
 
+
+// ---- both stages of a single token in ONE launch of about one workgroup per compute unit -----------
+// Two launches cost two launch boundaries and two serial prologues (activations in, planes staged)
+// in a call that streams its weights in a few microseconds.  Here every workgroup
+//   1. requests x, then the tiles of its own slice of V AND all tiles of its rows of U (they stay in
+//      registers: at most ONEPASS_NU per wavefront), so the U stream is in flight from the start;
+//   2. digitises x, multiplies its slice of V, scales by S and publishes its rows of z;
+//   3. collects the whole z from the other workgroups, digitises it into LDS;
+//   4. multiplies its rows of U (tiles already there) and stores y.
+// Hand-over of z between workgroups (they run on different XCDs, each with its own L2): element k
+// of z travels as ONE 64-bit word {tag : 32 | sign-magnitude fixed point : 32} written and read with
+// device-scope atomic stores / loads (they bypass the non-coherent caches), so a reader that sees the
+// call's tag has the value, with no fence and no separate flag.  The tag is the value of a counter in
+// device memory that every workgroup reads at entry and increments when it is done: a call never sees
+// a tag left by an earlier one (the words of a call carry tags from [c, c + grid), the next call's
+// start at c + grid), and a captured launch replays correctly because the host passes no per-call state.
+// The buffer and the counter belong to the handle (zeroed at tsvd_pack); calls of one handle must
+// not overlap on the device (the dispatcher keeps them on one stream).
+// No workgroup ever depends on another one for progress: a reader polls at most spin_limit times for
+// a slice and then computes that slice itself from V and x (same arithmetic, so same bits), straight
+// into its LDS planes.  Workgroups that are not resident yet (a busy GPU) therefore cost time, never
+// a hang, and a launch of any size drains.
+#define ONEPASS_XR 2      // x: rounds of 4096 elements        (Np <= 8192)
+#define ONEPASS_ZR 2      // z: rounds of 4096 elements        (Kp <= 8192)
+template <int NV, int NU>
+__global__ void __launch_bounds__(1024)
+tsvd_gemv_onepass_kernel(tsvd_gemv_onepass_args p) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 15, g = lane >> 4;
+    const int xstride = p.Np + 16, zstride = p.Kp + 16;
+    unsigned char* xplanes = smem;                                                       // [8][Np + 16]
+    unsigned char* zplanes = smem + (((size_t)8 * xstride + 255) & ~(size_t)255);        // [8][Kp + 16]
+    float* red = reinterpret_cast<float*>(zplanes + (((size_t)8 * zstride + 255) & ~(size_t)255));   // [16][256]
+    float* sums = red + 16 * 256;                                                        // [256][8]
+    float* scratch = sums + 256 * 8;                                                     // [16]
+    unsigned* missing = reinterpret_cast<unsigned*>(scratch + 16);                       // [8]: bit per slice
+    const int kw_v = 1 << p.kwl_v, kw_u = 1 << p.kwl_u;
+    const int sidx_v = wave >> p.kwl_v, q_v = wave & (kw_v - 1);
+    const int sidx_u = wave >> p.kwl_u, q_u = wave & (kw_u - 1);
+    const int strip_u = blockIdx.x * p.sw_u + sidx_u;
+    const bool active_u = sidx_u < p.sw_u && strip_u < p.strips_u;
+    const u32x4* tv = reinterpret_cast<const u32x4*>(p.tiles_v) + lane;
+    const u32x4* tu = reinterpret_cast<const u32x4*>(p.tiles_u) + ((size_t)(active_u ? strip_u : 0) * p.nkt_u) * 64 + lane;
+    TICK(0);
+    const long long wave_t0 = p.clocks ? wall_clock64() : 0;
+
+    // ---- loads, in the order of need: the call's tag and x, then (once x is here) the weight tiles
+    const unsigned tag = __hip_atomic_load(p.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    float xv[ONEPASS_XR][4];
+#pragma unroll
+    for (int r = 0; r < ONEPASS_XR; ++r) {
+        const int k = 4 * (threadIdx.x + 1024 * r);
+        if (p.x_vec) {
+            const int kc = min(k, p.N - 4);
+            if (p.x_is_bf16) {
+                const u32x2 v = *reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(p.x) + kc);
+                xv[r][0] = __uint_as_float(v.x << 16); xv[r][1] = __uint_as_float(v.x & 0xFFFF0000u);
+                xv[r][2] = __uint_as_float(v.y << 16); xv[r][3] = __uint_as_float(v.y & 0xFFFF0000u);
+            } else {
+                const f32x4 v = *reinterpret_cast<const f32x4*>(static_cast<const float*>(p.x) + kc);
+                xv[r][0] = v.x; xv[r][1] = v.y; xv[r][2] = v.z; xv[r][3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const size_t off = (size_t)min(k + e, p.N - 1) * p.ldx;
+                xv[r][e] = p.x_is_bf16 ? __uint_as_float(((uint32_t) static_cast<const uint16_t*>(p.x)[off]) << 16)
+                                       : static_cast<const float*>(p.x)[off];
+            }
+        }
+    }
+    // scale of the row of z and bias of the row of y that this thread finishes (vector-memory results return in
+    // issue order: a load issued after the weight tiles would hold its consumer back until all of them are in)
+    const float s_own = p.S[min((int)blockIdx.x * p.sw_v * 16 + (int)(threadIdx.x & 255), p.Kp - 1)];
+    const float bias_own = p.bias ? p.bias[min((int)blockIdx.x * p.sw_u * 16 + (int)(threadIdx.x & 255), p.M - 1)] : 0.f;
+    // tiles of slice j of V for this wavefront (clamped, unconditional loads)
+    u32x4 pv[NV];
+    auto load_v = [&](int j) {
+        const int strip = min(j * p.sw_v + sidx_v, p.strips_v - 1);
+#pragma unroll
+        for (int n = 0; n < NV; ++n)
+            pv[n] = __builtin_nontemporal_load(tv + ((size_t)strip * p.nkt_v + min(q_v + n * kw_v, p.nkt_v - 1)) * 64);
+    };
+    // The tiles of U are requested in batches, so that the memory system always has work but the latency-critical
+    // answers (the tiles of V, the polls for z) never queue behind all of U: a quarter with the tiles of V, a
+    // quarter once x is digitised, a quarter once z is published, the rest around the polls.
+    constexpr int NU1 = (NU + 3) / 4, NU2 = NU / 2, NU3 = NU2 + NU / 4;
+    u32x4 pu[NU];
+    auto load_u = [&](int from, int to) {
+#pragma unroll
+        for (int n = 0; n < NU; ++n)
+            if (n >= from && n < to) pu[n] = __builtin_nontemporal_load(tu + (size_t)min(q_u + n * kw_u, p.nkt_u - 1) * 64);
+    };
+    load_v(blockIdx.x);
+    load_u(0, NU1);
+    TICK(1);
+
+    // ---- x -> digit planes in LDS
+    float m = 0.f;
+#pragma unroll
+    for (int r = 0; r < ONEPASS_XR; ++r) {
+        const int k = 4 * (threadIdx.x + 1024 * r);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            xv[r][e] = k + e < p.N ? xv[r][e] : 0.f;
+            m = fmaxf(m, fabsf(xv[r][e]));
+        }
+    }
+    m = wave_max(m);
+    if (lane == 0) scratch[wave] = m;
+    if (threadIdx.x < 8) missing[threadIdx.x] = 0u;
+    if (p.clocks && lane == 0) reinterpret_cast<long long*>(sums)[wave] = wave_t0;
+    __syncthreads();
+    TICK(9);
+    if (p.clocks && threadIdx.x == 0) {
+        long long mx = 0;
+        for (int w2 = 0; w2 < 16; ++w2) mx = max(mx, reinterpret_cast<long long*>(sums)[w2]);
+        p.clocks[blockIdx.x * 16 + 8] = mx;
+    }
+    m = wave_max(scratch[lane & 15]);
+    const int ex_x = bound_exponent(m);
+    const int ex_z = bound_exponent(p.bound_V * m) + 1;   // one more bit for the rounding of the bound itself
+#pragma unroll
+    for (int r = 0; r < ONEPASS_XR; ++r) {
+        const int k = 4 * (threadIdx.x + 1024 * r);
+        if (k < p.Np) {
+            uint32_t w[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) w[e] = fixed_word(xv[r][e], ex_x);
+            store_planes_of_fixed(xplanes, xstride, k, w);
+        }
+    }
+    TICK(10);
+    __syncthreads();
+    load_u(NU1, NU2);
+    TICK(2);
+
+    // ---- slice j of z = S * (V x) from the tiles in pv: published (own slice) or written into zplanes (help)
+    const unsigned char* xlane = xplanes + (size_t)(i & 7) * xstride + 32 * g;
+    auto v_slice = [&](int j, bool publish) {
+        float s_row = s_own;
+        if (!publish) s_row = p.S[min(j * p.sw_v * 16 + (int)(threadIdx.x & 255), p.Kp - 1)];
+        const bool active = sidx_v < p.sw_v && j * p.sw_v + sidx_v < p.strips_v;
+        f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int n = 0; n < NV; ++n) {
+            const int T = q_v + n * kw_v;
+            if (active && T < p.nkt_v) tile_steps(pv[n], xlane + T * 256, acc0, acc1);
+        }
+        if (i < 8) {
+            float* mine = red + (size_t)wave * 256;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) mine[(4 * g + v) * 16 + i] = acc0[v] + acc1[v];
+        }
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < p.sw_v * 128; idx += 1024) {
+            const int rl = idx >> 3, pc = idx & 7;
+            const float* src = red + (size_t)((rl >> 4) * kw_v) * 256 + (rl & 15) * 16 + pc;
+            float part = 0.f;
+            for (int qq = 0; qq < kw_v; ++qq) part += src[qq * 256];      // integers < 2^24: exact
+            sums[idx] = part;
+        }
+        __syncthreads();
+        for (int rl = threadIdx.x; rl < p.sw_v * 16; rl += 1024) {
+            const int row = j * p.sw_v * 16 + rl;
+            if (row >= p.Kp) continue;
+            const double val = combine_planes(sums + rl * 8) * pow2(ex_x - 31);
+            const float z = (float)((double)s_row * val);
+            const uint32_t mag = fixed_magnitude(z, ex_z);
+            if (publish) {
+                const unsigned long long word = ((unsigned long long)tag << 32) | mag | (z < 0.f ? 0x80000000u : 0u);
+                __hip_atomic_store(p.zbuf + row, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                uint32_t ev, od;
+                codes_of_fixed(mag, z < 0.f, ev, od);
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    zplanes[(size_t)(2 * d) * zstride + row] = (unsigned char)(ev >> (8 * d));
+                    zplanes[(size_t)(2 * d + 1) * zstride + row] = (unsigned char)(od >> (8 * d));
+                }
+            }
+        }
+        __syncthreads();
+    };
+    v_slice(blockIdx.x, true);
+    TICK(3);
+
+    // ---- collect z: thread t owns elements 4 (t + 1024 r) .. + 3
+    unsigned long long zw[ONEPASS_ZR][4] = {};
+    bool have = p.spin_limit >= 0;
+    auto poll = [&]() {
+#pragma unroll
+        for (int r = 0; r < ONEPASS_ZR; ++r) {
+            const int k = min(4 * (threadIdx.x + 1024 * r), p.Kp - 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) zw[r][e] = __hip_atomic_load(p.zbuf + k + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    };
+    // One more batch of U, then the first poll.  While a poll fails (a slice of another workgroup is not there yet),
+    // every retry is preceded by ONE more tile request per wavefront: the memory system stays busy, and the retry
+    // queues behind 4 MB instead of behind the rest of U.  The loop is uniform over the wavefront.
+    load_u(NU2, NU3);
+    int issued = NU3;
+    if (p.spin_limit >= 0) {
+        for (int spin = 0;; ++spin) {
+            poll();
+            have = true;
+#pragma unroll
+            for (int r = 0; r < ONEPASS_ZR; ++r)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) have = have && (unsigned)(zw[r][e] >> 32) == tag;
+            if (__builtin_amdgcn_ballot_w64(!have) == 0ull || spin >= p.spin_limit) break;
+#pragma unroll
+            for (int n = 0; n < NU; ++n)
+                if (n >= NU3 && n == issued) pu[n] = __builtin_nontemporal_load(tu + (size_t)min(q_u + n * kw_u, p.nkt_u - 1) * 64);
+            ++issued;
+            __builtin_amdgcn_s_sleep(1);
+        }
+    }
+#pragma unroll
+    for (int n = 0; n < NU; ++n)
+        if (n >= NU3 && n >= issued) pu[n] = __builtin_nontemporal_load(tu + (size_t)min(q_u + n * kw_u, p.nkt_u - 1) * 64);
+    const int slice_rows = p.sw_v * 16;
+#pragma unroll
+    for (int r = 0; r < ONEPASS_ZR; ++r) {
+        const int k = 4 * (threadIdx.x + 1024 * r);
+        if (k < p.Kp) {
+            uint32_t w[4];
+            bool all = p.spin_limit >= 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                w[e] = (uint32_t)zw[r][e];
+                all = all && (unsigned)(zw[r][e] >> 32) == tag;
+            }
+            if (all) {
+                store_planes_of_fixed(zplanes, zstride, k, w);
+            } else {
+                // (a slice holds a multiple of 16 rows, so the four elements lie in one slice)
+                const int j = k / slice_rows;
+                atomicOr(&missing[j >> 5], 1u << (j & 31));
+            }
+        }
+    }
+    __syncthreads();
+    TICK(4);
+    // ---- slices that did not arrive in time: compute them here (uniform over the workgroup)
+    for (int wd = 0; wd < 8; ++wd) {
+        unsigned bits = missing[wd];
+        while (bits) {
+            const int j = 32 * wd + __builtin_ctz(bits);
+            bits &= bits - 1;
+            load_v(j);
+            v_slice(j, false);
+        }
+    }
+    TICK(5);
+
+    // ---- y = U z for this workgroup's rows, tiles from registers
+    const unsigned char* zlane = zplanes + (size_t)(i & 7) * zstride + 32 * g;
+    {
+        f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int n = 0; n < NU; ++n) {
+            const int T = q_u + n * kw_u;
+            if (active_u && T < p.nkt_u) tile_steps(pu[n], zlane + T * 256, acc0, acc1);
+        }
+        if (i < 8) {
+            float* mine = red + (size_t)wave * 256;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) mine[(4 * g + v) * 16 + i] = acc0[v] + acc1[v];
+        }
+    }
+    __syncthreads();
+    TICK(6);
+    for (int idx = threadIdx.x; idx < p.sw_u * 128; idx += 1024) {
+        const int rl = idx >> 3, pc = idx & 7;
+        const float* src = red + (size_t)((rl >> 4) * kw_u) * 256 + (rl & 15) * 16 + pc;
+        float part = 0.f;
+        for (int qq = 0; qq < kw_u; ++qq) part += src[qq * 256];
+        sums[idx] = part;
+    }
+    __syncthreads();
+    for (int rl = threadIdx.x; rl < p.sw_u * 16; rl += 1024) {
+        const int row = blockIdx.x * p.sw_u * 16 + rl;
+        if (row >= p.M) continue;
+        const double val = combine_planes(sums + rl * 8) * pow2(ex_z - 31);
+        tsvd_store_y(p.y, (size_t)row * p.ldy, (float)(p.bias ? val + (double)bias_own : val), p.out_bf16);
+    }
+    // this workgroup is done with the call's tag (no result wanted: fire and forget)
+    if (threadIdx.x == 0) (void)__hip_atomic_fetch_add(p.counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    TICK(7);
+}
+
+namespace {
+size_t onepass_lds_bytes(long long Np, long long Kp) {
+    return ((8 * (size_t)(Np + 16) + 255) & ~(size_t)255) + ((8 * (size_t)(Kp + 16) + 255) & ~(size_t)255) +
+           (16 * 256 + 256 * 8 + 16 + 8) * sizeof(float);
+}
+// tiles per wavefront of a stage for a workgroup shape
+int onepass_tiles(int nkt, int kwl) { return (nkt + (1 << kwl) - 1) >> kwl; }
+}  // namespace
+
+// Shape of the one-launch call: grid, strips per workgroup and contraction splits of both stages.
+// Returns false when the problem does not fit (tiles per wavefront beyond the register budget, LDS).
+bool tsvd_gemv_onepass_shape(long long M, long long Mp, long long Kp, long long Np, int cus, tsvd_gemv_onepass_args* a) {
+    (void)Mp;
+    if (Np > 4096 * ONEPASS_XR || Kp > 4096 * ONEPASS_ZR || onepass_lds_bytes(Np, Kp) > TSVD_SKINNY_MAX_LDS) return false;
+    const int strips_v = (int)(Kp / 16), strips_u = (int)((M + 15) / 16);
+    const int nkt_v = (int)(Np / 256), nkt_u = (int)(Kp / 256);
+    const int G = std::min(std::min(cus, 256), std::max(strips_v, strips_u));
+    const int sw_v = (strips_v + G - 1) / G, sw_u = (strips_u + G - 1) / G;
+    if (sw_v > 16 || sw_u > 16) return false;
+    auto splits = [](int sw, int nkt) {
+        int kl = 0;
+        while ((sw << (kl + 1)) <= 16 && (2 << kl) <= nkt) ++kl;
+        return kl;
+    };
+    const int kwl_v = splits(sw_v, nkt_v), kwl_u = splits(sw_u, nkt_u);
+    const int nv = onepass_tiles(nkt_v, kwl_v), nu = onepass_tiles(nkt_u, kwl_u);
+    if (nv > 4 || nu > 16 || (nv > 2 && nu > 8)) return false;       // register budget of 1024-thread workgroups
+    if (a) {
+        a->strips_v = strips_v; a->nkt_v = nkt_v; a->sw_v = sw_v; a->kwl_v = kwl_v;
+        a->strips_u = strips_u; a->nkt_u = nkt_u; a->sw_u = sw_u; a->kwl_u = kwl_u;
+        a->grid = G;
+    }
+    return true;
+}
+
+hipError_t tsvd_launch_gemv_onepass(const tsvd_gemv_onepass_args& a, hipStream_t stream) {
+    if (a.grid < 1 || a.grid > 256 || a.sw_v < 1 || a.sw_u < 1 || (a.sw_v << a.kwl_v) > 16 || (a.sw_u << a.kwl_u) > 16 ||
+        a.grid * a.sw_v < a.strips_v || a.grid * a.sw_u < a.strips_u || a.Np > 4096 * ONEPASS_XR || a.Kp > 4096 * ONEPASS_ZR ||
+        a.Np != a.nkt_v * 256 || a.Kp != a.nkt_u * 256 || a.Kp != a.strips_v * 16 || !a.zbuf || !a.counter)
+        return hipErrorInvalidValue;
+    const int nv = onepass_tiles(a.nkt_v, a.kwl_v), nu = onepass_tiles(a.nkt_u, a.kwl_u);
+    if (nv > 4 || nu > 16 || (nv > 2 && nu > 8)) return hipErrorInvalidValue;
+    const size_t lds = onepass_lds_bytes(a.Np, a.Kp);
+    const dim3 grid(a.grid), block(1024);
+#define ONEPASS_LAUNCH(NV_, NU_) hipLaunchKernelGGL((tsvd_gemv_onepass_kernel<NV_, NU_>), grid, block, lds, stream, a)
+    if (nv <= 2) {
+        if (nu <= 4) ONEPASS_LAUNCH(2, 4);
+        else if (nu <= 8) ONEPASS_LAUNCH(2, 8);
+        else ONEPASS_LAUNCH(2, 16);
+    } else {
+        if (nu <= 4) ONEPASS_LAUNCH(4, 4);
+        else if (nu <= 8) ONEPASS_LAUNCH(4, 8);
+        else return hipErrorInvalidValue;
+    }
+#undef ONEPASS_LAUNCH
+    return hipGetLastError();
+}
+
 size_t gemv_fused_lds_bytes(long long Np, long long Kp) {
     return ((8 * (size_t)(Np + 16) + 255) & ~(size_t)255) + ((8 * (size_t)(Kp + 16) + 255) & ~(size_t)255) + (16 * 128 + 64) * sizeof(float);
 }
@@ -472,6 +874,11 @@ hipError_t tsvd_gemv_init() {
     hipError_t e;
     if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemv_fused_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  TSVD_SKINNY_MAX_LDS)) != hipSuccess) return e;
+#define ONEPASS_ATTR(NV_, NU_) \
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemv_onepass_kernel<NV_, NU_>), \
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, TSVD_SKINNY_MAX_LDS)) != hipSuccess) return e;
+    ONEPASS_ATTR(2, 4) ONEPASS_ATTR(2, 8) ONEPASS_ATTR(2, 16) ONEPASS_ATTR(4, 4) ONEPASS_ATTR(4, 8)
+#undef ONEPASS_ATTR
     if ((e = init_one<false, 1>()) != hipSuccess) return e;
     if ((e = init_one<false, 2>()) != hipSuccess) return e;
     if ((e = init_one<false, 4>()) != hipSuccess) return e;

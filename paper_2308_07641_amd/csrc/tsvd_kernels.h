@@ -65,6 +65,24 @@ struct tsvd_gemv_fused_args {
     const float* S; float bound_V;
     void* y; long long ldy; const float* bias; int out_bf16;
 };
+// Both stages of a single token in ONE launch of about one workgroup per compute unit (tsvd_gemv.hip):
+// workgroup b computes slice b of z (sw_v strips of V) and rows [b sw_u 16, ...) of y; z crosses
+// between workgroups as tagged 64-bit words in zbuf.
+struct tsvd_gemv_onepass_args {
+    const void* tiles_v; int strips_v, nkt_v, sw_v, kwl_v;   // V: Kp/16 strips, Np/256 tiles; workgroup = sw_v strips x 2^kwl_v splits
+    const void* tiles_u; int strips_u, nkt_u, sw_u, kwl_u;   // U: ceil(M/16) strips, Kp/256 tiles
+    int grid;                                                // workgroups (<= 256)
+    int N, Np, Kp, M;
+    const void* x; int x_is_bf16; int x_vec; long long ldx;
+    const float* S; float bound_V;
+    unsigned long long* zbuf;                                // [Kp] {tag : 32 | fixed-point z : 32}, handle-owned
+    unsigned* counter;                                       // tag source, handle-owned
+    int spin_limit;                                          // polls for a slice before computing it locally; < 0: never poll
+    void* y; long long ldy; const float* bias; int out_bf16;
+    long long* clocks;                                       // optional tuning aid: [grid][16] phase timestamps, or null
+};
+bool tsvd_gemv_onepass_shape(long long M, long long Mp, long long Kp, long long Np, int cus, tsvd_gemv_onepass_args* a);
+hipError_t tsvd_launch_gemv_onepass(const tsvd_gemv_onepass_args& a, hipStream_t stream);
 bool tsvd_gemv_fused_fits(long long Mp, long long Kp, long long Np);
 hipError_t tsvd_launch_gemv_fused(const tsvd_gemv_fused_args& a, hipStream_t stream);
 hipError_t tsvd_gemv_init();

@@ -306,6 +306,66 @@ def test_small_single_token_fused_launch(tsvd, M, N, K, x_dtype, fused):
         assert not np.any(y)
 
 
+# ---- single token, both stages in one launch (z handed over between workgroups as tagged words)
+ONEPASS_SHAPES = [(300, 513, 270), (1000, 700, 200), (2100, 1030, 1500), (4100, 2050, 4000), (700, 8000, 520),
+                  (8200, 1000, 8100)]
+
+
+@pytest.mark.parametrize("mode", ["onepass", "onepass_help_all", "onepass_poll_once", "two_launches"])
+@pytest.mark.parametrize("M,N,K", ONEPASS_SHAPES)
+def test_single_token_one_launch(tsvd, M, N, K, mode):
+    """The one-launch kernel against the oracle: exact on integer instances, 1e-5 / 2e-3 on random ones, with the
+    slices of z arriving from the other workgroups (default), never polled for (every workgroup computes all of z
+    itself: the path taken when a slice does not arrive in time), polled for exactly once, and on the two-launch
+    kernels that other streams fall back to.  Several calls in a row reuse the handle's hand-over buffer."""
+    import torch
+    tsvd.tsvd_tuning_set("TSVD_GEMV_FUSED", 0)
+    tsvd.tsvd_tuning_set("TSVD_GEMV_ONEPASS", 0 if mode == "two_launches" else 1)      # (off by default: measured slower)
+    if mode == "onepass_help_all":
+        tsvd.tsvd_tuning_set("TSVD_SPIN_LIMIT", -1)
+    elif mode == "onepass_poll_once":
+        tsvd.tsvd_tuning_set("TSVD_SPIN_LIMIT", 0)
+    print(f"case one launch M={M} N={N} K={K} {mode}", flush=True)
+    for x_dtype in ("bf16", "f32"):
+        i = workloads.make_integer_inputs(M, N, K, 1, 0.5, x_dtype, seed=5 * M + N + K)
+        ref = oracle.forward(i.U, i.S, i.V, i.X)
+        h = tsvd.tsvd_pack(i.U, i.S, i.V)
+        x = to_device(i)
+        for rep in range(3):                                   # the tag of the hand-over buffer advances per call
+            y = torch.full((M, 1), float("nan"), dtype=torch.float32, device=x.device)
+            tsvd.tsvd_forward(h, x * float(rep + 1), y)
+            torch.cuda.synchronize()
+            assert np.array_equal(y.cpu().numpy().astype(np.float64), ref * (rep + 1)), f"{x_dtype} call {rep}"
+        tsvd.tsvd_free(h)
+        j = workloads.make_inputs(M, N, K, 1, 0.6, 0.02, x_dtype, seed=6 * M + N + K)
+        y, h = run_forward(j)
+        tsvd.tsvd_free(h)
+        assert rel_err(y, oracle.forward(j.U, j.S, j.V, j.X)) <= (1e-5 if x_dtype == "f32" else 2e-3)
+
+
+def test_single_token_one_launch_second_stream_falls_back(tsvd):
+    """The hand-over buffer belongs to the first stream that uses the handle for a single token; a call on another
+    stream takes the two-launch kernels (its own workspace), so concurrent use stays correct."""
+    import torch
+    tsvd.tsvd_tuning_set("TSVD_GEMV_ONEPASS", 1)
+    i = workloads.make_integer_inputs(2100, 1030, 1500, 1, 0.5, "bf16", seed=77)
+    ref = oracle.forward(i.U, i.S, i.V, i.X)
+    h = tsvd.tsvd_pack(i.U, i.S, i.V)
+    x = to_device(i)
+    side = torch.cuda.Stream()
+    ws = [torch.empty(tsvd.tsvd_workspace_bytes(h, 1, tsvd.TSVD_BF16), dtype=torch.uint8, device=x.device) for _ in range(2)]
+    y0 = torch.full((2100, 1), float("nan"), dtype=torch.float32, device=x.device)
+    y1 = torch.full((2100, 1), float("nan"), dtype=torch.float32, device=x.device)
+    torch.cuda.synchronize()
+    for _ in range(4):
+        tsvd.tsvd_forward(h, x, y0, workspace=ws[0])
+        tsvd.tsvd_forward(h, x, y1, workspace=ws[1], stream=side.cuda_stream)
+    torch.cuda.synchronize()
+    tsvd.tsvd_free(h)
+    assert np.array_equal(y0.cpu().numpy().astype(np.float64), ref)
+    assert np.array_equal(y1.cpu().numpy().astype(np.float64), ref)
+
+
 def test_general_single_token_kernel(tsvd):
     """The slab kernel that serves contraction lengths beyond the fast single-token kernel's
     limits, forced on ordinary sizes (exact instance, then a random one per activation type)."""
