@@ -108,13 +108,15 @@ def round_to_bf16(y) -> np.ndarray:
     return np.ldexp(np.rint(np.ldexp(m, 8)), e - 8)
 
 
-def forward_layer(U, S, V, X, bias=None, x_layout="feature_major", y_dtype="f32") -> np.ndarray:
+def forward_layer(U, S, V, X, bias=None, x_layout="feature_major", y_dtype="f32", y_layout="feature_major") -> np.ndarray:
     """The map as a linear layer uses it: Y = U (diag(S) (V X)) + bias, per token.
 
     The paper's listing of a converted network (supplement) shows its ternary-SVD linear
     layers with bias=True: the bias [M] is added to every token's output.  x_layout
     "token_major" takes X as [B,N] (one row per token).  y_dtype "bf16" rounds the result
-    (after the bias) to the nearest bf16 value; the return is always [M,B] float64.
+    (after the bias) to the nearest bf16 value; the return is float64, [M,B] or, with y_layout
+    "token_major", [B,M]: one row per token, written out token by token below (row b of the
+    result is the layer's output for token b, i.e. for column b / row b of X).
     """
     X = np.asarray(X)
     if x_layout == "token_major":
@@ -131,6 +133,13 @@ def forward_layer(U, S, V, X, bias=None, x_layout="feature_major", y_dtype="f32"
         Y = round_to_bf16(Y)
     elif y_dtype != "f32":
         raise ValueError("y_dtype")
+    if y_layout == "token_major":
+        out = np.empty((Y.shape[1], Y.shape[0]), dtype=np.float64)
+        for b in range(Y.shape[1]):
+            out[b, :] = Y[:, b]
+        return out
+    if y_layout != "feature_major":
+        raise ValueError("y_layout")
     return Y
 
 

@@ -292,3 +292,25 @@ def test_layer_form_bias_layout_and_output_type():
     assert np.max(np.abs(yb - got) / np.abs(got)) > 2.0 ** -11           # and it does round
     assert np.array_equal(oracle.round_to_bf16(yb), yb)
     assert np.array_equal(workloads.bf16_bits_to_f32(workloads.f32_to_bf16_bits(yb.astype(np.float32))).astype(np.float64), yb)
+
+
+def test_layer_form_token_major_output_is_one_row_per_token():
+    """y_layout "token_major": row b of the result is the dense layer applied to token b alone (library matmul on
+    the explicit W' = U diag(S) V, one token at a time), for both layouts of x; a transposed bias or a swapped
+    index would fail on this non-square instance."""
+    rng = np.random.default_rng(31)
+    M, N, K, B = 7, 5, 9, 4
+    U = rng.integers(-1, 2, size=(M, K)).astype(np.int8)
+    V = rng.integers(-1, 2, size=(K, N)).astype(np.int8)
+    S = rng.standard_normal(K).astype(np.float32)
+    X = rng.standard_normal((N, B)).astype(np.float32)
+    bias = rng.standard_normal(M).astype(np.float32)
+    W = (U.astype(np.float64) * S.astype(np.float64)[None, :]) @ V.astype(np.float64)
+    want = np.stack([W @ X[:, b].astype(np.float64) + bias.astype(np.float64) for b in range(B)])     # [B, M]
+    got = oracle.forward_layer(U, S, V, X, bias=bias, y_layout="token_major")
+    assert got.shape == (B, M) and np.allclose(got, want, rtol=1e-12, atol=1e-12)
+    got2 = oracle.forward_layer(U, S, V, np.ascontiguousarray(X.T), bias=bias, x_layout="token_major", y_layout="token_major")
+    assert np.array_equal(got, got2)
+    assert np.array_equal(got, oracle.forward_layer(U, S, V, X, bias=bias).T)
+    with pytest.raises(ValueError):
+        oracle.forward_layer(U, S, V, X, y_layout="rows")
