@@ -137,6 +137,20 @@ tsvd_status tsvd_forward_ex(const tsvd_handle* h, const void* x_dev, tsvd_dtype 
                             int64_t B, int64_t ldx, const float* bias_dev, void* y_dev, tsvd_dtype y_dtype,
                             int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- forward with a choice of both layouts -------------------------------------------------
+ *
+ * tsvd_forward_ex with the layout of y chosen as well:
+ *   y_layout : TSVD_FEATURE_MAJOR: y_dev is [M][B], ldy >= B (as above);
+ *              TSVD_TOKEN_MAJOR:   y_dev is [B][M], ldy >= M: one row per token, what a following
+ *              token-major layer reads.  It is written in place by the last kernel of the call (each
+ *              lane of a result block stores four consecutive rows of one token: 16-byte stores when
+ *              ldy is a multiple of 4 and y_dev is 16-byte aligned), not by a transposition pass.
+ * Everything else is as for tsvd_forward_ex, which is this call with a feature-major y.
+ */
+tsvd_status tsvd_forward_io(const tsvd_handle* h, const void* x_dev, tsvd_dtype x_dtype, tsvd_layout x_layout,
+                            int64_t B, int64_t ldx, const float* bias_dev, void* y_dev, tsvd_dtype y_dtype,
+                            tsvd_layout y_layout, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- forward for callers that cannot allocate -------------------------------------------
  *
  * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc:

@@ -48,6 +48,7 @@ size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 struct out_opts {
     const float* bias;   // device [M] or null
     int out_bf16;
+    int token_major;     // y is [B][ldy] instead of [M][ldy]
 };
 
 // Token-major activations [B][ldx] -> feature-major [N][ldt] (ldt a multiple of 8 elements, the
@@ -246,8 +247,10 @@ tsvd_status forward_skinny(const tsvd_handle* h, const void* x, tsvd_dtype x_dty
         // one token at a time through the fast kernels (each pass re-reads the weights)
         for (int64_t b0 = 0; b0 < B; ++b0) {
             tsvd_status gst = TSVD_OK;
+            // one token's output: column b0 of y [M][ldy], or row b0 of y [B][ldy] (then consecutive in memory)
+            uint8_t* yb = static_cast<uint8_t*>(y) + (oo.token_major ? (size_t)b0 * (size_t)ldy : (size_t)b0) * yelt;
             if (!try_gemv(h, static_cast<const uint8_t*>(x) + (size_t)b0 * xelt, x_dtype, ldx,
-                          static_cast<uint8_t*>(y) + (size_t)b0 * yelt, ldy, oo, meta, planes, stream, &gst))
+                          yb, oo.token_major ? 1 : ldy, oo, meta, planes, stream, &gst))
                 return TSVD_EUNSUPPORTED;
             if (gst != TSVD_OK) return gst;
         }
@@ -285,8 +288,9 @@ tsvd_status forward_skinny(const tsvd_handle* h, const void* x, tsvd_dtype x_dty
         u.ld_in = hd.Kp;
         u.tokens = tokens;
         u.meta_in = meta;
-        u.out = static_cast<uint8_t*>(y) + (size_t)b0 * yelt;
+        u.out = static_cast<uint8_t*>(y) + (oo.token_major ? (size_t)b0 * (size_t)ldy : (size_t)b0) * yelt;
         u.ld_out = ldy;
+        u.out_token_major = oo.token_major;
         u.rows_out = (int)hd.M;
         u.bias = oo.bias;
         u.out_bf16 = oo.out_bf16;
@@ -378,8 +382,9 @@ tsvd_status forward_mid(const tsvd_handle* h, const void* x, int64_t B, int64_t 
         a.kvalid = (int)hd.Kp;
         a.act_bytes = (unsigned)((size_t)hd.Kp * 32);
         a.S = nullptr;
-        a.out = static_cast<uint8_t*>(y) + (size_t)b0 * (oo.out_bf16 ? 2 : 4);
+        a.out = static_cast<uint8_t*>(y) + (oo.token_major ? (size_t)b0 * (size_t)ldy : (size_t)b0) * (oo.out_bf16 ? 2 : 4);
         a.ld_out = ldy;
+        a.out_token_major = oo.token_major;
         a.rows_valid = (int)hd.M;
         a.bias = oo.bias;
         a.out_bf16 = oo.out_bf16;
@@ -548,7 +553,16 @@ extern "C" size_t tsvd_workspace_bytes(const tsvd_handle* h, int64_t B, tsvd_dty
 extern "C" tsvd_status tsvd_forward_ex(const tsvd_handle* h, const void* x_dev, tsvd_dtype x_dtype, tsvd_layout x_layout,
                                        int64_t B, int64_t ldx, const float* bias_dev, void* y_dev, tsvd_dtype y_dtype,
                                        int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
-    if (!h || !x_dev || !y_dev || B <= 0 || ldy < B) return TSVD_EINVAL;
+    return tsvd_forward_io(h, x_dev, x_dtype, x_layout, B, ldx, bias_dev, y_dev, y_dtype, TSVD_FEATURE_MAJOR, ldy, workspace,
+                           workspace_bytes, stream);
+}
+
+extern "C" tsvd_status tsvd_forward_io(const tsvd_handle* h, const void* x_dev, tsvd_dtype x_dtype, tsvd_layout x_layout,
+                                       int64_t B, int64_t ldx, const float* bias_dev, void* y_dev, tsvd_dtype y_dtype,
+                                       tsvd_layout y_layout, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!h || !x_dev || !y_dev || B <= 0) return TSVD_EINVAL;
+    if (y_layout != TSVD_FEATURE_MAJOR && y_layout != TSVD_TOKEN_MAJOR) return TSVD_EINVAL;
+    if (ldy < (y_layout == TSVD_TOKEN_MAJOR ? h->hd.M : B)) return TSVD_EINVAL;
     if (x_dtype != TSVD_F32 && x_dtype != TSVD_BF16) return TSVD_EINVAL;
     if (y_dtype != TSVD_F32 && y_dtype != TSVD_BF16) return TSVD_EINVAL;
     if (x_layout != TSVD_FEATURE_MAJOR && x_layout != TSVD_TOKEN_MAJOR) return TSVD_EINVAL;
@@ -580,7 +594,7 @@ extern "C" tsvd_status tsvd_forward_ex(const tsvd_handle* h, const void* x_dev, 
         ws = hm->scratch;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const out_opts oo = {bias_dev, y_dtype == TSVD_BF16};
+    const out_opts oo = {bias_dev, y_dtype == TSVD_BF16, y_layout == TSVD_TOKEN_MAJOR};
     if (x_layout == TSVD_TOKEN_MAJOR) {
         // one pass that rewrites x as [N][B rounded up to 8] at the front of the workspace; the rows
         // of the copy are 16-byte aligned, so every kernel family takes its fast loads
@@ -622,6 +636,7 @@ extern "C" tsvd_status tsvd_forward_ex(const tsvd_handle* h, const void* x_dev, 
         g.ldy = ldy;
         g.bias = oo.bias;
         g.out_bf16 = oo.out_bf16;
+        g.y_token_major = oo.token_major;
         g.ws = ws;
         g.cu_count = h->cu_count;
         g.clocks = h->clocks;

@@ -50,3 +50,28 @@ __device__ __forceinline__ void tsvd_store_row_pair_bf16(void* y, long long ld, 
         }
     }
 }
+
+// Token-major output y[token][row]: the lane of a 16 x 16 result block that holds token `token` of rows
+// row0 .. row0 + 3 (row0 a multiple of 4) writes them side by side: one 16-byte (fp32) or 8-byte (bf16)
+// store when the four rows exist and vec_ok says that ld is a multiple of 4 elements and y is 16-byte
+// aligned; element by element otherwise.
+__device__ __forceinline__ void tsvd_store_token_major4(void* y, long long ld, int token, int row0, int rows_valid,
+                                                        float v0, float v1, float v2, float v3, int out_bf16, bool vec_ok) {
+    typedef float f32x4_t __attribute__((ext_vector_type(4)));
+    typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+    const size_t at = (size_t)token * ld + row0;
+    if (vec_ok && row0 + 3 < rows_valid) {
+        if (out_bf16) {
+            const u32x2_t pk = {(uint32_t)tsvd_bf16_rne(v0) | ((uint32_t)tsvd_bf16_rne(v1) << 16),
+                                (uint32_t)tsvd_bf16_rne(v2) | ((uint32_t)tsvd_bf16_rne(v3) << 16)};
+            *reinterpret_cast<u32x2_t*>(static_cast<uint16_t*>(y) + at) = pk;
+        } else {
+            *reinterpret_cast<f32x4_t*>(static_cast<float*>(y) + at) = f32x4_t{v0, v1, v2, v3};
+        }
+        return;
+    }
+    const float v[4] = {v0, v1, v2, v3};
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if (row0 + e < rows_valid) tsvd_store_y(y, at + e, v[e], out_bf16);
+}

@@ -175,6 +175,7 @@ struct gemm_args {
     long long ld_out;
     const float* bias;        // stage 2 (EX kernels): added per output row, or null
     int out_bf16;             // stage 2 (EX kernels): output type
+    int out_token_major;      // stage 2 (EX = 3): out is [tokens][ld_out] (one row per token) instead of [M][ld_out]
     int rows_valid;           // stage 2: M
     long long* clocks;        // tuning aid: phase timestamps per workgroup (stage 1: 0..7, stage 2: 8..15), or null
 };
@@ -223,7 +224,7 @@ __device__ __forceinline__ void publish_column_factor(const gemm_args& p, int co
 // Result block layout: lane (i, g) holds token i, weight rows 4 g + v.
 // EX: the variants with the bias and the choice of the output type (instantiated apart so that the
 // plain fp32 epilogue of the tuned kernels stays as it is): 1 = fp32 with bias, 2 = bf16 (with or
-// without bias), two rows per store.
+// without bias), two rows per store, 3 = token-major output (either type, with or without bias).
 template <int TM, int TN, bool STAGE2, int EX = 0>
 __device__ __forceinline__ void gemm_epilogue(const gemm_args& p, f32x4 (&acc)[TM][TN], int strip0, int b0, int tok0,
                                               const float* cs_lds, int i, int g) {
@@ -252,6 +253,21 @@ __device__ __forceinline__ void gemm_epilogue(const gemm_args& p, f32x4 (&acc)[T
 #pragma unroll
                 for (int v = 0; v < 4; ++v) sr[a][v] = 0.f;
         }
+    }
+    if constexpr (STAGE2 && EX == 3) {        // token-major output (fp32 or bf16, with or without bias): four rows per store
+        const bool vec_ok = !(p.ld_out & 3) && !(reinterpret_cast<uintptr_t>(p.out) & 15);
+#pragma unroll
+        for (int a = 0; a < TM; ++a) {
+#pragma unroll
+            for (int b = 0; b < TN; ++b) {
+                const int col = col0 + b * 16 + i;
+                if (col < p.bvalid)
+                    tsvd_store_token_major4(p.out, p.ld_out, col, (strip0 + a) * 16 + 4 * g, p.rows_valid, acc[a][b][0] * cs[b] + sr[a][0],
+                                            acc[a][b][1] * cs[b] + sr[a][1], acc[a][b][2] * cs[b] + sr[a][2], acc[a][b][3] * cs[b] + sr[a][3],
+                                            p.out_bf16, vec_ok);
+            }
+        }
+        return;
     }
     if constexpr (STAGE2 && EX == 2) {        // bf16 in pairs: rows two by two, tokens left to right
         const bool aligned4 = !(p.ld_out & 1) && !(reinterpret_cast<uintptr_t>(p.out) & 3);
@@ -1205,6 +1221,7 @@ struct panel_args {
     long long ldy;
     const float* bias;        // EX kernels: added per output row, or null
     int out_bf16;             // EX kernels: output type
+    int out_token_major;      // EX = 3: y is [tokens][ldy]
     long long* clocks;
 };
 #define TSVD_PANEL_MAX_KP 1024
@@ -1501,7 +1518,20 @@ tsvd_panel_kernel(panel_args p) {
                 else if (p.bias) fill([&](int row) { return p.bias[row]; });
                 else fill([](int) { return 0.f; });
             }
-            if constexpr (EX == 2) {
+            if constexpr (EX == 3) {
+                const bool vec_ok = !(p.ldy & 3) && !(reinterpret_cast<uintptr_t>(p.y) & 15);
+#pragma unroll
+                for (int a = 0; a < TM; ++a) {
+#pragma unroll
+                    for (int b = 0; b < TN; ++b) {
+                        const int col = b0 + b * 16 + i;
+                        if (col < p.B)
+                            tsvd_store_token_major4(p.y, p.ldy, col, (strip0 + a) * 16 + 4 * g, p.M, acc[a][b][0] * c2[b] + br[a][0],
+                                                    acc[a][b][1] * c2[b] + br[a][1], acc[a][b][2] * c2[b] + br[a][2],
+                                                    acc[a][b][3] * c2[b] + br[a][3], p.out_bf16, vec_ok);
+                    }
+                }
+            } else if constexpr (EX == 2) {
                 const bool aligned4 = !(p.ldy & 1) && !(reinterpret_cast<uintptr_t>(p.y) & 3);
 #pragma unroll
                 for (int a = 0; a < TM; ++a) {
@@ -1552,9 +1582,9 @@ tsvd_panel_kernel(panel_args p) {
         p.clocks[blockIdx.x * 16 + 8 + wave / (NW / 8)] = wall_clock64();   // end of (one of) the wavefronts of each eighth
 }
 
-// Epilogue variant of a stage-U launch: 0 plain fp32, 1 fp32 with bias, 2 bf16.
-int out_variant(const float* bias, int out_bf16, const void*, long long) {
-    return out_bf16 ? 2 : bias ? 1 : 0;
+// Epilogue variant of a stage-U launch: 0 plain fp32, 1 fp32 with bias, 2 bf16, 3 token-major output.
+int out_variant(const float* bias, int out_bf16, int token_major) {
+    return token_major ? 3 : out_bf16 ? 2 : bias ? 1 : 0;
 }
 
 template <int WM, int WN, int TM, int TN, bool STAGE2>
@@ -1564,7 +1594,7 @@ hipError_t launch_gemm(const gemm_args& a, bool fast, long long rows, int Bp, hi
     // (token tiles that lie wholly beyond the last token are not launched: nothing reads what they would write)
     const dim3 grid((a.bvalid + BT - 1) / BT, (unsigned)(rows / MT)), block(64 * WM * WN);
     if constexpr (STAGE2) {
-        const int ex = out_variant(a.bias, a.out_bf16, a.out, a.ld_out);    // the epilogues with bias / bf16 output
+        const int ex = out_variant(a.bias, a.out_bf16, a.out_token_major);    // the epilogues with bias / bf16 output
         if (ex == 2) {
             if (fast) hipLaunchKernelGGL((tsvd_gemm_pipe_kernel<WM, WN, TM, TN, true, 2>), grid, block, 2 * lds + cs, stream, a);
             else hipLaunchKernelGGL((tsvd_gemm_kernel<WM, WN, TM, TN, true, false, 2>), grid, block, lds + cs, stream, a);
@@ -1573,6 +1603,11 @@ hipError_t launch_gemm(const gemm_args& a, bool fast, long long rows, int Bp, hi
         if (ex == 1) {
             if (fast) hipLaunchKernelGGL((tsvd_gemm_pipe_kernel<WM, WN, TM, TN, true, 1>), grid, block, 2 * lds + cs, stream, a);
             else hipLaunchKernelGGL((tsvd_gemm_kernel<WM, WN, TM, TN, true, false, 1>), grid, block, lds + cs, stream, a);
+            return hipGetLastError();
+        }
+        if (ex == 3) {
+            if (fast) hipLaunchKernelGGL((tsvd_gemm_pipe_kernel<WM, WN, TM, TN, true, 3>), grid, block, 2 * lds + cs, stream, a);
+            else hipLaunchKernelGGL((tsvd_gemm_kernel<WM, WN, TM, TN, true, false, 3>), grid, block, lds + cs, stream, a);
             return hipGetLastError();
         }
     }
@@ -1594,6 +1629,12 @@ hipError_t init_gemm() {
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_pipe_kernel<WM, WN, TM, TN, true, 2>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 2 * lds + cs);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_pipe_kernel<WM, WN, TM, TN, true, 3>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * lds + cs);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_kernel<WM, WN, TM, TN, true, false, 3>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds + cs);
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_kernel<WM, WN, TM, TN, true, false, 1>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds + cs);
@@ -1617,9 +1658,10 @@ hipError_t launch_ring(const gemm_args& a, long long rows, int Bp, hipStream_t s
     if (rows % MT) return hipErrorInvalidValue;      // (96-row tiles: the rule asks for them only when they divide the rows)
     const dim3 grid((a.bvalid + BT - 1) / BT, (unsigned)(rows / MT)), block(64 * WM * WN * KG);
     if constexpr (STAGE2) {
-        const int ex = out_variant(a.bias, a.out_bf16, a.out, a.ld_out);
+        const int ex = out_variant(a.bias, a.out_bf16, a.out_token_major);
         if (ex == 2) hipLaunchKernelGGL((tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false, KG, 2>), grid, block, lds, stream, a);
         if (ex == 1) hipLaunchKernelGGL((tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false, KG, 1>), grid, block, lds, stream, a);
+        if (ex == 3) hipLaunchKernelGGL((tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false, KG, 3>), grid, block, lds, stream, a);
         if (ex != 0) return hipGetLastError();
     }
     hipLaunchKernelGGL((tsvd_gemm_ring_kernel<WM, WN, TM, TN, STAGE2, NPB, FUSEMAX, KG>), grid, block, lds, stream, a);
@@ -1635,6 +1677,9 @@ hipError_t init_ring() {
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false, KG, 2>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false, KG, 3>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_ring_kernel<WM, WN, TM, TN, false, NPB, false, KG>),
@@ -1760,6 +1805,7 @@ hipError_t init_fp6() {
     if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 0, WM, WN, TM, NPL>), hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 1, WM, WN, TM, NPL>), hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 2, WM, WN, TM, NPL>), hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<true, 3, WM, WN, TM, NPL>), hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<false, 0, WM, WN, TM, NPL>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
 }
 // rows_p: padded rows of the stage's weights; ex: output variant (stage U only)
@@ -1771,6 +1817,7 @@ hipError_t launch_fp6(bool stage2, const gemm_args& a, long long rows_p, int Bp,
     if (!stage2) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<false, 0, WM, WN, TM, NPL>), grid, block, lds, stream, a);
     else if (ex == 2) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 2, WM, WN, TM, NPL>), grid, block, lds, stream, a);
     else if (ex == 1) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 1, WM, WN, TM, NPL>), grid, block, lds, stream, a);
+    else if (ex == 3) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 3, WM, WN, TM, NPL>), grid, block, lds, stream, a);
     else hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 0, WM, WN, TM, NPL>), grid, block, lds, stream, a);
     return hipGetLastError();
 }
@@ -1818,6 +1865,10 @@ hipError_t tsvd_gemm_init() {
     if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_kernel<8, 2>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  TSVD_PANEL_LDS_EX(8))) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_kernel<16, 2>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 TSVD_PANEL_LDS_EX(16))) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_kernel<8, 3>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 TSVD_PANEL_LDS_EX(8))) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_kernel<16, 3>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  TSVD_PANEL_LDS_EX(16))) != hipSuccess) return e;
 #define TSVD_RING_INIT(id, wm, wn, tm, tn, npb, kg) \
     if ((e = init_ring<wm, wn, tm, tn, npb, kg>()) != hipSuccess) return e;
@@ -1873,6 +1924,7 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     a2.ld_out = g.ldy;
     a2.bias = g.bias;
     a2.out_bf16 = g.out_bf16;
+    a2.out_token_major = g.y_token_major;
     a2.rows_valid = (int)hd.M;
 
     if (tsvd_stage_mask() == 7 && tsvd_gemm_use_panel(hd.Mp, hd.Kp, hd.Np, g.B, g.cu_count, fast1)) {
@@ -1896,15 +1948,18 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
         pa.ldy = g.ldy;
         pa.bias = g.bias;
         pa.out_bf16 = g.out_bf16;
+        pa.out_token_major = g.y_token_major;
         pa.clocks = g.clocks;
         const dim3 pgrid((unsigned)((g.B + 63) / 64));
-        const int ex = out_variant(g.bias, g.out_bf16, g.y, g.ldy);
+        const int ex = out_variant(g.bias, g.out_bf16, g.y_token_major);
         if (env_cfg("TSVD_PANEL_WAVES", 16) == 16) {   // tuning switch: 16 is about 5 % faster on MI355X
-            if (ex == 2) hipLaunchKernelGGL((tsvd_panel_kernel<16, 2>), pgrid, dim3(1024), TSVD_PANEL_LDS_EX(16), stream, pa);
+            if (ex == 3) hipLaunchKernelGGL((tsvd_panel_kernel<16, 3>), pgrid, dim3(1024), TSVD_PANEL_LDS_EX(16), stream, pa);
+            else if (ex == 2) hipLaunchKernelGGL((tsvd_panel_kernel<16, 2>), pgrid, dim3(1024), TSVD_PANEL_LDS_EX(16), stream, pa);
             else if (ex == 1) hipLaunchKernelGGL((tsvd_panel_kernel<16, 1>), pgrid, dim3(1024), TSVD_PANEL_LDS_EX(16), stream, pa);
             else hipLaunchKernelGGL((tsvd_panel_kernel<16>), pgrid, dim3(1024), TSVD_PANEL_LDS(16), stream, pa);
         } else {
-            if (ex == 2) hipLaunchKernelGGL((tsvd_panel_kernel<8, 2>), pgrid, dim3(512), TSVD_PANEL_LDS_EX(8), stream, pa);
+            if (ex == 3) hipLaunchKernelGGL((tsvd_panel_kernel<8, 3>), pgrid, dim3(512), TSVD_PANEL_LDS_EX(8), stream, pa);
+            else if (ex == 2) hipLaunchKernelGGL((tsvd_panel_kernel<8, 2>), pgrid, dim3(512), TSVD_PANEL_LDS_EX(8), stream, pa);
             else if (ex == 1) hipLaunchKernelGGL((tsvd_panel_kernel<8, 1>), pgrid, dim3(512), TSVD_PANEL_LDS_EX(8), stream, pa);
             else hipLaunchKernelGGL((tsvd_panel_kernel<8>), pgrid, dim3(512), TSVD_PANEL_LDS(8), stream, pa);
         }
@@ -1953,7 +2008,7 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
         gemm_args a3 = a2;
         a3.act = reinterpret_cast<const uint16_t*>(planes);
         a3.act_bytes = (unsigned)tsvd_gemm_fp6_bytes(hd.Kp, Bp);
-        return launch_fp6_any(true, a3, hd.Mp, Bp, out_variant(a3.bias, a3.out_bf16, a3.out, a3.ld_out), g.cu_count, stream);
+        return launch_fp6_any(true, a3, hd.Mp, Bp, out_variant(a3.bias, a3.out_bf16, a3.out_token_major), g.cu_count, stream);
     }
     if (mask & 4) e = launch_cfg<true, false>(cfg2, a2, true, hd.Mp, Bp, stream);
     return e;

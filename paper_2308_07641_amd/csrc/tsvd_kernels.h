@@ -31,6 +31,7 @@ struct tsvd_skinny_args {
     int sw, kw;             // workgroup = sw strips x kw contraction splits (one wavefront each)
     const float* bias;      // stage U: added per output row, or null
     int out_bf16;           // stage U: out is bf16 [rows_out][ld_out] instead of fp32
+    int out_token_major;    // stage U: out is [tokens][ld_out] instead of [rows_out][ld_out]
 };
 
 hipError_t tsvd_launch_skinny(const tsvd_skinny_args& a, hipStream_t stream);
@@ -103,6 +104,7 @@ struct tsvd_mid_args {
     float* colmax;                        // [16] per-token max |x| (stage V writes, stage U reads)
     void* out; long long ld_out;          // stage V: z fp16 [Kp][16]; stage U: y fp32 (or bf16) [M][ld_out]
     const float* bias; int out_bf16;      // stage U: bias per output row or null; output type
+    int out_token_major;                  // stage U: out is [tokens][ld_out] instead of [M][ld_out]
     int rows_valid;                       // stage U: M
     long long* clocks;                    // optional tuning aid: [grid][16] phase timestamps (stage V 0..7, U 8..15), or null
     int resident_ok;                      // tuning switch: 0 forces the slab hand-over loop for short contractions too
@@ -128,6 +130,7 @@ struct tsvd_gemm_problem {
     long long ldy;
     const float* bias;              // device [M] added per output row, or null
     int out_bf16;
+    int y_token_major;              // y is [B][ldy] (one row per token) instead of [M][ldy]
     void* ws;                       // device workspace (see gemm_workspace in tsvd_api.hip)
     int cu_count;                   // compute units of the device
     long long* clocks;              // optional tuning aid: [TSVD_GEMV_MAX_GRID][16] phase timestamps, or null

@@ -302,7 +302,8 @@ tsvd_mid_kernel(tsvd_mid_args p) {
             const int row = blockIdx.x * p.sw * 16 + rl;
             if constexpr (STAGE2) {
                 if (row < p.rows_valid && tok < p.bvalid)
-                    tsvd_store_y(p.out, (size_t)row * p.ld_out + tok, p.bias ? sum * ftok + p.bias[row] : sum * ftok, p.out_bf16);
+                    tsvd_store_y(p.out, p.out_token_major ? (size_t)tok * p.ld_out + row : (size_t)row * p.ld_out + tok,
+                                 p.bias ? sum * ftok + p.bias[row] : sum * ftok, p.out_bf16);
             } else {
                 if (row < p.strips * 16)   // S is zero beyond K: padded rows of z are written as zeros
                     static_cast<_Float16*>(p.out)[(size_t)row * 16 + tok] = (_Float16)((sum * fin[n]) * ftok);

@@ -235,7 +235,8 @@ tsvd_skinny_kernel(tsvd_skinny_args p) {
                 dst[(size_t)(d + 4) * p.ld_out] = (unsigned char)(hi >> (8 * d));
             }
         } else {
-            tsvd_store_y(p.out, (size_t)row * p.ld_out + tok, (float)(p.bias ? val + (double)p.bias[row] : val), p.out_bf16);
+            tsvd_store_y(p.out, p.out_token_major ? (size_t)tok * p.ld_out + row : (size_t)row * p.ld_out + tok,
+                         (float)(p.bias ? val + (double)p.bias[row] : val), p.out_bf16);
         }
     }
 }

@@ -36,6 +36,8 @@ _PROTOTYPES = {
     "tsvd_workspace_bytes_ex": (_sz, [_vp, _i64, ctypes.c_int, ctypes.c_int]),
     "tsvd_forward_ex": (ctypes.c_int, [_vp, _vp, ctypes.c_int, ctypes.c_int, _i64, _i64, _vp, _vp, ctypes.c_int, _i64,
                                        _vp, _sz, _vp]),
+    "tsvd_forward_io": (ctypes.c_int, [_vp, _vp, ctypes.c_int, ctypes.c_int, _i64, _i64, _vp, _vp, ctypes.c_int, ctypes.c_int, _i64,
+                                       _vp, _sz, _vp]),
     "tsvd_forward_noalloc": (ctypes.c_int, [_vp, _vp, ctypes.c_int, ctypes.c_int, _i64, _i64, _vp, _vp, ctypes.c_int, _i64, _vp]),
     "tsvd_tuning_set": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_int]),
     "tsvd_tuning_reset": (None, []),
@@ -252,6 +254,38 @@ def tsvd_forward_ex(h: Handle, x, x_layout=TSVD_FEATURE_MAJOR, bias=None, y=None
         stream = torch.cuda.current_stream(x.device).cuda_stream
     _check(load_library().tsvd_forward_ex(h.ptr, x.data_ptr(), _dtype_code(x), x_layout, B, ldx, bias_ptr, y.data_ptr(),
                                           y_dtype, ldy, ws_ptr, ws_bytes, stream), "tsvd_forward_ex")
+    return y
+
+
+def tsvd_forward_io(h: Handle, x, x_layout=TSVD_FEATURE_MAJOR, bias=None, y=None, y_dtype=TSVD_F32, y_layout=TSVD_FEATURE_MAJOR,
+                    workspace=None, stream=None):
+    """tsvd_forward_ex with the layout of y chosen too: [M,B] (feature-major) or [B,M] (token-major)."""
+    import torch
+    if not x.is_cuda or x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be a 2-d GPU tensor with unit inner stride")
+    B, feat = (x.shape[0], x.shape[1]) if x_layout == TSVD_TOKEN_MAJOR else (x.shape[1], x.shape[0])
+    if feat != h.N:
+        raise ValueError("x does not have N features")
+    ldx = x.stride(0) if x.shape[0] > 1 else max(x.shape[1], x.stride(0))
+    ydt = torch.bfloat16 if y_dtype == TSVD_BF16 else torch.float32
+    yshape = (B, h.M) if y_layout == TSVD_TOKEN_MAJOR else (h.M, B)
+    if y is None:
+        y = torch.empty(yshape, dtype=ydt, device=x.device)
+    if y.dtype != ydt or tuple(y.shape) != yshape or y.stride(1) != 1 or not y.is_cuda:
+        raise ValueError("y must be a GPU tensor of the requested type and layout with unit inner stride")
+    ldy = y.stride(0) if y.shape[0] > 1 else max(y.shape[1], y.stride(0))
+    bias_ptr = None
+    if bias is not None:
+        if bias.dtype != torch.float32 or bias.shape != (h.M,) or not bias.is_cuda or not bias.is_contiguous():
+            raise ValueError("bias must be a contiguous float32 GPU tensor [M]")
+        bias_ptr = bias.data_ptr()
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    _check(load_library().tsvd_forward_io(h.ptr, x.data_ptr(), _dtype_code(x), x_layout, B, ldx, bias_ptr, y.data_ptr(),
+                                          y_dtype, y_layout, ldy, ws_ptr, ws_bytes, stream), "tsvd_forward_io")
     return y
 
 

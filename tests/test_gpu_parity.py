@@ -437,6 +437,8 @@ LAYER_CASES = [
     (300, 200, 520, 304, {"TSVD_PANEL": "1", "TSVD_PANEL_WAVES": "8"}),   # token-panel kernel, 8 wavefronts
     (300, 200, 520, 304, {"TSVD_PANEL": "0", "TSVD_GEMM_CFG_U": "14", "TSVD_GEMM_CFG_V": "15"}),   # ring kernels, other shapes
     (700, 200, 760, 304, {"TSVD_PANEL": "0", "TSVD_GEMM_CFG_U": "17", "TSVD_GEMM_CFG_V": "17"}),   # ring kernels, 96-row tiles
+    (515, 300, 777, 130, {"TSVD_PANEL": "0", "TSVD_FP6": "1", "TSVD_FP6_V": "0", "TSVD_FP6_TALL": "1"}),   # fp4 x fp6 stage U, 512 x 64 tiles
+    (300, 200, 270, 100, {"TSVD_PANEL": "0", "TSVD_FP6": "1", "TSVD_FP6_V": "1", "TSVD_GEMM_CFG_V": "3", "TSVD_FP6_TALL": "3"}),   # both stages on planes
 ]
 
 
@@ -456,8 +458,16 @@ def test_layer_form_every_kernel_family(tsvd, M, N, K, B, env):
         b = None if bias is None else torch.from_numpy(bias).to(dev)
         y = torch.full((M, B), float("nan"), dtype=torch.bfloat16 if y_dtype == tsvd.TSVD_BF16 else torch.float32, device=dev)
         tsvd.tsvd_forward_ex(h, x, x_layout=layout, bias=b, y=y, y_dtype=y_dtype)
+        # the same call with one row per token in y ([B][M], row pitch M + pad: padded and unpadded rows take the
+        # vector and the element-wise stores): must hold the same values, and leave the padding alone
+        pad = 4 if (M + B) % 2 else 3
+        yt = torch.full((B, M + pad), float("nan"), dtype=y.dtype, device=dev)
+        tsvd.tsvd_forward_io(h, x, x_layout=layout, bias=b, y=yt[:, :M], y_dtype=y_dtype, y_layout=tsvd.TSVD_TOKEN_MAJOR)
         torch.cuda.synchronize()
         tsvd.tsvd_free(h)
+        assert torch.isnan(yt[:, M:]).all()
+        assert torch.equal(yt[:, :M].t().contiguous().view(torch.int16 if y_dtype == tsvd.TSVD_BF16 else torch.int32),
+                           y.view(torch.int16 if y_dtype == tsvd.TSVD_BF16 else torch.int32)), "token-major y differs"
         return y.float().cpu().numpy().astype(np.float64)
 
     i = workloads.make_integer_inputs(M, N, K, B, 0.5, "bf16", seed=5 + M + B)
@@ -496,9 +506,13 @@ def test_layer_form_fp32_activations(tsvd, B):
     xt = to_device(i).t().contiguous()
     ws = torch.empty(tsvd.tsvd_workspace_bytes_ex(h, B, tsvd.TSVD_F32, tsvd.TSVD_TOKEN_MAJOR), dtype=torch.uint8, device="cuda:0")
     y = tsvd.tsvd_forward_ex(h, xt, x_layout=tsvd.TSVD_TOKEN_MAJOR, bias=torch.from_numpy(bias).to("cuda:0"), workspace=ws)
+    yt = tsvd.tsvd_forward_io(h, xt, x_layout=tsvd.TSVD_TOKEN_MAJOR, bias=torch.from_numpy(bias).to("cuda:0"), workspace=ws,
+                              y_layout=tsvd.TSVD_TOKEN_MAJOR)
     torch.cuda.synchronize()
     tsvd.tsvd_free(h)
     assert np.max(np.abs(y.cpu().numpy().astype(np.float64) - ref)) <= 1e-5 * np.max(np.abs(ref))
+    ref_t = oracle.forward_layer(i.U, i.S, i.V, i.X, bias=bias, y_layout="token_major")
+    assert yt.shape == (B, 256) and np.max(np.abs(yt.cpu().numpy().astype(np.float64) - ref_t)) <= 1e-5 * np.max(np.abs(ref))
 
 
 def test_strided_inputs_outputs_and_caller_workspace(tsvd):
