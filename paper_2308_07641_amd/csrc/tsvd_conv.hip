@@ -139,6 +139,7 @@ struct grouped_args {
     const uint32_t* U; int u_tps;        // code words of U, tiles per 16-row strip (Kp / 256)
     const uint32_t* V; int v_tps;        // code words of V, tiles per strip (Np / 256)
     const float* S;
+    int K;                               // rank of the packed triple (positions of the rank index: tsvd_rank_position)
     const uint16_t* x; void* y; const float* bias; int out_bf16;
     int cg, mg, kg, ng;                  // per group: input channels, output channels, ranks, taps (cg k1 k2)
     int images, H, W, Ho, Wo, k1, k2, s1, s2, p1, p2, d1, d2;
@@ -193,14 +194,14 @@ tsvd_grouped_conv_kernel(grouped_args p) {
     // ---- the codes of V_g, all loads in flight at once, then per rank (one wavefront each) the list of its non-zero taps
     for (int idx = threadIdx.x; idx < p.kg * p.ng; idx += blockDim.x) {
         const int k = idx / p.ng, j = idx - k * p.ng;
-        codes[k * stride + j] = (unsigned char)code_at(p.V, p.v_tps, g * p.kg + k, j);
+        codes[k * stride + j] = (unsigned char)code_at(p.V, p.v_tps, (int)tsvd_rank_position(g * p.kg + k, p.K), j);
     }
     for (int idx = threadIdx.x; idx < MG * p.kg; idx += blockDim.x) {
         const int m = idx / p.kg, k = idx % p.kg;
-        const int code = m < p.mg ? code_at(p.U, p.u_tps, g * p.mg + m, g * p.kg + k) : 0;
+        const int code = m < p.mg ? code_at(p.U, p.u_tps, g * p.mg + m, (int)tsvd_rank_position(g * p.kg + k, p.K)) : 0;
         ucode[idx] = code == 1 ? 1.f : code == 3 ? -1.f : 0.f;
     }
-    for (int k = threadIdx.x; k < p.kg; k += blockDim.x) sval[k] = p.S[g * p.kg + k];
+    for (int k = threadIdx.x; k < p.kg; k += blockDim.x) sval[k] = p.S[tsvd_rank_position(g * p.kg + k, p.K)];
     __syncthreads();
     for (int k = wave; k < p.kg; k += nwaves) {
         int cnt = 0;
@@ -465,6 +466,7 @@ extern "C" tsvd_status tsvd_conv2d_forward(const tsvd_handle* h, const tsvd_conv
         a.U = reinterpret_cast<const uint32_t*>(blob + hd->off_U); a.u_tps = (int)(hd->Kp / TSVD_TILE_COLS);
         a.V = reinterpret_cast<const uint32_t*>(blob + hd->off_V); a.v_tps = (int)(hd->Np / TSVD_TILE_COLS);
         a.S = reinterpret_cast<const float*>(blob + hd->off_S);
+        a.K = (int)hd->K;
         a.x = static_cast<const uint16_t*>(x_dev); a.y = y_dev; a.bias = bias_dev; a.out_bf16 = y_dtype == TSVD_BF16;
         hipStream_t gs = static_cast<hipStream_t>(stream);
         if (MG == 1) launch_grouped<1>(a, ROWS, P, PAIR, g->groups, threads, gs);

@@ -159,7 +159,9 @@ __device__ __forceinline__ constexpr int swizzle(int r) {
 // ---- kernels 1 and 2 ------------------------------------------------------------------------
 struct gemm_args {
     const uint32_t* tiles;    // packed A: [strips][nkt][256 words]
-    int nkt;                  // 256-wide tiles along the contraction index
+    int nkt;                  // 256-wide tiles along the contraction index (the stride of a strip)
+    int npairs;               // 128-index steps of the contraction that hold anything (<= 2 nkt): the loops end there
+    int last_steps;           // 32-index sub-steps of the last of them that hold anything (1..4; see tsvd_rank_position)
     const uint16_t* act;      // activations [kdim][ld] 16-bit
     long long ld;
     int kvalid;               // activation rows that exist (stage 1: N); others read as zero
@@ -177,6 +179,7 @@ struct gemm_args {
     int out_bf16;             // stage 2 (EX kernels): output type
     int out_token_major;      // stage 2 (EX = 3): out is [tokens][ld_out] (one row per token) instead of [M][ld_out]
     int rows_valid;           // stage 2: M
+    int rows_need;            // rows of the stage that have to be computed (stage 1: the rank positions stage 2 reads; stage 2: M)
     long long* clocks;        // tuning aid: phase timestamps per workgroup (stage 1: 0..7, stage 2: 8..15), or null
 };
 
@@ -355,7 +358,7 @@ tsvd_gemm_kernel(gemm_args p) {
     const int i = lane & 15, g = lane >> 4;
     const int b0 = blockIdx.x * BT;
     const int strip0 = (blockIdx.y * WM + wm) * TM;  // first 16-row strip of this wavefront
-    const int nstages = p.nkt * (256 / KT);
+    const int nstages = 2 * p.npairs - (p.last_steps <= 2 ? 1 : 0);   // (a stage is one code word: two sub-steps)
 
     // Stage st covers code word d = st & 3 of tile T = st >> 2: contraction indices
     // k0 + 64 (r >> 5) + (r & 31), r = 0..63, with k0 = 256 T + 128 (d >> 1) + 32 (d & 1).
@@ -472,7 +475,7 @@ tsvd_gemm_kernel(gemm_args p) {
         __syncthreads();
         load_x(min(s + 2, last));
         load_w(min(s + 2, last), w0);
-        compute(1, w1);
+        if (s + 1 < nstages) compute(1, w1);
         store_x(0);
         __syncthreads();
     }
@@ -525,7 +528,7 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
     const int i = lane & 15, g = lane >> 4;
     const int b0 = blockIdx.x * BT;
     const int strip0 = (blockIdx.y * WM + wm) * TM;
-    const int nstages = p.nkt * (256 / KT), last = nstages - 1;
+    const int nstages = 2 * p.npairs, last = nstages - 1;
     auto tick = [&](int n) {
         const unsigned wg = blockIdx.y * gridDim.x + blockIdx.x;
         if (p.clocks && threadIdx.x == 0 && wg < TSVD_GEMV_MAX_GRID) p.clocks[wg * 16 + (STAGE2 ? 8 : 0) + n] = wall_clock64();
@@ -669,7 +672,7 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
         load_w(nx, wa);
         issue_x(2 * nx, 0);
         issue_x(2 * nx + 1, 1);
-        compute_pair(2, wb);
+        if (P + 1 <= lastp) compute_pair(2, wb);      // (an odd number of 128-index steps: the contraction ends inside this tile of codes)
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         touch(wa);
         __syncthreads();
@@ -819,7 +822,8 @@ tsvd_gemm_fp6_kernel(gemm_args p) {
     const int i = lane & 15, g = lane >> 4;
     const int b0 = blockIdx.x * BT;
     const int strip0 = (blockIdx.y * WM + wm) * TM;
-    const int nblocks = p.nkt * 2, lastb = nblocks - 1;
+    const int nblocks = p.nkt * 2;                    // blocks per token group in the planes' layout
+    const int nrun = p.npairs, lastb = nrun - 1;      // blocks that hold anything
 
     const i32x4 act_rsrc = raw_rsrc(p.act, p.act_bytes);
     const __amdgpu_buffer_rsrc_t w_rsrc =
@@ -903,7 +907,7 @@ tsvd_gemm_fp6_kernel(gemm_args p) {
     touch(wa);
     if (threadIdx.x < BT) publish_column_factor<STAGE2>(p, b0 + threadIdx.x, cmax, cs_lds, threadIdx.x);
     __syncthreads();
-    for (int P = 0; P < nblocks; P += 2) {
+    for (int P = 0; P < nrun; P += 2) {
         int nx = min(P + 1, lastb);
         load_w(nx, wb);
         issue(nx, 1);
@@ -914,7 +918,7 @@ tsvd_gemm_fp6_kernel(gemm_args p) {
         nx = min(P + 2, lastb);
         load_w(nx, wa);
         issue(nx, 0);
-        compute(1, wb);
+        if (P + 1 <= lastb) compute(1, wb);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         touch(wa);
         __syncthreads();
@@ -989,7 +993,9 @@ tsvd_gemm_ring_kernel(gemm_args p) {
     const int i = lane & 15, g = lane >> 4;
     const int b0 = blockIdx.x * BT;
     const int strip0 = (blockIdx.y * WM + wm) * TM;
-    const int nslots = p.nkt * 2 / KG, lasts = nslots - 1;   // ring slots to go through
+    const int nslots = (p.npairs + KG - 1) / KG, lasts = nslots - 1;   // ring slots to go through
+    // sub-steps of this wavefront group's pair in the last slot: all four, the partly filled last pair's, or none
+    const int tail_steps = KG * lasts + kg < p.npairs - 1 ? 4 : KG * lasts + kg == p.npairs - 1 ? p.last_steps : 0;
     auto tick = [&](int n) {
         const unsigned wg = blockIdx.y * gridDim.x + blockIdx.x;
         if (p.clocks && threadIdx.x == 0 && wg < TSVD_GEMV_MAX_GRID) p.clocks[wg * 16 + (STAGE2 ? 8 : 0) + n] = wall_clock64();
@@ -1076,8 +1082,20 @@ tsvd_gemm_ring_kernel(gemm_args p) {
         }
     };
     // this wavefront's pair of ring slot `slot`, while the loads of slot index next_sl go out
-    auto compute_pair = [&](int slot, int next_sl, int next_slot) {
+    auto compute_pair = [&](int slot, int next_sl, int next_slot, int steps) {
         const unsigned char* base = smem + slot * SLOT_BYTES + kg * SUB_BYTES;
+        if (steps < 4) {            // (uniform over the wavefront; only ever in the last slot, where nothing is left to request)
+            u32x2 wl2[TM];
+            const uint32_t* wq = reinterpret_cast<const uint32_t*>(base + 2 * STAGE_BYTES) + wm * TM * 128 + lane;
+#pragma unroll
+            for (int a = 0; a < TM; ++a) wl2[a] = u32x2{wq[a * 128], wq[a * 128 + 64]};
+            u32x2 flo[TN], fhi[TN];
+            if (steps > 0) { load_frags(base, 0, flo, fhi); mfma_step(wl2, 0, 0, flo, fhi); }
+            if (steps > 1) { load_frags(base, 1, flo, fhi); mfma_step(wl2, 0, 1, flo, fhi); }
+            if (steps > 2) { load_frags(base + STAGE_BYTES, 0, flo, fhi); mfma_step(wl2, 1, 0, flo, fhi); }
+            __builtin_amdgcn_sched_barrier(0);
+            return;
+        }
         u32x2 w[TM];
         const uint32_t* wl = reinterpret_cast<const uint32_t*>(base + 2 * STAGE_BYTES) + wm * TM * 128 + lane;
 #pragma unroll
@@ -1145,7 +1163,7 @@ tsvd_gemm_ring_kernel(gemm_args p) {
 #pragma unroll
         for (int j = 0; j < NPB; ++j) {
             if (P + j >= nslots) break;
-            compute_pair(j, P + j + NPB - 1, (j + NPB - 1) % NPB);   // loads go into the slot multiplied last time
+            compute_pair(j, P + j + NPB - 1, (j + NPB - 1) % NPB, P + j == lasts ? tail_steps : 4);   // loads go into the slot multiplied last time
             scan_slot(j);
             // slot P + j + 1 has landed: all but the loads of the NPB - 2 younger slots are back.  Near
             // the end fewer slots are requested, so everything outstanding is awaited.
@@ -1211,6 +1229,7 @@ struct panel_args {
     const uint32_t* tiles_u;  // packed U [Mp/16][Kp/256][256 words]
     unsigned tile_v_bytes, tile_u_bytes;
     int nkt_v, nkt_u;         // Np / 256, Kp / 256
+    int npairs_v, npairs_u;   // 128-index steps of either contraction that hold anything (ceil(N / 128), ceil(K / 128))
     const uint16_t* x;        // bf16 [N][ldx]
     long long ldx;
     unsigned x_bytes;
@@ -1381,7 +1400,7 @@ tsvd_panel_kernel(panel_args p) {
         // will hold Z afterwards: one wait, one barrier, and the wavefronts run their contraction
         // loops without meeting again until all of them are done with X.
         clear_acc();
-        const int npairs = p.nkt_v * 2, lastp = npairs - 1, nst = 2 * npairs;
+        const int npairs = p.npairs_v, lastp = npairs - 1, nst = 2 * npairs;
         u32x2 wa[TM], wb[TM];
         load_w(0, wa);
         for (int st = wave >> 3; st < nst; st += NW / 8) issue_x(st, st);
@@ -1424,7 +1443,7 @@ tsvd_panel_kernel(panel_args p) {
             load_w(min(P + 1, lastp), wb);
             compute_pair(std::false_type{}, zl + (2 * P) * STAGE_BYTES, zl + (2 * P + 1) * STAGE_BYTES, wa);
             load_w(min(P + 2, lastp), wa);
-            compute_pair(std::false_type{}, zl + (2 * P + 2) * STAGE_BYTES, zl + (2 * P + 3) * STAGE_BYTES, wb);
+            if (P + 1 <= lastp) compute_pair(std::false_type{}, zl + (2 * P + 2) * STAGE_BYTES, zl + (2 * P + 3) * STAGE_BYTES, wb);
         }
         // S of this wavefront's rows
         f32x4 sv[TM];
@@ -1472,7 +1491,7 @@ tsvd_panel_kernel(panel_args p) {
         float c2[TN];
 #pragma unroll
         for (int b = 0; b < TN; ++b) c2[b] = cs2[b * 16 + i];
-        const int npairs = p.nkt_u * 2, lastp = npairs - 1;
+        const int npairs = p.npairs_u, lastp = npairs - 1;
         // Units of TM strips (64 or 128 rows).  A SIMD always issues from its oldest ready wavefront,
         // so with equal shares the wavefronts of a SIMD (w, w + 4, w + 8, w + 12) finish one after
         // the other and the last runs alone (phase timestamps: 41, 47, 54, 60 us).  The units of a
@@ -1503,7 +1522,7 @@ tsvd_panel_kernel(panel_args p) {
                 load_w(min(P + 1, lastp), wb);
                 compute_pair(std::true_type{}, zl + (2 * P) * STAGE_BYTES, zl + (2 * P + 1) * STAGE_BYTES, wa);
                 load_w(min(P + 2, lastp), wa);
-                compute_pair(std::true_type{}, zl + (2 * P + 2) * STAGE_BYTES, zl + (2 * P + 3) * STAGE_BYTES, wb);
+                if (P + 1 <= lastp) compute_pair(std::true_type{}, zl + (2 * P + 2) * STAGE_BYTES, zl + (2 * P + 3) * STAGE_BYTES, wb);
             }
             float br[TM][4];
             if constexpr (EX != 0) {
@@ -1592,7 +1611,8 @@ hipError_t launch_gemm(const gemm_args& a, bool fast, long long rows, int Bp, hi
     constexpr int BT = WN * TN * 16, MT = WM * TM * 16;
     constexpr size_t lds = 2 * KT * BT * 2, cs = BT * 4;      // two stages; the column factors
     // (token tiles that lie wholly beyond the last token are not launched: nothing reads what they would write)
-    const dim3 grid((a.bvalid + BT - 1) / BT, (unsigned)(rows / MT)), block(64 * WM * WN);
+    (void)rows;   // (padded rows, a multiple of MT: the row tiles that hold rows to compute lie inside them)
+    const dim3 grid((a.bvalid + BT - 1) / BT, (unsigned)((a.rows_need + MT - 1) / MT)), block(64 * WM * WN);
     if constexpr (STAGE2) {
         const int ex = out_variant(a.bias, a.out_bf16, a.out_token_major);    // the epilogues with bias / bf16 output
         if (ex == 2) {
@@ -1656,7 +1676,7 @@ hipError_t launch_ring(const gemm_args& a, long long rows, int Bp, hipStream_t s
     constexpr int BT = WN * TN * 16, MT = WM * TM * 16;
     constexpr size_t lds = ring_lds_bytes<WM, WN, TM, TN, NPB, KG>();
     if (rows % MT) return hipErrorInvalidValue;      // (96-row tiles: the rule asks for them only when they divide the rows)
-    const dim3 grid((a.bvalid + BT - 1) / BT, (unsigned)(rows / MT)), block(64 * WM * WN * KG);
+    const dim3 grid((a.bvalid + BT - 1) / BT, (unsigned)((a.rows_need + MT - 1) / MT)), block(64 * WM * WN * KG);
     if constexpr (STAGE2) {
         const int ex = out_variant(a.bias, a.out_bf16, a.out_token_major);
         if (ex == 2) hipLaunchKernelGGL((tsvd_gemm_ring_kernel<WM, WN, TM, TN, true, NPB, false, KG, 2>), grid, block, lds, stream, a);
@@ -1813,7 +1833,7 @@ template <int WM, int WN, int TM, int NPL = 3>
 hipError_t launch_fp6(bool stage2, const gemm_args& a, long long rows_p, int Bp, int ex, hipStream_t stream) {
     constexpr int lds = 2 * (WN * 4 * FP6_REC_BYTES) + 512;
     if (rows_p % (WM * TM * 16)) return hipErrorInvalidValue;
-    const dim3 grid((a.bvalid + WN * 64 - 1) / (WN * 64), (unsigned)(rows_p / (WM * TM * 16))), block(256);
+    const dim3 grid((a.bvalid + WN * 64 - 1) / (WN * 64), (unsigned)((a.rows_need + WM * TM * 16 - 1) / (WM * TM * 16))), block(256);
     if (!stage2) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<false, 0, WM, WN, TM, NPL>), grid, block, lds, stream, a);
     else if (ex == 2) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 2, WM, WN, TM, NPL>), grid, block, lds, stream, a);
     else if (ex == 1) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<true, 1, WM, WN, TM, NPL>), grid, block, lds, stream, a);
@@ -1909,6 +1929,12 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     a1.out_bf16 = 0;
     a1.rows_valid = (int)hd.Kp;
     a1.clocks = g.clocks;
+    // contraction lengths: stage V runs over N, stage U over K, both in steps of 128 indices; the last step of K is
+    // filled from its first sub-steps (tsvd_rank_position), so stage U stops after those
+    const int pairs_n = (int)((hd.N + 127) / 128), pairs_k = (int)((hd.K + 127) / 128);
+    a1.npairs = pairs_n;
+    a1.last_steps = 4;
+    a1.rows_need = 128 * pairs_k;              // every rank position that stage U reads is written (zeros beyond K)
 
     gemm_args a2 = a1;
     a2.tiles = reinterpret_cast<const uint32_t*>(g.blob + hd.off_U);
@@ -1926,6 +1952,9 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     a2.out_bf16 = g.out_bf16;
     a2.out_token_major = g.y_token_major;
     a2.rows_valid = (int)hd.M;
+    a2.rows_need = (int)hd.M;
+    a2.npairs = pairs_k;
+    a2.last_steps = hd.K % 128 == 0 ? 4 : (int)((hd.K % 128 + 31) / 32);
 
     if (tsvd_stage_mask() == 7 && tsvd_gemm_use_panel(hd.Mp, hd.Kp, hd.Np, g.B, g.cu_count, fast1)) {
         panel_args pa;
@@ -1935,6 +1964,8 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
         pa.tile_u_bytes = a2.tile_bytes;
         pa.nkt_v = a1.nkt;
         pa.nkt_u = a2.nkt;
+        pa.npairs_v = a1.npairs;
+        pa.npairs_u = a2.npairs;
         pa.x = a1.act;
         pa.ldx = g.ldx;
         pa.x_bytes = a1.act_bytes;
@@ -1989,7 +2020,7 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     if ((mask & 2) && fp6_v) {
         unsigned char* xplanes = reinterpret_cast<unsigned char*>(Z) + (((size_t)hd.Kp * Bp * 2 + 255) & ~(size_t)255) +
                                  ((tsvd_gemm_fp6_bytes(hd.Kp, Bp) + 255) & ~(size_t)255);
-        hipLaunchKernelGGL(tsvd_z_planes_kernel<true>, dim3((unsigned)((g.B + 127) / 128), (unsigned)(hd.Np / 128)), dim3(512), 0, stream,
+        hipLaunchKernelGGL(tsvd_z_planes_kernel<true>, dim3((unsigned)((g.B + 127) / 128), (unsigned)a1.npairs), dim3(512), 0, stream,
                            static_cast<const uint16_t*>(g.x), (long long)g.ldx, (int)hd.N, (int)g.B, (int)(hd.Np / 128), xplanes);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         gemm_args a4 = a1;
@@ -2002,7 +2033,7 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     if ((mask & 4) && tsvd_gemm_use_fp6(hd.Mp, hd.Kp, hd.Np, g.B, g.cu_count, fast1)) {
         // Z (fp16) -> three fp6 planes in operand order, then stage U on fp4 x fp6
         unsigned char* planes = reinterpret_cast<unsigned char*>(Z) + (((size_t)hd.Kp * Bp * 2 + 255) & ~(size_t)255);
-        hipLaunchKernelGGL(tsvd_z_planes_kernel<false>, dim3((unsigned)((g.B + 127) / 128), (unsigned)(hd.Kp / 128)), dim3(512), 0, stream,
+        hipLaunchKernelGGL(tsvd_z_planes_kernel<false>, dim3((unsigned)((g.B + 127) / 128), (unsigned)a2.npairs), dim3(512), 0, stream,
                            reinterpret_cast<const uint16_t*>(Z), (long long)Bp, (int)hd.Kp, Bp, (int)(hd.Kp / 128), planes);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         gemm_args a3 = a2;

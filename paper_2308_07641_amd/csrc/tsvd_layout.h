@@ -22,13 +22,24 @@
 // (w << (14 - 2 c)) & 0xC000C000 turns codes c and c + 8 into the two 16-bit floats 0x0000,
 // 0x4000 (+2), 0xC000 (-2) (same patterns in bf16 and fp16) and the activation rows are fetched
 // in the matching order.  The factor 2 per stage is removed exactly by the epilogues.
+//
+// Position of the rank index.  The order of the rank index k (columns of U, entries of S, rows of V) is free
+// (the sum over k does not depend on it), and the format uses that freedom in ONE place: when K is not a
+// multiple of 128, the last, partly filled block of 128 rank positions stores its K % 128 valid indices in the
+// positions that the first MFMA sub-steps of a 128-step touch.  A sub-step (u, p) of 32 contraction indices
+// (word u of the pair, even / odd codes p) covers the positions kk = 64 a + 32 u + 16 b + 8 p + n (a, b in
+// {0, 1}, n < 8), so logical offset j = 64 u + 32 p + 16 a + 8 b + n of that block lives at position kk: a
+// permutation of four bits of the offset.  With r = K % 128 valid indices only the first ceil(r / 32)
+// sub-steps of the last step hold anything but zeros, and the batched kernels skip the others.
+// tsvd_rank_position / tsvd_rank_logical are the map and its inverse; every reader of U's columns, S and V's
+// rows that starts from a logical rank index goes through them (the packer, the grouped-convolution kernel).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
 
 #define TSVD_MAGIC 0x5449423244565354ull /* "TSVD2BIT" little endian */
-#define TSVD_FORMAT_VERSION 2u
+#define TSVD_FORMAT_VERSION 3u
 #define TSVD_TILE_ROWS 16
 #define TSVD_TILE_COLS 256
 #define TSVD_TILE_BYTES 1024
@@ -48,6 +59,20 @@ struct tsvd_blob_header {
 static_assert(sizeof(tsvd_blob_header) == 256, "header must be 256 bytes");
 
 static inline int64_t tsvd_round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+// Physical position of logical rank index k (0 <= k < Kp) for a matrix of rank K, and the inverse.
+__host__ __device__ static inline int64_t tsvd_rank_position(int64_t k, int64_t K) {
+    if ((K & 127) == 0 || (k >> 7) != (K >> 7)) return k;
+    const int j = (int)(k & 127);
+    const int kk = (((j >> 4) & 1) << 6) | (((j >> 6) & 1) << 5) | (((j >> 3) & 1) << 4) | (((j >> 5) & 1) << 3) | (j & 7);
+    return (k & ~(int64_t)127) | kk;
+}
+__host__ __device__ static inline int64_t tsvd_rank_logical(int64_t pos, int64_t K) {
+    if ((K & 127) == 0 || (pos >> 7) != (K >> 7)) return pos;
+    const int kk = (int)(pos & 127);
+    const int j = (((kk >> 5) & 1) << 6) | (((kk >> 3) & 1) << 5) | (((kk >> 6) & 1) << 4) | (((kk >> 4) & 1) << 3) | (kk & 7);
+    return (pos & ~(int64_t)127) | j;
+}
 
 // Column kk (0..127) of an MFMA step  <->  (lane group g, operand element e).
 static inline int tsvd_step_column(int g, int e) { return 64 * (g & 1) + 32 * (e >> 4) + 16 * (g >> 1) + (e & 15); }

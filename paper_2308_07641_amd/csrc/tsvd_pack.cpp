@@ -49,9 +49,10 @@ unsigned worker_count(int64_t work_items) {
     return (unsigned)std::min<int64_t>(hw, work_items / 32 + 1);
 }
 
-// Packs A [R][C] (row-major, valid part R x C, padded to Rp x Cp) into tiles.
+// Packs A [R][C] (row-major, valid part R x C, padded to Rp x Cp) into tiles.  rank_rows / rank_cols: the
+// rank K when the rows / columns of A are the rank index (they are stored at tsvd_rank_position), else 0.
 // Returns false if an entry is outside {-1,0,+1}.  nnz_total receives the sum of counts.
-bool pack_matrix(const int8_t* A, int64_t R, int64_t C, int64_t Rp, int64_t Cp,
+bool pack_matrix(const int8_t* A, int64_t R, int64_t C, int64_t Rp, int64_t Cp, int64_t rank_rows, int64_t rank_cols,
                  uint32_t* tiles, uint16_t* nnz, int64_t* nnz_total) {
     const int64_t strips = Rp / TSVD_TILE_ROWS, nkt = Cp / TSVD_TILE_COLS;
     std::atomic<bool> bad(false);
@@ -64,13 +65,15 @@ bool pack_matrix(const int8_t* A, int64_t R, int64_t C, int64_t Rp, int64_t Cp,
                 std::memset(tile, 0, TSVD_TILE_BYTES);
                 int count = 0;
                 for (int i = 0; i < TSVD_TILE_ROWS; ++i) {
-                    const int64_t r = s * TSVD_TILE_ROWS + i;
-                    if (r >= R) break;
+                    const int64_t pr = s * TSVD_TILE_ROWS + i;                      // physical row -> logical row
+                    const int64_t r = rank_rows ? tsvd_rank_logical(pr, rank_rows) : pr;
+                    if (r >= R) continue;
                     const int64_t c0 = T * TSVD_TILE_COLS;
-                    const int64_t cn = std::min<int64_t>(TSVD_TILE_COLS, C - c0);
-                    const int8_t* row = A + r * C + c0;
-                    for (int64_t c = 0; c < cn; ++c) {
-                        const int v = row[c];
+                    const int8_t* row = A + r * C;
+                    for (int64_t c = 0; c < TSVD_TILE_COLS; ++c) {
+                        const int64_t col = rank_cols ? tsvd_rank_logical(c0 + c, rank_cols) : c0 + c;
+                        if (col >= C) continue;
+                        const int v = row[col];
                         if (v == 0) continue;
                         if (v != 1 && v != -1) { bad.store(true); return; }
                         int word, bit;
@@ -103,7 +106,7 @@ bool pack_matrix(const int8_t* A, int64_t R, int64_t C, int64_t Rp, int64_t Cp,
 
 // Inverse of pack_matrix for the valid R x C part; verifies padding is zero, no code is 10b
 // and the stored counts match.  Returns false on any corruption.
-bool unpack_matrix(int8_t* A, int64_t R, int64_t C, int64_t Rp, int64_t Cp,
+bool unpack_matrix(int8_t* A, int64_t R, int64_t C, int64_t Rp, int64_t Cp, int64_t rank_rows, int64_t rank_cols,
                    const uint32_t* tiles, const uint16_t* nnz, bool check_only) {
     const int64_t strips = Rp / TSVD_TILE_ROWS, nkt = Cp / TSVD_TILE_COLS;
     std::atomic<bool> bad(false);
@@ -113,12 +116,14 @@ bool unpack_matrix(int8_t* A, int64_t R, int64_t C, int64_t Rp, int64_t Cp,
                 const uint32_t* tile = tiles + (s * nkt + T) * (TSVD_TILE_BYTES / 4);
                 int count = 0;
                 for (int i = 0; i < TSVD_TILE_ROWS; ++i) {
-                    const int64_t r = s * TSVD_TILE_ROWS + i;
+                    const int64_t pr = s * TSVD_TILE_ROWS + i;
+                    const int64_t r = rank_rows ? tsvd_rank_logical(pr, rank_rows) : pr;
                     for (int c = 0; c < TSVD_TILE_COLS; ++c) {
                         int word, bit;
                         tsvd_code_position(i, c, &word, &bit);
                         const unsigned code = (tile[word] >> bit) & 3u;
-                        const int64_t col = T * TSVD_TILE_COLS + c;
+                        const int64_t pc = T * TSVD_TILE_COLS + c;
+                        const int64_t col = rank_cols ? tsvd_rank_logical(pc, rank_cols) : pc;
                         const bool inside = r < R && col < C;
                         if (code == 2u || (!inside && code != 0u)) { bad.store(true); return; }
                         if (code) ++count;
@@ -177,11 +182,14 @@ extern "C" tsvd_status tsvd_pack_host(const int8_t* U, const float* S, const int
     hd.off_nnzU = sc.off_nnzU; hd.off_nnzV = sc.off_nnzV;
     hd.total_bytes = sc.total;
 
-    std::memcpy(base + sc.off_S, S, (size_t)K * sizeof(float));
-    if (!pack_matrix(U, M, K, sc.Mp, sc.Kp, reinterpret_cast<uint32_t*>(base + sc.off_U),
+    {
+        float* Sp = reinterpret_cast<float*>(base + sc.off_S);
+        for (int64_t k = 0; k < K; ++k) Sp[tsvd_rank_position(k, K)] = S[k];
+    }
+    if (!pack_matrix(U, M, K, sc.Mp, sc.Kp, 0, K, reinterpret_cast<uint32_t*>(base + sc.off_U),
                      reinterpret_cast<uint16_t*>(base + sc.off_nnzU), &hd.nnzU))
         return TSVD_EVALUE;
-    if (!pack_matrix(V, K, N, sc.Kp, sc.Np, reinterpret_cast<uint32_t*>(base + sc.off_V),
+    if (!pack_matrix(V, K, N, sc.Kp, sc.Np, K, 0, reinterpret_cast<uint32_t*>(base + sc.off_V),
                      reinterpret_cast<uint16_t*>(base + sc.off_nnzV), &hd.nnzV))
         return TSVD_EVALUE;
     std::memcpy(base, &hd, sizeof hd);
@@ -205,18 +213,20 @@ extern "C" tsvd_status tsvd_unpack_host(const void* blob, size_t blob_bytes, int
     if (U || S || V) {
         // S padding must be zero: the kernels rely on it.
         const float* Sp = reinterpret_cast<const float*>(base + sc.off_S);
-        for (int64_t k = hd.K; k < sc.Kp; ++k) {
+        for (int64_t pos = 0; pos < sc.Kp; ++pos) {
+            if (tsvd_rank_logical(pos, hd.K) < hd.K) continue;
             uint32_t bits;
-            std::memcpy(&bits, Sp + k, 4);
+            std::memcpy(&bits, Sp + pos, 4);
             if (bits != 0) return TSVD_EVALUE;
         }
-        if (!unpack_matrix(U, hd.M, hd.K, sc.Mp, sc.Kp, reinterpret_cast<const uint32_t*>(base + sc.off_U),
+        if (!unpack_matrix(U, hd.M, hd.K, sc.Mp, sc.Kp, 0, hd.K, reinterpret_cast<const uint32_t*>(base + sc.off_U),
                            reinterpret_cast<const uint16_t*>(base + sc.off_nnzU), U == nullptr))
             return TSVD_EVALUE;
-        if (!unpack_matrix(V, hd.K, hd.N, sc.Kp, sc.Np, reinterpret_cast<const uint32_t*>(base + sc.off_V),
+        if (!unpack_matrix(V, hd.K, hd.N, sc.Kp, sc.Np, hd.K, 0, reinterpret_cast<const uint32_t*>(base + sc.off_V),
                            reinterpret_cast<const uint16_t*>(base + sc.off_nnzV), V == nullptr))
             return TSVD_EVALUE;
-        if (S) std::memcpy(S, Sp, (size_t)hd.K * sizeof(float));
+        if (S)
+            for (int64_t k = 0; k < hd.K; ++k) std::memcpy(S + k, Sp + tsvd_rank_position(k, hd.K), sizeof(float));
     }
     if (M) *M = hd.M;
     if (K) *K = hd.K;

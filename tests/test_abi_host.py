@@ -113,16 +113,38 @@ def _code_at(words, tiles_per_strip, r, c):
     return (int(words[((r >> 4) * tiles_per_strip + (c >> 8)) * 256 + word]) >> (2 * (2 * n + (v & 1)))) & 3
 
 
-def test_element_position_rule_of_the_tile_format():
-    """Kernels that read single codes (the grouped convolution) use this rule; it must agree with the packer."""
-    i = workloads.make_inputs(40, 300, 70, 1, 0.6, 0.02, "f32", seed=5)
+def _rank_position(k, K):
+    """Where rank index k is stored: the last, partly filled block of 128 rank positions keeps its valid indices in the
+    positions of the first 32-index sub-steps (offset bits [u p a b n] -> position bits [a u b p n])."""
+    if K % 128 == 0 or k // 128 != K // 128:
+        return k
+    j = k % 128
+    u, p_, a, b, n = (j >> 6) & 1, (j >> 5) & 1, (j >> 4) & 1, (j >> 3) & 1, j & 7
+    return (k - j) + (a << 6 | u << 5 | b << 4 | p_ << 3 | n)
+
+
+@pytest.mark.parametrize("K", [70, 128, 200, 345, 9])
+def test_element_position_rule_of_the_tile_format(K):
+    """Kernels that read single codes (the grouped convolution) use this rule; it must agree with the packer.  The
+    rank index goes through the position rule of the format; S sits at the same positions, zeros elsewhere."""
+    i = workloads.make_inputs(40, 300, K, 1, 0.6, 0.02, "f32", seed=5)
     blob = tsvd.tsvd_pack_host(i.U, i.S, i.V)
     s = _sections(blob)
     Uw = np.frombuffer(blob[s["off_U"]:s["off_V"]].tobytes(), dtype=np.uint32)
     Vw = np.frombuffer(blob[s["off_V"]:s["off_nnzU"]].tobytes(), dtype=np.uint32)
+    Sw = np.frombuffer(blob[s["off_S"]:s["off_S"] + 4 * s["Kp"]].tobytes(), dtype=np.float32)
     value = {0: 0, 1: 1, 3: -1}
-    assert all(value[_code_at(Uw, s["Kp"] // 256, r, c)] == i.U[r, c] for r in range(40) for c in range(70))
-    assert all(value[_code_at(Vw, s["Np"] // 256, r, c)] == i.V[r, c] for r in range(70) for c in range(0, 300, 7))
+    pos = [_rank_position(k, K) for k in range(K)]
+    assert len(set(pos)) == K and max(pos) < s["Kp"]
+    # valid indices of the last block fill the first sub-steps: position bits 5 (u) and 3 (p) in that order
+    r = K % 128
+    if r:
+        steps = sorted({((q % 128) >> 5 & 1) * 2 + ((q % 128) >> 3 & 1) for q in pos[K - r:]})
+        assert steps == list(range(-(-r // 32)))
+    assert all(value[_code_at(Uw, s["Kp"] // 256, r_, pos[c])] == i.U[r_, c] for r_ in range(40) for c in range(K))
+    assert all(value[_code_at(Vw, s["Np"] // 256, pos[r_], c)] == i.V[r_, c] for r_ in range(K) for c in range(0, 300, 7))
+    assert all(Sw[pos[k]] == i.S[k] for k in range(K))
+    assert np.count_nonzero(Sw) == np.count_nonzero(i.S)
 
 
 def test_single_element_sets_exactly_its_code():
@@ -131,7 +153,7 @@ def test_single_element_sets_exactly_its_code():
     S = np.ones(300, dtype=np.float32)
     base = tsvd.tsvd_pack_host(U, S, V)
     s = _sections(base)
-    for (r, c, val, bits) in ((0, 0, 1, 1), (19, 299, -1, 2), (7, 131, 1, 1), (16, 256, -1, 2)):
+    for (r, c, val, bits) in ((0, 0, 1, 1), (19, 299, -1, 2), (7, 131, 1, 1), (16, 256, -1, 2), (3, 260, 1, 1)):
         U2 = U.copy()
         U2[r, c] = val
         b2 = tsvd.tsvd_pack_host(U2, S, V)

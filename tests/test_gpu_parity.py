@@ -419,6 +419,51 @@ def test_degenerate_inputs(tsvd, B):
         assert rel_err(y, ref) <= TOL["bf16"]
 
 
+# ---- ranks that are not multiples of the tile: the ranks of the supplement's layer listing (5, 63, 345, 1545, 2415)
+# ---- on its layer shapes (768 -> 3072, 768 -> 1000, 3072 -> 768 reduced).  The batched kernels run ceil(K / 128) steps of
+# ---- the contraction and only the filled 32-index sub-steps of the last one.
+RAGGED_RANKS = [5, 63, 96, 129, 345, 1545, 2415]
+
+
+@pytest.mark.parametrize("family", ["rule", "ring14", "ring16", "pipe1", "pipe3", "fallback", "panel", "fp6"])
+@pytest.mark.parametrize("K", RAGGED_RANKS)
+def test_ragged_rank_batched(tsvd, K, family):
+    M, N, B = (1000, 768, 200) if K == 2415 else (600, 384, 200)
+    if family == "panel" and K > 1024:
+        pytest.skip("the token-panel kernel serves ranks up to 1024")
+    sw = {"rule": {}, "ring14": {"TSVD_PANEL": 0, "TSVD_FP6": 0, "TSVD_GEMM_CFG_U": 14, "TSVD_GEMM_CFG_V": 15},
+          "ring16": {"TSVD_PANEL": 0, "TSVD_FP6": 0, "TSVD_GEMM_CFG_U": 16, "TSVD_GEMM_CFG_V": 16},
+          "pipe1": {"TSVD_PANEL": 0, "TSVD_FP6": 0, "TSVD_GEMM_CFG_U": 1, "TSVD_GEMM_CFG_V": 2},
+          "pipe3": {"TSVD_PANEL": 0, "TSVD_FP6": 0, "TSVD_GEMM_CFG_U": 3, "TSVD_GEMM_CFG_V": 0},
+          "fallback": {"TSVD_PANEL": 0, "TSVD_FP6": 0, "TSVD_REALIGN": 0, "TSVD_GEMM_CFG_U": 2, "TSVD_GEMM_CFG_V": 3},
+          "panel": {"TSVD_PANEL": 1},
+          "fp6": {"TSVD_PANEL": 0, "TSVD_FP6": 1, "TSVD_FP6_V": 1, "TSVD_GEMM_CFG_V": 3, "TSVD_FP6_TALL": 3}}[family]
+    for k, v in sw.items():
+        tsvd.tsvd_tuning_set(k, v)
+    Bx = B + 1 if family == "fallback" else B                 # odd row pitch: the register-staged kernel
+    print(f"case ragged rank K={K} {family}", flush=True)
+    i = workloads.make_integer_inputs(M, N, K, Bx, 0.5, "bf16", seed=31 * K + len(family))
+    y, h = run_forward(i)
+    tsvd.tsvd_free(h)
+    assert not np.isnan(y).any()
+    assert np.array_equal(y, oracle.forward(i.U, i.S, i.V, i.X))
+    j = workloads.make_inputs(M, N, K, Bx, 0.7, 0.02, "bf16", seed=32 * K + len(family))
+    y, h = run_forward(j)
+    tsvd.tsvd_free(h)
+    assert rel_err(y, oracle.forward(j.U, j.S, j.V, j.X)) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("B", [1, 2, 9])
+@pytest.mark.parametrize("K", RAGGED_RANKS)
+def test_ragged_rank_few_tokens(tsvd, K, B):
+    """The single-token and few-token kernels read whole tiles; the positions of the rank index must agree with theirs."""
+    for x_dtype in ("bf16", "f32"):
+        i = workloads.make_integer_inputs(520, 300, K, B, 0.5, x_dtype, seed=77 * K + B)
+        y, h = run_forward(i)
+        tsvd.tsvd_free(h)
+        assert np.array_equal(y, oracle.forward(i.U, i.S, i.V, i.X)), f"{x_dtype}"
+
+
 # ---- the layer form (tsvd_forward_ex): bias, bf16 output, token-major activations, in every
 # ---- kernel family.  Exact instances: an integer bias keeps every value an exactly representable
 # ---- integer, so the fp32 output must equal the oracle and the bf16 output its exact rounding.
