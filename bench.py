@@ -5,10 +5,14 @@
 
 A step is one pass of the whole hot path (all kernels of tsvd_forward) over one batch of the
 seeded synthetic workload; inputs are resident in HBM before the timed region.  The headline
-line is for the BERT-base FFN-in shape (configs[1] of the benchmark spec); the other workloads are
-reported in "per_config" of the same JSON line.  Rooflines use executed flops 2 K (M+N) B
-against 2.5 PFLOP/s (bf16/fp16 MFMA) for the batched shapes and algorithmic bytes
-K (M+N)/4 + 4K + N sizeof(x) + 4M against 8 TB/s for B = 1.
+line is for the largest configuration of the benchmark spec that fits one GPU, the OPT-66B fc1 prefill
+shape (opt66b_fc1_prefill); the other workloads are reported in "per_config" of the same JSON line.
+The roofline of a batched workload prices the algorithmic flops of its dominant kernel (stage U:
+2 M K B) against the dense MFMA peak of the operand types that kernel multiplies (fp4 x fp6:
+10.1 PFLOP/s; bf16 / fp16: 2.5 PFLOP/s, given beside it); B = 1 prices algorithmic bytes
+K (M+N)/4 + 4K + N sizeof(x) + 4M against 8 TB/s.  "traffic" is read from the tracked counter summary
+profiles/hbm_traffic_fetch_write_size.md and only reported when that summary was taken on the kernel
+the library selects now (else null).
 """
 from __future__ import annotations
 
@@ -29,15 +33,24 @@ import workloads  # noqa: E402
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_TFLOPS = 2500.0
 PEAK_MFMA_FP6_TFLOPS = 10100.0      # dense fp6 / fp4 MFMA
-PRIMARY = "bert_ffn_in"
-# HBM bytes per launch of the stage-U kernel (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors a
-# plain 256 MiB copy gives), from profiles/hbm_traffic_fetch_write_size.md.  Counters cannot be read
-# inside this process; the figures belong to the launch shapes bench.py uses.
-PANEL_TRAFFIC_BYTES = {"convnext_mlp": 18.4e6 + 102.8e6}   # token-panel launches, same profile
-STAGE_U_TRAFFIC_BYTES = {"bert_ffn_in": 11.1e6 + 6.29e6, "convnext_mlp": 186e6 + 102.8e6,
-                         "opt66b_fc1_prefill": 1817.2e6 + 302.0e6 + 75.6e6 + 89.7e6,   # fp6 kernel fetch + write, planes pass fetch + write
-                         "opt6b7_fc1_decode": 34.2e6 + 0.066e6,
-                         "opt6b7_fc1_decode_b16": 35.9e6 + 1.05e6}
+PRIMARY = "opt66b_fc1_prefill"
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "hbm_traffic_fetch_write_size.md")
+
+
+def _traffic_from_profile(workload, kernel_key):
+    """HBM bytes per launch of the dominant kernel (scaled FETCH_SIZE + WRITE_SIZE) from the tracked counter
+    summary, or None when the summary has no record for this workload or was taken on another kernel / tile
+    shape than the library selects now (kernel_key).  The record is the fenced block "json bench-traffic"."""
+    try:
+        text = open(TRAFFIC_PROFILE).read()
+        start = text.index("```json bench-traffic") + len("```json bench-traffic")
+        table = json.loads(text[start:text.index("```", start)])
+    except (OSError, ValueError):
+        return None
+    rec = table.get(workload)
+    if not rec or rec.get("kernel") != kernel_key:
+        return None
+    return float(rec["fetch_bytes"]) + float(rec["write_bytes"])
 
 
 def _device_x(inputs, dev):
@@ -70,14 +83,14 @@ def _stage_u_kernel_name(tsvd, handle, B):
     try:
         _, su = tsvd.tsvd_tuning_tile_shapes(handle, B)
     except ValueError:
-        return "batched stage-U kernel"
+        return "batched stage-U kernel", -1
     if su < 0:
-        return "batched stage-U kernel"
+        return "batched stage-U kernel", su
     if su == 32:
-        return "tsvd_panel_kernel"
+        return "tsvd_panel_kernel", su
     if su == 40:
-        return "tsvd_gemm_fp6_kernel"
-    return "tsvd_gemm_ring_kernel" if su >= 14 else "tsvd_gemm_pipe_kernel"
+        return "tsvd_gemm_fp6_kernel", su
+    return ("tsvd_gemm_ring_kernel" if su >= 14 else "tsvd_gemm_pipe_kernel"), su
 
 
 def cpu_baseline(w, inputs, budget_s):
@@ -161,7 +174,10 @@ def bench_workload(name, steps, warmup, with_cpu=True, cpu_budget_s=4.0):
     step_rot()                      # a full pass again: y is compared with the oracle below
     torch.cuda.synchronize()
     res["stage_ms"] = {"V": v_ms, "U": u_ms}
-    kernel_name = _stage_u_kernel_name(tsvd, handles[0], w.B) if batched else None
+    kernel_name, shape_u = _stage_u_kernel_name(tsvd, handles[0], w.B) if batched else (None, -1)
+    kernel_key = f"{kernel_name}:{shape_u}" if batched else ("tsvd_mid_kernel" if w.B > 1 else "tsvd_gemv_kernel")
+    traffic = _traffic_from_profile(name, kernel_key)
+    res["dominant_kernel_key"] = kernel_key
     if batched and kernel_name == "tsvd_panel_kernel":
         # one launch does both stages (z stays in LDS): the call IS the dominant kernel; the stage
         # times above belong to the two-launch path that the stage mask falls back to
@@ -169,7 +185,7 @@ def bench_workload(name, steps, warmup, with_cpu=True, cpu_budget_s=4.0):
         res["roofline"] = {"bound": "mfma", "kernel": "tsvd_panel_kernel (both stages, bf16 + fp16 MFMA)",
                            "achieved": res["executed_tflops"], "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                            "frac": res["executed_tflops"] / PEAK_MFMA_TFLOPS,
-                           "traffic": PANEL_TRAFFIC_BYTES.get(name),
+                           "traffic": traffic,
                            "whole_path_frac": res["executed_tflops"] / PEAK_MFMA_TFLOPS}
     elif batched and kernel_name == "tsvd_gemm_fp6_kernel":
         # stage U = planes pass + fp4 x fp6 kernel.  Achieved = ALGORITHMIC flops (2 M K B) per second; the
@@ -178,18 +194,20 @@ def bench_workload(name, steps, warmup, with_cpu=True, cpu_budget_s=4.0):
         # is what every other batched kernel here is priced against.
         fl_u = 2.0 * w.K * w.M * w.B
         ach = fl_u / (u_ms * 1e-3) / 1e12
-        res["roofline"] = {"bound": "mfma", "kernel": "tsvd_z_planes_kernel + tsvd_gemm_fp6_kernel (stage U, fp4 x fp6 MFMA, 3 planes)",
+        res["roofline"] = {"bound": "mfma", "kernel": "tsvd_gemm_fp6_kernel (stage U, fp4 x fp6 MFMA, 3 planes) with its operand pass tsvd_z_planes_kernel "
+                                                     "(about 2 % of the time; both are timed together)",
                            "achieved": ach, "peak": PEAK_MFMA_FP6_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_MFMA_FP6_TFLOPS,
+                           "algorithmic_flops": fl_u, "launch_ms": u_ms,
                            "executed_tflops": 3.0 * ach, "executed_frac": 3.0 * ach / PEAK_MFMA_FP6_TFLOPS,
-                           "frac_of_fp16_peak": ach / PEAK_MFMA_TFLOPS,
-                           "traffic": STAGE_U_TRAFFIC_BYTES.get(name),
-                           "whole_path_frac_of_fp16_peak": res["executed_tflops"] / PEAK_MFMA_TFLOPS}
+                           "frac_of_bf16_peak": ach / PEAK_MFMA_TFLOPS,
+                           "traffic": traffic,
+                           "whole_path_frac_of_bf16_peak": res["executed_tflops"] / PEAK_MFMA_TFLOPS}
     elif batched:
         fl_u = 2.0 * w.K * w.M * w.B
         res["roofline"] = {"bound": "mfma", "kernel": kernel_name + " (stage U, fp16 MFMA)",
                            "achieved": fl_u / (u_ms * 1e-3) / 1e12, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                            "frac": fl_u / (u_ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS,
-                           "traffic": STAGE_U_TRAFFIC_BYTES.get(name),
+                           "traffic": traffic,
                            "whole_path_frac": res["executed_tflops"] / PEAK_MFMA_TFLOPS}
     else:
         xb = 2 if w.x_dtype == "bf16" else 4
@@ -203,7 +221,7 @@ def bench_workload(name, steps, warmup, with_cpu=True, cpu_budget_s=4.0):
         gbs = bytes_u / (u_ms * 1e-3) / 1e9
         res["roofline"] = {"bound": "hbm", "kernel": "tsvd_mid_kernel (stage U)" if few else "tsvd_gemv_kernel (stage U)",
                            "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
-                           "traffic": STAGE_U_TRAFFIC_BYTES.get(name), "algorithmic_bytes": bytes_u,
+                           "traffic": traffic, "algorithmic_bytes": bytes_u,
                            "whole_path_gbs": bytes_alg / (ev_ms * 1e-3) / 1e9,
                            "whole_path_frac": bytes_alg / (ev_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
                            "whole_path_bytes": bytes_alg,
@@ -319,7 +337,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workloads",
-                    default="bert_ffn_in,tiny,convnext_mlp,opt6b7_fc1_decode,opt6b7_fc1_decode_b16,opt6b7_fc1_prefill_b256,opt66b_fc1_prefill")
+                    default="opt66b_fc1_prefill,tiny,bert_ffn_in,convnext_mlp,opt6b7_fc1_decode,opt6b7_fc1_decode_b16,opt6b7_fc1_prefill_b256,ffn_768x3072_rank1545")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing / parity leg")
     ap.add_argument("--no-transition", action="store_true", help="skip the transition (Algorithm 2) measurement")
     ap.add_argument("--conv-only", action="store_true", help="run only the convolution-form measurement (for profiling)")
@@ -379,9 +397,12 @@ def main():
         "metric": "TSVD linear fwd: tokens/s + HBM GB/s (B=1) / MFMA util (batched) vs roofline",
         "value": p["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": p["steps"], "warmup": args.warmup,
         "ms_per_step": p["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{PRIMARY}: M={w.M} N={w.N} K={w.K} B={w.B}, ternary U,V P(0)={w.p0}, bf16 X"},
-        "roofline": {k: p["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")},
+        "dtype": "fp4 codes x fp6 (E2M3) planes of bf16 x / fp16 z, fp32 accumulation",
+        "data": "synthetic",
+        "config": {"workload": f"{PRIMARY}: M={w.M} N={w.N} K={w.K} B={w.B}, ternary U,V P(0)={w.p0}, bf16 X",
+                   "executed_tflops": p["executed_tflops"], "dense_equiv_tflops": p["dense_equiv_tflops"]},
+        "roofline": {k: p["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel",
+                                                    "frac_of_bf16_peak", "whole_path_frac_of_bf16_peak") if k in p["roofline"]},
         "cpu_baseline": p.get("cpu_baseline"),
         "per_config": per,
     }

@@ -40,6 +40,7 @@ def test_columns_cover_the_whole_token_range():
     ("opt66b_fc1_prefill", 64, 2e-3),
     ("opt6b7_fc1_decode_b16", None, 2e-3),
     ("opt6b7_fc1_prefill_b256", 64, 2e-3),
+    ("ffn_768x3072_rank1545", 96, 2e-3),
 ])
 def test_named_workload(name, ncols, tol):
     import paper_2308_07641_amd as tsvd

@@ -47,6 +47,9 @@ WORKLOADS = {
         Workload("opt6b7_fc1_decode_b16", 6, 16384, 4096, 8192, 16, 0.6, 0.01, "bf16"),
         # the same layer on a prefill chunk of 256 tokens (measurement case of the small tiles of the batched path)
         Workload("opt6b7_fc1_prefill_b256", 7, 16384, 4096, 8192, 256, 0.6, 0.01, "bf16"),
+        # a 768 -> 3072 layer at a rank of the supplement's layer listing that is no multiple of the tile (1545), with the
+        # non-zero rate the paper reports for converted layers (about 0.28), on 4096 tokens (measurement case of ragged ranks)
+        Workload("ffn_768x3072_rank1545", 8, 3072, 768, 1545, 4096, 0.72, 0.02, "bf16"),
     )
 }
 
