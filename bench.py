@@ -236,6 +236,48 @@ def bench_workload(name, steps, warmup, with_cpu=True, cpu_budget_s=4.0):
     return res
 
 
+def bench_dense_codes(steps=200, warmup=20):
+    """NEXT row of the scope table (the paper's remark that 2 bits per ternary element are redundant): stage U of
+    the single-token decode workload on the five-elements-per-byte code of U (1.6 bits per element) against the
+    2-bit tiles, weights rotating through HBM.  The dense code is a diagnostic switch, never a default."""
+    import torch
+    import paper_2308_07641_amd as tsvd
+    name = "opt6b7_fc1_decode"
+    w = workloads.WORKLOADS[name]
+    inputs = workloads.make_workload(name)
+    dev = torch.device("cuda:0")
+    x = _device_x(inputs, dev)
+    y = torch.empty((w.M, 1), dtype=torch.float32, device=dev)
+    out = {"workload": f"{name}: stage U on 2-bit tiles vs five elements per byte", "bytes_of_U": {"two_bit": w.M * w.K / 4.0,
+           "dense": float(tsvd.tsvd_dense_bytes(w.M, w.K))}}
+    import oracle
+    ref = oracle.forward(inputs.U, inputs.S, inputs.V, inputs.X)
+    for label, flag in (("two_bit", 0), ("dense", 1)):
+        tsvd.tsvd_tuning_set("TSVD_DENSE_U", flag)
+        handles = [tsvd.tsvd_pack(inputs.U, inputs.S, inputs.V) for _ in range(16)]
+        tsvd.tsvd_tuning_reset()
+        ws = torch.empty(tsvd.tsvd_workspace_bytes(handles[0], 1, tsvd.TSVD_BF16), dtype=torch.uint8, device=dev)
+        state = {"i": 0}
+
+        def full():
+            state["i"] += 1
+            tsvd.tsvd_forward(handles[state["i"] % 16], x, y, workspace=ws)
+
+        def stage_u():
+            state["i"] += 1
+            tsvd.tsvd_tuning_forward_stages(handles[state["i"] % 16], x, y, 4, workspace=ws)
+
+        _, call_ms = _timed(full, steps, warmup)
+        _, u_ms = _timed(stage_u, steps, warmup)
+        full()
+        torch.cuda.synchronize()
+        err = float(np.max(np.abs(y.cpu().numpy().astype(np.float64) - ref)) / np.max(np.abs(ref)))
+        out[label] = {"call_us": call_ms * 1e3, "stage_u_us": u_ms * 1e3, "parity_rel_err": err}
+        for h in handles:
+            tsvd.tsvd_free(h)
+    return out
+
+
 def bench_transition(max_rank_gpu=64, max_rank_cpu=24):
     """NEXT row of the scope table: the direct transition W -> (U, S, V) (Algorithm 2) on the
     paper's random-matrix setting, a [512, 256] Laplace matrix at theta = 0.576.  A bounded number
@@ -340,6 +382,7 @@ def main():
                     default="opt66b_fc1_prefill,tiny,bert_ffn_in,convnext_mlp,opt6b7_fc1_decode,opt6b7_fc1_decode_b16,opt6b7_fc1_prefill_b256,ffn_768x3072_rank1545")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing / parity leg")
     ap.add_argument("--no-transition", action="store_true", help="skip the transition (Algorithm 2) measurement")
+    ap.add_argument("--dense-codes-only", action="store_true", help="run only the dense-code measurement (for profiling)")
     ap.add_argument("--conv-only", action="store_true", help="run only the convolution-form measurement (for profiling)")
     ap.add_argument("--transition-only", action="store_true",
                     help="run only the transition measurement and print its record (for profiling)")
@@ -364,6 +407,9 @@ def main():
         return
     if args.conv_only:
         print(json.dumps(bench_conv()), flush=True)
+        return
+    if args.dense_codes_only:
+        print(json.dumps(bench_dense_codes()), flush=True)
         return
 
     if args.copy_calibration:
@@ -390,6 +436,8 @@ def main():
         print(f"[bench] transition: {json.dumps(per['transition_laplace_512x256'])}", file=sys.stderr, flush=True)
         per["conv3x3_c256"] = bench_conv()
         print(f"[bench] conv: {json.dumps(per['conv3x3_c256'])}", file=sys.stderr, flush=True)
+        per["dense_codes_decode"] = bench_dense_codes()
+        print(f"[bench] dense codes: {json.dumps(per['dense_codes_decode'])}", file=sys.stderr, flush=True)
 
     p = per[PRIMARY]
     w = workloads.WORKLOADS[PRIMARY]

@@ -84,6 +84,23 @@ tsvd_status tsvd_unpack(const tsvd_handle* h, int8_t* U, float* S, int8_t* V);
 tsvd_status tsvd_info(const tsvd_handle* h, int64_t* M, int64_t* K, int64_t* N,
                       int64_t* nnzU, int64_t* nnzV);
 
+/* ---- a denser code of U (measurement path) ----------------------------------------------
+ *
+ * The paper's discussion calls 2 bits per ternary element overly redundant.  These calls hold the densest
+ * byte-aligned alternative: five elements per byte (3^5 = 243 <= 256), 1.6 bits per element, in groups of five
+ * 16-row strips (4 KiB per group and 256 columns: lane-ordered like the 2-bit tiles, byte j of a lane =
+ * sum_i trit(5 j + i) 3^i over the lane's 320 codes of the five strips, trit 0 / 1 / 2 for 0 / +1 / -1).  The
+ * forward path uses it only when asked to (diagnostic switch TSVD_DENSE_U of tsvd_tuning.h at tsvd_pack:
+ * stage U of single-token calls then reads this code): on MI355X it reads 20 % fewer bytes and is slower,
+ * because decoding costs more than the bytes save.
+ *   tsvd_dense_bytes(M, K)      : size of the code of U [M][K] (0 if a dimension is <= 0)
+ *   tsvd_dense_pack_host        : U host int8 [M][K] row-major -> blob (host); TSVD_EVALUE for non-ternary entries
+ *   tsvd_dense_unpack_host      : exact inverse; TSVD_EVALUE for a byte above 242 or a non-empty padding row
+ */
+size_t tsvd_dense_bytes(int64_t M, int64_t K);
+tsvd_status tsvd_dense_pack_host(const int8_t* U, int64_t M, int64_t K, void* blob, size_t blob_bytes);
+tsvd_status tsvd_dense_unpack_host(const void* blob, size_t blob_bytes, int8_t* U, int64_t M, int64_t K);
+
 /* ---- forward ------------------------------------------------------------------------
  *
  * Y = U (diag(S) (V X)) for B tokens (columns), following the three steps of the paper's

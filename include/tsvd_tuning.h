@@ -26,7 +26,8 @@ extern "C" {
  *   TSVD_FP6, TSVD_FP6_V, TSVD_FP6_TALL, TSVD_FP6_PLANES (2: two instead of three fp6 planes -- about five
  *   times the error, inside the tolerance without margin; never a default), TSVD_GROUPED_PAIR,
  *   TSVD_CLOCKS (1 at tsvd_pack: record phase timestamps per workgroup), TSVD_SPIN_LIMIT (bound of the
- *   single-launch kernels' wait for another workgroup's slice of z, in polls).
+ *   single-launch kernels' wait for another workgroup's slice of z, in polls), TSVD_DENSE_U (1 at tsvd_pack: keep a
+ *   second copy of U in the five-elements-per-byte code and run stage U of single-token calls on it).
  * Returns 0, or 1 for an unknown name. */
 int tsvd_tuning_set(const char* name, int value);
 

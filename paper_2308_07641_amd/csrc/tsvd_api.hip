@@ -27,6 +27,7 @@ struct tsvd_handle {
     // One-launch single-token path: [counter: 256 B][z as tagged 64-bit words: Kp], device, zeroed at pack
     // (counter = 1); null when the shape does not fit that kernel.  The path belongs to the first stream
     // that uses it: calls on one stream never overlap, calls on other streams take the two-launch kernels.
+    uint8_t* dense_u;       // device: U in the denser code (five elements per byte), only with TSVD_DENSE_U = 1 at pack time
     uint8_t* sync;
     std::atomic<int> sync_claimed;
     void* sync_stream;
@@ -99,6 +100,8 @@ hipError_t device_init(int device) {
     if (e != hipSuccess) return e;
     e = tsvd_mid_init();
     if (e != hipSuccess) return e;
+    e = tsvd_gemv_dense_init();
+    if (e != hipSuccess) return e;
     e = tsvd_transition_init();
     if (e != hipSuccess) return e;
     done[device] = true;
@@ -143,7 +146,7 @@ bool try_gemv(const tsvd_handle* h, const void* x, tsvd_dtype x_dtype, int64_t l
     const tsvd_blob_header& hd = h->hd;
     if (env_int("TSVD_GEMV", 1) == 0 || !tsvd_gemv_fits(hd.Np, hd.Kp)) return false;
     const int mask = tsvd_stage_mask();
-    if (mask == 7 && env_int("TSVD_GEMV_FUSED", 1) != 0 && tsvd_gemv_fused_fits(hd.Mp, hd.Kp, hd.Np)) {
+    if (mask == 7 && !h->dense_u && env_int("TSVD_GEMV_FUSED", 1) != 0 && tsvd_gemv_fused_fits(hd.Mp, hd.Kp, hd.Np)) {
         // a small matrix: both stages in one launch of one workgroup
         tsvd_gemv_fused_args f;
         std::memset(&f, 0, sizeof f);
@@ -158,7 +161,7 @@ bool try_gemv(const tsvd_handle* h, const void* x, tsvd_dtype x_dtype, int64_t l
         *st = tsvd_launch_gemv_fused(f, stream) == hipSuccess ? TSVD_OK : TSVD_EDEVICE;
         return true;
     }
-    if (mask == 7 && h->sync && env_int("TSVD_GEMV_ONEPASS", 0) != 0) {
+    if (mask == 7 && h->sync && !h->dense_u && env_int("TSVD_GEMV_ONEPASS", 0) != 0) {
         // both stages in one launch (z handed over between workgroups through the handle's tagged buffer)
         tsvd_handle* hm = const_cast<tsvd_handle*>(h);
         int expected = 0;
@@ -214,6 +217,18 @@ bool try_gemv(const tsvd_handle* h, const void* x, tsvd_dtype x_dtype, int64_t l
             *st = TSVD_EDEVICE;
             return true;
         }
+    }
+    if ((mask & 4) && h->dense_u && tsvd_gemv_dense_lds(hd.Kp) <= TSVD_SKINNY_MAX_LDS) {
+        tsvd_gemv_dense_args d;
+        std::memset(&d, 0, sizeof d);
+        d.dense = h->dense_u;
+        d.groups = (int)((hd.Mp / 16 + 4) / 5);
+        d.nkt = (int)(hd.Kp / 256);
+        d.Kp = (int)hd.Kp; d.M = (int)hd.M;
+        d.planes_in = planes; d.meta = meta;
+        d.y = y; d.ldy = ldy; d.bias = oo.bias; d.out_bf16 = oo.out_bf16;
+        *st = tsvd_launch_gemv_dense(d, stream) == hipSuccess ? TSVD_OK : TSVD_EDEVICE;
+        return true;
     }
     if (mask & 4) {
         a.tiles = h->blob + hd.off_U;
@@ -446,6 +461,7 @@ extern "C" tsvd_status tsvd_pack(const int8_t* U, const float* S, const int8_t* 
     h->clocks = nullptr;
     h->cu_count = 256;
     h->sync = nullptr;
+    h->dense_u = nullptr;
     h->sync_claimed.store(0);
     h->sync_stream = nullptr;
 
@@ -478,6 +494,19 @@ extern "C" tsvd_status tsvd_pack(const int8_t* U, const float* S, const int8_t* 
                     ok = hipMemset(d, 0, sb) == hipSuccess && hipMemcpy(d, &one, sizeof one, hipMemcpyHostToDevice) == hipSuccess;
                 }
             }
+            if (ok && env_int("TSVD_DENSE_U", 0) != 0) {
+                // measurement switch: a second copy of U in the denser code, used by stage U of single-token calls
+                const size_t db = tsvd_dense_bytes(M, K);
+                void* hostd = std::malloc(db);
+                void* d = nullptr;
+                ok = hostd && hipMalloc(&d, db) == hipSuccess;
+                if (ok) {
+                    tsvd_internal_dense_from_blob(host, hostd);
+                    h->dense_u = static_cast<uint8_t*>(d);
+                    ok = hipMemcpy(d, hostd, db, hipMemcpyHostToDevice) == hipSuccess;
+                }
+                std::free(hostd);
+            }
             if (ok && env_int("TSVD_CLOCKS", 0)) {
                 void* c = nullptr;
                 if (hipMalloc(&c, TSVD_GEMV_MAX_GRID * 16 * sizeof(long long)) == hipSuccess) {
@@ -491,6 +520,7 @@ extern "C" tsvd_status tsvd_pack(const int8_t* U, const float* S, const int8_t* 
     if (!ok) {
         if (h->owns_blob && h->blob) (void)hipFree(h->blob);
         if (h->sync) (void)hipFree(h->sync);
+        if (h->dense_u) (void)hipFree(h->dense_u);
         delete h;
         (void)hipGetLastError();
         return TSVD_EDEVICE;
@@ -673,7 +703,7 @@ const char* const tuning_names[] = {
     "TSVD_MID", "TSVD_MID_MAX_B", "TSVD_MID_SW", "TSVD_MID_KWLOG2", "TSVD_MID_RESIDENT", "TSVD_GEMM_MIN_B",
     "TSVD_GEMM_CFG_V", "TSVD_GEMM_CFG_U", "TSVD_FUSEMAX", "TSVD_COLMAX_SCALAR", "TSVD_REALIGN", "TSVD_PANEL",
     "TSVD_PANEL_WAVES", "TSVD_FP6", "TSVD_FP6_V", "TSVD_FP6_TALL", "TSVD_FP6_PLANES", "TSVD_GROUPED_PAIR", "TSVD_CLOCKS",
-    "TSVD_SPIN_LIMIT"};
+    "TSVD_SPIN_LIMIT", "TSVD_DENSE_U"};
 constexpr int tuning_count = (int)(sizeof tuning_names / sizeof tuning_names[0]);
 int tuning_value[tuning_count];
 bool tuning_is_set[tuning_count];
@@ -749,6 +779,7 @@ extern "C" void tsvd_free(tsvd_handle* h) {
     if (h->scratch) (void)hipFree(h->scratch);
     if (h->clocks) (void)hipFree(h->clocks);
     if (h->sync) (void)hipFree(h->sync);
+    if (h->dense_u) (void)hipFree(h->dense_u);
     if (h->owns_blob && h->blob) (void)hipFree(h->blob);
     delete h;
 }

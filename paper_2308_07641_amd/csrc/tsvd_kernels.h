@@ -84,6 +84,17 @@ struct tsvd_gemv_onepass_args {
 };
 bool tsvd_gemv_onepass_shape(long long M, long long Mp, long long Kp, long long Np, int cus, tsvd_gemv_onepass_args* a);
 hipError_t tsvd_launch_gemv_onepass(const tsvd_gemv_onepass_args& a, hipStream_t stream);
+// Stage U of a single token on the denser code of U (tsvd_dense.hip): one workgroup per group of five strips.
+struct tsvd_gemv_dense_args {
+    const void* dense; int groups, nkt;                     // [groups][nkt][4 KiB]; Kp / 256 tile columns
+    int Kp, M;
+    const unsigned char* planes_in; const int* meta;        // digit planes of z [8][Kp] and their exponent (stage V's output)
+    void* y; long long ldy; const float* bias; int out_bf16;
+};
+size_t tsvd_gemv_dense_lds(long long Kp);
+hipError_t tsvd_gemv_dense_init();
+hipError_t tsvd_launch_gemv_dense(const tsvd_gemv_dense_args& a, hipStream_t stream);
+void tsvd_internal_dense_from_blob(const void* blob, void* out);   // tsvd_pack.cpp: recodes U's tiles of a host blob
 bool tsvd_gemv_fused_fits(long long Mp, long long Kp, long long Np);
 hipError_t tsvd_launch_gemv_fused(const tsvd_gemv_fused_args& a, hipStream_t stream);
 hipError_t tsvd_gemv_init();

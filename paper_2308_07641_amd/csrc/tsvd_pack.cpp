@@ -234,6 +234,107 @@ extern "C" tsvd_status tsvd_unpack_host(const void* blob, size_t blob_bytes, int
     return TSVD_OK;
 }
 
+// ---- denser code of U: five ternary elements per byte (3^5 = 243 <= 256), 1.6 bits per element --------
+// Layout: groups of five consecutive 16-row strips; group-tile (G, T) = the five 1-KiB tiles (strips 5 G .. 5 G + 4,
+// tile column T) recoded into 4 KiB: [4 chunks][64 lanes][16 bytes].  A lane's 64 bytes hold its 320 codes
+// q = 64 t + 16 w + n (t = strip in the group, w = word of the lane in the 2-bit tile, n = code in the word), five
+// per byte: byte j = sum_i trit(q = 5 j + i) 3^i with trit 0 / 1 / 2 for the elements 0 / +1 / -1.
+namespace {
+constexpr int DENSE_GROUP = 5;
+int64_t dense_groups(int64_t M) { return (tsvd_round_up(M, TSVD_DIM_ALIGN) / TSVD_TILE_ROWS + DENSE_GROUP - 1) / DENSE_GROUP; }
+
+void dense_from_tiles(const uint32_t* tiles, int64_t strips, int64_t nkt, uint8_t* out) {
+    const int64_t groups = (strips + DENSE_GROUP - 1) / DENSE_GROUP;
+    for (int64_t G = 0; G < groups; ++G)
+        for (int64_t T = 0; T < nkt; ++T) {
+            uint8_t* gt = out + (G * nkt + T) * 4096;
+            for (int lane = 0; lane < 64; ++lane)
+                for (int j = 0; j < 64; ++j) {
+                    unsigned value = 0, pw = 1;
+                    for (int i = 0; i < 5; ++i, pw *= 3) {
+                        const int q = 5 * j + i, t = q >> 6, w = (q >> 4) & 3, n = q & 15;
+                        const int64_t strip = G * DENSE_GROUP + t;
+                        unsigned code = 0;
+                        if (strip < strips) code = (tiles[(strip * nkt + T) * 256 + lane * 4 + w] >> (2 * n)) & 3u;
+                        value += (code == 0 ? 0u : code == 1 ? 1u : 2u) * pw;
+                    }
+                    gt[(j >> 4) * 1024 + lane * 16 + (j & 15)] = (uint8_t)value;
+                }
+        }
+}
+
+// Inverse; false if a byte is not a valid code (>= 243) or a padding strip is not empty.
+bool tiles_from_dense(const uint8_t* in, int64_t strips, int64_t nkt, uint32_t* tiles) {
+    const int64_t groups = (strips + DENSE_GROUP - 1) / DENSE_GROUP;
+    std::memset(tiles, 0, (size_t)(strips * nkt) * 1024);
+    for (int64_t G = 0; G < groups; ++G)
+        for (int64_t T = 0; T < nkt; ++T) {
+            const uint8_t* gt = in + (G * nkt + T) * 4096;
+            for (int lane = 0; lane < 64; ++lane)
+                for (int j = 0; j < 64; ++j) {
+                    unsigned value = gt[(j >> 4) * 1024 + lane * 16 + (j & 15)];
+                    if (value >= 243u) return false;
+                    for (int i = 0; i < 5; ++i, value /= 3) {
+                        const unsigned trit = value % 3u;
+                        if (!trit) continue;
+                        const int q = 5 * j + i, t = q >> 6, w = (q >> 4) & 3, n = q & 15;
+                        const int64_t strip = G * DENSE_GROUP + t;
+                        if (strip >= strips) return false;
+                        tiles[(strip * nkt + T) * 256 + lane * 4 + w] |= (trit == 1 ? 1u : 3u) << (2 * n);
+                    }
+                }
+        }
+    return true;
+}
+}  // namespace
+
+extern "C" size_t tsvd_dense_bytes(int64_t M, int64_t K) {
+    if (M <= 0 || K <= 0 || M > (int64_t(1) << 30) || K > (int64_t(1) << 30)) return 0;
+    return (size_t)(dense_groups(M) * (tsvd_round_up(K, TSVD_DIM_ALIGN) / TSVD_TILE_COLS)) * 4096;
+}
+
+extern "C" tsvd_status tsvd_dense_pack_host(const int8_t* U, int64_t M, int64_t K, void* blob, size_t blob_bytes) {
+    const size_t need = tsvd_dense_bytes(M, K);
+    if (!U || !blob || need == 0 || blob_bytes < need) return TSVD_EINVAL;
+    for (int64_t i = 0; i < M * K; ++i)
+        if (U[i] < -1 || U[i] > 1) return TSVD_EVALUE;
+    const int64_t Mp = tsvd_round_up(M, TSVD_DIM_ALIGN), Kp = tsvd_round_up(K, TSVD_DIM_ALIGN);
+    const int64_t strips = Mp / TSVD_TILE_ROWS, nkt = Kp / TSVD_TILE_COLS;
+    std::vector<uint32_t> tiles((size_t)(strips * nkt) * 256);
+    std::vector<uint16_t> nnz((size_t)(strips * nkt));
+    int64_t total = 0;
+    if (!pack_matrix(U, M, K, Mp, Kp, 0, K, tiles.data(), nnz.data(), &total)) return TSVD_EVALUE;
+    dense_from_tiles(tiles.data(), strips, nkt, static_cast<uint8_t*>(blob));
+    return TSVD_OK;
+}
+
+extern "C" tsvd_status tsvd_dense_unpack_host(const void* blob, size_t blob_bytes, int8_t* U, int64_t M, int64_t K) {
+    const size_t need = tsvd_dense_bytes(M, K);
+    if (!U || !blob || need == 0 || blob_bytes < need) return TSVD_EINVAL;
+    const int64_t Mp = tsvd_round_up(M, TSVD_DIM_ALIGN), Kp = tsvd_round_up(K, TSVD_DIM_ALIGN);
+    const int64_t strips = Mp / TSVD_TILE_ROWS, nkt = Kp / TSVD_TILE_COLS;
+    std::vector<uint32_t> tiles((size_t)(strips * nkt) * 256);
+    if (!tiles_from_dense(static_cast<const uint8_t*>(blob), strips, nkt, tiles.data())) return TSVD_EVALUE;
+    std::vector<uint16_t> nnz((size_t)(strips * nkt));
+    for (int64_t t = 0; t < strips * nkt; ++t) {                 // the counts unpack_matrix checks against
+        int c = 0;
+        for (int w = 0; w < 256; ++w) {
+            const uint32_t v = tiles[(size_t)t * 256 + w];
+            c += __builtin_popcount(v & 0x55555555u);
+        }
+        nnz[(size_t)t] = (uint16_t)c;
+    }
+    return unpack_matrix(U, M, K, Mp, Kp, 0, K, tiles.data(), nnz.data(), false) ? TSVD_OK : TSVD_EVALUE;
+}
+
+// Recodes the packed tiles of U inside a blob of tsvd_pack_host (internal: tsvd_pack uploads the result).
+void tsvd_internal_dense_from_blob(const void* blob, void* out) {
+    tsvd_blob_header hd;
+    std::memcpy(&hd, blob, sizeof hd);
+    dense_from_tiles(reinterpret_cast<const uint32_t*>(static_cast<const uint8_t*>(blob) + hd.off_U), hd.Mp / TSVD_TILE_ROWS,
+                     hd.Kp / TSVD_TILE_COLS, static_cast<uint8_t*>(out));
+}
+
 extern "C" const char* tsvd_strerror(tsvd_status s) {
     switch (s) {
         case TSVD_OK: return "ok";

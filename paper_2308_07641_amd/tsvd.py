@@ -28,6 +28,9 @@ _PROTOTYPES = {
     "tsvd_packed_bytes": (_sz, [_i64, _i64, _i64]),
     "tsvd_pack_host": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _sz]),
     "tsvd_unpack_host": (ctypes.c_int, [_vp, _sz, _vp, _vp, _vp, _pi64, _pi64, _pi64]),
+    "tsvd_dense_bytes": (_sz, [_i64, _i64]),
+    "tsvd_dense_pack_host": (ctypes.c_int, [_vp, _i64, _i64, _vp, _sz]),
+    "tsvd_dense_unpack_host": (ctypes.c_int, [_vp, _sz, _vp, _i64, _i64]),
     "tsvd_pack": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _sz, ctypes.POINTER(_vp)]),
     "tsvd_unpack": (ctypes.c_int, [_vp, _vp, _vp, _vp]),
     "tsvd_info": (ctypes.c_int, [_vp, _pi64, _pi64, _pi64, _pi64, _pi64]),
@@ -131,6 +134,25 @@ def tsvd_unpack_host(blob: np.ndarray):
     _check(lib.tsvd_unpack_host(blob.ctypes.data, blob.nbytes, U.ctypes.data, S.ctypes.data, V.ctypes.data,
                                 None, None, None), "tsvd_unpack_host")
     return U, S, V
+
+
+def tsvd_dense_bytes(M: int, K: int) -> int:
+    return int(load_library().tsvd_dense_bytes(M, K))
+
+
+def tsvd_dense_pack_host(U) -> np.ndarray:
+    """U int8 [M,K] -> the five-elements-per-byte code (host uint8 array)."""
+    U = np.ascontiguousarray(U, dtype=np.int8)
+    blob = np.empty(tsvd_dense_bytes(*U.shape), dtype=np.uint8)
+    _check(load_library().tsvd_dense_pack_host(U.ctypes.data, U.shape[0], U.shape[1], blob.ctypes.data, blob.nbytes), "tsvd_dense_pack_host")
+    return blob
+
+
+def tsvd_dense_unpack_host(blob: np.ndarray, M: int, K: int) -> np.ndarray:
+    blob = np.ascontiguousarray(blob, dtype=np.uint8)
+    U = np.empty((M, K), dtype=np.int8)
+    _check(load_library().tsvd_dense_unpack_host(blob.ctypes.data, blob.nbytes, U.ctypes.data, M, K), "tsvd_dense_unpack_host")
+    return U
 
 
 class Handle:

@@ -248,3 +248,59 @@ def test_new_entry_points_validate_arguments_before_touching_a_device():
     assert lib.tsvd_conv2d_forward(None, p, p, 1, 4, 4, None, p, 0, p, 0, None) == 1
     assert lib.tsvd_workspace_bytes_ex(None, 4, 0, 0) == 0
     assert lib.tsvd_forward_ex(None, p, 0, 0, 1, 1, None, p, 0, 1, None, 0, None) == 1
+
+
+# ---- the denser code of U: five ternary elements per byte
+def _dense_decode(blob, M, K):
+    """The documented rule written out independently: group of five strips, 4 KiB per (group, tile column) as
+    [4 chunks][64 lanes][16 bytes]; byte j of a lane = sum_i trit(5 j + i) 3^i over the lane's codes q = 64 t + 16 w + n
+    (strip t of the group, word w and code n of the lane in the 2-bit tile); columns through the rank position rule."""
+    Mp, Kp = -(-M // 256) * 256, -(-K // 256) * 256
+    strips, nkt = Mp // 16, Kp // 256
+    U = np.zeros((M, K), dtype=np.int8)
+    value = {0: 0, 1: 1, 2: -1}
+    for r in range(M):
+        strip, i = r // 16, r % 16
+        G, t = strip // 5, strip % 5
+        for c in range(K):
+            pc = _rank_position(c, K)
+            T, cc = pc // 256, pc % 256
+            h, kk = cc >> 7, cc & 127
+            g = ((kk >> 6) & 1) | (((kk >> 4) & 1) << 1)
+            e = (((kk >> 5) & 1) << 4) | (kk & 15)
+            v, n8 = e >> 3, e & 7
+            lane, w, n = 16 * g + i, 2 * h + (v >> 1), 2 * n8 + (v & 1)
+            q = 64 * t + 16 * w + n
+            j, d = q // 5, q % 5
+            byte = int(blob[(G * nkt + T) * 4096 + (j >> 4) * 1024 + lane * 16 + (j & 15)])
+            U[r, c] = value[(byte // 3 ** d) % 3]
+    return U
+
+
+@pytest.mark.parametrize("M,K", [(1, 1), (17, 33), (80, 256), (81, 300), (200, 70), (96, 513)])
+def test_dense_code_round_trip_and_position_rule(M, K):
+    U = workloads.make_inputs(M, 8, K, 1, 0.6, 0.02, "f32", seed=M + 7 * K).U
+    blob = tsvd.tsvd_dense_pack_host(U)
+    assert blob.nbytes == tsvd.tsvd_dense_bytes(M, K)
+    assert blob.max() <= 242
+    assert np.array_equal(tsvd.tsvd_dense_unpack_host(blob, M, K), U)
+    assert np.array_equal(_dense_decode(blob, M, K), U)
+    assert np.array_equal(blob, tsvd.tsvd_dense_pack_host(U))
+
+
+def test_dense_code_is_1_6_bits_per_element_and_rejects_corruption():
+    assert tsvd.tsvd_dense_bytes(16384, 8192) * 8 == int(1.6 * 16400 * 8192)       # 205 groups of 80 rows: 16400 rows stored
+    assert tsvd.tsvd_dense_bytes(16384, 8192) / (16384 * 8192 / 4) < 0.801           # against 2 bits per element
+    U = workloads.make_inputs(40, 8, 300, 1, 0.5, 0.02, "f32", seed=3).U
+    blob = tsvd.tsvd_dense_pack_host(U)
+    bad = blob.copy()
+    bad[5] = 250                                                                      # not a number below 3^5
+    with pytest.raises(tsvd.TsvdError) as e:
+        tsvd.tsvd_dense_unpack_host(bad, 40, 300)
+    assert e.value.status == 2
+    U2 = U.copy()
+    U2[3, 3] = 2
+    lib = tsvd.load_library()
+    out = np.full(blob.nbytes, 0xAB, dtype=np.uint8)
+    assert lib.tsvd_dense_pack_host(U2.ctypes.data, 40, 300, out.ctypes.data, out.nbytes) == 2 and np.all(out == 0xAB)
+    assert lib.tsvd_dense_pack_host(U.ctypes.data, 40, 300, out.ctypes.data, out.nbytes - 1) == 1

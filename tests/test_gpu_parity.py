@@ -366,6 +366,27 @@ def test_single_token_one_launch_second_stream_falls_back(tsvd):
     assert np.array_equal(y1.cpu().numpy().astype(np.float64), ref)
 
 
+# ---- stage U of a single token on the denser code of U (five elements per byte; measurement path)
+@pytest.mark.parametrize("M,N,K", [(300, 513, 270), (1000, 700, 200), (81, 64, 2415), (4100, 2050, 4000), (700, 300, 8100)])
+def test_single_token_dense_code(tsvd, M, N, K):
+    import torch
+    tsvd.tsvd_tuning_set("TSVD_DENSE_U", 1)
+    print(f"case dense code M={M} N={N} K={K}", flush=True)
+    for x_dtype in ("bf16", "f32"):
+        i = workloads.make_integer_inputs(M, N, K, 1, 0.5, x_dtype, seed=9 * M + N + K)
+        y, h = run_forward(i)
+        tsvd.tsvd_free(h)
+        assert not np.isnan(y).any()
+        assert np.array_equal(y, oracle.forward(i.U, i.S, i.V, i.X)), x_dtype
+        j = workloads.make_inputs(M, N, K, 1, 0.6, 0.02, x_dtype, seed=8 * M + N + K)
+        bias = torch.linspace(-1.0, 1.0, M, device="cuda:0")
+        h = tsvd.tsvd_pack(j.U, j.S, j.V)
+        y = tsvd.tsvd_forward_ex(h, to_device(j), bias=bias).cpu().numpy().astype(np.float64)
+        tsvd.tsvd_free(h)
+        ref = oracle.forward_layer(j.U, j.S, j.V, j.X, bias=bias.cpu().numpy().astype(np.float64))
+        assert np.max(np.abs(y - ref)) <= (1e-5 if x_dtype == "f32" else 2e-3) * np.max(np.abs(oracle.forward(j.U, j.S, j.V, j.X)))
+
+
 def test_general_single_token_kernel(tsvd):
     """The slab kernel that serves contraction lengths beyond the fast single-token kernel's
     limits, forced on ordinary sizes (exact instance, then a random one per activation type)."""
