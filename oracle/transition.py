@@ -1,7 +1,7 @@
 """CPU oracle for the direct transition W -> (U, S, V) (TEST INFRASTRUCTURE ONLY).
 
-Plain numpy in fp64, following the section "Direct Transition Algorithm to TSVD form" of the
-paper step by step:
+Plain numpy in fp64, written from the definitions in the section "Direct Transition Algorithm to
+TSVD form" of the paper:
 
   * gamma          -- Theorem 1: the bound gamma_N on the cosine that some ternary vector
                       reaches for every unit vector of dimension N.
@@ -61,11 +61,29 @@ def fit_scales(U, V, W) -> np.ndarray:
     return np.linalg.pinv(G) @ d
 
 
+def leading_pairs(R, q: int):
+    """The q singular pairs of R with the largest singular values: lists of left and right unit vectors."""
+    left, _, right_t = np.linalg.svd(np.asarray(R, dtype=np.float64), full_matrices=False)
+    return [left[:, j] for j in range(q)], [right_t[j, :] for j in range(q)]
+
+
+def reconstruction(U, S, V) -> np.ndarray:
+    """U diag(S) V as the explicit sum of its rank-one terms S_k u_k v_k^T."""
+    U = np.asarray(U, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    out = np.zeros((U.shape[0], V.shape[1]))
+    for k in range(U.shape[1]):
+        out += S[k] * np.outer(U[:, k], V[k, :])
+    return out
+
+
 def transition(W, theta: float, q: int = 1, tol: float | None = None, max_rank: int | None = None, norm: str = "fro"):
-    """Algorithm 2.  Stops when the relative error |W - U diag(S) V| / |W| (Frobenius norm, or
-    the operator norm with norm="op" as in the paper's random-matrix figure) is at most tol, or
-    when the rank reaches max_rank.  Returns (U int8 [M,K], S float64 [K], V int8 [K,N], errors),
-    errors[i] being the relative error after iteration i + 1.
+    """Algorithm 2: greedy growth of the ternary factors.  Every round takes the q leading singular pairs of the
+    current residual W - U diag(S) V, replaces each vector by its ternary neighbour T(., theta), appends the q
+    new components and refits ALL scales by Eq. (3).  Stops when the relative error |W - U diag(S) V| / |W|
+    (Frobenius norm, or the operator norm with norm="op" as in the paper's random-matrix figure) is at most tol,
+    or when the rank reaches max_rank.  Returns (U int8 [M,K], S float64 [K], V int8 [K,N], errors), errors[i]
+    being the relative error after round i + 1.
     """
     W = np.asarray(W, dtype=np.float64)
     M, N = W.shape
@@ -73,22 +91,18 @@ def transition(W, theta: float, q: int = 1, tol: float | None = None, max_rank: 
         raise ValueError("an exit condition is needed")
     ordn = 2 if norm == "op" else "fro"
     wnorm = np.linalg.norm(W, ordn)
-    U = np.zeros((M, 0), dtype=np.int8)
-    V = np.zeros((0, N), dtype=np.int8)
+    columns, rows = [], []                     # ternary columns of U, ternary rows of V
     S = np.zeros(0)
-    R = W.copy()
     errors = []
+    residual = W
     while True:
-        u, _, v = np.linalg.svd(R, full_matrices=False)
-        Tu = np.stack([ternarize(u[:, j], theta) for j in range(q)], axis=1)
-        Tv = np.stack([ternarize(v[j, :], theta) for j in range(q)], axis=0)
-        U = np.concatenate([U, Tu], axis=1)
-        V = np.concatenate([V, Tv], axis=0)
+        lefts, rights = leading_pairs(residual, q)
+        columns += [ternarize(u, theta) for u in lefts]
+        rows += [ternarize(v, theta) for v in rights]
+        U = np.stack(columns, axis=1)
+        V = np.stack(rows, axis=0)
         S = fit_scales(U, V, W)
-        R = W - (U.astype(np.float64) * S[None, :]) @ V.astype(np.float64)
-        errors.append(float(np.linalg.norm(R, ordn) / wnorm))
-        if tol is not None and errors[-1] <= tol:
-            break
-        if max_rank is not None and U.shape[1] >= max_rank:
-            break
-    return U, S, V, errors
+        residual = W - reconstruction(U, S, V)
+        errors.append(float(np.linalg.norm(residual, ordn) / wnorm))
+        if (tol is not None and errors[-1] <= tol) or (max_rank is not None and len(columns) >= max_rank):
+            return U, S, V, errors

@@ -155,3 +155,32 @@ def test_sparsity_at_the_papers_size():
     U, S, V, errs = tr.transition(W, THETA, max_rank=24)
     r = (np.count_nonzero(U) + np.count_nonzero(V)) / (U.size + V.size)
     assert 0.26 < r < 0.32
+
+
+def test_transition_with_several_components_per_round():
+    """q > 1 (the top-q singular pairs of one residual per round).  On an exactly ternary-factorisable matrix
+    W = sum_k s_k a_k b_k^T with orthogonal ternary a_k (disjoint supports) and b_k, the singular vectors ARE the
+    normalised a_k, b_k, so q = 3 must recover all three components in ONE round with error 0 and S = s; and a
+    round with q = 2 must equal two rounds' worth of components while refitting all scales (Eq. 3)."""
+    a = np.zeros((12, 3)); b = np.zeros((3, 10))
+    a[0:4, 0] = [1, -1, 1, 1]; a[4:8, 1] = [1, 1, -1, 1]; a[8:12, 2] = [-1, 1, 1, 1]
+    b[0, 0:3] = [1, 1, -1]; b[1, 3:6] = [1, -1, 1]; b[2, 6:10] = [1, 1, 1, -1]
+    s = np.array([5.0, 3.0, 2.0])
+    W = (a * s[None, :]) @ b
+    U, S, V, errs = tr.transition(W, 0.3, q=3, max_rank=3)
+    assert U.shape == (12, 3) and len(errs) == 1 and errs[0] < 1e-12
+    for k in range(3):
+        sign = 1 if np.array_equal(U[:, k], a[:, k]) else -1
+        assert np.array_equal(sign * U[:, k], a[:, k]) and np.array_equal(sign * V[k, :], b[k, :])
+    assert np.allclose(S, s, rtol=1e-12)
+    # q = 2 on a generic matrix: 2 components per round, every round's scales are the least-squares optimum
+    Wg = np.random.default_rng(5).laplace(size=(40, 24))
+    U2, S2, V2, e2 = tr.transition(Wg, 0.576, q=2, max_rank=8)
+    assert U2.shape == (40, 8) and len(e2) == 4 and all(y <= x + 1e-12 for x, y in zip(e2, e2[1:]))
+    best = np.linalg.lstsq(np.stack([np.outer(U2[:, k], V2[k, :]).ravel() for k in range(8)], axis=1), Wg.ravel(), rcond=None)[0]
+    assert np.allclose(S2, best, rtol=1e-9, atol=1e-12)
+    assert np.allclose(tr.reconstruction(U2, S2, V2), (U2 * S2[None, :]) @ V2.astype(np.float64), atol=1e-12)
+    # the first round of q = 2 takes the two leading pairs of W itself
+    lefts, rights = tr.leading_pairs(Wg, 2)
+    for k in range(2):
+        assert np.array_equal(U2[:, k], tr.ternarize(lefts[k], 0.576)) and np.array_equal(V2[k, :], tr.ternarize(rights[k], 0.576))
