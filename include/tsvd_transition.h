@@ -77,6 +77,16 @@ tsvd_status tsvd_transition(const double* W_dev, int64_t M, int64_t N, double th
                             int8_t* U_dev, double* S_dev, int8_t* V_dev, int64_t* rank_out, double* errors_host,
                             void* stream);
 
+/* Algorithm 2 with q components per iteration (the paper's q; its experiments use an adaptive q): every iteration
+ * takes the q leading singular triples of the residual -- the leading triple of R, then of R minus that triple, and
+ * so on (deflation in a working copy of R) --, ternarizes the 2 q vectors, appends the q components, refits all
+ * scales (Eq. 3) and recomputes the residual.  The last iteration takes only what still fits below max_rank.
+ * errors_host[k] is the relative error after the iteration that added component k.  If a vector of an iteration
+ * has no ternary neighbour within theta the whole iteration is dropped (TSVD_EVALUE, *rank_out = rank before it).
+ * 1 <= q <= min(M, N, max_rank); everything else as for tsvd_transition, which is this call with q = 1. */
+tsvd_status tsvd_transition_q(const double* W_dev, int64_t M, int64_t N, double theta, double tol, int64_t max_rank, int64_t q,
+                              int8_t* U_dev, double* S_dev, int8_t* V_dev, int64_t* rank_out, double* errors_host, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -509,6 +509,16 @@ int pow2_at_least(int64_t v) {
 
 }  // namespace
 
+// R[m][n] -= sigma u[m] v[n]: removes a converged singular triple, so that the next call for the leading pair
+// returns the following one (Algorithm 2 with q > 1 takes the top q vectors of the same residual).
+__global__ void __launch_bounds__(256)
+tsvd_deflate_kernel(double* __restrict__ R, int M, int N, const double* __restrict__ u, const double* __restrict__ v,
+                    const double* __restrict__ sigma) {
+    const int m = blockIdx.y;
+    const double f = sigma[0] * u[m];
+    for (int n = blockIdx.x * 256 + threadIdx.x; n < N; n += gridDim.x * 256) R[(size_t)m * N + n] -= f * v[n];
+}
+
 extern "C" tsvd_status tsvd_ternarize(const double* x_dev, int64_t n, int64_t count, int64_t ldx, double theta, int8_t* t_dev,
                                       int64_t ldt, int32_t* status_dev, void* stream) {
     if (!x_dev || !t_dev || !status_dev || n < 1 || n > TERN_MAX_N || count < 1 || count > (1 << 30) || ldx < n || ldt < n)
@@ -649,8 +659,14 @@ hipError_t tsvd_transition_init() {
 extern "C" tsvd_status tsvd_transition(const double* W_dev, int64_t M, int64_t N, double theta, double tol, int64_t max_rank,
                                        int8_t* U_dev, double* S_dev, int8_t* V_dev, int64_t* rank_out, double* errors_host,
                                        void* stream) {
+    return tsvd_transition_q(W_dev, M, N, theta, tol, max_rank, 1, U_dev, S_dev, V_dev, rank_out, errors_host, stream);
+}
+
+extern "C" tsvd_status tsvd_transition_q(const double* W_dev, int64_t M, int64_t N, double theta, double tol, int64_t max_rank,
+                                         int64_t q, int8_t* U_dev, double* S_dev, int8_t* V_dev, int64_t* rank_out,
+                                         double* errors_host, void* stream) {
     if (!W_dev || !U_dev || !S_dev || !V_dev || !rank_out || M < 1 || N < 1 || M > TERN_MAX_N || N > TERN_MAX_N || max_rank < 1 ||
-        max_rank > FIT_MAX_K || !(tol >= 0.0))
+        max_rank > FIT_MAX_K || !(tol >= 0.0) || q < 1 || q > max_rank || q > std::min(M, N))
         return TSVD_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     *rank_out = 0;
@@ -658,8 +674,9 @@ extern "C" tsvd_status tsvd_transition(const double* W_dev, int64_t M, int64_t N
     const size_t bytes_R = round256((size_t)M * N * 8), bytes_u = round256((size_t)M * 8), bytes_v = round256((size_t)N * 8);
     const size_t bytes_tu = round256((size_t)M), bytes_misc = 256, bytes_fit = tsvd_fit_scales_workspace(max_rank);
     const size_t bytes_svd = tsvd_leading_singular_pair_workspace(M, N);
+    const size_t bytes_defl = q > 1 ? bytes_R : 0;             // working copy of the residual for the second .. q-th triple
     uint8_t* base = nullptr;
-    if (hipMalloc(reinterpret_cast<void**>(&base), bytes_R + bytes_u + bytes_v + bytes_tu + bytes_misc + bytes_fit + bytes_svd) !=
+    if (hipMalloc(reinterpret_cast<void**>(&base), bytes_R + bytes_u + bytes_v + bytes_tu + bytes_misc + bytes_fit + bytes_svd + bytes_defl) !=
         hipSuccess) {
         (void)hipGetLastError();
         return TSVD_EDEVICE;
@@ -674,6 +691,7 @@ extern "C" tsvd_status tsvd_transition(const double* W_dev, int64_t M, int64_t N
     double* G = reinterpret_cast<double*>(fit_ws);                              // [max_rank][max_rank], grown row by row
     double* dvec = reinterpret_cast<double*>(fit_ws + round256((size_t)max_rank * (size_t)max_rank * 8));
     void* svd_ws = fit_ws + bytes_fit;
+    double* Rwork = q > 1 ? reinterpret_cast<double*>(fit_ws + bytes_fit + bytes_svd) : nullptr;
 
     tsvd_status st = TSVD_OK;
     auto ok = [&](hipError_t e) {
@@ -690,27 +708,46 @@ extern "C" tsvd_status tsvd_transition(const double* W_dev, int64_t M, int64_t N
     ok(hipStreamSynchronize(s));
     int64_t K = 0;
     while (st == TSVD_OK && K < max_rank && wnorm2 > 0.0) {
-        st = tsvd_leading_singular_pair(R, M, N, 4 * GKL_MAX_STEPS, u, v, misc, nullptr, svd_ws, bytes_svd, s);
-        if (st != TSVD_OK) break;
-        // column K of U (row stride max_rank) is written through a contiguous temporary
-        st = tsvd_ternarize(u, M, 1, M, theta, tu, M, flags, s);
-        if (st != TSVD_OK) break;
-        st = tsvd_ternarize(v, N, 1, N, theta, V_dev + (size_t)K * N, N, flags + 1, s);
-        if (st != TSVD_OK) break;
-        int32_t fl[2] = {0, 0};
-        if (!ok(hipMemcpy2DAsync(U_dev + K, (size_t)max_rank, tu, 1, 1, (size_t)M, hipMemcpyDeviceToDevice, s))) break;
-        if (!ok(hipMemcpyAsync(fl, flags, 8, hipMemcpyDeviceToHost, s)) || !ok(hipStreamSynchronize(s))) break;
-        if (fl[0] != 0 || fl[1] != 0) {
-            st = TSVD_EVALUE;                                   // no ternary vector within theta
+        // the top q singular triples of the residual, one after the other: the leading triple of R, then of R with
+        // that triple removed, ... (the last iteration takes what still fits below max_rank)
+        const int64_t take = std::min<int64_t>(q, max_rank - K);
+        if (take > 1 && !ok(hipMemcpyAsync(Rwork, R, (size_t)M * N * 8, hipMemcpyDeviceToDevice, s))) break;
+        const int64_t K0 = K;
+        for (int64_t j = 0; j < take && st == TSVD_OK; ++j) {
+            const double* src = take > 1 ? Rwork : R;
+            st = tsvd_leading_singular_pair(src, M, N, 4 * GKL_MAX_STEPS, u, v, misc, nullptr, svd_ws, bytes_svd, s);
+            if (st != TSVD_OK) break;
+            if (j + 1 < take) {
+                hipLaunchKernelGGL(tsvd_deflate_kernel, dim3((unsigned)std::min<int64_t>(16, (N + 255) / 256), (unsigned)M), dim3(256), 0, s,
+                                   Rwork, (int)M, (int)N, u, v, misc);
+                if (!ok(hipGetLastError())) break;
+            }
+            // column K of U (row stride max_rank) is written through a contiguous temporary
+            st = tsvd_ternarize(u, M, 1, M, theta, tu, M, flags, s);
+            if (st != TSVD_OK) break;
+            st = tsvd_ternarize(v, N, 1, N, theta, V_dev + (size_t)K * N, N, flags + 1, s);
+            if (st != TSVD_OK) break;
+            int32_t fl[2] = {0, 0};
+            if (!ok(hipMemcpy2DAsync(U_dev + K, (size_t)max_rank, tu, 1, 1, (size_t)M, hipMemcpyDeviceToDevice, s))) break;
+            if (!ok(hipMemcpyAsync(fl, flags, 8, hipMemcpyDeviceToHost, s)) || !ok(hipStreamSynchronize(s))) break;
+            if (fl[0] != 0 || fl[1] != 0) {
+                st = TSVD_EVALUE;                                   // no ternary vector within theta
+                break;
+            }
+            ++K;
+        }
+        if (st != TSVD_OK) {
+            K = K0;            // (the components of an unfinished iteration are dropped: *rank_out stays at the last complete one)
             break;
         }
-        ++K;
-        // Eq. (3) with what changed only: row / column K - 1 of the Gram matrix and entry K - 1 of the right
-        // side; the solve starts from the previous scales (the new one at 0, set when S was cleared)
-        hipLaunchKernelGGL(tsvd_gram_kernel, dim3((unsigned)((K + 255) / 256), 1), dim3(256), 0, s, U_dev, (long long)max_rank, V_dev,
-                           (int)M, (int)K, (int)N, G, (long long)max_rank, (int)(K - 1));
-        hipLaunchKernelGGL(tsvd_rhs_kernel, dim3(1), dim3(256), 0, s, U_dev, (long long)max_rank, V_dev, W_dev, (int)M, (int)N, dvec,
-                           (int)(K - 1));
+        // Eq. (3) with what changed only: the new rows / columns of the Gram matrix and entries of the right
+        // side; the solve starts from the previous scales (the new ones at 0, set when S was cleared)
+        for (int64_t r = K0; r < K; ++r) {
+            hipLaunchKernelGGL(tsvd_gram_kernel, dim3((unsigned)((K + 255) / 256), 1), dim3(256), 0, s, U_dev, (long long)max_rank, V_dev,
+                               (int)M, (int)K, (int)N, G, (long long)max_rank, (int)r);
+            hipLaunchKernelGGL(tsvd_rhs_kernel, dim3(1), dim3(256), 0, s, U_dev, (long long)max_rank, V_dev, W_dev, (int)M, (int)N, dvec,
+                               (int)r);
+        }
         hipLaunchKernelGGL(tsvd_pcg_kernel, dim3(1), dim3(1024), (size_t)5 * K * 8 + 1024 * 8, s, G, (long long)max_rank, dvec, (int)K,
                            S_dev, 1, static_cast<int*>(nullptr));
         if (!ok(hipGetLastError())) break;
@@ -719,7 +756,8 @@ extern "C" tsvd_status tsvd_transition(const double* W_dev, int64_t M, int64_t N
         double rnorm2 = 0.0;
         if (!ok(hipMemcpyAsync(&rnorm2, misc + 1, 8, hipMemcpyDeviceToHost, s)) || !ok(hipStreamSynchronize(s))) break;
         const double err = std::sqrt(rnorm2 / wnorm2);
-        if (errors_host) errors_host[K - 1] = err;
+        if (errors_host)
+            for (int64_t r = K0; r < K; ++r) errors_host[r] = err;      // (one error per iteration, repeated for its components)
         *rank_out = K;
         if (err <= tol) break;
     }

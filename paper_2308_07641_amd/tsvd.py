@@ -55,6 +55,7 @@ _PROTOTYPES = {
     "tsvd_leading_singular_pair_workspace": (_sz, [_i64, _i64]),
     "tsvd_leading_singular_pair": (ctypes.c_int, [_vp, _i64, _i64, ctypes.c_int32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "tsvd_transition": (ctypes.c_int, [_vp, _i64, _i64, ctypes.c_double, ctypes.c_double, _i64, _vp, _vp, _vp, _pi64, _vp, _vp]),
+    "tsvd_transition_q": (ctypes.c_int, [_vp, _i64, _i64, ctypes.c_double, ctypes.c_double, _i64, _i64, _vp, _vp, _vp, _pi64, _vp, _vp]),
     "tsvd_conv2d_workspace_bytes": (_sz, [_vp, _vp, _i64, _i64, _i64]),
     "tsvd_conv2d_forward": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, ctypes.c_int, _vp, _sz, _vp]),
     "tsvd_free": (None, [_vp]),
@@ -453,8 +454,9 @@ def tsvd_leading_singular_pair(R, max_iters: int = 512, stream=None):
     return u, sigma, v, iters
 
 
-def tsvd_transition(W, theta: float, tol: float, max_rank: int, stream=None):
-    """Algorithm 2 (q = 1) for W float64 [M, N]: returns (U int8 [M, K], S float64 [K], V int8 [K, N], errors list)."""
+def tsvd_transition(W, theta: float, tol: float, max_rank: int, stream=None, q: int = 1):
+    """Algorithm 2 (q components per iteration) for W float64 [M, N]: returns (U int8 [M, K], S float64 [K],
+    V int8 [K, N], errors list with one entry per component, status)."""
     import torch
     M, N = W.shape
     _need(W, torch.float64, (M, N), "W")
@@ -463,8 +465,8 @@ def tsvd_transition(W, theta: float, tol: float, max_rank: int, stream=None):
     S = torch.empty((max_rank,), dtype=torch.float64, device=W.device)
     rank = _i64(0)
     errors = np.zeros(max_rank, dtype=np.float64)
-    status = load_library().tsvd_transition(W.data_ptr(), M, N, float(theta), float(tol), int(max_rank), U.data_ptr(), S.data_ptr(),
-                                            V.data_ptr(), ctypes.byref(rank), errors.ctypes.data, _stream(W, stream))
+    status = load_library().tsvd_transition_q(W.data_ptr(), M, N, float(theta), float(tol), int(max_rank), int(q), U.data_ptr(),
+                                              S.data_ptr(), V.data_ptr(), ctypes.byref(rank), errors.ctypes.data, _stream(W, stream))
     K = int(rank.value)
     if status != 0 and not (status == 2 and K > 0):
         _check(status, "tsvd_transition")

@@ -122,6 +122,36 @@ def test_transition_follows_the_oracle_on_separated_spectra(tsvd):
     assert np.max(np.abs(np.array(errs) - np.array(eo))) <= 1e-9
 
 
+@pytest.mark.parametrize("q", [2, 3, 4])
+def test_transition_with_several_components_per_iteration(tsvd, q):
+    """q > 1: the top q singular triples of one residual per iteration (by deflation on the GPU, by a full SVD in the
+    oracle).  Separated spectrum: both must pick the same ternary vectors, scales and errors; a rank limit that q does
+    not divide ends with a shorter last iteration."""
+    rng = np.random.default_rng(9)           # (a seed at which every leading vector has a ternary neighbour within theta)
+    M, N, r = 96, 80, 14
+    A, _ = np.linalg.qr(rng.standard_normal((M, r)))
+    B, _ = np.linalg.qr(rng.standard_normal((N, r)))
+    W = (A * (1.7 ** -np.arange(r))[None, :]) @ B.T
+    rank = 12
+    Uo, So, Vo, eo = tr.transition(W, THETA, q=q, max_rank=rank)
+    U, S, V, errs, status = tsvd.tsvd_transition(_dev(W), THETA, 0.0, rank, q=q)
+    assert status == 0
+    U, S, V = U.cpu().numpy(), S.cpu().numpy(), V.cpu().numpy()
+    assert U.shape == Uo.shape == (M, rank) and V.shape == Vo.shape
+    for k in range(rank):
+        sign = 1 if np.array_equal(U[:, k], Uo[:, k]) else -1
+        assert np.array_equal(sign * U[:, k], Uo[:, k]) and np.array_equal(sign * V[k, :], Vo[k, :]), k
+    assert np.max(np.abs(S - So)) <= 1e-8 * np.max(np.abs(So))
+    assert np.max(np.abs(np.array(errs)[q - 1::q] - np.array(eo))) <= 1e-9          # one error per iteration
+    # rank limit 7 with q = 3: iterations of 3, 3 and 1 components; the first six equal the oracle's two rounds
+    if q == 3:
+        U7, S7, V7, e7, status = tsvd.tsvd_transition(_dev(W), THETA, 0.0, 7, q=3)
+        assert status == 0 and U7.shape == (M, 7) and len(e7) == 7
+        Uo6 = tr.transition(W, THETA, q=3, max_rank=6)[0]
+        U7 = U7.cpu().numpy()
+        assert all(np.array_equal(U7[:, k], Uo6[:, k]) or np.array_equal(-U7[:, k], Uo6[:, k]) for k in range(6))
+
+
 def test_transition_wide_matrix_and_rank_limit(tsvd):
     """M < N, exit by the rank limit, status and shapes; the first components equal the oracle's."""
     W = np.random.default_rng(12).laplace(size=(48, 160))
