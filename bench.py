@@ -386,6 +386,8 @@ def main():
     ap.add_argument("--conv-only", action="store_true", help="run only the convolution-form measurement (for profiling)")
     ap.add_argument("--transition-only", action="store_true",
                     help="run only the transition measurement and print its record (for profiling)")
+    ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
+                    help="set a diagnostic switch of include/tsvd_tuning.h for this run (A/B measurements; repeatable)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -401,6 +403,9 @@ def main():
     torch.cuda.set_device(0)
     import paper_2308_07641_amd as tsvd
     tsvd.load_library()
+    for item in args.tune:
+        k, v = item.split("=", 1)
+        tsvd.tsvd_tuning_set(k, int(v))
 
     if args.transition_only:
         print(json.dumps(bench_transition()), flush=True)

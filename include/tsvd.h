@@ -120,10 +120,21 @@ tsvd_status tsvd_dense_unpack_host(const void* blob, size_t blob_bytes, int8_t* 
  *   stream : hipStream_t as void* (NULL = the default stream).  Work is enqueued and the
  *            call returns without synchronising.
  * x, y and workspace are owned by the caller and must not alias.  Inputs must be finite.
- * Accumulation is fp32; TSVD_F32 activations are consumed exactly (split into bf16 parts),
- * so the result differs from exact arithmetic only by fp32 summation rounding.  For B >= 2
- * with TSVD_BF16 activations the intermediate z is rounded to fp16 (11 significant bits)
- * after a per-token power-of-two scaling that keeps it in range.
+ *
+ * Arithmetic (accumulation is fp32 or exact everywhere; the oracle-relative bounds are those the tests check):
+ *   B = 1 (and TSVD_F32 activations with B >= 2, which are handled one token at a time, each pass streaming the
+ *     weights again): x is converted to sign-magnitude fixed point with 30 bits below the largest |x| (entries below
+ *     2^-31 of it become 0), every sum of V(.) and U(.) is then an exact integer; z = S * (V x) is rounded to fp32
+ *     and converted the same way relative to the bound max_k |S_k| nnz(V[k,:]) * max|x|.  Error: 1e-5 of max|y| at
+ *     most (measured 1e-7 .. 8e-7).
+ *   2 <= B (TSVD_BF16): x enters exactly, stage V accumulates exact products in fp32, z is multiplied by a
+ *     per-token power of two that keeps it in range and rounded to fp16 (11 significant bits), stage U accumulates
+ *     exact products in fp32.  Long contractions with many tiles run both stages on fp4 codes and three fp6 (E2M3)
+ *     planes of the activations with block scales, which resolve 2^-14.7 of the largest magnitude among 32
+ *     neighbours (below the fp16 rounding of z).  Error: 2e-3 of max|y| at most (measured 2.0e-4 .. 2.4e-4).
+ * Limits of the batched kernels (32-bit buffer offsets): N * ldx, Kp * (B rounded up to 256), Mp * Kp / 8 and
+ * Kp * Np / 8 must each be below 2^30; larger calls return TSVD_EUNSUPPORTED (split the tokens).  B <= 2^24.
+ * A single-token call may also be enqueued on several streams at once with separate workspaces.
  */
 size_t tsvd_workspace_bytes(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype);
 

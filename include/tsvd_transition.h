@@ -70,6 +70,10 @@ tsvd_status tsvd_leading_singular_pair(const double* R_dev, int64_t M, int64_t N
  *   W_dev : [M][N] fp64.   U_dev : [M][max_rank] int8, V_dev : [max_rank][N] int8, S_dev :
  *   [max_rank] fp64: the first *rank_out columns / rows / entries are the result (U has row stride
  *   max_rank).   errors_host : optional host array [max_rank]: relative error after each iteration.
+ * Inside the loop Eq. (3) is solved by conjugate gradients started from the previous scales (the new ones at 0).
+ * For a non-singular Gram matrix that is the solution of Eq. (3); if two components coincide (a singular Gram
+ * matrix) it is A least-squares optimum with the same residual, not necessarily the minimum-norm one that the
+ * pseudo-inverse of Eq. (3) selects (tsvd_fit_scales, started from zero, gives that one).
  * Returns TSVD_EVALUE if some leading vector has no ternary vector within theta (the paper's
  * algorithm raises an error there); the components found so far are kept in *rank_out.
  * max_rank <= 2048, M, N <= 8192.  Allocates and frees its own device scratch. */

@@ -21,6 +21,8 @@ struct tsvd_handle {
     bool owns_blob;
     void* scratch;          // device, handle-owned workspace (grown on demand)
     size_t scratch_bytes;
+    void* retired[16];      // earlier, smaller scratch buffers: enqueued work may still use them, so they live until tsvd_free
+    int retired_count;
     float bound_V;          // max_k |S_k| * nnz(V[k,:]) : |z_k| <= bound_V * max|x| for every token
     int cu_count;           // compute units of the device
     long long* clocks;      // tuning aid (TSVD_CLOCKS=1 at pack time): phase timestamps of the B <= 2 kernel
@@ -458,6 +460,7 @@ extern "C" tsvd_status tsvd_pack(const int8_t* U, const float* S, const int8_t* 
     h->bound_V = (float)bound;
     h->scratch = nullptr;
     h->scratch_bytes = 0;
+    h->retired_count = 0;
     h->clocks = nullptr;
     h->cu_count = 256;
     h->sync = nullptr;
@@ -606,20 +609,26 @@ extern "C" tsvd_status tsvd_forward_io(const tsvd_handle* h, const void* x_dev, 
         if (workspace_bytes != 0) return TSVD_EINVAL;
         tsvd_handle* hm = const_cast<tsvd_handle*>(h);
         if (hm->scratch_bytes < need) {
-            // Stream-ordered work may still use the old buffer: drain before replacing it.
-            if (hm->scratch) {
-                if (hipDeviceSynchronize() != hipSuccess) return TSVD_EDEVICE;
-                (void)hipFree(hm->scratch);
-                hm->scratch = nullptr;
-                hm->scratch_bytes = 0;
-            }
+            // Enqueued work may still use the old buffer.  It is not freed here (hipFree would wait for the whole
+            // device): it is kept until tsvd_free, and the new one is at least twice as large, so at most 16
+            // buffers ever retire and their sizes sum to less than the live one.  Only when that list is full
+            // does the call fall back to draining the device.
             void* d = nullptr;
-            if (hipMalloc(&d, need) != hipSuccess) {
+            const size_t grow = std::max(need, 2 * hm->scratch_bytes);
+            if (hipMalloc(&d, grow) != hipSuccess) {
                 (void)hipGetLastError();
                 return TSVD_EDEVICE;
             }
+            if (hm->scratch) {
+                if (hm->retired_count < 16) {
+                    hm->retired[hm->retired_count++] = hm->scratch;
+                } else {
+                    if (hipDeviceSynchronize() != hipSuccess) return TSVD_EDEVICE;
+                    (void)hipFree(hm->scratch);
+                }
+            }
             hm->scratch = d;
-            hm->scratch_bytes = need;
+            hm->scratch_bytes = grow;
         }
         ws = hm->scratch;
     }
@@ -670,7 +679,8 @@ extern "C" tsvd_status tsvd_forward_io(const tsvd_handle* h, const void* x_dev, 
         g.ws = ws;
         g.cu_count = h->cu_count;
         g.clocks = h->clocks;
-        return tsvd_forward_gemm(g, s) == hipSuccess ? TSVD_OK : TSVD_EDEVICE;
+        const hipError_t ge = tsvd_forward_gemm(g, s);
+        return ge == hipSuccess ? TSVD_OK : ge == hipErrorNotSupported ? TSVD_EUNSUPPORTED : TSVD_EDEVICE;
     }
     return forward_skinny(h, x_dev, x_dtype, B, ldx, y_dev, ldy, oo, ws, s);
 }
@@ -777,6 +787,7 @@ extern "C" int tsvd_tuning_read_clocks(const tsvd_handle* h, long long* out, int
 extern "C" void tsvd_free(tsvd_handle* h) {
     if (!h) return;
     if (h->scratch) (void)hipFree(h->scratch);
+    for (int r = 0; r < h->retired_count; ++r) (void)hipFree(h->retired[r]);
     if (h->clocks) (void)hipFree(h->clocks);
     if (h->sync) (void)hipFree(h->sync);
     if (h->dense_u) (void)hipFree(h->dense_u);

@@ -1,4 +1,4 @@
-// Batched path (B >= 64, bf16 activations): both stages of Y = U (diag(S) (V X)) as
+// Batched path (B >= 17, bf16 activations; the few-token kernels take most calls below 65 tokens): both stages of Y = U (diag(S) (V X)) as
 // ternary-weight x 16-bit-activation contractions on the matrix cores.
 //
 // Paper: section "Truncated SVD in Network Compression" (the three-step identity) and
@@ -1907,7 +1907,7 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     // buffer loads address with 32-bit byte offsets
     if ((size_t)hd.N * g.ldx * 2 >= (1ull << 31) || (size_t)hd.Kp * Bp * 2 >= (1ull << 31) ||
         (size_t)hd.Mp * hd.Kp / 4 >= (1ull << 31) || (size_t)hd.Kp * hd.Np / 4 >= (1ull << 31))
-        return hipErrorInvalidValue;
+        return hipErrorNotSupported;         // (reported as TSVD_EUNSUPPORTED; the limits are documented in tsvd.h)
     gemm_args a1;
     a1.tiles = reinterpret_cast<const uint32_t*>(g.blob + hd.off_V);
     a1.nkt = (int)(hd.Np / 256);
