@@ -304,3 +304,13 @@ def test_dense_code_is_1_6_bits_per_element_and_rejects_corruption():
     out = np.full(blob.nbytes, 0xAB, dtype=np.uint8)
     assert lib.tsvd_dense_pack_host(U2.ctypes.data, 40, 300, out.ctypes.data, out.nbytes) == 2 and np.all(out == 0xAB)
     assert lib.tsvd_dense_pack_host(U.ctypes.data, 40, 300, out.ctypes.data, out.nbytes - 1) == 1
+
+
+def test_bench_reads_traffic_records_from_the_tracked_profile():
+    """bench.py takes roofline.traffic from profiles/hbm_traffic_fetch_write_size.md and only for the kernel selection
+    the record was measured on."""
+    import bench
+    got = bench._traffic_from_profile("opt66b_fc1_prefill", "tsvd_gemm_fp6_kernel:40")
+    assert got is not None and 1.5e9 < got < 4e9
+    assert bench._traffic_from_profile("opt66b_fc1_prefill", "tsvd_gemm_pipe_kernel:1") is None      # another kernel: no claim
+    assert bench._traffic_from_profile("no_such_workload", "x") is None
