@@ -27,7 +27,8 @@ extern "C" {
  *   times the error, inside the tolerance without margin; never a default), TSVD_GROUPED_PAIR,
  *   TSVD_CLOCKS (1 at tsvd_pack: record phase timestamps per workgroup), TSVD_SPIN_LIMIT (bound of the
  *   single-launch kernels' wait for another workgroup's slice of z, in polls), TSVD_DENSE_U (1 at tsvd_pack: keep a
- *   second copy of U in the five-elements-per-byte code and run stage U of single-token calls on it).
+ *   second copy of U in the five-elements-per-byte code and run stage U of single-token calls on it),
+ *   TSVD_EARLY_TILES (0: the single-token kernels request their first weight tile only after the activations are in).
  * Returns 0, or 1 for an unknown name. */
 int tsvd_tuning_set(const char* name, int value);
 

@@ -202,6 +202,7 @@ bool try_gemv(const tsvd_handle* h, const void* x, tsvd_dtype x_dtype, int64_t l
     a.N = (int)hd.N; a.Np = (int)hd.Np; a.Kp = (int)hd.Kp;
     a.meta = meta;
     a.clocks = h->clocks;
+    a.early_tiles = env_int("TSVD_EARLY_TILES", 1);
     if (mask & 2) {
         a.tiles = h->blob + hd.off_V;
         a.strips = (int)(hd.Kp / 16);
@@ -713,7 +714,7 @@ const char* const tuning_names[] = {
     "TSVD_MID", "TSVD_MID_MAX_B", "TSVD_MID_SW", "TSVD_MID_KWLOG2", "TSVD_MID_RESIDENT", "TSVD_GEMM_MIN_B",
     "TSVD_GEMM_CFG_V", "TSVD_GEMM_CFG_U", "TSVD_FUSEMAX", "TSVD_COLMAX_SCALAR", "TSVD_REALIGN", "TSVD_PANEL",
     "TSVD_PANEL_WAVES", "TSVD_FP6", "TSVD_FP6_V", "TSVD_FP6_TALL", "TSVD_FP6_PLANES", "TSVD_GROUPED_PAIR", "TSVD_CLOCKS",
-    "TSVD_SPIN_LIMIT", "TSVD_DENSE_U"};
+    "TSVD_SPIN_LIMIT", "TSVD_DENSE_U", "TSVD_EARLY_TILES"};
 constexpr int tuning_count = (int)(sizeof tuning_names / sizeof tuning_names[0]);
 int tuning_value[tuning_count];
 bool tuning_is_set[tuning_count];

@@ -54,6 +54,7 @@ struct tsvd_gemv_args {
     void* y; long long ldy;               // fp32 (or bf16 with out_bf16) [M][ldy]
     const float* bias; int out_bf16;      // bias per output row or null; output type
     int* meta;                            // fixed-point exponent of z (written by V, read by U)
+    int early_tiles;                      // 1: the first tile request goes out with the activation loads (default), 0: after them
     long long* clocks;                    // optional tuning aid: [grid][16] phase timestamps, or null
 };
 // Both stages of a single token in ONE launch of ONE workgroup, for matrices of at most 64 tiles
