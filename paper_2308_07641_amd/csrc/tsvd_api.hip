@@ -635,6 +635,11 @@ extern "C" tsvd_status tsvd_forward_io(const tsvd_handle* h, const void* x_dev, 
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     const out_opts oo = {bias_dev, y_dtype == TSVD_BF16, y_layout == TSVD_TOKEN_MAJOR};
+    if (x_layout == TSVD_TOKEN_MAJOR && B == 1) {
+        // a single token is one contiguous vector in either layout: feature-major with unit row pitch, no copy
+        x_layout = TSVD_FEATURE_MAJOR;
+        ldx = 1;
+    }
     if (x_layout == TSVD_TOKEN_MAJOR) {
         // one pass that rewrites x as [N][B rounded up to 8] at the front of the workspace; the rows
         // of the copy are 16-byte aligned, so every kernel family takes its fast loads
