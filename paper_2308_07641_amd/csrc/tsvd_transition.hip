@@ -270,144 +270,135 @@ tsvd_sum_kernel(const double* __restrict__ partial, int count, double* __restric
     if (threadIdx.x == 0) out[0] = total;
 }
 
-// ---- leading singular pair by Golub-Kahan-Lanczos bidiagonalisation, one workgroup ----------------
+// ---- leading singular pair by Golub-Kahan-Lanczos bidiagonalisation ------------------------------------
 // R V_k = U_k B_k with B_k upper bidiagonal (alpha on the diagonal, beta above it):
 //   u_i = R v_i - beta_{i-1} u_{i-1},  alpha_i = |u_i|;   w = R^T u_i - alpha_i v_i,  beta_i = |w|,  v_{i+1} = w / beta_i,
 // every new vector orthogonalised against all earlier ones (classical Gram-Schmidt, twice).  The
 // leading singular triple of the small B_k (found on the host) gives that of R; for the close
 // singular values of a random matrix this needs tens of steps where the power iteration needs
-// thousands.  Steps k0 .. k1 - 1 of a run are done per launch (v_{k0} must be in vb[k0]); the work
-// vectors live in LDS, the bases ub [kmax][M], vb [kmax + 1][N] in global memory (L2).
+// thousands.  A step is four launches: the two matrix-vector products run on all compute units
+// (tsvd_gkl_rv_kernel: a wavefront per row; tsvd_gkl_rtu_kernel: 64 columns x a slice of the rows per
+// workgroup, partial sums), each followed by one workgroup that orthogonalises and normalises the new
+// vector with it in LDS (tsvd_gkl_finish_kernel).  (One workgroup doing everything took 100 us per step on
+// a [512, 256] matrix, 95 % of the transition's time.)  The bases ub [kmax][M], vb [kmax + 1][N] live in
+// global memory (L2).
 #define GKL_MAX_STEPS 128
+#define GKL_ROW_SLICES 16
+
+// uw[m] = sum_n R[m][n] v[n] - beta_prev * u_prev[m]: one wavefront per row (grid ceil(M / 4), block 256).
+__global__ void __launch_bounds__(256)
+tsvd_gkl_rv_kernel(const double* __restrict__ R, int M, int N, const double* __restrict__ v, const double* __restrict__ u_prev,
+                   const double* __restrict__ beta_prev, double* __restrict__ uw) {
+    const int m = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (m >= M) return;
+    const double* row = R + (size_t)m * N;
+    double a0 = 0.0, a1 = 0.0;
+    int n = lane;
+    for (; n + 64 < N; n += 128) {
+        a0 += row[n] * v[n];
+        a1 += row[n + 64] * v[n + 64];
+    }
+    if (n < N) a0 += row[n] * v[n];
+    double a = a0 + a1;
+    for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o, 64);
+    if (lane == 0) uw[m] = a - (u_prev ? beta_prev[0] * u_prev[m] : 0.0);
+}
+
+// part[slice][n] = sum over the rows of the slice of R[m][n] u[m]: grid (ceil(N / 64), GKL_ROW_SLICES), block 256 =
+// 64 columns x 4 row phases.
+__global__ void __launch_bounds__(256)
+tsvd_gkl_rtu_kernel(const double* __restrict__ R, int M, int N, const double* __restrict__ u, double* __restrict__ part) {
+    __shared__ double red[4][64];
+    const int col = blockIdx.x * 64 + (threadIdx.x & 63), phase = threadIdx.x >> 6;
+    const int m0 = (int)(((long long)M * blockIdx.y) / GKL_ROW_SLICES), m1 = (int)(((long long)M * (blockIdx.y + 1)) / GKL_ROW_SLICES);
+    double a0 = 0.0, a1 = 0.0;
+    if (col < N) {
+        int m = m0 + phase;
+        for (; m + 4 < m1; m += 8) {
+            a0 += R[(size_t)m * N + col] * u[m];
+            a1 += R[(size_t)(m + 4) * N + col] * u[m + 4];
+        }
+        if (m < m1) a0 += R[(size_t)m * N + col] * u[m];
+    }
+    red[phase][threadIdx.x & 63] = a0 + a1;
+    __syncthreads();
+    if (phase == 0 && col < N) part[(size_t)blockIdx.y * N + col] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+}
+
+// One workgroup: x = (raw vector, or the sum of `slices` partial vectors minus scale[0] * sub) orthogonalised twice
+// against basis[0 .. count), normalised, written to basis[count]; its norm to norm_out[0].  init: x is the fixed start
+// vector instead (count = 0).
 __global__ void __launch_bounds__(1024)
-tsvd_gkl_kernel(const double* __restrict__ R, int M, int N, int k0, int k1, int fresh, double* __restrict__ ub,
-                double* __restrict__ vb, double* __restrict__ alpha, double* __restrict__ beta) {
+tsvd_gkl_finish_kernel(const double* __restrict__ raw, int slices, const double* __restrict__ sub, const double* __restrict__ scale,
+                       int len, double* __restrict__ basis, int count, double* __restrict__ norm_out, int init) {
     extern __shared__ __align__(16) unsigned char smem[];
-    double* u = reinterpret_cast<double*>(smem);    // [M]
-    double* w = u + M;                              // [N]
-    double* part = w + N;                           // [4][max(M, N)] partial sums (columns of R^T u, projections)
-    double* coef = part + 4 * (size_t)(M > N ? M : N);   // [GKL_MAX_STEPS + 1] projections
+    double* x = reinterpret_cast<double*>(smem);    // [len]
+    double* part = x + len;                         // [4][len] partial sums of the projections
+    double* coef = part + 4 * (size_t)len;          // [GKL_MAX_STEPS + 1]
     double* red = coef + GKL_MAX_STEPS + 1;         // [1024]
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    auto norm2 = [&](const double* x, int len) {
-        double a = 0.0;
-        for (int k = tid; k < len; k += 1024) a += x[k] * x[k];
-        red[tid] = a;
-        __syncthreads();
-        for (int st = 512; st > 0; st >>= 1) {
-            if (tid < st) red[tid] += red[tid + st];
-            __syncthreads();
+    if (init) {                  // a fixed start vector with no special symmetry
+        for (int n = tid; n < len; n += 1024) x[n] = 1.0 + 0.5 * sin(1.0 + 0.7 * (double)n);
+    } else {
+        const double sc = sub ? scale[0] : 0.0;
+        for (int e = tid; e < len; e += 1024) {
+            double a = raw[e];
+            for (int q = 1; q < slices; ++q) a += raw[(size_t)q * len + e];
+            x[e] = a - (sub ? sc * sub[e] : 0.0);
         }
-        const double out = red[0];
-        __syncthreads();
-        return out;
-    };
-    // x (LDS, length len) -= sum_j <basis_j, x> basis_j for j < count, twice
-    auto orthogonalise = [&](double* x, int len, const double* basis, int count) {
-        for (int pass = 0; pass < 2 && count > 0; ++pass) {
-            // four basis vectors per wavefront at a time: their loads overlap (one at a time the loop
-            // waits an L2 round trip per vector)
-            for (int j0 = wave * 4; j0 < count; j0 += 64) {
-                double a[4] = {0.0, 0.0, 0.0, 0.0};
-                for (int e = lane; e < len; e += 64) {
-                    const double xe = x[e];
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) a[t] += basis[(size_t)min(j0 + t, count - 1) * len + e] * xe;
-                }
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    for (int o = 32; o > 0; o >>= 1) a[t] += __shfl_xor(a[t], o, 64);
-                    if (lane == 0 && j0 + t < count) coef[j0 + t] = a[t];
-                }
-            }
-            __syncthreads();
-            // x[e] -= sum_j coef[j] basis_j[e]: for short vectors the basis range is split over groups of
-            // threads (partial sums through `part`), so that all 1024 threads have loads in flight
-            const int groups = len <= 256 ? 4 : len <= 512 ? 2 : 1, per = 1024 / groups;
-            const int grp = tid / per, t = tid - grp * per;
-            const int j0 = (count * grp) / groups, j1 = (count * (grp + 1)) / groups;
-            for (int e = t; e < len; e += per) {
-                double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
-                int j = j0;
-                for (; j + 3 < j1; j += 4) {
-                    a0 += coef[j] * basis[(size_t)j * len + e];
-                    a1 += coef[j + 1] * basis[(size_t)(j + 1) * len + e];
-                    a2 += coef[j + 2] * basis[(size_t)(j + 2) * len + e];
-                    a3 += coef[j + 3] * basis[(size_t)(j + 3) * len + e];
-                }
-                for (; j < j1; ++j) a0 += coef[j] * basis[(size_t)j * len + e];
-                part[(size_t)grp * len + e] = (a0 + a1) + (a2 + a3);
-            }
-            __syncthreads();
-            for (int e = tid; e < len; e += 1024) {
-                double a = x[e];
-                for (int gq = 0; gq < groups; ++gq) a -= part[(size_t)gq * len + e];
-                x[e] = a;
-            }
-            __syncthreads();
-        }
-    };
-    if (k0 == 0 && fresh) {      // a fixed start vector with no special symmetry (a restart finds its own in vb[0])
-        for (int n = tid; n < N; n += 1024) w[n] = 1.0 + 0.5 * sin(1.0 + 0.7 * (double)n);
-        __syncthreads();
-        const double nv = sqrt(norm2(w, N));
-        for (int n = tid; n < N; n += 1024) vb[n] = w[n] / nv;
-        __syncthreads();
     }
-    for (int i = k0; i < k1; ++i) {
-        const double* vi = vb + (size_t)i * N;
-        const double bprev = i > 0 ? beta[i - 1] : 0.0;
-        for (int m0 = wave * 4; m0 < M; m0 += 64) {             // u = R v_i - beta_{i-1} u_{i-1}, four rows at a time
+    __syncthreads();
+    for (int pass = 0; pass < 2 && count > 0; ++pass) {
+        // four basis vectors per wavefront at a time: their loads overlap
+        for (int j0 = wave * 4; j0 < count; j0 += 64) {
             double a[4] = {0.0, 0.0, 0.0, 0.0};
-            for (int n = lane; n < N; n += 64) {
-                const double vn = vi[n];
+            for (int e = lane; e < len; e += 64) {
+                const double xe = x[e];
 #pragma unroll
-                for (int t = 0; t < 4; ++t) a[t] += R[(size_t)min(m0 + t, M - 1) * N + n] * vn;
+                for (int t = 0; t < 4; ++t) a[t] += basis[(size_t)min(j0 + t, count - 1) * len + e] * xe;
             }
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 for (int o = 32; o > 0; o >>= 1) a[t] += __shfl_xor(a[t], o, 64);
-                const int m = m0 + t;
-                if (lane == 0 && m < M) u[m] = a[t] - (i > 0 ? bprev * ub[(size_t)(i - 1) * M + m] : 0.0);
+                if (lane == 0 && j0 + t < count) coef[j0 + t] = a[t];
             }
         }
         __syncthreads();
-        orthogonalise(u, M, ub, i);
-        const double al = sqrt(norm2(u, M));
-        for (int m = tid; m < M; m += 1024) {
-            const double q = al > 0.0 ? u[m] / al : 0.0;
-            u[m] = q;
-            ub[(size_t)i * M + m] = q;
-        }
-        __syncthreads();
-        {                                                       // w = R^T u_i - alpha_i v_i: four row groups per column
-            const int grp = tid >> 8, t = tid & 255;
-            const int m0 = (int)(((long long)M * grp) / 4), m1 = (int)(((long long)M * (grp + 1)) / 4);
-            for (int n = t; n < N; n += 256) {
-                double a[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};      // independent chains: the loads overlap
-                int m = m0;
-                for (; m + 7 < m1; m += 8) {
-#pragma unroll
-                    for (int q = 0; q < 8; ++q) a[q] += R[(size_t)(m + q) * N + n] * u[m + q];
-                }
-                for (; m < m1; ++m) a[0] += R[(size_t)m * N + n] * u[m];
-                part[(size_t)grp * N + n] = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+        // x[e] -= sum_j coef[j] basis_j[e]: for short vectors the basis range is split over groups of threads
+        const int groups = len <= 256 ? 4 : len <= 512 ? 2 : 1, per = 1024 / groups;
+        const int grp = tid / per, t = tid - grp * per;
+        const int j0 = (count * grp) / groups, j1 = (count * (grp + 1)) / groups;
+        for (int e = t; e < len; e += per) {
+            double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+            int j = j0;
+            for (; j + 3 < j1; j += 4) {
+                a0 += coef[j] * basis[(size_t)j * len + e];
+                a1 += coef[j + 1] * basis[(size_t)(j + 1) * len + e];
+                a2 += coef[j + 2] * basis[(size_t)(j + 2) * len + e];
+                a3 += coef[j + 3] * basis[(size_t)(j + 3) * len + e];
             }
+            for (; j < j1; ++j) a0 += coef[j] * basis[(size_t)j * len + e];
+            part[(size_t)grp * len + e] = (a0 + a1) + (a2 + a3);
         }
         __syncthreads();
-        for (int n = tid; n < N; n += 1024)
-            w[n] = (part[n] + part[N + n]) + (part[2 * (size_t)N + n] + part[3 * (size_t)N + n]) - al * vi[n];
-        __syncthreads();
-        orthogonalise(w, N, vb, i + 1);
-        const double be = sqrt(norm2(w, N));
-        for (int n = tid; n < N; n += 1024) vb[(size_t)(i + 1) * N + n] = be > 0.0 ? w[n] / be : 0.0;
-        if (tid == 0) {
-            alpha[i] = al;
-            beta[i] = be;
+        for (int e = tid; e < len; e += 1024) {
+            double a = x[e];
+            for (int gq = 0; gq < groups; ++gq) a -= part[(size_t)gq * len + e];
+            x[e] = a;
         }
-        __threadfence();
         __syncthreads();
     }
+    double ss = 0.0;
+    for (int e = tid; e < len; e += 1024) ss += x[e] * x[e];
+    red[tid] = ss;
+    __syncthreads();
+    for (int st = 512; st > 0; st >>= 1) {
+        if (tid < st) red[tid] += red[tid + st];
+        __syncthreads();
+    }
+    const double nrm = sqrt(red[0]);
+    for (int e = tid; e < len; e += 1024) basis[(size_t)count * len + e] = nrm > 0.0 ? x[e] / nrm : 0.0;
+    if (tid == 0 && norm_out) norm_out[0] = nrm;
 }
 
 // x = sum_j c_j basis_j (j < count), normalised; one workgroup per output vector (blockIdx.x: 0 = u, 1 = v).
@@ -576,7 +567,8 @@ extern "C" tsvd_status tsvd_residual(const double* W_dev, const int8_t* U_dev, i
 
 extern "C" size_t tsvd_leading_singular_pair_workspace(int64_t M, int64_t N) {
     if (M < 1 || N < 1 || M > TERN_MAX_N || N > TERN_MAX_N) return 0;
-    return round256((size_t)GKL_MAX_STEPS * M * 8) + round256((size_t)(GKL_MAX_STEPS + 1) * N * 8) + 4 * round256(GKL_MAX_STEPS * 8);
+    return round256((size_t)GKL_MAX_STEPS * M * 8) + round256((size_t)(GKL_MAX_STEPS + 1) * N * 8) + 4 * round256(GKL_MAX_STEPS * 8) +
+           round256((size_t)M * 8) + round256((size_t)GKL_ROW_SLICES * N * 8);      // raw R v, partial R^T u
 }
 
 extern "C" tsvd_status tsvd_leading_singular_pair(const double* R_dev, int64_t M, int64_t N, int32_t max_steps, double* u_dev,
@@ -587,8 +579,8 @@ extern "C" tsvd_status tsvd_leading_singular_pair(const double* R_dev, int64_t M
         return TSVD_EINVAL;
     if (workspace_bytes < tsvd_leading_singular_pair_workspace(M, N) || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return TSVD_EINVAL;
-    const size_t lds = ((size_t)M + (size_t)N + 4 * (size_t)std::max(M, N) + GKL_MAX_STEPS + 1 + 1024) * 8;
-    if (lds > 150 * 1024) return TSVD_EUNSUPPORTED;
+    auto finish_lds = [](int64_t len) { return ((size_t)5 * (size_t)len + GKL_MAX_STEPS + 1 + 1024) * 8; };
+    if (finish_lds(std::max(M, N)) > 150 * 1024) return TSVD_EUNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t* w8 = static_cast<uint8_t*>(workspace);
     double* ub = reinterpret_cast<double*>(w8);
@@ -597,6 +589,8 @@ extern "C" tsvd_status tsvd_leading_singular_pair(const double* R_dev, int64_t M
     double* beta = alpha + round256(GKL_MAX_STEPS * 8) / 8;
     double* zc = beta + round256(GKL_MAX_STEPS * 8) / 8;
     double* yc = zc + round256(GKL_MAX_STEPS * 8) / 8;
+    double* uw = yc + round256(GKL_MAX_STEPS * 8) / 8;                          // R v_i before orthogonalisation
+    double* wpart = uw + round256((size_t)M * 8) / 8;                           // [GKL_ROW_SLICES][N] partial R^T u_i
     const int kmax = (int)std::min<int64_t>(GKL_MAX_STEPS, std::min(M, N));   // the Krylov space cannot outgrow the matrix
     std::vector<double> ha(GKL_MAX_STEPS), hb(GKL_MAX_STEPS), d, e, y, z;
     int total = 0, fresh = 1;
@@ -606,7 +600,21 @@ extern "C" tsvd_status tsvd_leading_singular_pair(const double* R_dev, int64_t M
         bool done = false;
         while (!done) {
             const int k1 = std::min(kmax, k == 0 ? std::min(32, kmax) : k + 16);
-            hipLaunchKernelGGL(tsvd_gkl_kernel, dim3(1), dim3(1024), lds, s, R_dev, (int)M, (int)N, k, k1, fresh, ub, vb, alpha, beta);
+            if (k == 0 && fresh)       // a restart finds its start vector in vb[0]
+                hipLaunchKernelGGL(tsvd_gkl_finish_kernel, dim3(1), dim3(1024), finish_lds(N), s, static_cast<const double*>(nullptr), 0,
+                                   static_cast<const double*>(nullptr), static_cast<const double*>(nullptr), (int)N, vb, 0,
+                                   static_cast<double*>(nullptr), 1);
+            for (int i = k; i < k1; ++i) {
+                const double* vi = vb + (size_t)i * N;
+                hipLaunchKernelGGL(tsvd_gkl_rv_kernel, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, s, R_dev, (int)M, (int)N, vi,
+                                   i > 0 ? ub + (size_t)(i - 1) * M : static_cast<const double*>(nullptr), i > 0 ? beta + (i - 1) : beta, uw);
+                hipLaunchKernelGGL(tsvd_gkl_finish_kernel, dim3(1), dim3(1024), finish_lds(M), s, uw, 1, static_cast<const double*>(nullptr),
+                                   static_cast<const double*>(nullptr), (int)M, ub, i, alpha + i, 0);
+                hipLaunchKernelGGL(tsvd_gkl_rtu_kernel, dim3((unsigned)((N + 63) / 64), GKL_ROW_SLICES), dim3(256), 0, s, R_dev, (int)M, (int)N,
+                                   ub + (size_t)i * M, wpart);
+                hipLaunchKernelGGL(tsvd_gkl_finish_kernel, dim3(1), dim3(1024), finish_lds(N), s, wpart, GKL_ROW_SLICES, vi, alpha + i, (int)N,
+                                   vb, i + 1, beta + i, 0);
+            }
             if (hipMemcpyAsync(ha.data(), alpha, (size_t)k1 * 8, hipMemcpyDeviceToHost, s) != hipSuccess ||
                 hipMemcpyAsync(hb.data(), beta, (size_t)k1 * 8, hipMemcpyDeviceToHost, s) != hipSuccess ||
                 hipStreamSynchronize(s) != hipSuccess)
@@ -653,7 +661,7 @@ hipError_t tsvd_transition_init() {
                                  5 * FIT_MAX_K * 8 + 1024 * 8)) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_residual_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  FIT_MAX_K * 8)) != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gkl_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gkl_finish_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
 }
 
 extern "C" tsvd_status tsvd_transition(const double* W_dev, int64_t M, int64_t N, double theta, double tol, int64_t max_rank,
