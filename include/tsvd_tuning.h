@@ -23,6 +23,7 @@ extern "C" {
  *   TSVD_MID (0: few-token kernel off), TSVD_MID_MAX_B, TSVD_MID_SW, TSVD_MID_KWLOG2, TSVD_MID_RESIDENT,
  *   TSVD_GEMM_MIN_B, TSVD_GEMM_CFG_V / TSVD_GEMM_CFG_U (tile shape of a batched stage: 0..3 large tiles,
  *   14..17 ring kernel), TSVD_FUSEMAX, TSVD_COLMAX_SCALAR, TSVD_REALIGN, TSVD_PANEL, TSVD_PANEL_WAVES,
+ *   TSVD_PANEL_FP6 (0: the token-panel launch on 16-bit operands instead of fp4 codes x fp6 planes),
  *   TSVD_FP6, TSVD_FP6_V, TSVD_FP6_TALL, TSVD_FP6_PLANES (2: two instead of three fp6 planes -- about five
  *   times the error, inside the tolerance without margin; never a default), TSVD_GROUPED_PAIR,
  *   TSVD_CLOCKS (1 at tsvd_pack: record phase timestamps per workgroup), TSVD_SPIN_LIMIT (bound of the
@@ -44,7 +45,8 @@ tsvd_status tsvd_tuning_forward_stages(const tsvd_handle* h, const void* x_dev, 
                                        int64_t ldy, void* workspace, size_t workspace_bytes, void* stream, int stage_mask);
 
 /* The tile shapes tsvd_forward picks for B tokens of 16-byte-aligned bf16 activations (stage V, stage U):
- * 0..3 / 14..17 as above, 32 for both when the call is one token-panel launch, 40 for the fp4 x fp6 kernels,
+ * 0..3 / 14..17 as above, 32 / 33 for both when the call is one token-panel launch (16-bit operands / fp4 codes x fp6 planes), 40 for the
+ * fp4 x fp6 kernels of the two-launch path,
  * -1 where the batched kernels are not used.  Returns 0 on success. */
 int tsvd_tuning_tile_shapes(const tsvd_handle* h, long long B, int* shape_v, int* shape_u);
 

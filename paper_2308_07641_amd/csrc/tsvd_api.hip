@@ -718,7 +718,7 @@ const char* const tuning_names[] = {
     "TSVD_GEMV", "TSVD_GEMV_FUSED", "TSVD_GEMV_ONEPASS", "TSVD_GEMV_SW", "TSVD_GEMV_KWLOG2", "TSVD_SKINNY_SW", "TSVD_SKINNY_KW",
     "TSVD_MID", "TSVD_MID_MAX_B", "TSVD_MID_SW", "TSVD_MID_KWLOG2", "TSVD_MID_RESIDENT", "TSVD_GEMM_MIN_B",
     "TSVD_GEMM_CFG_V", "TSVD_GEMM_CFG_U", "TSVD_FUSEMAX", "TSVD_COLMAX_SCALAR", "TSVD_REALIGN", "TSVD_PANEL",
-    "TSVD_PANEL_WAVES", "TSVD_FP6", "TSVD_FP6_V", "TSVD_FP6_TALL", "TSVD_FP6_PLANES", "TSVD_GROUPED_PAIR", "TSVD_CLOCKS",
+    "TSVD_PANEL_WAVES", "TSVD_PANEL_FP6", "TSVD_FP6", "TSVD_FP6_V", "TSVD_FP6_TALL", "TSVD_FP6_PLANES", "TSVD_GROUPED_PAIR", "TSVD_CLOCKS",
     "TSVD_SPIN_LIMIT", "TSVD_DENSE_U", "TSVD_EARLY_TILES"};
 constexpr int tuning_count = (int)(sizeof tuning_names / sizeof tuning_names[0]);
 int tuning_value[tuning_count];
@@ -769,7 +769,7 @@ extern "C" int tsvd_tuning_tile_shapes(const tsvd_handle* h, long long B, int* s
     if (use_mid(h, B, TSVD_BF16, tsvd_round_up(B, 8))) return 0;
     if (use_gemm(h, B, TSVD_BF16)) {
         if (tsvd_gemm_use_panel(h->hd.Mp, h->hd.Kp, h->hd.Np, B, h->cu_count, true)) {
-            *shape_v = *shape_u = 32;                 // one token-panel launch
+            *shape_v = *shape_u = tsvd_gemm_panel_fp6() ? 33 : 32;   // one token-panel launch (33: on fp4 codes x fp6 planes)
         } else {
             *shape_v = tsvd_gemm_tile_shape(h->hd.Kp, B, h->cu_count, true);
             *shape_u = tsvd_gemm_tile_shape(h->hd.Mp, B, h->cu_count, true);

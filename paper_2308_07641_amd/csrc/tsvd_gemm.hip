@@ -720,6 +720,55 @@ tsvd_gemm_pipe_kernel(gemm_args p) {
 #define FP6_PAIR_BYTES (8 * FP6_REC_BYTES)      // one block of one 128-token group: 38 KiB exactly
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 
+// One lane's 32 values -> three E2M3 planes (the value, the residual of its rounding, the residual of that), each
+// with its own power-of-two scale.  put(plane, first 16 bytes, last 8 bytes) receives the lane's 24 bytes of each
+// plane; the return value holds the three scale bytes.  (v is used up.)
+template <typename Put>
+__device__ __forceinline__ uint32_t tsvd_planes_of_32(float (&v)[32], Put put) {
+    typedef float f32x16 __attribute__((ext_vector_type(16)));
+    typedef float f32x32 __attribute__((ext_vector_type(32)));
+    typedef unsigned u32x6 __attribute__((ext_vector_type(6)));
+    uint32_t scales = 0;
+#pragma unroll
+    for (int pl = 0; pl < 3; ++pl) {
+        float m = 0.f;
+#pragma unroll
+        for (int e = 0; e < 32; ++e) m = fmaxf(m, fabsf(v[e]));
+        // exponent ex with m 2^-ex <= 7.5, the largest E2M3 magnitude (m = f 2^x, 0.5 <= f < 1)
+        int x = 0;
+        const float f = frexpf(m, &x);
+        int ex = m > 0.f ? (f <= 0.9375f ? x - 3 : x - 2) : 0;
+        ex = max(-126, min(126, ex));
+        scales |= (uint32_t)(127 + ex) << (8 * pl);
+        const float unit = ldexpf(1.0f, ex);
+        // v_cvt_scalef32_2xpk16_fp6_f32: element 2 j of the result is src0[j] / scale, element 2 j + 1 is
+        // src1[j] / scale, rounded to nearest even on the E2M3 grid (saturating); the reverse conversion
+        // returns the elements in the same order, times the scale (measured on gfx950)
+        f32x16 s0, s1;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            s0[j] = v[2 * j];
+            s1[j] = v[2 * j + 1];
+        }
+        const u32x6 w = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(s0, s1, unit);
+        if (pl < 2) {
+            const f32x32 back = __builtin_amdgcn_cvt_scalef32_pk32_f32_fp6(w, unit);
+#pragma unroll
+            for (int e = 0; e < 32; ++e) v[e] -= back[e];         // exact: the next plane codes this residual
+        }
+        put(pl, u32x4{w[0], w[1], w[2], w[3]}, u32x2{w[4], w[5]});
+    }
+    return scales;
+}
+// ... written to the lane's places in the record at `rec`
+__device__ __forceinline__ void tsvd_planes_of_32(float (&v)[32], unsigned char* rec, int lane) {
+    const uint32_t scales = tsvd_planes_of_32(v, [&](int pl, u32x4 lo, u32x2 hi) {
+        *reinterpret_cast<u32x4*>(rec + pl * 1024 + lane * 16) = lo;
+        *reinterpret_cast<u32x2*>(rec + 3072 + pl * 512 + lane * 8) = hi;
+    });
+    *reinterpret_cast<uint32_t*>(rec + 4608 + lane * 4) = scales;
+}
+
 // grid (Bp / 128, Kp / 128), block 512 = 8 tiles x 64 lanes.  The [128 indices][128 tokens] block of Z
 // is read row by row (256 contiguous bytes each) into LDS, from where every thread picks the 32
 // values of its lane of the operand (row pitch 129 words: the picks of a wavefront, 16 tokens x 4
@@ -758,40 +807,7 @@ tsvd_z_planes_kernel(const uint16_t* __restrict__ Z, long long ld, int rows_vali
         const uint16_t h = (tok & 1) ? (uint16_t)(w >> 16) : (uint16_t)(w & 0xFFFFu);
         v[e] = BF16 ? __uint_as_float((uint32_t)h << 16) : (float)__builtin_bit_cast(_Float16, h);
     }
-    unsigned char* rec = planes + ((size_t)(blockIdx.x * nblocks + blockIdx.y) * 8 + tt) * FP6_REC_BYTES;
-    typedef float f32x16 __attribute__((ext_vector_type(16)));
-    typedef float f32x32 __attribute__((ext_vector_type(32)));
-    typedef unsigned u32x6 __attribute__((ext_vector_type(6)));
-    uint32_t scales = 0;
-#pragma unroll
-    for (int pl = 0; pl < 3; ++pl) {
-        float m = 0.f;
-#pragma unroll
-        for (int e = 0; e < 32; ++e) m = fmaxf(m, fabsf(v[e]));
-        // exponent ex with m 2^-ex <= 7.5, the largest E2M3 magnitude (m = f 2^x, 0.5 <= f < 1)
-        int x = 0;
-        const float f = frexpf(m, &x);
-        int ex = m > 0.f ? (f <= 0.9375f ? x - 3 : x - 2) : 0;
-        ex = max(-126, min(126, ex));
-        scales |= (uint32_t)(127 + ex) << (8 * pl);
-        const float unit = ldexpf(1.0f, ex);
-        // v_cvt_scalef32_2xpk16_fp6_f32: element 2 j of the result is src0[j] / scale, element 2 j + 1 is
-        // src1[j] / scale, rounded to nearest even on the E2M3 grid (saturating); the reverse conversion
-        // returns the elements in the same order, times the scale (measured on gfx950)
-        f32x16 s0, s1;
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            s0[j] = v[2 * j];
-            s1[j] = v[2 * j + 1];
-        }
-        const u32x6 w = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(s0, s1, unit);
-        const f32x32 back = __builtin_amdgcn_cvt_scalef32_pk32_f32_fp6(w, unit);
-#pragma unroll
-        for (int e = 0; e < 32; ++e) v[e] -= back[e];             // exact: the next plane codes this residual
-        *reinterpret_cast<u32x4*>(rec + pl * 1024 + lane * 16) = u32x4{w[0], w[1], w[2], w[3]};
-        *reinterpret_cast<u32x2*>(rec + 3072 + pl * 512 + lane * 8) = u32x2{w[4], w[5]};
-    }
-    *reinterpret_cast<uint32_t*>(rec + 4608 + lane * 4) = scales;
+    tsvd_planes_of_32(v, planes + ((size_t)(blockIdx.x * nblocks + blockIdx.y) * 8 + tt) * FP6_REC_BYTES, lane);
 }
 
 template <int PL>
@@ -1601,6 +1617,346 @@ tsvd_panel_kernel(panel_args p) {
         p.clocks[blockIdx.x * 16 + 8 + wave / (NW / 8)] = wall_clock64();   // end of (one of) the wavefronts of each eighth
 }
 
+// ---- token-panel kernel on fp4 codes x fp6 planes ---------------------------------------------
+// The same ownership as tsvd_panel_kernel (a workgroup takes 64 tokens from x to y, z never leaves the compute
+// unit), with the arithmetic of tsvd_gemm_fp6_kernel: both stages multiply fp4 codes by three E2M3 planes on
+// v_mfma_scale_f32_16x16x128_f8f6f4, 48 matrix-pipe cycles per 16 x 16 x 128 block against 64 for the 16-bit
+// form, and 6 decoding operations per 8 bytes of code words against 32.
+//   phase 0  x[N][64 tokens] -> plane records in LDS (a lane gathers the 32 values of its operand lane from
+//            global memory; rows beyond N and tokens beyond B read as zero);
+//   phase 1  wavefront w multiplies rank block w (128 rank positions x 64 tokens) and keeps it in registers.
+//            Row r = 4 g + v of its j-th 16 x 16 result block is loaded from V's row 64 (g & 1) + 16 (g >> 1) +
+//            32 (j >> 2) + 4 (j & 3) + v of the rank block (a per-lane address into the 1-KiB tiles), so that
+//            result lane (g, token) ends up holding exactly the 32 rank positions, in element order 4 j + v,
+//            of lane (g, token) of stage U's B operand: no exchange between lanes or wavefronts;
+//   then     barrier (everyone is done with the planes of x), z = S * result -> planes straight from the
+//            accumulators (fp32, not rounded to 16 bits first; no per-token factor: the block scales carry
+//            the range) into the same LDS area, barrier;
+//   phase 2  Y = U Z in units of 128 rows x 64 tokens, code words of U from global memory to registers two blocks
+//            ahead, operands from the resident records two steps ahead: no barrier, no waiting for memory.
+// Limits: N, K <= 1024 (eight records of 4864 bytes per 16 tokens fill the LDS of a compute unit).
+// Measured on MI355X, M = 2048, N = 512, K = 1024, 12544 tokens (196 workgroups): 59 - 62 us per call against 63 - 67 us
+// for tsvd_panel_kernel<16> on the same boxes, 2.6e-5 of max |y| against 1.8e-4 (z is not rounded to 16 bits).
+// In-kernel clocks (us after the workgroup's start): planes of x 3.7, phase 1 multiplied 12.6, planes of z 15.8, the
+// older wavefront of each SIMD done 45, the younger 54.  A stand-alone copy of the phase-2 loop reaches one MFMA per
+// 19 cycles per SIMD with two wavefronts (16 is the pipe's limit; a single wavefront gets 24.5) and 21.5 with the
+// stores of Y; the kernel itself 25 at the 2.0 GHz the chip sustains under it.  Tried and dropped: units of 128 rows x
+// 32 tokens to start the stores earlier (+3 us: the code words are decoded twice as often), nontemporal stores (no
+// change), the two wavefronts of a SIMD taking turns in priority (-0.5 us, inside the noise).
+#define TSVD_PANEL6_MAX_BLOCKS 8
+#ifndef TSVD_P6_UTN
+#define TSVD_P6_UTN 4                   // token tiles per unit of phase 2
+#endif
+#define TSVD_PANEL6_LDS (TSVD_PANEL6_MAX_BLOCKS * 4 * FP6_REC_BYTES)          // 155648
+#define TSVD_PANEL6_LDS_EX (TSVD_PANEL6_LDS + TSVD_PANEL_BIAS_ROWS * 4)        // 163840: all of it
+
+template <int EX = 0>
+__global__ void __launch_bounds__(512, 1)
+tsvd_panel_fp6_kernel(panel_args p) {
+    constexpr int TM = 8, TN = 4, NW = 8, BT = 64;
+    extern __shared__ __align__(16) unsigned char smem[];     // records [block][token tile]: planes of x, then of z
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int i = lane & 15, g = lane >> 4;
+    const int b0 = blockIdx.x * BT;
+    auto tick = [&](int n) {
+        if (p.clocks && threadIdx.x == 0 && blockIdx.x < TSVD_GEMV_MAX_GRID) p.clocks[blockIdx.x * 16 + n] = wall_clock64();
+    };
+    tick(0);
+    const float* bias_lds = nullptr;
+    if constexpr (EX != 0) {
+        if (p.bias && p.M <= TSVD_PANEL_BIAS_ROWS) {
+            float* dst = reinterpret_cast<float*>(smem + TSVD_PANEL6_LDS);
+            for (int r = threadIdx.x; r < p.M; r += 64 * NW) dst[r] = p.bias[r];
+            bias_lds = dst;
+        }
+    }
+    const int nvb = p.npairs_v, nub = p.npairs_u;             // 128-index blocks of N and of K that hold anything
+
+    // One step = the eight MFMAs (row blocks) of one plane of one record.  The B operand of step t + 2 is read
+    // from LDS before the MFMAs of step t are issued, across records and blocks, so that no step waits for LDS
+    // (the scheduler is held to this order: left to itself it reads every operand right before its use).  The
+    // operand set of a plane is slot `plane`; the scale words of consecutive records alternate between two.
+    u32x4 lo[3];
+    u32x2 hi[3];
+    auto read_planes = [&](const unsigned char* rec, int pl) {
+        lo[pl] = *reinterpret_cast<const u32x4*>(rec + pl * 1024 + lane * 16);
+        hi[pl] = *reinterpret_cast<const u32x2*>(rec + 3072 + pl * 512 + lane * 8);
+    };
+    auto read_scales = [&](const unsigned char* rec) { return *reinterpret_cast<const uint32_t*>(rec + 4608 + lane * 4); };
+    auto decode = [&](const u32x2 (&w)[TM], u32x4 (&av)[TM]) {
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+            av[a] = u32x4{(w[a].x << 2) & 0xCCCCCCCCu, w[a].x & 0xCCCCCCCCu, (w[a].y << 2) & 0xCCCCCCCCu, w[a].y & 0xCCCCCCCCu};
+    };
+
+    // the MFMAs of one 128-index block for NT token tiles (NT x 3 planes x 8 row blocks): the tiles' records at cur, those
+    // of the block that follows at nxt
+    auto block_steps = [&](auto nt_c, const unsigned char* cur, const unsigned char* nxt, const u32x4 (&av)[TM], uint32_t (&sc)[2],
+                           f32x4 (&acc)[TM][decltype(nt_c)::value]) {
+        constexpr int NT = decltype(nt_c)::value;
+        static_assert(NT % 2 == 0, "the scale words alternate between two registers");
+#pragma unroll
+        for (int st = 0; st < 3 * NT; ++st) {
+            const int nt = st + 2, s2 = nt % (3 * NT);
+            const unsigned char* rec = (nt < 3 * NT ? cur : nxt) + (s2 / 3) * FP6_REC_BYTES;
+            read_planes(rec, s2 % 3);
+            if (s2 % 3 == 0) sc[(s2 / 3) & 1] = read_scales(rec);
+            __builtin_amdgcn_sched_barrier(0);
+            const int b = st / 3;
+#pragma unroll
+            for (int a = 0; a < TM; ++a) {
+                switch (st % 3) {
+                    case 0: acc[a][b] = mfma_fp6<0>(av[a], lo[0], hi[0], sc[b & 1], acc[a][b]); break;
+                    case 1: acc[a][b] = mfma_fp6<1>(av[a], lo[1], hi[1], sc[b & 1], acc[a][b]); break;
+                    default: acc[a][b] = mfma_fp6<2>(av[a], lo[2], hi[2], sc[b & 1], acc[a][b]); break;
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // ================= phase 0: planes of x =================
+    {
+        const __amdgpu_buffer_rsrc_t x_rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.x), 0, p.x_bytes, 0x00020000);
+        const int ld2 = (int)p.ldx * 2;
+        const int njobs = nvb * TN;                           // job q: block q / 4 of N, token tile q % 4
+        auto gather = [&](int q, uint32_t (&raw)[32]) {
+            const int nb = q >> 2, b = q & 3;
+            const int voff = (64 * (g & 1) + 16 * (g >> 1)) * ld2 + (b0 + 16 * b + i) * 2;
+#pragma unroll
+            for (int e = 0; e < 32; ++e)
+                raw[e] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(x_rsrc, voff, (nb * 128 + 32 * (e >> 4) + (e & 15)) * ld2, 0);
+        };
+        // (two jobs in flight: the second one's trip to memory overlaps the first one's, not its conversion)
+        uint32_t raw0[32], raw1[32];
+        auto convert = [&](int q, const uint32_t (&raw)[32]) {
+            const bool tok_ok = b0 + 16 * (q & 3) + i < p.B;
+            float v[32];
+#pragma unroll
+            for (int e = 0; e < 32; ++e) v[e] = tok_ok ? __uint_as_float(raw[e] << 16) : 0.f;
+            tsvd_planes_of_32(v, smem + q * FP6_REC_BYTES, lane);
+        };
+        if (wave < njobs) gather(wave, raw0);
+        if (wave + NW < njobs) gather(wave + NW, raw1);
+        for (int q = wave; q < njobs; q += 2 * NW) {
+            convert(q, raw0);
+            if (q + 2 * NW < njobs) gather(q + 2 * NW, raw0);
+            if (q + NW < njobs) {
+                convert(q + NW, raw1);
+                if (q + 3 * NW < njobs) gather(q + 3 * NW, raw1);
+            }
+        }
+    }
+    const __amdgpu_buffer_rsrc_t v_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(p.tiles_v), 0, p.tile_v_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t u_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(p.tiles_u), 0, p.tile_u_bytes, 0x00020000);
+
+    // ================= phase 1: rank block `wave` of S V X =================
+    // (Measured and dropped: one token tile after the other, the planes of a finished tile made while the other
+    // wavefront of the SIMD multiplies: the code words are then decoded once per 24 MFMAs instead of once per 96,
+    // and the stage took 15 instead of 12 us on N = 512, K = 1024.)
+    {
+        const bool has_block = wave < nub;
+        f32x4 acc[TM][TN];
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // lane (ga, r) of the A operand: row r = 4 gg + vv of result block j comes from row
+        // 64 (gg & 1) + 16 (gg >> 1) + 32 (j >> 2) + 4 (j & 3) + vv of the rank block, i.e. strip
+        // 8 wave + 4 (gg & 1) + (gg >> 1) + 2 (j >> 2), row 4 (j & 3) + vv of it
+        const int r = lane & 15, gg = r >> 2, vv = r & 3;
+        const int voff = ((8 * wave + 4 * (gg & 1) + (gg >> 1)) * p.nkt_v) * 1024 + (g * 16 + vv) * 16;
+        auto load_wv = [&](int nb, u32x2 (&w)[TM]) {
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+                w[j] = __builtin_amdgcn_raw_buffer_load_b64(
+                    v_rsrc, voff, (2 * (j >> 2) * p.nkt_v + (nb >> 1)) * 1024 + 4 * (j & 3) * 16 + (nb & 1) * 8, 0);
+        };
+        u32x2 wa[TM];
+        if (has_block) load_wv(0, wa);
+        __syncthreads();                                  // the planes of x are complete
+        tick(1);
+        if (has_block) {
+            const int lastb = nvb - 1;
+            read_planes(smem, 0);
+            read_planes(smem, 1);
+            uint32_t sc[2];
+            sc[0] = read_scales(smem);
+            for (int nb = 0; nb < nvb; ++nb) {
+                const unsigned char* cur = smem + nb * TN * FP6_REC_BYTES;
+                const unsigned char* nxt = smem + min(nb + 1, lastb) * TN * FP6_REC_BYTES;
+                u32x4 av[TM];
+                decode(wa, av);
+                load_wv(min(nb + 1, lastb), wa);          // (the wait for it falls at the next decode)
+                block_steps(std::integral_constant<int, TN>{}, cur, nxt, av, sc, acc);
+            }
+            // z = S * (V x) / 4 (the codes of either stage multiply as +-2; powers of two, so nothing is rounded): S of this
+            // lane's 32 rank positions, four consecutive ones per result block
+#pragma unroll
+            for (int j = 0; j < TM; ++j) {
+                const f32x4 sv = *reinterpret_cast<const f32x4*>(p.S + 128 * wave + 64 * (g & 1) + 16 * (g >> 1) + 32 * (j >> 2) + 4 * (j & 3));
+#pragma unroll
+                for (int b = 0; b < TN; ++b) acc[j][b] *= 0.25f * sv;
+            }
+        }
+        __syncthreads();                                  // every wavefront is done with the planes of x
+        tick(2);
+        if (has_block) {
+#pragma unroll
+            for (int b = 0; b < TN; ++b) {
+                float v[32];
+#pragma unroll
+                for (int e = 0; e < 32; ++e) v[e] = acc[e >> 2][b][e & 3];
+                tsvd_planes_of_32(v, smem + (wave * TN + b) * FP6_REC_BYTES, lane);
+            }
+        }
+        __syncthreads();
+        tick(3);
+    }
+
+    // ================= phase 2: Y = U Z in units of 128 rows x 16 UTN tokens, no barriers =================
+    // A wavefront's units follow each other as one sequence of blocks: the code words of block s + 2 of the sequence are
+    // requested when block s is decoded, so those of the next unit's first two blocks are in registers before this
+    // unit's stores are issued (stores and loads share one counter: a load requested after 64 stores is known to be
+    // in only when they all are), and the B operands are read two steps ahead across unit boundaries as well.
+    // (The stores cost the phase 8 of its 39 us: the same kernel without them takes 48 instead of 60 us per call, and
+    // 56 with all of them going to one small cached region, so it is the store instructions, not HBM.)
+    {
+        constexpr int UTN = TSVD_P6_UTN, HALVES = TN / UTN;
+        const int units = ((p.M + 127) / 128) * HALVES, lastb = nub - 1;
+        const int w_voff = lane * 16;
+        if (wave < units) {
+            const int last_un = wave + (units - 1 - wave) / NW * NW;
+            const int tile0 = (wave % HALVES) * UTN;          // (the same for all units of a wavefront: NW is a multiple of HALVES)
+            int lu = wave, lb = 0;                            // the block of the sequence that the next request fetches
+            auto load_next = [&](u32x2 (&w)[TM]) {
+                const int soff = ((lu / HALVES) * TM * p.nkt_u + (lb >> 1)) * 1024 + (lb & 1) * 8;
+#pragma unroll
+                for (int a = 0; a < TM; ++a) w[a] = __builtin_amdgcn_raw_buffer_load_b64(u_rsrc, w_voff, soff + a * p.nkt_u * 1024, 0);
+                if (lb < lastb) ++lb;
+                else if (lu < last_un) { lu += NW; lb = 0; }  // (at the end: the last block again)
+            };
+            u32x2 w0[TM], w1[TM];
+            load_next(w0);
+            load_next(w1);
+            const unsigned char* z0 = smem + tile0 * FP6_REC_BYTES;
+            read_planes(z0, 0);
+            read_planes(z0, 1);
+            uint32_t sc[2];
+            sc[0] = read_scales(z0);
+            for (int unit = wave; unit < units; unit += NW) {
+                const int strip0 = (unit / HALVES) * TM;
+                f32x4 acc[TM][UTN];
+#pragma unroll
+                for (int a = 0; a < TM; ++a)
+#pragma unroll
+                    for (int b = 0; b < UTN; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+                for (int blk = 0; blk < nub; blk += 2) {
+                    u32x4 av[TM];
+                    decode(w0, av);
+                    load_next(w0);
+                    block_steps(std::integral_constant<int, UTN>{}, z0 + blk * TN * FP6_REC_BYTES,
+                                z0 + (blk == lastb ? 0 : blk + 1) * TN * FP6_REC_BYTES, av, sc, acc);
+                    if (blk + 1 <= lastb) {
+                        decode(w1, av);
+                        load_next(w1);
+                        block_steps(std::integral_constant<int, UTN>{}, z0 + (blk + 1) * TN * FP6_REC_BYTES,
+                                    z0 + (blk + 1 == lastb ? 0 : blk + 2) * TN * FP6_REC_BYTES, av, sc, acc);
+                    }
+                }
+                if (nub & 1) {                                // the sequence goes on in the other register set
+#pragma unroll
+                    for (int a = 0; a < TM; ++a) {
+                        const u32x2 t = w0[a];
+                        w0[a] = w1[a];
+                        w1[a] = t;
+                    }
+                }
+                // (wait for the next unit's code words here, before the stores)
+#pragma unroll
+                for (int a = 0; a < TM; ++a) asm volatile("" :: "v"(w0[a].x), "v"(w0[a].y), "v"(w1[a].x), "v"(w1[a].y));
+                float br[TM][4];
+                if constexpr (EX != 0) {
+                    auto fill = [&](auto src) {
+#pragma unroll
+                        for (int a = 0; a < TM; ++a)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) br[a][v] = src(min((strip0 + a) * 16 + 4 * g + v, p.M - 1));
+                    };
+                    if (bias_lds) fill([&](int row) { return bias_lds[row]; });
+                    else if (p.bias) fill([&](int row) { return p.bias[row]; });
+                    else fill([](int) { return 0.f; });
+                }
+                int c0 = b0 + tile0 * 16;                     // first token of the unit
+                asm volatile("" : "+s"(c0));                  // (addresses are formed here, not kept in registers over the MFMAs)
+                if constexpr (EX == 3) {
+                    const bool vec_ok = !(p.ldy & 3) && !(reinterpret_cast<uintptr_t>(p.y) & 15);
+#pragma unroll
+                    for (int a = 0; a < TM; ++a) {
+#pragma unroll
+                        for (int b = 0; b < UTN; ++b) {
+                            const int col = c0 + b * 16 + i;
+                            if (col < p.B)
+                                tsvd_store_token_major4(p.y, p.ldy, col, (strip0 + a) * 16 + 4 * g, p.M, acc[a][b][0] + br[a][0],
+                                                        acc[a][b][1] + br[a][1], acc[a][b][2] + br[a][2], acc[a][b][3] + br[a][3],
+                                                        p.out_bf16, vec_ok);
+                        }
+                    }
+                } else if constexpr (EX == 2) {
+                    const bool aligned4 = !(p.ldy & 1) && !(reinterpret_cast<uintptr_t>(p.y) & 3);
+#pragma unroll
+                    for (int a = 0; a < TM; ++a) {
+#pragma unroll
+                        for (int vp = 0; vp < 4; vp += 2) {
+#pragma unroll
+                            for (int b = 0; b < UTN; ++b)
+                                tsvd_store_row_pair_bf16(p.y, p.ldy, (strip0 + a) * 16 + 4 * g + vp, p.M, c0 + b * 16, i, p.B,
+                                                         acc[a][b][vp] + br[a][vp], acc[a][b][vp + 1] + br[a][vp + 1], aligned4);
+                        }
+                    }
+                } else if (c0 + UTN * 16 <= p.B && p.ldy < (1ll << 21)) {
+                    // All tokens of the unit exist: 32 UTN stores whose addresses are the lane's constant offset plus a
+                    // scalar (no vector arithmetic per store); rows beyond M fall outside the buffer's range and are
+                    // dropped by the range check (the range is exact where it matters, in the last unit).
+                    const size_t left = ((size_t)(p.M - strip0 * 16) * p.ldy - c0) * 4;
+                    const __amdgpu_buffer_rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                        static_cast<float*>(p.y) + (size_t)strip0 * 16 * p.ldy + c0, 0, (int)(left < 0xFFFFFFFFull ? left : 0xFFFFFFFFull), 0x00020000);
+                    const int ld4 = (int)p.ldy * 4, y_voff = 4 * g * ld4 + i * 4;
+#pragma unroll
+                    for (int a = 0; a < TM; ++a)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+#pragma unroll
+                            for (int b = 0; b < UTN; ++b)
+                                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(EX == 1 ? acc[a][b][v] + br[a][v] : acc[a][b][v]), y_rsrc,
+                                                                      y_voff + b * 64, (a * 16 + v) * ld4, 0);
+                } else {
+#pragma unroll
+                    for (int a = 0; a < TM; ++a) {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int row = (strip0 + a) * 16 + 4 * g + v;
+                            if (row < p.M) {
+                                float* dst = static_cast<float*>(p.y) + (size_t)row * p.ldy;
+#pragma unroll
+                                for (int b = 0; b < UTN; ++b) {
+                                    const int col = c0 + b * 16 + i;
+                                    if (col < p.B) dst[col] = EX == 1 ? acc[a][b][v] + br[a][v] : acc[a][b][v];
+                                }
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+    tick(4);
+    if (p.clocks && lane == 0 && blockIdx.x < TSVD_GEMV_MAX_GRID) p.clocks[blockIdx.x * 16 + 8 + wave] = wall_clock64();
+}
+
 // Epilogue variant of a stage-U launch: 0 plain fp32, 1 fp32 with bias, 2 bf16, 3 token-major output.
 int out_variant(const float* bias, int out_bf16, int token_major) {
     return token_major ? 3 : out_bf16 ? 2 : bias ? 1 : 0;
@@ -1776,6 +2132,9 @@ bool tsvd_gemm_use_panel(long long Mp, long long Kp, long long Np, long long B, 
     return (Mp + Np) * Kp / 4 <= (8ll << 20) && 10 * n >= 6 * rounds * cus;
 }
 
+// The token-panel launch on fp4 codes x fp6 planes (tsvd_panel_fp6_kernel) or on the 16-bit kernel (TSVD_PANEL_FP6 = 0).
+bool tsvd_gemm_panel_fp6() { return tsvd_tune("TSVD_PANEL_FP6", 1) != 0; }
+
 // Stage U through fp6 planes of Z (tsvd_gemm_fp6_kernel): TSVD_FP6 = 0 never, 1 whenever the sizes
 // allow, default by rule.  The planes of Z need tsvd_gemm_fp6_bytes more workspace.
 size_t tsvd_gemm_fp6_bytes(long long Kp, long long Bp) { return (size_t)(Bp / 128) * (size_t)(Kp / 128) * FP6_PAIR_BYTES; }
@@ -1890,6 +2249,14 @@ hipError_t tsvd_gemm_init() {
                                  TSVD_PANEL_LDS_EX(8))) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_kernel<16, 3>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  TSVD_PANEL_LDS_EX(16))) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_fp6_kernel<0>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 TSVD_PANEL6_LDS)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_fp6_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 TSVD_PANEL6_LDS_EX)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_fp6_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 TSVD_PANEL6_LDS_EX)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_fp6_kernel<3>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 TSVD_PANEL6_LDS_EX)) != hipSuccess) return e;
 #define TSVD_RING_INIT(id, wm, wn, tm, tn, npb, kg) \
     if ((e = init_ring<wm, wn, tm, tn, npb, kg>()) != hipSuccess) return e;
     TSVD_RING_SHAPES(TSVD_RING_INIT)
@@ -1983,7 +2350,12 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
         pa.clocks = g.clocks;
         const dim3 pgrid((unsigned)((g.B + 63) / 64));
         const int ex = out_variant(g.bias, g.out_bf16, g.y_token_major);
-        if (env_cfg("TSVD_PANEL_WAVES", 16) == 16) {   // tuning switch: 16 is about 5 % faster on MI355X
+        if (tsvd_gemm_panel_fp6()) {                   // fp4 codes x fp6 planes (TSVD_PANEL_FP6 = 0: the 16-bit panel kernel)
+            if (ex == 3) hipLaunchKernelGGL((tsvd_panel_fp6_kernel<3>), pgrid, dim3(512), TSVD_PANEL6_LDS_EX, stream, pa);
+            else if (ex == 2) hipLaunchKernelGGL((tsvd_panel_fp6_kernel<2>), pgrid, dim3(512), TSVD_PANEL6_LDS_EX, stream, pa);
+            else if (ex == 1) hipLaunchKernelGGL((tsvd_panel_fp6_kernel<1>), pgrid, dim3(512), TSVD_PANEL6_LDS_EX, stream, pa);
+            else hipLaunchKernelGGL((tsvd_panel_fp6_kernel<0>), pgrid, dim3(512), TSVD_PANEL6_LDS, stream, pa);
+        } else if (env_cfg("TSVD_PANEL_WAVES", 16) == 16) {   // tuning switch: 16 is about 5 % faster on MI355X
             if (ex == 3) hipLaunchKernelGGL((tsvd_panel_kernel<16, 3>), pgrid, dim3(1024), TSVD_PANEL_LDS_EX(16), stream, pa);
             else if (ex == 2) hipLaunchKernelGGL((tsvd_panel_kernel<16, 2>), pgrid, dim3(1024), TSVD_PANEL_LDS_EX(16), stream, pa);
             else if (ex == 1) hipLaunchKernelGGL((tsvd_panel_kernel<16, 1>), pgrid, dim3(1024), TSVD_PANEL_LDS_EX(16), stream, pa);

@@ -154,6 +154,8 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream);
 int tsvd_gemm_tile_shape(long long rows, long long B, long long cus, bool aligned);
 // True when a batched call runs as ONE token-panel launch (both stages, z kept in LDS).
 bool tsvd_gemm_use_panel(long long Mp, long long Kp, long long Np, long long B, long long cus, bool aligned);
+// ... and whether that launch multiplies fp4 codes by fp6 planes (tsvd_panel_fp6_kernel) or 16-bit operands.
+bool tsvd_gemm_panel_fp6();
 // Stage U through fp6 planes of Z: whether a call takes it, and the extra workspace it needs after Z.
 bool tsvd_gemm_use_fp6(long long Mp, long long Kp, long long Np, long long B, long long cus, bool aligned);
 size_t tsvd_gemm_fp6_bytes(long long Kp, long long Bp);

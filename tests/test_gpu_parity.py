@@ -133,15 +133,19 @@ def test_tile_shape_of_96_rows(tsvd, fuse):
     assert rel_err(y, ref) <= TOL["bf16"]
 
 
-@pytest.mark.parametrize("waves", ["16", "8"])
-@pytest.mark.parametrize("M,N,K,B", [(300, 200, 520, 300), (64, 48, 200, 17), (1030, 100, 1000, 70), (2048, 512, 1024, 1000)])
+@pytest.mark.parametrize("waves", ["fp6", "16", "8"])
+@pytest.mark.parametrize("M,N,K,B", [(300, 200, 520, 300), (64, 48, 200, 17), (1030, 100, 1000, 70), (2048, 512, 1024, 1000),
+                                     (260, 1024, 1024, 129), (129, 1000, 130, 64)])
 def test_token_panel_kernel(tsvd, M, N, K, B, waves):
     """Both stages in one launch with z kept in LDS (K <= 1024), forced on small instances: exact
-    integers bit for bit, random values within tolerance, and next to identical to the two-launch path."""
-    print(f"case panel M={M} N={N} K={K} B={B}", flush=True)
+    integers bit for bit, random values within tolerance, and next to identical to the two-launch path.
+    "fp6": the kernel on fp4 codes x fp6 planes; "16" / "8": the 16-bit kernel with that many wavefronts."""
+    print(f"case panel M={M} N={N} K={K} B={B} {waves}", flush=True)
     i = workloads.make_integer_inputs(M, N, K, B, 0.5, "bf16", seed=5150 + B)
     tsvd.tsvd_tuning_set("TSVD_PANEL", 1)
-    tsvd.tsvd_tuning_set("TSVD_PANEL_WAVES", int(waves))
+    tsvd.tsvd_tuning_set("TSVD_PANEL_FP6", int(waves == "fp6"))
+    if waves != "fp6":
+        tsvd.tsvd_tuning_set("TSVD_PANEL_WAVES", int(waves))
     y, h = run_forward(i)
     tsvd.tsvd_free(h)
     assert not np.isnan(y).any()
@@ -155,9 +159,9 @@ def test_token_panel_kernel(tsvd, M, N, K, B, waves):
     tsvd.tsvd_tuning_set("TSVD_PANEL", 0)
     y0, h = run_forward(j)
     tsvd.tsvd_free(h)
-    # same products; only the fp32 summation order differs between the kernels (a different order in
-    # stage V can move an fp16 rounding of z by one unit in the last place)
-    assert rel_err(y0, y1) <= 1e-5
+    # same products; only the fp32 summation order differs between the 16-bit kernels (a different order in
+    # stage V can move an fp16 rounding of z by one unit in the last place); the planes round z differently
+    assert rel_err(y0, y1) <= (5e-4 if waves == "fp6" else 1e-5)
 
 
 def test_larger_small_problem_uses_wider_ring_tiles(tsvd):
@@ -446,18 +450,19 @@ def test_degenerate_inputs(tsvd, B):
 RAGGED_RANKS = [5, 63, 96, 129, 345, 1545, 2415]
 
 
-@pytest.mark.parametrize("family", ["rule", "ring14", "ring16", "pipe1", "pipe3", "fallback", "panel", "fp6"])
+@pytest.mark.parametrize("family", ["rule", "ring14", "ring16", "pipe1", "pipe3", "fallback", "panel", "panel6", "fp6"])
 @pytest.mark.parametrize("K", RAGGED_RANKS)
 def test_ragged_rank_batched(tsvd, K, family):
     M, N, B = (1000, 768, 200) if K == 2415 else (600, 384, 200)
-    if family == "panel" and K > 1024:
+    if family in ("panel", "panel6") and K > 1024:
         pytest.skip("the token-panel kernel serves ranks up to 1024")
     sw = {"rule": {}, "ring14": {"TSVD_PANEL": 0, "TSVD_FP6": 0, "TSVD_GEMM_CFG_U": 14, "TSVD_GEMM_CFG_V": 15},
           "ring16": {"TSVD_PANEL": 0, "TSVD_FP6": 0, "TSVD_GEMM_CFG_U": 16, "TSVD_GEMM_CFG_V": 16},
           "pipe1": {"TSVD_PANEL": 0, "TSVD_FP6": 0, "TSVD_GEMM_CFG_U": 1, "TSVD_GEMM_CFG_V": 2},
           "pipe3": {"TSVD_PANEL": 0, "TSVD_FP6": 0, "TSVD_GEMM_CFG_U": 3, "TSVD_GEMM_CFG_V": 0},
           "fallback": {"TSVD_PANEL": 0, "TSVD_FP6": 0, "TSVD_REALIGN": 0, "TSVD_GEMM_CFG_U": 2, "TSVD_GEMM_CFG_V": 3},
-          "panel": {"TSVD_PANEL": 1},
+          "panel": {"TSVD_PANEL": 1, "TSVD_PANEL_FP6": 0},
+          "panel6": {"TSVD_PANEL": 1, "TSVD_PANEL_FP6": 1},
           "fp6": {"TSVD_PANEL": 0, "TSVD_FP6": 1, "TSVD_FP6_V": 1, "TSVD_GEMM_CFG_V": 3, "TSVD_FP6_TALL": 3}}[family]
     for k, v in sw.items():
         tsvd.tsvd_tuning_set(k, v)
@@ -499,8 +504,9 @@ LAYER_CASES = [
     (130, 64, 520, 264, {}),                                  # ring kernels (aligned rows)
     (300, 200, 270, 72, {"TSVD_MID": "0", "TSVD_GEMM_CFG_U": "0", "TSVD_GEMM_CFG_V": "1"}),   # pipelined large tiles
     (300, 200, 270, 72, {"TSVD_MID": "0", "TSVD_GEMM_CFG_U": "2", "TSVD_GEMM_CFG_V": "3"}),
-    (300, 200, 520, 304, {"TSVD_PANEL": "1"}),                            # token-panel kernel, 16 wavefronts
-    (300, 200, 520, 304, {"TSVD_PANEL": "1", "TSVD_PANEL_WAVES": "8"}),   # token-panel kernel, 8 wavefronts
+    (300, 200, 520, 304, {"TSVD_PANEL": "1", "TSVD_PANEL_FP6": "0"}),                            # token-panel kernel, 16 wavefronts
+    (300, 200, 520, 304, {"TSVD_PANEL": "1", "TSVD_PANEL_FP6": "0", "TSVD_PANEL_WAVES": "8"}),   # token-panel kernel, 8 wavefronts
+    (300, 200, 520, 304, {"TSVD_PANEL": "1", "TSVD_PANEL_FP6": "1"}),                            # token-panel kernel on fp4 codes x fp6 planes
     (300, 200, 520, 304, {"TSVD_PANEL": "0", "TSVD_GEMM_CFG_U": "14", "TSVD_GEMM_CFG_V": "15"}),   # ring kernels, other shapes
     (700, 200, 760, 304, {"TSVD_PANEL": "0", "TSVD_GEMM_CFG_U": "17", "TSVD_GEMM_CFG_V": "17"}),   # ring kernels, 96-row tiles
     (515, 300, 777, 130, {"TSVD_PANEL": "0", "TSVD_FP6": "1", "TSVD_FP6_V": "0", "TSVD_FP6_TALL": "1"}),   # fp4 x fp6 stage U, 512 x 64 tiles
