@@ -750,9 +750,15 @@ __device__ __forceinline__ uint32_t tsvd_planes_of_32(float (&v)[32], Put put) {
             s0[j] = v[2 * j];
             s1[j] = v[2 * j + 1];
         }
-        const u32x6 w = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(s0, s1, unit);
+        // The conversions take several passes over their registers, and the register allocator lets the result of the
+        // builtins share registers with operands that die at the instruction.  Measured on gfx950: a result tuple that
+        // started in the scale's register left elements 2..31 converted with a wrong scale.  Hence the instructions are
+        // written out with results that may not overlap any operand.
+        u32x6 w;
+        asm("v_cvt_scalef32_2xpk16_fp6_f32 %0, %1, %2, %3" : "=&v"(w) : "v"(s0), "v"(s1), "v"(unit));
         if (pl < 2) {
-            const f32x32 back = __builtin_amdgcn_cvt_scalef32_pk32_f32_fp6(w, unit);
+            f32x32 back;
+            asm("v_cvt_scalef32_pk32_f32_fp6 %0, %1, %2" : "=&v"(back) : "v"(w), "v"(unit));
 #pragma unroll
             for (int e = 0; e < 32; ++e) v[e] -= back[e];         // exact: the next plane codes this residual
         }
@@ -823,10 +829,11 @@ __device__ __forceinline__ f32x4 mfma_fp6(const u32x4& a, const u32x4& lo, const
 // registers, one block ahead.
 // NPL: planes multiplied, 3 or (switch TSVD_FP6_PLANES=2, never by default) the first two: two thirds of the MFMAs
 // for activations exact to 2^-9.8 instead of 2^-14.7 of a block's largest magnitude.
-template <bool STAGE2, int EX, int WM = 2, int WN = 2, int TM = 8, int NPL = 3>
+template <bool STAGE2, int EX, int WM = 2, int WN = 2, int TM = 8, int NPL = 3, bool DIRECT = false>
 __global__ void __launch_bounds__(256, 2)
 tsvd_gemm_fp6_kernel(gemm_args p) {
     static_assert(WM * WN == 4, "four wavefronts");
+    static_assert(!DIRECT || (!STAGE2 && TM == 8 && NPL == 3 && EX == 0), "planes straight from stage V: a wavefront owns whole 128-index blocks");
     constexpr int TN = 4, BT = WN * 64;
     constexpr int BLK_BYTES = BT / 16 * FP6_REC_BYTES;      // one 128-index block of this workgroup's tokens
     constexpr int PIECES = BLK_BYTES / 1024;                // 38 or 19 pieces of 1 KiB
@@ -863,11 +870,16 @@ tsvd_gemm_fp6_kernel(gemm_args p) {
             buf_load128_to_lds(act_rsrc, lds_base + buf * BLK_BYTES + piece * 1024, lane * 16, rec0 + piece * 1024);
         }
     };
-    const int w_voff = lane * 16;
+    // DIRECT: row r = 4 gg + vv of result block a is loaded from row 64 (gg & 1) + 16 (gg >> 1) + 32 (a >> 2) + 4 (a & 3) + vv
+    // of the wavefront's 128 rows (any row order is free on the A side), so that result lane (g, token) ends up holding the
+    // 32 rank positions of lane (g, token) of stage U's B operand, in element order 4 a + v (see tsvd_panel_fp6_kernel)
+    const int rr = lane & 15, gg = rr >> 2, vv = rr & 3;
+    const int w_voff = DIRECT ? (4 * (gg & 1) + (gg >> 1)) * p.nkt * 1024 + (g * 16 + vv) * 16 : lane * 16;
     auto load_w = [&](int blk, u32x2 (&w)[TM]) {
         const int soff = (strip0 * p.nkt + (blk >> 1)) * 1024 + (blk & 1) * 8;
 #pragma unroll
-        for (int a = 0; a < TM; ++a) w[a] = __builtin_amdgcn_raw_buffer_load_b64(w_rsrc, w_voff, soff + a * p.nkt * 1024, 0);
+        for (int a = 0; a < TM; ++a)
+            w[a] = __builtin_amdgcn_raw_buffer_load_b64(w_rsrc, w_voff, soff + (DIRECT ? 2 * (a >> 2) * p.nkt * 1024 + 4 * (a & 3) * 16 : a * p.nkt * 1024), 0);
     };
     auto compute = [&](int buf, const u32x2 (&w)[TM]) {
         u32x4 av[TM];
@@ -916,12 +928,18 @@ tsvd_gemm_fp6_kernel(gemm_args p) {
 
     u32x2 wa[TM], wb[TM];
     float cmax = 0.f;
-    if (threadIdx.x < BT) cmax = load_column_max<STAGE2>(p, b0 + threadIdx.x);
+    // (no per-token factors when z comes as planes straight from stage V, DIRECT there, colmax == null here:
+    // the block scales carry the range, and S / 4 has undone the +-2 of both stages' codes)
+    const bool factors = !DIRECT && p.colmax != nullptr;
+    if (threadIdx.x < BT && factors) cmax = load_column_max<STAGE2>(p, b0 + threadIdx.x);
     load_w(0, wa);
     issue(0, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     touch(wa);
-    if (threadIdx.x < BT) publish_column_factor<STAGE2>(p, b0 + threadIdx.x, cmax, cs_lds, threadIdx.x);
+    if (threadIdx.x < BT) {
+        if (factors) publish_column_factor<STAGE2>(p, b0 + threadIdx.x, cmax, cs_lds, threadIdx.x);
+        else cs_lds[threadIdx.x] = 1.0f;
+    }
     __syncthreads();
     for (int P = 0; P < nrun; P += 2) {
         int nx = min(P + 1, lastb);
@@ -939,7 +957,28 @@ tsvd_gemm_fp6_kernel(gemm_args p) {
         touch(wa);
         __syncthreads();
     }
-    gemm_epilogue<TM, TN, STAGE2, EX>(p, acc, strip0, b0, wn * TN * 16, cs_lds, i, g);
+    if constexpr (DIRECT) {
+        // z = S (V x) / 4 -> three planes per lane and token tile, written as the records stage U reads
+        // ([128-token group][128-index block][16-token tile], the layout of tsvd_z_planes_kernel)
+        const int kb = strip0 >> 3;
+#pragma unroll
+        for (int a = 0; a < TM; ++a) {
+            const f32x4 sv = *reinterpret_cast<const f32x4*>(p.S + 128 * kb + 64 * (g & 1) + 16 * (g >> 1) + 32 * (a >> 2) + 4 * (a & 3));
+#pragma unroll
+            for (int b = 0; b < TN; ++b) acc[a][b] *= 0.25f * sv;
+        }
+        const int tok = b0 + wn * TN * 16;
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+            float v[32];
+#pragma unroll
+            for (int e = 0; e < 32; ++e) v[e] = acc[e >> 2][b][e & 3];
+            tsvd_planes_of_32(v, static_cast<unsigned char*>(p.out) +
+                                     ((size_t)(((tok + 16 * b) >> 7) * (int)p.ld_out + kb) * 8 + (((tok + 16 * b) & 127) >> 4)) * FP6_REC_BYTES, lane);   // (ld_out: blocks per token group)
+        }
+    } else {
+        gemm_epilogue<TM, TN, STAGE2, EX>(p, acc, strip0, b0, wn * TN * 16, cs_lds, i, g);
+    }
 }
 
 // ---- ring variant for small problems -----------------------------------------------------------
@@ -2177,6 +2216,11 @@ bool tsvd_gemm_use_fp6_v(long long Mp, long long Kp, long long Np, long long B, 
     return (Np >= 2048 && (Kp / 256) * ((B + 127) / 128) >= cus) || (Np >= 4096 && (Kp / 128) * ((B + 63) / 64) >= cus);
 }
 
+template <int WM, int WN>
+hipError_t init_fp6_direct() {
+    constexpr int lds = 2 * (WN * 4 * FP6_REC_BYTES) + 512;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_kernel<false, 0, WM, WN, 8, 3, true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+}
 template <int WM, int WN, int TM, int NPL = 3>
 hipError_t init_fp6() {
     constexpr int lds = 2 * (WN * 4 * FP6_REC_BYTES) + 512;
@@ -2203,18 +2247,40 @@ hipError_t launch_fp6(bool stage2, const gemm_args& a, long long rows_p, int Bp,
 // 512 x 64 tiles (4 x 1 wavefronts) when the rows allow: half the traffic of the planes, twice that of the codes;
 // 256 x 64 (four row blocks per wavefront) when those would leave compute units without a tile, 128 x 64 (two)
 // when even those would leave more than a quarter of them without
+// The tile of a launch: 0: 256 x 128 (2 x 2 wavefronts), 1: 512 x 64, 2: 256 x 64, 3: 128 x 64 (4 x 1 wavefronts of 8, 4, 2 row blocks)
+int fp6_tile(long long rows_p, long long bvalid, long long cus) {
+    const int tall = env_cfg("TSVD_FP6_TALL", -1);       // forces one of them, default by rule
+    const long long c128 = (bvalid + 127) / 128, c64 = (bvalid + 63) / 64;   // token tiles that are launched
+    const bool small = tall < 0 && (rows_p / 256) * c128 < cus;
+    if (tall == 3 || (small && 4 * (rows_p / 256) * c64 < 3 * cus)) return 3;
+    if (tall == 2 || small) return 2;
+    if (rows_p % 512 == 0 && tall != 0) return 1;
+    return 0;
+}
 hipError_t launch_fp6_any(bool stage2, const gemm_args& a, long long rows_p, int Bp, int ex, long long cus, hipStream_t stream) {
-    const int tall = env_cfg("TSVD_FP6_TALL", -1);       // 0: 256 x 128, 1: 512 x 64, 2: 256 x 64, 3: 128 x 64, default by rule
     if (env_cfg("TSVD_FP6_PLANES", 3) == 2) {            // accuracy / speed switch (512 x 64 and 256 x 64 tiles only)
         if (rows_p % 512 == 0 && (rows_p / 256) * ((a.bvalid + 127) / 128) >= cus) return launch_fp6<4, 1, 8, 2>(stage2, a, rows_p, Bp, ex, stream);
         return launch_fp6<4, 1, 4, 2>(stage2, a, rows_p, Bp, ex, stream);
     }
-    const long long c128 = (a.bvalid + 127) / 128, c64 = (a.bvalid + 63) / 64;   // token tiles that are launched
-    const bool small = tall < 0 && (rows_p / 256) * c128 < cus;
-    if (tall == 3 || (small && 4 * (rows_p / 256) * c64 < 3 * cus)) return launch_fp6<4, 1, 2>(stage2, a, rows_p, Bp, ex, stream);
-    if (tall == 2 || small) return launch_fp6<4, 1, 4>(stage2, a, rows_p, Bp, ex, stream);
-    if (rows_p % 512 == 0 && tall != 0) return launch_fp6<4, 1, 8>(stage2, a, rows_p, Bp, ex, stream);
-    return launch_fp6<2, 2, 8>(stage2, a, rows_p, Bp, ex, stream);
+    switch (fp6_tile(rows_p, a.bvalid, cus)) {
+        case 3: return launch_fp6<4, 1, 2>(stage2, a, rows_p, Bp, ex, stream);
+        case 2: return launch_fp6<4, 1, 4>(stage2, a, rows_p, Bp, ex, stream);
+        case 1: return launch_fp6<4, 1, 8>(stage2, a, rows_p, Bp, ex, stream);
+        default: return launch_fp6<2, 2, 8>(stage2, a, rows_p, Bp, ex, stream);
+    }
+}
+// Stage V writing the planes of z itself (tiles whose wavefronts own whole 128-index blocks: 256 x 128 and 512 x 64)
+bool fp6_direct_possible(long long rows_p, long long bvalid, long long cus) {
+    return env_cfg("TSVD_FP6_DIRECT", 1) != 0 && env_cfg("TSVD_FP6_PLANES", 3) != 2 && fp6_tile(rows_p, bvalid, cus) <= 1;
+}
+hipError_t launch_fp6_direct(const gemm_args& a, long long rows_p, long long cus, hipStream_t stream) {
+    const bool tall = fp6_tile(rows_p, a.bvalid, cus) == 1;
+    const int wn = tall ? 1 : 2, rows_tile = tall ? 512 : 256, lds = 2 * (wn * 4 * FP6_REC_BYTES) + 512;
+    if (rows_p % rows_tile) return hipErrorInvalidValue;
+    const dim3 grid((a.bvalid + wn * 64 - 1) / (wn * 64), (unsigned)((a.rows_need + rows_tile - 1) / rows_tile)), block(256);
+    if (tall) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<false, 0, 4, 1, 8, 3, true>), grid, block, lds, stream, a);
+    else hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<false, 0, 2, 2, 8, 3, true>), grid, block, lds, stream, a);
+    return hipGetLastError();
 }
 
 hipError_t tsvd_gemm_init() {
@@ -2225,6 +2291,8 @@ hipError_t tsvd_gemm_init() {
     if ((e = init_fp6<4, 1, 2>()) != hipSuccess) return e;
     if ((e = init_fp6<4, 1, 8, 2>()) != hipSuccess) return e;
     if ((e = init_fp6<4, 1, 4, 2>()) != hipSuccess) return e;
+    if ((e = init_fp6_direct<2, 2>()) != hipSuccess) return e;
+    if ((e = init_fp6_direct<4, 1>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 4, 8, 4, false>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 4, 8, 4, true>()) != hipSuccess) return e;
     if ((e = init_gemm<2, 2, 8, 4, false>()) != hipSuccess) return e;
@@ -2371,14 +2439,16 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     int cfg1 = env_cfg("TSVD_GEMM_CFG_V", tsvd_gemm_tile_shape(hd.Kp, g.B, g.cu_count, fast1));
     int cfg2 = env_cfg("TSVD_GEMM_CFG_U", tsvd_gemm_tile_shape(hd.Mp, g.B, g.cu_count, true));
     if (is_ring(cfg1) && !fast1) cfg1 = 3;
-    const bool fp6_v = tsvd_gemm_use_fp6_v(hd.Mp, hd.Kp, hd.Np, g.B, g.cu_count, fast1);   // stage V on planes of x (needs the column maxima)
+    const bool fp6_v = tsvd_gemm_use_fp6_v(hd.Mp, hd.Kp, hd.Np, g.B, g.cu_count, fast1);   // stage V on planes of x
+    // ... writing the planes of z itself where its tile allows: no fp16 z, no column maxima, no separate pass over z
+    const bool direct = fp6_v && fp6_direct_possible(hd.Kp, g.B, g.cu_count);
     const bool fuse = is_ring(cfg1) && env_cfg("TSVD_FUSEMAX", 1) != 0 && !fp6_v;
 
     // Profiling switch: TSVD_STAGE_MASK selects the kernels to launch (1 column maxima,
     // 2 stage V, 4 stage U; default all).  Skipped kernels leave the workspace as it is.
     const int mask = tsvd_stage_mask();
     hipError_t e = hipSuccess;
-    if ((mask & 1) && !fuse) {
+    if ((mask & 1) && !fuse && !direct) {
         if (fast1 && env_cfg("TSVD_COLMAX_SCALAR", 0) == 0)
             hipLaunchKernelGGL(tsvd_colmax_vec_kernel, dim3((unsigned)((g.B + 127) / 128), TSVD_COLMAX_PARTS), dim3(256),
                                0, stream, static_cast<const uint16_t*>(g.x), g.ldx, (int)hd.N, (int)g.B, Bp, colpart);
@@ -2398,17 +2468,27 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
         gemm_args a4 = a1;
         a4.act = reinterpret_cast<const uint16_t*>(xplanes);
         a4.act_bytes = (unsigned)tsvd_gemm_fp6_bytes(hd.Np, Bp);
-        e = launch_fp6_any(false, a4, hd.Kp, Bp, 0, g.cu_count, stream);
+        if (direct) {
+            a4.out = reinterpret_cast<unsigned char*>(Z) + (((size_t)hd.Kp * Bp * 2 + 255) & ~(size_t)255);   // the planes of z
+            a4.ld_out = hd.Kp / 128;                                                                       // blocks per token group
+            a4.colmax = nullptr;
+            e = launch_fp6_direct(a4, hd.Kp, g.cu_count, stream);
+        } else {
+            e = launch_fp6_any(false, a4, hd.Kp, Bp, 0, g.cu_count, stream);
+        }
     } else if (mask & 2) e = fuse ? launch_cfg<false, true>(cfg1, a1, fast1, hd.Kp, Bp, stream)
                            : launch_cfg<false, false>(cfg1, a1, fast1, hd.Kp, Bp, stream);
     if (e != hipSuccess) return e;
     if ((mask & 4) && tsvd_gemm_use_fp6(hd.Mp, hd.Kp, hd.Np, g.B, g.cu_count, fast1)) {
         // Z (fp16) -> three fp6 planes in operand order, then stage U on fp4 x fp6
         unsigned char* planes = reinterpret_cast<unsigned char*>(Z) + (((size_t)hd.Kp * Bp * 2 + 255) & ~(size_t)255);
-        hipLaunchKernelGGL(tsvd_z_planes_kernel<false>, dim3((unsigned)((g.B + 127) / 128), (unsigned)a2.npairs), dim3(512), 0, stream,
-                           reinterpret_cast<const uint16_t*>(Z), (long long)Bp, (int)hd.Kp, Bp, (int)(hd.Kp / 128), planes);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
+        if (!direct) {
+            hipLaunchKernelGGL(tsvd_z_planes_kernel<false>, dim3((unsigned)((g.B + 127) / 128), (unsigned)a2.npairs), dim3(512), 0, stream,
+                               reinterpret_cast<const uint16_t*>(Z), (long long)Bp, (int)hd.Kp, Bp, (int)(hd.Kp / 128), planes);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+        }
         gemm_args a3 = a2;
+        if (direct) a3.colmax = nullptr;               // (no per-token factors: z came scaled and as planes)
         a3.act = reinterpret_cast<const uint16_t*>(planes);
         a3.act_bytes = (unsigned)tsvd_gemm_fp6_bytes(hd.Kp, Bp);
         return launch_fp6_any(true, a3, hd.Mp, Bp, out_variant(a3.bias, a3.out_bf16, a3.out_token_major), g.cu_count, stream);
