@@ -203,14 +203,14 @@ def bench_workload(name, steps, warmup, with_cpu=True, cpu_budget_s=4.0):
                            "traffic": traffic,
                            "whole_path_frac_of_bf16_peak": ach / PEAK_MFMA_TFLOPS}
     elif batched and kernel_name == "tsvd_gemm_fp6_kernel":
-        # stage U = planes pass + fp4 x fp6 kernel.  Achieved = ALGORITHMIC flops (2 M K B) per second; the
+        # stage U = fp4 x fp6 kernel (+ the planes pass where stage V leaves fp16 z).  Achieved = ALGORITHMIC flops (2 M K B) per second; the
         # kernel executes three times as many (three planes) on the fp4 / fp6 MFMA path, whose dense
         # peak is 10.1 PFLOP/s; the fraction of the 2.5 PFLOP/s fp16 peak is given beside it because that
         # is what every other batched kernel here is priced against.
         fl_u = 2.0 * w.K * w.M * w.B
         ach = fl_u / (u_ms * 1e-3) / 1e12
-        res["roofline"] = {"bound": "mfma", "kernel": "tsvd_gemm_fp6_kernel (stage U, fp4 x fp6 MFMA, 3 planes) with its operand pass tsvd_z_planes_kernel "
-                                                     "(about 2 % of the time; both are timed together)",
+        res["roofline"] = {"bound": "mfma", "kernel": "tsvd_gemm_fp6_kernel (stage U, fp4 x fp6 MFMA, 3 planes; where stage V does not write the planes of z "
+                                                     "itself, timed together with the operand pass tsvd_z_planes_kernel, about 2 % of it)",
                            "achieved": ach, "peak": PEAK_MFMA_FP6_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_MFMA_FP6_TFLOPS,
                            "algorithmic_flops": fl_u, "launch_ms": u_ms,
                            "executed_tflops": 3.0 * ach, "executed_frac": 3.0 * ach / PEAK_MFMA_FP6_TFLOPS,
