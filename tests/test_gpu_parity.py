@@ -702,6 +702,28 @@ def test_fp6_planes_stage_u(tsvd, M, N, K, B, stage_v, tile):
     assert rel_err(y0, y1) <= 5e-4        # both round Z to about 12 bits, differently
 
 
+@pytest.mark.parametrize("family", ["panel6", "direct 256x128", "direct 512x64"])
+def test_plane_kernels_resolve_three_planes(tsvd, family):
+    """Where z goes from the fp32 accumulators straight into three E2M3 planes (the fp4 x fp6 token-panel launch, the
+    fp4 x fp6 stage V that writes the planes itself) nothing is rounded to 16 bits on the way: the error is that of
+    the planes, about 3e-5 of max |y|, in EVERY 16-token tile.  (A plane converted with a wrong scale costs a factor
+    of 30 to 100 in the tiles it touches and still passes the 2e-3 tolerance of the other tests.)"""
+    M, N, K, B = (600, 384, 700, 200)
+    sw = {"panel6": {"TSVD_PANEL": 1, "TSVD_PANEL_FP6": 1},
+          "direct 256x128": {"TSVD_PANEL": 0, "TSVD_FP6": 1, "TSVD_FP6_V": 1, "TSVD_GEMM_CFG_V": 3, "TSVD_FP6_TALL": 0},
+          "direct 512x64": {"TSVD_PANEL": 0, "TSVD_FP6": 1, "TSVD_FP6_V": 1, "TSVD_GEMM_CFG_V": 3, "TSVD_FP6_TALL": 1}}[family]
+    for k, v in sw.items():
+        tsvd.tsvd_tuning_set(k, v)
+    print(f"case three planes {family}", flush=True)
+    j = workloads.make_inputs(M, N, K, B, 0.7, 0.02, "bf16", seed=4711)
+    ref = oracle.forward(j.U, j.S, j.V, j.X)
+    y, h = run_forward(j)
+    tsvd.tsvd_free(h)
+    err = np.abs(y - ref) / np.max(np.abs(ref))
+    per_tile = [float(err[:, c:c + 16].max()) for c in range(0, B, 16)]
+    assert max(per_tile) <= 1e-4, per_tile
+
+
 @pytest.mark.parametrize("mode", ["fp16", "fp6"])
 def test_outlier_features(tsvd, mode):
     """Activations with outlier features (1 % of the features 300 times larger, as in transformer
