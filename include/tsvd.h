@@ -129,9 +129,11 @@ tsvd_status tsvd_dense_unpack_host(const void* blob, size_t blob_bytes, int8_t* 
  *     most (measured 1e-7 .. 8e-7).
  *   2 <= B (TSVD_BF16): x enters exactly, stage V accumulates exact products in fp32, z is multiplied by a
  *     per-token power of two that keeps it in range and rounded to fp16 (11 significant bits), stage U accumulates
- *     exact products in fp32.  Long contractions with many tiles run both stages on fp4 codes and three fp6 (E2M3)
- *     planes of the activations with block scales, which resolve 2^-14.7 of the largest magnitude among 32
- *     neighbours (below the fp16 rounding of z).  Error: 2e-3 of max|y| at most (measured 2.0e-4 .. 2.4e-4).
+ *     exact products in fp32.  Long contractions with many tiles, and calls with many tokens on a small
+ *     factorisation (one launch for both stages), multiply fp4 codes by three fp6 (E2M3) planes of the
+ *     activations with block scales, which resolve 2^-14.7 of the largest magnitude among 32 neighbours; where
+ *     stage V makes the planes of z itself, z is never rounded to 16 bits.  Error: 2e-3 of max|y| at most
+ *     (measured 2.0e-4 .. 2.4e-4 with fp16 z, 2e-5 .. 4e-5 without).
  * Limits of the batched kernels (32-bit buffer offsets): N * ldx, Kp * (B rounded up to 256), Mp * Kp / 8 and
  * Kp * Np / 8 must each be below 2^30; larger calls return TSVD_EUNSUPPORTED (split the tokens).  B <= 2^24.
  * A single-token call may also be enqueued on several streams at once with separate workspaces.
