@@ -465,7 +465,7 @@ def main():
         "metric": "TSVD linear fwd: tokens/s + HBM GB/s (B=1) / MFMA util (batched) vs roofline",
         "value": p["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": p["steps"], "warmup": args.warmup,
         "ms_per_step": p["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "fp4 codes x fp6 (E2M3) planes of bf16 x / fp16 z, fp32 accumulation",
+        "dtype": "fp4 codes x fp6 (E2M3) planes of bf16 x and of fp32 z, fp32 accumulation",
         "data": "synthetic",
         "config": {"workload": f"{PRIMARY}: M={w.M} N={w.N} K={w.K} B={w.B}, ternary U,V P(0)={w.p0}, bf16 X",
                    "executed_tflops": p["executed_tflops"], "dense_equiv_tflops": p["dense_equiv_tflops"]},
