@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtsvd.so")
-SOURCES = ["tsvd_pack.cpp", "tsvd_api.hip", "tsvd_skinny.hip", "tsvd_gemv.hip", "tsvd_mid.hip", "tsvd_dense.hip", "tsvd_gemm.hip", "tsvd_transition.hip", "tsvd_conv.hip"]
+SOURCES = ["tsvd_pack.cpp", "tsvd_api.hip", "tsvd_skinny.hip", "tsvd_gemv.hip", "tsvd_mid.hip", "tsvd_dense.hip", "tsvd_gemm.hip", "tsvd_fp6.hip", "tsvd_transition.hip", "tsvd_conv.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-unused-command-line-argument"]
