@@ -151,8 +151,9 @@ tsvd_status tsvd_forward(const tsvd_handle* h, const void* x_dev, tsvd_dtype x_d
  * bias=True) added to every token, fused into the last kernel of the call.
  *
  *   x_layout : TSVD_FEATURE_MAJOR: x_dev is [N][B], ldx >= B (as tsvd_forward);
- *              TSVD_TOKEN_MAJOR:   x_dev is [B][N], ldx >= N; the call first rewrites it
- *              feature-major into the workspace (one extra pass over x), then proceeds as above.
+ *              TSVD_TOKEN_MAJOR:   x_dev is [B][N], ldx >= N.  Batched bf16 calls that run on fp4 codes x fp6
+ *              planes (many tokens on a small factorisation; long contractions with many tiles) read it in place;
+ *              other calls first rewrite it feature-major into the workspace (one extra pass over x).
  *   bias_dev : device fp32 [M], or NULL for none.
  *   y_dev    : [M][B] with row stride ldy >= B, TSVD_F32 or TSVD_BF16 (rounded to nearest even
  *              from the fp32 value after the bias).

@@ -640,7 +640,11 @@ extern "C" tsvd_status tsvd_forward_io(const tsvd_handle* h, const void* x_dev, 
         x_layout = TSVD_FEATURE_MAJOR;
         ldx = 1;
     }
-    if (x_layout == TSVD_TOKEN_MAJOR) {
+    int x_in_place = 0;
+    if (x_layout == TSVD_TOKEN_MAJOR && x_dtype == TSVD_BF16 && use_gemm(h, B, x_dtype) && !use_mid(h, B, x_dtype, tsvd_round_up(B, 8)) &&
+        tsvd_gemm_reads_token_major(h->hd.Mp, h->hd.Kp, h->hd.Np, B, h->cu_count)) {
+        x_in_place = 1;       // the kernels this call takes gather their operand lanes from [B][ldx] themselves
+    } else if (x_layout == TSVD_TOKEN_MAJOR) {
         // one pass that rewrites x as [N][B rounded up to 8] at the front of the workspace; the rows
         // of the copy are 16-byte aligned, so every kernel family takes its fast loads
         const int64_t ldt = tsvd_round_up(B, 8);
@@ -668,7 +672,7 @@ extern "C" tsvd_status tsvd_forward_io(const tsvd_handle* h, const void* x_dev, 
         ldx = ldt;
         ws = static_cast<uint8_t*>(ws) + transposed_bytes(h, B, x_dtype);
     }
-    if (use_mid(h, B, x_dtype, ldx)) return forward_mid(h, x_dev, B, ldx, y_dev, ldy, oo, ws, s);
+    if (!x_in_place && use_mid(h, B, x_dtype, ldx)) return forward_mid(h, x_dev, B, ldx, y_dev, ldy, oo, ws, s);
     if (use_gemm(h, B, x_dtype)) {
         tsvd_gemm_problem g;
         g.blob = h->blob;
@@ -677,6 +681,7 @@ extern "C" tsvd_status tsvd_forward_io(const tsvd_handle* h, const void* x_dev, 
         g.x = x_dev;
         g.B = B;
         g.ldx = ldx;
+        g.x_token_major = x_in_place;
         g.y = y_dev;
         g.ldy = ldy;
         g.bias = oo.bias;
@@ -718,7 +723,7 @@ const char* const tuning_names[] = {
     "TSVD_GEMV", "TSVD_GEMV_FUSED", "TSVD_GEMV_ONEPASS", "TSVD_GEMV_SW", "TSVD_GEMV_KWLOG2", "TSVD_SKINNY_SW", "TSVD_SKINNY_KW",
     "TSVD_MID", "TSVD_MID_MAX_B", "TSVD_MID_SW", "TSVD_MID_KWLOG2", "TSVD_MID_RESIDENT", "TSVD_GEMM_MIN_B",
     "TSVD_GEMM_CFG_V", "TSVD_GEMM_CFG_U", "TSVD_FUSEMAX", "TSVD_COLMAX_SCALAR", "TSVD_REALIGN", "TSVD_PANEL",
-    "TSVD_PANEL_WAVES", "TSVD_PANEL_FP6", "TSVD_FP6", "TSVD_FP6_V", "TSVD_FP6_TALL", "TSVD_FP6_PLANES", "TSVD_FP6_DIRECT", "TSVD_GROUPED_PAIR", "TSVD_CLOCKS",
+    "TSVD_PANEL_WAVES", "TSVD_PANEL_FP6", "TSVD_FP6", "TSVD_FP6_V", "TSVD_FP6_TALL", "TSVD_FP6_PLANES", "TSVD_FP6_DIRECT", "TSVD_TOKEN_MAJOR_COPY", "TSVD_GROUPED_PAIR", "TSVD_CLOCKS",
     "TSVD_SPIN_LIMIT", "TSVD_DENSE_U", "TSVD_EARLY_TILES"};
 constexpr int tuning_count = (int)(sizeof tuning_names / sizeof tuning_names[0]);
 int tuning_value[tuning_count];

@@ -104,6 +104,45 @@ __device__ __forceinline__ void tsvd_planes_of_32(float (&v)[32], unsigned char*
     *reinterpret_cast<uint32_t*>(rec + 4608 + lane * 4) = scales;
 }
 
+// The 32 values of one operand lane from bf16 activations stored one row per token (token-major, row pitch ld
+// elements): indices k0 + 32 (e >> 4) + (e & 15), two runs of 16 consecutive elements.  vec: rows and base are 16-byte
+// aligned (four 16-byte loads), else 32 two-byte loads.  The buffer's range check gives zero beyond the last token's
+// row; indices beyond kvalid and tokens beyond the batch are zeroed here.
+__device__ __forceinline__ void tsvd_gather_token_major(__amdgpu_buffer_rsrc_t x_rsrc, int ld2, int tok, int k0, int kvalid, bool tok_ok,
+                                                        bool vec, float (&v)[32]) {
+    const int voff = tok * ld2;
+    if (vec) {
+        u32x4 q[4];
+#pragma unroll
+        for (int h = 0; h < 4; ++h) q[h] = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, voff, (k0 + 32 * (h >> 1) + 8 * (h & 1)) * 2, 0);
+#pragma unroll
+        for (int e = 0; e < 32; ++e) {
+            const uint32_t w = q[2 * (e >> 4) + ((e >> 3) & 1)][(e & 7) >> 1];
+            v[e] = __uint_as_float((e & 1) ? (w & 0xFFFF0000u) : (w << 16));
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 32; ++e)
+            v[e] = __uint_as_float((uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(x_rsrc, voff, (k0 + 32 * (e >> 4) + (e & 15)) * 2, 0) << 16);
+    }
+#pragma unroll
+    for (int e = 0; e < 32; ++e)
+        if (!tok_ok || k0 + 32 * (e >> 4) + (e & 15) >= kvalid) v[e] = 0.f;
+}
+
+// The operand pass for token-major bf16 activations x [cols_valid tokens][ld]: no transposition through LDS, a lane's
+// values are contiguous in memory.  Same grid and records as tsvd_z_planes_kernel.
+__global__ void __launch_bounds__(512)
+tsvd_x_planes_token_major_kernel(const uint16_t* __restrict__ x, long long ld, unsigned x_bytes, int rows_valid, int cols_valid, int nblocks,
+                                 int vec, unsigned char* __restrict__ planes) {
+    const int tt = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, g = lane >> 4;
+    const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(x), 0, x_bytes, 0x00020000);
+    const int tok = blockIdx.x * 128 + tt * 16 + i;
+    float v[32];
+    tsvd_gather_token_major(x_rsrc, (int)ld * 2, tok, blockIdx.y * 128 + 64 * (g & 1) + 16 * (g >> 1), rows_valid, tok < cols_valid, vec != 0, v);
+    tsvd_planes_of_32(v, planes + ((size_t)(blockIdx.x * nblocks + blockIdx.y) * 8 + tt) * FP6_REC_BYTES, lane);
+}
+
 // grid (Bp / 128, Kp / 128), block 512 = 8 tiles x 64 lanes.  The [128 indices][128 tokens] block of Z
 // is read row by row (256 contiguous bytes each) into LDS, from where every thread picks the 32
 // values of its lane of the operand (row pitch 129 words: the picks of a wavefront, 16 tokens x 4
@@ -421,6 +460,16 @@ tsvd_panel_fp6_kernel(panel_args p) {
             for (int e = 0; e < 32; ++e)
                 raw[e] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(x_rsrc, voff, (nb * 128 + 32 * (e >> 4) + (e & 15)) * ld2, 0);
         };
+        if (p.x_token_major) {
+            // x is [tokens][ldx]: a lane's two runs of 16 indices are contiguous, nothing to transpose
+            const bool vec = !(p.ldx & 7) && !(reinterpret_cast<uintptr_t>(p.x) & 15);
+            for (int q = wave; q < njobs; q += NW) {
+                const int tok = b0 + 16 * (q & 3) + i;
+                float v[32];
+                tsvd_gather_token_major(x_rsrc, ld2, tok, (q >> 2) * 128 + 64 * (g & 1) + 16 * (g >> 1), p.N, tok < p.B, vec, v);
+                tsvd_planes_of_32(v, smem + q * FP6_REC_BYTES, lane);
+            }
+        } else {
         // (two jobs in flight: the second one's trip to memory overlaps the first one's, not its conversion)
         uint32_t raw0[32], raw1[32];
         auto convert = [&](int q, const uint32_t (&raw)[32]) {
@@ -439,6 +488,7 @@ tsvd_panel_fp6_kernel(panel_args p) {
                 convert(q + NW, raw1);
                 if (q + 3 * NW < njobs) gather(q + 3 * NW, raw1);
             }
+        }
         }
     }
     const __amdgpu_buffer_rsrc_t v_rsrc =
@@ -765,8 +815,14 @@ hipError_t tsvd_fp6_launch_direct(const gemm_args& a, long long rows_p, long lon
 }
 
 hipError_t tsvd_fp6_launch_planes(bool bf16, const uint16_t* src, long long ld, int rows_valid, int cols_valid, int nblocks_per_group,
-                                  int blocks, long long B, unsigned char* planes, hipStream_t stream) {
+                                  int blocks, long long B, unsigned char* planes, hipStream_t stream, bool token_major) {
     const dim3 grid((unsigned)((B + 127) / 128), (unsigned)blocks), block(512);
+    if (token_major) {       // (bf16 x, one row per token)
+        const int vec = !(ld & 7) && !(reinterpret_cast<uintptr_t>(src) & 15);
+        hipLaunchKernelGGL(tsvd_x_planes_token_major_kernel, grid, block, 0, stream, src, ld, (unsigned)((size_t)cols_valid * ld * 2), rows_valid,
+                           cols_valid, nblocks_per_group, vec, planes);
+        return hipGetLastError();
+    }
     if (bf16) hipLaunchKernelGGL(tsvd_z_planes_kernel<true>, grid, block, 0, stream, src, ld, rows_valid, cols_valid, nblocks_per_group, planes);
     else hipLaunchKernelGGL(tsvd_z_planes_kernel<false>, grid, block, 0, stream, src, ld, rows_valid, cols_valid, nblocks_per_group, planes);
     return hipGetLastError();

@@ -1303,6 +1303,14 @@ int tsvd_gemm_tile_shape(long long rows, long long B, long long cus, bool aligne
     return 16;
 }
 
+// Token-major x in place: the token-panel launch on fp4 x fp6, and the fp4 x fp6 stage V that needs no column maxima
+// (TSVD_TOKEN_MAJOR_COPY = 1: always copy first).
+bool tsvd_gemm_reads_token_major(long long Mp, long long Kp, long long Np, long long B, long long cus) {
+    if (tsvd_tune("TSVD_TOKEN_MAJOR_COPY", 0) != 0) return false;
+    if (tsvd_stage_mask() == 7 && tsvd_gemm_use_panel(Mp, Kp, Np, B, cus, true)) return tsvd_gemm_panel_fp6();
+    return tsvd_gemm_use_fp6_v(Mp, Kp, Np, B, cus, true) && tsvd_fp6_direct_possible(Kp, B, cus);
+}
+
 // The token-panel kernel serves 16-byte-aligned activations, K <= 1024, N <= 1024, code words of both factors
 // small enough to stay in every L2 (each workgroup reads all of them), and a token count whose
 // 64-token panels fill at least 60 % of the compute units of their last round.
@@ -1356,7 +1364,7 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     _Float16* Z = reinterpret_cast<_Float16*>(static_cast<uint8_t*>(g.ws) + part_bytes);
 
     // buffer loads address with 32-bit byte offsets
-    if ((size_t)hd.N * g.ldx * 2 >= (1ull << 31) || (size_t)hd.Kp * Bp * 2 >= (1ull << 31) ||
+    if ((size_t)(g.x_token_major ? g.B : hd.N) * g.ldx * 2 >= (1ull << 31) || (size_t)hd.Kp * Bp * 2 >= (1ull << 31) ||
         (size_t)hd.Mp * hd.Kp / 4 >= (1ull << 31) || (size_t)hd.Kp * hd.Np / 4 >= (1ull << 31))
         return hipErrorNotSupported;         // (reported as TSVD_EUNSUPPORTED; the limits are documented in tsvd.h)
     gemm_args a1;
@@ -1366,8 +1374,9 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     a1.ld = g.ldx;
     a1.kvalid = (int)hd.N;
     a1.bvalid = (int)g.B;
-    const bool fast1 = (g.ldx % 8 == 0) && ((reinterpret_cast<uintptr_t>(g.x) & 15u) == 0);
-    a1.act_bytes = (unsigned)((size_t)hd.N * g.ldx * 2);
+    // (token-major x is read in place by the fp4 x fp6 kernels only, which need no alignment: the rules see it as aligned)
+    const bool fast1 = g.x_token_major || ((g.ldx % 8 == 0) && ((reinterpret_cast<uintptr_t>(g.x) & 15u) == 0));
+    a1.act_bytes = (unsigned)((size_t)(g.x_token_major ? g.B : hd.N) * g.ldx * 2);
     a1.tile_bytes = (unsigned)((size_t)hd.Kp * hd.Np / 4);
     a1.S = reinterpret_cast<const float*>(g.blob + hd.off_S);
     a1.colpart = colpart;
@@ -1420,6 +1429,8 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
         pa.x = a1.act;
         pa.ldx = g.ldx;
         pa.x_bytes = a1.act_bytes;
+        pa.N = (int)hd.N;
+        pa.x_token_major = g.x_token_major;
         pa.S = a1.S;
         pa.bound_V = g.bound_V;
         pa.Kp = (int)hd.Kp;
@@ -1436,6 +1447,8 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
         const int ex = out_variant(g.bias, g.out_bf16, g.y_token_major);
         if (tsvd_gemm_panel_fp6()) {                   // fp4 codes x fp6 planes (TSVD_PANEL_FP6 = 0: the 16-bit panel kernel)
             return tsvd_fp6_launch_panel(pa, ex, stream);
+        } else if (g.x_token_major) {
+            return hipErrorInvalidValue;               // (tsvd_gemm_reads_token_major said no)
         } else if (env_cfg("TSVD_PANEL_WAVES", 16) == 16) {   // tuning switch: 16 is about 5 % faster on MI355X
             if (ex == 3) hipLaunchKernelGGL((tsvd_panel_kernel<16, 3>), pgrid, dim3(1024), TSVD_PANEL_LDS_EX(16), stream, pa);
             else if (ex == 2) hipLaunchKernelGGL((tsvd_panel_kernel<16, 2>), pgrid, dim3(1024), TSVD_PANEL_LDS_EX(16), stream, pa);
@@ -1456,6 +1469,7 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     // ... writing the planes of z itself where its tile allows: no fp16 z, no column maxima, no separate pass over z
     const bool direct = fp6_v && tsvd_fp6_direct_possible(hd.Kp, g.B, g.cu_count);
     const bool fuse = is_ring(cfg1) && env_cfg("TSVD_FUSEMAX", 1) != 0 && !fp6_v;
+    if (g.x_token_major && !direct) return hipErrorInvalidValue;   // (tsvd_gemm_reads_token_major said no)
 
     // Profiling switch: TSVD_STAGE_MASK selects the kernels to launch (1 column maxima,
     // 2 stage V, 4 stage U; default all).  Skipped kernels leave the workspace as it is.
@@ -1476,7 +1490,7 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
         unsigned char* xplanes = reinterpret_cast<unsigned char*>(Z) + (((size_t)hd.Kp * Bp * 2 + 255) & ~(size_t)255) +
                                  ((tsvd_gemm_fp6_bytes(hd.Kp, Bp) + 255) & ~(size_t)255);
         if ((e = tsvd_fp6_launch_planes(true, static_cast<const uint16_t*>(g.x), (long long)g.ldx, (int)hd.N, (int)g.B, (int)(hd.Np / 128),
-                                        a1.npairs, g.B, xplanes, stream)) != hipSuccess) return e;
+                                        a1.npairs, g.B, xplanes, stream, g.x_token_major != 0)) != hipSuccess) return e;
         gemm_args a4 = a1;
         a4.act = reinterpret_cast<const uint16_t*>(xplanes);
         a4.act_bytes = (unsigned)tsvd_gemm_fp6_bytes(hd.Np, Bp);

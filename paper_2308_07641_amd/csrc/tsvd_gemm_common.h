@@ -52,9 +52,10 @@ struct panel_args {
     unsigned tile_v_bytes, tile_u_bytes;
     int nkt_v, nkt_u;         // Np / 256, Kp / 256
     int npairs_v, npairs_u;   // 128-index steps of either contraction that hold anything (ceil(N / 128), ceil(K / 128))
-    const uint16_t* x;        // bf16 [N][ldx]
+    const uint16_t* x;        // bf16 [N][ldx], or [B][ldx] with x_token_major (tsvd_panel_fp6_kernel only)
     long long ldx;
     unsigned x_bytes;
+    int N, x_token_major;
     const float* S;
     float bound_V;
     int Kp, Mp, M, B;
@@ -237,10 +238,10 @@ int env_cfg(const char* name, int fallback) { return tsvd_tune(name, fallback); 
 
 // ---- tsvd_fp6.hip, called from tsvd_forward_gemm -----------------------------------------------------------------
 hipError_t tsvd_fp6_init();
-// x (bf16) or z (fp16) [rows_valid][ld] -> plane records [128-token group][nblocks_per_group][16-token tile]; `blocks`
+// x (bf16) or z (fp16) [rows_valid][ld] (token_major: bf16 x [cols_valid][ld]) -> plane records [128-token group][nblocks_per_group][16-token tile]; `blocks`
 // 128-index blocks of the source are converted
 hipError_t tsvd_fp6_launch_planes(bool bf16, const uint16_t* src, long long ld, int rows_valid, int cols_valid, int nblocks_per_group,
-                                  int blocks, long long B, unsigned char* planes, hipStream_t stream);
+                                  int blocks, long long B, unsigned char* planes, hipStream_t stream, bool token_major = false);
 // one stage on fp4 codes x fp6 planes (a.act = the planes); rows_p: padded rows of the stage's weights; ex: output variant (stage U)
 hipError_t tsvd_fp6_launch(bool stage2, const gemm_args& a, long long rows_p, int Bp, int ex, long long cus, hipStream_t stream);
 // stage V writing the planes of z itself (a.out = those planes, a.ld_out = 128-index blocks per token group), where its tile allows

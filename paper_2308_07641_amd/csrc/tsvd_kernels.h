@@ -136,8 +136,9 @@ struct tsvd_gemm_problem {
     const uint8_t* blob;            // device blob
     const tsvd_blob_header* hd;     // host copy of its header
     float bound_V;                  // |z[k][b]| <= bound_V * max_n |x[n][b]|
-    const void* x;                  // device bf16 [N][ldx]
+    const void* x;                  // device bf16 [N][ldx], or [B][ldx] with x_token_major
     long long B, ldx;
+    int x_token_major;              // only where tsvd_gemm_reads_token_major says so
     void* y;                        // device fp32 (or bf16 with out_bf16) [M][ldy]
     long long ldy;
     const float* bias;              // device [M] added per output row, or null
@@ -156,6 +157,9 @@ int tsvd_gemm_tile_shape(long long rows, long long B, long long cus, bool aligne
 bool tsvd_gemm_use_panel(long long Mp, long long Kp, long long Np, long long B, long long cus, bool aligned);
 // ... and whether that launch multiplies fp4 codes by fp6 planes (tsvd_panel_fp6_kernel) or 16-bit operands.
 bool tsvd_gemm_panel_fp6();
+// True when a batched call reads token-major bf16 activations in place (the kernels on fp4 codes x fp6 planes gather
+// their operand lanes themselves); other calls get a feature-major copy first.
+bool tsvd_gemm_reads_token_major(long long Mp, long long Kp, long long Np, long long B, long long cus);
 // Stage U through fp6 planes of Z: whether a call takes it, and the extra workspace it needs after Z.
 bool tsvd_gemm_use_fp6(long long Mp, long long Kp, long long Np, long long B, long long cus, bool aligned);
 size_t tsvd_gemm_fp6_bytes(long long Kp, long long Bp);

@@ -513,6 +513,9 @@ LAYER_CASES = [
     (515, 300, 777, 130, {"TSVD_PANEL": "0", "TSVD_FP6": "1", "TSVD_FP6_V": "0", "TSVD_FP6_TALL": "1"}),   # fp4 x fp6 stage U, 512 x 64 tiles
     (300, 200, 270, 100, {"TSVD_PANEL": "0", "TSVD_FP6": "1", "TSVD_FP6_V": "1", "TSVD_GEMM_CFG_V": "3", "TSVD_FP6_TALL": "3"}),   # both stages on planes
     (515, 300, 777, 130, {"TSVD_PANEL": "0", "TSVD_FP6": "1", "TSVD_FP6_V": "1", "TSVD_GEMM_CFG_V": "3", "TSVD_FP6_TALL": "1"}),   # ... stage V writing the planes of z itself
+    (260, 296, 300, 130, {"TSVD_PANEL": "0", "TSVD_FP6": "1", "TSVD_FP6_V": "1", "TSVD_GEMM_CFG_V": "3", "TSVD_FP6_TALL": "0"}),   # ... token-major rows 16-byte aligned
+    (300, 204, 520, 304, {"TSVD_PANEL": "1", "TSVD_PANEL_FP6": "1"}),                            # fp4 x fp6 token-panel kernel, token-major rows not 16-byte aligned
+    (300, 200, 520, 304, {"TSVD_PANEL": "1", "TSVD_PANEL_FP6": "1", "TSVD_TOKEN_MAJOR_COPY": "1"}),   # ... token-major x copied first
 ]
 
 
@@ -528,7 +531,11 @@ def test_layer_form_every_kernel_family(tsvd, M, N, K, B, env):
         h = tsvd.tsvd_pack(i.U, i.S, i.V)
         x = to_device(i)
         if layout == tsvd.TSVD_TOKEN_MAJOR:
-            x = x.t().contiguous()
+            # one row per token with a padded pitch; the padding is NaN (kernels that read token-major x in place
+            # fetch whole 16-byte runs and must drop what lies beyond N)
+            xt = torch.full((B, N + 8), float("nan"), dtype=x.dtype, device=dev)
+            xt[:, :N] = x.t()
+            x = xt[:, :N]
         b = None if bias is None else torch.from_numpy(bias).to(dev)
         y = torch.full((M, B), float("nan"), dtype=torch.bfloat16 if y_dtype == tsvd.TSVD_BF16 else torch.float32, device=dev)
         tsvd.tsvd_forward_ex(h, x, x_layout=layout, bias=b, y=y, y_dtype=y_dtype)
