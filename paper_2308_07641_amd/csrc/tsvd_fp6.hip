@@ -637,6 +637,31 @@ tsvd_panel_fp6_kernel(panel_args p) {
                 asm volatile("" : "+s"(c0));                  // (addresses are formed here, not kept in registers over the MFMAs)
                 if constexpr (EX == 3) {
                     const bool vec_ok = !(p.ldy & 3) && !(reinterpret_cast<uintptr_t>(p.y) & 15);
+                    if (vec_ok && c0 + UTN * 16 <= p.B && strip0 * 16 + 128 <= p.M && p.ldy < (1ll << 22)) {
+                        // every token and row of the unit exists: the lane's four rows of a token as one 16-byte (fp32) or
+                        // 8-byte (bf16) store at a per-lane constant offset plus a scalar
+                        const int esz = p.out_bf16 ? 2 : 4;
+                        const size_t left = ((size_t)(p.B - c0) * p.ldy - strip0 * 16) * esz;
+                        const __amdgpu_buffer_rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                            static_cast<unsigned char*>(p.y) + ((size_t)c0 * p.ldy + strip0 * 16) * esz, 0,
+                            (int)(left < 0xFFFFFFFFull ? left : 0xFFFFFFFFull), 0x00020000);
+                        const int y_voff = (i * (int)p.ldy + 4 * g) * esz;
+#pragma unroll
+                        for (int a = 0; a < TM; ++a)
+#pragma unroll
+                            for (int b = 0; b < UTN; ++b) {
+                                const float v0 = acc[a][b][0] + br[a][0], v1 = acc[a][b][1] + br[a][1], v2 = acc[a][b][2] + br[a][2],
+                                            v3 = acc[a][b][3] + br[a][3];
+                                if (p.out_bf16)
+                                    __builtin_amdgcn_raw_buffer_store_b64(u32x2{(uint32_t)tsvd_bf16_rne(v0) | ((uint32_t)tsvd_bf16_rne(v1) << 16),
+                                                                                (uint32_t)tsvd_bf16_rne(v2) | ((uint32_t)tsvd_bf16_rne(v3) << 16)},
+                                                                          y_rsrc, y_voff + a * 16 * 2, b * 16 * (int)p.ldy * 2, 0);
+                                else
+                                    __builtin_amdgcn_raw_buffer_store_b128(u32x4{__float_as_uint(v0), __float_as_uint(v1), __float_as_uint(v2), __float_as_uint(v3)},
+                                                                           y_rsrc, y_voff + a * 16 * 4, b * 16 * (int)p.ldy * 4, 0);
+                            }
+                        continue;
+                    }
 #pragma unroll
                     for (int a = 0; a < TM; ++a) {
 #pragma unroll
@@ -650,14 +675,39 @@ tsvd_panel_fp6_kernel(panel_args p) {
                     }
                 } else if constexpr (EX == 2) {
                     const bool aligned4 = !(p.ldy & 1) && !(reinterpret_cast<uintptr_t>(p.y) & 3);
+                    if (aligned4 && c0 + UTN * 16 <= p.B && p.ldy < (1ll << 21)) {
+                        // all tokens of the unit exist: the row pairs of tsvd_store_row_pair_bf16 (neighbouring lanes swap one
+                        // value, an even lane stores tokens (i, i + 1) of row r, the odd one next to it tokens (i - 1, i) of
+                        // row r + 1) as stores at a per-lane constant offset plus a scalar; rows beyond M fall outside the
+                        // buffer's range
+                        typedef float f32x2_t __attribute__((ext_vector_type(2)));
+                        typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+                        const size_t left = ((size_t)(p.M - strip0 * 16) * p.ldy - c0) * 2;
+                        const __amdgpu_buffer_rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                            static_cast<uint16_t*>(p.y) + (size_t)strip0 * 16 * p.ldy + c0, 0, (int)(left < 0xFFFFFFFFull ? left : 0xFFFFFFFFull), 0x00020000);
+                        const int odd = i & 1, ld2 = (int)p.ldy * 2, y_voff = (4 * g + odd) * ld2 + (i - odd) * 2;
 #pragma unroll
-                    for (int a = 0; a < TM; ++a) {
+                        for (int a = 0; a < TM; ++a)
 #pragma unroll
-                        for (int vp = 0; vp < 4; vp += 2) {
+                            for (int vp = 0; vp < 4; vp += 2)
 #pragma unroll
-                            for (int b = 0; b < UTN; ++b)
-                                tsvd_store_row_pair_bf16(p.y, p.ldy, (strip0 + a) * 16 + 4 * g + vp, p.M, c0 + b * 16, i, p.B,
-                                                         acc[a][b][vp] + br[a][vp], acc[a][b][vp + 1] + br[a][vp + 1], aligned4);
+                                for (int b = 0; b < UTN; ++b) {
+                                    const float v0 = acc[a][b][vp] + br[a][vp], v1 = acc[a][b][vp + 1] + br[a][vp + 1];
+                                    const float recv = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(odd ? v0 : v1), 0xB1, 0xF, 0xF, true));
+                                    const f32x2_t two = odd ? f32x2_t{recv, v1} : f32x2_t{v0, recv};
+                                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2_t)), y_rsrc,
+                                                                          y_voff + b * 32, (a * 16 + vp) * ld2, 0);
+                                }
+                    } else {
+#pragma unroll
+                        for (int a = 0; a < TM; ++a) {
+#pragma unroll
+                            for (int vp = 0; vp < 4; vp += 2) {
+#pragma unroll
+                                for (int b = 0; b < UTN; ++b)
+                                    tsvd_store_row_pair_bf16(p.y, p.ldy, (strip0 + a) * 16 + 4 * g + vp, p.M, c0 + b * 16, i, p.B,
+                                                             acc[a][b][vp] + br[a][vp], acc[a][b][vp + 1] + br[a][vp + 1], aligned4);
+                            }
                         }
                     }
                 } else if (c0 + UTN * 16 <= p.B && p.ldy < (1ll << 21)) {
