@@ -713,11 +713,13 @@ tsvd_panel_fp6_kernel(panel_args p) {
                 } else if (c0 + UTN * 16 <= p.B && p.ldy < (1ll << 21)) {
                     // All tokens of the unit exist: 32 UTN stores whose addresses are the lane's constant offset plus a
                     // scalar (no vector arithmetic per store); rows beyond M fall outside the buffer's range and are
-                    // dropped by the range check (the range is exact where it matters, in the last unit).
+                    // dropped by the range check (the range is exact where it matters, in the last unit).  (Two tokens per
+                    // lane and 8-byte stores, as in the bf16 form below: 62 - 66 against 60.6 - 62 us on 12544 tokens x 2048 rows.)
                     const size_t left = ((size_t)(p.M - strip0 * 16) * p.ldy - c0) * 4;
                     const __amdgpu_buffer_rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(
                         static_cast<float*>(p.y) + (size_t)strip0 * 16 * p.ldy + c0, 0, (int)(left < 0xFFFFFFFFull ? left : 0xFFFFFFFFull), 0x00020000);
-                    const int ld4 = (int)p.ldy * 4, y_voff = 4 * g * ld4 + i * 4;
+                    const int ld4 = (int)p.ldy * 4;
+                    const int y_voff = 4 * g * ld4 + i * 4;
 #pragma unroll
                     for (int a = 0; a < TM; ++a)
 #pragma unroll
