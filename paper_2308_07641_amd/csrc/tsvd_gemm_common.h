@@ -181,6 +181,25 @@ __device__ __forceinline__ void gemm_epilogue(const gemm_args& p, f32x4 (&acc)[T
         }
         return;
     }
+    if constexpr (STAGE2) {
+        // All tokens of the wavefront's tile exist (every tile but the last of a ragged batch): stores at a per-lane
+        // constant offset plus a scalar, no address arithmetic or masks per store; rows beyond M fall outside the
+        // buffer's range and are dropped.
+        if (col0 + TN * 16 <= p.bvalid && p.ld_out < (1ll << 21) && strip0 * 16 < p.rows_valid) {
+            const size_t left = ((size_t)(p.rows_valid - strip0 * 16) * p.ld_out - col0) * 4;
+            const __amdgpu_buffer_rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                static_cast<float*>(p.out) + (size_t)strip0 * 16 * p.ld_out + col0, 0, (int)(left < 0xFFFFFFFFull ? left : 0xFFFFFFFFull), 0x00020000);
+            const int ld4 = (int)p.ld_out * 4, y_voff = 4 * g * ld4 + i * 4;
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+#pragma unroll
+                    for (int b = 0; b < TN; ++b)
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[a][b][v] * cs[b]), y_rsrc, y_voff + b * 64, (a * 16 + v) * ld4, 0);
+            return;
+        }
+    }
 #pragma unroll
     for (int a = 0; a < TM; ++a) {
 #pragma unroll
