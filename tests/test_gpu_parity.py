@@ -766,3 +766,56 @@ def test_fp6_two_planes_switch(tsvd, M, N, K, B):
     tsvd.tsvd_free(h)
     assert not np.isnan(y).any()
     assert rel_err(y, ref) <= TOL["bf16"]
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_randomized_layer_calls_on_the_plane_kernels(tsvd, seed):
+    """Seeded random shapes, layouts, row pitches (NaN in the padding of x, untouched padding of y), bias and output
+    types on the fp4 x fp6 token-panel launch and on the fp4 x fp6 stage V that writes the planes of z (both tiles):
+    exact on integer instances, within tolerance on random ones."""
+    import torch
+    dev = "cuda:0"
+    rng = np.random.default_rng(seed)
+    for trial in range(12):
+        fam = ["panel6", "direct0", "direct1"][trial % 3]
+        M = int(rng.integers(1, 700))
+        N = int(rng.integers(1, 1024 if fam == "panel6" else 1500))
+        K = int(rng.integers(1, 1024 if fam == "panel6" else 1800))
+        B = int(rng.integers(17, 1500))
+        xl, yl, ybf, use_bias = (int(rng.integers(0, 2)) for _ in range(4))
+        padx, pady = int(rng.choice([0, 3, 8])), int(rng.choice([0, 1, 4]))
+        tsvd.tsvd_tuning_reset()
+        sw = {"panel6": {"TSVD_PANEL": 1, "TSVD_PANEL_FP6": 1},
+              "direct0": {"TSVD_PANEL": 0, "TSVD_FP6": 1, "TSVD_FP6_V": 1, "TSVD_GEMM_CFG_V": 3, "TSVD_FP6_TALL": 0},
+              "direct1": {"TSVD_PANEL": 0, "TSVD_FP6": 1, "TSVD_FP6_V": 1, "TSVD_GEMM_CFG_V": 3, "TSVD_FP6_TALL": 1}}[fam]
+        for k, v in sw.items():
+            tsvd.tsvd_tuning_set(k, v)
+        integer = trial % 2 == 0
+        i = (workloads.make_integer_inputs(M, N, K, B, 0.5, "bf16", seed=100 * seed + trial) if integer
+             else workloads.make_inputs(M, N, K, B, 0.6, 0.02, "bf16", seed=100 * seed + trial))
+        bias = None
+        if use_bias:
+            bias = rng.integers(-8, 9, size=M).astype(np.float32) if integer else rng.standard_normal(M).astype(np.float32)
+        print(f"case trial {trial} {fam} M={M} N={N} K={K} B={B} x_layout={xl} y_layout={yl} bf16={ybf} bias={use_bias} "
+              f"padx={padx} pady={pady} integer={integer}", flush=True)
+        ref = oracle.forward_layer(i.U, i.S, i.V, i.X, bias=bias)
+        h = tsvd.tsvd_pack(i.U, i.S, i.V)
+        x = to_device(i)
+        xb = torch.full((B, N + padx) if xl else (N, B + padx), float("nan"), dtype=x.dtype, device=dev)
+        xx = xb[:, :N] if xl else xb[:, :B]
+        xx.copy_(x.t() if xl else x)
+        ydt = torch.bfloat16 if ybf else torch.float32
+        yb = torch.full((B, M + pady) if yl else (M, B + pady), float("nan"), dtype=ydt, device=dev)
+        yy = yb[:, :M] if yl else yb[:, :B]
+        b = None if bias is None else torch.from_numpy(bias).to(dev)
+        tsvd.tsvd_forward_io(h, xx, x_layout=xl, bias=b, y=yy, y_dtype=tsvd.TSVD_BF16 if ybf else tsvd.TSVD_F32, y_layout=yl)
+        torch.cuda.synchronize()
+        tsvd.tsvd_free(h)
+        got = (yy.t() if yl else yy).float().cpu().numpy().astype(np.float64)
+        assert bool(torch.isnan(yb[:, (M if yl else B):]).all()), "padding of y touched"
+        assert not np.isnan(got).any()
+        want = oracle.round_to_bf16(ref) if ybf else ref
+        if integer:
+            assert np.array_equal(got, want)
+        else:
+            scale = np.max(np.abs(oracle.forward(i.U, i.S, i.V, i.X)))
+            assert np.all(np.abs(got - want) <= TOL["bf16"] * scale + (2.0 ** -7 * np.abs(ref) if ybf else 0.0))
