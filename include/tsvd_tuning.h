@@ -26,7 +26,8 @@ extern "C" {
  *   TSVD_PANEL_FP6 (0: the token-panel launch on 16-bit operands instead of fp4 codes x fp6 planes),
  *   TSVD_FP6, TSVD_FP6_V, TSVD_FP6_TALL, TSVD_FP6_PLANES (2: two instead of three fp6 planes -- about five
  *   times the error, inside the tolerance without margin; never a default), TSVD_FP6_DIRECT (0: the fp4 x fp6
- *   stage V always writes fp16 z for a separate pass to turn into planes), TSVD_TOKEN_MAJOR_COPY (1: token-major
+ *   stage V always writes fp16 z for a separate pass to turn into planes), TSVD_FP6_TAIL (0: no narrower tiles in the
+ *   last round of a launch of 512 x 64 tiles), TSVD_TOKEN_MAJOR_COPY (1: token-major
  *   activations are always copied to feature-major rows first, also for the kernels that can read them in place),
  *   TSVD_GROUPED_PAIR,
  *   TSVD_CLOCKS (1 at tsvd_pack: record phase timestamps per workgroup), TSVD_SPIN_LIMIT (bound of the

@@ -723,7 +723,7 @@ const char* const tuning_names[] = {
     "TSVD_GEMV", "TSVD_GEMV_FUSED", "TSVD_GEMV_ONEPASS", "TSVD_GEMV_SW", "TSVD_GEMV_KWLOG2", "TSVD_SKINNY_SW", "TSVD_SKINNY_KW",
     "TSVD_MID", "TSVD_MID_MAX_B", "TSVD_MID_SW", "TSVD_MID_KWLOG2", "TSVD_MID_RESIDENT", "TSVD_GEMM_MIN_B",
     "TSVD_GEMM_CFG_V", "TSVD_GEMM_CFG_U", "TSVD_FUSEMAX", "TSVD_COLMAX_SCALAR", "TSVD_REALIGN", "TSVD_PANEL",
-    "TSVD_PANEL_WAVES", "TSVD_PANEL_FP6", "TSVD_FP6", "TSVD_FP6_V", "TSVD_FP6_TALL", "TSVD_FP6_PLANES", "TSVD_FP6_DIRECT", "TSVD_TOKEN_MAJOR_COPY", "TSVD_GROUPED_PAIR", "TSVD_CLOCKS",
+    "TSVD_PANEL_WAVES", "TSVD_PANEL_FP6", "TSVD_FP6", "TSVD_FP6_V", "TSVD_FP6_TALL", "TSVD_FP6_PLANES", "TSVD_FP6_DIRECT", "TSVD_FP6_TAIL", "TSVD_TOKEN_MAJOR_COPY", "TSVD_GROUPED_PAIR", "TSVD_CLOCKS",
     "TSVD_SPIN_LIMIT", "TSVD_DENSE_U", "TSVD_EARLY_TILES"};
 constexpr int tuning_count = (int)(sizeof tuning_names / sizeof tuning_names[0]);
 int tuning_value[tuning_count];

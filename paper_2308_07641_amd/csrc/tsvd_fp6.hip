@@ -197,22 +197,21 @@ __device__ __forceinline__ f32x4 mfma_fp6(const u32x4& a, const u32x4& lo, const
 // registers, one block ahead.
 // NPL: planes multiplied, 3 or (switch TSVD_FP6_PLANES=2, never by default) the first two: two thirds of the MFMAs
 // for activations exact to 2^-9.8 instead of 2^-14.7 of a block's largest magnitude.
-template <bool STAGE2, int EX, int WM = 2, int WN = 2, int TM = 8, int NPL = 3, bool DIRECT = false>
-__global__ void __launch_bounds__(256, 2)
-tsvd_gemm_fp6_kernel(gemm_args p) {
+// The work of one workgroup: the tile of WM TM 16 rows from strip tile_strip0 on, tokens b0 .. b0 + 16 TN WN
+// (TN = 4 token blocks per wavefront everywhere but in the last, partly filled round of tsvd_gemm_fp6_tail_kernel).
+template <bool STAGE2, int EX, int WM, int WN, int TM, int NPL, bool DIRECT, int TN = 4>
+__device__ __forceinline__ void fp6_tile(const gemm_args& p, const int b0, const int tile_strip0, unsigned char* smem) {
     static_assert(WM * WN == 4, "four wavefronts");
     static_assert(!DIRECT || (!STAGE2 && TM == 8 && NPL == 3 && EX == 0), "planes straight from stage V: a wavefront owns whole 128-index blocks");
-    constexpr int TN = 4, BT = WN * 64;
+    constexpr int BT = WN * TN * 16;
     constexpr int BLK_BYTES = BT / 16 * FP6_REC_BYTES;      // one 128-index block of this workgroup's tokens
-    constexpr int PIECES = BLK_BYTES / 1024;                // 38 or 19 pieces of 1 KiB
-    static_assert(BLK_BYTES % 1024 == 0, "whole pieces");
-    extern __shared__ __align__(16) unsigned char smem[];   // 2 x BLK_BYTES, then BT column factors
-    float* cs_lds = reinterpret_cast<float*>(smem + 2 * BLK_BYTES);
+    constexpr int PIECES = (BLK_BYTES + 1023) / 1024;       // 38 or 19 pieces of 1 KiB (narrow tiles: the last one partly filled)
+    constexpr bool PARTIAL = BLK_BYTES % 1024 != 0;
+    float* cs_lds = reinterpret_cast<float*>(smem + 2 * BLK_BYTES);   // (LDS: 2 x BLK_BYTES, then BT column factors)
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave / WN, wn = wave - wm * WN;
     const int i = lane & 15, g = lane >> 4;
-    const int b0 = blockIdx.x * BT;
-    const int strip0 = (blockIdx.y * WM + wm) * TM;
+    const int strip0 = tile_strip0 + wm * TM;
     const int nblocks = p.nkt * 2;                    // blocks per token group in the planes' layout
     const int nrun = p.npairs, lastb = nrun - 1;      // blocks that hold anything
 
@@ -235,7 +234,8 @@ tsvd_gemm_fp6_kernel(gemm_args p) {
 #pragma unroll
         for (int c = 0; c < (PIECES + 3) / 4; ++c) {
             const int piece = min(c * 4 + wave, PIECES - 1);
-            buf_load128_to_lds(act_rsrc, lds_base + buf * BLK_BYTES + piece * 1024, lane * 16, rec0 + piece * 1024);
+            if (!PARTIAL || piece * 1024 + lane * 16 < BLK_BYTES)      // (lanes beyond the block would write into the other buffer)
+                buf_load128_to_lds(act_rsrc, lds_base + buf * BLK_BYTES + piece * 1024, lane * 16, rec0 + piece * 1024);
         }
     };
     // DIRECT: row r = 4 gg + vv of result block a is loaded from row 64 (gg & 1) + 16 (gg >> 1) + 32 (a >> 2) + 4 (a & 3) + vv
@@ -346,6 +346,32 @@ tsvd_gemm_fp6_kernel(gemm_args p) {
         }
     } else {
         gemm_epilogue<TM, TN, STAGE2, EX>(p, acc, strip0, b0, wn * TN * 16, cs_lds, i, g);
+    }
+}
+
+template <bool STAGE2, int EX, int WM = 2, int WN = 2, int TM = 8, int NPL = 3, bool DIRECT = false>
+__global__ void __launch_bounds__(256, 2)
+tsvd_gemm_fp6_kernel(gemm_args p) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    fp6_tile<STAGE2, EX, WM, WN, TM, NPL, DIRECT>(p, blockIdx.x * WN * 64, blockIdx.y * WM * TM, smem);
+}
+
+// A stage in 512 x 64 tiles with a tail of narrower ones.  All tiles of a launch cost the same and two workgroups share a
+// compute unit, so T tiles take ceil(T / (2 CUs)) rounds: stage U of a 36864 x 18432 factor at 2048 tokens is 4.5 rounds of work in
+// the time of 5, its stage V 2.25 in the time of 3.  Here the rows of tiles that fill whole rounds (the first big_tiles) are
+// 512 x 64; the rest is cut along the tokens into 512 x 16 TNT tiles (TNT = 2 or 1), two or four times as many workgroups that
+// fill the last round.  (Cut along the rows instead, 256 x 64, a tail tile took 0.85 of a whole one: it streams the same planes
+// for half the MFMAs.)  One-dimensional grid: big_tiles x ceil(B / 64) workgroups, then the tail's, token tile fastest.
+template <bool STAGE2, int EX, bool DIRECT, int TNT>
+__global__ void __launch_bounds__(256, 2)
+tsvd_gemm_fp6_tail_kernel(gemm_args p) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int cols = (p.bvalid + 63) / 64, nbig = p.big_tiles * cols, id = blockIdx.x;
+    if (id < nbig) {
+        fp6_tile<STAGE2, EX, 4, 1, 8, 3, DIRECT, 4>(p, (id % cols) * 64, (id / cols) * 32, smem);
+    } else {
+        const int tcols = (p.bvalid + 16 * TNT - 1) / (16 * TNT), t = id - nbig;
+        fp6_tile<STAGE2, EX, 4, 1, 8, 3, DIRECT, TNT>(p, (t % tcols) * 16 * TNT, (p.big_tiles + t / tcols) * 32, smem);
     }
 }
 
@@ -840,6 +866,39 @@ static int fp6_tile(long long rows_p, long long bvalid, long long cus) {
     if (rows_p % 512 == 0 && tall != 0) return 1;
     return 0;
 }
+// A stage in 512 x 64 tiles whose last round of workgroups would be at most half full: rows of tiles that fill whole rounds,
+// then a tail cut along the tokens (tsvd_gemm_fp6_tail_kernel; TSVD_FP6_TAIL = 0: never).  Returns false when the plain launch is
+// as good; else the rows of whole tiles, the rows of tail tiles and the token blocks per wavefront of the tail (2 or 1).
+static bool fp6_tail_shape(const gemm_args& a, long long cus, int* big, int* rest, int* tnt) {
+    if (env_cfg("TSVD_FP6_TAIL", 1) == 0) return false;
+    const long long C = (a.bvalid + 63) / 64, slots = 2 * cus;
+    if (C <= 0 || slots % C) return false;
+    const long long rows_per_round = slots / C, R = (a.rows_need + 511) / 512;
+    const long long b = R / rows_per_round * rows_per_round, r = R - b;
+    if (b == 0 || r == 0 || 2 * r * C > slots) return false;
+    *big = (int)b;
+    *rest = (int)r;
+    *tnt = 4 * r * C <= slots ? 1 : 2;
+    return true;
+}
+template <bool STAGE2, int EX, bool DIRECT>
+static hipError_t launch_fp6_tail(const gemm_args& a, int big, int rest, int tnt, hipStream_t stream) {
+    constexpr int lds = 2 * (4 * FP6_REC_BYTES) + 512;
+    gemm_args t = a;
+    t.big_tiles = big;
+    const long long C = (a.bvalid + 63) / 64, TC = (a.bvalid + 16 * tnt - 1) / (16 * tnt);
+    const dim3 grid((unsigned)(big * C + rest * TC)), block(256);
+    if (tnt == 1) hipLaunchKernelGGL((tsvd_gemm_fp6_tail_kernel<STAGE2, EX, DIRECT, 1>), grid, block, lds, stream, t);
+    else hipLaunchKernelGGL((tsvd_gemm_fp6_tail_kernel<STAGE2, EX, DIRECT, 2>), grid, block, lds, stream, t);
+    return hipGetLastError();
+}
+template <bool STAGE2, int EX, bool DIRECT>
+static hipError_t init_fp6_tail() {
+    constexpr int lds = 2 * (4 * FP6_REC_BYTES) + 512;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_tail_kernel<STAGE2, EX, DIRECT, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_gemm_fp6_tail_kernel<STAGE2, EX, DIRECT, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+}
 hipError_t tsvd_fp6_launch(bool stage2, const gemm_args& a, long long rows_p, int Bp, int ex, long long cus, hipStream_t stream) {
     if (env_cfg("TSVD_FP6_PLANES", 3) == 2) {            // accuracy / speed switch (512 x 64 and 256 x 64 tiles only)
         if (rows_p % 512 == 0 && (rows_p / 256) * ((a.bvalid + 127) / 128) >= cus) return launch_fp6<4, 1, 8, 2>(stage2, a, rows_p, Bp, ex, stream);
@@ -848,7 +907,16 @@ hipError_t tsvd_fp6_launch(bool stage2, const gemm_args& a, long long rows_p, in
     switch (fp6_tile(rows_p, a.bvalid, cus)) {
         case 3: return launch_fp6<4, 1, 2>(stage2, a, rows_p, Bp, ex, stream);
         case 2: return launch_fp6<4, 1, 4>(stage2, a, rows_p, Bp, ex, stream);
-        case 1: return launch_fp6<4, 1, 8>(stage2, a, rows_p, Bp, ex, stream);
+        case 1: {
+            int big, rest, tnt;
+            if (stage2 && rows_p % 512 == 0 && fp6_tail_shape(a, cus, &big, &rest, &tnt)) {
+                if (ex == 2) return launch_fp6_tail<true, 2, false>(a, big, rest, tnt, stream);
+                if (ex == 1) return launch_fp6_tail<true, 1, false>(a, big, rest, tnt, stream);
+                if (ex == 3) return launch_fp6_tail<true, 3, false>(a, big, rest, tnt, stream);
+                return launch_fp6_tail<true, 0, false>(a, big, rest, tnt, stream);
+            }
+            return launch_fp6<4, 1, 8>(stage2, a, rows_p, Bp, ex, stream);
+        }
         default: return launch_fp6<2, 2, 8>(stage2, a, rows_p, Bp, ex, stream);
     }
 }
@@ -861,6 +929,8 @@ hipError_t tsvd_fp6_launch_direct(const gemm_args& a, long long rows_p, long lon
     const int wn = tall ? 1 : 2, rows_tile = tall ? 512 : 256, lds = 2 * (wn * 4 * FP6_REC_BYTES) + 512;
     if (rows_p % rows_tile) return hipErrorInvalidValue;
     const dim3 grid((a.bvalid + wn * 64 - 1) / (wn * 64), (unsigned)((a.rows_need + rows_tile - 1) / rows_tile)), block(256);
+    int big, rest, tnt;
+    if (tall && fp6_tail_shape(a, cus, &big, &rest, &tnt)) return launch_fp6_tail<false, 0, true>(a, big, rest, tnt, stream);
     if (tall) hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<false, 0, 4, 1, 8, 3, true>), grid, block, lds, stream, a);
     else hipLaunchKernelGGL((tsvd_gemm_fp6_kernel<false, 0, 2, 2, 8, 3, true>), grid, block, lds, stream, a);
     return hipGetLastError();
@@ -897,6 +967,11 @@ hipError_t tsvd_fp6_init() {
     if ((e = init_fp6<4, 1, 2>()) != hipSuccess) return e;
     if ((e = init_fp6<4, 1, 8, 2>()) != hipSuccess) return e;
     if ((e = init_fp6<4, 1, 4, 2>()) != hipSuccess) return e;
+    if ((e = init_fp6_tail<true, 0, false>()) != hipSuccess) return e;
+    if ((e = init_fp6_tail<true, 1, false>()) != hipSuccess) return e;
+    if ((e = init_fp6_tail<true, 2, false>()) != hipSuccess) return e;
+    if ((e = init_fp6_tail<true, 3, false>()) != hipSuccess) return e;
+    if ((e = init_fp6_tail<false, 0, true>()) != hipSuccess) return e;
     if ((e = init_fp6_direct<2, 2>()) != hipSuccess) return e;
     if ((e = init_fp6_direct<4, 1>()) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsvd_panel_fp6_kernel<0>), hipFuncAttributeMaxDynamicSharedMemorySize,

@@ -42,6 +42,7 @@ struct gemm_args {
     int out_bf16;             // stage 2 (EX kernels): output type
     int out_token_major;      // stage 2 (EX = 3): out is [tokens][ld_out] (one row per token) instead of [M][ld_out]
     int rows_valid;           // stage 2: M
+    int big_tiles;            // tsvd_gemm_fp6_tail_kernel: rows of 512 x 64 tiles before the narrower ones
     int rows_need;            // rows of the stage that have to be computed (stage 1: the rank positions stage 2 reads; stage 2: M)
     long long* clocks;        // tuning aid: phase timestamps per workgroup (stage 1: 0..7, stage 2: 8..15), or null
 };

@@ -819,3 +819,25 @@ def test_randomized_layer_calls_on_the_plane_kernels(tsvd, seed):
         else:
             scale = np.max(np.abs(oracle.forward(i.U, i.S, i.V, i.X)))
             assert np.all(np.abs(got - want) <= TOL["bf16"] * scale + (2.0 ** -7 * np.abs(ref) if ybf else 0.0))
+
+@pytest.mark.parametrize("M,K", [(17 * 512 + 300, 17 * 512 + 512), (22 * 512, 21 * 512 + 130)])
+def test_fp6_tail_tiles(tsvd, M, K):
+    """Launches of more than one round of 512 x 64 tiles whose last round would be at most half full end in tiles cut along
+    the tokens (stage U, and the stage V that writes the planes of z): a quarter or an eighth of a round left over here,
+    ragged rows and tokens; sampled columns against the oracle, and the same bits as the plain launch."""
+    import torch
+    N, B = 200, 2048 - 37
+    for k, v in {"TSVD_PANEL": 0, "TSVD_FP6": 1, "TSVD_FP6_V": 1, "TSVD_GEMM_CFG_V": 3, "TSVD_FP6_TALL": 1}.items():
+        tsvd.tsvd_tuning_set(k, v)
+    print(f"case fp6 tail M={M} K={K}", flush=True)
+    j = workloads.make_inputs(M, N, K, B, 0.6, 0.02, "bf16", seed=M + K)
+    cols = sorted(set([0, 15, 16, 31, 32, 63, 64, B - 1, B - 16, B - 17, B - 33, B // 2] + list(np.random.default_rng(3).integers(0, B, 30))))
+    ref = oracle.forward_columns(j.U, j.S, j.V, j.X, cols)
+    y1, h = run_forward(j)
+    tsvd.tsvd_free(h)
+    assert not np.isnan(y1).any()
+    assert rel_err(y1[:, cols], ref) <= 1e-4            # (three planes, z never rounded to 16 bits)
+    tsvd.tsvd_tuning_set("TSVD_FP6_TAIL", 0)
+    y0, h = run_forward(j)
+    tsvd.tsvd_free(h)
+    assert np.array_equal(y0, y1)
