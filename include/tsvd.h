@@ -122,8 +122,8 @@ tsvd_status tsvd_dense_unpack_host(const void* blob, size_t blob_bytes, int8_t* 
  * x, y and workspace are owned by the caller and must not alias.  Inputs must be finite.
  *
  * Arithmetic (accumulation is fp32 or exact everywhere; the oracle-relative bounds are those the tests check):
- *   B = 1 (and TSVD_F32 activations with B >= 2, which are handled one token at a time, each pass streaming the
- *     weights again): x is converted to sign-magnitude fixed point with 30 bits below the largest |x| (entries below
+ *   B = 1 (and TSVD_F32 activations with 2 <= B <= 16, which are handled one token at a time, each pass streaming
+ *     the weights again): x is converted to sign-magnitude fixed point with 30 bits below the largest |x| (entries below
  *     2^-31 of it become 0), every sum of V(.) and U(.) is then an exact integer; z = S * (V x) is rounded to fp32
  *     and converted the same way relative to the bound max_k |S_k| nnz(V[k,:]) * max|x|.  Error: 1e-5 of max|y| at
  *     most (measured 1e-7 .. 8e-7).
@@ -134,6 +134,9 @@ tsvd_status tsvd_dense_unpack_host(const void* blob, size_t blob_bytes, int8_t* 
  *     activations with block scales, which resolve 2^-14.7 of the largest magnitude among 32 neighbours; where
  *     stage V makes the planes of z itself, z is never rounded to 16 bits.  Error: 2e-3 of max|y| at most
  *     (measured 2.0e-4 .. 2.4e-4 with fp16 z, 2e-5 .. 4e-5 without).
+ *   17 <= B (TSVD_F32): fp4 codes times SIX fp6 planes of the activations of either stage (three, and three more for
+ *     what those leave: below the last bit of an fp32 value of a block's largest magnitude), fp32 accumulation; z goes
+ *     from the accumulators straight into its planes.  Error: 1e-5 of max|y| at most (measured 2e-7 .. 1.4e-6).
  * Limits of the batched kernels (32-bit buffer offsets): N * ldx, Kp * (B rounded up to 256), Mp * Kp / 8 and
  * Kp * Np / 8 must each be below 2^30; larger calls return TSVD_EUNSUPPORTED (split the tokens).  B <= 2^24.
  * A single-token call may also be enqueued on several streams at once with separate workspaces.

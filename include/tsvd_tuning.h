@@ -23,6 +23,7 @@ extern "C" {
  *   TSVD_MID (0: few-token kernel off), TSVD_MID_MAX_B, TSVD_MID_SW, TSVD_MID_KWLOG2, TSVD_MID_RESIDENT,
  *   TSVD_GEMM_MIN_B, TSVD_GEMM_CFG_V / TSVD_GEMM_CFG_U (tile shape of a batched stage: 0..3 large tiles,
  *   14..17 ring kernel), TSVD_FUSEMAX, TSVD_COLMAX_SCALAR, TSVD_REALIGN, TSVD_PANEL, TSVD_PANEL_WAVES,
+ *   TSVD_GEMM_MIN_B_F32 (fewest tokens of fp32 activations that take the batched kernels, default 17),
  *   TSVD_PANEL_FP6 (0: the token-panel launch on 16-bit operands instead of fp4 codes x fp6 planes),
  *   TSVD_FP6, TSVD_FP6_V, TSVD_FP6_TALL, TSVD_FP6_PLANES (2: two instead of three fp6 planes -- about five
  *   times the error, inside the tolerance without margin; never a default), TSVD_FP6_DIRECT (0: the fp4 x fp6

@@ -414,13 +414,16 @@ tsvd_status forward_mid(const tsvd_handle* h, const void* x, int64_t B, int64_t 
 }
 
 bool use_gemm(const tsvd_handle*, int64_t B, tsvd_dtype x_dtype) {
-    const int min_b = env_int("TSVD_GEMM_MIN_B", 17);
-    return x_dtype == TSVD_BF16 && B >= min_b;
+    // (fp32 activations: fewer tokens are handled one at a time by the single-token kernels, each pass streaming the weights)
+    const int min_b = x_dtype == TSVD_BF16 ? env_int("TSVD_GEMM_MIN_B", 17) : env_int("TSVD_GEMM_MIN_B_F32", 17);
+    return B >= min_b;
 }
 
-size_t gemm_workspace(const tsvd_handle* h, int64_t B) {
-    // partial column maxima [PARTS][Bp] fp32, then Z as fp16 [Kp][Bp]
+size_t gemm_workspace(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype) {
     const int64_t Bp = tsvd_round_up(B, 256);
+    if (x_dtype == TSVD_F32)      // two sets of planes of x, two of z (blocks that hold anything only)
+        return round256(tsvd_gemm_fp6_bytes(256 * ((h->hd.N + 127) / 128), Bp)) + round256(tsvd_gemm_fp6_bytes(256 * ((h->hd.K + 127) / 128), Bp));
+    // partial column maxima [PARTS][Bp] fp32, then Z as fp16 [Kp][Bp]
     size_t bytes = round256((size_t)(TSVD_COLMAX_PARTS + 1) * Bp * 4) + round256((size_t)h->hd.Kp * (size_t)Bp * 2);
     // (the rule is asked as for aligned rows: a caller with unaligned rows then reserves a little too much)
     if (tsvd_gemm_use_fp6(h->hd.Mp, h->hd.Kp, h->hd.Np, B, h->cu_count, true))      // planes of Z, and of X for stage V
@@ -562,7 +565,7 @@ namespace {
 size_t base_workspace(const tsvd_handle* h, int64_t B, tsvd_dtype x_dtype) {
     // (the few-token path is chosen per call, by the row stride too: cover every candidate)
     const size_t few = round256(std::max(skinny_workspace(h), mid_workspace(h)));
-    if (use_gemm(h, B, x_dtype)) return std::max(gemm_workspace(h, B), B <= 64 ? few : (size_t)0);
+    if (use_gemm(h, B, x_dtype)) return std::max(gemm_workspace(h, B, x_dtype), B <= 64 ? few : (size_t)0);
     return few;
 }
 // feature-major copy of token-major activations: [N][B rounded up to 8] elements
@@ -659,7 +662,7 @@ extern "C" tsvd_status tsvd_forward_io(const tsvd_handle* h, const void* x_dev, 
         x_dev = ws;
         ldx = ldt;
         ws = static_cast<uint8_t*>(ws) + transposed_bytes(h, B, x_dtype);
-    } else if (use_gemm(h, B, x_dtype) && (ldx % 8 != 0 || (reinterpret_cast<uintptr_t>(x_dev) & 15u)) && env_int("TSVD_REALIGN", 1) != 0 &&
+    } else if (x_dtype == TSVD_BF16 && use_gemm(h, B, x_dtype) && (ldx % 8 != 0 || (reinterpret_cast<uintptr_t>(x_dev) & 15u)) && env_int("TSVD_REALIGN", 1) != 0 &&
              h->hd.N <= 65535) {
         // more than 16 tokens in rows that are not 16-byte aligned: one pass that copies them to aligned rows costs
         // less than the element-wise gathers of the kernels that take such rows (stage V of a 4096 x 8192
@@ -682,6 +685,7 @@ extern "C" tsvd_status tsvd_forward_io(const tsvd_handle* h, const void* x_dev, 
         g.B = B;
         g.ldx = ldx;
         g.x_token_major = x_in_place;
+        g.x_f32 = x_dtype == TSVD_F32;
         g.y = y_dev;
         g.ldy = ldy;
         g.bias = oo.bias;
@@ -721,7 +725,7 @@ extern "C" tsvd_status tsvd_forward_noalloc(const tsvd_handle* h, const void* x_
 namespace {
 const char* const tuning_names[] = {
     "TSVD_GEMV", "TSVD_GEMV_FUSED", "TSVD_GEMV_ONEPASS", "TSVD_GEMV_SW", "TSVD_GEMV_KWLOG2", "TSVD_SKINNY_SW", "TSVD_SKINNY_KW",
-    "TSVD_MID", "TSVD_MID_MAX_B", "TSVD_MID_SW", "TSVD_MID_KWLOG2", "TSVD_MID_RESIDENT", "TSVD_GEMM_MIN_B",
+    "TSVD_MID", "TSVD_MID_MAX_B", "TSVD_MID_SW", "TSVD_MID_KWLOG2", "TSVD_MID_RESIDENT", "TSVD_GEMM_MIN_B", "TSVD_GEMM_MIN_B_F32",
     "TSVD_GEMM_CFG_V", "TSVD_GEMM_CFG_U", "TSVD_FUSEMAX", "TSVD_COLMAX_SCALAR", "TSVD_REALIGN", "TSVD_PANEL",
     "TSVD_PANEL_WAVES", "TSVD_PANEL_FP6", "TSVD_FP6", "TSVD_FP6_V", "TSVD_FP6_TALL", "TSVD_FP6_PLANES", "TSVD_FP6_DIRECT", "TSVD_FP6_TAIL", "TSVD_TOKEN_MAJOR_COPY", "TSVD_GROUPED_PAIR", "TSVD_CLOCKS",
     "TSVD_SPIN_LIMIT", "TSVD_DENSE_U", "TSVD_EARLY_TILES"};

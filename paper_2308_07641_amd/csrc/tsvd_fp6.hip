@@ -51,8 +51,9 @@ typedef int i32x8 __attribute__((ext_vector_type(8)));
 
 // One lane's 32 values -> three E2M3 planes (the value, the residual of its rounding, the residual of that), each
 // with its own power-of-two scale.  put(plane, first 16 bytes, last 8 bytes) receives the lane's 24 bytes of each
-// plane; the return value holds the three scale bytes.  (v is used up.)
-template <typename Put>
+// plane; the return value holds the three scale bytes.  KEEP: v is left holding what the three planes do not resolve
+// (for a second set of planes); else it is used up.
+template <bool KEEP = false, typename Put>
 __device__ __forceinline__ uint32_t tsvd_planes_of_32(float (&v)[32], Put put) {
     typedef float f32x16 __attribute__((ext_vector_type(16)));
     typedef float f32x32 __attribute__((ext_vector_type(32)));
@@ -85,7 +86,7 @@ __device__ __forceinline__ uint32_t tsvd_planes_of_32(float (&v)[32], Put put) {
         // written out with results that may not overlap any operand.
         u32x6 w;
         asm("v_cvt_scalef32_2xpk16_fp6_f32 %0, %1, %2, %3" : "=&v"(w) : "v"(s0), "v"(s1), "v"(unit));
-        if (pl < 2) {
+        if (pl < 2 || KEEP) {
             f32x32 back;
             asm("v_cvt_scalef32_pk32_f32_fp6 %0, %1, %2" : "=&v"(back) : "v"(w), "v"(unit));
 #pragma unroll
@@ -96,12 +97,19 @@ __device__ __forceinline__ uint32_t tsvd_planes_of_32(float (&v)[32], Put put) {
     return scales;
 }
 // ... written to the lane's places in the record at `rec`
+template <bool KEEP = false>
 __device__ __forceinline__ void tsvd_planes_of_32(float (&v)[32], unsigned char* rec, int lane) {
-    const uint32_t scales = tsvd_planes_of_32(v, [&](int pl, u32x4 lo, u32x2 hi) {
+    const uint32_t scales = tsvd_planes_of_32<KEEP>(v, [&](int pl, u32x4 lo, u32x2 hi) {
         *reinterpret_cast<u32x4*>(rec + pl * 1024 + lane * 16) = lo;
         *reinterpret_cast<u32x2*>(rec + 3072 + pl * 512 + lane * 8) = hi;
     });
     *reinterpret_cast<uint32_t*>(rec + 4608 + lane * 4) = scales;
+}
+// Six planes for fp32 values: a record of three, and a second record for what those leave (2^-14.7 of a block's largest
+// magnitude times 2^-14.7 again: below the last bit of an fp32 value of that magnitude).
+__device__ __forceinline__ void tsvd_planes_of_32_twice(float (&v)[32], unsigned char* rec, unsigned char* rec2, int lane) {
+    tsvd_planes_of_32<true>(v, rec, lane);
+    tsvd_planes_of_32<false>(v, rec2, lane);
 }
 
 // The 32 values of one operand lane from bf16 activations stored one row per token (token-major, row pitch ld
@@ -128,6 +136,25 @@ __device__ __forceinline__ void tsvd_gather_token_major(__amdgpu_buffer_rsrc_t x
 #pragma unroll
     for (int e = 0; e < 32; ++e)
         if (!tok_ok || k0 + 32 * (e >> 4) + (e & 15) >= kvalid) v[e] = 0.f;
+}
+
+// The operand pass for fp32 activations x [rows_valid][ld] (feature-major, any row pitch): two records per (16-token
+// tile, 128-index block), the second `set_offset` blocks behind the first in a layout of `nblocks` blocks per token
+// group.  A lane gathers its 32 values itself (rows beyond the matrix and tokens beyond the batch read as zero).
+__global__ void __launch_bounds__(512)
+tsvd_x_planes_f32_kernel(const float* __restrict__ x, long long ld, int rows_valid, int cols_valid, int nblocks, int set_offset,
+                         unsigned char* __restrict__ planes) {
+    const int tt = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, g = lane >> 4;
+    const int tok = blockIdx.x * 128 + tt * 16 + i, k0 = blockIdx.y * 128 + 64 * (g & 1) + 16 * (g >> 1);
+    float v[32];
+#pragma unroll
+    for (int e = 0; e < 32; ++e) {
+        const int k = k0 + 32 * (e >> 4) + (e & 15);
+        const float q = x[(size_t)min(k, rows_valid - 1) * ld + min(tok, cols_valid - 1)];
+        v[e] = k < rows_valid && tok < cols_valid ? q : 0.f;
+    }
+    unsigned char* rec = planes + ((size_t)(blockIdx.x * nblocks + blockIdx.y) * 8 + tt) * FP6_REC_BYTES;
+    tsvd_planes_of_32_twice(v, rec, rec + (size_t)set_offset * 8 * FP6_REC_BYTES, lane);
 }
 
 // The operand pass for token-major bf16 activations x [cols_valid tokens][ld]: no transposition through LDS, a lane's
@@ -212,7 +239,7 @@ __device__ __forceinline__ void fp6_tile(const gemm_args& p, const int b0, const
     const int wm = wave / WN, wn = wave - wm * WN;
     const int i = lane & 15, g = lane >> 4;
     const int strip0 = tile_strip0 + wm * TM;
-    const int nblocks = p.nkt * 2;                    // blocks per token group in the planes' layout
+    const int nblocks = p.plane_blocks ? p.plane_blocks : p.nkt * 2;   // blocks per token group in the planes' layout
     const int nrun = p.npairs, lastb = nrun - 1;      // blocks that hold anything
 
     const i32x4 act_rsrc = raw_rsrc(p.act, p.act_bytes);
@@ -244,6 +271,8 @@ __device__ __forceinline__ void fp6_tile(const gemm_args& p, const int b0, const
     const int rr = lane & 15, gg = rr >> 2, vv = rr & 3;
     const int w_voff = DIRECT ? (4 * (gg & 1) + (gg >> 1)) * p.nkt * 1024 + (g * 16 + vv) * 16 : lane * 16;
     auto load_w = [&](int blk, u32x2 (&w)[TM]) {
+        // (fp32 activations come as two sets of planes, the second set's blocks behind the first's: the same code words again)
+        if (p.code_blocks && blk >= p.code_blocks) blk -= p.code_blocks;
         const int soff = (strip0 * p.nkt + (blk >> 1)) * 1024 + (blk & 1) * 8;
 #pragma unroll
         for (int a = 0; a < TM; ++a)
@@ -341,8 +370,10 @@ __device__ __forceinline__ void fp6_tile(const gemm_args& p, const int b0, const
             float v[32];
 #pragma unroll
             for (int e = 0; e < 32; ++e) v[e] = acc[e >> 2][b][e & 3];
-            tsvd_planes_of_32(v, static_cast<unsigned char*>(p.out) +
-                                     ((size_t)(((tok + 16 * b) >> 7) * (int)p.ld_out + kb) * 8 + (((tok + 16 * b) & 127) >> 4)) * FP6_REC_BYTES, lane);   // (ld_out: blocks per token group)
+            unsigned char* rec = static_cast<unsigned char*>(p.out) +
+                                 ((size_t)(((tok + 16 * b) >> 7) * (int)p.ld_out + kb) * 8 + (((tok + 16 * b) & 127) >> 4)) * FP6_REC_BYTES;   // (ld_out: blocks per token group)
+            if (!p.two_sets) tsvd_planes_of_32(v, rec, lane);
+            else if (kb < p.two_sets) tsvd_planes_of_32_twice(v, rec, rec + (size_t)p.two_sets * 8 * FP6_REC_BYTES, lane);   // (fp32 path: six planes)
         }
     } else {
         gemm_epilogue<TM, TN, STAGE2, EX>(p, acc, strip0, b0, wn * TN * 16, cs_lds, i, g);
@@ -947,6 +978,13 @@ hipError_t tsvd_fp6_launch_planes(bool bf16, const uint16_t* src, long long ld, 
     }
     if (bf16) hipLaunchKernelGGL(tsvd_z_planes_kernel<true>, grid, block, 0, stream, src, ld, rows_valid, cols_valid, nblocks_per_group, planes);
     else hipLaunchKernelGGL(tsvd_z_planes_kernel<false>, grid, block, 0, stream, src, ld, rows_valid, cols_valid, nblocks_per_group, planes);
+    return hipGetLastError();
+}
+
+hipError_t tsvd_fp6_launch_planes_f32(const float* x, long long ld, int rows_valid, int cols_valid, int blocks, unsigned char* planes,
+                                      hipStream_t stream) {
+    hipLaunchKernelGGL(tsvd_x_planes_f32_kernel, dim3((unsigned)((cols_valid + 127) / 128), (unsigned)blocks), dim3(512), 0, stream, x, ld,
+                       rows_valid, cols_valid, 2 * blocks, blocks, planes);
     return hipGetLastError();
 }
 

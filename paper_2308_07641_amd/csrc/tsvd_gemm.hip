@@ -1364,7 +1364,7 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     _Float16* Z = reinterpret_cast<_Float16*>(static_cast<uint8_t*>(g.ws) + part_bytes);
 
     // buffer loads address with 32-bit byte offsets
-    if ((size_t)(g.x_token_major ? g.B : hd.N) * g.ldx * 2 >= (1ull << 31) || (size_t)hd.Kp * Bp * 2 >= (1ull << 31) ||
+    if ((!g.x_f32 && (size_t)(g.x_token_major ? g.B : hd.N) * g.ldx * 2 >= (1ull << 31)) || (size_t)hd.Kp * Bp * 2 >= (1ull << 31) ||
         (size_t)hd.Mp * hd.Kp / 4 >= (1ull << 31) || (size_t)hd.Kp * hd.Np / 4 >= (1ull << 31))
         return hipErrorNotSupported;         // (reported as TSVD_EUNSUPPORTED; the limits are documented in tsvd.h)
     gemm_args a1;
@@ -1389,6 +1389,10 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     a1.out_bf16 = 0;
     a1.rows_valid = (int)hd.Kp;
     a1.clocks = g.clocks;
+    a1.big_tiles = 0;
+    a1.plane_blocks = 0;
+    a1.code_blocks = 0;
+    a1.two_sets = 0;
     // contraction lengths: stage V runs over N, stage U over K, both in steps of 128 indices; the last step of K is
     // filled from its first sub-steps (tsvd_rank_position), so stage U stops after those
     const int pairs_n = (int)((hd.N + 127) / 128), pairs_k = (int)((hd.K + 127) / 128);
@@ -1416,6 +1420,43 @@ hipError_t tsvd_forward_gemm(const tsvd_gemm_problem& g, hipStream_t stream) {
     a2.npairs = pairs_k;
     a2.last_steps = hd.K % 128 == 0 ? 4 : (int)((hd.K % 128 + 31) / 32);
 
+    if (g.x_f32) {
+        // fp32 activations: six planes of x (three, and three more for what those leave), both stages on fp4 codes x fp6
+        // planes with the second set of planes as further blocks of the contraction (same code words again), stage V
+        // writing six planes of z from its fp32 accumulators.  Workspace: planes of x, then planes of z.
+        const size_t xp_bytes = tsvd_gemm_fp6_bytes(256ll * pairs_n, Bp), zp_bytes = tsvd_gemm_fp6_bytes(256ll * pairs_k, Bp);
+        if (xp_bytes >= (1ull << 31) || zp_bytes >= (1ull << 31)) return hipErrorNotSupported;
+        unsigned char* xplanes = static_cast<unsigned char*>(g.ws);
+        unsigned char* zplanes = xplanes + ((xp_bytes + 255) & ~(size_t)255);
+        const int mask = tsvd_stage_mask();
+        hipError_t e = hipSuccess;
+        if (mask & 1)
+            if ((e = tsvd_fp6_launch_planes_f32(static_cast<const float*>(g.x), g.ldx, (int)hd.N, (int)g.B, pairs_n, xplanes, stream)) != hipSuccess) return e;
+        if (mask & 2) {
+            gemm_args a4 = a1;
+            a4.act = reinterpret_cast<const uint16_t*>(xplanes);
+            a4.act_bytes = (unsigned)xp_bytes;
+            a4.npairs = 2 * pairs_n;
+            a4.code_blocks = pairs_n;
+            a4.plane_blocks = 2 * pairs_n;
+            a4.out = zplanes;
+            a4.ld_out = 2 * pairs_k;
+            a4.two_sets = pairs_k;
+            a4.colmax = nullptr;
+            if ((e = tsvd_fp6_launch_direct(a4, hd.Kp, g.cu_count, stream)) != hipSuccess) return e;
+        }
+        if (mask & 4) {
+            gemm_args a3 = a2;
+            a3.act = reinterpret_cast<const uint16_t*>(zplanes);
+            a3.act_bytes = (unsigned)zp_bytes;
+            a3.npairs = 2 * pairs_k;
+            a3.code_blocks = pairs_k;
+            a3.plane_blocks = 2 * pairs_k;
+            a3.colmax = nullptr;
+            e = tsvd_fp6_launch(true, a3, hd.Mp, Bp, out_variant(a3.bias, a3.out_bf16, a3.out_token_major), g.cu_count, stream);
+        }
+        return e;
+    }
     if (tsvd_stage_mask() == 7 && tsvd_gemm_use_panel(hd.Mp, hd.Kp, hd.Np, g.B, g.cu_count, fast1)) {
         panel_args pa;
         pa.tiles_v = a1.tiles;

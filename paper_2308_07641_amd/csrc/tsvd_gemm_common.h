@@ -43,6 +43,9 @@ struct gemm_args {
     int out_token_major;      // stage 2 (EX = 3): out is [tokens][ld_out] (one row per token) instead of [M][ld_out]
     int rows_valid;           // stage 2: M
     int big_tiles;            // tsvd_gemm_fp6_tail_kernel: rows of 512 x 64 tiles before the narrower ones
+    int plane_blocks;         // fp4 x fp6 kernels: 128-index blocks per token group in the planes at `act` (0: 2 nkt)
+    int code_blocks;          // fp4 x fp6 kernels, fp32 activations: blocks of the contraction after which the code words repeat (0: never)
+    int two_sets;             // fp4 x fp6 stage V writing planes: 0, or the number of valid blocks = distance of the second set of planes
     int rows_need;            // rows of the stage that have to be computed (stage 1: the rank positions stage 2 reads; stage 2: M)
     long long* clocks;        // tuning aid: phase timestamps per workgroup (stage 1: 0..7, stage 2: 8..15), or null
 };
@@ -267,6 +270,9 @@ hipError_t tsvd_fp6_launch(bool stage2, const gemm_args& a, long long rows_p, in
 // stage V writing the planes of z itself (a.out = those planes, a.ld_out = 128-index blocks per token group), where its tile allows
 bool tsvd_fp6_direct_possible(long long rows_p, long long bvalid, long long cus);
 hipError_t tsvd_fp6_launch_direct(const gemm_args& a, long long rows_p, long long cus, hipStream_t stream);
+// fp32 x [rows_valid][ld] -> two sets of planes (six planes), `blocks` blocks each, layout of 2 * blocks blocks per token group
+hipError_t tsvd_fp6_launch_planes_f32(const float* x, long long ld, int rows_valid, int cols_valid, int blocks, unsigned char* planes,
+                                      hipStream_t stream);
 // the token-panel launch on fp4 codes x fp6 planes
 hipError_t tsvd_fp6_launch_panel(const panel_args& pa, int ex, hipStream_t stream);
 #endif  // TSVD_GEMM_COMMON_H

@@ -139,6 +139,7 @@ struct tsvd_gemm_problem {
     const void* x;                  // device bf16 [N][ldx], or [B][ldx] with x_token_major
     long long B, ldx;
     int x_token_major;              // only where tsvd_gemm_reads_token_major says so
+    int x_f32;                      // x is fp32 [N][ldx] (six planes; the fp4 x fp6 kernels)
     void* y;                        // device fp32 (or bf16 with out_bf16) [M][ldy]
     long long ldy;
     const float* bias;              // device [M] added per output row, or null

@@ -841,3 +841,38 @@ def test_fp6_tail_tiles(tsvd, M, K):
     y0, h = run_forward(j)
     tsvd.tsvd_free(h)
     assert np.array_equal(y0, y1)
+
+@pytest.mark.parametrize("tile", [0, 1])
+@pytest.mark.parametrize("M,N,K,B", [(300, 200, 270, 17), (515, 300, 777, 130), (1030, 512, 1024, 300), (64, 1300, 129, 65)])
+def test_fp32_activations_batched(tsvd, M, N, K, B, tile):
+    """fp32 activations with 17 tokens or more: six E2M3 planes of x (three, and three for what those leave), stage V
+    writing six planes of z from its fp32 accumulators, the second set of planes as further blocks of the contraction.
+    Exact on integer instances, 1e-5 of max |y| on random ones (measured about 2e-7), bias / bf16 / token-major options,
+    and the same result as one token at a time up to that tolerance."""
+    import torch
+    tsvd.tsvd_tuning_set("TSVD_FP6_TALL", tile)
+    i = workloads.make_integer_inputs(M, N, K, B, 0.5, "f32", seed=808 + B)
+    print(f"case fp32 batched int M={M} N={N} K={K} B={B} tile={tile}", flush=True)
+    y, h = run_forward(i)
+    tsvd.tsvd_free(h)
+    assert np.array_equal(y, oracle.forward(i.U, i.S, i.V, i.X))
+    j = workloads.make_inputs(M, N, K, B, 0.6, 0.02, "f32", seed=809 + B)
+    print(f"case fp32 batched rand M={M} N={N} K={K} B={B} tile={tile}", flush=True)
+    ref = oracle.forward(j.U, j.S, j.V, j.X)
+    y1, h = run_forward(j)
+    assert not np.isnan(y1).any()
+    assert rel_err(y1, ref) <= TOL["f32"]
+    bias = torch.linspace(-1.0, 1.0, M, device="cuda:0")
+    refb = ref + bias.cpu().numpy().astype(np.float64)[:, None]
+    xt = torch.full((B, N + 3), float("nan"), dtype=torch.float32, device="cuda:0")
+    xt[:, :N] = to_device(j).t()
+    yt = torch.full((B, M + 1), float("nan"), dtype=torch.float32, device="cuda:0")
+    tsvd.tsvd_forward_io(h, xt[:, :N], x_layout=tsvd.TSVD_TOKEN_MAJOR, bias=bias, y=yt[:, :M], y_dtype=tsvd.TSVD_F32, y_layout=tsvd.TSVD_TOKEN_MAJOR)
+    assert bool(torch.isnan(yt[:, M:]).all())
+    assert np.max(np.abs(yt[:, :M].t().cpu().numpy().astype(np.float64) - refb)) <= TOL["f32"] * np.max(np.abs(ref))
+    yb = tsvd.tsvd_forward_ex(h, to_device(j), bias=bias, y_dtype=tsvd.TSVD_BF16).float().cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(yb - refb) <= TOL["f32"] * np.max(np.abs(ref)) + 2.0 ** -8 * np.abs(refb))
+    tsvd.tsvd_tuning_set("TSVD_GEMM_MIN_B_F32", 1 << 30)      # one token at a time
+    y0 = tsvd.tsvd_forward(h, to_device(j)).cpu().numpy().astype(np.float64)
+    tsvd.tsvd_free(h)
+    assert rel_err(y0, y1) <= TOL["f32"]
