@@ -196,6 +196,8 @@ tsvd_status tsvd_forward_io(const tsvd_handle* h, const void* x_dev, tsvd_dtype 
  *     tsvd_workspace_bytes_ex(h, B, x_dtype, x_layout) exceeds TSVD_NOALLOC_MAX_WORKSPACE
  *     (16 MiB: any single-token or few-token call, and batched calls whose fp16 z [K][B rounded up to
  *     256] plus a copy of x fit, e.g. 512 tokens at K = 1536, N = 768 need 2.4 MB).
+ *     An fp32 batch whose six planes of x and z do not fit is not rejected: it goes one token at a time, as fp32
+ *     batches below 17 tokens do.
  *   - All calls on one GPU share that GPU's array, whatever the handle or stream: calls that
  *     overlap in time on one GPU race on z and give wrong results.  Order them on one stream (or with
  *     events).  The array keeps the previous call's contents; no kernel depends on them.

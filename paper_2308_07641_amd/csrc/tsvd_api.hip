@@ -413,7 +413,12 @@ tsvd_status forward_mid(const tsvd_handle* h, const void* x, int64_t B, int64_t 
     return TSVD_OK;
 }
 
+// (set for the duration of a tsvd_forward_noalloc call whose fp32 batch would not fit the fixed workspace as planes:
+// such a call goes one token at a time, as every fp32 batch did before the six-plane path existed)
+thread_local bool f32_one_token_at_a_time = false;
+
 bool use_gemm(const tsvd_handle*, int64_t B, tsvd_dtype x_dtype) {
+    if (x_dtype == TSVD_F32 && f32_one_token_at_a_time) return false;
     // (fp32 activations: fewer tokens are handled one at a time by the single-token kernels, each pass streaming the weights)
     const int min_b = x_dtype == TSVD_BF16 ? env_int("TSVD_GEMM_MIN_B", 17) : env_int("TSVD_GEMM_MIN_B_F32", 17);
     return B >= min_b;
@@ -713,12 +718,23 @@ extern "C" tsvd_status tsvd_forward_noalloc(const tsvd_handle* h, const void* x_
     if (!h || B <= 0) return TSVD_EINVAL;
     if (x_dtype != TSVD_F32 && x_dtype != TSVD_BF16) return TSVD_EINVAL;
     if (x_layout != TSVD_FEATURE_MAJOR && x_layout != TSVD_TOKEN_MAJOR) return TSVD_EINVAL;
-    if (tsvd_workspace_bytes_ex(h, B, x_dtype, x_layout) > (size_t)TSVD_NOALLOC_MAX_WORKSPACE) return TSVD_ETOOLARGE;
     if (h->device < 0 || h->device >= 64 || !noalloc_ptr[h->device]) return TSVD_EDEVICE;
+    bool slow_f32 = false;
+    if (tsvd_workspace_bytes_ex(h, B, x_dtype, x_layout) > (size_t)TSVD_NOALLOC_MAX_WORKSPACE) {
+        // an fp32 batch whose planes do not fit can still go one token at a time (a small workspace)
+        if (x_dtype != TSVD_F32) return TSVD_ETOOLARGE;
+        f32_one_token_at_a_time = slow_f32 = true;
+        if (tsvd_workspace_bytes_ex(h, B, x_dtype, x_layout) > (size_t)TSVD_NOALLOC_MAX_WORKSPACE) {
+            f32_one_token_at_a_time = false;
+            return TSVD_ETOOLARGE;
+        }
+    }
     // the workspace contents are undefined on entry for every kernel family (each writes z before it
     // reads it), so nothing has to be cleared between calls
-    return tsvd_forward_ex(h, x_dev, x_dtype, x_layout, B, ldx, bias_dev, y_dev, y_dtype, ldy, noalloc_ptr[h->device],
-                           (size_t)TSVD_NOALLOC_MAX_WORKSPACE, stream);
+    const tsvd_status st = tsvd_forward_ex(h, x_dev, x_dtype, x_layout, B, ldx, bias_dev, y_dev, y_dtype, ldy, noalloc_ptr[h->device],
+                                           (size_t)TSVD_NOALLOC_MAX_WORKSPACE, stream);
+    if (slow_f32) f32_one_token_at_a_time = false;
+    return st;
 }
 
 // ---- diagnostic interface (include/tsvd_tuning.h) ------------------------------------------------

@@ -76,3 +76,24 @@ def test_noalloc_rejects_calls_beyond_the_fixed_workspace():
     torch.cuda.synchronize()
     assert bool((y == 7.0).all())                           # nothing was enqueued
     tsvd.tsvd_free(h)
+
+
+def test_noalloc_fp32_batches():
+    """fp32 batches take the batched kernels on six planes when those fit the fixed workspace (same bits as
+    tsvd_forward_ex), and go one token at a time when they do not (same tolerance, no rejection)."""
+    import torch
+    import paper_2308_07641_amd as tsvd
+    i = workloads.make_inputs(300, 200, 520, 40, 0.6, 0.02, "f32", seed=930)
+    h = tsvd.tsvd_pack(i.U, i.S, i.V)
+    y_ref, y_new = _both(tsvd, torch, h, i)
+    assert torch.equal(y_ref, y_new)
+    assert rel_err(y_new.cpu().numpy().astype(np.float64), oracle.forward(i.U, i.S, i.V, i.X)) <= 1e-5
+    tsvd.tsvd_free(h)
+    i = workloads.make_inputs(128, 8192, 8192, 20, 0.6, 0.02, "f32", seed=931)      # planes of x and z: 20 MiB
+    h = tsvd.tsvd_pack(i.U, i.S, i.V)
+    assert tsvd.tsvd_workspace_bytes_ex(h, 20, tsvd.TSVD_F32, tsvd.TSVD_FEATURE_MAJOR) > tsvd.TSVD_NOALLOC_MAX_WORKSPACE
+    y = torch.full((128, 20), float("nan"), dtype=torch.float32, device="cuda:0")
+    tsvd.tsvd_forward_noalloc(h, to_device(i), y)
+    torch.cuda.synchronize()
+    assert rel_err(y.cpu().numpy().astype(np.float64), oracle.forward(i.U, i.S, i.V, i.X)) <= 1e-5
+    tsvd.tsvd_free(h)
