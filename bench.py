@@ -176,6 +176,13 @@ def bench_workload(name, steps, warmup, with_cpu=True, cpu_budget_s=4.0):
     step_rot()                      # a full pass again: y is compared with the oracle below
     torch.cuda.synchronize()
     res["stage_ms"] = {"V": v_ms, "U": u_ms}
+    if batched:
+        # the layer form beside it (bf16 y instead of fp32, same arithmetic until the last rounding): half the output bytes
+        yb = torch.empty((w.M, w.B), dtype=torch.bfloat16, device=dev)
+        _, lb_ms = _timed(lambda: tsvd.tsvd_forward_ex(handles[0], x, y=yb, y_dtype=tsvd.TSVD_BF16, workspace=ws), steps, max(2, warmup // 2))
+        res["bf16_output"] = {"event_ms_per_step": lb_ms, "executed_tflops": flops_exec / (lb_ms * 1e-3) / 1e12,
+                              "frac_of_bf16_peak": flops_exec / (lb_ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS}
+        del yb
     kernel_name, shape_u = _stage_u_kernel_name(tsvd, handles[0], w.B) if batched else (None, -1)
     kernel_key = f"{kernel_name}:{shape_u}" if batched else ("tsvd_mid_kernel" if w.B > 1 else "tsvd_gemv_kernel")
     traffic = _traffic_from_profile(name, kernel_key)
